@@ -1,0 +1,245 @@
+"""Seeded synthetic inputs and operator graphs of the five workloads.
+
+This module holds no arithmetic of the method: it draws Gaussian tensors in a
+fixed order from a seeded CPU generator and writes down operator graphs as
+plain lists.  Both the tests of the CPU oracle and the tests / benchmark of the
+HIP library take their inputs from here, so the two are fed identical data.
+
+The paper measured pretrained models on ImageNet / MS-COCO inputs (Sec. 4.1)
+and notes that the data does not affect latency; seeded Gaussians of the same
+shapes stand in for them.  Recipe: inputs and the diffusion context ~ N(0,1);
+every Linear weight, bias and the relative-position table ~ N(0, 0.02); norm
+gains 1 + N(0, 0.02), norm shifts N(0, 0.02).  Tensors are drawn in the order
+"input, then parameters in forward order".  For bf16 workloads every tensor is
+rounded once to bf16 (round to nearest even) and both sides consume the
+rounded values.  Linear weights are stored [out_features, in_features]: the
+reduction dimension is contiguous, which is the layout the reduction-dimension
+rule (Sec. 3.2.2) selects for a MatMul operand.
+"""
+import torch
+
+STD = 0.02
+
+
+class Draw:
+    def __init__(self, seed=0, bf16=False, std=STD):
+        self.g = torch.Generator(device="cpu").manual_seed(seed)
+        self.bf16 = bf16
+        self.std = std
+
+    def _q(self, t):
+        return t.to(torch.bfloat16).to(torch.float32) if self.bf16 else t
+
+    def normal(self, *shape, std=1.0, mean=0.0):
+        return self._q(torch.randn(*shape, generator=self.g, dtype=torch.float32) * std + mean)
+
+    def weight(self, *shape):
+        return self.normal(*shape, std=self.std)
+
+    def gain(self, n):
+        return self.normal(n, std=self.std, mean=1.0)
+
+
+def swin_block_params(dr, C, h, w, mlp_ratio=4):
+    p = {}
+    p["ln1_g"], p["ln1_b"] = dr.gain(C), dr.weight(C)
+    p["wqkv"], p["bqkv"] = dr.weight(3 * C, C), dr.weight(3 * C)
+    p["rpb_table"] = dr.weight((2 * w - 1) ** 2, h)
+    p["wproj"], p["bproj"] = dr.weight(C, C), dr.weight(C)
+    p["ln2_g"], p["ln2_b"] = dr.gain(C), dr.weight(C)
+    p["w1"], p["b1"] = dr.weight(mlp_ratio * C, C), dr.weight(mlp_ratio * C)
+    p["w2"], p["b2"] = dr.weight(C, mlp_ratio * C), dr.weight(C)
+    return p
+
+
+def swin_block_case(B, H, W, C, h, w, seed=0, bf16=False, std=STD, in_std=1.0):
+    dr = Draw(seed, bf16, std)
+    x = dr.normal(B, H * W, C, std=in_std)
+    return x, swin_block_params(dr, C, h, w)
+
+
+def swin_stage_case(B, H, W, C, h, w, depth, seed=0, bf16=True):
+    dr = Draw(seed, bf16)
+    x = dr.normal(B, H * W, C)
+    return x, [swin_block_params(dr, C, h, w) for _ in range(depth)]
+
+
+def swin_net_case(B, img=224, patch=4, embed=128, depths=(2, 2, 18, 2), heads=(4, 8, 16, 32),
+                  w=7, n_cls=1000, seed=0, bf16=True):
+    dr = Draw(seed, bf16)
+    image = dr.normal(B, 3, img, img)
+    net = {"embed": {"w": dr.weight(embed, 3 * patch * patch), "b": dr.weight(embed),
+                     "ln_g": dr.gain(embed), "ln_b": dr.weight(embed)},
+           "stages": [], "merges": []}
+    C = embed
+    for si, (dep, h) in enumerate(zip(depths, heads)):
+        net["stages"].append([swin_block_params(dr, C, h, w) for _ in range(dep)])
+        if si + 1 < len(depths):
+            net["merges"].append({"ln_g": dr.gain(4 * C), "ln_b": dr.weight(4 * C),
+                                  "w": dr.weight(2 * C, 4 * C)})
+            C *= 2
+    net["head"] = {"ln_g": dr.gain(C), "ln_b": dr.weight(C),
+                   "w": dr.weight(n_cls, C), "b": dr.weight(n_cls)}
+    return image, net
+
+
+def llama_case(B, S, E, F, seed=0, bf16=True, std=STD, in_std=1.0):
+    dr = Draw(seed, bf16, std)
+    x = dr.normal(B, S, E, std=in_std)
+    p = {"rms1_g": dr.gain(E),
+         "wq": dr.weight(E, E), "wk": dr.weight(E, E), "wv": dr.weight(E, E), "wo": dr.weight(E, E),
+         "rms2_g": dr.gain(E),
+         "wgate": dr.weight(F, E), "wup": dr.weight(F, E), "wdown": dr.weight(E, F)}
+    return x, p
+
+
+def sd_case(B, C, H, W, Sc, Dc, F, seed=0, bf16=True, std=STD, in_std=1.0):
+    dr = Draw(seed, bf16, std)
+    x = dr.normal(B, C, H, W, std=in_std)
+    ctx = dr.normal(B, Sc, Dc)
+    p = {"gn_g": dr.gain(C), "gn_b": dr.weight(C),
+         "win": dr.weight(C, C), "bin": dr.weight(C),
+         "ln1_g": dr.gain(C), "ln1_b": dr.weight(C),
+         "a1_wq": dr.weight(C, C), "a1_wk": dr.weight(C, C), "a1_wv": dr.weight(C, C),
+         "a1_wo": dr.weight(C, C), "a1_bo": dr.weight(C),
+         "ln2_g": dr.gain(C), "ln2_b": dr.weight(C),
+         "a2_wq": dr.weight(C, C), "a2_wk": dr.weight(C, Dc), "a2_wv": dr.weight(C, Dc),
+         "a2_wo": dr.weight(C, C), "a2_bo": dr.weight(C),
+         "ln3_g": dr.gain(C), "ln3_b": dr.weight(C),
+         "ff_w1": dr.weight(2 * F, C), "ff_b1": dr.weight(2 * F),
+         "ff_w2": dr.weight(C, F), "ff_b2": dr.weight(C),
+         "wout": dr.weight(C, C), "bout": dr.weight(C)}
+    return x, ctx, p
+
+
+# ---------------------------------------------------------------------------
+# Operator graphs (explicit form: every layout transformation is its own op).
+# tensors: list of shapes; ops: {"kind", "in", "out", "attr"} in topological order.
+# ---------------------------------------------------------------------------
+
+class Graph:
+    def __init__(self):
+        self.tensors, self.ops, self.names = [], [], {}
+
+    def tensor(self, shape, name=None):
+        self.tensors.append(tuple(int(s) for s in shape))
+        if name:
+            self.names[name] = len(self.tensors) - 1
+        return len(self.tensors) - 1
+
+    def op(self, kind, ins, out_shape, name=None, **attr):
+        out = self.tensor(out_shape)
+        self.ops.append({"kind": kind, "in": list(ins), "out": out, "attr": attr, "name": name or kind})
+        return out
+
+    def find(self, name):
+        return [i for i, o in enumerate(self.ops) if o["name"] == name][0]
+
+    # layout ops
+    def reshape(self, t, shape):
+        return self.op("RESHAPE", [t], shape)
+
+    def transpose(self, t, perm):
+        s = self.tensors[t]
+        return self.op("TRANSPOSE", [t], [s[p] for p in perm], perm=tuple(perm))
+
+    def roll(self, t, axis, shift):
+        return self.op("ROLL", [t], self.tensors[t], axis=axis, shift=shift)
+
+    def slice(self, t, axis, start, stop):
+        s = list(self.tensors[t])
+        s[axis] = stop - start
+        return self.op("SLICE", [t], s, axis=axis, start=start, stop=stop, step=1)
+
+    def linear(self, t, n_out, name, bias=True):
+        s = list(self.tensors[t])
+        s[-1] = n_out
+        y = self.op("MATMUL", [t], s, name=name, red=[len(s) - 1])
+        if bias:
+            y = self.op("BIAS", [y], s, name=name + ".bias")
+        return y
+
+
+def swin_block_graph(B, H, W, C, h, w, s):
+    g = Graph()
+    L, N, d = H * W, w * w, C // h
+    nWy, nWx = H // w, W // w
+    B_ = B * nWy * nWx
+    x = g.tensor((B, L, C), "x")
+    t = g.op("LAYERNORM", [x], (B, L, C), name="ln1", red=[2])
+    t = g.reshape(t, (B, H, W, C))
+    if s:
+        t = g.roll(t, 1, -s)
+        t = g.roll(t, 2, -s)
+    t = g.reshape(t, (B, nWy, w, nWx, w, C))
+    t = g.transpose(t, (0, 1, 3, 2, 4, 5))
+    t = g.reshape(t, (B_, N, C))
+    t = g.linear(t, 3 * C, "qkv")
+    t = g.reshape(t, (B_, N, 3, h, d))
+    t = g.transpose(t, (2, 0, 3, 1, 4))
+    qkv = []
+    for k in range(3):
+        u = g.slice(t, 0, k, k + 1)
+        qkv.append(g.reshape(u, (B_, h, N, d)))
+    t = g.op("ATTENTION", qkv, (B_, h, N, d), name="attn", red=[3, 3, None])
+    t = g.transpose(t, (0, 2, 1, 3))
+    t = g.reshape(t, (B_, N, C))
+    t = g.linear(t, C, "proj")
+    t = g.reshape(t, (B, nWy, nWx, w, w, C))
+    t = g.transpose(t, (0, 1, 3, 2, 4, 5))
+    t = g.reshape(t, (B, H, W, C))
+    if s:
+        t = g.roll(t, 1, s)
+        t = g.roll(t, 2, s)
+    t = g.reshape(t, (B, L, C))
+    x1 = g.op("ADD", [x, t], (B, L, C), name="res1")
+    t = g.op("LAYERNORM", [x1], (B, L, C), name="ln2", red=[2])
+    t = g.linear(t, 4 * C, "fc1")
+    t = g.op("UNARY", [t], (B, L, 4 * C), name="gelu")
+    t = g.linear(t, C, "fc2")
+    g.op("ADD", [x1, t], (B, L, C), name="res2")
+    return g
+
+
+def llama_layer_graph(B, S, E, h, F):
+    g = Graph()
+    d = E // h
+    x = g.tensor((B, S, E), "x")
+    n1 = g.op("RMSNORM", [x], (B, S, E), name="rms1", red=[2])
+    t = g.linear(n1, 3 * E, "qkv", bias=False)
+    parts = []
+    for k in range(3):
+        u = g.slice(t, 2, k * E, (k + 1) * E)
+        u = g.reshape(u, (B, S, h, d))
+        u = g.transpose(u, (0, 2, 1, 3))
+        if k < 2:
+            u = g.op("ROPE", [u], (B, h, S, d), name="rope%d" % k)
+        parts.append(u)
+    t = g.op("ATTENTION", parts, (B, h, S, d), name="attn", red=[3, 3, None])
+    t = g.transpose(t, (0, 2, 1, 3))
+    t = g.reshape(t, (B, S, E))
+    t = g.linear(t, E, "wo", bias=False)
+    h1 = g.op("ADD", [x, t], (B, S, E), name="res1")
+    n2 = g.op("RMSNORM", [h1], (B, S, E), name="rms2", red=[2])
+    gu = g.linear(n2, 2 * F, "gate_up", bias=False)
+    ga = g.op("UNARY", [g.slice(gu, 2, 0, F)], (B, S, F), name="silu")
+    up = g.slice(gu, 2, F, 2 * F)
+    act = g.op("MUL", [ga, up], (B, S, F), name="swiglu")
+    t = g.linear(act, E, "down", bias=False)
+    g.op("ADD", [h1, t], (B, S, E), name="res2")
+    return g
+
+
+def fig4_graph(D1=6, D2=4, D3=8):
+    """The simplified graph of the paper's layout-selection example (Sec. 3.2.2):
+    MatMul -> Transpose -> Reshape -> {Reduce over D3, Reduce' over D1, Conv over D3}."""
+    g = Graph()
+    D0 = D2 * D3
+    a = g.tensor((D0, 16), "a")
+    t = g.op("MATMUL", [a], (D0, D1), name="matmul", red=[1])
+    t = g.transpose(t, (1, 0))
+    t = g.reshape(t, (D1, D2, D3))
+    g.op("REDUCE", [t], (D1, D2), name="reduce", red=[2])
+    g.op("REDUCE", [t], (D2, D3), name="reduce_p", red=[0])
+    g.op("CONV", [t], (D1, D2, 4), name="conv", red=[2])
+    return g

@@ -1,0 +1,207 @@
+"""Pins for the block-level oracle: each block is re-assembled from torch CPU
+library ops (torch.roll, view/permute, F.layer_norm, F.scaled_dot_product_attention,
+F.conv2d, ...) at tiny shapes and compared with the oracle, which pins the
+conventions (roll direction, bias indexing, mask regions, RoPE pairing, GEGLU
+chunk order, patch-merge order) to the public definitions; plus mask / softmax
+invariants.  Stress distributions (weights and inputs N(0,1)-scaled so logits
+are O(1)) are used so that a wrong index or sign is not hidden by near-uniform
+softmax."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+from oracle import swin, llama, sd, ops as O, views as V
+from paper_2404_13528_amd import workloads as Wl
+
+
+def npd(p):
+    return {k: v.double().numpy() for k, v in p.items()}
+
+
+def td(p):
+    return {k: v.double() for k, v in p.items()}
+
+
+def torch_swin_block(x, p, H, W, w, h, s):
+    B, L, C = x.shape
+    N, d = w * w, C // h
+    u = F.layer_norm(x, (C,), p["ln1_g"], p["ln1_b"], 1e-5).view(B, H, W, C)
+    if s:
+        u = torch.roll(u, shifts=(-s, -s), dims=(1, 2))
+    u = u.view(B, H // w, w, W // w, w, C).permute(0, 1, 3, 2, 4, 5).reshape(-1, N, C)
+    qkv = F.linear(u, p["wqkv"], p["bqkv"]).reshape(-1, N, 3, h, d).permute(2, 0, 3, 1, 4)
+    q, k, v = qkv[0], qkv[1], qkv[2]
+    coords = torch.stack(torch.meshgrid(torch.arange(w), torch.arange(w), indexing="ij")).flatten(1)
+    rel = (coords[:, :, None] - coords[:, None, :]).permute(1, 2, 0) + (w - 1)
+    idx = rel[..., 0] * (2 * w - 1) + rel[..., 1]
+    bias = p["rpb_table"][idx.view(-1)].view(N, N, h).permute(2, 0, 1)
+    att = (q * d ** -0.5) @ k.transpose(-2, -1) + bias[None]
+    if s:
+        img = torch.zeros(1, H, W, 1, dtype=x.dtype)
+        c = 0
+        for ys in (slice(0, -w), slice(-w, -s), slice(-s, None)):
+            for xs in (slice(0, -w), slice(-w, -s), slice(-s, None)):
+                img[:, ys, xs, :] = c
+                c += 1
+        mw = img.view(1, H // w, w, W // w, w, 1).permute(0, 1, 3, 2, 4, 5).reshape(-1, N)
+        am = mw[:, None, :] - mw[:, :, None]
+        am = am.masked_fill(am != 0, -100.0)
+        nW = am.shape[0]
+        att = (att.view(-1, nW, h, N, N) + am[None, :, None]).view(-1, h, N, N)
+    o = (att.softmax(-1) @ v).transpose(1, 2).reshape(-1, N, C)
+    o = F.linear(o, p["wproj"], p["bproj"]).view(B, H // w, W // w, w, w, C)
+    o = o.permute(0, 1, 3, 2, 4, 5).reshape(B, H, W, C)
+    if s:
+        o = torch.roll(o, shifts=(s, s), dims=(1, 2))
+    x1 = x + o.view(B, L, C)
+    m = F.linear(F.gelu(F.linear(F.layer_norm(x1, (C,), p["ln2_g"], p["ln2_b"], 1e-5), p["w1"], p["b1"])),
+                 p["w2"], p["b2"])
+    return x1 + m
+
+
+@pytest.mark.parametrize("s", [0, 3])
+@pytest.mark.parametrize("std", [0.02, 0.3])
+def test_swin_block_vs_torch_chain(s, std):
+    B, H, W, C, h, w = 2, 14, 21, 32, 2, 7
+    x, p = Wl.swin_block_case(B, H, W, C, h, w, seed=3, std=std)
+    got = swin.swin_block(x.double().numpy(), npd(p), H, W, w, h, s)
+    ref = torch_swin_block(x.double(), td(p), H, W, w, h, s).numpy()
+    assert np.abs(got - ref).max() < 1e-10
+    assert np.abs(got - x.double().numpy()).max() > 1e-2      # the branches do contribute
+
+
+def test_shift_mask_regions_and_rows():
+    H = W = 56; w, s = 7, 3
+    m = swin.shift_mask(H, W, w, s)
+    assert m.shape == (64, 49, 49)
+    assert set(np.unique(m)) == {-100.0, 0.0}
+    nreg = []
+    for win in range(64):
+        # number of distinct regions = number of distinct mask rows' zero patterns
+        nreg.append(len({tuple(r) for r in (m[win] == 0)}))
+    nreg = np.array(nreg).reshape(8, 8)
+    assert np.all(nreg[:7, :7] == 1) and np.all(nreg[7, :7] == 2) and np.all(nreg[:7, 7] == 2) and nreg[7, 7] == 4
+    assert np.all(np.diagonal(m, axis1=1, axis2=2) == 0)        # a token always sees itself
+    assert np.all(swin.shift_mask(H, W, w, 0) == 0)
+    # masked softmax rows still sum to one, masked entries vanish
+    rng = np.random.default_rng(0)
+    p = O.softmax(rng.standard_normal((64, 49, 49)) + m)
+    assert np.allclose(p.sum(-1), 1, atol=1e-12) and p[m < 0].max() < 1e-40
+
+
+def test_rel_pos_bias_definition():
+    w, h = 7, 3
+    table = np.random.default_rng(1).standard_normal(((2 * w - 1) ** 2, h))
+    b = swin.rel_pos_bias(table, w, h)
+    for (i, j, hh) in [(0, 0, 0), (0, 48, 1), (48, 0, 2), (10, 30, 1), (23, 8, 0)]:
+        yi, xi, yj, xj = i // w, i % w, j // w, j % w
+        assert b[hh, i, j] == table[(yi - yj + w - 1) * (2 * w - 1) + (xi - xj + w - 1), hh]
+    assert np.all(np.diagonal(b, axis1=1, axis2=2) == table[(w - 1) * (2 * w - 1) + w - 1][:, None])
+
+
+def test_window_attention_reduces_to_textbook():
+    # one window, one head, zero bias, no shift -> softmax(q k^T / sqrt(d)) v
+    N, C = 49, 16
+    rng = np.random.default_rng(2)
+    u = rng.standard_normal((1, N, C))
+    p = {"wqkv": rng.standard_normal((3 * C, C)) * 0.3, "bqkv": rng.standard_normal(3 * C) * 0.1,
+         "rpb_table": np.zeros((169, 1))}
+    a = swin.window_attention(u, p, 7, 1, None)
+    qkv = torch.from_numpy(u) @ torch.from_numpy(p["wqkv"]).T + torch.from_numpy(p["bqkv"])
+    q, k, v = qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:]
+    ref = F.scaled_dot_product_attention(q[None], k[None], v[None])[0].numpy()
+    assert np.allclose(a["o"], ref, atol=1e-12)
+    assert np.allclose(a["P"].sum(-1), 1, atol=1e-12)
+
+
+def test_patch_embed_is_strided_conv_and_merge_definition():
+    dr = Wl.Draw(5, std=0.3)
+    img = dr.normal(2, 3, 16, 24)
+    p = {"w": dr.weight(10, 48), "b": dr.weight(10), "ln_g": dr.gain(10), "ln_b": dr.weight(10)}
+    got = swin.patch_embed(img.double().numpy(), npd(p), 4)
+    c = F.conv2d(img.double(), p["w"].double().view(10, 3, 4, 4), p["b"].double(), stride=4)   # [B,10,4,6]
+    ref = F.layer_norm(c.flatten(2).transpose(1, 2), (10,), p["ln_g"].double(), p["ln_b"].double(), 1e-5)
+    assert np.allclose(got, ref.numpy(), atol=1e-12)
+    x = dr.normal(2, 6 * 8, 5)
+    pm = {"ln_g": dr.gain(20), "ln_b": dr.weight(20), "w": dr.weight(10, 20)}
+    got = swin.patch_merge(x.double().numpy(), npd(pm), 6, 8)
+    xv = x.double().view(2, 6, 8, 5)
+    cat = torch.cat([xv[:, 0::2, 0::2], xv[:, 1::2, 0::2], xv[:, 0::2, 1::2], xv[:, 1::2, 1::2]], -1).view(2, 12, 20)
+    ref = F.linear(F.layer_norm(cat, (20,), pm["ln_g"].double(), pm["ln_b"].double(), 1e-5), pm["w"].double())
+    assert np.allclose(got, ref.numpy(), atol=1e-12)
+
+
+def test_stage_shift_rule():
+    assert [swin.block_shift(k, 14, 7) for k in range(4)] == [0, 3, 0, 3]
+    assert [swin.block_shift(k, 7, 7) for k in range(2)] == [0, 0]
+
+
+def torch_llama(x, p, h):
+    B, S, E = x.shape
+    d = E // h
+    n1 = F.rms_norm(x, (E,), p["rms1_g"], 1e-5)
+    sp = lambda t: t.view(B, S, h, d).transpose(1, 2)
+    q, k, v = sp(F.linear(n1, p["wq"])), sp(F.linear(n1, p["wk"])), sp(F.linear(n1, p["wv"]))
+    inv = 1.0 / (10000.0 ** (torch.arange(0, d, 2, dtype=torch.float64) / d))
+    ang = torch.outer(torch.arange(S, dtype=torch.float64), inv)
+    cos, sin = torch.cat([ang.cos(), ang.cos()], -1), torch.cat([ang.sin(), ang.sin()], -1)
+    rot = lambda t: torch.cat([-t[..., d // 2:], t[..., :d // 2]], -1)
+    q, k = q * cos + rot(q) * sin, k * cos + rot(k) * sin
+    o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B, S, E)
+    h1 = x + F.linear(o, p["wo"])
+    n2 = F.rms_norm(h1, (E,), p["rms2_g"], 1e-5)
+    return h1 + F.linear(F.silu(F.linear(n2, p["wgate"])) * F.linear(n2, p["wup"]), p["wdown"])
+
+
+@pytest.mark.parametrize("std", [0.02, 0.15])
+def test_llama_layer_vs_torch_chain(std):
+    x, p = Wl.llama_case(2, 24, 64, 96, seed=1, bf16=False, std=std)
+    got = llama.llama_layer(x.double().numpy(), npd(p), 4)
+    ref = torch_llama(x.double(), td(p), 4).numpy()
+    assert np.abs(got - ref).max() < 1e-10
+
+
+def torch_sd(x, ctx, p, G, h):
+    B, C, H, W = x.shape
+    t = F.group_norm(x, G, p["gn_g"], p["gn_b"], 1e-6)
+    t = F.conv2d(t, p["win"].view(C, C, 1, 1), p["bin"])
+    t = t.flatten(2).transpose(1, 2)
+
+    def mha(xq, xkv, pre):
+        Sq, Sk, d = xq.shape[1], xkv.shape[1], C // h
+        q = F.linear(xq, p[pre + "_wq"]).view(B, Sq, h, d).transpose(1, 2)
+        k = F.linear(xkv, p[pre + "_wk"]).view(B, Sk, h, d).transpose(1, 2)
+        v = F.linear(xkv, p[pre + "_wv"]).view(B, Sk, h, d).transpose(1, 2)
+        o = F.scaled_dot_product_attention(q, k, v).transpose(1, 2).reshape(B, Sq, C)
+        return F.linear(o, p[pre + "_wo"], p[pre + "_bo"])
+    n = F.layer_norm(t, (C,), p["ln1_g"], p["ln1_b"], 1e-5)
+    t = t + mha(n, n, "a1")
+    t = t + mha(F.layer_norm(t, (C,), p["ln2_g"], p["ln2_b"], 1e-5), ctx, "a2")
+    z = F.linear(F.layer_norm(t, (C,), p["ln3_g"], p["ln3_b"], 1e-5), p["ff_w1"], p["ff_b1"])
+    a, g = z.chunk(2, dim=-1)
+    t = t + F.linear(a * F.gelu(g), p["ff_w2"], p["ff_b2"])
+    t = t.transpose(1, 2).reshape(B, C, H, W)
+    return F.conv2d(t, p["wout"].view(C, C, 1, 1), p["bout"]) + x
+
+
+@pytest.mark.parametrize("std", [0.02, 0.15])
+def test_sd_block_vs_torch_chain(std):
+    x, ctx, p = Wl.sd_case(2, 32, 6, 5, 7, 24, 64, seed=2, bf16=False, std=std)
+    got = sd.spatial_transformer(x.double().numpy(), ctx.double().numpy(), npd(p), 4, 4)
+    ref = torch_sd(x.double(), ctx.double(), td(p), 4, 4).numpy()
+    assert np.abs(got - ref).max() < 1e-10
+
+
+def test_swin_net_runs_and_matches_stagewise_composition():
+    image, net = Wl.swin_net_case(1, img=56, patch=4, embed=16, depths=(2, 2), heads=(2, 4), w=7, n_cls=5, bf16=False)
+    netn = {"embed": npd(net["embed"]), "stages": [[npd(b) for b in st] for st in net["stages"]],
+            "merges": [npd(m) for m in net["merges"]], "head": npd(net["head"])}
+    f, logits = swin.swin_net(image.double().numpy(), netn, 4, 7, (2, 4))
+    assert f.shape == (1, 49, 32) and logits.shape == (1, 5)
+    x = swin.patch_embed(image.double().numpy(), netn["embed"], 4)
+    x = swin.swin_block(x, netn["stages"][0][0], 14, 14, 7, 2, 0)
+    x = swin.swin_block(x, netn["stages"][0][1], 14, 14, 7, 2, 3)
+    x = swin.patch_merge(x, netn["merges"][0], 14, 14)
+    x = swin.swin_block(x, netn["stages"][1][0], 7, 7, 7, 4, 0)
+    x = swin.swin_block(x, netn["stages"][1][1], 7, 7, 7, 4, 0)     # 7x7 stage never shifts
+    assert np.allclose(O.layer_norm(x, netn["head"]["ln_g"], netn["head"]["ln_b"]), f)
