@@ -1,0 +1,295 @@
+/* smartmem.h - C ABI of the MI355X layout-elided transformer-chain library.
+ *
+ * The library executes transformer operator chains with their explicit layout
+ * transformations (Reshape, Transpose/Permute, cyclic roll, window partition and
+ * reverse, head split and merge, patch merging, NCHW<->token rearrangement)
+ * eliminated: a consumer kernel reads its producer's tensor in the producer's
+ * layout through a composed index map (SmartMem, arxiv 2404.13528, Sec. 3).
+ *
+ * General conventions
+ *   - Every function returns an int status (SM_OK or a negative SM_ERR_*);
+ *     sm_last_error() gives a thread-local message for the last failure.
+ *     No exception crosses this boundary.
+ *   - "device pointer": memory of the current HIP device, owned by the caller,
+ *     16-byte aligned.  "host pointer": ordinary process memory.
+ *   - The library never allocates or frees device memory and never
+ *     synchronises: all device work is enqueued on the hipStream_t passed as
+ *     `void* stream` (NULL = the default stream).  Scratch memory comes from the
+ *     caller as `ws` / `ws_bytes`; the matching *_workspace_bytes() call gives
+ *     the size needed.  An undersized workspace returns SM_ERR_WORKSPACE before
+ *     anything is launched.
+ *   - Opaque handles (sm_map, sm_plan) are host objects created and destroyed by
+ *     the library.  Descriptor structs are plain data owned by the caller and
+ *     copied during the call.
+ *   - Tensors are row-major.  Linear weights are [out_features, in_features]
+ *     (the reduction dimension contiguous, Sec. 3.2.2).  All tensors of a call
+ *     share the element type given by `dtype`.
+ *   - Shapes that do not divide (H or W not a multiple of the window) return
+ *     SM_ERR_SHAPE; there is no padding path.
+ */
+#ifndef SMARTMEM_H
+#define SMARTMEM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SM_OK = 0, SM_ERR_INVALID_ARG = -1, SM_ERR_SHAPE = -2, SM_ERR_UNSUPPORTED = -3,
+       SM_ERR_WORKSPACE = -4, SM_ERR_DEVICE = -5 };
+enum { SM_F32 = 0, SM_BF16 = 1 };
+enum { SM_ELIDED = 0, SM_EXPLICIT = 1 };
+#define SM_MAX_RANK 8
+
+const char* sm_last_error(void);
+/* Version of this ABI (increments on incompatible change). */
+int sm_abi_version(void);
+
+/* ------------------------------------------------------------------------ */
+/* Operator graph and layout planner (Sec. 3.1, 3.2; Tables 3, 5, 6)         */
+/* ------------------------------------------------------------------------ */
+
+/* Operator groups of Table 3: input layout dependent / independent x output
+ * layout variable / fixed. */
+enum { SM_ILD_VAR = 0, SM_ILI_VAR = 1, SM_ILD_FIX = 2, SM_ILI_FIX = 3 };
+/* Pair actions of Table 5 and layout-search policies of Table 6. */
+enum { SM_KEEP_BOTH = 0, SM_TRY_FUSE = 1, SM_ELIM_2ND = 2, SM_ELIM_1ST = 3, SM_ELIM_BOTH = 4 };
+enum { SM_SEARCH_BOTH = 0, SM_SEARCH_FUSED = 1, SM_SEARCH_1ST = 2, SM_SEARCH_2ND = 3, SM_NO_SEARCH = 4 };
+/* What became of an operator after planning. */
+enum { SM_KEPT = 0, SM_FUSED = 1, SM_ELIMINATED_STORE = 2, SM_ELIMINATED_LOAD = 3, SM_MATERIALISED = 4 };
+
+/* Operator kinds.  0..15 ILD&Variable, 16..31 ILD&Fixed, 32..47 ILI&Variable,
+ * 48..63 ILI&Fixed.  The first four of each row are the paper's Table 3; the
+ * others are classified by the definitions of Table 4. */
+enum {
+  SM_OP_CONV = 0, SM_OP_MATMUL = 1, SM_OP_LAYERNORM = 2, SM_OP_SOFTMAX = 3,
+  SM_OP_GROUPNORM = 4, SM_OP_RMSNORM = 5, SM_OP_ATTENTION = 6, SM_OP_REDUCE = 7,
+  SM_OP_RESHAPE = 16, SM_OP_TRANSPOSE = 17, SM_OP_DTOS = 18, SM_OP_STOD = 19,
+  SM_OP_UNARY = 32, SM_OP_ADD = 33, SM_OP_MUL = 34, SM_OP_BIAS = 35, SM_OP_ROPE = 36,
+  SM_OP_GATHER = 48, SM_OP_SLICE = 49, SM_OP_ROLL = 50, SM_OP_CONCAT = 51
+};
+
+typedef struct { int32_t rank; int64_t shape[SM_MAX_RANK]; int32_t dtype; } sm_tensor_desc;
+
+/* One operator.  `in` are tensor ids (indices into the tensor array), `out` the
+ * tensor it produces.  Operators must be given in topological order.
+ * attr: TRANSPOSE attr[0..rank) = perm (output axis k is input axis perm[k]);
+ *       ROLL attr = {axis, shift} (out[i] = in[(i - shift) mod n]);
+ *       SLICE attr = {axis, start, stop, step}; RESHAPE none (shape of `out`);
+ *       ILD&Variable kinds: attr[i] = reduction axis of operand i, -1 for none
+ *       (Sec. 3.2.2 "reduction dimension"). */
+typedef struct { int32_t kind; int32_t n_in; int32_t in[4]; int32_t out; int32_t n_attr; int64_t attr[16]; } sm_op_desc;
+
+typedef struct sm_plan sm_plan;
+typedef struct sm_map sm_map;
+
+/* Table 3: group of an operator kind; SM_ERR_INVALID_ARG for an unknown kind. */
+int sm_op_group(int kind, int* group);
+/* Table 5 / Table 6 for a (first, second) pair of groups.  result_group is -1
+ * for the N/A cells. */
+int sm_pair_action(int first_group, int second_group, int* action);
+int sm_pair_outcome(int first_group, int second_group, int* result_group, int* search);
+
+/* Plans a producer-consumer operator graph: classifies every operator
+ * (Table 3), merges Fixed-Fixed pairs, absorbs every run of Fixed operators
+ * into the store of the preceding Variable operator or the load of the
+ * following one (Table 5; write side when every consumer sees the same
+ * bijective run, Sec. 3.2.2), fuses ILI&Variable operators into a neighbour
+ * until only ILD&Variable operators survive, then selects the layout of every
+ * stored tensor from its consumers' reduction dimensions with k directly
+ * indexable dimensions (k = 1 on linear HBM; k = 2 reproduces the 2.5D case).
+ * Host only.  *out is owned by the library until sm_plan_destroy. */
+int sm_layout_plan(const sm_tensor_desc* tensors, int n_tensors, const sm_op_desc* ops, int n_ops,
+                   int k, sm_plan** out);
+/* Per operator: group, the Table 5 action that decided it, its status (SM_KEPT..),
+ * the surviving operator that absorbed it (itself when kept, -1 when
+ * materialised) and the group of the merged node (Table 6). Any out pointer
+ * may be NULL. */
+int sm_plan_op(const sm_plan*, int op, int* group, int* action, int* status, int* absorbed_by, int* node_group);
+/* Per stored tensor: dimension order chosen (outermost first, length rank),
+ * the reduction dimensions its consumers requested (up to SM_MAX_RANK, count in
+ * *n_red) and the number of copies kept (> 1 when more than k are requested).
+ * SM_ERR_INVALID_ARG if the tensor is never stored (eliminated view). */
+int sm_plan_tensor(const sm_plan*, int tensor, int* dim_order, int* red_dims, int* n_red, int* n_copies);
+/* Composed map seen by operand `operand` of surviving operator `consumer_op`
+ * (view index -> element offset in the stored tensor).  *stored_tensor is the
+ * tensor id the offsets refer to.  *borrowed is NULL when the operand is read
+ * directly.  The map belongs to the plan. */
+int sm_plan_load_map(const sm_plan*, int consumer_op, int operand, const sm_map** borrowed, int* stored_tensor);
+/* Map applied by surviving operator `producer_op` when it stores its result:
+ * natural output index -> element offset in the tensor it stores
+ * (*stored_tensor, the output of the last absorbed operator).  NULL when the
+ * result is stored as computed. */
+int sm_plan_store_map(const sm_plan*, int producer_op, const sm_map** borrowed, int* stored_tensor);
+void sm_plan_destroy(sm_plan*);
+
+/* ------------------------------------------------------------------------ */
+/* Index-map composer (Sec. 3.2.1: index comprehension and strength reduction) */
+/* ------------------------------------------------------------------------ */
+
+enum { SM_VIEW_RESHAPE = 0, SM_VIEW_PERMUTE = 1, SM_VIEW_ROLL = 2, SM_VIEW_SLICE = 3 };
+/* RESHAPE: n = new rank, arg = new shape.  PERMUTE: n = rank, arg = perm.
+ * ROLL: arg = {axis, shift}.  SLICE: arg = {axis, start, stop, step}, step >= 1. */
+typedef struct { int32_t kind; int32_t n; int64_t arg[SM_MAX_RANK]; } sm_view_op;
+
+/* Composes a chain of view operators applied to a contiguous row-major source
+ * of shape `src` into one map: view multi-index -> source element offset, built
+ * from identity / split (//, %) / merge (*, +) index dependencies and
+ * simplified with exact strength-reduction rules. */
+int sm_map_create(const sm_tensor_desc* src, const sm_view_op* chain, int n, sm_map** out);
+/* outer is a map whose *source shape* equals inner's view shape; the result
+ * maps outer's view index to inner's source offset. Not needed for chains
+ * built in one go; provided for maps planned separately. */
+int sm_map_compose(const sm_map* inner, const sm_map* outer, sm_map** out);
+int sm_map_rank(const sm_map*);
+int sm_map_shape(const sm_map*, int64_t* shape /* SM_MAX_RANK */);
+int64_t sm_map_numel(const sm_map*);
+/* Number of // and % operations left in the simplified map, and in the map
+ * before simplification (what strength reduction removed). */
+int sm_map_cost(const sm_map*, int* n_divmod, int* n_divmod_unsimplified);
+/* offsets[o] = source element offset of view element o (row-major over the
+ * view shape), o in [0, n); n must equal sm_map_numel.  Host pointer. */
+int sm_map_eval_host(const sm_map*, int64_t* offsets, int64_t n);
+/* 1 if the map is affine (no // or % left): then offset = base + sum stride[k]*i[k]. */
+int sm_map_affine(const sm_map*, int64_t* base, int64_t* strides /* SM_MAX_RANK */);
+void sm_map_destroy(sm_map*);
+
+/* dst[o] = src[map(o)] for every view element o; dst is contiguous with the
+ * view's shape.  on_device = 0: host pointers, executed on the host;
+ * on_device = 1: device pointers, one HIP kernel on `stream`.  This is the
+ * materialised form of an eliminated transformation (a test instrument and the
+ * copy kernel of the explicit baseline). */
+int sm_gather_mapped(const sm_map*, const void* src, void* dst, int dtype, int on_device, void* stream);
+
+/* ------------------------------------------------------------------------ */
+/* Single operators with mapped operands (device pointers)                    */
+/* ------------------------------------------------------------------------ */
+
+/* y = LayerNorm(x) over the last dimension C of x [rows, C] (fp32 statistics,
+ * biased variance).  rms != 0: RMSNorm (no mean subtraction, beta ignored).
+ * store_map (nullable): a map with view shape [rows, C] (or any shape with
+ * rows*C elements whose last dimension is C) giving the offset in y of each
+ * natural output element; its last dimension must be contiguous. */
+int sm_norm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows, int C, float eps,
+            int rms, int dtype, const sm_map* store_map, void* stream);
+/* GroupNorm over x NCHW [B, C, H, W] with G groups.  tokens_out = 0: y is NCHW;
+ * tokens_out = 1: y is written token-major [B, H*W, C] (the layout a following
+ * MatMul over C prefers). */
+int sm_groupnorm(const void* x, const void* gamma, const void* beta, void* y, int B, int C, int HW, int G,
+                 float eps, int tokens_out, int dtype, void* stream);
+
+/* Epilogue of sm_linear, applied in this order to acc = A.W^T:
+ * +bias[n]; activation; RoPE; *gate; +residual. */
+enum { SM_ACT_NONE = 0, SM_ACT_GELU = 1, SM_ACT_SWIGLU = 2, SM_ACT_GEGLU = 3 };
+typedef struct {
+  int64_t M; int32_t N, K;      /* C[M, N] = A[M, K] . W[N, K]^T */
+  int32_t dtype;
+  int32_t act;                  /* SM_ACT_*; SWIGLU / GEGLU: W has 2N' rows, output has N' = N/2 columns:
+                                   SWIGLU out = silu(acc[:, j]) * acc[:, N' + j]; GEGLU out = acc[:, j] * gelu(acc[:, N' + j]) */
+  int32_t rope_cols;            /* > 0: columns [0, rope_cols) are heads of size rope_dim rotated by RoPE (half-split pairs) */
+  int32_t rope_dim; int32_t rope_seq;   /* position of row r is r mod rope_seq */
+  float rope_base;
+  int32_t c_transposed;         /* 1: C is stored column-major per batch of c_batch_rows rows:
+                                   offset = (r / c_batch_rows) * N * c_batch_rows + n * c_batch_rows + r % c_batch_rows
+                                   (NCHW store); residual is read the same way */
+  int64_t c_batch_rows;
+} sm_linear_desc;
+/* a_map / c_map (nullable): maps with view shape [M, K] / natural output shape
+ * [M, Nout] whose last dimension is contiguous: row r of A is read at
+ * a_map(r, 0); row r of the result is written at c_map(r, 0) and the residual
+ * is read at the same offset.  bias, residual nullable. */
+int sm_linear(const sm_linear_desc*, const void* A, const void* W, const void* bias, const void* residual,
+              void* C, const sm_map* a_map, const sm_map* c_map, void* stream);
+
+/* Fused attention O = softmax(scale * Q K^T + bias + mask) V per (batch, head).
+ * Q, K, V, O are 4-D strided views [nb, heads, n, d] (element strides, innermost
+ * stride 1) so that head split / merge permutes are address arithmetic.
+ * kind: SM_ATT_FULL, SM_ATT_CAUSAL (key j visible to query i iff j <= i), or
+ * SM_ATT_WINDOW (Swin: n = window*window tokens, rel-pos bias gathered from
+ * rpb_table [(2w-1)^2, heads], shifted-window mask computed from the window's
+ * position on the H x W grid when shift > 0; masked logits get -100). */
+enum { SM_ATT_FULL = 0, SM_ATT_CAUSAL = 1, SM_ATT_WINDOW = 2 };
+typedef struct {
+  int32_t kind, dtype;
+  int32_t nb, heads, nq, nk, d;
+  float scale;
+  int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];   /* batch, head, token */
+  int32_t window, shift, H, W;      /* SM_ATT_WINDOW only; batch index = (image, wy, wx) row-major */
+} sm_attention_desc;
+int sm_attention(const sm_attention_desc*, const void* q, const void* k, const void* v, void* o,
+                 const void* rpb_table, void* stream);
+
+/* ------------------------------------------------------------------------ */
+/* Block and chain executors                                                  */
+/* ------------------------------------------------------------------------ */
+
+/* One Swin block on x [B, H*W, C] -> y [B, H*W, C]:
+ * LayerNorm -> (roll, window partition) -> QKV Linear -> window attention ->
+ * proj Linear -> (reverse, roll back) -> +x -> LayerNorm -> MLP (GELU) -> +.
+ * SM_ELIDED: 7 kernels, the layout transformations are folded into their
+ * neighbours' addressing as planned by sm_layout_plan.  SM_EXPLICIT: the same
+ * 7 kernels with identity maps plus one copy kernel per transformation that
+ * moves data (the baseline the paper's Table 1 calls explicit). */
+typedef struct { int32_t B, H, W, C, heads, window, shift, mlp_ratio, dtype; float eps; } sm_swin_cfg;
+typedef struct {
+  const void *ln1_g, *ln1_b, *wqkv, *bqkv, *rpb_table, *wproj, *bproj,
+             *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+} sm_swin_weights;
+size_t sm_swin_block_workspace_bytes(const sm_swin_cfg*, int mode);
+int sm_swin_block(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y,
+                  void* ws, size_t ws_bytes, int mode, void* stream);
+
+/* Llama-style decoder layer (prefill) or diffusion-UNet spatial-transformer
+ * block.  weights: array of device pointers in this order
+ *   SM_ATTN_LLAMA (9): rms1_g, wqkv [3E, E] (rows q | k | v), wo, rms2_g,
+ *                      w_gate_up [2F, E] (rows gate | up), wdown [E, F]
+ *                      -- 6 pointers: {rms1_g, wqkv, wo, rms2_g, w_gate_up, wdown}
+ *   SM_ATTN_SD (23): gn_g, gn_b, win, bin, ln1_g, ln1_b, a1_wqkv [3C, C], a1_wo, a1_bo,
+ *                    ln2_g, ln2_b, a2_wq, a2_wkv [2C, Dc], a2_wo, a2_bo, ln3_g, ln3_b,
+ *                    ff_w1 [2F, C], ff_b1, ff_w2, ff_b2, wout, bout
+ * x: LLAMA [B, S, E]; SD NCHW [B, C, Hs, Ws]; context: SD only, [B, Sc, Dc]. */
+enum { SM_ATTN_LLAMA = 0, SM_ATTN_SD = 1 };
+typedef struct {
+  int32_t kind, dtype;
+  int32_t B, S, E, heads, F;          /* LLAMA: S tokens, E hidden; SD: S = Hs*Ws, E = C channels */
+  int32_t Hs, Ws, groups, Sc, Dc;     /* SD only */
+  float rope_base, eps_norm, eps_gn;
+} sm_attn_cfg;
+size_t sm_attn_block_workspace_bytes(const sm_attn_cfg*, int mode);
+int sm_attn_block(const sm_attn_cfg*, const void* const* weights, const void* x, const void* context,
+                  void* y, void* ws, size_t ws_bytes, int mode, void* stream);
+
+/* A Swin chain: optional patch embedding (NCHW image, patch x patch stride
+ * patch unfold folded into the Linear's A addressing), stages of blocks
+ * (block k of a stage shifts by window/2 when k is odd and the stage is larger
+ * than one window), patch merging between stages (2x2 gather folded into the
+ * LayerNorm's load), optional head (LayerNorm, mean over tokens, Linear).
+ * weights: device pointers in forward order: embed {w, b, ln_g, ln_b} if
+ * has_embed; per stage: per block the 13 pointers of sm_swin_weights in
+ * declaration order, then (between stages) merge {ln_g, ln_b, w}; head
+ * {ln_g, ln_b, w, b} if has_head.
+ * x: image [B, in_ch, img, img] if has_embed else tokens [B, H0*W0, C0].
+ * y: logits [B, n_cls] if has_head else tokens of the last stage.
+ * y_feat (nullable): the normalised feature map [B, L_last, C_last] before pooling. */
+typedef struct { int32_t C, heads, depth, H, W; } sm_stage_desc;
+typedef struct {
+  int32_t B, dtype, window, mlp_ratio;
+  int32_t has_embed, in_ch, img, patch;
+  int32_t n_stages; sm_stage_desc stages[4];
+  int32_t has_head, n_cls;
+  float eps;
+} sm_chain_desc;
+size_t sm_run_chain_workspace_bytes(const sm_chain_desc*, int mode);
+int sm_run_chain(const sm_chain_desc*, const void* const* weights, int n_weights, const void* x,
+                 void* y, void* y_feat, void* ws, size_t ws_bytes, int mode, void* stream);
+
+/* Number of kernels the last sm_swin_block / sm_attn_block / sm_run_chain call
+ * of this thread enqueued, split into compute and copy kernels. */
+int sm_last_launch_counts(int* n_compute, int* n_copy);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

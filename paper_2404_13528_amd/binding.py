@@ -1,0 +1,229 @@
+"""Thin ctypes binding of libsmartmem.so: argument marshalling only.
+
+Every computation happens inside the library's HIP kernels (or, for the
+host-side planner and index-map composer, its C++ host code).  There is no
+Python or CPU fallback: if the library is missing, loading raises.
+torch is used for device memory and streams only.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsmartmem.so")
+_lib = None
+
+SM_OK = 0
+SM_F32, SM_BF16 = 0, 1
+SM_ELIDED, SM_EXPLICIT = 0, 1
+MAX_RANK = 8
+GROUPS = ("ILD_VAR", "ILI_VAR", "ILD_FIX", "ILI_FIX")
+ACTIONS = ("KEEP_BOTH", "TRY_FUSE", "ELIM_2ND", "ELIM_1ST", "ELIM_BOTH")
+SEARCH = ("SEARCH_BOTH", "SEARCH_FUSED", "SEARCH_1ST", "SEARCH_2ND", "NO_SEARCH")
+STATUS = ("kept", "fused", "eliminated_store", "eliminated_load", "materialised")
+OP_KIND = {"CONV": 0, "MATMUL": 1, "LAYERNORM": 2, "SOFTMAX": 3, "GROUPNORM": 4, "RMSNORM": 5,
+           "ATTENTION": 6, "REDUCE": 7, "RESHAPE": 16, "TRANSPOSE": 17, "DTOS": 18, "STOD": 19,
+           "UNARY": 32, "ADD": 33, "MUL": 34, "BIAS": 35, "ROPE": 36,
+           "GATHER": 48, "SLICE": 49, "ROLL": 50, "CONCAT": 51}
+VIEW_KIND = {"reshape": 0, "permute": 1, "roll": 2, "slice": 3}
+ACT = {"none": 0, "gelu": 1, "swiglu": 2, "geglu": 3}
+ATT = {"full": 0, "causal": 1, "window": 2}
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("shape", C.c_int64 * MAX_RANK), ("dtype", C.c_int32)]
+
+
+class OpDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("n_in", C.c_int32), ("in_", C.c_int32 * 4), ("out", C.c_int32),
+                ("n_attr", C.c_int32), ("attr", C.c_int64 * 16)]
+
+
+class ViewOp(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("n", C.c_int32), ("arg", C.c_int64 * MAX_RANK)]
+
+
+class LinearDesc(C.Structure):
+    _fields_ = [("M", C.c_int64), ("N", C.c_int32), ("K", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
+                ("rope_cols", C.c_int32), ("rope_dim", C.c_int32), ("rope_seq", C.c_int32), ("rope_base", C.c_float),
+                ("c_transposed", C.c_int32), ("c_batch_rows", C.c_int64)]
+
+
+class AttentionDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("nb", C.c_int32), ("heads", C.c_int32),
+                ("nq", C.c_int32), ("nk", C.c_int32), ("d", C.c_int32), ("scale", C.c_float),
+                ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3), ("v_stride", C.c_int64 * 3),
+                ("o_stride", C.c_int64 * 3),
+                ("window", C.c_int32), ("shift", C.c_int32), ("H", C.c_int32), ("W", C.c_int32)]
+
+
+class SwinCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "H", "W", "C", "heads", "window", "shift", "mlp_ratio", "dtype")] + \
+               [("eps", C.c_float)]
+
+
+SWIN_WEIGHT_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rpb_table", "wproj", "bproj",
+                     "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+
+class SwinWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in SWIN_WEIGHT_NAMES]
+
+
+class AttnCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kind", "dtype", "B", "S", "E", "heads", "F", "Hs", "Ws", "groups", "Sc", "Dc")] + \
+               [("rope_base", C.c_float), ("eps_norm", C.c_float), ("eps_gn", C.c_float)]
+
+
+class StageDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("C", "heads", "depth", "H", "W")]
+
+
+class ChainDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("dtype", C.c_int32), ("window", C.c_int32), ("mlp_ratio", C.c_int32),
+                ("has_embed", C.c_int32), ("in_ch", C.c_int32), ("img", C.c_int32), ("patch", C.c_int32),
+                ("n_stages", C.c_int32), ("stages", StageDesc * 4),
+                ("has_head", C.c_int32), ("n_cls", C.c_int32), ("eps", C.c_float)]
+
+
+def lib():
+    """Loads the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libsmartmem.so is missing: run `python -m paper_2404_13528_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH, mode=C.RTLD_GLOBAL)
+        L.sm_last_error.restype = C.c_char_p
+        L.sm_map_numel.restype = C.c_int64
+        for f in ("sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes"):
+            getattr(L, f).restype = C.c_size_t
+        _lib = L
+    return _lib
+
+
+class SmError(RuntimeError):
+    pass
+
+
+def check(rc, what=""):
+    if rc < 0:
+        raise SmError("%s failed (%d): %s" % (what, rc, lib().sm_last_error().decode()))
+    return rc
+
+
+def _tdesc(shape, dtype=SM_F32):
+    t = TensorDesc()
+    t.rank = len(shape)
+    for i, s in enumerate(shape):
+        t.shape[i] = int(s)
+    t.dtype = dtype
+    return t
+
+
+def _view_ops(chain):
+    arr = (ViewOp * max(1, len(chain)))()
+    for i, op in enumerate(chain):
+        v = arr[i]
+        v.kind = VIEW_KIND[op[0]]
+        if op[0] in ("reshape", "permute"):
+            v.n = len(op[1])
+            for k, a in enumerate(op[1]):
+                v.arg[k] = int(a)
+        elif op[0] == "roll":
+            v.n = 2
+            v.arg[0], v.arg[1] = int(op[1]), int(op[2])
+        else:
+            v.n = 4
+            v.arg[0], v.arg[1], v.arg[2] = int(op[1]), int(op[2]), int(op[3])
+            v.arg[3] = int(op[4]) if len(op) > 4 else 1
+    return arr
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dt(t):
+    import torch
+    if t.dtype == torch.float32:
+        return SM_F32
+    if t.dtype == torch.bfloat16:
+        return SM_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+class Map:
+    """Handle of a composed index map (sm_map)."""
+
+    def __init__(self, handle, owned=True):
+        self.h = handle
+        self.owned = owned
+
+    @classmethod
+    def create(cls, src_shape, chain):
+        h = C.c_void_p()
+        src = _tdesc(src_shape)
+        check(lib().sm_map_create(C.byref(src), _view_ops(chain), len(chain), C.byref(h)), "sm_map_create")
+        return cls(h)
+
+    def compose(self, outer):
+        h = C.c_void_p()
+        check(lib().sm_map_compose(self.h, outer.h, C.byref(h)), "sm_map_compose")
+        return Map(h)
+
+    @property
+    def shape(self):
+        r = lib().sm_map_rank(self.h)
+        s = (C.c_int64 * MAX_RANK)()
+        check(lib().sm_map_shape(self.h, s), "sm_map_shape")
+        return tuple(s[i] for i in range(r))
+
+    def numel(self):
+        return lib().sm_map_numel(self.h)
+
+    def cost(self):
+        a, b = C.c_int(), C.c_int()
+        check(lib().sm_map_cost(self.h, C.byref(a), C.byref(b)), "sm_map_cost")
+        return a.value, b.value
+
+    def eval_host(self):
+        import numpy as np
+        n = self.numel()
+        out = np.empty(n, dtype=np.int64)
+        check(lib().sm_map_eval_host(self.h, out.ctypes.data_as(C.POINTER(C.c_int64)), C.c_int64(n)), "sm_map_eval_host")
+        return out.reshape(self.shape)
+
+    def affine(self):
+        base = C.c_int64()
+        st = (C.c_int64 * MAX_RANK)()
+        r = check(lib().sm_map_affine(self.h, C.byref(base), st), "sm_map_affine")
+        return (base.value, tuple(st[i] for i in range(len(self.shape)))) if r == 1 else None
+
+    def gather_host(self, src):
+        """numpy in, numpy out, executed by the library's host path."""
+        import numpy as np
+        src = np.ascontiguousarray(src)
+        dt = {4: SM_F32, 2: SM_BF16}[src.dtype.itemsize]
+        dst = np.empty(self.shape, dtype=src.dtype)
+        check(lib().sm_gather_mapped(self.h, src.ctypes.data_as(C.c_void_p), dst.ctypes.data_as(C.c_void_p),
+                                     dt, 0, None), "sm_gather_mapped")
+        return dst
+
+    def gather(self, src, stream=None):
+        """torch device tensor in, new torch device tensor out (HIP kernel)."""
+        import torch
+        assert src.is_cuda and src.is_contiguous()
+        dst = torch.empty(self.shape, dtype=src.dtype, device=src.device)
+        check(lib().sm_gather_mapped(self.h, _ptr(src), _ptr(dst), _dt(src), 1, _stream(stream)), "sm_gather_mapped")
+        return dst
+
+    def __del__(self):
+        if self.owned and self.h and _lib is not None:
+            _lib.sm_map_destroy(self.h)
+            self.h = None

@@ -1,0 +1,71 @@
+// Device-side helpers: bf16 conversion, index-program evaluation, wave reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include "index_map.h"
+
+namespace sm {
+
+typedef unsigned short bf16_t;     // raw bits
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest even
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int VEC = 4;     // elements per 16 bytes
+  __device__ static float ld(const float* p) { return *p; }
+  __device__ static void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int VEC = 8;
+  __device__ static float ld(const bf16_t* p) { return bf2f(*p); }
+  __device__ static void st(bf16_t* p, float v) { *p = f2bf(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// value of atom list for one variable assignment; vars[] are the view indices
+template <int NV>
+__device__ __forceinline__ void eval_atoms(const ProgAtom* atoms, int n_atoms, const int* vars, int* val) {
+  for (int i = 0; i < n_atoms; ++i) {
+    const ProgAtom& a = atoms[i];
+    int x = a.c0;
+    for (int t = 0; t < a.nterm; ++t) {
+      int id = a.t_atom[t];
+      x += a.t_coef[t] * (id < 0 ? vars[~id] : val[id]);
+    }
+    if (a.div > 1) x /= a.div;
+    if (a.mod > 0) x %= a.mod;
+    val[i] = x;
+  }
+}
+
+__device__ __forceinline__ int64_t eval_rows(const RowProg& p, int64_t r) {
+  if (p.identity) return r * p.ld;
+  int val[PROG_MAX_ATOMS];
+  int vars[1] = {(int)r};
+  eval_atoms<1>(p.atoms, p.n_atoms, vars, val);
+  int64_t off = p.c0;
+  for (int t = 0; t < p.nterm; ++t) {
+    int id = p.t_atom[t];
+    off += p.t_coef[t] * (int64_t)(id < 0 ? vars[0] : val[id]);
+  }
+  return off;
+}
+
+}  // namespace sm

@@ -1,0 +1,48 @@
+// out[o] = in[map(o)]: the materialised form of an eliminated layout
+// transformation (paper Sec. 2.2 "explicit" transformations; Sec. 3.2.1 folds
+// them into index computation instead).  One thread per vector of `vec`
+// consecutive view elements along the last axis; the host guarantees that the
+// map moves such vectors as a whole (unit stride, no // or % on the last axis
+// finer than vec, aligned offsets).
+#include "device_common.h"
+#include "kernels.h"
+
+namespace sm {
+
+template <typename V>
+__global__ __launch_bounds__(256) void gather_kernel(MapProg p, int64_t nvec, int vec, const V* __restrict__ src, V* __restrict__ dst) {
+  int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= nvec) return;
+  int vars[SM_MAX_RANK];
+  int64_t rem = o;
+  for (int k = p.rank - 1; k >= 0; --k) {
+    int ext = p.shape[k];
+    if (k == p.rank - 1) ext /= vec;
+    vars[k] = (int)(rem % ext);
+    rem /= ext;
+  }
+  vars[p.rank - 1] *= vec;
+  int val[PROG_MAX_ATOMS];
+  eval_atoms<SM_MAX_RANK>(p.atoms, p.n_atoms, vars, val);
+  int64_t off = p.c0;
+  for (int t = 0; t < p.nterm; ++t) {
+    int id = p.t_atom[t];
+    off += p.t_coef[t] * (int64_t)(id < 0 ? vars[~id] : val[id]);
+  }
+  dst[o] = src[off / vec];
+}
+
+int launch_gather(const MapProg& prog, int64_t numel, int vec_elems, const void* src, void* dst, int esize, void* stream) {
+  if (numel == 0) return 0;
+  int64_t nvec = numel / vec_elems;
+  dim3 grid((unsigned)((nvec + 255) / 256)), block(256);
+  hipStream_t s = (hipStream_t)stream;
+  int bytes = vec_elems * esize;
+  if (bytes == 16) gather_kernel<uint4><<<grid, block, 0, s>>>(prog, nvec, vec_elems, (const uint4*)src, (uint4*)dst);
+  else if (bytes == 8) gather_kernel<uint2><<<grid, block, 0, s>>>(prog, nvec, vec_elems, (const uint2*)src, (uint2*)dst);
+  else if (bytes == 4) gather_kernel<uint32_t><<<grid, block, 0, s>>>(prog, nvec, vec_elems, (const uint32_t*)src, (uint32_t*)dst);
+  else gather_kernel<uint16_t><<<grid, block, 0, s>>>(prog, nvec, vec_elems, (const uint16_t*)src, (uint16_t*)dst);
+  return (int)hipGetLastError();
+}
+
+}  // namespace sm

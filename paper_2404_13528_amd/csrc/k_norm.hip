@@ -1,0 +1,190 @@
+// LayerNorm / RMSNorm / GroupNorm / token mean: HBM-bound, one pass over the
+// data, fp32 statistics with wavefront-shuffle reductions.  The row kernels
+// read and write through row programs, so that a following or preceding
+// layout transformation (window partition / reverse, cyclic roll, patch-merge
+// gather) costs only address arithmetic (paper Sec. 3.2.1; LayerNorm is
+// ILD & Variable in Table 3: its output layout is free to choose).
+#include "device_common.h"
+#include "kernels.h"
+
+namespace sm {
+
+template <typename T> struct Vec16;
+template <> struct Vec16<float> { typedef float4 type; };
+template <> struct Vec16<bf16_t> { typedef uint4 type; };
+
+template <typename T>
+__device__ __forceinline__ void unpack(const typename Vec16<T>::type& v, float* f);
+template <>
+__device__ __forceinline__ void unpack<float>(const float4& v, float* f) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+template <>
+__device__ __forceinline__ void unpack<bf16_t>(const uint4& v, float* f) {
+  const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { f[2 * i] = __uint_as_float(w[i] << 16); f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+}
+template <typename T>
+__device__ __forceinline__ typename Vec16<T>::type pack(const float* f);
+template <>
+__device__ __forceinline__ float4 pack<float>(const float* f) { return make_float4(f[0], f[1], f[2], f[3]); }
+template <>
+__device__ __forceinline__ uint4 pack<bf16_t>(const float* f) {
+  unsigned w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = (unsigned)f2bf(f[2 * i]) | ((unsigned)f2bf(f[2 * i + 1]) << 16);
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// One wave per logical row; lane l owns 16-byte chunks l, l+64, ...
+template <typename T, int MAXCH>
+__global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
+  constexpr int VEC = Elem<T>::VEC;
+  typedef typename Vec16<T>::type V;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= a.rows) return;
+  const int nchunk = a.C / VEC;
+  const int seg_chunks = nchunk / a.nseg;
+  // segment base offsets: lane j < nseg evaluates segment j, then broadcast
+  int64_t my_seg = 0;
+  if (lane < a.nseg) my_seg = eval_rows(a.load, row * a.nseg + lane);
+  const T* x = (const T*)a.x;
+  float v[MAXCH][VEC];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXCH; ++i) {
+    const int ch = lane + 64 * i;
+    const int seg = ch < nchunk ? ch / seg_chunks : 0;
+    const int64_t base = __shfl(my_seg, seg, 64);
+    if (ch < nchunk) {
+      V raw = *(const V*)(x + base + (int64_t)(ch - seg * seg_chunks) * VEC);
+      unpack<T>(raw, v[i]);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sum += v[i][e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[i][e] = 0.f;
+    }
+  }
+  float mean = 0.f, ss = 0.f;
+  if (!a.rms) mean = wave_sum(sum) / (float)a.C;
+#pragma unroll
+  for (int i = 0; i < MAXCH; ++i) {
+    if (lane + 64 * i < nchunk) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { float dlt = v[i][e] - mean; ss += dlt * dlt; }
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(ss) / (float)a.C + a.eps);
+  const int64_t obase = eval_rows(a.store, row);
+  T* y = (T*)a.y;
+  const T* g = (const T*)a.gamma;
+  const T* bta = (const T*)a.beta;
+#pragma unroll
+  for (int i = 0; i < MAXCH; ++i) {
+    const int ch = lane + 64 * i;
+    if (ch < nchunk) {
+      float gg[VEC], bb[VEC], o[VEC];
+      unpack<T>(*(const V*)(g + ch * VEC), gg);
+      if (!a.rms && bta) unpack<T>(*(const V*)(bta + ch * VEC), bb);
+      else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) bb[e] = 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o[e] = (v[i][e] - mean) * rstd * gg[e] + bb[e];
+      *(V*)(y + obase + (int64_t)ch * VEC) = pack<T>(o);
+    }
+  }
+}
+
+template <typename T>
+static int norm_dispatch(const NormArgs& a, hipStream_t s) {
+  constexpr int VEC = Elem<T>::VEC;
+  const int nchunk = a.C / VEC;
+  dim3 grid((unsigned)((a.rows + 3) / 4)), block(256);
+  if (nchunk <= 64) norm_rows_kernel<T, 1><<<grid, block, 0, s>>>(a);
+  else if (nchunk <= 128) norm_rows_kernel<T, 2><<<grid, block, 0, s>>>(a);
+  else if (nchunk <= 256) norm_rows_kernel<T, 4><<<grid, block, 0, s>>>(a);
+  else norm_rows_kernel<T, 8><<<grid, block, 0, s>>>(a);
+  return (int)hipGetLastError();
+}
+
+int launch_norm(const NormArgs& a, void* stream) {
+  if (a.rows == 0) return 0;
+  return a.dtype == SM_F32 ? norm_dispatch<float>(a, (hipStream_t)stream) : norm_dispatch<bf16_t>(a, (hipStream_t)stream);
+}
+
+// ---- GroupNorm over NCHW: one workgroup per (image, group); the group's
+// channels are one contiguous run of cpg*HW elements.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+
+template <typename T>
+__global__ __launch_bounds__(512) void groupnorm_kernel(GroupNormArgs a) {
+  __shared__ float red[8];
+  const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
+  const int cpg = a.C / a.G;
+  const int64_t n = (int64_t)cpg * a.HW;
+  const T* x = (const T*)a.x + ((int64_t)b * a.C + (int64_t)g * cpg) * a.HW;
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += blockDim.x) s += Elem<T>::ld(x + i);
+  const float mean = block_sum(s, red) / (float)n;
+  float ss = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += blockDim.x) { float d = Elem<T>::ld(x + i) - mean; ss += d * d; }
+  const float rstd = rsqrtf(block_sum(ss, red) / (float)n + a.eps);
+  const T* gm = (const T*)a.gamma; const T* bt = (const T*)a.beta;
+  T* y = (T*)a.y;
+  if (!a.tokens_out) {
+    T* yo = y + ((int64_t)b * a.C + (int64_t)g * cpg) * a.HW;
+    for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
+      const int c = g * cpg + (int)(i / a.HW);
+      Elem<T>::st(yo + i, (Elem<T>::ld(x + i) - mean) * rstd * Elem<T>::ld(gm + c) + Elem<T>::ld(bt + c));
+    }
+  } else {
+    // token-major store [B, HW, C]: thread per token, cpg adjacent channels each
+    for (int t = threadIdx.x; t < a.HW; t += blockDim.x) {
+      T* yo = y + ((int64_t)b * a.HW + t) * a.C + g * cpg;
+      for (int c = 0; c < cpg; ++c) {
+        const int cc = g * cpg + c;
+        Elem<T>::st(yo + c, (Elem<T>::ld(x + (int64_t)c * a.HW + t) - mean) * rstd * Elem<T>::ld(gm + cc) + Elem<T>::ld(bt + cc));
+      }
+    }
+  }
+}
+
+int launch_groupnorm(const GroupNormArgs& a, void* stream) {
+  dim3 grid((unsigned)(a.B * a.G)), block(512);
+  if (a.dtype == SM_F32) groupnorm_kernel<float><<<grid, block, 0, (hipStream_t)stream>>>(a);
+  else groupnorm_kernel<bf16_t><<<grid, block, 0, (hipStream_t)stream>>>(a);
+  return (int)hipGetLastError();
+}
+
+// ---- mean over tokens: x [B, L, C] -> y [B, C]
+template <typename T>
+__global__ __launch_bounds__(256) void mean_tokens_kernel(const T* x, T* y, int L, int C) {
+  const int b = blockIdx.y;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  float s = 0.f;
+  const T* p = x + (int64_t)b * L * C + c;
+  for (int t = 0; t < L; ++t) s += Elem<T>::ld(p + (int64_t)t * C);
+  Elem<T>::st(y + (int64_t)b * C + c, s / (float)L);
+}
+
+int launch_mean_tokens(const void* x, void* y, int B, int L, int C, int dtype, void* stream) {
+  dim3 grid((unsigned)((C + 255) / 256), (unsigned)B), block(256);
+  if (dtype == SM_F32) mean_tokens_kernel<float><<<grid, block, 0, (hipStream_t)stream>>>((const float*)x, (float*)y, L, C);
+  else mean_tokens_kernel<bf16_t><<<grid, block, 0, (hipStream_t)stream>>>((const bf16_t*)x, (bf16_t*)y, L, C);
+  return (int)hipGetLastError();
+}
+
+}  // namespace sm

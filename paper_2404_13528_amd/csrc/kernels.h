@@ -1,0 +1,41 @@
+// Launchers of the HIP kernels (C++ linkage, called by the C-ABI layer).
+// Every launcher validates nothing: shapes and pointers are checked by the
+// callers before anything is enqueued.  Each returns the hipError_t of the
+// launch as an int (0 = success).
+#pragma once
+#include <cstdint>
+#include "index_map.h"
+
+namespace sm {
+
+int launch_gather(const MapProg& prog, int64_t numel, int vec_elems, const void* src, void* dst, int esize, void* stream);
+
+struct NormArgs {
+  const void* x; const void* gamma; const void* beta; void* y;
+  int64_t rows; int C; float eps; int rms; int dtype;
+  int nseg;             // a logical row is nseg segments of C/nseg elements; segment j of row r is load-row r*nseg+j
+  RowProg load, store;
+};
+int launch_norm(const NormArgs& a, void* stream);
+
+struct GroupNormArgs { const void* x; const void* gamma; const void* beta; void* y; int B, C, HW, G; float eps; int tokens_out; int dtype; };
+int launch_groupnorm(const GroupNormArgs& a, void* stream);
+
+struct GemmArgs {
+  const void* A; const void* W; const void* bias; const void* residual; void* C;
+  int64_t M; int N, K;          // N = rows of W (logical columns before gating)
+  int dtype, act;
+  int rope_cols, rope_dim, rope_seq; float rope_base;
+  int c_transposed; int64_t c_batch_rows;
+  int64_t ldw;                  // row pitch of W in elements
+  RowProg a_rows, c_rows;       // c_rows.ld = pitch of C / residual
+};
+int launch_gemm(const GemmArgs& a, void* stream);
+
+int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,
+                     const void* rpb_table, void* stream);
+
+// mean over tokens: x [B, L, C] -> y [B, C]
+int launch_mean_tokens(const void* x, void* y, int B, int L, int C, int dtype, void* stream);
+
+}  // namespace sm
