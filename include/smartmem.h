@@ -154,6 +154,9 @@ int sm_map_cost(const sm_map*, int* n_divmod, int* n_divmod_unsimplified);
 int sm_map_eval_host(const sm_map*, int64_t* offsets, int64_t n);
 /* 1 if the map is affine (no // or % left): then offset = base + sum stride[k]*i[k]. */
 int sm_map_affine(const sm_map*, int64_t* base, int64_t* strides /* SM_MAX_RANK */);
+/* Writes the simplified offset expression as text ("i0, i1, ..." are the view
+ * indices) into buf (n bytes, truncated). */
+int sm_map_describe(const sm_map*, char* buf, int n);
 void sm_map_destroy(sm_map*);
 
 /* dst[o] = src[map(o)] for every view element o; dst is contiguous with the

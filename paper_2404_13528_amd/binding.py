@@ -199,6 +199,11 @@ class Map:
         check(lib().sm_map_eval_host(self.h, out.ctypes.data_as(C.POINTER(C.c_int64)), C.c_int64(n)), "sm_map_eval_host")
         return out.reshape(self.shape)
 
+    def describe(self):
+        buf = C.create_string_buffer(4096)
+        check(lib().sm_map_describe(self.h, buf, 4096), "sm_map_describe")
+        return buf.value.decode()
+
     def affine(self):
         base = C.c_int64()
         st = (C.c_int64 * MAX_RANK)()
@@ -227,3 +232,71 @@ class Map:
         if self.owned and self.h and _lib is not None:
             _lib.sm_map_destroy(self.h)
             self.h = None
+
+
+# --------------------------------------------------------------------------
+# single operators (device tensors in, device tensors out)
+# --------------------------------------------------------------------------
+
+def norm(x, gamma, beta=None, eps=1e-5, rms=False, store_map=None, out=None, stream=None):
+    import torch
+    C_ = x.shape[-1]
+    rows = x.numel() // C_
+    y = torch.empty_like(x) if out is None else out
+    check(lib().sm_norm(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), C.c_int64(rows), C_, C.c_float(eps),
+                        int(rms), _dt(x), store_map.h if store_map else None, _stream(stream)), "sm_norm")
+    return y
+
+
+def groupnorm(x, gamma, beta, G, eps=1e-6, tokens_out=False, stream=None):
+    import torch
+    B, Cc, H, W = x.shape
+    y = torch.empty((B, H * W, Cc) if tokens_out else x.shape, dtype=x.dtype, device=x.device)
+    check(lib().sm_groupnorm(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), B, Cc, H * W, G, C.c_float(eps),
+                             int(tokens_out), _dt(x), _stream(stream)), "sm_groupnorm")
+    return y
+
+
+def linear(A, W, bias=None, residual=None, act="none", rope=None, a_map=None, c_map=None,
+           c_transposed_batch=0, out=None, M=None, stream=None):
+    """C = epilogue(A . W^T).  rope = (rope_cols, rope_dim, seq, base) or None."""
+    import torch
+    N, K = W.shape
+    if M is None:
+        M = A.numel() // K
+    n_out = N // 2 if act in ("swiglu", "geglu") else N
+    d = LinearDesc()
+    d.M, d.N, d.K, d.dtype, d.act = M, N, K, _dt(A), ACT[act]
+    if rope:
+        d.rope_cols, d.rope_dim, d.rope_seq, d.rope_base = rope
+    d.c_transposed = 1 if c_transposed_batch else 0
+    d.c_batch_rows = c_transposed_batch
+    Cm = torch.empty((M, n_out), dtype=A.dtype, device=A.device) if out is None else out
+    check(lib().sm_linear(C.byref(d), _ptr(A), _ptr(W), _ptr(bias), _ptr(residual), _ptr(Cm),
+                          a_map.h if a_map else None, c_map.h if c_map else None, _stream(stream)), "sm_linear")
+    return Cm
+
+
+def attention(q, k, v, kind="full", scale=None, out=None, rpb_table=None, window=0, shift=0, H=0, W=0,
+              shape=None, q_stride=None, k_stride=None, v_stride=None, o_stride=None, stream=None):
+    """q, k, v: 4-D tensors [nb, heads, n, d] (any strides with unit innermost stride), or raw
+    buffers with explicit shape = (nb, heads, nq, nk, d) and element strides (batch, head, token)."""
+    import torch
+    d = AttentionDesc()
+    if shape is None:
+        nb, heads, nq, dd = q.shape
+        nk = k.shape[2]
+        q_stride, k_stride, v_stride = q.stride()[:3], k.stride()[:3], v.stride()[:3]
+        if out is None:
+            out = torch.empty((nb, heads, nq, dd), dtype=q.dtype, device=q.device)
+        o_stride = out.stride()[:3]
+    else:
+        nb, heads, nq, nk, dd = shape
+    d.kind, d.dtype, d.nb, d.heads, d.nq, d.nk, d.d = ATT[kind], _dt(q), nb, heads, nq, nk, dd
+    d.scale = dd ** -0.5 if scale is None else scale
+    for i in range(3):
+        d.q_stride[i], d.k_stride[i], d.v_stride[i], d.o_stride[i] = q_stride[i], k_stride[i], v_stride[i], o_stride[i]
+    d.window, d.shift, d.H, d.W = window, shift, H, W
+    check(lib().sm_attention(C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rpb_table), _stream(stream)),
+          "sm_attention")
+    return out

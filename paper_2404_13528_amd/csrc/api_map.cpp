@@ -99,3 +99,30 @@ extern "C" int sm_gather_mapped(const sm_map* m, const void* src, void* dst, int
   count_copy();
   return SM_OK;
 }
+
+// Human-readable form of the simplified map ("i0, i1, ..." are the view indices).
+static std::string affine_str(const sm_map* m, const Affine& a);
+static std::string atom_str(const sm_map* m, int id) {
+  const Atom& t = m->atoms[id];
+  if (t.kind == ATOM_VAR) return "i" + std::to_string(t.var);
+  std::string s = "(" + affine_str(m, t.arg) + ")";
+  if (t.div > 1) s += " // " + std::to_string(t.div);
+  if (t.mod > 0) s = "(" + s + ") % " + std::to_string(t.mod);
+  return "(" + s + ")";
+}
+static std::string affine_str(const sm_map* m, const Affine& a) {
+  std::string s;
+  for (auto& t : a.terms) {
+    if (!s.empty()) s += " + ";
+    if (t.second != 1) s += std::to_string(t.second) + "*";
+    s += atom_str(m, t.first);
+  }
+  if (a.c0 || s.empty()) s += (s.empty() ? "" : " + ") + std::to_string(a.c0);
+  return s;
+}
+extern "C" int sm_map_describe(const sm_map* m, char* buf, int n) {
+  if (!m || !buf || n < 1) return fail(SM_ERR_INVALID_ARG, "sm_map_describe: bad argument");
+  std::string s = affine_str(m, m->offset);
+  snprintf(buf, n, "%s", s.c_str());
+  return SM_OK;
+}

@@ -1,0 +1,135 @@
+// C ABI of the single operators: validation and map compilation, then one launch.
+#include <cstring>
+#include "common.h"
+#include "index_map.h"
+#include "kernels.h"
+
+using namespace sm;
+
+namespace sm {
+
+// row program of a map whose view has `rows * inner` elements and last dimension `inner`
+int rows_of(const sm_map* m, int64_t rows, int64_t inner, int64_t identity_ld, RowProg* out, const char* who) {
+  if (!m) { *out = identity_rows(identity_ld); return SM_OK; }
+  if (m->numel() != rows * inner || m->shape.back() != inner)
+    return fail(SM_ERR_SHAPE, "%s: map has %lld elements / last dimension %lld, operand needs %lld x %lld", who,
+                (long long)m->numel(), (long long)m->shape.back(), (long long)rows, (long long)inner);
+  std::string err;
+  if (!m->compile_rows(out, &err)) return fail(SM_ERR_UNSUPPORTED, "%s: %s", who, err.c_str());
+  return SM_OK;
+}
+
+int norm_checked(NormArgs& a, void* stream, const char* who) {
+  if (!a.x || !a.gamma || !a.y) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
+  if (!dtype_ok(a.dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
+  const int vec = a.dtype == SM_F32 ? 4 : 8;
+  if (a.rows < 0 || a.C < 1 || a.nseg < 1 || a.C % a.nseg) return fail(SM_ERR_SHAPE, "%s: bad shape", who);
+  if (a.C % vec || (a.C / a.nseg) % vec) return fail(SM_ERR_SHAPE, "%s: C (and C / segments) must be a multiple of %d", who, vec);
+  if (a.C / vec > 512) return fail(SM_ERR_UNSUPPORTED, "%s: C = %d exceeds %d", who, a.C, 512 * vec);
+  if (!aligned16(a.x) || !aligned16(a.y) || !aligned16(a.gamma) || (a.beta && !aligned16(a.beta)))
+    return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  int rc = launch_norm(a, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
+  count_compute();
+  return SM_OK;
+}
+
+int gemm_checked(GemmArgs& g, void* stream, const char* who) {
+  if (!g.A || !g.W || !g.C) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
+  if (!dtype_ok(g.dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
+  const int vec = g.dtype == SM_F32 ? 4 : 8;
+  if (g.M < 0 || g.N < 1 || g.K < 1) return fail(SM_ERR_SHAPE, "%s: bad shape", who);
+  if (g.K % vec || g.ldw % vec) return fail(SM_ERR_SHAPE, "%s: K and the pitch of W must be multiples of %d", who, vec);
+  if (g.act < SM_ACT_NONE || g.act > SM_ACT_GEGLU) return fail(SM_ERR_INVALID_ARG, "%s: unknown activation", who);
+  const bool gated = g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU;
+  if (gated && (g.N % 64)) return fail(SM_ERR_SHAPE, "%s: gated activations need N / 2 to be a multiple of 32", who);
+  if (gated && g.rope_cols) return fail(SM_ERR_UNSUPPORTED, "%s: RoPE with a gated activation", who);
+  if (g.rope_cols) {
+    if (g.rope_dim < 64 || g.rope_dim % 64 || g.rope_cols % g.rope_dim || g.rope_cols > g.N || g.rope_seq < 1)
+      return fail(SM_ERR_SHAPE, "%s: RoPE needs head size a multiple of 64 and whole heads", who);
+  }
+  if (g.c_transposed && (g.c_batch_rows < 1 || g.M % g.c_batch_rows)) return fail(SM_ERR_SHAPE, "%s: bad transposed-store batch", who);
+  if (!aligned16(g.A) || !aligned16(g.W) || !aligned16(g.C)) return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  if ((int64_t)g.N * g.ldw > INT32_MAX * 16LL) return fail(SM_ERR_UNSUPPORTED, "%s: weight too large", who);
+  int rc = launch_gemm(g, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
+  count_compute();
+  return SM_OK;
+}
+
+int attention_checked(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table,
+                      void* stream, const char* who) {
+  if (!q || !k || !v || !o) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
+  if (!dtype_ok(d.dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
+  if (d.kind < SM_ATT_FULL || d.kind > SM_ATT_WINDOW) return fail(SM_ERR_INVALID_ARG, "%s: unknown kind", who);
+  if (d.nb < 1 || d.heads < 1 || d.nq < 1 || d.nk < 1 || d.d < 1) return fail(SM_ERR_SHAPE, "%s: bad shape", who);
+  const int vec = d.dtype == SM_F32 ? 4 : 8;
+  if (d.d % vec || d.d > 128) return fail(SM_ERR_SHAPE, "%s: head size must be a multiple of %d and <= 128", who, vec);
+  for (int i = 0; i < 3; ++i)
+    if (d.q_stride[i] % vec || d.k_stride[i] % vec || d.v_stride[i] % vec || d.o_stride[i] % 4)
+      return fail(SM_ERR_SHAPE, "%s: strides must keep 16-byte alignment", who);
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  if (d.kind == SM_ATT_CAUSAL && d.nq != d.nk) return fail(SM_ERR_SHAPE, "%s: causal attention needs nq == nk", who);
+  if (d.kind == SM_ATT_WINDOW) {
+    if (!table) return fail(SM_ERR_INVALID_ARG, "%s: window attention needs the relative-position table", who);
+    if (d.window < 1 || d.nq != d.window * d.window || d.nk != d.nq) return fail(SM_ERR_SHAPE, "%s: window attention needs nq == nk == window^2", who);
+    if (d.H < d.window || d.W < d.window || d.H % d.window || d.W % d.window) return fail(SM_ERR_SHAPE, "%s: grid %d x %d is not a multiple of the window %d", who, d.H, d.W, d.window);
+    if (d.shift < 0 || d.shift >= d.window) return fail(SM_ERR_SHAPE, "%s: shift out of range", who);
+    if (d.nb % ((d.H / d.window) * (d.W / d.window))) return fail(SM_ERR_SHAPE, "%s: batch is not a whole number of images", who);
+  }
+  if (d.dtype == SM_F32) {
+    if (d.kind != SM_ATT_WINDOW) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 supports window attention only", who);
+    if (d.nq > 64 || d.d > 64) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 window attention needs window^2 <= 64 and head size <= 64", who);
+  }
+  int rc = launch_attention(d, q, k, v, o, table, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
+  count_compute();
+  return SM_OK;
+}
+
+}  // namespace sm
+
+extern "C" int sm_norm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows, int C, float eps,
+                       int rms, int dtype, const sm_map* store_map, void* stream) {
+  NormArgs a; std::memset(&a, 0, sizeof(a));
+  a.x = x; a.gamma = gamma; a.beta = beta; a.y = y; a.rows = rows; a.C = C; a.eps = eps; a.rms = rms; a.dtype = dtype; a.nseg = 1;
+  a.load = identity_rows(C);
+  int rc = rows_of(store_map, rows, C, C, &a.store, "sm_norm");
+  if (rc) return rc;
+  return norm_checked(a, stream, "sm_norm");
+}
+
+extern "C" int sm_groupnorm(const void* x, const void* gamma, const void* beta, void* y, int B, int C, int HW, int G,
+                            float eps, int tokens_out, int dtype, void* stream) {
+  if (!x || !gamma || !beta || !y) return fail(SM_ERR_INVALID_ARG, "sm_groupnorm: null pointer");
+  if (!dtype_ok(dtype)) return fail(SM_ERR_INVALID_ARG, "sm_groupnorm: unknown dtype");
+  if (B < 1 || C < 1 || HW < 1 || G < 1 || C % G) return fail(SM_ERR_SHAPE, "sm_groupnorm: bad shape");
+  GroupNormArgs a{x, gamma, beta, y, B, C, HW, G, eps, tokens_out, dtype};
+  int rc = launch_groupnorm(a, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "sm_groupnorm: launch failed (hip error %d)", rc);
+  count_compute();
+  return SM_OK;
+}
+
+extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, const void* bias, const void* residual,
+                         void* C, const sm_map* a_map, const sm_map* c_map, void* stream) {
+  if (!d) return fail(SM_ERR_INVALID_ARG, "sm_linear: null descriptor");
+  GemmArgs g; std::memset(&g, 0, sizeof(g));
+  g.A = A; g.W = W; g.bias = bias; g.residual = residual; g.C = C;
+  g.M = d->M; g.N = d->N; g.K = d->K; g.dtype = d->dtype; g.act = d->act;
+  g.rope_cols = d->rope_cols; g.rope_dim = d->rope_dim; g.rope_seq = d->rope_seq; g.rope_base = d->rope_base;
+  g.c_transposed = d->c_transposed; g.c_batch_rows = d->c_batch_rows; g.ldw = d->K;
+  const int n_out = (d->act == SM_ACT_SWIGLU || d->act == SM_ACT_GEGLU) ? d->N / 2 : d->N;
+  int rc = rows_of(a_map, d->M, d->K, d->K, &g.a_rows, "sm_linear(A)");
+  if (rc) return rc;
+  if (d->c_transposed && c_map) return fail(SM_ERR_UNSUPPORTED, "sm_linear: transposed store with a row map");
+  rc = rows_of(c_map, d->M, n_out, n_out, &g.c_rows, "sm_linear(C)");
+  if (rc) return rc;
+  return gemm_checked(g, stream, "sm_linear");
+}
+
+extern "C" int sm_attention(const sm_attention_desc* d, const void* q, const void* k, const void* v, void* o,
+                            const void* rpb_table, void* stream) {
+  if (!d) return fail(SM_ERR_INVALID_ARG, "sm_attention: null descriptor");
+  return attention_checked(*d, q, k, v, o, rpb_table, stream, "sm_attention");
+}

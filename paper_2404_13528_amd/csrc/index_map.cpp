@@ -94,6 +94,22 @@ struct Builder {
         }
     }
   }
+  // x = g*y + small with g | c, g > 1 and 0 <= small < g
+  bool split_by_factor(const Affine& x, int64_t c, int64_t* g_out, Affine* y, Affine* small) {
+    for (auto& cand : x.terms) {
+      const int64_t g = cand.second;
+      if (g <= 1 || c % g != 0 || g == c) continue;
+      Affine yy, ss;
+      yy.c0 = x.c0 / g; ss.c0 = x.c0 % g;
+      for (auto& t : x.terms) {
+        if (t.second % g == 0) add_term(yy, t.first, t.second / g);
+        else add_term(ss, t.first, t.second);
+      }
+      if (ss.terms.empty() && ss.c0 == 0) continue;     // nothing small: plain common factor, handled elsewhere
+      if (affine_hi(atoms, ss) < g) { *g_out = g; *y = yy; *small = ss; return true; }
+    }
+    return false;
+  }
   Affine div(Affine x, int64_t c) {
     if (c == 1) return x;
     if (!simplify) return digit(x, c, 0);
@@ -105,6 +121,15 @@ struct Builder {
       else add_term(r, t.first, t.second);
     }
     if (affine_hi(atoms, r) < c) return q;
+    {  // (g*Y + S) // (g*c') -> Y // c' when 0 <= S < g
+      Affine y, sm_;
+      int64_t g;
+      if (split_by_factor(r, c, &g, &y, &sm_)) {
+        add_scaled(q, div(y, c / g), 1);
+        recombine(q);
+        return q;
+      }
+    }
     if (r.c0 == 0 && r.terms.size() == 1 && r.terms[0].second == 1) {
       const Atom in = atoms[r.terms[0].first];
       if (in.kind == ATOM_DIGIT && (in.mod == 0 || in.mod % c == 0)) {
@@ -126,6 +151,16 @@ struct Builder {
     r.c0 = x.c0 % c;
     for (auto& t : x.terms) add_term(r, t.first, t.second % c);
     if (affine_hi(atoms, r) < c) return r;
+    {  // (g*Y + S) % (g*c') -> g*(Y % c') + S when 0 <= S < g
+      Affine y, sm_;
+      int64_t g;
+      if (split_by_factor(r, c, &g, &y, &sm_)) {
+        Affine out = sm_;
+        add_scaled(out, mod(y, c / g), g);
+        recombine(out);
+        return out;
+      }
+    }
     if (r.c0 == 0 && r.terms.size() == 1 && r.terms[0].second == 1) {
       const Atom in = atoms[r.terms[0].first];
       // (X % a) % c -> X % c when c divides a (the rule printed in Sec. 3.2.1), also through a division

@@ -1,0 +1,230 @@
+// Fused attention O = softmax(scale Q K^T + bias + mask) V reading Q, K, V in
+// place through 4-D strides, so that head split / merge permutes and the
+// q/k/v slices are address arithmetic (paper Sec. 3.2.1).  The paper treats
+// QK^T, Softmax and AV as separate operators and names tiled attention as
+// complementary (Sec. 6); here they are one ILD & Variable kernel.
+//
+// bf16 path (matrix cores): one wave owns 32 queries and walks the keys in
+// blocks of 32 with an online softmax.  Scores are computed transposed,
+// S^T = K Q^T, so that a lane holds one query (column) and 16 keys (rows):
+// row max / sum are in-lane reductions plus one cross-half shuffle, the
+// probabilities are already in the register layout the next MFMA wants as its
+// B operand (O^T = V^T P^T), and the running rescale of O^T is lane-local.
+// Window attention (Swin) adds the relative-position bias gathered from its
+// table and the shifted-window mask computed from the window's position: no
+// bias or mask tensor is ever materialised.
+//
+// fp32 path (window attention only): plain FMA kernel, one workgroup per
+// (window, head), K / V / scores in LDS.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace sm {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+struct WinGeom { int w, shift, H, W, nWx, nW; };
+
+__device__ __forceinline__ int region(int c, int extent, int w, int s) { return c < extent - w ? 0 : (c < extent - s ? 1 : 2); }
+
+// additive term for (query i, key j) of window `win` and head `hh`
+template <typename T>
+__device__ __forceinline__ float window_term(const WinGeom& g, const T* table, int heads, int hh, int win, int i, int j) {
+  const int yi = i / g.w, xi = i - yi * g.w, yj = j / g.w, xj = j - yj * g.w;
+  float t = Elem<T>::ld(table + ((yi - yj + g.w - 1) * (2 * g.w - 1) + (xi - xj + g.w - 1)) * heads + hh);
+  if (g.shift > 0) {
+    const int wy = win / g.nWx, wx = win - wy * g.nWx;
+    const int ri = 3 * region(wy * g.w + yi, g.H, g.w, g.shift) + region(wx * g.w + xi, g.W, g.w, g.shift);
+    const int rj = 3 * region(wy * g.w + yj, g.H, g.w, g.shift) + region(wx * g.w + xj, g.W, g.w, g.shift);
+    if (ri != rj) t += -100.f;
+  }
+  return t;
+}
+
+template <int DK, int DB>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                        const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
+                                                        const bf16_t* __restrict__ table, int n_qblk, long total_waves) {
+  const int lane = threadIdx.x & 63, l32 = lane & 31, hf = lane >> 5;
+  const long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (wid >= total_waves) return;
+  // query block fastest, then head, then batch: the waves of one workgroup share K and V
+  const int qb = (int)(wid % n_qblk);
+  const long bh = wid / n_qblk;
+  const int hh = (int)(bh % a.heads);
+  const int b = (int)(bh / a.heads);
+  const bf16_t* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
+  const bf16_t* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
+  const bf16_t* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
+  bf16_t* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
+  const int q0 = qb * 32, qi = q0 + l32;
+  const bool q_ok = qi < a.nq;
+  WinGeom wg;
+  int win = 0;
+  if (a.kind == SM_ATT_WINDOW) {
+    wg.w = a.window; wg.shift = a.shift; wg.H = a.H; wg.W = a.W; wg.nWx = a.W / a.window; wg.nW = (a.H / a.window) * wg.nWx;
+    win = b % wg.nW;
+  }
+  const uint4 zero = make_uint4(0, 0, 0, 0);
+  uint4 qf[DK];
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) {
+    const int e = 16 * ks + 8 * hf;
+    qf[ks] = (q_ok && e < a.d) ? *(const uint4*)(qp + (int64_t)qi * a.q_stride[2] + e) : zero;
+  }
+  f32x16_t oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  int n_kblk = (a.nk + 31) / 32;
+  if (a.kind == SM_ATT_CAUSAL) { const int lim = (min(q0 + 31, a.nq - 1)) / 32 + 1; n_kblk = min(n_kblk, lim); }
+
+  for (int jb = 0; jb < n_kblk; ++jb) {
+    const int j0 = jb * 32;
+    f32x16_t s;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+    {
+      const int kj = j0 + l32;
+      const bool k_ok = kj < a.nk;
+#pragma unroll
+      for (int ks = 0; ks < DK; ++ks) {
+        const int e = 16 * ks + 8 * hf;
+        const uint4 kf = (k_ok && e < a.d) ? *(const uint4*)(kp + (int64_t)kj * a.k_stride[2] + e) : zero;
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[ks]), s, 0, 0, 0);
+      }
+    }
+    float bm = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int j = j0 + (i >> 2) * 8 + hf * 4 + (i & 3);
+      float x = s[i] * a.scale;
+      if (a.kind == SM_ATT_WINDOW && q_ok && j < a.nk) x += window_term<bf16_t>(wg, table, a.heads, hh, win, qi, j);
+      if (j >= a.nk || (a.kind == SM_ATT_CAUSAL && j > qi)) x = -INFINITY;
+      s[i] = x;
+      bm = fmaxf(bm, x);
+    }
+    bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+    const float m_new = fmaxf(m_run, bm);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __expf(m_run - m_use);        // m_run = -inf gives 0
+    float rs = 0.f;
+    unsigned pk[8];
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+      const float p0 = __expf(s[i] - m_use), p1 = __expf(s[i + 1] - m_use);
+      const bf16_t h0 = f2bf(p0), h1 = f2bf(p1);
+      rs += bf2f(h0) + bf2f(h1);                      // the sum of what the MFMA will actually use
+      pk[i >> 1] = (unsigned)h0 | ((unsigned)h1 << 16);
+    }
+    rs += __shfl_xor(rs, 32, 64);
+    l_run = l_run * alpha + rs;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const uint4 pf = make_uint4(pk[4 * ks2], pk[4 * ks2 + 1], pk[4 * ks2 + 2], pk[4 * ks2 + 3]);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const int e = 32 * db + l32;
+        unsigned vw[4];
+#pragma unroll
+        for (int t = 0; t < 8; t += 2) {
+          const int ja = j0 + (2 * ks2 + (t >> 2)) * 8 + hf * 4 + (t & 3);
+          const unsigned lo = (ja < a.nk && e < a.d) ? vp[(int64_t)ja * a.v_stride[2] + e] : 0;
+          const unsigned hi = (ja + 1 < a.nk && e < a.d) ? vp[(int64_t)(ja + 1) * a.v_stride[2] + e] : 0;
+          vw[t >> 1] = lo | (hi << 16);
+        }
+        const uint4 vf = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf), oacc[db], 0, 0, 0);
+      }
+    }
+  }
+  if (!q_ok) return;
+  const float inv = 1.f / l_run;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int e = 32 * db + g4 * 8 + hf * 4;
+      if (e < a.d) {
+        const unsigned w0 = (unsigned)f2bf(oacc[db][4 * g4] * inv) | ((unsigned)f2bf(oacc[db][4 * g4 + 1] * inv) << 16);
+        const unsigned w1 = (unsigned)f2bf(oacc[db][4 * g4 + 2] * inv) | ((unsigned)f2bf(oacc[db][4 * g4 + 3] * inv) << 16);
+        *(uint2*)(op + (int64_t)qi * a.o_stride[2] + e) = make_uint2(w0, w1);
+      }
+    }
+}
+
+// fp32 window attention: nq, nk <= 64, d <= 64.  One workgroup of 64 threads
+// per (window, head); thread i owns query i.
+__global__ __launch_bounds__(64) void attn_window_f32_kernel(sm_attention_desc a, const float* __restrict__ q, const float* __restrict__ k,
+                                                             const float* __restrict__ v, float* __restrict__ o, const float* __restrict__ table) {
+  __shared__ float ks[64 * 65], vs[64 * 65], ss[64 * 65];
+  const int b = blockIdx.x / a.heads, hh = blockIdx.x % a.heads;
+  const float* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
+  const float* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
+  const float* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
+  float* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < a.nk * a.d; idx += 64) {
+    const int j = idx / a.d, e = idx - j * a.d;
+    ks[j * 65 + e] = kp[(int64_t)j * a.k_stride[2] + e];
+    vs[j * 65 + e] = vp[(int64_t)j * a.v_stride[2] + e];
+  }
+  __syncthreads();
+  WinGeom wg;
+  wg.w = a.window; wg.shift = a.shift; wg.H = a.H; wg.W = a.W; wg.nWx = a.W / a.window; wg.nW = (a.H / a.window) * wg.nWx;
+  const int win = b % wg.nW;
+  const int i = tid;
+  if (i >= a.nq) return;
+  float qr[64];
+#pragma unroll
+  for (int e = 0; e < 64; ++e) qr[e] = e < a.d ? qp[(int64_t)i * a.q_stride[2] + e] * a.scale : 0.f;
+  float mx = -INFINITY;
+  for (int j = 0; j < a.nk; ++j) {
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 64; ++e) if (e < a.d) s = fmaf(qr[e], ks[j * 65 + e], s);
+    if (a.kind == SM_ATT_WINDOW) s += window_term<float>(wg, table, a.heads, hh, win, i, j);
+    ss[i * 65 + j] = s;
+    mx = fmaxf(mx, s);
+  }
+  float sum = 0.f;
+  for (int j = 0; j < a.nk; ++j) { const float p = expf(ss[i * 65 + j] - mx); ss[i * 65 + j] = p; sum += p; }
+  const float inv = 1.f / sum;
+  for (int e = 0; e < a.d; ++e) {
+    float acc = 0.f;
+    for (int j = 0; j < a.nk; ++j) acc = fmaf(ss[i * 65 + j], vs[j * 65 + e], acc);
+    op[(int64_t)i * a.o_stride[2] + e] = acc * inv;
+  }
+}
+
+int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,
+                     const void* rpb_table, void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  if (d.dtype == SM_F32) {
+    attn_window_f32_kernel<<<dim3((unsigned)(d.nb * d.heads)), dim3(64), 0, s>>>(d, (const float*)q, (const float*)k, (const float*)v,
+                                                                               (float*)o, (const float*)rpb_table);
+    return (int)hipGetLastError();
+  }
+  const int n_qblk = (d.nq + 31) / 32;
+  const long waves = (long)d.nb * d.heads * n_qblk;
+  dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+  const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v, *tt = (const bf16_t*)rpb_table;
+  bf16_t* oo = (bf16_t*)o;
+  const int dk = (d.d + 15) / 16;
+  if (dk <= 2) attn_bf16_kernel<2, 1><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
+  else if (dk == 3) attn_bf16_kernel<3, 2><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
+  else if (dk == 4) attn_bf16_kernel<4, 2><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
+  else if (dk <= 6) attn_bf16_kernel<6, 3><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
+  else attn_bf16_kernel<8, 4><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
+  return (int)hipGetLastError();
+}
+
+}  // namespace sm

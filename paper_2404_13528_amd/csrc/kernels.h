@@ -39,3 +39,13 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
 int launch_mean_tokens(const void* x, void* y, int B, int L, int C, int dtype, void* stream);
 
 }  // namespace sm
+
+// validated wrappers shared by the single-operator entry points and the block executors
+namespace sm {
+int rows_of(const sm_map* m, int64_t rows, int64_t inner, int64_t identity_ld, RowProg* out, const char* who);
+int norm_checked(NormArgs& a, void* stream, const char* who);
+int gemm_checked(GemmArgs& g, void* stream, const char* who);
+int attention_checked(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table,
+                      void* stream, const char* who);
+int map_vector_width(const sm_map& m, int esize);
+}

@@ -1,0 +1,194 @@
+"""GPU parity of the single operators against the oracle, through the C ABI,
+on stress distributions (O(1) logits, O(1) biases) so that a wrong index, sign
+or pairing cannot hide inside the tolerances."""
+import numpy as np
+import pytest
+import torch
+from oracle import ops as O, views as V, swin
+from paper_2404_13528_amd import binding as sm
+from util import to_np, dev, assert_close
+
+pytestmark = pytest.mark.gpu
+DT = [torch.float32, torch.bfloat16]
+
+
+def draw(shape, seed, dtype, std=1.0, mean=0.0):
+    g = torch.Generator().manual_seed(seed)
+    t = torch.randn(shape, generator=g) * std + mean
+    return t.to(dtype).float()          # values both sides consume
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("rows,C", [(37, 96), (200, 384), (5, 1024), (3, 4096)])
+def test_layernorm_and_rmsnorm(dtype, rows, C):
+    if dtype == torch.float32 and C > 2048:
+        pytest.skip("fp32 rows are limited to 2048 columns")
+    x = draw((rows, C), 1, dtype, 2.0, 0.5)
+    g = draw((C,), 2, dtype, 0.2, 1.0)
+    b = draw((C,), 3, dtype, 0.2)
+    y = sm.norm(dev(x, dtype), dev(g, dtype), dev(b, dtype))
+    assert_close(y, O.layer_norm(to_np(x), to_np(g), to_np(b)), dtype, "layernorm", 4.0)
+    y = sm.norm(dev(x, dtype), dev(g, dtype), None, rms=True)
+    assert_close(y, O.rms_norm(to_np(x), to_np(g)), dtype, "rmsnorm", 4.0)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("s", [0, 3])
+def test_layernorm_store_through_window_map(dtype, s):
+    B, H, W, C, w = 2, 14, 21, 96, 7
+    x = draw((B, H * W, C), 4, dtype)
+    g = draw((C,), 5, dtype, 0.2, 1.0)
+    b = draw((C,), 6, dtype, 0.2)
+    # natural output index -> position in the window-major tensor = map of the inverse chain
+    inv = sm.Map.create((B * (H // w) * (W // w), w * w, C), V.window_reverse_chain(B, H, W, C, w, s))
+    y = sm.norm(dev(x, dtype), dev(g, dtype), dev(b, dtype), store_map=inv)
+    ln = O.layer_norm(to_np(x), to_np(g), to_np(b)).reshape(B, H, W, C)
+    want = V.apply_chain(ln, V.window_partition_chain(B, H, W, C, w, s))
+    assert_close(y.reshape(want.shape), want, dtype, "layernorm -> windows", 4.0)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("tokens_out", [False, True])
+def test_groupnorm(dtype, tokens_out):
+    B, C, H, W, G = 2, 64, 9, 7, 8
+    x = draw((B, C, H, W), 7, dtype, 2.0, -0.5)
+    g = draw((C,), 8, dtype, 0.2, 1.0)
+    b = draw((C,), 9, dtype, 0.2)
+    y = sm.groupnorm(dev(x, dtype), dev(g, dtype), dev(b, dtype), G, tokens_out=tokens_out)
+    want = O.group_norm_nchw(to_np(x), G, to_np(g), to_np(b))
+    if tokens_out:
+        want = V.apply_chain(want, V.nchw_to_tokens_chain(B, C, H, W))
+    assert_close(y, want, dtype, "groupnorm", 4.0)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("M,N,K", [(70, 96, 96), (300, 288, 96), (129, 130, 200), (1000, 384, 1536), (9000, 256, 64)])
+def test_linear_plain_bias_gelu_residual(dtype, M, N, K):
+    if dtype == torch.bfloat16 and N % 2:
+        pytest.skip("odd N")
+    A = draw((M, K), 10, dtype)
+    W = draw((N, K), 11, dtype, K ** -0.5)
+    b = draw((N,), 12, dtype)
+    R = draw((M, N), 13, dtype)
+    want = O.linear(to_np(A), to_np(W))
+    scale = float(np.abs(want).max()) + 1.0
+    assert_close(sm.linear(dev(A, dtype), dev(W, dtype)), want, dtype, "A W^T", scale)
+    want = O.gelu(O.linear(to_np(A), to_np(W), to_np(b)))
+    assert_close(sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype), act="gelu"), want, dtype, "gelu(A W^T + b)", scale)
+    want = O.linear(to_np(A), to_np(W), to_np(b)) + to_np(R)
+    assert_close(sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype), residual=dev(R, dtype)), want, dtype, "+residual", scale)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_linear_row_maps(dtype):
+    # A rows gathered through the window map; C rows (and the residual) scattered back
+    B, H, W, C, w, s, N = 2, 14, 14, 64, 7, 3, 96
+    x = draw((B, H, W, C), 14, dtype)
+    Wt = draw((N, C), 15, dtype, C ** -0.5)
+    part = V.window_partition_chain(B, H, W, C, w, s)
+    a_map = sm.Map.create((B, H, W, C), part)
+    got = sm.linear(dev(x, dtype), dev(Wt, dtype), a_map=a_map, M=B * H * W)
+    want = O.linear(V.apply_chain(to_np(x), part).reshape(-1, C), to_np(Wt))
+    assert_close(got, want, dtype, "gathered A", 4.0)
+    # scatter: natural row (window-major) -> position in the [B,H,W,N] tensor
+    R = draw((B, H, W, N), 16, dtype)
+    xw = draw((B * H * W, C), 17, dtype)
+    c_map = sm.Map.create((B, H, W, N), V.window_partition_chain(B, H, W, N, w, s))
+    got = sm.linear(dev(xw, dtype), dev(Wt, dtype), residual=dev(R, dtype), c_map=c_map)
+    y = O.linear(to_np(xw), to_np(Wt)).reshape(-1, w * w, N)
+    want = V.apply_chain(y, V.window_reverse_chain(B, H, W, N, w, s)) + to_np(R)
+    assert_close(got.reshape(want.shape), want, dtype, "scattered C + residual", 4.0)
+
+
+@pytest.mark.parametrize("act", ["swiglu", "geglu"])
+def test_linear_gated(act):
+    dtype = torch.bfloat16
+    M, K, F = 150, 128, 192
+    A = draw((M, K), 18, dtype)
+    W = draw((2 * F, K), 19, dtype, K ** -0.5)
+    b = draw((2 * F,), 20, dtype, 0.5)
+    z = O.linear(to_np(A), to_np(W), to_np(b))
+    want = O.silu(z[:, :F]) * z[:, F:] if act == "swiglu" else z[:, :F] * O.gelu(z[:, F:])
+    assert_close(sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype), act=act), want, dtype, act)
+
+
+def test_linear_rope_epilogue():
+    dtype = torch.bfloat16
+    Bn, S, E, h = 2, 80, 256, 2       # head size 128
+    d = E // h
+    A = draw((Bn * S, 64), 21, dtype)
+    W = draw((3 * E, 64), 22, dtype, 0.125)
+    got = to_np(sm.linear(dev(A, dtype), dev(W, dtype), rope=(2 * E, d, S, 10000.0)))
+    z = O.linear(to_np(A), to_np(W)).reshape(Bn, S, 3, h, d)
+    want = z.copy()
+    for t in range(2):
+        r = O.rope_half_split(np.transpose(z[:, :, t], (0, 2, 1, 3)))       # [B, h, S, d]
+        want[:, :, t] = np.transpose(r, (0, 2, 1, 3))
+    assert_close(got.reshape(want.shape), want, dtype, "rope(q), rope(k), v")
+    # the rotation must matter at this tolerance
+    assert np.linalg.norm(z - want) / np.linalg.norm(want) > 0.3
+
+
+def test_linear_transposed_store():
+    dtype = torch.bfloat16
+    Bn, HW, K, N = 2, 72, 64, 40
+    A = draw((Bn * HW, K), 23, dtype)
+    W = draw((N, K), 24, dtype, 0.125)
+    b = draw((N,), 25, dtype)
+    R = draw((Bn, N, HW), 26, dtype)
+    out = torch.empty((Bn, N, HW), dtype=dtype, device="cuda")
+    sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype), residual=dev(R, dtype), c_transposed_batch=HW, out=out)
+    want = np.transpose(O.linear(to_np(A), to_np(W), to_np(b)).reshape(Bn, HW, N), (0, 2, 1)) + to_np(R)
+    assert_close(out, want, dtype, "NCHW store")
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("s", [0, 3])
+def test_window_attention_in_place_qkv(dtype, s):
+    B, H, W, C, h, w = 2, 14, 21, 96, 3, 7
+    N, d = w * w, C // h
+    B_ = B * (H // w) * (W // w)
+    qkv = draw((B_, N, 3 * C), 27, dtype)               # O(1) logits
+    table = draw(((2 * w - 1) ** 2, h), 28, dtype)      # O(1) bias
+    dq, dt = dev(qkv, dtype), dev(table, dtype)
+    out = torch.empty((B_, N, C), dtype=dtype, device="cuda")
+    st = (N * 3 * C, d, 3 * C)
+    sm.attention(dq, dq[..., C:], dq[..., 2 * C:], kind="window", rpb_table=dt, window=w, shift=s, H=H, W=W,
+                 shape=(B_, h, N, N, d), q_stride=st, k_stride=st, v_stride=st, o_stride=(N * C, d, C), out=out)
+    t = V.apply_chain(to_np(qkv), V.qkv_split_chain(B_, N, h, d))
+    add = swin.rel_pos_bias(to_np(table), w, h)[None]
+    if s:
+        add = add + np.tile(swin.shift_mask(H, W, w, s), (B, 1, 1))[:, None]
+    o, _ = O.attention(t[0], t[1], t[2], d ** -0.5, add=add)
+    want = V.apply_chain(o, V.head_merge_chain(B_, N, h, d))
+    assert_close(out, want, dtype, "window attention")
+    o_nobias, _ = O.attention(t[0], t[1], t[2], d ** -0.5)
+    assert np.abs(V.apply_chain(o_nobias, V.head_merge_chain(B_, N, h, d)) - want).max() > 0.1   # bias and mask matter
+
+
+@pytest.mark.parametrize("kind,nq,nk,d,h", [("full", 100, 77, 40, 2), ("full", 257, 257, 40, 3), ("causal", 200, 200, 128, 2),
+                                           ("causal", 64, 64, 64, 1), ("full", 33, 500, 32, 2)])
+def test_global_attention_strided_heads(kind, nq, nk, d, h):
+    dtype = torch.bfloat16
+    Bn = 2
+    q = draw((Bn, nq, h * d), 29, dtype)
+    k = draw((Bn, nk, h * d), 30, dtype)
+    v = draw((Bn, nk, h * d), 31, dtype)
+    dq, dk, dv = dev(q, dtype), dev(k, dtype), dev(v, dtype)
+    out = torch.empty((Bn, nq, h * d), dtype=dtype, device="cuda")
+    sm.attention(dq, dk, dv, kind=kind, shape=(Bn, h, nq, nk, d), q_stride=(nq * h * d, d, h * d),
+                 k_stride=(nk * h * d, d, h * d), v_stride=(nk * h * d, d, h * d), o_stride=(nq * h * d, d, h * d), out=out)
+    sp = lambda t, n: V.apply_chain(to_np(t), V.head_split_chain(Bn, n, h, d))
+    o, _ = O.attention(sp(q, nq), sp(k, nk), sp(v, nk), d ** -0.5, causal=(kind == "causal"))
+    assert_close(out, V.apply_chain(o, V.head_merge_chain(Bn, nq, h, d)), dtype, kind + " attention")
+
+
+def test_argument_errors():
+    x = torch.zeros(4, 96, device="cuda")
+    with pytest.raises(sm.SmError):
+        sm.norm(x[:, :94].contiguous(), x[0, :94].contiguous())                 # C not a multiple of 4
+    with pytest.raises(sm.SmError):
+        sm.linear(x, torch.zeros(8, 95, device="cuda"), M=4)                  # K not a multiple of 4
+    with pytest.raises(sm.SmError):
+        q = torch.zeros(1, 1, 50, 32, device="cuda")
+        sm.attention(q, q, q, kind="window", rpb_table=x, window=7, H=14, W=14)   # 50 != 49
