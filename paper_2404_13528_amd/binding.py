@@ -300,3 +300,36 @@ def attention(q, k, v, kind="full", scale=None, out=None, rpb_table=None, window
     check(lib().sm_attention(C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rpb_table), _stream(stream)),
           "sm_attention")
     return out
+
+
+# --------------------------------------------------------------------------
+# block and chain executors
+# --------------------------------------------------------------------------
+
+def launch_counts():
+    a, b = C.c_int(), C.c_int()
+    lib().sm_last_launch_counts(C.byref(a), C.byref(b))
+    return a.value, b.value
+
+
+class SwinBlock:
+    """One Swin block; owns its workspace tensor (allocated through torch, once)."""
+
+    def __init__(self, B, H, W, Cc, heads, window, shift, params, dtype, mode=SM_ELIDED, mlp_ratio=4, eps=1e-5):
+        import torch
+        self.cfg = SwinCfg(B, H, W, Cc, heads, window, shift, mlp_ratio,
+                           SM_F32 if dtype == torch.float32 else SM_BF16, eps)
+        self.mode = mode
+        self.params = params           # keeps the device tensors alive
+        self.w = SwinWeights(*[params[n].data_ptr() for n in SWIN_WEIGHT_NAMES])
+        n = lib().sm_swin_block_workspace_bytes(C.byref(self.cfg), mode)
+        if n == 0:
+            raise SmError("sm_swin_block_workspace_bytes: " + lib().sm_last_error().decode())
+        self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def __call__(self, x, out=None, stream=None):
+        import torch
+        y = torch.empty_like(x) if out is None else out
+        check(lib().sm_swin_block(C.byref(self.cfg), C.byref(self.w), _ptr(x), _ptr(y), _ptr(self.ws),
+                                  C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_swin_block")
+        return y

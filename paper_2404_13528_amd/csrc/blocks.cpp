@@ -1,0 +1,211 @@
+// Block and chain executors: sm_swin_block and sm_run_chain.
+//
+// Each executor asks the composer for the maps of the layout transformations
+// in its operator chain and hands them to the kernels (elided mode), or runs
+// one copy kernel per transformation that moves data (explicit mode: Reshape
+// is metadata only on linear memory, paper Sec. 2.3).  Plans are cached per
+// configuration; the cache is guarded by a mutex.
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <tuple>
+#include <vector>
+#include "common.h"
+#include "index_map.h"
+#include "kernels.h"
+#include "plan_chains.h"
+
+using namespace sm;
+
+namespace {
+
+struct Copy {            // one materialised layout transformation
+  MapProg prog; int64_t numel; int vec;
+};
+
+struct SwinPlan {
+  // elided
+  RowProg ln1_store;     // natural token row -> row offset in the window-major tensor
+  RowProg proj_store;    // window-major row -> row offset in the natural tensor
+  // explicit
+  bool has_roll;
+  Copy roll, partition, head_split, head_merge, reverse, unroll;
+  int n_layout_ops, n_eliminated;
+};
+
+struct Key {
+  int v[8];
+  bool operator<(const Key& o) const { return std::memcmp(v, o.v, sizeof(v)) < 0; }
+};
+
+std::mutex g_mu;
+std::map<Key, std::shared_ptr<SwinPlan>> g_swin;
+
+bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, int esize, Copy* out, std::string* err) {
+  sm_map* m = nullptr;
+  if (map_create(src, chain.data(), (int)chain.size(), &m, err) != SM_OK) return false;
+  bool ok = m->compile(&out->prog, err);
+  out->numel = m->numel();
+  out->vec = map_vector_width(*m, esize);
+  delete m;
+  return ok;
+}
+
+bool make_rows(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, RowProg* out, std::string* err) {
+  sm_map* m = nullptr;
+  if (map_create(src, chain.data(), (int)chain.size(), &m, err) != SM_OK) return false;
+  bool ok = m->compile_rows(out, err);
+  delete m;
+  return ok;
+}
+
+std::shared_ptr<SwinPlan> swin_plan(const sm_swin_cfg& c, std::string* err) {
+  Key key{{c.B, c.H, c.W, c.C, c.heads, c.window, c.shift, c.dtype}};
+  std::lock_guard<std::mutex> lock(g_mu);
+  auto it = g_swin.find(key);
+  if (it != g_swin.end()) return it->second;
+  auto p = std::make_shared<SwinPlan>();
+  const int64_t B = c.B, H = c.H, W = c.W, C = c.C, w = c.window, s = c.shift, h = c.heads;
+  const int64_t N = w * w, d = C / h, B_ = B * (H / w) * (W / w);
+  const int es = (int)dtype_size(c.dtype);
+  // elided: LayerNorm's store absorbs {reshape, roll, roll, reshape, permute, reshape}: the map of the
+  // inverse run over the stored (window-major) tensor; proj's store absorbs the reverse run likewise.
+  if (!make_rows({B_, N, C}, chains::window_reverse(B, H, W, C, w, s), &p->ln1_store, err)) return nullptr;
+  if (!make_rows({B, H, W, C}, chains::window_partition(B, H, W, C, w, s), &p->proj_store, err)) return nullptr;
+  // explicit: one copy per transformation that moves data
+  p->has_roll = s != 0;
+  if (s) {
+    if (!make_copy({B, H, W, C}, chains::roll2(-s), es, &p->roll, err)) return nullptr;
+    if (!make_copy({B, H, W, C}, chains::roll2(s), es, &p->unroll, err)) return nullptr;
+  }
+  if (!make_copy({B, H, W, C}, chains::window_partition(B, H, W, C, w, 0), es, &p->partition, err)) return nullptr;
+  if (!make_copy({B_, N, C}, chains::window_reverse(B, H, W, C, w, 0), es, &p->reverse, err)) return nullptr;
+  if (!make_copy({B_, N, 3 * C}, chains::qkv_split(B_, N, h, d), es, &p->head_split, err)) return nullptr;
+  if (!make_copy({B_, h, N, d}, chains::head_merge(B_, N, h, d), es, &p->head_merge, err)) return nullptr;
+  g_swin[key] = p;
+  return p;
+}
+
+int check_swin(const sm_swin_cfg* c, const char* who) {
+  if (!c) return fail(SM_ERR_INVALID_ARG, "%s: null configuration", who);
+  if (!dtype_ok(c->dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
+  if (c->B < 1 || c->H < 1 || c->W < 1 || c->C < 1 || c->heads < 1 || c->window < 1 || c->mlp_ratio < 1)
+    return fail(SM_ERR_SHAPE, "%s: non-positive dimension", who);
+  if (c->H % c->window || c->W % c->window)
+    return fail(SM_ERR_SHAPE, "%s: grid %d x %d is not a multiple of the window %d", who, c->H, c->W, c->window);
+  if (c->C % c->heads) return fail(SM_ERR_SHAPE, "%s: C = %d is not a multiple of heads = %d", who, c->C, c->heads);
+  if (c->shift < 0 || c->shift >= c->window) return fail(SM_ERR_SHAPE, "%s: shift out of range", who);
+  const int vec = c->dtype == SM_F32 ? 4 : 8;
+  if ((c->C / c->heads) % vec) return fail(SM_ERR_SHAPE, "%s: head size must be a multiple of %d", who, vec);
+  return SM_OK;
+}
+
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+int copy_launch(const Copy& cp, const void* src, void* dst, int dtype, void* stream, const void* addend = nullptr) {
+  int rc = addend ? launch_gather_add(cp.prog, cp.numel, cp.vec, src, addend, dst, dtype, stream)
+                  : launch_gather(cp.prog, cp.numel, cp.vec, src, dst, (int)dtype_size(dtype), stream);
+  if (rc) return fail(SM_ERR_DEVICE, "copy kernel launch failed (hip error %d)", rc);
+  count_copy();
+  return SM_OK;
+}
+
+int run_norm(const void* x, const void* g, const void* b, void* y, int64_t rows, int C, float eps, int rms, int dtype,
+             const RowProg* load, int nseg, const RowProg* store, void* stream) {
+  NormArgs a; std::memset(&a, 0, sizeof(a));
+  a.x = x; a.gamma = g; a.beta = b; a.y = y; a.rows = rows; a.C = C; a.eps = eps; a.rms = rms; a.dtype = dtype; a.nseg = nseg;
+  a.load = load ? *load : identity_rows(C);
+  a.store = store ? *store : identity_rows(C);
+  return norm_checked(a, stream, "norm");
+}
+
+int run_gemm(const void* A, const void* W, const void* bias, const void* res, void* C, int64_t M, int N, int K, int dtype,
+             int act, const RowProg* a_rows, const RowProg* c_rows, void* stream) {
+  GemmArgs g; std::memset(&g, 0, sizeof(g));
+  g.A = A; g.W = W; g.bias = bias; g.residual = res; g.C = C; g.M = M; g.N = N; g.K = K; g.dtype = dtype; g.act = act; g.ldw = K;
+  const int n_out = (act == SM_ACT_SWIGLU || act == SM_ACT_GEGLU) ? N / 2 : N;
+  g.a_rows = a_rows ? *a_rows : identity_rows(K);
+  g.c_rows = c_rows ? *c_rows : identity_rows(n_out);
+  return gemm_checked(g, stream, "linear");
+}
+
+}  // namespace
+
+extern "C" size_t sm_swin_block_workspace_bytes(const sm_swin_cfg* c, int mode) {
+  if (check_swin(c, "sm_swin_block_workspace_bytes") != SM_OK) return 0;
+  const size_t tc = align256((size_t)c->B * c->H * c->W * c->C * dtype_size(c->dtype));
+  const size_t units = mode == SM_EXPLICIT ? 4 + 3 + 3 + 1 + c->mlp_ratio : 1 + 3 + 1 + 1 + c->mlp_ratio;
+  return tc * units;
+}
+
+extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y,
+                             void* ws, size_t ws_bytes, int mode, void* stream) {
+  int rc = check_swin(c, "sm_swin_block");
+  if (rc) return rc;
+  if (!wt || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: null pointer");
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: unknown mode %d", mode);
+  if (ws_bytes < sm_swin_block_workspace_bytes(c, mode))
+    return fail(SM_ERR_WORKSPACE, "sm_swin_block: workspace of %zu bytes, %zu needed", ws_bytes, sm_swin_block_workspace_bytes(c, mode));
+  if (!aligned16(x) || !aligned16(y) || !aligned16(ws)) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: pointers must be 16-byte aligned");
+  std::string err;
+  auto plan = swin_plan(*c, &err);
+  if (!plan) return fail(SM_ERR_UNSUPPORTED, "sm_swin_block: %s", err.c_str());
+  count_reset();
+  const int64_t T = (int64_t)c->B * c->H * c->W;
+  const int C = c->C, h = c->heads, w = c->window, N = w * w, d = C / h, dt = c->dtype;
+  const int64_t B_ = T / N;
+  const size_t tc = align256((size_t)T * C * dtype_size(dt));
+  char* base = (char*)ws;
+  const float eps = c->eps;
+
+  sm_attention_desc ad; std::memset(&ad, 0, sizeof(ad));
+  ad.kind = SM_ATT_WINDOW; ad.dtype = dt; ad.nb = (int)B_; ad.heads = h; ad.nq = N; ad.nk = N; ad.d = d;
+  ad.scale = 1.0f / sqrtf((float)d);
+  ad.window = w; ad.shift = c->shift; ad.H = c->H; ad.W = c->W;
+
+  if (mode == SM_ELIDED) {
+    void* bufA = base; void* qkv = base + tc; void* bufO = base + 4 * tc; void* x1 = base + 5 * tc; void* hid = base + 6 * tc;
+    if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, bufA, T, C, eps, 0, dt, nullptr, 1, &plan->ln1_store, stream))) return rc;
+    if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    const size_t es = dtype_size(dt);
+    for (int i = 0; i < 3; ++i) {
+      const int64_t st[3] = {(int64_t)N * 3 * C, d, 3 * C};
+      ad.q_stride[i] = ad.k_stride[i] = ad.v_stride[i] = st[i];
+    }
+    ad.o_stride[0] = (int64_t)N * C; ad.o_stride[1] = d; ad.o_stride[2] = C;
+    if ((rc = attention_checked(ad, qkv, (char*)qkv + (size_t)C * es, (char*)qkv + (size_t)2 * C * es, bufO, wt->rpb_table, stream, "window attention"))) return rc;
+    if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
+    if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, bufA, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+    if ((rc = run_gemm(bufA, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;
+    if ((rc = run_gemm(hid, wt->w2, wt->b2, x1, y, T, C, c->mlp_ratio * C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    return SM_OK;
+  }
+
+  void* s0 = base; void* s1 = base + tc; void* s2 = base + 2 * tc; void* s3 = base + 3 * tc;
+  void* qkv = base + 4 * tc; void* qkvp = base + 7 * tc; void* x1 = base + 10 * tc; void* hid = base + 11 * tc;
+  if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+  void* cur = s0;
+  if (plan->has_roll) { if ((rc = copy_launch(plan->roll, s0, s1, dt, stream))) return rc; cur = s1; }
+  if ((rc = copy_launch(plan->partition, cur, s2, dt, stream))) return rc;
+  if ((rc = run_gemm(s2, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+  if ((rc = copy_launch(plan->head_split, qkv, qkvp, dt, stream))) return rc;          // [3, B_, h, N, d]
+  ad.q_stride[0] = ad.k_stride[0] = ad.v_stride[0] = ad.o_stride[0] = (int64_t)h * N * d;
+  ad.q_stride[1] = ad.k_stride[1] = ad.v_stride[1] = ad.o_stride[1] = (int64_t)N * d;
+  ad.q_stride[2] = ad.k_stride[2] = ad.v_stride[2] = ad.o_stride[2] = d;
+  const size_t part = (size_t)T * C * dtype_size(dt);
+  if ((rc = attention_checked(ad, qkvp, (char*)qkvp + part, (char*)qkvp + 2 * part, s0, wt->rpb_table, stream, "window attention"))) return rc;
+  if ((rc = copy_launch(plan->head_merge, s0, s1, dt, stream))) return rc;             // [B_, N, C]
+  if ((rc = run_gemm(s1, wt->wproj, wt->bproj, nullptr, s2, T, C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+  if (plan->has_roll) {
+    if ((rc = copy_launch(plan->reverse, s2, s3, dt, stream))) return rc;
+    if ((rc = copy_launch(plan->unroll, s3, x1, dt, stream, x))) return rc;            // + residual
+  } else {
+    if ((rc = copy_launch(plan->reverse, s2, x1, dt, stream, x))) return rc;
+  }
+  if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+  if ((rc = run_gemm(s0, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;
+  if ((rc = run_gemm(hid, wt->w2, wt->b2, x1, y, T, C, c->mlp_ratio * C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+  return SM_OK;
+}

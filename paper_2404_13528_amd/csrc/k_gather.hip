@@ -32,6 +32,47 @@ __global__ __launch_bounds__(256) void gather_kernel(MapProg p, int64_t nvec, in
   dst[o] = src[off / vec];
 }
 
+// dst[o] = src[map(o)] + addend[o]: the last copy of an explicit chain fused with the residual Add that follows it.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void gather_add_kernel(MapProg p, int64_t nvec, const T* __restrict__ src, const T* __restrict__ addend, T* __restrict__ dst) {
+  int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= nvec) return;
+  int vars[SM_MAX_RANK];
+  int64_t rem = o;
+  for (int k = p.rank - 1; k >= 0; --k) {
+    int ext = p.shape[k];
+    if (k == p.rank - 1) ext /= VEC;
+    vars[k] = (int)(rem % ext);
+    rem /= ext;
+  }
+  vars[p.rank - 1] *= VEC;
+  int val[PROG_MAX_ATOMS];
+  eval_atoms<SM_MAX_RANK>(p.atoms, p.n_atoms, vars, val);
+  int64_t off = p.c0;
+  for (int t = 0; t < p.nterm; ++t) {
+    int id = p.t_atom[t];
+    off += p.t_coef[t] * (int64_t)(id < 0 ? vars[~id] : val[id]);
+  }
+  struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
+  const Pack a = *(const Pack*)(src + off), b = *(const Pack*)(addend + o * VEC);
+  Pack r;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) Elem<T>::st(&r.v[e], Elem<T>::ld(&a.v[e]) + Elem<T>::ld(&b.v[e]));
+  *(Pack*)(dst + o * VEC) = r;
+}
+
+int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const void* src, const void* addend, void* dst, int dtype, void* stream) {
+  if (numel == 0) return 0;
+  const int64_t nvec = numel / vec_elems;
+  dim3 grid((unsigned)((nvec + 255) / 256)), block(256);
+  hipStream_t s = (hipStream_t)stream;
+#define GA(T, V) gather_add_kernel<T, V><<<grid, block, 0, s>>>(prog, nvec, (const T*)src, (const T*)addend, (T*)dst)
+  if (dtype == SM_F32) { if (vec_elems == 4) GA(float, 4); else if (vec_elems == 2) GA(float, 2); else GA(float, 1); }
+  else { if (vec_elems == 8) GA(bf16_t, 8); else if (vec_elems == 4) GA(bf16_t, 4); else if (vec_elems == 2) GA(bf16_t, 2); else GA(bf16_t, 1); }
+#undef GA
+  return (int)hipGetLastError();
+}
+
 int launch_gather(const MapProg& prog, int64_t numel, int vec_elems, const void* src, void* dst, int esize, void* stream) {
   if (numel == 0) return 0;
   int64_t nvec = numel / vec_elems;

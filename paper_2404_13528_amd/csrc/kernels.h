@@ -10,6 +10,8 @@ namespace sm {
 
 int launch_gather(const MapProg& prog, int64_t numel, int vec_elems, const void* src, void* dst, int esize, void* stream);
 
+int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const void* src, const void* addend, void* dst, int dtype, void* stream);
+
 struct NormArgs {
   const void* x; const void* gamma; const void* beta; void* y;
   int64_t rows; int C; float eps; int rms; int dtype;
