@@ -333,3 +333,50 @@ class SwinBlock:
         check(lib().sm_swin_block(C.byref(self.cfg), C.byref(self.w), _ptr(x), _ptr(y), _ptr(self.ws),
                                   C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_swin_block")
         return y
+
+
+class SwinChain:
+    """sm_run_chain: optional patch embedding, stages of Swin blocks with patch merging between them,
+    optional head.  `net` follows workloads.swin_net_case ({"embed", "stages", "merges", "head"}), with
+    device tensors; for a bare stage pass {"stages": [[block params...]]}."""
+
+    def __init__(self, B, stages, window, net, dtype, mode=SM_ELIDED, img=0, patch=4, in_ch=3, n_cls=0,
+                 mlp_ratio=4, eps=1e-5):
+        import torch
+        d = ChainDesc()
+        d.B, d.dtype, d.window, d.mlp_ratio, d.eps = B, (SM_F32 if dtype == torch.float32 else SM_BF16), window, mlp_ratio, eps
+        d.has_embed = 1 if "embed" in net else 0
+        d.in_ch, d.img, d.patch = in_ch, img, patch
+        d.n_stages = len(stages)
+        for i, (Cc, heads, depth, H, W) in enumerate(stages):
+            d.stages[i] = StageDesc(Cc, heads, depth, H, W)
+        d.has_head = 1 if "head" in net else 0
+        d.n_cls = n_cls
+        self.desc, self.mode, self.net, self.dtype = d, mode, net, dtype
+        ptrs = []
+        if d.has_embed:
+            ptrs += [net["embed"][k] for k in ("w", "b", "ln_g", "ln_b")]
+        for si, blocks in enumerate(net["stages"]):
+            for p in blocks:
+                ptrs += [p[k] for k in SWIN_WEIGHT_NAMES]
+            if si + 1 < len(net["stages"]):
+                ptrs += [net["merges"][si][k] for k in ("ln_g", "ln_b", "w")]
+        if d.has_head:
+            ptrs += [net["head"][k] for k in ("ln_g", "ln_b", "w", "b")]
+        self._keep = ptrs
+        self.wptr = (C.c_void_p * len(ptrs))(*[t.data_ptr() for t in ptrs])
+        n = lib().sm_run_chain_workspace_bytes(C.byref(d), mode)
+        if n == 0:
+            raise SmError("sm_run_chain_workspace_bytes: " + lib().sm_last_error().decode())
+        self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        Cl, _, _, Hl, Wl = stages[-1]
+        self.out_shape = (B, n_cls) if d.has_head else (B, Hl * Wl, Cl)
+        self.feat_shape = (B, Hl * Wl, Cl)
+
+    def __call__(self, x, out=None, want_feat=False, stream=None):
+        import torch
+        y = torch.empty(self.out_shape, dtype=self.dtype, device="cuda") if out is None else out
+        feat = torch.empty(self.feat_shape, dtype=self.dtype, device="cuda") if (want_feat and self.desc.has_head) else None
+        check(lib().sm_run_chain(C.byref(self.desc), self.wptr, len(self._keep), _ptr(x), _ptr(y), _ptr(feat),
+                                 _ptr(self.ws), C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_run_chain")
+        return (y, feat) if want_feat else y

@@ -121,6 +121,13 @@ extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, 
   g.c_transposed = d->c_transposed; g.c_batch_rows = d->c_batch_rows; g.ldw = d->K;
   const int n_out = (d->act == SM_ACT_SWIGLU || d->act == SM_ACT_GEGLU) ? d->N / 2 : d->N;
   int rc = rows_of(a_map, d->M, d->K, d->K, &g.a_rows, "sm_linear(A)");
+  if (rc == SM_ERR_UNSUPPORTED && a_map && d->K % 4 == 0) {
+    // K contiguous only in granules of 4 (an unfold): separable row + column programs
+    std::string err;
+    if (!a_map->compile_rows_cols(4, &g.a_rows, &g.a_cols, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_linear(A): %s", err.c_str());
+    g.a_gran = 4;
+    rc = SM_OK;
+  }
   if (rc) return rc;
   if (d->c_transposed && c_map) return fail(SM_ERR_UNSUPPORTED, "sm_linear: transposed store with a row map");
   rc = rows_of(c_map, d->M, n_out, n_out, &g.c_rows, "sm_linear(C)");

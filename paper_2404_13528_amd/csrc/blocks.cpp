@@ -5,6 +5,7 @@
 // one copy kernel per transformation that moves data (explicit mode: Reshape
 // is metadata only on linear memory, paper Sec. 2.3).  Plans are cached per
 // configuration; the cache is guarded by a mutex.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <map>
@@ -207,5 +208,205 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
   if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
   if ((rc = run_gemm(s0, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;
   if ((rc = run_gemm(hid, wt->w2, wt->b2, x1, y, T, C, c->mlp_ratio * C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+  return SM_OK;
+}
+
+// ---------------------------------------------------------------------------
+// sm_run_chain
+// ---------------------------------------------------------------------------
+namespace {
+
+struct MergePlan { RowProg ln_load; Copy gather; };
+struct EmbedPlan { RowProg a_rows, a_cols; Copy unfold; };
+std::map<Key, std::shared_ptr<MergePlan>> g_merge;
+std::map<Key, std::shared_ptr<EmbedPlan>> g_embed;
+
+std::shared_ptr<MergePlan> merge_plan(int B, int H, int W, int C, int dtype, std::string* err) {
+  Key key{{B, H, W, C, dtype, 0, 0, 1}};
+  std::lock_guard<std::mutex> lock(g_mu);
+  auto it = g_merge.find(key);
+  if (it != g_merge.end()) return it->second;
+  auto p = std::make_shared<MergePlan>();
+  // LayerNorm's load absorbs the 2x2 gather: a logical row of 4C is four segments of C
+  std::vector<sm_view_op> ch = chains::patch_merge(B, H, W, C);
+  ch.push_back(chains::reshape({(int64_t)B * (H / 2) * (W / 2) * 4, C}));
+  if (!make_rows({B, H, W, C}, ch, &p->ln_load, err)) return nullptr;
+  if (!make_copy({B, H, W, C}, chains::patch_merge(B, H, W, C), (int)dtype_size(dtype), &p->gather, err)) return nullptr;
+  g_merge[key] = p;
+  return p;
+}
+
+std::shared_ptr<EmbedPlan> embed_plan(int B, int Cin, int img, int patch, int dtype, std::string* err) {
+  Key key{{B, Cin, img, patch, dtype, 0, 0, 2}};
+  std::lock_guard<std::mutex> lock(g_mu);
+  auto it = g_embed.find(key);
+  if (it != g_embed.end()) return it->second;
+  auto p = std::make_shared<EmbedPlan>();
+  sm_map* m = nullptr;
+  std::vector<sm_view_op> ch = chains::patch_embed(B, Cin, img, img, patch);
+  if (map_create({B, Cin, img, img}, ch.data(), (int)ch.size(), &m, err) != SM_OK) return nullptr;
+  bool ok = m->compile_rows_cols(4, &p->a_rows, &p->a_cols, err);
+  ok = ok && m->compile(&p->unfold.prog, err);
+  p->unfold.numel = m->numel();
+  p->unfold.vec = map_vector_width(*m, (int)dtype_size(dtype));
+  delete m;
+  if (!ok) return nullptr;
+  g_embed[key] = p;
+  return p;
+}
+
+int check_chain(const sm_chain_desc* c, const char* who) {
+  if (!c) return fail(SM_ERR_INVALID_ARG, "%s: null descriptor", who);
+  if (!dtype_ok(c->dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
+  if (c->B < 1 || c->n_stages < 1 || c->n_stages > 4 || c->window < 1 || c->mlp_ratio < 1) return fail(SM_ERR_SHAPE, "%s: bad descriptor", who);
+  for (int s = 0; s < c->n_stages; ++s) {
+    const sm_stage_desc& st = c->stages[s];
+    sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, 0, c->mlp_ratio, c->dtype, c->eps};
+    int rc = check_swin(&bc, who);
+    if (rc) return rc;
+    if (st.depth < 1) return fail(SM_ERR_SHAPE, "%s: stage %d has no blocks", who, s);
+    if (s > 0) {
+      const sm_stage_desc& pr = c->stages[s - 1];
+      if (pr.H % 2 || pr.W % 2 || st.H != pr.H / 2 || st.W != pr.W / 2 || st.C != 2 * pr.C)
+        return fail(SM_ERR_SHAPE, "%s: stage %d does not follow a 2x2 patch merge of stage %d", who, s, s - 1);
+    }
+  }
+  if (c->has_embed) {
+    if (c->patch != 4) return fail(SM_ERR_UNSUPPORTED, "%s: patch size must be 4", who);
+    if (c->img % c->patch || c->img / c->patch != c->stages[0].H || c->stages[0].H != c->stages[0].W)
+      return fail(SM_ERR_SHAPE, "%s: image / patch does not match stage 0", who);
+    if (c->in_ch < 1) return fail(SM_ERR_SHAPE, "%s: in_ch", who);
+  }
+  if (c->has_head && c->n_cls < 1) return fail(SM_ERR_SHAPE, "%s: n_cls", who);
+  return SM_OK;
+}
+
+int chain_weight_count(const sm_chain_desc* c) {
+  int n = c->has_embed ? 4 : 0;
+  for (int s = 0; s < c->n_stages; ++s) n += 13 * c->stages[s].depth + (s + 1 < c->n_stages ? 3 : 0);
+  return n + (c->has_head ? 4 : 0);
+}
+
+struct ChainSizes { size_t act, block, total; };
+ChainSizes chain_sizes(const sm_chain_desc* c, int mode) {
+  ChainSizes z{0, 0, 0};
+  for (int s = 0; s < c->n_stages; ++s) {
+    const sm_stage_desc& st = c->stages[s];
+    sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, 0, c->mlp_ratio, c->dtype, c->eps};
+    z.block = std::max(z.block, sm_swin_block_workspace_bytes(&bc, mode));
+    z.act = std::max(z.act, align256((size_t)c->B * st.H * st.W * st.C * dtype_size(c->dtype)));
+  }
+  z.total = z.block + 2 * z.act;
+  return z;
+}
+
+}  // namespace
+
+extern "C" size_t sm_run_chain_workspace_bytes(const sm_chain_desc* c, int mode) {
+  if (check_chain(c, "sm_run_chain_workspace_bytes") != SM_OK) return 0;
+  return chain_sizes(c, mode).total;
+}
+
+extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, int n_weights, const void* x,
+                            void* y, void* y_feat, void* ws, size_t ws_bytes, int mode, void* stream) {
+  int rc = check_chain(c, "sm_run_chain");
+  if (rc) return rc;
+  if (!weights || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: null pointer");
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: unknown mode %d", mode);
+  if (n_weights != chain_weight_count(c)) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: %d weight pointers given, %d expected", n_weights, chain_weight_count(c));
+  for (int i = 0; i < n_weights; ++i) if (!weights[i] || !aligned16(weights[i])) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: weight %d is null or misaligned", i);
+  const ChainSizes z = chain_sizes(c, mode);
+  if (ws_bytes < z.total) return fail(SM_ERR_WORKSPACE, "sm_run_chain: workspace of %zu bytes, %zu needed", ws_bytes, z.total);
+  if (!aligned16(x) || !aligned16(y) || !aligned16(ws) || (y_feat && !aligned16(y_feat))) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: pointers must be 16-byte aligned");
+  // build every plan before the first launch so that an unsupported shape enqueues nothing
+  std::string err;
+  const int dt = c->dtype;
+  std::shared_ptr<EmbedPlan> ep;
+  std::vector<std::shared_ptr<MergePlan>> mp;
+  if (c->has_embed && !(ep = embed_plan(c->B, c->in_ch, c->img, c->patch, dt, &err))) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
+  for (int s = 0; s < c->n_stages; ++s) {
+    const sm_stage_desc& st = c->stages[s];
+    for (int sh = 0; sh < 2; ++sh) {
+      sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, sh ? c->window / 2 : 0, c->mlp_ratio, dt, c->eps};
+      if (!swin_plan(bc, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
+    }
+    if (s + 1 < c->n_stages) {
+      mp.push_back(merge_plan(c->B, st.H, st.W, st.C, dt, &err));
+      if (!mp.back()) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
+    }
+  }
+  char* base = (char*)ws;
+  void* blk_ws = base;
+  void* act[2] = {base + z.block, base + z.block + z.act};
+  int n_compute = 0, n_copy = 0;
+  auto tally = [&]() { int a, b; counts(&a, &b); n_compute += a; n_copy += b; count_reset(); };
+  count_reset();
+  const void* const* wp = weights;
+  const void* cur = x;
+  int flip = 0;
+  if (c->has_embed) {
+    const sm_stage_desc& st = c->stages[0];
+    const int64_t T = (int64_t)c->B * st.H * st.W;
+    const int K = c->in_ch * c->patch * c->patch;
+    void* tmp = blk_ws;
+    if (mode == SM_ELIDED) {
+      GemmArgs g; std::memset(&g, 0, sizeof(g));
+      g.A = x; g.W = wp[0]; g.bias = wp[1]; g.C = tmp; g.M = T; g.N = st.C; g.K = K; g.dtype = dt; g.ldw = K;
+      g.a_rows = ep->a_rows; g.a_cols = ep->a_cols; g.a_gran = 4; g.c_rows = identity_rows(st.C);
+      if ((rc = gemm_checked(g, stream, "patch embedding"))) return rc;
+    } else {
+      void* unf = (char*)blk_ws + align256((size_t)T * st.C * dtype_size(dt));
+      if ((rc = copy_launch(ep->unfold, x, unf, dt, stream))) return rc;
+      if ((rc = run_gemm(unf, wp[0], wp[1], nullptr, tmp, T, st.C, K, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    }
+    if ((rc = run_norm(tmp, wp[2], wp[3], act[flip], T, st.C, c->eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+    cur = act[flip]; flip ^= 1;
+    wp += 4;
+    tally();
+  }
+  for (int s = 0; s < c->n_stages; ++s) {
+    const sm_stage_desc& st = c->stages[s];
+    const bool last_stage = s + 1 == c->n_stages;
+    for (int k = 0; k < st.depth; ++k) {
+      const int shift = (k % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0;
+      sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, shift, c->mlp_ratio, dt, c->eps};
+      sm_swin_weights bw;
+      std::memcpy(&bw, wp, sizeof(bw));
+      wp += 13;
+      const bool final_out = last_stage && k + 1 == st.depth && !c->has_head;
+      void* out = final_out ? y : act[flip];
+      if ((rc = sm_swin_block(&bc, &bw, cur, out, blk_ws, z.block, mode, stream))) return rc;
+      tally();
+      cur = out; flip ^= 1;
+    }
+    if (!last_stage) {
+      const int64_t T4 = (int64_t)c->B * (st.H / 2) * (st.W / 2);
+      void* normed = blk_ws;
+      if (mode == SM_ELIDED) {
+        if ((rc = run_norm(cur, wp[0], wp[1], normed, T4, 4 * st.C, c->eps, 0, dt, &mp[s]->ln_load, 4, nullptr, stream))) return rc;
+      } else {
+        void* gathered = (char*)blk_ws + align256((size_t)T4 * 4 * st.C * dtype_size(dt));
+        if ((rc = copy_launch(mp[s]->gather, cur, gathered, dt, stream))) return rc;
+        if ((rc = run_norm(gathered, wp[0], wp[1], normed, T4, 4 * st.C, c->eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+      }
+      if ((rc = run_gemm(normed, wp[2], nullptr, nullptr, act[flip], T4, 2 * st.C, 4 * st.C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+      cur = act[flip]; flip ^= 1;
+      wp += 3;
+      tally();
+    }
+  }
+  if (c->has_head) {
+    const sm_stage_desc& st = c->stages[c->n_stages - 1];
+    const int L = st.H * st.W;
+    void* feat = y_feat ? y_feat : act[flip];
+    if ((rc = run_norm(cur, wp[0], wp[1], feat, (int64_t)c->B * L, st.C, c->eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+    void* pooled = blk_ws;
+    int lrc = launch_mean_tokens(feat, pooled, c->B, L, st.C, dt, stream);
+    if (lrc) return fail(SM_ERR_DEVICE, "sm_run_chain: mean launch failed (hip error %d)", lrc);
+    count_compute();
+    if ((rc = run_gemm(pooled, wp[2], wp[3], nullptr, y, c->B, c->n_cls, st.C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    tally();
+  }
+  count_reset(); count_compute(n_compute); count_copy(n_copy);
   return SM_OK;
 }

@@ -322,10 +322,21 @@ RowProg identity_rows(int64_t ld) {
 template <class P>
 static bool emit(const std::vector<Atom>& atoms, const Affine& offset, P* out, std::string* err) {
   // atoms are stored with arguments referring to earlier ids (intern order after prune)
-  std::vector<int> slot(atoms.size(), 0);
+  std::vector<int> slot(atoms.size(), 0), used(atoms.size(), 0);
+  {
+    std::vector<int> stack;
+    for (auto& t : offset.terms) stack.push_back(t.first);
+    while (!stack.empty()) {
+      int id = stack.back(); stack.pop_back();
+      if (used[id]) continue;
+      used[id] = 1;
+      for (auto& t : atoms[id].arg.terms) stack.push_back(t.first);
+    }
+  }
   int n = 0;
   for (size_t i = 0; i < atoms.size(); ++i) {
     const Atom& a = atoms[i];
+    if (!used[i]) continue;
     if (a.kind == ATOM_VAR) { slot[i] = ~a.var; continue; }
     if (n >= PROG_MAX_ATOMS) { *err = "index map too complex for a device program (atoms)"; return false; }
     if ((int)a.arg.terms.size() > PROG_MAX_TERMS) { *err = "index map too complex for a device program (terms)"; return false; }
@@ -391,6 +402,41 @@ bool sm_map::compile_rows(RowProg* out, std::string* err) const {
   if (out->n_atoms == 0 && out->c0 == 0 && out->nterm == 1 && out->t_atom[0] == ~0) {
     out->identity = 1; out->ld = out->t_coef[0];
   }
+  return true;
+}
+
+bool sm_map::compile_rows_cols(int gran, RowProg* rows, RowProg* cols, std::string* err) const {
+  std::memset(rows, 0, sizeof(*rows)); std::memset(cols, 0, sizeof(*cols));
+  const int64_t K = shape.back();
+  if (K % gran) { *err = "last dimension is not a multiple of the granule"; return false; }
+  sm_map tmp = *this;
+  sm_view_op rs; rs.kind = SM_VIEW_RESHAPE; rs.n = 3; rs.arg[0] = numel() / K; rs.arg[1] = K / gran; rs.arg[2] = gran;
+  int made = 0;
+  if (!apply_view(tmp.shape, tmp.atoms, tmp.offset, rs, true, &made, err)) return false;
+  prune(&tmp);
+  // which view variables does each atom depend on (bit mask)
+  std::vector<int> dep(tmp.atoms.size(), 0);
+  for (size_t i = 0; i < tmp.atoms.size(); ++i) {
+    const Atom& a = tmp.atoms[i];
+    if (a.kind == ATOM_VAR) dep[i] = 1 << a.var;
+    else for (auto& t : a.arg.terms) dep[i] |= dep[t.first];
+  }
+  Affine r_part, c_part;
+  r_part.c0 = tmp.offset.c0;
+  bool unit = gran == 1;
+  for (auto& t : tmp.offset.terms) {
+    const int d = dep[t.first];
+    if (d == 1) r_part.terms.push_back(t);
+    else if (d == 2) c_part.terms.push_back(t);
+    else if (d == 4 && tmp.atoms[t.first].kind == ATOM_VAR && t.second == 1) unit = true;
+    else { *err = "operand offset is not separable into row and column parts"; return false; }
+  }
+  if (!unit) { *err = "operand's innermost granule is not contiguous"; return false; }
+  // column program: variable 1 becomes variable 0
+  std::vector<Atom> catoms = tmp.atoms;
+  for (auto& a : catoms) if (a.kind == ATOM_VAR && a.var == 1) a.var = 0; else if (a.kind == ATOM_VAR && a.var == 0) a.var = 1;
+  if (!emit(tmp.atoms, r_part, rows, err)) return false;
+  if (!emit(catoms, c_part, cols, err)) return false;
   return true;
 }
 

@@ -71,6 +71,8 @@ struct sm_map {
   bool compile(sm::MapProg* out, std::string* err) const;
   // view collapsed to [rows, inner]: inner = last axis, must be contiguous
   bool compile_rows(sm::RowProg* out, std::string* err) const;
+  // view collapsed to [rows, K / gran, gran] with offset = rows_part(r) + cols_part(k / gran) + k % gran
+  bool compile_rows_cols(int gran, sm::RowProg* rows, sm::RowProg* cols, std::string* err) const;
   void eval(int64_t* offsets) const;
   bool affine(int64_t* base, int64_t* strides) const;
 };

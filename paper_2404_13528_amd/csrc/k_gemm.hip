@@ -93,8 +93,26 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   const uint4 zero = make_uint4(0, 0, 0, 0);
   auto load_tile = [&](int k0) {
     const bool k_ok = k0 + lc * VEC < g.K;
+    if (g.a_gran > 0) {
+      // K contiguous only in granules of 4 elements (an unfold folded into the load): the chunk is one
+      // (fp32) or two (bf16) granules, each addressed through the column program
+      const int kq = (k0 + lc * VEC) / 4;
+      const int64_t c0 = k_ok ? eval_rows(g.a_cols, kq) : 0;
+      const int64_t c1 = (k_ok && VEC == 8) ? eval_rows(g.a_cols, kq + 1) : 0;
 #pragma unroll
-    for (int i = 0; i < 2 * MI; ++i) ra[i] = (a_ok[i] && k_ok) ? *(const uint4*)(a_ptr[i] + k0) : zero;
+      for (int i = 0; i < 2 * MI; ++i) {
+        if (!(a_ok[i] && k_ok)) { ra[i] = zero; continue; }
+        const T* base = a_ptr[i] - lc * VEC;
+        if constexpr (VEC == 4) ra[i] = *(const uint4*)(base + c0);
+        else {
+          const uint2 lo = *(const uint2*)(base + c0), hi = *(const uint2*)(base + c1);
+          ra[i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2 * MI; ++i) ra[i] = (a_ok[i] && k_ok) ? *(const uint4*)(a_ptr[i] + k0) : zero;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) rb[i] = (b_ok[i] && k_ok) ? *(const uint4*)(b_ptr[i] + k0) : zero;
   };
