@@ -1,0 +1,164 @@
+"""Benchmark of the layout-elided hot path on one MI355X.
+
+Workload (benchmark configs[1]): Swin stage-3 chain, bf16, B=32, 14x14
+tokens, C=384, 12 heads, window 7, 6 blocks alternating shift 0/3, MLP ratio 4;
+seeded synthetic inputs resident in HBM before the timed region.  One step =
+one pass of the whole chain (42 kernels in elided mode) over one batch.
+
+Prints ONE JSON line: whole-job throughput (images/s) of the elided chain, the
+explicit-transpose baseline chain timed the same way, per-kernel durations
+measured with HIP events on the launch stream, the roofline of the dominant
+kernel, and the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM = 8.0e12          # B/s, MI355X published
+PEAK_BF16 = 2.5e15         # FLOP/s dense bf16 MFMA, MI355X published
+
+# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (bytes, scaled by the
+# copy-kernel calibration described in the design doc); filled from profiles/, None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def kernel_model(label, e=2):
+    """Algorithmic bytes and flops of one launch, from the kernel label (tensor reads + writes at
+    kernel-per-op granularity with fused epilogues; weights and bias included)."""
+    m = re.match(r"gemm_\w+\[(\d+),(\d+),(\d+)\](.*)", label)
+    if m:
+        M, N, K = int(m.group(1)), int(m.group(2)), int(m.group(3))
+        n_out = N // 2 if "+glu" in m.group(4) else N
+        by = (M * K + N * K + N + M * n_out + (M * n_out if "+res" in m.group(4) else 0)) * e
+        return by, 2.0 * M * N * K
+    m = re.match(r"(layernorm|rmsnorm)_\w+\[(\d+),(\d+)\]", label)
+    if m:
+        R, C = int(m.group(2)), int(m.group(3))
+        return (2 * R * C + 2 * C) * e, 8.0 * R * C
+    m = re.match(r"attention_(\w+)_\w+\[(\d+),(\d+),(\d+),(\d+),(\d+)\]", label)
+    if m:
+        nb, h, nq, nk, d = [int(m.group(i)) for i in range(2, 7)]
+        fl = 4.0 * nb * h * nq * nk * d * (0.5 if m.group(1) == "causal" else 1.0)
+        return nb * h * (2 * nq + 2 * nk) * d * e, fl
+    m = re.match(r"copy_\w+\[(\d+)\](.*)", label)
+    if m:
+        n = int(m.group(1))
+        return (3 if "+add" in m.group(2) else 2) * n * e, 0.0
+    return 0, 0.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2404_13528_amd import binding as sm, workloads as Wl
+
+    B, H, W, C, h, w, depth = 32, 14, 14, 384, 12, 7, 6
+    dtype = torch.bfloat16
+    x, blocks = Wl.swin_stage_case(B, H, W, C, h, w, depth)
+    dev_blocks = [{k: v.to(dtype).cuda() for k, v in p.items()} for p in blocks]
+    xd = x.to(dtype).cuda()
+    chains = {name: sm.SwinChain(B, [(C, h, depth, H, W)], w, {"stages": [dev_blocks]}, dtype, mode)
+              for name, mode in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
+    y = torch.empty_like(xd)
+    stream = torch.cuda.current_stream()
+
+    def timed(chain):
+        for _ in range(a.warmup):
+            chain(xd, out=y, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            chain(xd, out=y, stream=stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / a.steps
+
+    def kernels(chain):
+        sm.timing_enable(True)
+        for _ in range(a.steps):
+            chain(xd, out=y, stream=stream)
+        torch.cuda.synchronize()
+        rep = sm.timing_report()
+        sm.timing_enable(False)
+        return rep
+
+    sec = {name: timed(c) for name, c in chains.items()}
+    rep = {name: kernels(c) for name, c in chains.items()}
+
+    def table(r):
+        rows = []
+        for label, (n, ms) in r.items():
+            by, fl = kernel_model(label)
+            us = ms / n * 1e3
+            rows.append({"kernel": label, "launches_per_step": n // a.steps, "avg_us": round(us, 3),
+                         "alg_bytes": by, "flops": fl,
+                         "GBps": round(by / us * 1e-3, 1), "TFLOPs": round(fl / us * 1e-6, 1)})
+        return rows
+
+    tab = table(rep["elided"])
+    dom = max(tab, key=lambda r: r["avg_us"] * r["launches_per_step"])
+    t_hbm, t_mfma = dom["alg_bytes"] / PEAK_HBM, dom["flops"] / PEAK_BF16
+    if t_mfma >= t_hbm:
+        roof = {"bound": "mfma", "achieved": dom["TFLOPs"], "peak": PEAK_BF16 * 1e-12, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["GBps"], "peak": PEAK_HBM * 1e-9, "unit": "GB/s"}
+    roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
+    roof["traffic"] = MEASURED_TRAFFIC.get(dom["kernel"])
+    roof["kernel"] = dom["kernel"]
+    roof["avg_us"] = dom["avg_us"]
+
+    alg_bytes = {name: sum(kernel_model(l)[0] * (n // a.steps) for l, (n, _) in r.items()) for name, r in rep.items()}
+    kern_us = {name: sum(ms for _, ms in r.values()) / a.steps * 1e3 for name, r in rep.items()}
+
+    out = {
+        "metric": "Swin/attention block images(tokens)/s + HBM bytes vs explicit-transpose chain",
+        "value": round(B / sec["elided"], 1), "unit": "images/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(sec["elided"] * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Swin stage-3 chain, B=32, 14x14 tokens, C=384, 12 heads, window 7, "
+                               "6 blocks shift 0/3, MLP 4x", "mode": "elided", "global_batch": B},
+        "explicit_chain": {"images_per_s": round(B / sec["explicit"], 1), "ms_per_step": round(sec["explicit"] * 1e3, 4),
+                           "alg_bytes_per_step": alg_bytes["explicit"], "kernel_us_per_step": round(kern_us["explicit"], 2)},
+        "elided_chain": {"alg_bytes_per_step": alg_bytes["elided"], "kernel_us_per_step": round(kern_us["elided"], 2),
+                         "speedup_vs_explicit": round(sec["explicit"] / sec["elided"], 3),
+                         "bytes_ratio_explicit_over_elided": round(alg_bytes["explicit"] / alg_bytes["elided"], 3)},
+        "roofline": roof,
+        "kernels": tab,
+    }
+
+    if not a.no_cpu_baseline:
+        from oracle import swin
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        xn = x.double().numpy()
+        pn = [{k: v.double().numpy() for k, v in p.items()} for p in blocks]
+        t0 = time.perf_counter()
+        swin.swin_stage(xn, pn, H, W, w, h)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(B / dt, 2), "unit": "images/s", "cores": cores, "kind": "oracle",
+                               "sample": "the full workload once (32 images through 6 blocks), float64 numpy, %.2f s" % dt}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -292,6 +292,14 @@ int sm_run_chain(const sm_chain_desc*, const void* const* weights, int n_weights
  * of this thread enqueued, split into compute and copy kernels. */
 int sm_last_launch_counts(int* n_compute, int* n_copy);
 
+/* Per-kernel timing for benchmarks.  sm_timing_enable(1) clears earlier records and makes every
+ * kernel launch of this library record a HIP event before and after itself on its stream (a small
+ * perturbation: do not enable it inside a region timed as a whole); sm_timing_enable(0) stops and
+ * clears.  sm_timing_report waits for the recorded events and writes one line per kernel label,
+ * "label<TAB>launches<TAB>total_ms", into buf (host pointer, n bytes). */
+int sm_timing_enable(int on);
+int sm_timing_report(char* buf, int n);
+
 #ifdef __cplusplus
 }
 #endif

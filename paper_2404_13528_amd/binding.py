@@ -380,3 +380,18 @@ class SwinChain:
         check(lib().sm_run_chain(C.byref(self.desc), self.wptr, len(self._keep), _ptr(x), _ptr(y), _ptr(feat),
                                  _ptr(self.ws), C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_run_chain")
         return (y, feat) if want_feat else y
+
+
+def timing_enable(on=True):
+    check(lib().sm_timing_enable(1 if on else 0), "sm_timing_enable")
+
+
+def timing_report():
+    """{label: (launches, total_ms)} of the launches since timing_enable(True), in first-launch order."""
+    buf = C.create_string_buffer(1 << 16)
+    check(lib().sm_timing_report(buf, len(buf)), "sm_timing_report")
+    out = {}
+    for line in buf.value.decode().splitlines():
+        label, n, ms = line.split("\t")
+        out[label] = (int(n), float(ms))
+    return out

@@ -40,7 +40,7 @@ def build(force=True, jobs=8, verbose=False):
         if n.endswith(".hip"):
             cmds.append([HIPCC, "-x", "hip"] + COMMON + HIPFLAGS + ["-c", src, "-o", obj])
         else:
-            cmds.append([HIPCC, "-x", "c++"] + COMMON + ["-c", src, "-o", obj])
+            cmds.append([HIPCC, "-x", "c++", "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__"] + COMMON + ["-c", src, "-o", obj])
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         for w in ex.map(_compile, cmds):
             if verbose and w.strip():

@@ -28,6 +28,9 @@ int norm_checked(NormArgs& a, void* stream, const char* who) {
   if (a.C / vec > 512) return fail(SM_ERR_UNSUPPORTED, "%s: C = %d exceeds %d", who, a.C, 512 * vec);
   if (!aligned16(a.x) || !aligned16(a.y) || !aligned16(a.gamma) || (a.beta && !aligned16(a.beta)))
     return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  char label[96];
+  snprintf(label, sizeof(label), "%s_%s[%lld,%d]%s", a.rms ? "rmsnorm" : "layernorm", a.dtype == SM_F32 ? "f32" : "bf16", (long long)a.rows, a.C, a.nseg > 1 ? "+gather" : (a.store.identity ? "" : "+scatter"));
+  Timed tm(label, stream);
   int rc = launch_norm(a, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
   count_compute();
@@ -43,6 +46,7 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   if (g.act < SM_ACT_NONE || g.act > SM_ACT_GEGLU) return fail(SM_ERR_INVALID_ARG, "%s: unknown activation", who);
   const bool gated = g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU;
   if (gated && (g.N % 64)) return fail(SM_ERR_SHAPE, "%s: gated activations need N / 2 to be a multiple of 32", who);
+  if (g.a_gran > 0 && (g.act != SM_ACT_NONE || g.rope_cols)) return fail(SM_ERR_UNSUPPORTED, "%s: activation or RoPE with an unfolded A operand", who);
   if (gated && g.rope_cols) return fail(SM_ERR_UNSUPPORTED, "%s: RoPE with a gated activation", who);
   if (g.rope_cols) {
     if (g.rope_dim < 64 || g.rope_dim % 64 || g.rope_cols % g.rope_dim || g.rope_cols > g.N || g.rope_seq < 1)
@@ -51,6 +55,10 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   if (g.c_transposed && (g.c_batch_rows < 1 || g.M % g.c_batch_rows)) return fail(SM_ERR_SHAPE, "%s: bad transposed-store batch", who);
   if (!aligned16(g.A) || !aligned16(g.W) || !aligned16(g.C)) return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
   if ((int64_t)g.N * g.ldw > INT32_MAX * 16LL) return fail(SM_ERR_UNSUPPORTED, "%s: weight too large", who);
+  char label[128];
+  snprintf(label, sizeof(label), "gemm_%s[%lld,%d,%d]%s%s%s", g.dtype == SM_F32 ? "f32" : "bf16", (long long)g.M, g.N, g.K,
+           g.act == SM_ACT_GELU ? "+gelu" : (g.act ? "+glu" : ""), g.residual ? "+res" : "", g.c_rows.identity ? "" : "+scatter");
+  Timed tm(label, stream);
   int rc = launch_gemm(g, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
   count_compute();
@@ -81,6 +89,10 @@ int attention_checked(const sm_attention_desc& d, const void* q, const void* k, 
     if (d.kind != SM_ATT_WINDOW) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 supports window attention only", who);
     if (d.nq > 64 || d.d > 64) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 window attention needs window^2 <= 64 and head size <= 64", who);
   }
+  char label[128];
+  snprintf(label, sizeof(label), "attention_%s_%s[%d,%d,%d,%d,%d]", d.kind == SM_ATT_WINDOW ? "window" : (d.kind == SM_ATT_CAUSAL ? "causal" : "full"),
+           d.dtype == SM_F32 ? "f32" : "bf16", d.nb, d.heads, d.nq, d.nk, d.d);
+  Timed tm(label, stream);
   int rc = launch_attention(d, q, k, v, o, table, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
   count_compute();
@@ -105,6 +117,7 @@ extern "C" int sm_groupnorm(const void* x, const void* gamma, const void* beta, 
   if (!dtype_ok(dtype)) return fail(SM_ERR_INVALID_ARG, "sm_groupnorm: unknown dtype");
   if (B < 1 || C < 1 || HW < 1 || G < 1 || C % G) return fail(SM_ERR_SHAPE, "sm_groupnorm: bad shape");
   GroupNormArgs a{x, gamma, beta, y, B, C, HW, G, eps, tokens_out, dtype};
+  Timed tm("groupnorm", stream);
   int rc = launch_groupnorm(a, stream);
   if (rc) return fail(SM_ERR_DEVICE, "sm_groupnorm: launch failed (hip error %d)", rc);
   count_compute();

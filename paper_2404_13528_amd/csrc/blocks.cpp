@@ -106,6 +106,9 @@ int check_swin(const sm_swin_cfg* c, const char* who) {
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 int copy_launch(const Copy& cp, const void* src, void* dst, int dtype, void* stream, const void* addend = nullptr) {
+  char label[64];
+  snprintf(label, sizeof(label), "copy_%s[%lld]%s", dtype == SM_F32 ? "f32" : "bf16", (long long)cp.numel, addend ? "+add" : "");
+  Timed tm(label, stream);
   int rc = addend ? launch_gather_add(cp.prog, cp.numel, cp.vec, src, addend, dst, dtype, stream)
                   : launch_gather(cp.prog, cp.numel, cp.vec, src, dst, (int)dtype_size(dtype), stream);
   if (rc) return fail(SM_ERR_DEVICE, "copy kernel launch failed (hip error %d)", rc);
@@ -401,7 +404,8 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
     void* feat = y_feat ? y_feat : act[flip];
     if ((rc = run_norm(cur, wp[0], wp[1], feat, (int64_t)c->B * L, st.C, c->eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
     void* pooled = blk_ws;
-    int lrc = launch_mean_tokens(feat, pooled, c->B, L, st.C, dt, stream);
+    int lrc;
+    { Timed tm("mean_tokens", stream); lrc = launch_mean_tokens(feat, pooled, c->B, L, st.C, dt, stream); }
     if (lrc) return fail(SM_ERR_DEVICE, "sm_run_chain: mean launch failed (hip error %d)", lrc);
     count_compute();
     if ((rc = run_gemm(pooled, wp[2], wp[3], nullptr, y, c->B, c->n_cls, st.C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;

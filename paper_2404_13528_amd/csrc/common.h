@@ -17,4 +17,13 @@ void count_compute(int n = 1);
 void count_copy(int n = 1);
 const char* last_error();
 int counts(int* a, int* b);
+// Optional per-kernel timing: when enabled, every launch made through Timed is bracketed by two
+// events on its stream; sm_timing_report sums them per label.
+int timing_enable(int on);
+int timing_report(char* buf, int n);
+struct Timed {
+  Timed(const char* label, void* stream);
+  ~Timed();
+  void* stream_; int slot_;
+};
 }  // namespace sm

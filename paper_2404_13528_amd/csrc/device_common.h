@@ -55,6 +55,37 @@ __device__ __forceinline__ void eval_atoms(const ProgAtom* atoms, int n_atoms, c
   }
 }
 
+// Kernel arguments live in the constant kernarg segment.  Reading a large by-value argument through
+// this pointer keeps dynamically indexed fields (the index programs) in scalar loads instead of a
+// private copy.  The first explicit argument of a kernel starts at offset 0 of the segment.
+#define SM_KARG __attribute__((address_space(4)))
+template <typename Args>
+__device__ __forceinline__ const SM_KARG Args* kernarg_ptr() { return (const SM_KARG Args*)__builtin_amdgcn_kernarg_segment_ptr(); }
+
+// out of line: one copy per translation unit, called once per row outside the hot loops
+__device__ __noinline__ static int64_t eval_rows_k(const SM_KARG RowProg* p, int64_t r) {
+  if (p->identity) return r * p->ld;
+  int val[PROG_MAX_ATOMS];
+  const int n = p->n_atoms;
+  for (int i = 0; i < n; ++i) {
+    const SM_KARG ProgAtom* a = &p->atoms[i];
+    int x = a->c0;
+    for (int t = 0; t < a->nterm; ++t) {
+      const int id = a->t_atom[t];
+      x += a->t_coef[t] * (id < 0 ? (int)r : val[id]);
+    }
+    if (a->div > 1) x /= a->div;
+    if (a->mod > 0) x %= a->mod;
+    val[i] = x;
+  }
+  int64_t off = p->c0;
+  for (int t = 0; t < p->nterm; ++t) {
+    const int id = p->t_atom[t];
+    off += p->t_coef[t] * (int64_t)(id < 0 ? (int)r : val[id]);
+  }
+  return off;
+}
+
 __device__ __forceinline__ int64_t eval_rows(const RowProg& p, int64_t r) {
   if (p.identity) return r * p.ld;
   int val[PROG_MAX_ATOMS];

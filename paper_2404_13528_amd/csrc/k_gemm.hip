@@ -23,6 +23,8 @@ namespace sm {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 struct ColMap {      // logical column n' -> physical W row / output column
   int mode;          // 0 identity, 1 gated halves, 2 rope
@@ -47,12 +49,15 @@ __device__ __forceinline__ int phys_col(const ColMap& cm, int n) {
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
-template <typename T, int MI>
+enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
+
+template <typename T, int MI, int EPI, bool AGRAN>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int tiles_n) {
+  const SM_KARG GemmArgs* gk = kernarg_ptr<GemmArgs>();      // g is the first argument
   constexpr int VEC = Elem<T>::VEC;
   constexpr int BM = 64 * MI, BN = 128, BK = 8 * VEC;
   constexpr int A_SLOTS = BM * 8, B_SLOTS = BN * 8;
-  extern __shared__ uint4 lds[];                     // [2][A_SLOTS + B_SLOTS]
+  extern __shared__ u32x4 lds[];                     // [2][A_SLOTS + B_SLOTS]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, hf = lane >> 5;
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   for (int i = 0; i < 2 * MI; ++i) {
     const int64_t r = m0 + lr + 32 * i;
     a_ok[i] = r < g.M;
-    a_ptr[i] = A + (a_ok[i] ? eval_rows(g.a_rows, r) : 0) + lc * VEC;
+    a_ptr[i] = A + (a_ok[i] ? (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) : 0) + lc * VEC;
   }
   const T* b_ptr[4];
   bool b_ok[4];
@@ -89,36 +94,36 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
-  uint4 ra[2 * MI], rb[4];
-  const uint4 zero = make_uint4(0, 0, 0, 0);
+  u32x4 ra[2 * MI], rb[4];
+  const u32x4 zero = {0u, 0u, 0u, 0u};
   auto load_tile = [&](int k0) {
     const bool k_ok = k0 + lc * VEC < g.K;
-    if (g.a_gran > 0) {
+    if constexpr (AGRAN) {
       // K contiguous only in granules of 4 elements (an unfold folded into the load): the chunk is one
       // (fp32) or two (bf16) granules, each addressed through the column program
       const int kq = (k0 + lc * VEC) / 4;
-      const int64_t c0 = k_ok ? eval_rows(g.a_cols, kq) : 0;
-      const int64_t c1 = (k_ok && VEC == 8) ? eval_rows(g.a_cols, kq + 1) : 0;
+      const int64_t c0 = k_ok ? eval_rows_k(&gk->a_cols, kq) : 0;
+      const int64_t c1 = (k_ok && VEC == 8) ? eval_rows_k(&gk->a_cols, kq + 1) : 0;
 #pragma unroll
       for (int i = 0; i < 2 * MI; ++i) {
         if (!(a_ok[i] && k_ok)) { ra[i] = zero; continue; }
         const T* base = a_ptr[i] - lc * VEC;
-        if constexpr (VEC == 4) ra[i] = *(const uint4*)(base + c0);
+        if constexpr (VEC == 4) ra[i] = *(const u32x4*)(base + c0);
         else {
-          const uint2 lo = *(const uint2*)(base + c0), hi = *(const uint2*)(base + c1);
-          ra[i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          const u32x2 lo = *(const u32x2*)(base + c0), hi = *(const u32x2*)(base + c1);
+          ra[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
         }
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < 2 * MI; ++i) ra[i] = (a_ok[i] && k_ok) ? *(const uint4*)(a_ptr[i] + k0) : zero;
+      for (int i = 0; i < 2 * MI; ++i) ra[i] = (a_ok[i] && k_ok) ? *(const u32x4*)(a_ptr[i] + k0) : zero;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) rb[i] = (b_ok[i] && k_ok) ? *(const uint4*)(b_ptr[i] + k0) : zero;
+    for (int i = 0; i < 4; ++i) rb[i] = (b_ok[i] && k_ok) ? *(const u32x4*)(b_ptr[i] + k0) : zero;
   };
   auto store_tile = [&](int buf) {
-    uint4* a_l = lds + buf * (A_SLOTS + B_SLOTS);
-    uint4* b_l = a_l + A_SLOTS;
+    u32x4* a_l = lds + buf * (A_SLOTS + B_SLOTS);
+    u32x4* b_l = a_l + A_SLOTS;
 #pragma unroll
     for (int i = 0; i < 2 * MI; ++i) { const int r = lr + 32 * i; a_l[r * 8 + (lc ^ (r & 7))] = ra[i]; }
 #pragma unroll
@@ -131,12 +136,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     if (kt + 1 < nk) load_tile((kt + 1) * BK);
-    const uint4* a_l = lds + (kt & 1) * (A_SLOTS + B_SLOTS);
-    const uint4* b_l = a_l + A_SLOTS;
+    const u32x4* a_l = lds + (kt & 1) * (A_SLOTS + B_SLOTS);
+    const u32x4* b_l = a_l + A_SLOTS;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int c = 2 * j + hf;
-      uint4 fa[MI], fb[2];
+      u32x4 fa[MI], fb[2];
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) { const int r = wm * 32 * MI + mi * 32 + l32; fa[mi] = a_l[r * 8 + (c ^ (r & 7))]; }
 #pragma unroll
@@ -168,7 +173,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
     int64_t off = 0;
     if (r < g.M) {
       if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; off = bi * g.c_batch_rows * (cm.mode == 1 ? cm.half : g.N) + (r - bi * g.c_batch_rows); }
-      else off = eval_rows(g.c_rows, r);
+      else off = g.c_rows.identity ? r * g.c_rows.ld : eval_rows_k(&gk->c_rows, r);
     }
     c_off[tid] = off;
   }
@@ -184,7 +189,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   const bool ok0 = nl0 < g.N, ok1 = nl1 < g.N;
   const float b0 = (bias && ok0) ? Elem<T>::ld(bias + pc0) : 0.f;
   const float b1 = (bias && ok1) ? Elem<T>::ld(bias + pc1) : 0.f;
-  const bool rope = cm.mode == 2 && nl0 < cm.rope_cols;
+  const bool rope = EPI == EPI_ROPE && nl0 < cm.rope_cols;
   float theta = 0.f;
   if (rope) {
     const int e = pc0 % cm.rope_dim;                  // index of the pair, < rope_dim / 2
@@ -199,7 +204,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
       if (r >= g.M) continue;
       float v0 = acc[mi][0][i] + b0, v1 = acc[mi][1][i] + b1;
       const int64_t ro = c_off[rl];
-      if (cm.mode == 1) {
+      if constexpr (EPI == EPI_GLU) {
         float o = g.act == SM_ACT_SWIGLU ? silu_f(v0) * v1 : v0 * gelu_erf(v1);
         if (ok0 && pc0 < cm.half) {
           const int64_t off = ro + pc0 * col_stride;
@@ -208,8 +213,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
         }
         continue;
       }
-      if (g.act == SM_ACT_GELU) { v0 = gelu_erf(v0); v1 = gelu_erf(v1); }
-      if (rope) {
+      if constexpr (EPI == EPI_GELU) { v0 = gelu_erf(v0); v1 = gelu_erf(v1); }
+      if (EPI == EPI_ROPE && rope) {
         const float ang = (float)(r % g.rope_seq) * theta;
         float sn, cs;
         sincosf(ang, &sn, &cs);
@@ -232,25 +237,32 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   (void)n_out;
 }
 
+template <typename T, int MI, int EPI, bool AGRAN>
+static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+  constexpr int BM = 64 * MI;
+  const int tiles_n = (g.N + 127) / 128;
+  const int64_t tiles_m = (g.M + BM - 1) / BM;
+  const size_t smem = 2 * (BM * 8 + 128 * 8) * sizeof(u32x4);
+  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) return (int)attr;
+  gemm_kernel<T, MI, EPI, AGRAN><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), smem, s>>>(g, cm, tiles_n);
+  return (int)hipGetLastError();
+}
+
+template <typename T, int MI>
+static int gemm_pick_epi(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+  if (g.a_gran > 0) return gemm_launch<T, MI, EPI_PLAIN, true>(g, cm, s);     // checked by the caller: no activation with an unfold
+  if (cm.mode == 1) return gemm_launch<T, MI, EPI_GLU, false>(g, cm, s);
+  if (cm.mode == 2) return gemm_launch<T, MI, EPI_ROPE, false>(g, cm, s);
+  if (g.act == SM_ACT_GELU) return gemm_launch<T, MI, EPI_GELU, false>(g, cm, s);
+  return gemm_launch<T, MI, EPI_PLAIN, false>(g, cm, s);
+}
+
 template <typename T>
 static int gemm_dispatch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   // small problems take the 64-row tile so that the grid still covers the chip
   const int64_t tiles128 = ((g.M + 127) / 128) * ((g.N + 127) / 128);
-  const int tiles_n = (g.N + 127) / 128;
-  if (tiles128 >= 512) {
-    const int64_t tiles_m = (g.M + 127) / 128;
-    const size_t smem = 2 * (128 * 8 + 128 * 8) * sizeof(uint4);
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (attr != hipSuccess) return (int)attr;
-    gemm_kernel<T, 2><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), smem, s>>>(g, cm, tiles_n);
-  } else {
-    const int64_t tiles_m = (g.M + 63) / 64;
-    const size_t smem = 2 * (64 * 8 + 128 * 8) * sizeof(uint4);
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (attr != hipSuccess) return (int)attr;
-    gemm_kernel<T, 1><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), smem, s>>>(g, cm, tiles_n);
-  }
-  return (int)hipGetLastError();
+  return tiles128 >= 512 ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
 }
 
 int launch_gemm(const GemmArgs& g, void* stream) {
