@@ -244,8 +244,8 @@ def plan(tensors, ops, k=1):
             changed = True
 
     for i in range(n):
-        if status[i][0] == "kept" and group[i] == ILD_VAR and action[i] is None:
-            action[i] = KEEP_BOTH
+        if status[i][0] == "kept" and action[i] is None:
+            action[i] = KEEP_BOTH                     # a preserved operator is reported as kept
         if status[i][0] == "eliminated":              # absorbed by the merged node's root
             status[i] = ("eliminated", find(status[i][1]), status[i][2])
     store_chain = {find(p_): v for p_, v in store_chain.items()}

@@ -395,3 +395,122 @@ def timing_report():
         label, n, ms = line.split("\t")
         out[label] = (int(n), float(ms))
     return out
+
+
+# --------------------------------------------------------------------------
+# layout planner
+# --------------------------------------------------------------------------
+
+def op_group(kind):
+    g = C.c_int()
+    check(lib().sm_op_group(OP_KIND[kind], C.byref(g)), "sm_op_group")
+    return GROUPS[g.value]
+
+
+def pair_action(first, second):
+    a = C.c_int()
+    check(lib().sm_pair_action(GROUPS.index(first), GROUPS.index(second), C.byref(a)), "sm_pair_action")
+    return ACTIONS[a.value]
+
+
+def pair_outcome(first, second):
+    r, s = C.c_int(), C.c_int()
+    check(lib().sm_pair_outcome(GROUPS.index(first), GROUPS.index(second), C.byref(r), C.byref(s)), "sm_pair_outcome")
+    return (None if r.value < 0 else GROUPS[r.value]), SEARCH[s.value]
+
+
+class Plan:
+    """sm_layout_plan over a graph given as (tensor shapes, op dicts) in the form of workloads.Graph."""
+
+    def __init__(self, tensors, ops, k=1):
+        self.n_ops, self.ranks = len(ops), [len(t) for t in tensors]
+        td = (TensorDesc * len(tensors))(*[_tdesc(t) for t in tensors])
+        od = (OpDesc * len(ops))()
+        for i, o in enumerate(ops):
+            d = od[i]
+            d.kind, d.n_in, d.out = OP_KIND[o["kind"]], len(o["in"]), o["out"]
+            for s, t in enumerate(o["in"]):
+                d.in_[s] = t
+            a = o.get("attr", {})
+            vals = []
+            if o["kind"] == "TRANSPOSE":
+                vals = list(a["perm"])
+            elif o["kind"] == "ROLL":
+                vals = [a["axis"], a["shift"]]
+            elif o["kind"] == "SLICE":
+                vals = [a["axis"], a["start"], a["stop"], a.get("step", 1)]
+            elif "red" in a:
+                vals = [-1 if r is None else r for r in a["red"]]
+            d.n_attr = len(vals)
+            for j, v in enumerate(vals):
+                d.attr[j] = int(v)
+        self.h = C.c_void_p()
+        check(lib().sm_layout_plan(td, len(tensors), od, len(ops), k, C.byref(self.h)), "sm_layout_plan")
+
+    def op(self, i):
+        g, a, s, by, ng = C.c_int(), C.c_int(), C.c_int(), C.c_int(), C.c_int()
+        check(lib().sm_plan_op(self.h, i, C.byref(g), C.byref(a), C.byref(s), C.byref(by), C.byref(ng)), "sm_plan_op")
+        return {"group": GROUPS[g.value], "action": ACTIONS[a.value], "status": STATUS[s.value],
+                "absorbed_by": by.value, "node_group": GROUPS[ng.value]}
+
+    def tensor(self, t):
+        order = (C.c_int * MAX_RANK)()
+        red = (C.c_int * MAX_RANK)()
+        nr, nc = C.c_int(), C.c_int()
+        rc = lib().sm_plan_tensor(self.h, t, order, red, C.byref(nr), C.byref(nc))
+        if rc < 0:
+            return None
+        return {"dim_order": [order[i] for i in range(self.ranks[t])], "red_dims": [red[i] for i in range(nr.value)],
+                "n_copies": nc.value}
+
+    def load_map(self, consumer, operand):
+        m, t = C.c_void_p(), C.c_int()
+        check(lib().sm_plan_load_map(self.h, consumer, operand, C.byref(m), C.byref(t)), "sm_plan_load_map")
+        return (Map(m, owned=False) if m.value else None), t.value
+
+    def store_map(self, producer):
+        m, t = C.c_void_p(), C.c_int()
+        check(lib().sm_plan_store_map(self.h, producer, C.byref(m), C.byref(t)), "sm_plan_store_map")
+        return (Map(m, owned=False) if m.value else None), t.value
+
+    def __del__(self):
+        if self.h and _lib is not None:
+            _lib.sm_plan_destroy(self.h)
+            self.h = None
+
+
+class AttnBlock:
+    """sm_attn_block: kind "llama" or "sd".  params follow workloads.llama_case / sd_case (device tensors);
+    the fused weight matrices the library takes (q|k|v, gate|up, k|v) are concatenated here, once."""
+
+    def __init__(self, kind, params, dtype, mode=SM_ELIDED, B=1, S=0, E=0, heads=1, F=0, Hs=0, Ws=0, groups=32, Sc=0, Dc=0,
+                 rope_base=10000.0, eps_norm=1e-5, eps_gn=1e-6):
+        import torch
+        p = params
+        if kind == "llama":
+            ws = [p["rms1_g"], torch.cat([p["wq"], p["wk"], p["wv"]], 0).contiguous(), p["wo"], p["rms2_g"],
+                  torch.cat([p["wgate"], p["wup"]], 0).contiguous(), p["wdown"]]
+            k = 0
+        else:
+            ws = [p["gn_g"], p["gn_b"], p["win"], p["bin"], p["ln1_g"], p["ln1_b"],
+                  torch.cat([p["a1_wq"], p["a1_wk"], p["a1_wv"]], 0).contiguous(), p["a1_wo"], p["a1_bo"],
+                  p["ln2_g"], p["ln2_b"], p["a2_wq"], torch.cat([p["a2_wk"], p["a2_wv"]], 0).contiguous(), p["a2_wo"], p["a2_bo"],
+                  p["ln3_g"], p["ln3_b"], p["ff_w1"], p["ff_b1"], p["ff_w2"], p["ff_b2"], p["wout"], p["bout"]]
+            k = 1
+            S = Hs * Ws
+        self.cfg = AttnCfg(k, SM_BF16 if dtype == torch.bfloat16 else SM_F32, B, S, E, heads, F, Hs, Ws, groups, Sc, Dc,
+                           rope_base, eps_norm, eps_gn)
+        self._keep = ws
+        self.wptr = (C.c_void_p * len(ws))(*[t.data_ptr() for t in ws])
+        self.mode = mode
+        n = lib().sm_attn_block_workspace_bytes(C.byref(self.cfg), mode)
+        if n == 0:
+            raise SmError("sm_attn_block_workspace_bytes: " + lib().sm_last_error().decode())
+        self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def __call__(self, x, context=None, out=None, stream=None):
+        import torch
+        y = torch.empty_like(x) if out is None else out
+        check(lib().sm_attn_block(C.byref(self.cfg), self.wptr, _ptr(x), _ptr(context), _ptr(y), _ptr(self.ws),
+                                  C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_attn_block")
+        return y

@@ -46,6 +46,7 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   if (g.act < SM_ACT_NONE || g.act > SM_ACT_GEGLU) return fail(SM_ERR_INVALID_ARG, "%s: unknown activation", who);
   const bool gated = g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU;
   if (gated && (g.N % 64)) return fail(SM_ERR_SHAPE, "%s: gated activations need N / 2 to be a multiple of 32", who);
+  if (g.c_cols_on && (g.c_transposed || g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU)) return fail(SM_ERR_UNSUPPORTED, "%s: column-splitting store with a gated activation or transposed store", who);
   if (g.a_gran > 0 && (g.act != SM_ACT_NONE || g.rope_cols)) return fail(SM_ERR_UNSUPPORTED, "%s: activation or RoPE with an unfolded A operand", who);
   if (gated && g.rope_cols) return fail(SM_ERR_UNSUPPORTED, "%s: RoPE with a gated activation", who);
   if (g.rope_cols) {
@@ -144,6 +145,13 @@ extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, 
   if (rc) return rc;
   if (d->c_transposed && c_map) return fail(SM_ERR_UNSUPPORTED, "sm_linear: transposed store with a row map");
   rc = rows_of(c_map, d->M, n_out, n_out, &g.c_rows, "sm_linear(C)");
+  if (rc == SM_ERR_UNSUPPORTED && c_map) {
+    // the store splits the column dimension (e.g. into heads): separable row + column programs
+    std::string err;
+    if (!c_map->compile_rows_cols(1, &g.c_rows, &g.c_cols, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_linear(C): %s", err.c_str());
+    g.c_cols_on = 1;
+    rc = SM_OK;
+  }
   if (rc) return rc;
   return gemm_checked(g, stream, "sm_linear");
 }

@@ -17,6 +17,7 @@
 #include "index_map.h"
 #include "kernels.h"
 #include "plan_chains.h"
+#include "graph_build.h"
 
 using namespace sm;
 
@@ -27,9 +28,10 @@ struct Copy {            // one materialised layout transformation
 };
 
 struct SwinPlan {
-  // elided
+  // elided: what sm_layout_plan decided for the block's operator graph
   RowProg ln1_store;     // natural token row -> row offset in the window-major tensor
   RowProg proj_store;    // window-major row -> row offset in the natural tensor
+  int64_t qkv_base[3], qkv_stride[3][3], o_stride[3];   // q, k, v and o as strided views [B_, h, N, d]
   // explicit
   bool has_roll;
   Copy roll, partition, head_split, head_merge, reverse, unroll;
@@ -71,10 +73,65 @@ std::shared_ptr<SwinPlan> swin_plan(const sm_swin_cfg& c, std::string* err) {
   const int64_t B = c.B, H = c.H, W = c.W, C = c.C, w = c.window, s = c.shift, h = c.heads;
   const int64_t N = w * w, d = C / h, B_ = B * (H / w) * (W / w);
   const int es = (int)dtype_size(c.dtype);
-  // elided: LayerNorm's store absorbs {reshape, roll, roll, reshape, permute, reshape}: the map of the
-  // inverse run over the stored (window-major) tensor; proj's store absorbs the reverse run likewise.
-  if (!make_rows({B_, N, C}, chains::window_reverse(B, H, W, C, w, s), &p->ln1_store, err)) return nullptr;
-  if (!make_rows({B, H, W, C}, chains::window_partition(B, H, W, C, w, s), &p->proj_store, err)) return nullptr;
+  // elided: describe the block as the exporter's operator graph and let the planner decide
+  {
+    GraphB g;
+    const int x = g.tensor({B, H * W, C});
+    int t = g.op(SM_OP_LAYERNORM, {x}, {B, H * W, C}, "ln1", {2});
+    t = g.reshape(t, {B, H, W, C});
+    if (s) { t = g.roll(t, 1, -s); t = g.roll(t, 2, -s); }
+    t = g.reshape(t, {B, H / w, w, W / w, w, C});
+    t = g.transpose(t, {0, 1, 3, 2, 4, 5});
+    t = g.reshape(t, {B_, N, C});
+    t = g.linear(t, 3 * C, "qkv", true);
+    t = g.reshape(t, {B_, N, 3, h, d});
+    t = g.transpose(t, {2, 0, 3, 1, 4});
+    std::vector<int> qkv;
+    for (int k = 0; k < 3; ++k) qkv.push_back(g.reshape(g.slice(t, 0, k, k + 1), {B_, h, N, d}));
+    t = g.op(SM_OP_ATTENTION, qkv, {B_, h, N, d}, "attn", {3, 3, -1});
+    t = g.transpose(t, {0, 2, 1, 3});
+    t = g.reshape(t, {B_, N, C});
+    t = g.linear(t, C, "proj", true);
+    t = g.reshape(t, {B, H / w, W / w, w, w, C});
+    t = g.transpose(t, {0, 1, 3, 2, 4, 5});
+    t = g.reshape(t, {B, H, W, C});
+    if (s) { t = g.roll(t, 1, s); t = g.roll(t, 2, s); }
+    t = g.reshape(t, {B, H * W, C});
+    const int x1 = g.op(SM_OP_ADD, {x, t}, {B, H * W, C}, "res1");
+    t = g.op(SM_OP_LAYERNORM, {x1}, {B, H * W, C}, "ln2", {2});
+    t = g.linear(t, c.mlp_ratio * C, "fc1", true);
+    t = g.op(SM_OP_UNARY, {t}, {B, H * W, c.mlp_ratio * C}, "gelu");
+    t = g.linear(t, C, "fc2", true);
+    g.op(SM_OP_ADD, {x1, t}, {B, H * W, C}, "res2");
+    sm_plan* plan = nullptr;
+    if (sm_layout_plan(g.tensors.data(), (int)g.tensors.size(), g.ops.data(), (int)g.ops.size(), 1, &plan) != SM_OK) { *err = sm_last_error(); return nullptr; }
+    std::unique_ptr<sm_plan, void (*)(sm_plan*)> guard(plan, sm_plan_destroy);
+    int kept = 0, layout_ops = 0, eliminated = 0;
+    for (int i = 0; i < (int)g.ops.size(); ++i) {
+      int grp, st;
+      sm_plan_op(plan, i, &grp, nullptr, &st, nullptr, nullptr);
+      kept += st == SM_KEPT;
+      if (grp == SM_ILD_FIX || grp == SM_ILI_FIX) { ++layout_ops; eliminated += (st == SM_ELIMINATED_STORE || st == SM_ELIMINATED_LOAD); }
+    }
+    p->n_layout_ops = layout_ops; p->n_eliminated = eliminated;
+    if (kept != 7 || eliminated != layout_ops) { *err = "planner did not reduce the Swin block to its seven compute kernels"; return nullptr; }
+    const sm_map* m = nullptr;
+    sm_plan_store_map(plan, g.find("ln1"), &m, nullptr);
+    if (!m || !m->compile_rows(&p->ln1_store, err)) { if (!m) *err = "no store map planned for LayerNorm"; return nullptr; }
+    sm_plan_store_map(plan, g.find("proj"), &m, nullptr);
+    if (!m || !m->compile_rows(&p->proj_store, err)) { if (!m) *err = "no store map planned for proj"; return nullptr; }
+    const int attn = g.find("attn");
+    int64_t st8[SM_MAX_RANK];
+    for (int k = 0; k < 3; ++k) {
+      sm_plan_load_map(plan, attn, k, &m, nullptr);
+      if (!m || !m->affine(&p->qkv_base[k], st8) || st8[3] != 1) { *err = "attention operand is not a strided view"; return nullptr; }
+      for (int j = 0; j < 3; ++j) p->qkv_stride[k][j] = st8[j];
+    }
+    int64_t obase;
+    sm_plan_store_map(plan, attn, &m, nullptr);
+    if (!m || !m->affine(&obase, st8) || st8[3] != 1 || obase != 0) { *err = "attention output is not a strided view"; return nullptr; }
+    for (int j = 0; j < 3; ++j) p->o_stride[j] = st8[j];
+  }
   // explicit: one copy per transformation that moves data
   p->has_roll = s != 0;
   if (s) {
@@ -175,11 +232,11 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
     if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
     const size_t es = dtype_size(dt);
     for (int i = 0; i < 3; ++i) {
-      const int64_t st[3] = {(int64_t)N * 3 * C, d, 3 * C};
-      ad.q_stride[i] = ad.k_stride[i] = ad.v_stride[i] = st[i];
+      ad.q_stride[i] = plan->qkv_stride[0][i]; ad.k_stride[i] = plan->qkv_stride[1][i]; ad.v_stride[i] = plan->qkv_stride[2][i];
+      ad.o_stride[i] = plan->o_stride[i];
     }
-    ad.o_stride[0] = (int64_t)N * C; ad.o_stride[1] = d; ad.o_stride[2] = C;
-    if ((rc = attention_checked(ad, qkv, (char*)qkv + (size_t)C * es, (char*)qkv + (size_t)2 * C * es, bufO, wt->rpb_table, stream, "window attention"))) return rc;
+    if ((rc = attention_checked(ad, (char*)qkv + plan->qkv_base[0] * es, (char*)qkv + plan->qkv_base[1] * es, (char*)qkv + plan->qkv_base[2] * es,
+                                bufO, wt->rpb_table, stream, "window attention"))) return rc;
     if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
     if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, bufA, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
     if ((rc = run_gemm(bufA, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;

@@ -54,6 +54,7 @@ struct Builder {
     return (int)atoms.size() - 1;
   }
   Affine var(int v, int64_t extent) {
+    if (extent == 1 && simplify) return Affine();     // an index that is always 0
     Atom a; a.kind = ATOM_VAR; a.var = v; a.div = 1; a.mod = 0; a.hi = extent - 1;
     Affine r; r.terms.emplace_back(intern(a), 1);
     return r;
@@ -458,6 +459,21 @@ void sm_map::eval(int64_t* offsets) const {
     offsets[o] = off;
     for (int k = rank - 1; k >= 0; --k) { if (++idx[k] < shape[k]) break; idx[k] = 0; }
   }
+}
+
+int64_t sm_map::at(const int64_t* idx) const {
+  std::vector<int64_t> val(atoms.size());
+  for (size_t i = 0; i < atoms.size(); ++i) {
+    const Atom& a = atoms[i];
+    if (a.kind == ATOM_VAR) { val[i] = idx[a.var]; continue; }
+    int64_t x = a.arg.c0;
+    for (auto& t : a.arg.terms) x += t.second * val[t.first];
+    x /= a.div;
+    val[i] = a.mod ? x % a.mod : x;
+  }
+  int64_t off = offset.c0;
+  for (auto& t : offset.terms) off += t.second * val[t.first];
+  return off;
 }
 
 bool sm_map::affine(int64_t* base, int64_t* strides) const {

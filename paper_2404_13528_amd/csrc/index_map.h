@@ -74,6 +74,7 @@ struct sm_map {
   // view collapsed to [rows, K / gran, gran] with offset = rows_part(r) + cols_part(k / gran) + k % gran
   bool compile_rows_cols(int gran, sm::RowProg* rows, sm::RowProg* cols, std::string* err) const;
   void eval(int64_t* offsets) const;
+  int64_t at(const int64_t* idx) const;       // offset of one view element
   bool affine(int64_t* base, int64_t* strides) const;
 };
 

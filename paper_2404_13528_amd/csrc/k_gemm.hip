@@ -187,6 +187,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   const int nl0 = span0 + l32, nl1 = span0 + 32 + l32;
   const int pc0 = phys_col(cm, nl0), pc1 = phys_col(cm, nl1);
   const bool ok0 = nl0 < g.N, ok1 = nl1 < g.N;
+  // column offsets: plain (n * stride) or through the column program of a store that splits the columns
+  int64_t co0 = pc0 * col_stride, co1 = pc1 * col_stride;
+  if (g.c_cols_on) { co0 = ok0 ? eval_rows_k(&gk->c_cols, pc0) : 0; co1 = ok1 ? eval_rows_k(&gk->c_cols, pc1) : 0; }
   const float b0 = (bias && ok0) ? Elem<T>::ld(bias + pc0) : 0.f;
   const float b1 = (bias && ok1) ? Elem<T>::ld(bias + pc1) : 0.f;
   const bool rope = EPI == EPI_ROPE && nl0 < cm.rope_cols;
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
       if constexpr (EPI == EPI_GLU) {
         float o = g.act == SM_ACT_SWIGLU ? silu_f(v0) * v1 : v0 * gelu_erf(v1);
         if (ok0 && pc0 < cm.half) {
-          const int64_t off = ro + pc0 * col_stride;
+          const int64_t off = ro + co0;
           if (R) o += Elem<T>::ld(R + off);
           Elem<T>::st(C + off, o);
         }
@@ -223,12 +226,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
         v1 = b * cs + a * sn;
       }
       if (ok0) {
-        const int64_t off = ro + pc0 * col_stride;
+        const int64_t off = ro + co0;
         if (R) v0 += Elem<T>::ld(R + off);
         Elem<T>::st(C + off, v0);
       }
       if (ok1) {
-        const int64_t off = ro + pc1 * col_stride;
+        const int64_t off = ro + co1;
         if (R) v1 += Elem<T>::ld(R + off);
         Elem<T>::st(C + off, v1);
       }

@@ -31,6 +31,8 @@ struct GemmArgs {
   int c_transposed; int64_t c_batch_rows;
   int64_t ldw;                  // row pitch of W in elements
   RowProg a_rows, c_rows;       // c_rows.ld = pitch of C / residual
+  int c_cols_on;                // 1: output column n is stored at c_rows(r) + c_cols(n) (a store that splits the
+  RowProg c_cols;               //    column dimension, e.g. into heads)
   int a_gran;                   // > 0: A's K axis is contiguous only in granules of a_gran (= 4) elements;
   RowProg a_cols;               //      offset(r, k) = a_rows(r) + a_cols(k / a_gran) + k % a_gran
 };

@@ -192,3 +192,15 @@ def test_argument_errors():
     with pytest.raises(sm.SmError):
         q = torch.zeros(1, 1, 50, 32, device="cuda")
         sm.attention(q, q, q, kind="window", rpb_table=x, window=7, H=14, W=14)   # 50 != 49
+
+
+def test_linear_store_splits_columns_into_heads():
+    # the store absorbs a head split: natural [B, S, h*d] -> stored [B, h, S, d]
+    dtype = torch.bfloat16
+    Bn, S, h, d, K = 2, 45, 3, 40, 64
+    A = draw((Bn * S, K), 40, dtype)
+    W = draw((h * d, K), 41, dtype, 0.125)
+    c_map = sm.Map.create((Bn, h, S, d), V.head_merge_chain(Bn, S, h, d))      # natural index -> stored offset
+    got = sm.linear(dev(A, dtype), dev(W, dtype), c_map=c_map)
+    want = V.apply_chain(O.linear(to_np(A), to_np(W)).reshape(Bn, S, h * d), V.head_split_chain(Bn, S, h, d))
+    assert_close(got.reshape(want.shape), want, dtype, "head-major store")
