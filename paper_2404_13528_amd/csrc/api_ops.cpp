@@ -84,6 +84,7 @@ int attention_checked(const sm_attention_desc& d, const void* q, const void* k, 
     if (d.window < 1 || d.nq != d.window * d.window || d.nk != d.nq) return fail(SM_ERR_SHAPE, "%s: window attention needs nq == nk == window^2", who);
     if (d.H < d.window || d.W < d.window || d.H % d.window || d.W % d.window) return fail(SM_ERR_SHAPE, "%s: grid %d x %d is not a multiple of the window %d", who, d.H, d.W, d.window);
     if (d.shift < 0 || d.shift >= d.window) return fail(SM_ERR_SHAPE, "%s: shift out of range", who);
+    if (d.nq > 64) return fail(SM_ERR_UNSUPPORTED, "%s: window attention supports windows of at most 64 tokens", who);
     if (d.nb % ((d.H / d.window) * (d.W / d.window))) return fail(SM_ERR_SHAPE, "%s: batch is not a whole number of images", who);
   }
   if (d.dtype == SM_F32) {

@@ -24,17 +24,20 @@ namespace sm {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
-struct WinGeom { int w, shift, H, W, nWx, nW; };
+struct WinGeom { int w, shift, H, W, nWx, nW, wy, wx; };
 
 __device__ __forceinline__ int region(int c, int extent, int w, int s) { return c < extent - w ? 0 : (c < extent - s ? 1 : 2); }
 
 // additive term for (query i, key j) of window `win` and head `hh`
 template <typename T>
 __device__ __forceinline__ float window_term(const WinGeom& g, const T* table, int heads, int hh, int win, int i, int j) {
-  const int yi = i / g.w, xi = i - yi * g.w, yj = j / g.w, xj = j - yj * g.w;
+  // token index -> (row, column) inside the window; exact for the small integers involved
+  const float inv_w = 1.0f / (float)g.w;
+  const int yi = (int)(((float)i + 0.5f) * inv_w), xi = i - yi * g.w;
+  const int yj = (int)(((float)j + 0.5f) * inv_w), xj = j - yj * g.w;
   float t = Elem<T>::ld(table + ((yi - yj + g.w - 1) * (2 * g.w - 1) + (xi - xj + g.w - 1)) * heads + hh);
   if (g.shift > 0) {
-    const int wy = win / g.nWx, wx = win - wy * g.nWx;
+    const int wy = g.wy, wx = g.wx;
     const int ri = 3 * region(wy * g.w + yi, g.H, g.w, g.shift) + region(wx * g.w + xi, g.W, g.w, g.shift);
     const int rj = 3 * region(wy * g.w + yj, g.H, g.w, g.shift) + region(wx * g.w + xj, g.W, g.w, g.shift);
     if (ri != rj) t += -100.f;
@@ -42,7 +45,7 @@ __device__ __forceinline__ float window_term(const WinGeom& g, const T* table, i
   return t;
 }
 
-template <int DK, int DB>
+template <int DK, int DB, int KIND>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                         const bf16_t* __restrict__ table, int n_qblk, long total_waves) {
@@ -62,9 +65,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, con
   const bool q_ok = qi < a.nq;
   WinGeom wg;
   int win = 0;
-  if (a.kind == SM_ATT_WINDOW) {
+  if (KIND == SM_ATT_WINDOW) {
     wg.w = a.window; wg.shift = a.shift; wg.H = a.H; wg.W = a.W; wg.nWx = a.W / a.window; wg.nW = (a.H / a.window) * wg.nWx;
     win = b % wg.nW;
+    wg.wy = win / wg.nWx; wg.wx = win - wg.wy * wg.nWx;
   }
   const uint4 zero = make_uint4(0, 0, 0, 0);
   uint4 qf[DK];
@@ -80,9 +84,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, con
     for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
   int n_kblk = (a.nk + 31) / 32;
-  if (a.kind == SM_ATT_CAUSAL) { const int lim = (min(q0 + 31, a.nq - 1)) / 32 + 1; n_kblk = min(n_kblk, lim); }
+  if (KIND == SM_ATT_CAUSAL) { const int lim = (min(q0 + 31, a.nq - 1)) / 32 + 1; n_kblk = min(n_kblk, lim); }
+  if (KIND == SM_ATT_WINDOW) n_kblk = 2;            // a window has at most 64 tokens: both key blocks unrolled
 
-  for (int jb = 0; jb < n_kblk; ++jb) {
+#pragma unroll
+  for (int jb = 0; jb < (KIND == SM_ATT_WINDOW ? 2 : n_kblk); ++jb) {
     const int j0 = jb * 32;
     f32x16_t s;
 #pragma unroll
@@ -102,8 +108,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, con
     for (int i = 0; i < 16; ++i) {
       const int j = j0 + (i >> 2) * 8 + hf * 4 + (i & 3);
       float x = s[i] * a.scale;
-      if (a.kind == SM_ATT_WINDOW && q_ok && j < a.nk) x += window_term<bf16_t>(wg, table, a.heads, hh, win, qi, j);
-      if (j >= a.nk || (a.kind == SM_ATT_CAUSAL && j > qi)) x = -INFINITY;
+      if (KIND == SM_ATT_WINDOW && q_ok && j < a.nk) x += window_term<bf16_t>(wg, table, a.heads, hh, win, qi, j);
+      if (j >= a.nk || (KIND == SM_ATT_CAUSAL && j > qi)) x = -INFINITY;
       s[i] = x;
       bm = fmaxf(bm, x);
     }
@@ -181,6 +187,7 @@ __global__ __launch_bounds__(64) void attn_window_f32_kernel(sm_attention_desc a
   WinGeom wg;
   wg.w = a.window; wg.shift = a.shift; wg.H = a.H; wg.W = a.W; wg.nWx = a.W / a.window; wg.nW = (a.H / a.window) * wg.nWx;
   const int win = b % wg.nW;
+  wg.wy = win / wg.nWx; wg.wx = win - wg.wy * wg.nWx;
   const int i = tid;
   if (i >= a.nq) return;
   float qr[64];
@@ -219,11 +226,16 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
   const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v, *tt = (const bf16_t*)rpb_table;
   bf16_t* oo = (bf16_t*)o;
   const int dk = (d.d + 15) / 16;
-  if (dk <= 2) attn_bf16_kernel<2, 1><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
-  else if (dk == 3) attn_bf16_kernel<3, 2><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
-  else if (dk == 4) attn_bf16_kernel<4, 2><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
-  else if (dk <= 6) attn_bf16_kernel<6, 3><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
-  else attn_bf16_kernel<8, 4><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves);
+#define ATT(DK_, DB_) do { \
+    if (d.kind == SM_ATT_WINDOW) attn_bf16_kernel<DK_, DB_, SM_ATT_WINDOW><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves); \
+    else if (d.kind == SM_ATT_CAUSAL) attn_bf16_kernel<DK_, DB_, SM_ATT_CAUSAL><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves); \
+    else attn_bf16_kernel<DK_, DB_, SM_ATT_FULL><<<grid, block, 0, s>>>(d, qq, kk, vv, oo, tt, n_qblk, waves); } while (0)
+  if (dk <= 2) ATT(2, 1);
+  else if (dk == 3) ATT(3, 2);
+  else if (dk == 4) ATT(4, 2);
+  else if (dk <= 6) ATT(6, 3);
+  else ATT(8, 4);
+#undef ATT
   return (int)hipGetLastError();
 }
 

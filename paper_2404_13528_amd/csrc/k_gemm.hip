@@ -16,6 +16,7 @@
 // logical column order of a wave's 64-column span (which W row feeds which
 // MFMA block), so that the two partners sit in the same lane: the Slice /
 // chunk operators of SwiGLU / GEGLU and the half-split of RoPE cost nothing.
+#include <type_traits>
 #include "device_common.h"
 #include "kernels.h"
 
@@ -46,7 +47,16 @@ __device__ __forceinline__ int phys_col(const ColMap& cm, int n) {
   return n;
 }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (absolute error < 1.5e-7), which costs one
+// reciprocal and one exponential instead of the library routine's long polynomial chain
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  const float t = __frcp_rn(1.f + 0.3275911f * ax);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float r = 1.f - poly * __expf(-ax * ax);
+  return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erf_as(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
 enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
@@ -61,7 +71,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, hf = lane >> 5;
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous range of
+  // tiles (column tiles fastest) so that the tiles sharing an A row panel share one L2.
+  const int n_tiles = gridDim.x;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if ((n_tiles & 7) != 0) tile_id = blockIdx.x;              // ragged grids keep the plain order
+  const int tile_m = tile_id / tiles_n, tile_n = tile_id - tile_m * tiles_n;
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
   const T* A = (const T*)g.A;
@@ -73,18 +89,38 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   bool a_ok[2 * MI];
 #pragma unroll
   for (int i = 0; i < 2 * MI; ++i) {
-    const int64_t r = m0 + lr + 32 * i;
-    a_ok[i] = r < g.M;
-    a_ptr[i] = A + (a_ok[i] ? (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) : 0) + lc * VEC;
+    // rows past M are clamped to the last row: their products land in output rows that are never stored
+    const int64_t r = min(m0 + lr + 32 * i, g.M - 1);
+    a_ok[i] = true;
+    a_ptr[i] = A + (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) + lc * VEC;
   }
   const T* b_ptr[4];
   bool b_ok[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int n = n0 + lr + 32 * i;
-    b_ok[i] = n < g.N;
-    b_ptr[i] = W + (int64_t)(b_ok[i] ? phys_col(cm, n) : 0) * g.ldw + lc * VEC;
+    const int n = min(n0 + lr + 32 * i, g.N - 1);          // clamped like the rows of A
+    b_ok[i] = true;
+    b_ptr[i] = W + (int64_t)phys_col(cm, n) * g.ldw + lc * VEC;
   }
+
+  // row (and column) offsets of C: evaluated here, before the accumulators are live, into LDS behind the tiles
+  int64_t* c_off = (int64_t*)(lds + 2 * (A_SLOTS + B_SLOTS));
+  if (tid < BM) {
+    const int64_t r = m0 + tid;
+    int64_t off = 0;
+    if (r < g.M) {
+      if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; off = bi * g.c_batch_rows * (cm.mode == 1 ? cm.half : g.N) + (r - bi * g.c_batch_rows); }
+      else off = g.c_rows.identity ? r * g.c_rows.ld : eval_rows_k(&gk->c_rows, r);
+    }
+    c_off[tid] = off;
+  }
+  const int span0 = n0 + wn * 64;                    // logical start of this wave's 64 columns
+  const int nl0 = span0 + l32, nl1 = span0 + 32 + l32;
+  const int pc0 = phys_col(cm, nl0), pc1 = phys_col(cm, nl1);
+  const bool ok0 = nl0 < g.N, ok1 = nl1 < g.N;
+  const int64_t col_stride = g.c_transposed ? g.c_batch_rows : 1;
+  int64_t co0 = pc0 * col_stride, co1 = pc1 * col_stride;
+  if (g.c_cols_on) { co0 = ok0 ? eval_rows_k(&gk->c_cols, pc0) : 0; co1 = ok1 ? eval_rows_k(&gk->c_cols, pc1) : 0; }
 
   f32x16_t acc[MI][2];
 #pragma unroll
@@ -94,49 +130,49 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
-  u32x4 ra[2 * MI], rb[4];
+  // global -> register staging, two K-tiles in flight (register sets 0 and 1)
+  u32x4 ra[2][2 * MI], rb[2][4];
+  bool kok[2] = {true, true};      // chunk of the staged tile lies inside K (zeroed when stored otherwise)
   const u32x4 zero = {0u, 0u, 0u, 0u};
-  auto load_tile = [&](int k0) {
+  auto load_tile = [&](int k0, auto SET) {
+    constexpr int S = decltype(SET)::value;
     const bool k_ok = k0 + lc * VEC < g.K;
+    kok[S] = k_ok;
     if constexpr (AGRAN) {
       // K contiguous only in granules of 4 elements (an unfold folded into the load): the chunk is one
       // (fp32) or two (bf16) granules, each addressed through the column program
       const int kq = (k0 + lc * VEC) / 4;
-      const int64_t c0 = k_ok ? eval_rows_k(&gk->a_cols, kq) : 0;
-      const int64_t c1 = (k_ok && VEC == 8) ? eval_rows_k(&gk->a_cols, kq + 1) : 0;
+      const int64_t c0 = eval_rows_k(&gk->a_cols, k_ok ? kq : 0);
+      const int64_t c1 = VEC == 8 ? eval_rows_k(&gk->a_cols, k_ok ? kq + 1 : 0) : 0;
 #pragma unroll
       for (int i = 0; i < 2 * MI; ++i) {
-        if (!(a_ok[i] && k_ok)) { ra[i] = zero; continue; }
         const T* base = a_ptr[i] - lc * VEC;
-        if constexpr (VEC == 4) ra[i] = *(const u32x4*)(base + c0);
+        if constexpr (VEC == 4) ra[S][i] = *(const u32x4*)(base + c0);
         else {
           const u32x2 lo = *(const u32x2*)(base + c0), hi = *(const u32x2*)(base + c1);
-          ra[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
+          ra[S][i] = u32x4{lo.x, lo.y, hi.x, hi.y};
         }
       }
     } else {
+      const int ks = k_ok ? k0 : 0;                          // a chunk past K is loaded from chunk 0 and zeroed
 #pragma unroll
-      for (int i = 0; i < 2 * MI; ++i) ra[i] = (a_ok[i] && k_ok) ? *(const u32x4*)(a_ptr[i] + k0) : zero;
+      for (int i = 0; i < 2 * MI; ++i) ra[S][i] = *(const u32x4*)(a_ptr[i] + ks);
     }
+    const int ks = k_ok ? k0 : 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) rb[i] = (b_ok[i] && k_ok) ? *(const u32x4*)(b_ptr[i] + k0) : zero;
+    for (int i = 0; i < 4; ++i) rb[S][i] = *(const u32x4*)(b_ptr[i] + ks);
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](int buf, auto SET) {
+    constexpr int S = decltype(SET)::value;
     u32x4* a_l = lds + buf * (A_SLOTS + B_SLOTS);
     u32x4* b_l = a_l + A_SLOTS;
 #pragma unroll
-    for (int i = 0; i < 2 * MI; ++i) { const int r = lr + 32 * i; a_l[r * 8 + (lc ^ (r & 7))] = ra[i]; }
+    for (int i = 0; i < 2 * MI; ++i) { const int r = lr + 32 * i; a_l[r * 8 + (lc ^ (r & 7))] = kok[S] ? ra[S][i] : zero; }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { const int r = lr + 32 * i; b_l[r * 8 + (lc ^ (r & 7))] = rb[i]; }
+    for (int i = 0; i < 4; ++i) { const int r = lr + 32 * i; b_l[r * 8 + (lc ^ (r & 7))] = kok[S] ? rb[S][i] : zero; }
   };
-
-  const int nk = (g.K + BK - 1) / BK;
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) load_tile((kt + 1) * BK);
-    const u32x4* a_l = lds + (kt & 1) * (A_SLOTS + B_SLOTS);
+  auto compute_tile = [&](int buf) {
+    const u32x4* a_l = lds + buf * (A_SLOTS + B_SLOTS);
     const u32x4* b_l = a_l + A_SLOTS;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -162,34 +198,51 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
           }
         }
     }
-    if (kt + 1 < nk) store_tile((kt + 1) & 1);
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+
+  // Software pipeline: while tile k is multiplied out of LDS buffer k&1, tile k+1 sits in registers and the
+  // loads of tile k+2 are in flight.  Tile t always uses register set t&1 and LDS buffer t&1.
+  const int nk = (g.K + BK - 1) / BK;
+  load_tile(0, S0{});
+  if (nk > 1) load_tile(BK, S1{});
+  store_tile(0, S0{});
+  __syncthreads();
+  // steady state: every load and store of a trip is unconditional, so that the compiler's wait counters see
+  // exactly one register set in flight at each store; the last one to three tiles are peeled below
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {
+    load_tile((kt + 2) * BK, S0{});
+    __builtin_amdgcn_sched_barrier(0);          // keep the loads at the top of the phase: they need its whole length
+    compute_tile(0);
+    store_tile(1, S1{});
+    __syncthreads();
+    load_tile((kt + 3) * BK, S1{});
+    __builtin_amdgcn_sched_barrier(0);
+    compute_tile(1);
+    store_tile(0, S0{});
     __syncthreads();
   }
-
-  // ---- epilogue: row offsets of C once per tile (LDS is free now)
-  int64_t* c_off = (int64_t*)lds;
-  if (tid < BM) {
-    const int64_t r = m0 + tid;
-    int64_t off = 0;
-    if (r < g.M) {
-      if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; off = bi * g.c_batch_rows * (cm.mode == 1 ? cm.half : g.N) + (r - bi * g.c_batch_rows); }
-      else off = g.c_rows.identity ? r * g.c_rows.ld : eval_rows_k(&gk->c_rows, r);
+  const int left = nk - kt;                     // 1, 2 or 3 tiles: kt in LDS buffer 0, kt + 1 in register set 1
+  if (left == 3) load_tile((kt + 2) * BK, S0{});
+  compute_tile(0);
+  if (left >= 2) {
+    store_tile(1, S1{});
+    __syncthreads();
+    compute_tile(1);
+    if (left == 3) {
+      store_tile(0, S0{});
+      __syncthreads();
+      compute_tile(0);
     }
-    c_off[tid] = off;
   }
   __syncthreads();
-  const int n_out = cm.mode == 1 ? cm.half : g.N;
-  const int64_t col_stride = g.c_transposed ? g.c_batch_rows : 1;
+
+  // ---- epilogue
   T* C = (T*)g.C;
   const T* R = (const T*)g.residual;
   const T* bias = (const T*)g.bias;
-  const int span0 = n0 + wn * 64;                    // logical start of this wave's 64 columns
-  const int nl0 = span0 + l32, nl1 = span0 + 32 + l32;
-  const int pc0 = phys_col(cm, nl0), pc1 = phys_col(cm, nl1);
-  const bool ok0 = nl0 < g.N, ok1 = nl1 < g.N;
-  // column offsets: plain (n * stride) or through the column program of a store that splits the columns
-  int64_t co0 = pc0 * col_stride, co1 = pc1 * col_stride;
-  if (g.c_cols_on) { co0 = ok0 ? eval_rows_k(&gk->c_cols, pc0) : 0; co1 = ok1 ? eval_rows_k(&gk->c_cols, pc1) : 0; }
   const float b0 = (bias && ok0) ? Elem<T>::ld(bias + pc0) : 0.f;
   const float b1 = (bias && ok1) ? Elem<T>::ld(bias + pc1) : 0.f;
   const bool rope = EPI == EPI_ROPE && nl0 < cm.rope_cols;
@@ -237,7 +290,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
       }
     }
   }
-  (void)n_out;
 }
 
 template <typename T, int MI, int EPI, bool AGRAN>
@@ -245,7 +297,7 @@ static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   constexpr int BM = 64 * MI;
   const int tiles_n = (g.N + 127) / 128;
   const int64_t tiles_m = (g.M + BM - 1) / BM;
-  const size_t smem = 2 * (BM * 8 + 128 * 8) * sizeof(u32x4);
+  const size_t smem = 2 * (BM * 8 + 128 * 8) * sizeof(u32x4) + BM * sizeof(int64_t);
   static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return (int)attr;
   gemm_kernel<T, MI, EPI, AGRAN><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), smem, s>>>(g, cm, tiles_n);

@@ -35,64 +35,94 @@ __device__ __forceinline__ uint4 pack<bf16_t>(const float* f) {
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// One wave per logical row; lane l owns 16-byte chunks l, l+64, ...
-template <typename T, int MAXCH>
+// Each wave owns RPW consecutive logical rows; lane l owns 16-byte chunks l, l+64, ... of each.  All loads
+// of the wave's rows are issued before the first reduction, so several rows are in flight per lane.
+template <typename T, int MAXCH, int RPW>
 __global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
   constexpr int VEC = Elem<T>::VEC;
   typedef typename Vec16<T>::type V;
+  const SM_KARG NormArgs* ak = kernarg_ptr<NormArgs>();
   const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= a.rows) return;
+  const int64_t row0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
+  if (row0 >= a.rows) return;
   const int nchunk = a.C / VEC;
   const int seg_chunks = nchunk / a.nseg;
-  // segment base offsets: lane j < nseg evaluates segment j, then broadcast
-  int64_t my_seg = 0;
-  if (lane < a.nseg) my_seg = eval_rows(a.load, row * a.nseg + lane);
   const T* x = (const T*)a.x;
-  float v[MAXCH][VEC];
-  float sum = 0.f;
+  // row offsets first: the index programs are evaluated out of line, before any data register is live
+  int64_t seg_off[RPW], out_off[RPW];
 #pragma unroll
-  for (int i = 0; i < MAXCH; ++i) {
-    const int ch = lane + 64 * i;
-    const int seg = ch < nchunk ? ch / seg_chunks : 0;
-    const int64_t base = __shfl(my_seg, seg, 64);
-    if (ch < nchunk) {
-      V raw = *(const V*)(x + base + (int64_t)(ch - seg * seg_chunks) * VEC);
-      unpack<T>(raw, v[i]);
+  for (int r = 0; r < RPW; ++r) {
+    const int64_t row = min(row0 + r, a.rows - 1);          // a clamped duplicate row is computed and not stored
+    // segment base offsets: lane j < nseg evaluates segment j, broadcast below
+    if (a.load.identity) seg_off[r] = (row * a.nseg + min(lane, a.nseg - 1)) * a.load.ld;
+    else seg_off[r] = eval_rows_k(&ak->load, row * a.nseg + min(lane, a.nseg - 1));
+    out_off[r] = a.store.identity ? row * a.store.ld : eval_rows_k(&ak->store, row);
+  }
+  float v[RPW][MAXCH][VEC];
+  float sum[RPW];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) sum += v[i][e];
-    } else {
+  for (int r = 0; r < RPW; ++r) {
+    const int64_t my_seg = seg_off[r];
+    sum[r] = 0.f;
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) v[i][e] = 0.f;
+    for (int i = 0; i < MAXCH; ++i) {
+      const int ch = lane + 64 * i;
+      const int seg = ch < nchunk ? ch / seg_chunks : 0;
+      const int64_t base = __shfl(my_seg, seg, 64);
+      if (ch < nchunk) {
+        V raw = *(const V*)(x + base + (int64_t)(ch - seg * seg_chunks) * VEC);
+        unpack<T>(raw, v[r][i]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[r][i][e] = 0.f;
+      }
     }
   }
-  float mean = 0.f, ss = 0.f;
-  if (!a.rms) mean = wave_sum(sum) / (float)a.C;
+  float mean[RPW], rstd[RPW];
 #pragma unroll
-  for (int i = 0; i < MAXCH; ++i) {
-    if (lane + 64 * i < nchunk) {
+  for (int r = 0; r < RPW; ++r) {
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) { float dlt = v[i][e] - mean; ss += dlt * dlt; }
-    }
+    for (int i = 0; i < MAXCH; ++i)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sum[r] += v[r][i][e];
   }
-  const float rstd = rsqrtf(wave_sum(ss) / (float)a.C + a.eps);
-  const int64_t obase = eval_rows(a.store, row);
+#pragma unroll
+  for (int r = 0; r < RPW; ++r) mean[r] = a.rms ? 0.f : wave_sum(sum[r]) / (float)a.C;
+#pragma unroll
+  for (int r = 0; r < RPW; ++r) {
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXCH; ++i)
+      if (lane + 64 * i < nchunk) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { const float dlt = v[r][i][e] - mean[r]; ss += dlt * dlt; }
+      }
+    sum[r] = ss;
+  }
+#pragma unroll
+  for (int r = 0; r < RPW; ++r) rstd[r] = rsqrtf(wave_sum(sum[r]) / (float)a.C + a.eps);
   T* y = (T*)a.y;
   const T* g = (const T*)a.gamma;
   const T* bta = (const T*)a.beta;
 #pragma unroll
   for (int i = 0; i < MAXCH; ++i) {
     const int ch = lane + 64 * i;
-    if (ch < nchunk) {
-      float gg[VEC], bb[VEC], o[VEC];
-      unpack<T>(*(const V*)(g + ch * VEC), gg);
-      if (!a.rms && bta) unpack<T>(*(const V*)(bta + ch * VEC), bb);
-      else {
+    if (ch >= nchunk) continue;
+    float gg[VEC], bb[VEC];
+    unpack<T>(*(const V*)(g + ch * VEC), gg);
+    if (!a.rms && bta) unpack<T>(*(const V*)(bta + ch * VEC), bb);
+    else {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) bb[e] = 0.f;
-      }
+      for (int e = 0; e < VEC; ++e) bb[e] = 0.f;
+    }
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) o[e] = (v[i][e] - mean) * rstd * gg[e] + bb[e];
+    for (int r = 0; r < RPW; ++r) {
+      const int64_t row = row0 + r;
+      if (row >= a.rows) continue;
+      const int64_t obase = out_off[r];
+      float o[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o[e] = (v[r][i][e] - mean[r]) * rstd[r] * gg[e] + bb[e];
       *(V*)(y + obase + (int64_t)ch * VEC) = pack<T>(o);
     }
   }
@@ -102,11 +132,11 @@ template <typename T>
 static int norm_dispatch(const NormArgs& a, hipStream_t s) {
   constexpr int VEC = Elem<T>::VEC;
   const int nchunk = a.C / VEC;
-  dim3 grid((unsigned)((a.rows + 3) / 4)), block(256);
-  if (nchunk <= 64) norm_rows_kernel<T, 1><<<grid, block, 0, s>>>(a);
-  else if (nchunk <= 128) norm_rows_kernel<T, 2><<<grid, block, 0, s>>>(a);
-  else if (nchunk <= 256) norm_rows_kernel<T, 4><<<grid, block, 0, s>>>(a);
-  else norm_rows_kernel<T, 8><<<grid, block, 0, s>>>(a);
+  dim3 block(256);
+  if (nchunk <= 64) norm_rows_kernel<T, 1, 2><<<dim3((unsigned)((a.rows + 7) / 8)), block, 0, s>>>(a);
+  else if (nchunk <= 128) norm_rows_kernel<T, 2, 1><<<dim3((unsigned)((a.rows + 3) / 4)), block, 0, s>>>(a);
+  else if (nchunk <= 256) norm_rows_kernel<T, 4, 1><<<dim3((unsigned)((a.rows + 3) / 4)), block, 0, s>>>(a);
+  else norm_rows_kernel<T, 8, 1><<<dim3((unsigned)((a.rows + 3) / 4)), block, 0, s>>>(a);
   return (int)hipGetLastError();
 }
 
