@@ -49,8 +49,9 @@ __device__ __forceinline__ void eval_atoms(const ProgAtom* atoms, int n_atoms, c
       int id = a.t_atom[t];
       x += a.t_coef[t] * (id < 0 ? vars[~id] : val[id]);
     }
-    if (a.div > 1) x /= a.div;
-    if (a.mod > 0) x %= a.mod;
+    if (a.div > 1) x = (int)(__umulhi((unsigned)x, a.div_mul) >> a.div_sh);
+    if (a.mod > 1) x -= (int)(__umulhi((unsigned)x, a.mod_mul) >> a.mod_sh) * a.mod;
+    else if (a.mod == 1) x = 0;
     val[i] = x;
   }
 }
@@ -62,26 +63,31 @@ __device__ __forceinline__ void eval_atoms(const ProgAtom* atoms, int n_atoms, c
 template <typename Args>
 __device__ __forceinline__ const SM_KARG Args* kernarg_ptr() { return (const SM_KARG Args*)__builtin_amdgcn_kernarg_segment_ptr(); }
 
-// out of line: one copy per translation unit, called once per row outside the hot loops
-__device__ __noinline__ static int64_t eval_rows_k(const SM_KARG RowProg* p, int64_t r) {
+// Atom values live in a 16-wide register vector indexed by wave-uniform ids taken from the kernarg segment, so
+// the evaluation touches no scratch memory.
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ int64_t eval_rows_k(const SM_KARG RowProg* p, int64_t r) {
   if (p->identity) return r * p->ld;
-  int val[PROG_MAX_ATOMS];
+  i32x16 val = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   const int n = p->n_atoms;
   for (int i = 0; i < n; ++i) {
     const SM_KARG ProgAtom* a = &p->atoms[i];
     int x = a->c0;
-    for (int t = 0; t < a->nterm; ++t) {
+    const int nt = a->nterm;
+    for (int t = 0; t < nt; ++t) {
       const int id = a->t_atom[t];
-      x += a->t_coef[t] * (id < 0 ? (int)r : val[id]);
+      x += a->t_coef[t] * (id < 0 ? (int)r : val[id & 15]);
     }
-    if (a->div > 1) x /= a->div;
-    if (a->mod > 0) x %= a->mod;
-    val[i] = x;
+    if (a->div > 1) x = (int)(__umulhi((unsigned)x, a->div_mul) >> a->div_sh);
+    if (a->mod > 1) x -= (int)(__umulhi((unsigned)x, a->mod_mul) >> a->mod_sh) * a->mod;
+    else if (a->mod == 1) x = 0;
+    val[i & 15] = x;
   }
   int64_t off = p->c0;
-  for (int t = 0; t < p->nterm; ++t) {
+  const int nt = p->nterm;
+  for (int t = 0; t < nt; ++t) {
     const int id = p->t_atom[t];
-    off += p->t_coef[t] * (int64_t)(id < 0 ? (int)r : val[id]);
+    off += p->t_coef[t] * (int64_t)(id < 0 ? (int)r : val[id & 15]);
   }
   return off;
 }

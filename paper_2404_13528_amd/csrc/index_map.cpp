@@ -320,6 +320,17 @@ RowProg identity_rows(int64_t ld) {
   return p;
 }
 
+// Division by an invariant: for 0 <= x < 2^31 and d > 1, with l = ceil(log2 d) and m = ceil(2^(31+l) / d) < 2^32,
+// floor(x / d) == (x * m) >> (31 + l) == umulhi(x, m) >> (l - 1).
+static void magic(int64_t d, uint32_t* mul, uint32_t* sh) {
+  if (d <= 1) { *mul = 0; *sh = 0; return; }
+  int l = 0;
+  while ((int64_t(1) << l) < d) ++l;
+  const unsigned __int128 num = (unsigned __int128)1 << (31 + l);
+  *mul = (uint32_t)((num + d - 1) / d);
+  *sh = (uint32_t)(l - 1);
+}
+
 template <class P>
 static bool emit(const std::vector<Atom>& atoms, const Affine& offset, P* out, std::string* err) {
   // atoms are stored with arguments referring to earlier ids (intern order after prune)
@@ -343,6 +354,8 @@ static bool emit(const std::vector<Atom>& atoms, const Affine& offset, P* out, s
     if ((int)a.arg.terms.size() > PROG_MAX_TERMS) { *err = "index map too complex for a device program (terms)"; return false; }
     ProgAtom& p = out->atoms[n];
     p.div = (int32_t)a.div; p.mod = (int32_t)a.mod; p.c0 = (int32_t)a.arg.c0; p.nterm = (int)a.arg.terms.size();
+    magic(a.div, &p.div_mul, &p.div_sh);
+    magic(a.mod, &p.mod_mul, &p.mod_sh);
     if (a.div > INT32_MAX || a.mod > INT32_MAX || a.arg.c0 > INT32_MAX || affine_hi(atoms, a.arg) > INT32_MAX) { *err = "index exceeds 32 bits"; return false; }
     for (int t = 0; t < p.nterm; ++t) {
       p.t_atom[t] = slot[a.arg.terms[t].first];

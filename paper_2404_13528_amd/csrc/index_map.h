@@ -32,6 +32,7 @@ constexpr int PROG_MAX_TERMS = 6;
 constexpr int PROG_MAX_FINAL = 12;
 struct ProgAtom {
   int32_t div; int32_t mod; int32_t c0; int32_t nterm;   // value = (c0 + sum coef*term) / div % mod (mod 0: none)
+  uint32_t div_mul, div_sh, mod_mul, mod_sh;             // x / d == umulhi(x, mul) >> sh for 0 <= x < 2^31 (d > 1)
   int32_t t_atom[PROG_MAX_TERMS];      // >= 0: earlier atom; < 0: view variable ~t_atom
   int32_t t_coef[PROG_MAX_TERMS];
 };
