@@ -167,6 +167,159 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, con
     }
 }
 
+// Window attention, bf16, head size 32, at most 64 tokens per window: one wave per (window, head), the four
+// waves of a workgroup taking adjacent heads of one window so that their Q / K / V rows are adjacent in memory.
+// Everything a wave needs is requested up front (Q and K fragments, V rows, its head's column of the
+// relative-position table); V and the table go through LDS, from where the transposed V fragments and the bias
+// values are read; the bias index is a difference of a per-query and a per-key term, the shift mask a comparison
+// of two region ids, both prepared once per wave.
+typedef unsigned int au32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                            const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
+                                                            const bf16_t* __restrict__ table, long total_waves) {
+  __shared__ bf16_t v_lds[4][64 * 32];
+  __shared__ float t_lds[4][256];
+  __shared__ int k_lds[4][64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, hf = lane >> 5;
+  const long wid = (long)blockIdx.x * 4 + wave;
+  if (wid >= total_waves) return;                    // whole waves leave; no workgroup barrier is used below
+  const int hh = (int)(wid % a.heads);
+  const int b = (int)(wid / a.heads);
+  const bf16_t* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
+  const bf16_t* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
+  const bf16_t* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
+  bf16_t* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
+  const int w = a.window, n = a.nq, tw = 2 * w - 1;
+  const au32x4 zero = {0u, 0u, 0u, 0u};
+  // ---- all global loads first
+  au32x4 qf[2][2], kf[2][2], vrow[4];
+  unsigned short tv[4];
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int i = 32 * blk + l32, e = 16 * ks + 8 * hf;
+      const int ic = min(i, n - 1);
+      qf[blk][ks] = *(const au32x4*)(qp + (int64_t)ic * a.q_stride[2] + e);
+      kf[blk][ks] = *(const au32x4*)(kp + (int64_t)ic * a.k_stride[2] + e);
+      if (i >= n) { qf[blk][ks] = zero; kf[blk][ks] = zero; }
+    }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int c = lane + 64 * t, row = c >> 2, part = c & 3;
+    vrow[t] = *(const au32x4*)(vp + (int64_t)min(row, n - 1) * a.v_stride[2] + part * 8);
+    if (row >= n) vrow[t] = zero;                    // padded keys must contribute exact zeros
+    const int ti = lane + 64 * t;
+    tv[t] = ti < tw * tw ? table[ti * a.heads + hh] : (unsigned short)0;
+  }
+  // ---- per-wave LDS: V rows, table column as floats, per-key (bias term | region << 16)
+  const int nWx = a.W / w, nW = (a.H / w) * nWx, win = b % nW, wy = win / nWx, wx = win - wy * nWx;
+  const float inv_w = 1.0f / (float)w;
+  {
+    const int j = lane;
+    const int yj = (int)(((float)j + 0.5f) * inv_w), xj = j - yj * w;
+    int info = yj * tw + xj;
+    if (a.shift > 0) info |= (3 * region(wy * w + yj, a.H, w, a.shift) + region(wx * w + xj, a.W, w, a.shift)) << 16;
+    k_lds[wave][j] = info;
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int c = lane + 64 * t;
+    *(au32x4*)(&v_lds[wave][c * 8]) = vrow[t];
+    t_lds[wave][lane + 64 * t] = bf2f(tv[t]);
+  }
+  // per-query terms (the query of this lane in each query block)
+  int qa[2], rq[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int i = 32 * qb + l32;
+    const int yi = (int)(((float)i + 0.5f) * inv_w), xi = i - yi * w;
+    qa[qb] = yi * tw + xi + (w - 1) * 2 * w;
+    rq[qb] = a.shift > 0 ? 3 * region(wy * w + yi, a.H, w, a.shift) + region(wx * w + xi, a.W, w, a.shift) : 0;
+  }
+  // ---- S^T[kb][qb] = K_kb Q_qb^T
+  f32x16_t s[2][2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[kb][qb][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+        s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[kb][ks]), __builtin_bit_cast(bf16x8_t, qf[qb][ks]), s[kb][qb], 0, 0, 0);
+    }
+  __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0): this wave's LDS writes are done (wave-private data)
+  // ---- bias, mask, softmax per query
+  float mx[2] = {-INFINITY, -INFINITY};
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int j = 32 * kb + (i >> 2) * 8 + hf * 4 + (i & 3);
+      const int info = k_lds[wave][j];
+      const int kk = info & 0xffff, rk = info >> 16;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float x = s[kb][qb][i] * a.scale + t_lds[wave][(qa[qb] - kk) & 255];
+        if (rq[qb] != rk) x += -100.f;
+        if (j >= n) x = -INFINITY;
+        s[kb][qb][i] = x;
+        mx[qb] = fmaxf(mx[qb], x);
+      }
+    }
+  au32x4 pf[2][2][2];
+  float inv[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    mx[qb] = fmaxf(mx[qb], __shfl_xor(mx[qb], 32, 64));
+    float sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const bf16_t h0 = f2bf(__expf(s[kb][qb][i] - mx[qb])), h1 = f2bf(__expf(s[kb][qb][i + 1] - mx[qb]));
+        sum += bf2f(h0) + bf2f(h1);
+        pf[qb][kb][i >> 3][(i >> 1) & 3] = (unsigned)h0 | ((unsigned)h1 << 16);
+      }
+    sum += __shfl_xor(sum, 32, 64);
+    inv[qb] = 1.f / sum;
+  }
+  // ---- O^T[qb] = V^T P_qb^T; the V^T fragment of a key step is shared by both query blocks
+  f32x16_t oacc[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[qb][i] = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      au32x4 vf;
+#pragma unroll
+      for (int t = 0; t < 8; t += 2) {
+        const int ja = 32 * kb + (2 * ks2 + (t >> 2)) * 8 + hf * 4 + (t & 3);
+        const unsigned lo = v_lds[wave][ja * 32 + l32], hi = v_lds[wave][(ja + 1) * 32 + l32];
+        vf[t >> 1] = lo | (hi << 16);
+      }
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+        oacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf[qb][kb][ks2]), oacc[qb], 0, 0, 0);
+    }
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int i = 32 * qb + l32;
+    if (i >= n) continue;
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int e = g4 * 8 + hf * 4;
+      const unsigned w0 = (unsigned)f2bf(oacc[qb][4 * g4] * inv[qb]) | ((unsigned)f2bf(oacc[qb][4 * g4 + 1] * inv[qb]) << 16);
+      const unsigned w1 = (unsigned)f2bf(oacc[qb][4 * g4 + 2] * inv[qb]) | ((unsigned)f2bf(oacc[qb][4 * g4 + 3] * inv[qb]) << 16);
+      *(uint2*)(op + (int64_t)i * a.o_stride[2] + e) = make_uint2(w0, w1);
+    }
+  }
+}
+
 // fp32 window attention: nq, nk <= 64, d <= 64.  One workgroup of 64 threads
 // per (window, head); thread i owns query i.
 __global__ __launch_bounds__(64) void attn_window_f32_kernel(sm_attention_desc a, const float* __restrict__ q, const float* __restrict__ k,
@@ -218,6 +371,12 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
   if (d.dtype == SM_F32) {
     attn_window_f32_kernel<<<dim3((unsigned)(d.nb * d.heads)), dim3(64), 0, s>>>(d, (const float*)q, (const float*)k, (const float*)v,
                                                                                (float*)o, (const float*)rpb_table);
+    return (int)hipGetLastError();
+  }
+  if (d.kind == SM_ATT_WINDOW && d.d == 32 && d.nq <= 64 && d.window <= 8) {
+    const long pairs = (long)d.nb * d.heads;
+    attn_window32_kernel<<<dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                                (bf16_t*)o, (const bf16_t*)rpb_table, pairs);
     return (int)hipGetLastError();
   }
   const int n_qblk = (d.nq + 31) / 32;
