@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run an identity sm_gather_mapped copy of 256 MiB three times (counter calibration for rocprofv3 --pmc)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % a.gpus, file=sys.stderr)
@@ -96,6 +98,15 @@ def main():
         rep = sm.timing_report()
         sm.timing_enable(False)
         return rep
+
+    if a.calibrate_copy:
+        n = 128 * 1024 * 1024                         # bf16 elements: 256 MiB read + 256 MiB written per launch
+        src = torch.zeros(n, dtype=dtype, device="cuda")
+        ident = sm.Map.create((n // 1024, 1024), [])
+        for _ in range(3):
+            ident.gather(src.view(n // 1024, 1024), stream=stream)
+        torch.cuda.synchronize()
+        del src
 
     sec = {name: timed(c) for name, c in chains.items()}
     rep = {name: kernels(c) for name, c in chains.items()}

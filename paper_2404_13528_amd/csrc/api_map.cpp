@@ -56,24 +56,9 @@ extern "C" void sm_map_destroy(sm_map* m) { delete m; }
 namespace sm {
 // largest power-of-two vector (in elements, <= 16 bytes) the map moves as a whole
 int map_vector_width(const sm_map& m, int esize) {
-  const int rank = (int)m.shape.size();
-  int last_atom = -1;
-  for (size_t i = 0; i < m.atoms.size(); ++i)
-    if (m.atoms[i].kind == ATOM_VAR && m.atoms[i].var == rank - 1) last_atom = (int)i;
-  for (auto& a : m.atoms)
-    for (auto& t : a.arg.terms)
-      if (t.first == last_atom) return 1;
-  int64_t coef_last = 0;
-  for (auto& t : m.offset.terms) if (t.first == last_atom) coef_last = t.second;
-  if (coef_last != 1 && m.shape[rank - 1] != 1) return 1;
-  int v = 16 / esize;
-  while (v > 1) {
-    bool ok = m.shape[rank - 1] % v == 0 && m.offset.c0 % v == 0;
-    for (auto& t : m.offset.terms) if (t.first != last_atom && t.second % v != 0) ok = false;
-    if (ok) break;
-    v >>= 1;
-  }
-  return v;
+  for (int v = 16 / esize; v > 1; v >>= 1)
+    if (m.inner_contiguous(v)) return v;
+  return 1;
 }
 }  // namespace sm
 

@@ -92,6 +92,48 @@ __device__ __forceinline__ int64_t eval_rows_k(const SM_KARG RowProg* p, int64_t
   return off;
 }
 
+// Offset of one view element under a full map program (vars = view indices), register-resident like eval_rows_k.
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ int64_t eval_map_k(const SM_KARG MapProg* p, i32x8 vars) {
+  i32x16 val = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  const int n = p->n_atoms;
+  for (int i = 0; i < n; ++i) {
+    const SM_KARG ProgAtom* a = &p->atoms[i];
+    int x = a->c0;
+    const int nt = a->nterm;
+    for (int t = 0; t < nt; ++t) {
+      const int id = a->t_atom[t];
+      x += a->t_coef[t] * (id < 0 ? vars[(~id) & 7] : val[id & 15]);
+    }
+    if (a->div > 1) x = (int)(__umulhi((unsigned)x, a->div_mul) >> a->div_sh);
+    if (a->mod > 1) x -= (int)(__umulhi((unsigned)x, a->mod_mul) >> a->mod_sh) * a->mod;
+    else if (a->mod == 1) x = 0;
+    val[i & 15] = x;
+  }
+  int64_t off = p->c0;
+  const int nt = p->nterm;
+  for (int t = 0; t < nt; ++t) {
+    const int id = p->t_atom[t];
+    off += p->t_coef[t] * (int64_t)(id < 0 ? vars[(~id) & 7] : val[id & 15]);
+  }
+  return off;
+}
+
+// view multi-index of flat vector index o (last axis counted in vectors of `vec` elements)
+__device__ __forceinline__ i32x8 unflatten_k(const SM_KARG MapProg* p, int64_t o, int vec) {
+  i32x8 vars = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int rank = p->rank;
+  int64_t rem = o;
+  for (int k = rank - 1; k >= 0; --k) {
+    int ext = p->shape[k];
+    if (k == rank - 1) ext /= vec;
+    const int64_t qd = rem / ext;
+    vars[k & 7] = (int)(rem - qd * ext) * (k == rank - 1 ? vec : 1);
+    rem = qd;
+  }
+  return vars;
+}
+
 __device__ __forceinline__ int64_t eval_rows(const RowProg& p, int64_t r) {
   if (p.identity) return r * p.ld;
   int val[PROG_MAX_ATOMS];

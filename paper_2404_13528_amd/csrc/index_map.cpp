@@ -489,6 +489,34 @@ int64_t sm_map::at(const int64_t* idx) const {
   return off;
 }
 
+bool sm_map::inner_contiguous(int v) const {
+  if (v == 1) return true;
+  const int64_t last = shape.back();
+  if (last % v) return false;
+  sm_map tmp = *this;
+  sm_view_op rs; rs.kind = SM_VIEW_RESHAPE; rs.n = (int)shape.size() + 1;
+  if (rs.n > SM_MAX_RANK) return false;
+  for (size_t k = 0; k + 1 < shape.size(); ++k) rs.arg[k] = shape[k];
+  rs.arg[shape.size() - 1] = last / v; rs.arg[shape.size()] = v;
+  int made = 0; std::string err;
+  if (!apply_view(tmp.shape, tmp.atoms, tmp.offset, rs, true, &made, &err)) return false;
+  prune(&tmp);
+  const int inner = (int)tmp.shape.size() - 1;
+  int inner_atom = -1;
+  for (size_t i = 0; i < tmp.atoms.size(); ++i)
+    if (tmp.atoms[i].kind == ATOM_VAR && tmp.atoms[i].var == inner) inner_atom = (int)i;
+  if (inner_atom < 0) return false;
+  for (auto& a : tmp.atoms)
+    for (auto& t : a.arg.terms) if (t.first == inner_atom) return false;
+  if (tmp.offset.c0 % v) return false;
+  bool unit = false;
+  for (auto& t : tmp.offset.terms) {
+    if (t.first == inner_atom) unit = t.second == 1;
+    else if (t.second % v) return false;
+  }
+  return unit;
+}
+
 bool sm_map::affine(int64_t* base, int64_t* strides) const {
   if (n_divmod() != 0) return false;
   for (size_t k = 0; k < SM_MAX_RANK; ++k) strides[k] = 0;

@@ -77,6 +77,9 @@ struct sm_map {
   void eval(int64_t* offsets) const;
   int64_t at(const int64_t* idx) const;       // offset of one view element
   bool affine(int64_t* base, int64_t* strides) const;
+  // true if every aligned group of v consecutive elements of the last view axis is contiguous in the source
+  // and starts at an offset that is a multiple of v
+  bool inner_contiguous(int v) const;
 };
 
 namespace sm {

@@ -13,22 +13,8 @@ template <typename V>
 __global__ __launch_bounds__(256) void gather_kernel(MapProg p, int64_t nvec, int vec, const V* __restrict__ src, V* __restrict__ dst) {
   int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (o >= nvec) return;
-  int vars[SM_MAX_RANK];
-  int64_t rem = o;
-  for (int k = p.rank - 1; k >= 0; --k) {
-    int ext = p.shape[k];
-    if (k == p.rank - 1) ext /= vec;
-    vars[k] = (int)(rem % ext);
-    rem /= ext;
-  }
-  vars[p.rank - 1] *= vec;
-  int val[PROG_MAX_ATOMS];
-  eval_atoms<SM_MAX_RANK>(p.atoms, p.n_atoms, vars, val);
-  int64_t off = p.c0;
-  for (int t = 0; t < p.nterm; ++t) {
-    int id = p.t_atom[t];
-    off += p.t_coef[t] * (int64_t)(id < 0 ? vars[~id] : val[id]);
-  }
+  const SM_KARG MapProg* pk = kernarg_ptr<MapProg>();        // p is the first argument
+  const int64_t off = eval_map_k(pk, unflatten_k(pk, o, vec));
   dst[o] = src[off / vec];
 }
 
@@ -37,22 +23,8 @@ template <typename T, int VEC>
 __global__ __launch_bounds__(256) void gather_add_kernel(MapProg p, int64_t nvec, const T* __restrict__ src, const T* __restrict__ addend, T* __restrict__ dst) {
   int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (o >= nvec) return;
-  int vars[SM_MAX_RANK];
-  int64_t rem = o;
-  for (int k = p.rank - 1; k >= 0; --k) {
-    int ext = p.shape[k];
-    if (k == p.rank - 1) ext /= VEC;
-    vars[k] = (int)(rem % ext);
-    rem /= ext;
-  }
-  vars[p.rank - 1] *= VEC;
-  int val[PROG_MAX_ATOMS];
-  eval_atoms<SM_MAX_RANK>(p.atoms, p.n_atoms, vars, val);
-  int64_t off = p.c0;
-  for (int t = 0; t < p.nterm; ++t) {
-    int id = p.t_atom[t];
-    off += p.t_coef[t] * (int64_t)(id < 0 ? vars[~id] : val[id]);
-  }
+  const SM_KARG MapProg* pk = kernarg_ptr<MapProg>();        // p is the first argument
+  const int64_t off = eval_map_k(pk, unflatten_k(pk, o, VEC));
   struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
   const Pack a = *(const Pack*)(src + off), b = *(const Pack*)(addend + o * VEC);
   Pack r;

@@ -81,9 +81,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous range of
   // tiles (column tiles fastest) so that the tiles sharing an A row panel share one L2.
   const int n_tiles = gridDim.x;
-  const int per_xcd = (n_tiles + 7) >> 3;
-  int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if ((n_tiles & 7) != 0) tile_id = blockIdx.x;              // ragged grids keep the plain order
+  const int xcd = blockIdx.x & 7, q8 = n_tiles >> 3, r8 = n_tiles & 7;
+  const int tile_id = xcd * q8 + min(xcd, r8) + (blockIdx.x >> 3);    // XCD x owns q8 (+1 if x < r8) consecutive tiles
   const int tile_m = tile_id / tiles_n, tile_n = tile_id - tile_m * tiles_n;
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
