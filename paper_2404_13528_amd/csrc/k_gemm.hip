@@ -68,11 +68,13 @@ enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
 // (global_load_lds_dwordx4, no staging registers), one tile ahead of the MFMAs; the fragment reads are
 // written as inline ds_read_b128 with explicit lgkmcnt waits and double-buffered registers, so that the
 // LDS latency of step j+1 hides behind the MFMAs of step j.
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int tiles_n) {
+// WM = waves along M (2 or 4): the workgroup has 2 * WM waves and a tile of 32 * MI * WM rows.  The 8-wave shape
+// (256 x 128) halves the L2 -> LDS traffic per flop of the 4-wave one and is used where the grid is large enough.
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM>
+__global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, int tiles_n) {
   const SM_KARG GemmArgs* gk = kernarg_ptr<GemmArgs>();      // g is the first argument
   constexpr int VEC = Elem<T>::VEC;
-  constexpr int BM = 64 * MI, BN = 128, BK = 8 * VEC;
+  constexpr int BM = 32 * MI * WM, BN = 128, BK = 8 * VEC, NT = 128 * WM;
   constexpr int A_SLOTS = BM * 8, B_SLOTS = BN * 8;
   extern __shared__ u32x4 lds[];                     // [2][A_SLOTS + B_SLOTS]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   if constexpr (DMA) {
     // wave-load i of this wave fills rows g8*8 .. g8*8+7 of a tile (1 KiB, 64 consecutive 16-byte slots):
     // lane -> (row, slot position); the chunk that belongs in that slot is position ^ (row & 7)
-    constexpr int LA = BM / 32, LB = 4, STAGE = A_SLOTS + B_SLOTS;
+    constexpr int LA = 2 * MI, LB = 8 / WM, STAGE = A_SLOTS + B_SLOTS;     // wave-loads per wave per stage
     const int lrow = lane >> 3, lpos = lane & 7;
     const T* a_src[LA];
     const T* b_src[LB];
@@ -400,7 +402,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
     constexpr int CPR = TW / VEC;                      // 16-byte pieces per row
     const int n_out = EPI == EPI_GLU ? cm.half : g.N;
     const int c_base = EPI == EPI_GLU ? n0 / 2 : n0;
-    for (int p = tid; p < BM * CPR; p += 256) {
+    for (int p = tid; p < BM * CPR; p += NT) {
       const int rl = p / CPR, cl = (p - rl * CPR) * VEC;
       const int64_t r = m0 + rl;
       const int col = c_base + cl;
@@ -440,23 +442,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g, ColMap cm, int ti
   }
 }
 
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA>
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM = 2>
 static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
-  constexpr int BM = 64 * MI;
+  constexpr int BM = 32 * MI * WM;
   const int tiles_n = (g.N + 127) / 128;
   const int64_t tiles_m = (g.M + BM - 1) / BM;
   const size_t tiles = 2 * (BM * 8 + 128 * 8) * sizeof(u32x4), stage = (size_t)BM * 132 * sizeof(float);
   const size_t smem = (tiles > stage ? tiles : stage) + BM * sizeof(int64_t);
-  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return (int)attr;
-  gemm_kernel<T, MI, EPI, AGRAN, DMA><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), smem, s>>>(g, cm, tiles_n);
+  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, tiles_n);
   return (int)hipGetLastError();
 }
 
 template <typename T, int MI, int EPI, bool AGRAN>
 static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   if constexpr (sizeof(T) == 2 && !AGRAN) {
-    if (g.K % 64 == 0) return gemm_launch2<T, MI, EPI, false, true>(g, cm, s);
+    if (g.K % 64 == 0) {
+      if constexpr (MI == 2) {
+        // 256 x 128 tiles when they fill the chip (one 8-wave workgroup per CU) about as well as the smaller ones
+        const int64_t t256 = ((g.M + 255) / 256) * ((g.N + 127) / 128);
+        const int64_t rounds = (t256 + 255) / 256;
+        if (t256 >= 200 && (double)t256 / (double)(rounds * 256) >= 0.8) return gemm_launch2<T, 2, EPI, false, true, 4>(g, cm, s);
+      }
+      return gemm_launch2<T, MI, EPI, false, true>(g, cm, s);
+    }
   }
   return gemm_launch2<T, MI, EPI, AGRAN, false>(g, cm, s);
 }
