@@ -24,6 +24,10 @@ namespace sm {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
+typedef unsigned int au32x4 __attribute__((ext_vector_type(4)));
+#define SM_GPTR_(p) ((const __attribute__((address_space(1))) void*)(p))
+#define SM_LPTR_(p) ((__attribute__((address_space(3))) void*)(p))
+
 struct WinGeom { int w, shift, H, W, nWx, nW, wy, wx; };
 
 __device__ __forceinline__ int region(int c, int extent, int w, int s) { return c < extent - w ? 0 : (c < extent - s ? 1 : 2); }
@@ -167,13 +171,186 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, con
     }
 }
 
+// Global attention (full or causal), bf16: a workgroup of four waves owns 128 consecutive queries of one
+// (batch, head), 32 per wave, and walks the keys in tiles of 64.  A K tile and a V tile go from global memory
+// straight into LDS (16-byte LDS-DMA loads, two stages: tile t+1 is in flight while tile t is consumed), each
+// read from HBM / L2 once per workgroup instead of once per wave.  Rows sit in LDS at a pitch of an odd number
+// of 16-byte chunks, which spreads both access patterns over all banks: the K fragments (one row per lane,
+// ds_read_b128) and the V^T fragments, which the transposing LDS read (ds_read_b64_tr_b16: within 16 lanes,
+// lane i receives element i % 4 of the 8 bytes addressed by lanes i / 4 + 4 j, j = 0..3) delivers directly in
+// the operand layout of the second MFMA.  The softmax runs in the exp2 domain with the scale folded into one
+// FMA per score, masks are applied only in tiles that cross the diagonal or the end of the keys, and the
+// running output is rescaled only when some row maximum of the wave actually moved.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+template <int DK, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                            const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh) {
+  constexpr int DB = (DK + 1) / 2;           // 32-wide output column blocks
+  constexpr int P = 2 * DK + 1;              // row pitch in 16-byte chunks
+  constexpr int TILE = 64 * P;               // chunks per operand tile
+  extern __shared__ au32x4 fl_lds[];         // [2 stages][K, V][TILE]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  // (batch, head) fastest: the workgroups that share K and V follow each other at a distance of nbh, which
+  // keeps them on one XCD (one L2) whenever nbh is a multiple of 8.  Causal: the first half of the ranks takes
+  // the long query tiles in descending order and the second half the short ones in ascending order, so that
+  // co-resident workgroups of ranks r and r + n_qt / 2 carry about the same total work.
+  const int bh = blockIdx.x % nbh, rank = blockIdx.x / nbh;
+  int qt = rank;
+  if (CAUSAL) { const int hq = (n_qt + 1) >> 1; qt = rank < hq ? n_qt - 1 - rank : rank - hq; }
+  const int hh = bh % a.heads, b = bh / a.heads;
+  const bf16_t* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
+  const bf16_t* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
+  const bf16_t* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
+  bf16_t* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
+  const int Q0 = qt * 128, q0 = Q0 + wave * 32, qi = q0 + l32;
+  const int chv = a.d >> 3;                  // valid chunks per row
+
+  // loader: wave-load i covers chunks [64 i, 64 i + 64) of a tile; wave w issues loads w, w + 4, ...
+  constexpr int NLW = (P + 3) / 4;
+  int ld_row[NLW], ld_col[NLW];
+#pragma unroll
+  for (int i = 0; i < NLW; ++i) {
+    const int s = (wave + 4 * i) * 64 + lane;
+    ld_row[i] = s / P;
+    ld_col[i] = min(s - ld_row[i] * P, chv - 1) * 8;      // pad chunks repeat the last valid one (finite data)
+  }
+  auto issue = [&](int kt) {
+    au32x4* st = fl_lds + (kt & 1) * 2 * TILE;
+#pragma unroll
+    for (int i = 0; i < NLW; ++i) {
+      if (wave + 4 * i < P) {                // wave-uniform
+        const int64_t key = min(kt * 64 + ld_row[i], a.nk - 1);    // rows past the end repeat the last key (masked below)
+        __builtin_amdgcn_global_load_lds(SM_GPTR_(kp + key * a.k_stride[2] + ld_col[i]), SM_LPTR_(st + (wave + 4 * i) * 64), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(SM_GPTR_(vp + key * a.v_stride[2] + ld_col[i]), SM_LPTR_(st + TILE + (wave + 4 * i) * 64), 16, 0, 0);
+      }
+    }
+  };
+
+  int n_kt = (a.nk + 63) >> 6;
+  if (CAUSAL) n_kt = min(n_kt, (min(Q0 + 127, a.nq - 1) >> 6) + 1);
+  issue(0);
+
+  const au32x4 zero = {0u, 0u, 0u, 0u};
+  au32x4 qf[DK];
+  {
+    const bf16_t* qrow = qp + (int64_t)min(qi, a.nq - 1) * a.q_stride[2];
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      const int e = 16 * ks + 8 * hf;
+      qf[ks] = *(const au32x4*)(qrow + min(e, a.d - 8));
+      if (e >= a.d) qf[ks] = zero;           // zero columns past the head size: they cancel the K tile's pad chunks
+    }
+  }
+  f32x16_t oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;      // l_run: this lane's half of the row sum
+  const float sc = a.scale * 1.4426950408889634f;
+  // per-lane LDS offsets (bytes): K fragment row l32, chunk hf; V^T fragment rows 4 hf + j, columns 16 eb + 4 aa
+  const unsigned k_lane = (unsigned)(l32 * P + hf) * 16u;
+  const unsigned v_lane = (unsigned)((4 * hf + ((lane & 15) >> 2)) * P * 16 + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+
+  for (int kt = 0; kt < n_kt; ++kt) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0): this wave's part of tile kt is in LDS
+    __builtin_amdgcn_s_barrier();            // ... and everybody's; the other stage is no longer read
+    if (kt + 1 < n_kt) issue(kt + 1);
+    const int j0 = kt * 64;
+    if (CAUSAL && j0 > q0 + 31) continue;    // wave-uniform: every key of the tile lies after every query of the wave
+    const char* kt_l = (const char*)(fl_lds + (kt & 1) * 2 * TILE);
+    const char* vt_l = kt_l + TILE * 16;
+    f32x16_t s[2];
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[jb][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < DK; ++ks) {
+        const au32x4 kf = *(const au32x4*)(kt_l + k_lane + (32 * jb * P + 2 * ks) * 16);
+        s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[ks]), s[jb], 0, 0, 0);
+      }
+    }
+    const bool masked = (CAUSAL && j0 + 63 > q0) || j0 + 64 > a.nk;      // wave-uniform
+    float bm = -INFINITY;
+    if (masked) {
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = j0 + 32 * jb + (i >> 2) * 8 + hf * 4 + (i & 3);
+          if (j >= a.nk || (CAUSAL && j > qi)) s[jb][i] = -INFINITY;
+          bm = fmaxf(bm, s[jb][i]);
+        }
+    } else {
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) bm = fmaxf(bm, s[jb][i]);
+    }
+    bm = fmaxf(bm, __shfl_xor(bm, 32, 64)) * sc;        // sc > 0: scaling commutes with the maximum
+    const float m_new = fmaxf(m_run, bm);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);          // m_run = -inf gives 0
+    const bool moved = m_new != m_run;
+    m_run = m_new;
+    float rs = 0.f;
+    au32x4 pf[2][2];
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[jb][i], sc, -m_use)), p1 = __builtin_amdgcn_exp2f(fmaf(s[jb][i + 1], sc, -m_use));
+        rs += p0 + p1;
+        const f32x2_t pp = {p0, p1};
+        pf[jb][i >> 3][(i >> 1) & 3] = __builtin_bit_cast(unsigned, __builtin_convertvector(pp, bf16x2_t));
+      }
+    l_run = l_run * alpha + rs;
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+    }
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const char* base = vt_l + v_lane + ((32 * jb + 16 * ks2) * P * 16 + 64 * db);
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(base));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(base + 8 * P * 16));
+          const s16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf[jb][ks2]), oacc[db], 0, 0, 0);
+        }
+  }
+  if (qi >= a.nq) return;
+  l_run += __shfl_xor(l_run, 32, 64);
+  const float inv = 1.f / l_run;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int e = 32 * db + g4 * 8 + hf * 4;
+      if (e < a.d) {
+        const f32x2_t x0 = {oacc[db][4 * g4] * inv, oacc[db][4 * g4 + 1] * inv}, x1 = {oacc[db][4 * g4 + 2] * inv, oacc[db][4 * g4 + 3] * inv};
+        *(uint2*)(op + (int64_t)qi * a.o_stride[2] + e) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
+                                                                    __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
+      }
+    }
+}
+
 // Window attention, bf16, head size 32, at most 64 tokens per window: one wave per (window, head), the four
 // waves of a workgroup taking adjacent heads of one window so that their Q / K / V rows are adjacent in memory.
 // Everything a wave needs is requested up front (Q and K fragments, V rows, its head's column of the
 // relative-position table); V and the table go through LDS, from where the transposed V fragments and the bias
 // values are read; the bias index is a difference of a per-query and a per-key term, the shift mask a comparison
 // of two region ids, both prepared once per wave.
-typedef unsigned int au32x4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                             const bf16_t* __restrict__ table, long total_waves) {
@@ -377,6 +554,26 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     const long pairs = (long)d.nb * d.heads;
     attn_window32_kernel<<<dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
                                                                                 (bf16_t*)o, (const bf16_t*)rpb_table, pairs);
+    return (int)hipGetLastError();
+  }
+  if (d.kind != SM_ATT_WINDOW && d.scale > 0.f) {
+    const int n_qt = (d.nq + 127) / 128, nbh = d.nb * d.heads, dk = (d.d + 15) / 16;
+    const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
+    bf16_t* oo = (bf16_t*)o;
+    const dim3 grid((unsigned)((long)n_qt * nbh)), block(256);
+#define FLASH(DK_) do { \
+      const size_t smem = 4 * 64 * (2 * DK_ + 1) * 16 + 64;      /* + one chunk: the last V^T read of an odd DK_ runs past its row */ \
+      static const hipError_t attr_f = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+      static const hipError_t attr_c = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+      if (attr_f != hipSuccess || attr_c != hipSuccess) return (int)(attr_f != hipSuccess ? attr_f : attr_c); \
+      if (d.kind == SM_ATT_CAUSAL) attn_flash_kernel<DK_, true><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); \
+      else attn_flash_kernel<DK_, false><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); } while (0)
+    if (dk <= 2) FLASH(2);
+    else if (dk == 3) FLASH(3);
+    else if (dk == 4) FLASH(4);
+    else if (dk <= 6) FLASH(6);
+    else FLASH(8);
+#undef FLASH
     return (int)hipGetLastError();
   }
   const int n_qblk = (d.nq + 31) / 32;
