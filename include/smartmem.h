@@ -300,6 +300,11 @@ int sm_last_launch_counts(int* n_compute, int* n_copy);
 int sm_timing_enable(int on);
 int sm_timing_report(char* buf, int n);
 
+/* Tuning hook for benchmarks: overrides the tile and pipeline choice of the bf16 Linear kernel for the calling
+ * process.  tile_rows: 0 (automatic), 64, 128 or 256 output rows per workgroup; stages: 0 (automatic) or 2..4
+ * K-tiles resident in LDS.  Returns SM_ERR_INVALID_ARG for other values.  Results do not depend on the choice. */
+int sm_gemm_tuning(int tile_rows, int stages);
+
 #ifdef __cplusplus
 }
 #endif

@@ -382,6 +382,11 @@ class SwinChain:
         return (y, feat) if want_feat else y
 
 
+def gemm_tuning(tile_rows=0, stages=0):
+    """Overrides the bf16 Linear kernel's tile height (64 / 128 / 256) and LDS stage count (2..4); 0 = automatic."""
+    check(lib().sm_gemm_tuning(int(tile_rows), int(stages)), "sm_gemm_tuning")
+
+
 def timing_enable(on=True):
     check(lib().sm_timing_enable(1 if on else 0), "sm_timing_enable")
 

@@ -54,7 +54,8 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
       return fail(SM_ERR_SHAPE, "%s: RoPE needs head size a multiple of 64 and whole heads", who);
   }
   if (g.c_transposed && (g.c_batch_rows < 1 || g.M % g.c_batch_rows)) return fail(SM_ERR_SHAPE, "%s: bad transposed-store batch", who);
-  if (!aligned16(g.A) || !aligned16(g.W) || !aligned16(g.C)) return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  if (!aligned16(g.A) || !aligned16(g.W) || !aligned16(g.C) || (g.bias && !aligned16(g.bias)) || (g.residual && !aligned16(g.residual)))
+    return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
   if ((int64_t)g.N * g.ldw > INT32_MAX * 16LL) return fail(SM_ERR_UNSUPPORTED, "%s: weight too large", who);
   char label[128];
   snprintf(label, sizeof(label), "gemm_%s[%lld,%d,%d]%s%s%s", g.dtype == SM_F32 ? "f32" : "bf16", (long long)g.M, g.N, g.K,
@@ -149,7 +150,13 @@ extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, 
   if (rc == SM_ERR_UNSUPPORTED && c_map) {
     // the store splits the column dimension (e.g. into heads): separable row + column programs
     std::string err;
-    if (!c_map->compile_rows_cols(1, &g.c_rows, &g.c_cols, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_linear(C): %s", err.c_str());
+    // (in granules of one 16-byte vector when the split keeps them whole, else per element)
+    const int vec = d->dtype == SM_F32 ? 4 : 8;
+    g.c_gran = vec;
+    if (!c_map->compile_rows_cols(vec, &g.c_rows, &g.c_cols, &err)) {
+      g.c_gran = 1;
+      if (!c_map->compile_rows_cols(1, &g.c_rows, &g.c_cols, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_linear(C): %s", err.c_str());
+    }
     g.c_cols_on = 1;
     rc = SM_OK;
   }
@@ -161,4 +168,9 @@ extern "C" int sm_attention(const sm_attention_desc* d, const void* q, const voi
                             const void* rpb_table, void* stream) {
   if (!d) return fail(SM_ERR_INVALID_ARG, "sm_attention: null descriptor");
   return attention_checked(*d, q, k, v, o, rpb_table, stream, "sm_attention");
+}
+
+extern "C" int sm_gemm_tuning(int tile_rows, int stages) {
+  if (sm::gemm_tuning(tile_rows, stages)) return sm::fail(SM_ERR_INVALID_ARG, "sm_gemm_tuning: tile_rows must be 0, 64, 128 or 256 and stages 0 or 2..4");
+  return SM_OK;
 }

@@ -28,7 +28,7 @@ struct Copy { MapProg prog; int64_t numel; int vec; };
 struct AttnPlan {
   View4 q1, k1, v1, o1;        // self attention operands as [B, h, S, d] views of their stored tensors
   View4 q2, k2, v2, o2;        // cross attention (SD)
-  bool q2_scatter; RowProg q2_rows, q2_cols;     // cross attention: q's Linear stores head-major when the planner says so
+  bool q2_scatter; int q2_gran; RowProg q2_rows, q2_cols;     // cross attention: q's Linear stores head-major when the planner says so
   Copy split_qkv, merge_o, to_tokens, split_q2, split_kv2, merge_o2, to_nchw;
   int n_kept, n_layout, n_eliminated;
 };
@@ -185,7 +185,11 @@ std::shared_ptr<AttnPlan> attn_plan(const sm_attn_cfg& c, std::string* err) {
     // index of the cross attention's q Linear: the MatMul named "q"
     sm_plan_store_map(plan, g.find("q"), &qm, nullptr);
     if (qm) {
-      if (!qm->compile_rows_cols(1, &p->q2_rows, &p->q2_cols, err)) return nullptr;
+      p->q2_gran = c.dtype == SM_F32 ? 4 : 8;       // whole 16-byte vectors when the head size allows, else per element
+      if (!qm->compile_rows_cols(p->q2_gran, &p->q2_rows, &p->q2_cols, err)) {
+        p->q2_gran = 1;
+        if (!qm->compile_rows_cols(1, &p->q2_rows, &p->q2_cols, err)) return nullptr;
+      }
       p->q2_scatter = true;
     }
     // GroupNorm must have been told to store token-major (its consumer reduces over C), proj_out to store NCHW
@@ -363,7 +367,7 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
     GemmArgs gq; std::memset(&gq, 0, sizeof(gq));
     gq.A = n; gq.W = w[11]; gq.C = qkv; gq.M = T; gq.N = E; gq.K = E; gq.dtype = dt; gq.ldw = E;
     gq.a_rows = identity_rows(E); gq.c_rows = identity_rows(E);
-    if (el && plan->q2_scatter) { gq.c_rows = plan->q2_rows; gq.c_cols = plan->q2_cols; gq.c_cols_on = 1; }
+    if (el && plan->q2_scatter) { gq.c_rows = plan->q2_rows; gq.c_cols = plan->q2_cols; gq.c_cols_on = 1; gq.c_gran = plan->q2_gran; }
     if ((rc = gemm_checked(gq, stream, "linear"))) return rc;
   }
   if ((rc = gemm(context, w[12], nullptr, nullptr, kv, (int64_t)B * Sc, 2 * E, c->Dc, dt, SM_ACT_NONE, stream))) return rc;

@@ -16,6 +16,7 @@
 // logical column order of a wave's 64-column span (which W row feeds which
 // MFMA block), so that the two partners sit in the same lane: the Slice /
 // chunk operators of SwiGLU / GEGLU and the half-split of RoPE cost nothing.
+#include <algorithm>
 #include <type_traits>
 #include "device_common.h"
 #include "kernels.h"
@@ -26,6 +27,8 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 struct ColMap {      // logical column n' -> physical W row / output column
   int mode;          // 0 identity, 1 gated halves, 2 rope
@@ -64,19 +67,24 @@ enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
 #define SM_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define SM_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+// The product is formed transposed, C^T = W A^T (the W fragment is the first MFMA operand), so that a lane ends up
+// owning ONE output row and runs of four consecutive columns: after one v_permlane32_swap per value pair a lane
+// holds eight consecutive bf16 columns, and bias, activation, RoPE, residual add and the 16-byte stores all happen
+// in registers: the epilogue needs neither LDS nor a barrier, and LDS holds nothing but K-tile stages.
+//
 // DMA = true (bf16, K a multiple of 64): the K-tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4, no staging registers), one tile ahead of the MFMAs; the fragment reads are
+// (global_load_lds_dwordx4, no staging registers), NS - 1 tiles ahead of the MFMAs; the fragment reads are
 // written as inline ds_read_b128 with explicit lgkmcnt waits and double-buffered registers, so that the
 // LDS latency of step j+1 hides behind the MFMAs of step j.
 // WM = waves along M (2 or 4): the workgroup has 2 * WM waves and a tile of 32 * MI * WM rows.  The 8-wave shape
 // (256 x 128) halves the L2 -> LDS traffic per flop of the 4-wave one and is used where the grid is large enough.
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM>
-__global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, int tiles_n) {
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM, int NS>
+__global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm, int tiles_n) {
   const SM_KARG GemmArgs* gk = kernarg_ptr<GemmArgs>();      // g is the first argument
   constexpr int VEC = Elem<T>::VEC;
-  constexpr int BM = 32 * MI * WM, BN = 128, BK = 8 * VEC, NT = 128 * WM;
+  constexpr int BM = 32 * MI * WM, BN = 128, BK = 8 * VEC;
   constexpr int A_SLOTS = BM * 8, B_SLOTS = BN * 8;
-  extern __shared__ u32x4 lds[];                     // [2][A_SLOTS + B_SLOTS]
+  extern __shared__ u32x4 lds[];                     // [stages][A_SLOTS + B_SLOTS]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, hf = lane >> 5;
@@ -90,46 +98,30 @@ __global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, i
   const int n0 = tile_n * BN;
   const T* A = (const T*)g.A;
   const T* W = (const T*)g.W;
-
-  // loader assignment: chunk c of rows lr + 32*i
-  const int lc = tid & 7, lr = tid >> 3;
-  const T* a_ptr[2 * MI];
-  bool a_ok[2 * MI];
-#pragma unroll
-  for (int i = 0; i < 2 * MI; ++i) {
-    // rows past M are clamped to the last row: their products land in output rows that are never stored
-    const int64_t r = min(m0 + lr + 32 * i, g.M - 1);
-    a_ok[i] = true;
-    a_ptr[i] = A + (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) + lc * VEC;
-  }
-  const T* b_ptr[4];
-  bool b_ok[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int n = min(n0 + lr + 32 * i, g.N - 1);          // clamped like the rows of A
-    b_ok[i] = true;
-    b_ptr[i] = W + (int64_t)phys_col(cm, n) * g.ldw + lc * VEC;
-  }
-
-  // row (and column) offsets of C: evaluated here, before the accumulators are live, into LDS behind the tiles
-  constexpr int TILE_BYTES = 2 * (A_SLOTS + B_SLOTS) * 16, STAGE_BYTES = BM * 132 * 4;
-  int64_t* c_off = (int64_t*)((char*)lds + (TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES));
-  if (tid < BM) {
-    const int64_t r = m0 + tid;
-    int64_t off = 0;
-    if (r < g.M) {
-      if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; off = bi * g.c_batch_rows * (cm.mode == 1 ? cm.half : g.N) + (r - bi * g.c_batch_rows); }
-      else off = g.c_rows.identity ? r * g.c_rows.ld : eval_rows_k(&gk->c_rows, r);
-    }
-    c_off[tid] = off;
-  }
   const int span0 = n0 + wn * 64;                    // logical start of this wave's 64 columns
-  const int nl0 = span0 + l32, nl1 = span0 + 32 + l32;
-  const int pc0 = phys_col(cm, nl0), pc1 = phys_col(cm, nl1);
-  const bool ok0 = nl0 < g.N, ok1 = nl1 < g.N;
-  const int64_t col_stride = g.c_transposed ? g.c_batch_rows : 1;
-  int64_t co0 = pc0 * col_stride, co1 = pc1 * col_stride;
-  if (g.c_cols_on) { co0 = ok0 ? eval_rows_k(&gk->c_cols, pc0) : 0; co1 = ok1 ? eval_rows_k(&gk->c_cols, pc1) : 0; }
+  const int pcb[2] = {phys_col(cm, span0), phys_col(cm, span0 + 32)};      // W row / bias index of a block's first column
+  // The bias words of this lane's columns (runs of four: 8 or 16 bytes each) are requested first of all, so that
+  // they are older than every K-tile load (the tile waits below count loads in issue order) and long since there
+  // when the epilogue unpacks them.
+  constexpr int BW = VEC == 8 ? 2 : 4;
+  unsigned braw[2][4][BW];
+  {
+    // unconditional loads (no select on the loaded words, which would make the prologue wait for them): without a
+    // bias, or where a run is cut by the end of the columns, a valid address is read and the words are not used
+    const bool bias_vec = g.bias && g.N >= 4;
+    const T* bp = bias_vec ? (const T*)g.bias : W;
+    const int pmax = bias_vec ? ((g.N - 4) & ~3) : 0;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int pc = min(pcb[ni] + g4 * 8 + hf * 4, pmax);
+        if constexpr (VEC == 8) { const u32x2 b2 = *(const u32x2*)(bp + pc); braw[ni][g4][0] = b2.x; braw[ni][g4][1] = b2.y; }
+        else { const u32x4 b4 = *(const u32x4*)(bp + pc); braw[ni][g4][0] = b4.x; braw[ni][g4][1] = b4.y; braw[ni][g4][2] = b4.z; braw[ni][g4][3] = b4.w; }
+      }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  }
 
   f32x16_t acc[MI][2];
 #pragma unroll
@@ -149,7 +141,7 @@ __global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, i
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
       const int rr = (wave * LA + i) * 8 + lrow;
-      const int64_t r = min(m0 + rr, g.M - 1);
+      const int64_t r = min(m0 + rr, g.M - 1);       // rows past M repeat the last row: their outputs are never stored
       a_src[i] = A + (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) + (lpos ^ (rr & 7)) * VEC;
     }
 #pragma unroll
@@ -158,8 +150,8 @@ __global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, i
       const int n = min(n0 + rr, g.N - 1);
       b_src[i] = W + (int64_t)phys_col(cm, n) * g.ldw + (lpos ^ (rr & 7)) * VEC;
     }
-    auto issue = [&](int kt) {
-      u32x4* st = lds + (kt & 1) * STAGE;
+    auto issue = [&](int kt, int stage) {
+      u32x4* st = lds + stage * STAGE;
       const int k0 = kt * BK;
 #pragma unroll
       for (int i = 0; i < LA; ++i) __builtin_amdgcn_global_load_lds(SM_GPTR(a_src[i] + k0), SM_LPTR(st + (wave * LA + i) * 64), 16, 0, 0);
@@ -185,8 +177,8 @@ __global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, i
         asm volatile("ds_read_b128 %0, %1" : "=v"(fb[ni]) : "v"(ad));
       }
     };
-    auto compute = [&](int kt) {
-      const unsigned sbase = (unsigned)((kt & 1) * STAGE * 16);
+    auto compute = [&](int stage) {
+      const unsigned sbase = (unsigned)(stage * STAGE * 16);
       u32x4 fa[2][MI], fb[2][2];
       read_frags(sbase, 0, fa[0], fb[0]);
 #pragma unroll
@@ -205,26 +197,55 @@ __global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, i
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
           for (int ni = 0; ni < 2; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[cur][mi]),
-                                                                  __builtin_bit_cast(bf16x8_t, fb[cur][ni]), acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb[cur][ni]),
+                                                                  __builtin_bit_cast(bf16x8_t, fa[cur][mi]), acc[mi][ni], 0, 0, 0);
       }
     };
-    // the row offsets of C written above must be visible before the epilogue: the loop's barriers order them
+    // NS stages, tiles kt+1 .. kt+NS-2 in flight while tile kt is multiplied.  Per tile: wait until this wave's part
+    // of it has landed (only the younger tiles' loads may still be outstanding), barrier (everybody's part has
+    // landed, and nobody reads the stage of tile kt-1 any more), refill that stage with tile kt+NS-1, multiply.
+    constexpr int LPT = LA + LB;                   // loads per wave per tile
     const int nk = g.K / BK;
-    issue(0);
-    int kt = 0;
-    for (; kt + 1 < nk; ++kt) {
-      __builtin_amdgcn_s_waitcnt(0x0f70);        // vmcnt(0): this wave's part of tile kt is in LDS
-      __builtin_amdgcn_s_barrier();              // ... and everybody's; buffer (kt + 1) & 1 is no longer read
-      issue(kt + 1);
-      compute(kt);
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t)
+      if (t < nk) issue(t, t);
+    int kt = 0, sc = 0;                            // sc = stage of tile kt
+    for (; kt + (NS - 1) < nk; ++kt) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPT) : "memory");
+      __builtin_amdgcn_s_barrier();
+      issue(kt + NS - 1, sc == 0 ? NS - 1 : sc - 1);
+      compute(sc);
+      sc = sc == NS - 1 ? 0 : sc + 1;
     }
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-    __builtin_amdgcn_s_barrier();
-    compute(kt);
-    __syncthreads();
+    // the last NS - 1 tiles (fewer if K is short): nothing left to issue, the wait count shrinks with the tiles in flight
+#pragma unroll
+    for (int left = NS - 2; left >= 0; --left) {
+      if (nk > left) {
+        if (left == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+        else if (left == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        compute(sc);
+        sc = sc == NS - 1 ? 0 : sc + 1;
+      }
+    }
   } else {
-  // global -> register staging, two K-tiles in flight (register sets 0 and 1)
+    // global -> register staging, two K-tiles in flight (register sets 0 and 1)
+    // loader assignment: chunk lc of rows lr + 32 i
+    const int lc = tid & 7, lr = tid >> 3;
+    const T* a_ptr[2 * MI];
+#pragma unroll
+    for (int i = 0; i < 2 * MI; ++i) {
+      // rows past M are clamped to the last row: their products land in output rows that are never stored
+      const int64_t r = min(m0 + lr + 32 * i, g.M - 1);
+      a_ptr[i] = A + (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) + lc * VEC;
+    }
+    const T* b_ptr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = min(n0 + lr + 32 * i, g.N - 1);          // clamped like the rows of A
+      b_ptr[i] = W + (int64_t)phys_col(cm, n) * g.ldw + lc * VEC;
+    }
     u32x4 ra[2][2 * MI], rb[2][4];
     bool kok[2] = {true, true};      // chunk of the staged tile lies inside K (zeroed when stored otherwise)
     const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -281,14 +302,14 @@ __global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, i
 #pragma unroll
           for (int ni = 0; ni < 2; ++ni) {
             if constexpr (sizeof(T) == 2) {
-              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[mi]),
-                                                                    __builtin_bit_cast(bf16x8_t, fb[ni]), acc[mi][ni], 0, 0, 0);
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb[ni]),
+                                                                    __builtin_bit_cast(bf16x8_t, fa[mi]), acc[mi][ni], 0, 0, 0);
             } else {
               const float* pa = (const float*)&fa[mi];
               const float* pb = (const float*)&fb[ni];
 #pragma unroll
               for (int t = 0; t < 4; ++t)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[t], pb[t], acc[mi][ni], 0, 0, 0);
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(pb[t], pa[t], acc[mi][ni], 0, 0, 0);
             }
           }
       }
@@ -331,141 +352,203 @@ __global__ __launch_bounds__(128 * WM) void gemm_kernel(GemmArgs g, ColMap cm, i
         compute_tile(0);
       }
     }
-    __syncthreads();
   }
 
-  // ---- epilogue
+  // ---- epilogue, in registers.  acc[mi][ni][i] is the output of row m0 + (wm MI + mi) 32 + l32 and logical
+  // column span0 + 32 ni + cl(i), cl(i) = 8 (i / 4) + 4 hf + i % 4.  A block of 32 logical columns is a run of 32
+  // physical columns in every column order (identity, gated halves, RoPE halves).
   T* C = (T*)g.C;
   const T* R = (const T*)g.residual;
-  const T* bias = (const T*)g.bias;
-  const float b0 = (bias && ok0) ? Elem<T>::ld(bias + pc0) : 0.f;
-  const float b1 = (bias && ok1) ? Elem<T>::ld(bias + pc1) : 0.f;
-  const bool rope = EPI == EPI_ROPE && nl0 < cm.rope_cols;
-  float theta = 0.f;
-  if (rope) {
-    const int e = pc0 % cm.rope_dim;                  // index of the pair, < rope_dim / 2
-    theta = exp2f(-2.f * (float)e / (float)cm.rope_dim * log2f(g.rope_base));
-  }
-  // Staged epilogue: when the tile's output columns are one contiguous run and rows are stored whole, the values
-  // (bias, activation, RoPE applied) go through LDS as fp32 so that the residual is read and the result written
-  // in 16-byte row pieces; otherwise each lane stores its own elements.
-  constexpr int EP = 132;                              // padded row pitch of the staging tile (floats)
-  const bool staged = !g.c_cols_on && !g.c_transposed && (EPI != EPI_ROPE || cm.rope_dim <= 128);
-  float* stage = (float*)lds;
+  const int n_out = EPI == EPI_GLU ? cm.half : g.N;
+  float bv[2][16];
+  {
+    const T* bias = (const T*)g.bias;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
+    for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int rl = wm * 32 * MI + mi * 32 + (i >> 2) * 8 + hf * 4 + (i & 3);
-      const int64_t r = m0 + rl;
-      float v0 = acc[mi][0][i] + b0, v1 = acc[mi][1][i] + b1;
-      if constexpr (EPI == EPI_GLU) {
-        const float o = g.act == SM_ACT_SWIGLU ? silu_f(v0) * v1 : v0 * gelu_erf(v1);
-        if (staged) { stage[rl * EP + wn * 32 + l32] = o; continue; }
-        if (r < g.M && ok0 && pc0 < cm.half) {
-          const int64_t off = c_off[rl] + co0;
-          Elem<T>::st(C + off, R ? o + Elem<T>::ld(R + off) : o);
-        }
-        continue;
-      }
-      if constexpr (EPI == EPI_GELU) { v0 = gelu_erf(v0); v1 = gelu_erf(v1); }
-      if (EPI == EPI_ROPE && rope) {
-        const float ang = (float)(r % g.rope_seq) * theta;
-        float sn, cs;
-        sincosf(ang, &sn, &cs);
-        const float a = v0, b = v1;
-        v0 = a * cs - b * sn;
-        v1 = b * cs + a * sn;
-      }
-      if (staged) {                                    // physical column inside the tile
-        stage[rl * EP + (pc0 - n0)] = v0;
-        stage[rl * EP + (pc1 - n0)] = v1;
-        continue;
-      }
-      if (r >= g.M) continue;
-      const int64_t ro = c_off[rl];
-      if (ok0) {
-        const int64_t off = ro + co0;
-        if (R) v0 += Elem<T>::ld(R + off);
-        Elem<T>::st(C + off, v0);
-      }
-      if (ok1) {
-        const int64_t off = ro + co1;
-        if (R) v1 += Elem<T>::ld(R + off);
-        Elem<T>::st(C + off, v1);
-      }
-    }
-  }
-  if (staged) {
-    __syncthreads();
-    constexpr int TW = EPI == EPI_GLU ? 64 : 128;      // output columns of the tile
-    constexpr int CPR = TW / VEC;                      // 16-byte pieces per row
-    const int n_out = EPI == EPI_GLU ? cm.half : g.N;
-    const int c_base = EPI == EPI_GLU ? n0 / 2 : n0;
-    for (int p = tid; p < BM * CPR; p += NT) {
-      const int rl = p / CPR, cl = (p - rl * CPR) * VEC;
-      const int64_t r = m0 + rl;
-      const int col = c_base + cl;
-      if (r >= g.M || col >= n_out) continue;
-      const int64_t off = c_off[rl] + col;
-      float v[VEC];
-#pragma unroll
-      for (int e = 0; e < VEC; e += 4) {
-        const float4 t = *(const float4*)(stage + rl * EP + cl + e);
-        v[e] = t.x; v[e + 1] = t.y; v[e + 2] = t.z; v[e + 3] = t.w;
-      }
-      if (col + VEC <= n_out && (off & (VEC - 1)) == 0) {
-        if (R) {
-          const u32x4 rr = *(const u32x4*)(R + off);
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int pc = pcb[ni] + g4 * 8 + hf * 4;
+        if (bias && pc + 4 <= g.N) {
           if constexpr (VEC == 8) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(rr[e] << 16); v[2 * e + 1] += __uint_as_float(rr[e] & 0xffff0000u); }
+            const unsigned b0 = braw[ni][g4][0], b1 = braw[ni][g4][1];
+            bv[ni][4 * g4] = __uint_as_float(b0 << 16); bv[ni][4 * g4 + 1] = __uint_as_float(b0 & 0xffff0000u);
+            bv[ni][4 * g4 + 2] = __uint_as_float(b1 << 16); bv[ni][4 * g4 + 3] = __uint_as_float(b1 & 0xffff0000u);
           } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(rr[e]);
+            for (int j = 0; j < 4; ++j) bv[ni][4 * g4 + j] = __uint_as_float(braw[ni][g4][j]);
           }
-        }
-        u32x4 out;
-        if constexpr (VEC == 8) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) out[e] = (unsigned)f2bf(v[2 * e]) | ((unsigned)f2bf(v[2 * e + 1]) << 16);
         } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(v[e]);
+          for (int j = 0; j < 4; ++j) bv[ni][4 * g4 + j] = (bias && pc + j < g.N) ? Elem<T>::ld(bias + pc + j) : 0.f;
         }
-        *(u32x4*)(C + off) = out;
-      } else {
-        for (int e = 0; e < VEC && col + e < n_out; ++e)
-          Elem<T>::st(C + off + e, R ? v[e] + Elem<T>::ld(R + off + e) : v[e]);
       }
+  }
+  float theta[16];
+  const bool rope = EPI == EPI_ROPE && span0 < cm.rope_cols;
+  if (rope) {
+    const float l2b = log2f(g.rope_base);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int e = (pcb[0] + (i >> 2) * 8 + hf * 4 + (i & 3)) % cm.rope_dim;      // index of the pair, < rope_dim / 2
+      theta[i] = exp2f(-2.f * (float)e / (float)cm.rope_dim * l2b);
     }
   }
+  // VEC values w[] for columns col .. col + VEC - 1 of row r (output offset of the row: ro)
+  auto store_chunk = [&](bool row_ok, int64_t ro, int col, const float* w) __attribute__((always_inline)) {
+    if (!row_ok || col >= n_out) return;
+    if (g.c_transposed) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (col + e < n_out) {
+          const int64_t off = ro + (int64_t)(col + e) * g.c_batch_rows;
+          Elem<T>::st(C + off, R ? w[e] + Elem<T>::ld(R + off) : w[e]);
+        }
+      return;
+    }
+    const bool whole = col + VEC <= n_out && (!g.c_cols_on || g.c_gran == VEC);
+    const int64_t off = ro + (g.c_cols_on ? (g.c_gran == VEC ? eval_rows_k(&gk->c_cols, col / VEC) : 0) : col);
+    if (whole && (off & (VEC - 1)) == 0) {
+      float v[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[e] = w[e];
+      if (R) {
+        const u32x4 rr = *(const u32x4*)(R + off);
+        if constexpr (VEC == 8) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(rr[e] << 16); v[2 * e + 1] += __uint_as_float(rr[e] & 0xffff0000u); }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(rr[e]);
+        }
+      }
+      u32x4 out;
+      if constexpr (VEC == 8) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { const f32x2 pr = {v[2 * e], v[2 * e + 1]}; out[e] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2)); }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(v[e]);
+      }
+      *(u32x4*)(C + off) = out;
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (col + e < n_out) {
+          int64_t oe = off + e;
+          if (g.c_cols_on && g.c_gran != VEC) oe = ro + eval_rows_k(&gk->c_cols, col + e);
+          Elem<T>::st(C + oe, R ? w[e] + Elem<T>::ld(R + oe) : w[e]);
+        }
+    }
+  };
+  // one block of 32 output columns starting at ocb: a lane's sixteen values -> chunks of VEC consecutive columns
+  auto store_block = [&](bool row_ok, int64_t ro, int ocb, const float* v) __attribute__((always_inline)) {
+    if constexpr (VEC == 8) {
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) {
+        // lanes l and l + 32 own the same row: the lower one gives its second run of four and takes the partner's
+        // first, so that it holds columns 16 gp .. 16 gp + 7 and the partner 16 gp + 8 .. 16 gp + 15
+        float w[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * gp + j]), __float_as_uint(v[8 * gp + 4 + j]), false, false);
+          w[j] = __uint_as_float(sw.x);
+          w[4 + j] = __uint_as_float(sw.y);
+        }
+        store_chunk(row_ok, ro, ocb + (2 * gp + hf) * 8, w);
+      }
+    } else {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) store_chunk(row_ok, ro, ocb + g4 * 8 + hf * 4, v + 4 * g4);
+    }
+  };
+  auto epilogue_rows = [&](auto MI_) __attribute__((always_inline)) {
+    constexpr int mi = decltype(MI_)::value;
+    const int64_t r = m0 + (wm * MI + mi) * 32 + l32;
+    const bool row_ok = r < g.M;
+    int64_t ro = 0;
+    if (row_ok) {
+      if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; ro = bi * g.c_batch_rows * n_out + (r - bi * g.c_batch_rows); }
+      else ro = g.c_rows.identity ? r * g.c_rows.ld : eval_rows_k(&gk->c_rows, r);
+    }
+    float v0[16], v1[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { v0[i] = acc[mi][0][i] + bv[0][i]; v1[i] = acc[mi][1][i] + bv[1][i]; }
+    if constexpr (EPI == EPI_GLU) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v0[i] = g.act == SM_ACT_SWIGLU ? silu_f(v0[i]) * v1[i] : v0[i] * gelu_erf(v1[i]);
+      store_block(row_ok, ro, pcb[0], v0);
+    } else {
+      if constexpr (EPI == EPI_GELU) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { v0[i] = gelu_erf(v0[i]); v1[i] = gelu_erf(v1[i]); }
+      }
+      if (EPI == EPI_ROPE && rope) {
+        const float pos = (float)(r % g.rope_seq);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float sn, cs;
+          sincosf(pos * theta[i], &sn, &cs);
+          const float a = v0[i], b = v1[i];
+          v0[i] = a * cs - b * sn;
+          v1[i] = b * cs + a * sn;
+        }
+      }
+      store_block(row_ok, ro, pcb[0], v0);
+      store_block(row_ok, ro, pcb[1], v1);
+    }
+  };
+  epilogue_rows(std::integral_constant<int, 0>{});
+  if constexpr (MI == 2) epilogue_rows(std::integral_constant<int, 1>{});
 }
 
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM = 2>
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM = 2, int NS = 2>
 static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   constexpr int BM = 32 * MI * WM;
   const int tiles_n = (g.N + 127) / 128;
   const int64_t tiles_m = (g.M + BM - 1) / BM;
-  const size_t tiles = 2 * (BM * 8 + 128 * 8) * sizeof(u32x4), stage = (size_t)BM * 132 * sizeof(float);
-  const size_t smem = (tiles > stage ? tiles : stage) + BM * sizeof(int64_t);
-  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  const size_t smem = (size_t)NS * (BM * 8 + 128 * 8) * sizeof(u32x4);
+  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return (int)attr;
-  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, tiles_n);
+  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, tiles_n);
   return (int)hipGetLastError();
+}
+
+// Stage count of the LDS-DMA pipeline: as deep as the LDS of a CU (160 KiB) allows once it holds as many workgroups
+// as one round of residency needs (grids of up to 256 tiles get the whole CU: four stages in flight hide the
+// global latency that a single resident workgroup cannot hide by occupancy).
+static int g_force_rows = 0, g_force_stages = 0;       // sm_gemm_tuning
+
+template <typename T, int MI, int EPI, int WM>
+static int gemm_launch_dma(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+  constexpr int BM = 32 * MI * WM;
+  const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + 127) / 128);
+  const int64_t per_cu = std::min<int64_t>((tiles + 255) / 256, 8);
+  const int64_t stage = (BM + 128) * 128;
+  int ns = (int)((160 * 1024) / (per_cu * stage));
+  ns = std::max(2, std::min(ns, 4));
+  if (g.K / 64 < ns) ns = std::max(2, g.K / 64);
+  if (g_force_stages) ns = std::min<int>(g_force_stages, (int)((160 * 1024) / stage));
+  if (ns == 4) return gemm_launch2<T, MI, EPI, false, true, WM, 4>(g, cm, s);
+  if (ns == 3) return gemm_launch2<T, MI, EPI, false, true, WM, 3>(g, cm, s);
+  return gemm_launch2<T, MI, EPI, false, true, WM, 2>(g, cm, s);
 }
 
 template <typename T, int MI, int EPI, bool AGRAN>
 static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   if constexpr (sizeof(T) == 2 && !AGRAN) {
     if (g.K % 64 == 0) {
+      if (g_force_rows == 256 || g_force_rows == 128) {
+        if constexpr (MI == 2) return g_force_rows == 256 ? gemm_launch_dma<T, 2, EPI, 4>(g, cm, s) : gemm_launch_dma<T, 2, EPI, 2>(g, cm, s);
+      } else if (g_force_rows == 64) {
+        if constexpr (MI == 1) return gemm_launch_dma<T, 1, EPI, 2>(g, cm, s);
+      }
       if constexpr (MI == 2) {
         // 256 x 128 tiles when they fill the chip (one 8-wave workgroup per CU) about as well as the smaller ones
         const int64_t t256 = ((g.M + 255) / 256) * ((g.N + 127) / 128);
         const int64_t rounds = (t256 + 255) / 256;
-        if (t256 >= 200 && (double)t256 / (double)(rounds * 256) >= 0.8) return gemm_launch2<T, 2, EPI, false, true, 4>(g, cm, s);
+        if (t256 >= 200 && (double)t256 / (double)(rounds * 256) >= 0.8) return gemm_launch_dma<T, 2, EPI, 4>(g, cm, s);
       }
-      return gemm_launch2<T, MI, EPI, false, true>(g, cm, s);
+      return gemm_launch_dma<T, MI, EPI, 2>(g, cm, s);
     }
   }
   return gemm_launch2<T, MI, EPI, AGRAN, false>(g, cm, s);
@@ -487,6 +570,7 @@ static int gemm_dispatch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   const int64_t tn = (g.N + 127) / 128;
   const int64_t t128 = ((g.M + 127) / 128) * tn, t64 = ((g.M + 63) / 64) * tn;
   const double cost128 = (double)((t128 + 511) / 512) * 2.0, cost64 = (double)((t64 + 767) / 768) * 1.2;
+  if (g_force_rows) return g_force_rows >= 128 ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
   return (t128 >= 1024 || cost128 <= cost64) ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
 }
 
@@ -497,6 +581,12 @@ int launch_gemm(const GemmArgs& g, void* stream) {
   if (g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU) cm.mode = 1;
   else if (g.rope_cols > 0) cm.mode = 2;
   return g.dtype == SM_F32 ? gemm_dispatch<float>(g, cm, (hipStream_t)stream) : gemm_dispatch<bf16_t>(g, cm, (hipStream_t)stream);
+}
+
+int gemm_tuning(int tile_rows, int stages) {
+  if ((tile_rows != 0 && tile_rows != 64 && tile_rows != 128 && tile_rows != 256) || (stages != 0 && (stages < 2 || stages > 4))) return -1;
+  g_force_rows = tile_rows; g_force_stages = stages;
+  return 0;
 }
 
 }  // namespace sm

@@ -33,10 +33,12 @@ struct GemmArgs {
   RowProg a_rows, c_rows;       // c_rows.ld = pitch of C / residual
   int c_cols_on;                // 1: output column n is stored at c_rows(r) + c_cols(n) (a store that splits the
   RowProg c_cols;               //    column dimension, e.g. into heads)
+  int c_gran;                   // c_cols takes n / c_gran and the store adds n % c_gran: 1, or the 16-byte vector width
   int a_gran;                   // > 0: A's K axis is contiguous only in granules of a_gran (= 4) elements;
   RowProg a_cols;               //      offset(r, k) = a_rows(r) + a_cols(k / a_gran) + k % a_gran
 };
 int launch_gemm(const GemmArgs& a, void* stream);
+int gemm_tuning(int tile_rows, int stages);      // 0 = automatic; -1 on values the kernel has no variant for
 
 int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,
                      const void* rpb_table, void* stream);
