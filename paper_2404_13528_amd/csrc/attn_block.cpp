@@ -13,6 +13,7 @@
 #include <mutex>
 #include <vector>
 #include "common.h"
+#include "copy_plan.h"
 #include "graph_build.h"
 #include "index_map.h"
 #include "kernels.h"
@@ -23,7 +24,6 @@ using namespace sm;
 namespace {
 
 struct View4 { int64_t base; int64_t stride[3]; };
-struct Copy { MapProg prog; int64_t numel; int vec; };
 
 struct AttnPlan {
   View4 q1, k1, v1, o1;        // self attention operands as [B, h, S, d] views of their stored tensors
@@ -36,16 +36,6 @@ struct AttnPlan {
 struct Key { int v[12]; bool operator<(const Key& o) const { return std::memcmp(v, o.v, sizeof(v)) < 0; } };
 std::mutex g_mu;
 std::map<Key, std::shared_ptr<AttnPlan>> g_plans;
-
-bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, int esize, Copy* out, std::string* err) {
-  sm_map* m = nullptr;
-  if (map_create(src, chain.data(), (int)chain.size(), &m, err) != SM_OK) return false;
-  bool ok = m->compile(&out->prog, err);
-  out->numel = m->numel();
-  out->vec = map_vector_width(*m, esize);
-  delete m;
-  return ok;
-}
 
 bool view_from(const sm_map* m, View4* v, std::string* err, const char* what) {
   int64_t st[SM_MAX_RANK];
@@ -190,6 +180,7 @@ std::shared_ptr<AttnPlan> attn_plan(const sm_attn_cfg& c, std::string* err) {
         p->q2_gran = 1;
         if (!qm->compile_rows_cols(1, &p->q2_rows, &p->q2_cols, err)) return nullptr;
       }
+      if (!attach_row_table(&p->q2_rows, (int64_t)B * S, err) || !attach_row_table(&p->q2_cols, E / p->q2_gran, err)) return nullptr;
       p->q2_scatter = true;
     }
     // GroupNorm must have been told to store token-major (its consumer reduces over C), proj_out to store NCHW
@@ -246,16 +237,6 @@ Sizes sizes(const sm_attn_cfg* c, int mode) {
   return z;
 }
 
-int copy_launch(const Copy& cp, const void* src, void* dst, int dtype, void* stream, const void* addend = nullptr) {
-  char label[64];
-  snprintf(label, sizeof(label), "copy_%s[%lld]%s", dtype == SM_F32 ? "f32" : "bf16", (long long)cp.numel, addend ? "+add" : "");
-  Timed tm(label, stream);
-  int rc = addend ? launch_gather_add(cp.prog, cp.numel, cp.vec, src, addend, dst, dtype, stream)
-                  : launch_gather(cp.prog, cp.numel, cp.vec, src, dst, (int)dtype_size(dtype), stream);
-  if (rc) return fail(SM_ERR_DEVICE, "copy kernel launch failed (hip error %d)", rc);
-  count_copy();
-  return SM_OK;
-}
 
 int norm(const void* x, const void* g, const void* b, void* y, int64_t rows, int C, float eps, int rms, int dt, void* stream) {
   NormArgs a; std::memset(&a, 0, sizeof(a));

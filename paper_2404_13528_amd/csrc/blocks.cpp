@@ -17,15 +17,12 @@
 #include "index_map.h"
 #include "kernels.h"
 #include "plan_chains.h"
+#include "copy_plan.h"
 #include "graph_build.h"
 
 using namespace sm;
 
 namespace {
-
-struct Copy {            // one materialised layout transformation
-  MapProg prog; int64_t numel; int vec;
-};
 
 struct SwinPlan {
   // elided: what sm_layout_plan decided for the block's operator graph
@@ -46,20 +43,11 @@ struct Key {
 std::mutex g_mu;
 std::map<Key, std::shared_ptr<SwinPlan>> g_swin;
 
-bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, int esize, Copy* out, std::string* err) {
-  sm_map* m = nullptr;
-  if (map_create(src, chain.data(), (int)chain.size(), &m, err) != SM_OK) return false;
-  bool ok = m->compile(&out->prog, err);
-  out->numel = m->numel();
-  out->vec = map_vector_width(*m, esize);
-  delete m;
-  return ok;
-}
-
 bool make_rows(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, RowProg* out, std::string* err) {
   sm_map* m = nullptr;
   if (map_create(src, chain.data(), (int)chain.size(), &m, err) != SM_OK) return false;
   bool ok = m->compile_rows(out, err);
+  ok = ok && attach_row_table(out, m->numel() / m->shape.back(), err);
   delete m;
   return ok;
 }
@@ -118,8 +106,10 @@ std::shared_ptr<SwinPlan> swin_plan(const sm_swin_cfg& c, std::string* err) {
     const sm_map* m = nullptr;
     sm_plan_store_map(plan, g.find("ln1"), &m, nullptr);
     if (!m || !m->compile_rows(&p->ln1_store, err)) { if (!m) *err = "no store map planned for LayerNorm"; return nullptr; }
+    if (!attach_row_table(&p->ln1_store, B * H * W, err)) return nullptr;
     sm_plan_store_map(plan, g.find("proj"), &m, nullptr);
     if (!m || !m->compile_rows(&p->proj_store, err)) { if (!m) *err = "no store map planned for proj"; return nullptr; }
+    if (!attach_row_table(&p->proj_store, B_ * N, err)) return nullptr;
     const int attn = g.find("attn");
     int64_t st8[SM_MAX_RANK];
     for (int k = 0; k < 3; ++k) {
@@ -162,16 +152,6 @@ int check_swin(const sm_swin_cfg* c, const char* who) {
 
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
-int copy_launch(const Copy& cp, const void* src, void* dst, int dtype, void* stream, const void* addend = nullptr) {
-  char label[64];
-  snprintf(label, sizeof(label), "copy_%s[%lld]%s", dtype == SM_F32 ? "f32" : "bf16", (long long)cp.numel, addend ? "+add" : "");
-  Timed tm(label, stream);
-  int rc = addend ? launch_gather_add(cp.prog, cp.numel, cp.vec, src, addend, dst, dtype, stream)
-                  : launch_gather(cp.prog, cp.numel, cp.vec, src, dst, (int)dtype_size(dtype), stream);
-  if (rc) return fail(SM_ERR_DEVICE, "copy kernel launch failed (hip error %d)", rc);
-  count_copy();
-  return SM_OK;
-}
 
 int run_norm(const void* x, const void* g, const void* b, void* y, int64_t rows, int C, float eps, int rms, int dtype,
              const RowProg* load, int nseg, const RowProg* store, void* stream) {
@@ -306,10 +286,10 @@ std::shared_ptr<EmbedPlan> embed_plan(int B, int Cin, int img, int patch, int dt
   std::vector<sm_view_op> ch = chains::patch_embed(B, Cin, img, img, patch);
   if (map_create({B, Cin, img, img}, ch.data(), (int)ch.size(), &m, err) != SM_OK) return nullptr;
   bool ok = m->compile_rows_cols(4, &p->a_rows, &p->a_cols, err);
-  ok = ok && m->compile(&p->unfold.prog, err);
-  p->unfold.numel = m->numel();
-  p->unfold.vec = map_vector_width(*m, (int)dtype_size(dtype));
+  const int64_t kk = m->shape.back();
+  ok = ok && attach_row_table(&p->a_rows, m->numel() / kk, err) && attach_row_table(&p->a_cols, kk / 4, err);
   delete m;
+  ok = ok && make_copy({B, Cin, img, img}, ch, (int)dtype_size(dtype), &p->unfold, err);
   if (!ok) return nullptr;
   g_embed[key] = p;
   return p;

@@ -68,6 +68,7 @@ __device__ __forceinline__ const SM_KARG Args* kernarg_ptr() { return (const SM_
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ int64_t eval_rows_k(const SM_KARG RowProg* p, int64_t r) {
   if (p->identity) return r * p->ld;
+  if (p->table) return (int64_t)p->table[r];          // evaluated when the plan was built
   i32x16 val = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   const int n = p->n_atoms;
   for (int i = 0; i < n; ++i) {

@@ -322,7 +322,7 @@ RowProg identity_rows(int64_t ld) {
 
 // Division by an invariant: for 0 <= x < 2^31 and d > 1, with l = ceil(log2 d) and m = ceil(2^(31+l) / d) < 2^32,
 // floor(x / d) == (x * m) >> (31 + l) == umulhi(x, m) >> (l - 1).
-static void magic(int64_t d, uint32_t* mul, uint32_t* sh) {
+void magic(int64_t d, uint32_t* mul, uint32_t* sh) {
   if (d <= 1) { *mul = 0; *sh = 0; return; }
   int l = 0;
   while ((int64_t(1) << l) < d) ++l;
@@ -524,3 +524,21 @@ bool sm_map::affine(int64_t* base, int64_t* strides) const {
   for (auto& t : offset.terms) strides[atoms[t.first].var] = t.second;
   return true;
 }
+
+namespace sm {
+int64_t eval_rows_host(const RowProg& p, int64_t r) {
+  if (p.identity) return r * p.ld;
+  int64_t val[PROG_MAX_ATOMS] = {0};
+  for (int i = 0; i < p.n_atoms; ++i) {
+    const ProgAtom& a = p.atoms[i];
+    int64_t x = a.c0;
+    for (int t = 0; t < a.nterm; ++t) x += (int64_t)a.t_coef[t] * (a.t_atom[t] < 0 ? r : val[a.t_atom[t]]);
+    if (a.div > 1) x /= a.div;
+    if (a.mod >= 1) x %= a.mod;
+    val[i] = x;
+  }
+  int64_t off = p.c0;
+  for (int t = 0; t < p.nterm; ++t) off += p.t_coef[t] * (p.t_atom[t] < 0 ? r : val[p.t_atom[t]]);
+  return off;
+}
+}  // namespace sm

@@ -52,6 +52,7 @@ struct RowProg {
   int32_t n_atoms; int32_t nterm; int32_t pad;
   int64_t ld;              // identity only
   int64_t c0;
+  const int32_t* table;    // device memory or null: the program evaluated for rows 0 .. n-1 (attach_row_table)
   int32_t t_atom[PROG_MAX_FINAL];
   int64_t t_coef[PROG_MAX_FINAL];
   ProgAtom atoms[PROG_MAX_ATOMS];
@@ -85,4 +86,11 @@ struct sm_map {
 namespace sm {
 int map_create(const std::vector<int64_t>& src_shape, const sm_view_op* chain, int n, sm_map** out, std::string* err);
 RowProg identity_rows(int64_t ld);
+// x / d == umulhi(x, *mul) >> *sh for 0 <= x < 2^31 and d > 1 (d <= 1: both zero, callers test d)
+void magic(int64_t d, uint32_t* mul, uint32_t* sh);
+int64_t eval_rows_host(const RowProg& p, int64_t r);
+// Evaluates the program for rows 0 .. n_rows-1 on the host and leaves the offsets in device memory that lives
+// until the process ends (plans are cached for that long); kernels then read one word per row instead of
+// interpreting the program.  No table (and success) for identity programs and for offsets beyond 31 bits.
+bool attach_row_table(RowProg* p, int64_t n_rows, std::string* err);
 }

@@ -33,6 +33,58 @@ __global__ __launch_bounds__(256) void gather_add_kernel(MapProg p, int64_t nvec
   *(Pack*)(dst + o * VEC) = r;
 }
 
+// Row form: one thread per 16-byte vector; the row's source offset comes from the row program (one table word
+// per row once the plan has attached its table), the position inside the row is plain arithmetic.
+template <typename T, bool ADD>
+__global__ __launch_bounds__(256) void gather_rows_kernel(RowProg rows, int64_t nvec, int vpr, unsigned vpr_mul, unsigned vpr_sh,
+                                                          const T* __restrict__ src, const T* __restrict__ addend, T* __restrict__ dst) {
+  constexpr int VEC = Elem<T>::VEC;
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= nvec) return;
+  const SM_KARG RowProg* pk = kernarg_ptr<RowProg>();        // rows is the first argument
+  // o < 2^31 vectors (checked by the launcher): row = o / vpr by multiplication
+  const unsigned r = vpr == 1 ? (unsigned)o : (__umulhi((unsigned)o, vpr_mul) >> vpr_sh);
+  const unsigned c = (unsigned)o - r * (unsigned)vpr;
+  const int64_t off = eval_rows_k(pk, (int64_t)r) + (int64_t)c * VEC;
+  typedef unsigned int v4 __attribute__((ext_vector_type(4)));
+  v4 a = *(const v4*)(src + off);
+  if (ADD) {
+    const v4 b = *(const v4*)(addend + o * VEC);
+    if constexpr (VEC == 8) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float lo = __uint_as_float(a[e] << 16) + __uint_as_float(b[e] << 16);
+        const float hi = __uint_as_float(a[e] & 0xffff0000u) + __uint_as_float(b[e] & 0xffff0000u);
+        a[e] = (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a[e] = __float_as_uint(__uint_as_float(a[e]) + __uint_as_float(b[e]));
+    }
+  }
+  *(v4*)(dst + o * VEC) = a;
+}
+
+int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const void* src, const void* addend, void* dst, int dtype, void* stream) {
+  const int vec = dtype == SM_F32 ? 4 : 8;
+  const int vpr = inner / vec;
+  const int64_t nvec = n_rows * vpr;
+  if (nvec == 0) return 0;
+  if (nvec >= (1LL << 31)) return (int)hipErrorInvalidValue;
+  unsigned mul = 0, sh = 0;
+  magic(vpr, &mul, &sh);
+  dim3 grid((unsigned)((nvec + 255) / 256)), block(256);
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == SM_F32) {
+    if (addend) gather_rows_kernel<float, true><<<grid, block, 0, s>>>(rows, nvec, vpr, mul, sh, (const float*)src, (const float*)addend, (float*)dst);
+    else gather_rows_kernel<float, false><<<grid, block, 0, s>>>(rows, nvec, vpr, mul, sh, (const float*)src, (const float*)addend, (float*)dst);
+  } else {
+    if (addend) gather_rows_kernel<bf16_t, true><<<grid, block, 0, s>>>(rows, nvec, vpr, mul, sh, (const bf16_t*)src, (const bf16_t*)addend, (bf16_t*)dst);
+    else gather_rows_kernel<bf16_t, false><<<grid, block, 0, s>>>(rows, nvec, vpr, mul, sh, (const bf16_t*)src, (const bf16_t*)addend, (bf16_t*)dst);
+  }
+  return (int)hipGetLastError();
+}
+
 int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const void* src, const void* addend, void* dst, int dtype, void* stream) {
   if (numel == 0) return 0;
   const int64_t nvec = numel / vec_elems;
