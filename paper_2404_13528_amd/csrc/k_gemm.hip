@@ -60,6 +60,25 @@ __device__ __forceinline__ float erf_as(float x) {
   return copysignf(r, x);
 }
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erf_as(x * 0.70710678118654752f)); }
+// bf16 outputs: erf(x / sqrt 2) as an odd polynomial of degree 13 on the clamped argument (|error| < 1.4e-4, i.e.
+// |GELU error| < 2.6e-4, a fifteenth of a bf16 ulp at 1): seven FMAs and no transcendental instruction
+__device__ __forceinline__ float gelu_poly(float x) {
+  const float xc = __builtin_amdgcn_fmed3f(x, -3.8183766f, 3.8183766f);
+  const float u = xc * xc;
+  float p = 7.157552710e-08f;
+  p = fmaf(p, u, -4.470385145e-06f);
+  p = fmaf(p, u, 1.201538955e-04f);
+  p = fmaf(p, u, -1.853696382e-03f);
+  p = fmaf(p, u, 1.859850362e-02f);
+  p = fmaf(p, u, -1.313855874e-01f);
+  p = fmaf(p, u, 7.973302013e-01f);
+  const float hx = 0.5f * x;
+  return fmaf(hx, p * xc, hx);
+}
+template <typename T> __device__ __forceinline__ float gelu_t(float x) {
+  if constexpr (sizeof(T) == 2) return gelu_poly(x);
+  else return gelu_erf(x);
+}
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
 enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
@@ -475,12 +494,12 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     for (int i = 0; i < 16; ++i) { v0[i] = acc[mi][0][i] + bv[0][i]; v1[i] = acc[mi][1][i] + bv[1][i]; }
     if constexpr (EPI == EPI_GLU) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) v0[i] = g.act == SM_ACT_SWIGLU ? silu_f(v0[i]) * v1[i] : v0[i] * gelu_erf(v1[i]);
+      for (int i = 0; i < 16; ++i) v0[i] = g.act == SM_ACT_SWIGLU ? silu_f(v0[i]) * v1[i] : v0[i] * gelu_t<T>(v1[i]);
       store_block(row_ok, ro, pcb[0], v0);
     } else {
       if constexpr (EPI == EPI_GELU) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { v0[i] = gelu_erf(v0[i]); v1[i] = gelu_erf(v1[i]); }
+        for (int i = 0; i < 16; ++i) { v0[i] = gelu_t<T>(v0[i]); v1[i] = gelu_t<T>(v1[i]); }
       }
       if (EPI == EPI_ROPE && rope) {
         const float pos = (float)(r % g.rope_seq);
@@ -513,21 +532,16 @@ static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
-// Stage count of the LDS-DMA pipeline: as deep as the LDS of a CU (160 KiB) allows once it holds as many workgroups
-// as one round of residency needs (grids of up to 256 tiles get the whole CU: four stages in flight hide the
-// global latency that a single resident workgroup cannot hide by occupancy).
 static int g_force_rows = 0, g_force_stages = 0;       // sm_gemm_tuning
 
+// Two stages (one K-tile in flight) unless the tuning hook asks for more: within a chain of kernels the operands
+// arrive from the memory-side cache, a workgroup's K step is bound by its own issue and fragment-read latencies
+// rather than by the tile's arrival, and every further stage costs a resident workgroup per CU.
 template <typename T, int MI, int EPI, int WM>
 static int gemm_launch_dma(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   constexpr int BM = 32 * MI * WM;
-  const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + 127) / 128);
-  const int64_t per_cu = std::min<int64_t>((tiles + 255) / 256, 8);
   const int64_t stage = (BM + 128) * 128;
-  int ns = (int)((160 * 1024) / (per_cu * stage));
-  ns = std::max(2, std::min(ns, 4));
-  if (g.K / 64 < ns) ns = std::max(2, g.K / 64);
-  if (g_force_stages) ns = std::min<int>(g_force_stages, (int)((160 * 1024) / stage));
+  const int ns = g_force_stages ? std::min<int>(g_force_stages, (int)((160 * 1024) / stage)) : 2;
   if (ns == 4) return gemm_launch2<T, MI, EPI, false, true, WM, 4>(g, cm, s);
   if (ns == 3) return gemm_launch2<T, MI, EPI, false, true, WM, 3>(g, cm, s);
   return gemm_launch2<T, MI, EPI, false, true, WM, 2>(g, cm, s);
@@ -543,10 +557,11 @@ static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
         if constexpr (MI == 1) return gemm_launch_dma<T, 1, EPI, 2>(g, cm, s);
       }
       if constexpr (MI == 2) {
-        // 256 x 128 tiles when they fill the chip (one 8-wave workgroup per CU) about as well as the smaller ones
+        // 256 x 128 tiles when they fill the chip (one 8-wave workgroup per CU) about as well as the smaller ones; with a
+        // short K loop only on grids of several rounds, where their lower L2 -> LDS traffic per flop pays
         const int64_t t256 = ((g.M + 255) / 256) * ((g.N + 127) / 128);
         const int64_t rounds = (t256 + 255) / 256;
-        if (t256 >= 200 && (double)t256 / (double)(rounds * 256) >= 0.8) return gemm_launch_dma<T, 2, EPI, 4>(g, cm, s);
+        if (t256 >= (g.K >= 1024 ? 200 : 512) && (double)t256 / (double)(rounds * 256) >= 0.8) return gemm_launch_dma<T, 2, EPI, 4>(g, cm, s);
       }
       return gemm_launch_dma<T, MI, EPI, 2>(g, cm, s);
     }
@@ -565,13 +580,20 @@ static int gemm_pick_epi(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
 
 template <typename T>
 static int gemm_dispatch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
-  // Tile height by how the grid fills the chip: 256 CUs hold 512 workgroups of the 128-row tile (64 KiB of LDS each)
-  // or 768 of the 64-row tile; count rounds of residency, the 64-row tile being about 0.6 as efficient per row.
+  if (g_force_rows) return g_force_rows >= 128 ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
+  // Tile height.  Large grids (several rounds of residency whatever the tile): the 128-row tile, or the 256-row one
+  // where gemm_launch finds that it fills the chip.  Small grids are decided by rounds of residency (256 CUs hold
+  // 768 workgroups of the 64-row tile, 512 of the 128-row one) times the time a workgroup lives: a fixed part plus
+  // its K steps, both measured on the chip (microseconds; the 128-row step moves twice the rows in about twice the time,
+  // so the smaller tile wins unless it needs an extra round).
   const int64_t tn = (g.N + 127) / 128;
   const int64_t t128 = ((g.M + 127) / 128) * tn, t64 = ((g.M + 63) / 64) * tn;
-  const double cost128 = (double)((t128 + 511) / 512) * 2.0, cost64 = (double)((t64 + 767) / 768) * 1.2;
-  if (g_force_rows) return g_force_rows >= 128 ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
-  return (t128 >= 1024 || cost128 <= cost64) ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
+  if (t128 >= 1024) return gemm_pick_epi<T, 2>(g, cm, s);
+  const double nk = (double)((g.K + 63) / 64);
+  double cost64 = (double)((t64 + 767) / 768) * (3.0 + 0.78 * nk), cost128 = (double)((t128 + 511) / 512) * (3.6 + 1.6 * nk);
+  // long K loops: the tile's L2 -> LDS traffic per flop decides, the 64-row tile being about 0.6 as efficient per row
+  if (nk > 16) { cost64 = (double)((t64 + 767) / 768) * 1.2; cost128 = (double)((t128 + 511) / 512) * 2.0; }
+  return cost128 <= cost64 ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
 }
 
 int launch_gemm(const GemmArgs& g, void* stream) {
