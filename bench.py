@@ -25,7 +25,14 @@ PEAK_BF16 = 2.5e15         # FLOP/s dense bf16 MFMA, MI355X published
 
 # HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (bytes, scaled by the
 # copy-kernel calibration described in the design doc); filled from profiles/, None = not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/swin_stage3_chain_b32_hbm_counters.md: (FETCH_SIZE KiB x 1.982 + WRITE_SIZE KiB x 1.000) x 1024
+    "gemm_bf16[6272,1536,384]+gelu": int((7304.6 * 1.982 + 18816.0) * 1024),
+    "gemm_bf16[6272,1152,384]": int((6445.5 * 1.982 + 14112.0) * 1024),
+    "attention_window_bf16[128,12,49,49,32]": int((7234.5 * 1.982 + 4704.0) * 1024),
+    "layernorm_bf16[6272,384]": int((2432.3 * 1.982 + 4704.0) * 1024),
+    "layernorm_bf16[6272,384]+scatter": int((2432.3 * 1.982 + 4704.0) * 1024),
+}
 
 
 def kernel_model(label, e=2):
@@ -94,10 +101,13 @@ def main():
         sm.timing_enable(True)
         for _ in range(a.steps):
             chain(xd, out=y, stream=stream)
+        sm.timing_calibrate(64, stream=stream)        # what an event pair adds to a kernel's own run time
         torch.cuda.synchronize()
         rep = sm.timing_report()
         sm.timing_enable(False)
-        return rep
+        n, ms = rep.pop("empty_kernel")
+        n2, ms2 = rep.pop("empty_pair")
+        return rep, {"empty_kernel_us": round(ms / n * 1e3, 3), "empty_pair_us": round(ms2 / n2 * 1e3, 3)}
 
     if a.calibrate_copy:
         n = 128 * 1024 * 1024                         # bf16 elements: 256 MiB read + 256 MiB written per launch
@@ -109,9 +119,14 @@ def main():
         del src
 
     sec = {name: timed(c) for name, c in chains.items()}
-    rep = {name: kernels(c) for name, c in chains.items()}
+    rep, overhead_us = {}, {}
+    for name, c in chains.items():
+        rep[name], overhead_us[name] = kernels(c)
 
     def table(r):
+        # avg_us: HIP-event time around each launch on the launch stream.  It contains the dispatch and the event
+        # records themselves: a profiler's kernel duration is 2.5 to 3 us shorter (see event_calibration below for
+        # what an event pair measures around an empty kernel and around nothing)
         rows = []
         for label, (n, ms) in r.items():
             by, fl = kernel_model(label)
@@ -151,6 +166,7 @@ def main():
                          "speedup_vs_explicit": round(sec["explicit"] / sec["elided"], 3),
                          "bytes_ratio_explicit_over_elided": round(alg_bytes["explicit"] / alg_bytes["elided"], 3)},
         "roofline": roof,
+        "event_calibration": overhead_us["elided"],
         "kernels": tab,
     }
 

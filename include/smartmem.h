@@ -299,6 +299,10 @@ int sm_last_launch_counts(int* n_compute, int* n_copy);
  * "label<TAB>launches<TAB>total_ms", into buf (host pointer, n bytes). */
 int sm_timing_enable(int on);
 int sm_timing_report(char* buf, int n);
+/* Launches n (1..1024) empty kernels on `stream`, each recorded like any other launch under the label
+ * "empty_kernel" (only while timing is enabled): their average is what an event pair measures on top of a
+ * kernel's own execution time (dispatch and completion), to be subtracted when comparing with a profiler. */
+int sm_timing_calibrate(int n, void* stream);
 
 /* Tuning hook for benchmarks: overrides the tile and pipeline choice of the bf16 Linear kernel for the calling
  * process.  tile_rows: 0 (automatic), 64, 128 or 256 output rows per workgroup; stages: 0 (automatic) or 2..4

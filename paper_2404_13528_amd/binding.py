@@ -391,6 +391,11 @@ def timing_enable(on=True):
     check(lib().sm_timing_enable(1 if on else 0), "sm_timing_enable")
 
 
+def timing_calibrate(n=64, stream=None):
+    """Records n empty-kernel launches under the label "empty_kernel" (timing must be enabled)."""
+    check(lib().sm_timing_calibrate(int(n), _stream(stream)), "sm_timing_calibrate")
+
+
 def timing_report():
     """{label: (launches, total_ms)} of the launches since timing_enable(True), in first-launch order."""
     buf = C.create_string_buffer(1 << 16)

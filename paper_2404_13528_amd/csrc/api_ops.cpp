@@ -174,3 +174,14 @@ extern "C" int sm_gemm_tuning(int tile_rows, int stages) {
   if (sm::gemm_tuning(tile_rows, stages)) return sm::fail(SM_ERR_INVALID_ARG, "sm_gemm_tuning: tile_rows must be 0, 64, 128 or 256 and stages 0 or 2..4");
   return SM_OK;
 }
+
+extern "C" int sm_timing_calibrate(int n, void* stream) {
+  if (n < 1 || n > 1024) return sm::fail(SM_ERR_INVALID_ARG, "sm_timing_calibrate: n must be 1..1024");
+  for (int i = 0; i < n; ++i) { sm::Timed tm("empty_pair", stream); }
+  for (int i = 0; i < n; ++i) {
+    sm::Timed tm("empty_kernel", stream);
+    const int rc = sm::launch_empty(stream);
+    if (rc) return sm::fail(SM_ERR_DEVICE, "sm_timing_calibrate: launch failed (hip error %d)", rc);
+  }
+  return SM_OK;
+}

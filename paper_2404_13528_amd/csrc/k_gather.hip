@@ -85,6 +85,12 @@ int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const voi
   return (int)hipGetLastError();
 }
 
+__global__ void empty_kernel() {}
+int launch_empty(void* stream) {
+  empty_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>();
+  return (int)hipGetLastError();
+}
+
 int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const void* src, const void* addend, void* dst, int dtype, void* stream) {
   if (numel == 0) return 0;
   const int64_t nvec = numel / vec_elems;

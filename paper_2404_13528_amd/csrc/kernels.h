@@ -12,6 +12,9 @@ int launch_gather(const MapProg& prog, int64_t numel, int vec_elems, const void*
 
 int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const void* src, const void* addend, void* dst, int dtype, void* stream);
 
+// one wave that returns at once: what an event pair around a launch measures beyond the kernel's own run time
+int launch_empty(void* stream);
+
 // row copies: dst row r (inner contiguous elements) = src[rows(r) ...] (+ addend row r); rows(r) keeps 16-byte alignment
 int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const void* src, const void* addend, void* dst, int dtype, void* stream);
 
