@@ -204,3 +204,86 @@ def test_linear_store_splits_columns_into_heads():
     got = sm.linear(dev(A, dtype), dev(W, dtype), c_map=c_map)
     want = V.apply_chain(O.linear(to_np(A), to_np(W)).reshape(Bn, S, h * d), V.head_split_chain(Bn, S, h, d))
     assert_close(got.reshape(want.shape), want, dtype, "head-major store")
+
+
+@pytest.mark.parametrize("kind,nq,nk,d,h", [("full", 130, 64, 32, 1), ("full", 300, 1, 40, 2), ("causal", 129, 129, 96, 2),
+                                           ("causal", 515, 515, 128, 1), ("full", 128, 191, 72, 1), ("full", 64, 130, 128, 2),
+                                           ("causal", 1, 1, 64, 1)])
+def test_global_attention_tile_edges(kind, nq, nk, d, h):
+    # query tiles of 128 and key tiles of 64 with ragged ends, every head-size bucket (2, 3, 4, 6, 8 sixteenths),
+    # a tile that lies entirely after the diagonal for some waves, a single key; contiguous [B, h, n, d] operands
+    dtype = torch.bfloat16
+    Bn = 2
+    q = draw((Bn, h, nq, d), 50, dtype, 1.5)
+    k = draw((Bn, h, nk, d), 51, dtype, 1.5)
+    v = draw((Bn, h, nk, d), 52, dtype)
+    out = sm.attention(dev(q, dtype), dev(k, dtype), dev(v, dtype), kind=kind)
+    o, _ = O.attention(to_np(q), to_np(k), to_np(v), d ** -0.5, causal=(kind == "causal"))
+    assert_close(out, o, dtype, "%s attention %dx%d d=%d" % (kind, nq, nk, d))
+
+
+def test_global_attention_full_size_sampled_rows():
+    # config-4 shape (32 heads, 2048 x 2048, d = 128, causal) in the bench's launch configuration: the oracle
+    # computes sampled (head, query) rows one by one
+    dtype = torch.bfloat16
+    h, n, d = 32, 2048, 128
+    q = draw((1, h, n, d), 53, dtype)
+    k = draw((1, h, n, d), 54, dtype)
+    v = draw((1, h, n, d), 55, dtype)
+    out = to_np(sm.attention(dev(q, dtype), dev(k, dtype), dev(v, dtype), kind="causal").float().cpu())
+    qn, kn, vn = to_np(q), to_np(k), to_np(v)
+    rng = np.random.default_rng(7)
+    for hh, i in [(0, 0), (31, 2047), (5, 127), (5, 128), (17, 1023)] + [(int(rng.integers(h)), int(rng.integers(n))) for _ in range(20)]:
+        s = (kn[0, hh, : i + 1] @ qn[0, hh, i]) * d ** -0.5
+        p = np.exp(s - s.max()); p /= p.sum()
+        want = p @ vn[0, hh, : i + 1]
+        assert np.linalg.norm(out[0, hh, i] - want) <= 2e-2 * np.linalg.norm(want) + 1e-3, (hh, i)
+
+
+@pytest.mark.parametrize("M,N,K", [(70, 100, 64), (257, 1000, 128), (64, 36, 192), (500, 130, 64)])
+def test_linear_ragged_columns_bf16(M, N, K):
+    # N that cuts a 128-column tile, an 8-column store chunk and a 4-column bias run; bias, GELU and residual together
+    dtype = torch.bfloat16
+    A = draw((M, K), 60, dtype)
+    W = draw((N, K), 61, dtype, K ** -0.5)
+    b = draw((N,), 62, dtype)
+    R = draw((M, N), 63, dtype)
+    want = O.gelu(O.linear(to_np(A), to_np(W), to_np(b))) + to_np(R)
+    got = sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype), residual=dev(R, dtype), act="gelu")
+    assert_close(got, want, dtype, "gelu(A W^T + b) + R, ragged N", float(np.abs(want).max()) + 1.0)
+
+
+def test_linear_results_do_not_depend_on_tuning():
+    dtype = torch.bfloat16
+    M, N, K = 700, 384, 256
+    A = draw((M, K), 64, dtype)
+    W = draw((N, K), 65, dtype, K ** -0.5)
+    b = draw((N,), 66, dtype)
+    want = O.linear(to_np(A), to_np(W), to_np(b))
+    ref = None
+    try:
+        for rows in (0, 64, 128, 256):
+            for stages in (0, 2, 3, 4):
+                sm.gemm_tuning(rows, stages)
+                got = sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype))
+                assert_close(got, want, dtype, "tile %d stages %d" % (rows, stages), float(np.abs(want).max()) + 1.0)
+                ref = got if ref is None else ref
+                assert torch.equal(got, ref), "tile %d stages %d changed the result" % (rows, stages)
+        with pytest.raises(sm.SmError):
+            sm.gemm_tuning(96, 2)
+        with pytest.raises(sm.SmError):
+            sm.gemm_tuning(64, 7)
+    finally:
+        sm.gemm_tuning(0, 0)
+
+
+def test_timing_calibration_labels():
+    sm.timing_enable(True)
+    try:
+        sm.timing_calibrate(8)
+        torch.cuda.synchronize()
+        rep = sm.timing_report()
+    finally:
+        sm.timing_enable(False)
+    assert rep["empty_kernel"][0] == 8 and rep["empty_pair"][0] == 8
+    assert rep["empty_kernel"][1] > 0.0
