@@ -345,12 +345,15 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
     }
 }
 
-// Window attention, bf16, head size 32, at most 64 tokens per window: one wave per (window, head), the four
-// waves of a workgroup taking adjacent heads of one window so that their Q / K / V rows are adjacent in memory.
-// Everything a wave needs is requested up front (Q and K fragments, V rows, its head's column of the
-// relative-position table); V and the table go through LDS, from where the transposed V fragments and the bias
-// values are read; the bias index is a difference of a per-query and a per-key term, the shift mask a comparison
-// of two region ids, both prepared once per wave.
+// Window attention, bf16, head size 32, at most 64 tokens per window: one wave per (window, head, block of 32
+// queries); the four waves of a workgroup are the two query blocks of two adjacent heads of one window, so that
+// their Q / K / V rows are adjacent in memory and the second reader of K and V hits the vector cache.  Short
+// dependency chains matter more than total work here (a window is 49 tokens: the kernel is latency-bound), hence
+// the split by query block.  Everything a wave needs is requested up front (Q and K fragments, V rows, its head's
+// column of the relative-position table); V and the table go through wave-private LDS, from where the transposed
+// V fragments and the bias values are read; the bias index is a difference of a per-query and a per-key term, the
+// shift mask a comparison of two region ids, both prepared once per wave.  The softmax works on base-2 logits:
+// scale and table are multiplied by log2 e on the way in.
 __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                             const bf16_t* __restrict__ table, long total_waves) {
@@ -358,29 +361,35 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
   __shared__ float t_lds[4][256];
   __shared__ int k_lds[4][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, hf = lane >> 5;
-  const long wid = (long)blockIdx.x * 4 + wave;
-  if (wid >= total_waves) return;                    // whole waves leave; no workgroup barrier is used below
-  const int hh = (int)(wid % a.heads);
-  const int b = (int)(wid / a.heads);
+  const unsigned wid = blockIdx.x * 4u + wave;       // < 2^31: checked by the launcher
+  if ((long)wid >= total_waves) return;              // whole waves leave; no workgroup barrier is used below
+  const int qb = (int)(wid & 1u);
+  const unsigned pair = wid >> 1;
+  const int b = (int)(pair / (unsigned)a.heads);
+  const int hh = (int)(pair - (unsigned)b * (unsigned)a.heads);
+  const int w = a.window, n = a.nq, tw = 2 * w - 1;
+  if (32 * qb >= n) return;                          // a window of at most 32 tokens has no second query block
   const bf16_t* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
   const bf16_t* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
   const bf16_t* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
   bf16_t* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
-  const int w = a.window, n = a.nq, tw = 2 * w - 1;
   const au32x4 zero = {0u, 0u, 0u, 0u};
+  constexpr float LOG2E = 1.4426950408889634f;
   // ---- all global loads first
-  au32x4 qf[2][2], kf[2][2], vrow[4];
+  au32x4 qf[2], kf[2][2], vrow[4];
   unsigned short tv[4];
+  const int qi = 32 * qb + l32;                      // this lane's query
 #pragma unroll
-  for (int blk = 0; blk < 2; ++blk)
+  for (int ks = 0; ks < 2; ++ks) {
+    const int e = 16 * ks + 8 * hf;
+    qf[ks] = *(const au32x4*)(qp + (int64_t)min(qi, n - 1) * a.q_stride[2] + e);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const int i = 32 * blk + l32, e = 16 * ks + 8 * hf;
-      const int ic = min(i, n - 1);
-      qf[blk][ks] = *(const au32x4*)(qp + (int64_t)ic * a.q_stride[2] + e);
-      kf[blk][ks] = *(const au32x4*)(kp + (int64_t)ic * a.k_stride[2] + e);
-      if (i >= n) { qf[blk][ks] = zero; kf[blk][ks] = zero; }
+    for (int kb = 0; kb < 2; ++kb) {
+      const int j = 32 * kb + l32;
+      kf[kb][ks] = *(const au32x4*)(kp + (int64_t)min(j, n - 1) * a.k_stride[2] + e);
+      if (j >= n) kf[kb][ks] = zero;
     }
+  }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int c = lane + 64 * t, row = c >> 2, part = c & 3;
@@ -389,7 +398,7 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
     const int ti = lane + 64 * t;
     tv[t] = ti < tw * tw ? table[ti * a.heads + hh] : (unsigned short)0;
   }
-  // ---- per-wave LDS: V rows, table column as floats, per-key (bias term | region << 16)
+  // ---- per-wave LDS: V rows, table column as base-2 floats, per-key (bias term | region << 16)
   const int nWx = a.W / w, nW = (a.H / w) * nWx, win = b % nW, wy = win / nWx, wx = win - wy * nWx;
   const float inv_w = 1.0f / (float)w;
   {
@@ -399,75 +408,64 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
     if (a.shift > 0) info |= (3 * region(wy * w + yj, a.H, w, a.shift) + region(wx * w + xj, a.W, w, a.shift)) << 16;
     k_lds[wave][j] = info;
   }
+  // per-query terms
+  const int yi = (int)(((float)qi + 0.5f) * inv_w), xi = qi - yi * w;
+  const int qa = yi * tw + xi + (w - 1) * 2 * w;
+  const int rq = a.shift > 0 ? 3 * region(wy * w + yi, a.H, w, a.shift) + region(wx * w + xi, a.W, w, a.shift) : 0;
+  __builtin_amdgcn_sched_barrier(0);                 // the index terms above are computed while the loads are in flight
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int c = lane + 64 * t;
     *(au32x4*)(&v_lds[wave][c * 8]) = vrow[t];
-    t_lds[wave][lane + 64 * t] = bf2f(tv[t]);
+    t_lds[wave][lane + 64 * t] = bf2f(tv[t]) * LOG2E;
   }
-  // per-query terms (the query of this lane in each query block)
-  int qa[2], rq[2];
+  // ---- S^T[kb] = K_kb Q^T
+  f32x16_t s[2];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int i = 32 * qb + l32;
-    const int yi = (int)(((float)i + 0.5f) * inv_w), xi = i - yi * w;
-    qa[qb] = yi * tw + xi + (w - 1) * 2 * w;
-    rq[qb] = a.shift > 0 ? 3 * region(wy * w + yi, a.H, w, a.shift) + region(wx * w + xi, a.W, w, a.shift) : 0;
+  for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+      s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[kb][ks]), __builtin_bit_cast(bf16x8_t, qf[ks]), s[kb], 0, 0, 0);
   }
-  // ---- S^T[kb][qb] = K_kb Q_qb^T
-  f32x16_t s[2][2];
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[kb][qb][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-        s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[kb][ks]), __builtin_bit_cast(bf16x8_t, qf[qb][ks]), s[kb][qb], 0, 0, 0);
-    }
   __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0): this wave's LDS writes are done (wave-private data)
-  // ---- bias, mask, softmax per query
-  float mx[2] = {-INFINITY, -INFINITY};
+  // ---- bias, mask, softmax for this lane's query (keys: 16 per block in this lane, the other 16 in lane ^ 32)
+  const float sc2 = a.scale * LOG2E;
+  const bool shifted = a.shift > 0;                  // wave-uniform
+  float mx = -INFINITY;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int j = 32 * kb + (i >> 2) * 8 + hf * 4 + (i & 3);
       const int info = k_lds[wave][j];
-      const int kk = info & 0xffff, rk = info >> 16;
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        float x = s[kb][qb][i] * a.scale + t_lds[wave][(qa[qb] - kk) & 255];
-        if (rq[qb] != rk) x += -100.f;
-        if (j >= n) x = -INFINITY;
-        s[kb][qb][i] = x;
-        mx[qb] = fmaxf(mx[qb], x);
-      }
+      float x = fmaf(s[kb][i], sc2, t_lds[wave][(qa - (info & 0xffff)) & 255]);
+      if (shifted && rq != (info >> 16)) x += -100.f * LOG2E;
+      if (j >= n) x = -INFINITY;
+      s[kb][i] = x;
+      mx = fmaxf(mx, x);
     }
-  au32x4 pf[2][2][2];
-  float inv[2];
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  au32x4 pf[2][2];
+  float sum = 0.f;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    mx[qb] = fmaxf(mx[qb], __shfl_xor(mx[qb], 32, 64));
-    float sum = 0.f;
+  for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int i = 0; i < 16; i += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(s[kb][i] - mx), p1 = __builtin_amdgcn_exp2f(s[kb][i + 1] - mx);
+      const f32x2_t pp = {p0, p1};
+      const bf16x2_t ph = __builtin_convertvector(pp, bf16x2_t);
+      const unsigned pw = __builtin_bit_cast(unsigned, ph);
+      sum += __uint_as_float(pw << 16) + __uint_as_float(pw & 0xffff0000u);      // the sum of what the MFMA will actually use
+      pf[kb][i >> 3][(i >> 1) & 3] = pw;
+    }
+  sum += __shfl_xor(sum, 32, 64);
+  const float inv = 1.f / sum;
+  // ---- O^T = V^T P^T
+  f32x16_t oacc;
 #pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        const bf16_t h0 = f2bf(__expf(s[kb][qb][i] - mx[qb])), h1 = f2bf(__expf(s[kb][qb][i + 1] - mx[qb]));
-        sum += bf2f(h0) + bf2f(h1);
-        pf[qb][kb][i >> 3][(i >> 1) & 3] = (unsigned)h0 | ((unsigned)h1 << 16);
-      }
-    sum += __shfl_xor(sum, 32, 64);
-    inv[qb] = 1.f / sum;
-  }
-  // ---- O^T[qb] = V^T P_qb^T; the V^T fragment of a key step is shared by both query blocks
-  f32x16_t oacc[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[qb][i] = 0.f;
+  for (int i = 0; i < 16; ++i) oacc[i] = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -479,21 +477,15 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
         const unsigned lo = v_lds[wave][ja * 32 + l32], hi = v_lds[wave][(ja + 1) * 32 + l32];
         vf[t >> 1] = lo | (hi << 16);
       }
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-        oacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf[qb][kb][ks2]), oacc[qb], 0, 0, 0);
+      oacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf[kb][ks2]), oacc, 0, 0, 0);
     }
+  if (qi >= n) return;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int i = 32 * qb + l32;
-    if (i >= n) continue;
-#pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      const int e = g4 * 8 + hf * 4;
-      const unsigned w0 = (unsigned)f2bf(oacc[qb][4 * g4] * inv[qb]) | ((unsigned)f2bf(oacc[qb][4 * g4 + 1] * inv[qb]) << 16);
-      const unsigned w1 = (unsigned)f2bf(oacc[qb][4 * g4 + 2] * inv[qb]) | ((unsigned)f2bf(oacc[qb][4 * g4 + 3] * inv[qb]) << 16);
-      *(uint2*)(op + (int64_t)i * a.o_stride[2] + e) = make_uint2(w0, w1);
-    }
+  for (int g4 = 0; g4 < 4; ++g4) {
+    const int e = g4 * 8 + hf * 4;
+    const f32x2_t x0 = {oacc[4 * g4] * inv, oacc[4 * g4 + 1] * inv}, x1 = {oacc[4 * g4 + 2] * inv, oacc[4 * g4 + 3] * inv};
+    *(uint2*)(op + (int64_t)qi * a.o_stride[2] + e) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
+                                                                __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
   }
 }
 
@@ -551,9 +543,10 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     return (int)hipGetLastError();
   }
   if (d.kind == SM_ATT_WINDOW && d.d == 32 && d.nq <= 64 && d.window <= 8) {
-    const long pairs = (long)d.nb * d.heads;
-    attn_window32_kernel<<<dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
-                                                                                (bf16_t*)o, (const bf16_t*)rpb_table, pairs);
+    const long waves = 2L * d.nb * d.heads;           // one per (window, head, query block)
+    if (waves >= (1L << 31)) return (int)hipErrorInvalidValue;
+    attn_window32_kernel<<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                                (bf16_t*)o, (const bf16_t*)rpb_table, waves);
     return (int)hipGetLastError();
   }
   if (d.kind != SM_ATT_WINDOW && d.scale > 0.f) {
