@@ -8,8 +8,10 @@
 // Tile: BM x 128 outputs per workgroup of 4 waves (2 x 2), BM = 64 * MI; each
 // wave owns MI x 2 MFMA blocks of 32 x 32.  A K-tile is 128 bytes per row
 // (64 bf16 / 32 fp32), staged through LDS in 16-byte chunks with an XOR swizzle
-// (chunk c of row r sits in slot c ^ (r & 7)) so that the 32 rows read by one
-// ds_read_b128 hit distinct banks.  Global loads of tile k+1 are issued before
+// (chunk c of row r sits in slot c ^ ((r >> 1) & 7)): the LDS has 64 banks of 4 bytes, a ds_read_b128 is served
+// 16 lanes (256 bytes) at a time, two rows span the banks once, so the sixteen consecutive rows read together must
+// put their chunk at eight different positions per row parity (the r & 7 form, right for 32 banks, measured half of
+// all LDS cycles as bank conflicts).  Global loads of tile k+1 are issued before
 // the MFMAs of tile k (register double buffering) and two LDS buffers alternate.
 //
 // Column pairing for gated activations and RoPE is done by permuting the
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
 
   if constexpr (DMA) {
     // wave-load i of this wave fills rows g8*8 .. g8*8+7 of a tile (1 KiB, 64 consecutive 16-byte slots):
-    // lane -> (row, slot position); the chunk that belongs in that slot is position ^ (row & 7)
+    // lane -> (row, slot position); the chunk that belongs in that slot is position ^ ((row >> 1) & 7)
     constexpr int LA = 2 * MI, LB = 8 / WM, STAGE = A_SLOTS + B_SLOTS;     // wave-loads per wave per stage
     const int lrow = lane >> 3, lpos = lane & 7;
     const T* a_src[LA];
@@ -161,13 +163,13 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     for (int i = 0; i < LA; ++i) {
       const int rr = (wave * LA + i) * 8 + lrow;
       const int64_t r = min(m0 + rr, g.M - 1);       // rows past M repeat the last row: their outputs are never stored
-      a_src[i] = A + (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) + (lpos ^ (rr & 7)) * VEC;
+      a_src[i] = A + (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) + (lpos ^ ((rr >> 1) & 7)) * VEC;
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
       const int rr = (wave * LB + i) * 8 + lrow;
       const int n = min(n0 + rr, g.N - 1);
-      b_src[i] = W + (int64_t)phys_col(cm, n) * g.ldw + (lpos ^ (rr & 7)) * VEC;
+      b_src[i] = W + (int64_t)phys_col(cm, n) * g.ldw + (lpos ^ ((rr >> 1) & 7)) * VEC;
     }
     auto issue = [&](int kt, int stage) {
       u32x4* st = lds + stage * STAGE;
@@ -180,9 +182,9 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     unsigned fa_addr[MI], fb_addr[2];
     int fa_x[MI], fb_x[2];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) { const int r = wm * 32 * MI + mi * 32 + l32; fa_addr[mi] = r * 128; fa_x[mi] = r & 7; }
+    for (int mi = 0; mi < MI; ++mi) { const int r = wm * 32 * MI + mi * 32 + l32; fa_addr[mi] = r * 128; fa_x[mi] = (r >> 1) & 7; }
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) { const int r = wn * 64 + ni * 32 + l32; fb_addr[ni] = (A_SLOTS + r * 8) * 16; fb_x[ni] = r & 7; }
+    for (int ni = 0; ni < 2; ++ni) { const int r = wn * 64 + ni * 32 + l32; fb_addr[ni] = (A_SLOTS + r * 8) * 16; fb_x[ni] = (r >> 1) & 7; }
     auto read_frags = [&](unsigned sbase, int j, u32x4* fa, u32x4* fb) {
       const int c = 2 * j + hf;
 #pragma unroll
@@ -301,9 +303,9 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
       u32x4* a_l = lds + buf * (A_SLOTS + B_SLOTS);
       u32x4* b_l = a_l + A_SLOTS;
 #pragma unroll
-      for (int i = 0; i < 2 * MI; ++i) { const int r = lr + 32 * i; a_l[r * 8 + (lc ^ (r & 7))] = kok[S] ? ra[S][i] : zero; }
+      for (int i = 0; i < 2 * MI; ++i) { const int r = lr + 32 * i; a_l[r * 8 + (lc ^ ((r >> 1) & 7))] = kok[S] ? ra[S][i] : zero; }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { const int r = lr + 32 * i; b_l[r * 8 + (lc ^ (r & 7))] = kok[S] ? rb[S][i] : zero; }
+      for (int i = 0; i < 4; ++i) { const int r = lr + 32 * i; b_l[r * 8 + (lc ^ ((r >> 1) & 7))] = kok[S] ? rb[S][i] : zero; }
     };
     auto compute_tile = [&](int buf) {
       const u32x4* a_l = lds + buf * (A_SLOTS + B_SLOTS);
@@ -313,9 +315,9 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
         const int c = 2 * j + hf;
         u32x4 fa[MI], fb[2];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) { const int r = wm * 32 * MI + mi * 32 + l32; fa[mi] = a_l[r * 8 + (c ^ (r & 7))]; }
+        for (int mi = 0; mi < MI; ++mi) { const int r = wm * 32 * MI + mi * 32 + l32; fa[mi] = a_l[r * 8 + (c ^ ((r >> 1) & 7))]; }
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) { const int r = wn * 64 + ni * 32 + l32; fb[ni] = b_l[r * 8 + (c ^ (r & 7))]; }
+        for (int ni = 0; ni < 2; ++ni) { const int r = wn * 64 + ni * 32 + l32; fb[ni] = b_l[r * 8 + (c ^ ((r >> 1) & 7))]; }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
