@@ -32,6 +32,8 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+struct TileOrder { int tiles_m, tiles_n, strip, group; };
+
 struct ColMap {      // logical column n' -> physical W row / output column
   int mode;          // 0 identity, 1 gated halves, 2 rope
   int half;          // gated: N / 2
@@ -100,7 +102,7 @@ enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
 // WM = waves along M (2 or 4): the workgroup has 2 * WM waves and a tile of 32 * MI * WM rows.  The 8-wave shape
 // (256 x 128) halves the L2 -> LDS traffic per flop of the 4-wave one and is used where the grid is large enough.
 template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM, int NS>
-__global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm, int tiles_n) {
+__global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm, TileOrder ts) {
   const SM_KARG GemmArgs* gk = kernarg_ptr<GemmArgs>();      // g is the first argument
   constexpr int VEC = Elem<T>::VEC;
   constexpr int BM = 32 * MI * WM, BN = 128, BK = 8 * VEC;
@@ -109,12 +111,22 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, hf = lane >> 5;
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous range of
-  // tiles (column tiles fastest) so that the tiles sharing an A row panel share one L2.
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The tiles are put in an order in which
+  // (1) every XCD owns one contiguous run (so what it fetches through its L2 is a compact block of the tile grid:
+  // the grid is cut into strips of `ts.strip` column tiles, as many strips as make the sum of the XCDs' A and W
+  // panels smallest), and (2) inside a strip the tiles that are resident together form blocks of `ts.group` row
+  // tiles by several column tiles rather than one long row, which shares both operands' panels between them.
   const int n_tiles = gridDim.x;
   const int xcd = blockIdx.x & 7, q8 = n_tiles >> 3, r8 = n_tiles & 7;
-  const int tile_id = xcd * q8 + min(xcd, r8) + (blockIdx.x >> 3);    // XCD x owns q8 (+1 if x < r8) consecutive tiles
-  const int tile_m = tile_id / tiles_n, tile_n = tile_id - tile_m * tiles_n;
+  const int t = xcd * q8 + min(xcd, r8) + (blockIdx.x >> 3);          // XCD x owns q8 (+1 if x < r8) consecutive positions
+  const int strip_tiles = ts.strip * ts.tiles_m;
+  const int sidx = min(t / strip_tiles, (ts.tiles_n - 1) / ts.strip);
+  const int rem = t - sidx * strip_tiles;
+  const int sw = min(ts.strip, ts.tiles_n - sidx * ts.strip);         // width of this strip
+  const int gidx = rem / (ts.group * sw), r2 = rem - gidx * ts.group * sw;
+  const int gh = min(ts.group, ts.tiles_m - gidx * ts.group);         // height of this group of rows
+  const int gcol = r2 / gh;
+  const int tile_m = gidx * ts.group + (r2 - gcol * gh), tile_n = sidx * ts.strip + gcol;
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
   const T* A = (const T*)g.A;
@@ -527,10 +539,23 @@ static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   constexpr int BM = 32 * MI * WM;
   const int tiles_n = (g.N + 127) / 128;
   const int64_t tiles_m = (g.M + BM - 1) / BM;
+  if (tiles_m * tiles_n > INT32_MAX) return (int)hipErrorInvalidValue;
   const size_t smem = (size_t)NS * (BM * 8 + 128 * 8) * sizeof(u32x4);
+  // strips: xn of them, 8 / xn XCDs per strip; an XCD then reads M / (8 / xn) rows of A and N / xn rows of W, in
+  // total xn M + (8 / xn) N rows of K elements: take the xn that makes that smallest
+  int xn = 1;
+  double best = 1e300;
+  for (int c = 1; c <= 8; c *= 2) {
+    const double rows = (double)c * (double)g.M + (8.0 / c) * (double)g.N;
+    if (rows < best && c <= tiles_n) { best = rows; xn = c; }
+  }
+  TileOrder ts;
+  ts.tiles_m = (int)tiles_m; ts.tiles_n = tiles_n;
+  ts.strip = (tiles_n + xn - 1) / xn;
+  ts.group = (int)std::min<int64_t>(4, tiles_m);
   static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return (int)attr;
-  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, tiles_n);
+  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, ts);
   return (int)hipGetLastError();
 }
 
