@@ -179,9 +179,11 @@ int sm_norm(const void* x, const void* gamma, const void* beta, void* y, int64_t
             int rms, int dtype, const sm_map* store_map, void* stream);
 /* GroupNorm over x NCHW [B, C, H, W] with G groups.  tokens_out = 0: y is NCHW;
  * tokens_out = 1: y is written token-major [B, H*W, C] (the layout a following
- * MatMul over C prefers). */
+ * MatMul over C prefers).  stats_scratch (nullable): device memory for 2 * B * G
+ * floats; with it the work runs as two fully parallel kernels (statistics, then
+ * apply with whole-row stores) instead of one workgroup per (image, group). */
 int sm_groupnorm(const void* x, const void* gamma, const void* beta, void* y, int B, int C, int HW, int G,
-                 float eps, int tokens_out, int dtype, void* stream);
+                 float eps, int tokens_out, int dtype, void* stats_scratch, void* stream);
 
 /* Epilogue of sm_linear, applied in this order to acc = A.W^T:
  * +bias[n]; activation; RoPE; *gate; +residual. */

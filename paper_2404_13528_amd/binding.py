@@ -248,12 +248,14 @@ def norm(x, gamma, beta=None, eps=1e-5, rms=False, store_map=None, out=None, str
     return y
 
 
-def groupnorm(x, gamma, beta, G, eps=1e-6, tokens_out=False, stream=None):
+def groupnorm(x, gamma, beta, G, eps=1e-6, tokens_out=False, split=False, stream=None):
+    """split=True passes scratch for the statistics: two fully parallel kernels instead of one workgroup per group."""
     import torch
     B, Cc, H, W = x.shape
     y = torch.empty((B, H * W, Cc) if tokens_out else x.shape, dtype=x.dtype, device=x.device)
+    stats = torch.empty(2 * B * G, dtype=torch.float32, device=x.device) if split else None
     check(lib().sm_groupnorm(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), B, Cc, H * W, G, C.c_float(eps),
-                             int(tokens_out), _dt(x), _stream(stream)), "sm_groupnorm")
+                             int(tokens_out), _dt(x), _ptr(stats), _stream(stream)), "sm_groupnorm")
     return y
 
 

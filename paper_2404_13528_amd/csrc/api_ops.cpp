@@ -115,15 +115,16 @@ extern "C" int sm_norm(const void* x, const void* gamma, const void* beta, void*
 }
 
 extern "C" int sm_groupnorm(const void* x, const void* gamma, const void* beta, void* y, int B, int C, int HW, int G,
-                            float eps, int tokens_out, int dtype, void* stream) {
+                            float eps, int tokens_out, int dtype, void* stats_scratch, void* stream) {
   if (!x || !gamma || !beta || !y) return fail(SM_ERR_INVALID_ARG, "sm_groupnorm: null pointer");
   if (!dtype_ok(dtype)) return fail(SM_ERR_INVALID_ARG, "sm_groupnorm: unknown dtype");
   if (B < 1 || C < 1 || HW < 1 || G < 1 || C % G) return fail(SM_ERR_SHAPE, "sm_groupnorm: bad shape");
-  GroupNormArgs a{x, gamma, beta, y, B, C, HW, G, eps, tokens_out, dtype};
+  if (stats_scratch && (!aligned16(x) || !aligned16(y))) return fail(SM_ERR_INVALID_ARG, "sm_groupnorm: pointers must be 16-byte aligned");
+  GroupNormArgs a{x, gamma, beta, y, B, C, HW, G, eps, tokens_out, dtype, (float*)stats_scratch};
   Timed tm("groupnorm", stream);
   int rc = launch_groupnorm(a, stream);
   if (rc) return fail(SM_ERR_DEVICE, "sm_groupnorm: launch failed (hip error %d)", rc);
-  count_compute();
+  count_compute(groupnorm_launches(a));
   return SM_OK;
 }
 

@@ -234,6 +234,7 @@ Sizes sizes(const sm_attn_cfg* c, int mode) {
   // buffers: n (1), qkv (3), o (1), r1, r2, r3 (3), act (F); explicit adds qkv' (3), o' (1), extra (1), ctx copies
   const size_t units = mode == SM_EXPLICIT ? 13 : 8;
   z.total = units * z.te + z.tf + 2 * z.ctx;
+  if (c->kind == SM_ATTN_SD) z.total += align256((size_t)2 * c->B * c->groups * sizeof(float));      // GroupNorm statistics
   return z;
 }
 
@@ -300,7 +301,7 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
   void *qkvp = nullptr, *op = nullptr, *extra = nullptr;
   if (mode == SM_EXPLICIT) { qkvp = after; op = after + 3 * z.te; extra = after + 4 * z.te; after += 5 * z.te; }
   void* act = after; after += z.tf;
-  void* kv = after; void* kvp = after + z.ctx;
+  void* kv = after; char* kvp = after + z.ctx;
   const bool el = mode == SM_ELIDED;
 
   if (c->kind == SM_ATTN_LLAMA) {
@@ -323,13 +324,13 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
 
   // ---- spatial transformer
   const int Sc = c->Sc;
-  GroupNormArgs ga{x, w[0], w[1], el ? o : extra, B, E, S, c->groups, c->eps_gn, el ? 1 : 0, dt};
+  GroupNormArgs ga{x, w[0], w[1], el ? o : extra, B, E, S, c->groups, c->eps_gn, el ? 1 : 0, dt, (float*)(kvp + z.ctx)};
   {
     Timed tm("groupnorm", stream);
     int lrc = launch_groupnorm(ga, stream);
     if (lrc) return fail(SM_ERR_DEVICE, "sm_attn_block: GroupNorm launch failed (hip error %d)", lrc);
   }
-  count_compute();
+  count_compute(groupnorm_launches(ga));
   if (!el) { if ((rc = copy_launch(plan->to_tokens, extra, o, dt, stream))) return rc; }
   if ((rc = gemm(o, w[2], w[3], nullptr, r1, T, E, E, dt, SM_ACT_NONE, stream))) return rc;                     // proj_in -> t0
   if ((rc = norm(r1, w[4], w[5], n, T, E, c->eps_norm, 0, dt, stream))) return rc;

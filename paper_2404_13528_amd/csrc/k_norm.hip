@@ -191,7 +191,131 @@ __global__ __launch_bounds__(512) void groupnorm_kernel(GroupNormArgs a) {
   }
 }
 
+// ---- GroupNorm in two kernels (the caller provides scratch for the statistics): every CU takes part, all
+// global accesses are 16-byte vectors, and the token-major store goes through an LDS transpose so that it writes
+// whole token rows.
+template <typename T>
+__global__ __launch_bounds__(512) void gn_stats_kernel(GroupNormArgs a) {
+  __shared__ float red[8];
+  constexpr int VEC = Elem<T>::VEC;
+  typedef typename Vec16<T>::type V;
+  const int cpg = a.C / a.G;
+  const int64_t nv = (int64_t)cpg * a.HW / VEC;                 // the group is one contiguous run of cpg * HW elements
+  const V* x = (const V*)((const T*)a.x + (int64_t)blockIdx.x * cpg * a.HW);
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < nv; i += blockDim.x) {
+    float f[VEC];
+    unpack<T>(x[i], f);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s += f[e];
+  }
+  const float mean = block_sum(s, red) / (float)(nv * VEC);
+  float ss = 0.f;
+  for (int64_t i = threadIdx.x; i < nv; i += blockDim.x) {      // second pass over data that is in L2 by now
+    float f[VEC];
+    unpack<T>(x[i], f);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { const float d = f[e] - mean; ss += d * d; }
+  }
+  const float var = block_sum(ss, red) / (float)(nv * VEC);
+  if (threadIdx.x == 0) { a.stats[2 * blockIdx.x] = mean; a.stats[2 * blockIdx.x + 1] = rsqrtf(var + a.eps); }
+}
+
+// channel-major in, channel-major out: one thread per 16-byte vector
+template <typename T>
+__global__ __launch_bounds__(256) void gn_apply_nchw_kernel(GroupNormArgs a) {
+  constexpr int VEC = Elem<T>::VEC;
+  typedef typename Vec16<T>::type V;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int vpc = a.HW / VEC;                                   // vectors per channel
+  if (i >= (int64_t)a.B * a.C * vpc) return;
+  const int64_t bc = i / vpc;                                   // image * C + channel
+  const int c = (int)(bc % a.C), b = (int)(bc / a.C);
+  const int g = c / (a.C / a.G);
+  const float mean = a.stats[2 * (b * a.G + g)], rstd = a.stats[2 * (b * a.G + g) + 1];
+  const float ga = Elem<T>::ld((const T*)a.gamma + c) * rstd, be = Elem<T>::ld((const T*)a.beta + c) - mean * ga;
+  float f[VEC];
+  unpack<T>(((const V*)a.x)[i], f);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) f[e] = fmaf(f[e], ga, be);
+  ((V*)a.y)[i] = pack<T>(f);
+}
+
+// channel-major in, token-major out: a workgroup owns TT tokens of one image, all channels
+template <typename T, int TT>
+__global__ __launch_bounds__(256) void gn_apply_tokens_kernel(GroupNormArgs a) {
+  constexpr int VEC = Elem<T>::VEC;
+  typedef typename Vec16<T>::type V;
+  extern __shared__ __align__(16) unsigned char gn_lds[];
+  T* tile = (T*)gn_lds;                                          // [TT][C + VEC]
+  const int pitch = a.C + VEC;
+  const int b = blockIdx.y, t0 = blockIdx.x * TT;
+  const int cpg = a.C / a.G;
+  constexpr int TV = TT / VEC;                                   // vectors per channel inside the tile
+  const T* x = (const T*)a.x + (int64_t)b * a.C * a.HW;
+  for (int p = threadIdx.x; p < a.C * TV; p += 256) {
+    const int c = p / TV, tv = p - c * TV;
+    const int t = t0 + tv * VEC;
+    if (t >= a.HW) continue;                                     // HW is a multiple of VEC: a vector is inside or outside
+    const int g = c / cpg;
+    const float mean = a.stats[2 * (b * a.G + g)], rstd = a.stats[2 * (b * a.G + g) + 1];
+    const float ga = Elem<T>::ld((const T*)a.gamma + c) * rstd, be = Elem<T>::ld((const T*)a.beta + c) - mean * ga;
+    float f[VEC];
+    unpack<T>(*(const V*)(x + (int64_t)c * a.HW + t), f);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) Elem<T>::st(tile + (tv * VEC + e) * pitch + c, fmaf(f[e], ga, be));
+  }
+  __syncthreads();
+  const int cv = a.C / VEC;                                      // vectors per token row
+  T* y = (T*)a.y + ((int64_t)b * a.HW + t0) * a.C;
+  for (int p = threadIdx.x; p < TT * cv; p += 256) {
+    const int t = p / cv, c8 = p - t * cv;
+    if (t0 + t >= a.HW) break;
+    *(V*)(y + (int64_t)t * a.C + c8 * VEC) = *(const V*)(tile + t * pitch + c8 * VEC);
+  }
+}
+
+static bool groupnorm_split(const GroupNormArgs& a) {
+  const int vec = a.dtype == SM_F32 ? 4 : 8;
+  const size_t es = a.dtype == SM_F32 ? 4 : 2;
+  return a.stats && a.HW % vec == 0 && a.C % vec == 0 && (size_t)32 * (a.C + vec) * es <= 160 * 1024;
+}
+int groupnorm_launches(const GroupNormArgs& a) { return groupnorm_split(a) ? 2 : 1; }
+
+template <typename T>
+static int groupnorm_split_launch(const GroupNormArgs& a, hipStream_t s) {
+  constexpr int VEC = Elem<T>::VEC;
+  gn_stats_kernel<T><<<dim3((unsigned)(a.B * a.G)), dim3(512), 0, s>>>(a);
+  if (!a.tokens_out) {
+    const int64_t nv = (int64_t)a.B * a.C * (a.HW / VEC);
+    gn_apply_nchw_kernel<T><<<dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, s>>>(a);
+    return (int)hipGetLastError();
+  }
+  const size_t row = (size_t)(a.C + VEC) * sizeof(T);
+  if (64 * row <= 160 * 1024) {
+    const size_t smem = 64 * row;
+    static size_t granted = 0;
+    if (smem > granted) {
+      const hipError_t e = hipFuncSetAttribute((const void*)gn_apply_tokens_kernel<T, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return (int)e;
+      granted = smem;
+    }
+    gn_apply_tokens_kernel<T, 64><<<dim3((unsigned)((a.HW + 63) / 64), (unsigned)a.B), dim3(256), smem, s>>>(a);
+  } else {
+    const size_t smem = 32 * row;
+    static size_t granted = 0;
+    if (smem > granted) {
+      const hipError_t e = hipFuncSetAttribute((const void*)gn_apply_tokens_kernel<T, 32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return (int)e;
+      granted = smem;
+    }
+    gn_apply_tokens_kernel<T, 32><<<dim3((unsigned)((a.HW + 31) / 32), (unsigned)a.B), dim3(256), smem, s>>>(a);
+  }
+  return (int)hipGetLastError();
+}
+
 int launch_groupnorm(const GroupNormArgs& a, void* stream) {
+  if (groupnorm_split(a)) return a.dtype == SM_F32 ? groupnorm_split_launch<float>(a, (hipStream_t)stream) : groupnorm_split_launch<bf16_t>(a, (hipStream_t)stream);
   dim3 grid((unsigned)(a.B * a.G)), block(512);
   if (a.dtype == SM_F32) groupnorm_kernel<float><<<grid, block, 0, (hipStream_t)stream>>>(a);
   else groupnorm_kernel<bf16_t><<<grid, block, 0, (hipStream_t)stream>>>(a);

@@ -26,8 +26,12 @@ struct NormArgs {
 };
 int launch_norm(const NormArgs& a, void* stream);
 
-struct GroupNormArgs { const void* x; const void* gamma; const void* beta; void* y; int B, C, HW, G; float eps; int tokens_out; int dtype; };
-int launch_groupnorm(const GroupNormArgs& a, void* stream);
+struct GroupNormArgs {
+  const void* x; const void* gamma; const void* beta; void* y; int B, C, HW, G; float eps; int tokens_out; int dtype;
+  float* stats;      // device scratch of 2 * B * G floats, or null: with it the work is split into a statistics kernel and a
+};                   // fully parallel apply kernel (two launches) instead of one workgroup per (image, group)
+int launch_groupnorm(const GroupNormArgs& a, void* stream);      // returns the hip error; *launches (if given) = kernels enqueued
+int groupnorm_launches(const GroupNormArgs& a);
 
 struct GemmArgs {
   const void* A; const void* W; const void* bias; const void* residual; void* C;

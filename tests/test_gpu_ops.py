@@ -49,12 +49,15 @@ def test_layernorm_store_through_window_map(dtype, s):
 
 @pytest.mark.parametrize("dtype", DT)
 @pytest.mark.parametrize("tokens_out", [False, True])
-def test_groupnorm(dtype, tokens_out):
-    B, C, H, W, G = 2, 64, 9, 7, 8
+@pytest.mark.parametrize("split", [False, True])
+@pytest.mark.parametrize("B,C,H,W,G", [(2, 64, 9, 7, 8), (2, 320, 8, 12, 32), (1, 40, 16, 13, 4)])
+def test_groupnorm(dtype, tokens_out, split, B, C, H, W, G):
+    # the second and third shapes take the two-kernel path when split is set (H W a multiple of the vector width),
+    # with token tiles of 64 that end ragged (96 and 208 tokens)
     x = draw((B, C, H, W), 7, dtype, 2.0, -0.5)
     g = draw((C,), 8, dtype, 0.2, 1.0)
     b = draw((C,), 9, dtype, 0.2)
-    y = sm.groupnorm(dev(x, dtype), dev(g, dtype), dev(b, dtype), G, tokens_out=tokens_out)
+    y = sm.groupnorm(dev(x, dtype), dev(g, dtype), dev(b, dtype), G, tokens_out=tokens_out, split=split)
     want = O.group_norm_nchw(to_np(x), G, to_np(g), to_np(b))
     if tokens_out:
         want = V.apply_chain(want, V.nchw_to_tokens_chain(B, C, H, W))
