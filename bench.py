@@ -26,12 +26,12 @@ PEAK_BF16 = 2.5e15         # FLOP/s dense bf16 MFMA, MI355X published
 # HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (bytes, scaled by the
 # copy-kernel calibration described in the design doc); filled from profiles/, None = not measured.
 MEASURED_TRAFFIC = {
-    # profiles/swin_stage3_chain_b32_hbm_counters.md: (FETCH_SIZE KiB x 1.982 + WRITE_SIZE KiB x 1.000) x 1024
-    "gemm_bf16[6272,1536,384]+gelu": int((7304.6 * 1.982 + 18816.0) * 1024),
-    "gemm_bf16[6272,1152,384]": int((6445.5 * 1.982 + 14112.0) * 1024),
-    "attention_window_bf16[128,12,49,49,32]": int((7234.5 * 1.982 + 4704.0) * 1024),
-    "layernorm_bf16[6272,384]": int((2432.3 * 1.982 + 4704.0) * 1024),
-    "layernorm_bf16[6272,384]+scatter": int((2432.3 * 1.982 + 4704.0) * 1024),
+    # profiles/swin_stage3_chain_b32_hbm_counters.md: (FETCH_SIZE KiB x 2.000 + WRITE_SIZE KiB x 1.000) x 1024
+    "gemm_bf16[6272,1536,384]+gelu": int((7315.1 * 2.0 + 18816.0) * 1024),
+    "gemm_bf16[6272,1152,384]": int((6457.5 * 2.0 + 14112.0) * 1024),
+    "attention_window_bf16[128,12,49,49,32]": int((7137.5 * 2.0 + 4704.0) * 1024),
+    "layernorm_bf16[6272,384]": int((2437.3 * 2.0 + 4704.0) * 1024),
+    "layernorm_bf16[6272,384]+scatter": int((2437.3 * 2.0 + 4704.0) * 1024),
 }
 
 

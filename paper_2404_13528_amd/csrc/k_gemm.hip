@@ -552,7 +552,9 @@ static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   TileOrder ts;
   ts.tiles_m = (int)tiles_m; ts.tiles_n = tiles_n;
   ts.strip = (tiles_n + xn - 1) / xn;
-  ts.group = (int)std::min<int64_t>(4, tiles_m);
+  // row groups pay where the operand panels are long (they then exceed what the L2 keeps between tiles); with short
+  // panels the plain row-major order inside a strip fetched less (measured on the K = 384 shapes)
+  ts.group = g.K >= 1024 ? (int)std::min<int64_t>(4, tiles_m) : 1;
   static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return (int)attr;
   gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, ts);
