@@ -200,6 +200,13 @@ typedef struct {
                                    offset = (r / c_batch_rows) * N * c_batch_rows + n * c_batch_rows + r % c_batch_rows
                                    (NCHW store); residual is read the same way */
   int64_t c_batch_rows;
+  int32_t norm;                 /* 0 none; 1 LayerNorm, 2 RMSNorm over K of every row of A, applied while A is loaded: the norm
+                                   that precedes the Linear folded into it (activation none or GELU only, no RoPE).
+                                   A's rows are normalised in fp32 and rounded to the element type before the product,
+                                   exactly as a separate sm_norm would have stored them */
+  float norm_eps;
+  const void* norm_gamma;       /* [K], device; required when norm != 0 */
+  const void* norm_beta;        /* [K], device; nullable (ignored by RMSNorm) */
 } sm_linear_desc;
 /* a_map / c_map (nullable): maps with view shape [M, K] / natural output shape
  * [M, Nout] whose last dimension is contiguous: row r of A is read at

@@ -45,7 +45,8 @@ class ViewOp(C.Structure):
 class LinearDesc(C.Structure):
     _fields_ = [("M", C.c_int64), ("N", C.c_int32), ("K", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
                 ("rope_cols", C.c_int32), ("rope_dim", C.c_int32), ("rope_seq", C.c_int32), ("rope_base", C.c_float),
-                ("c_transposed", C.c_int32), ("c_batch_rows", C.c_int64)]
+                ("c_transposed", C.c_int32), ("c_batch_rows", C.c_int64),
+                ("norm", C.c_int32), ("norm_eps", C.c_float), ("norm_gamma", C.c_void_p), ("norm_beta", C.c_void_p)]
 
 
 class AttentionDesc(C.Structure):
@@ -260,8 +261,9 @@ def groupnorm(x, gamma, beta, G, eps=1e-6, tokens_out=False, split=False, stream
 
 
 def linear(A, W, bias=None, residual=None, act="none", rope=None, a_map=None, c_map=None,
-           c_transposed_batch=0, out=None, M=None, stream=None):
-    """C = epilogue(A . W^T).  rope = (rope_cols, rope_dim, seq, base) or None."""
+           c_transposed_batch=0, out=None, M=None, norm=None, stream=None):
+    """C = epilogue(A . W^T).  rope = (rope_cols, rope_dim, seq, base) or None.
+    norm = ("layer" | "rms", gamma, beta or None, eps): that norm of A's rows folded into the load."""
     import torch
     N, K = W.shape
     if M is None:
@@ -271,6 +273,9 @@ def linear(A, W, bias=None, residual=None, act="none", rope=None, a_map=None, c_
     d.M, d.N, d.K, d.dtype, d.act = M, N, K, _dt(A), ACT[act]
     if rope:
         d.rope_cols, d.rope_dim, d.rope_seq, d.rope_base = rope
+    if norm:
+        d.norm = 1 if norm[0] == "layer" else 2
+        d.norm_gamma, d.norm_beta, d.norm_eps = _ptr(norm[1]).value, _ptr(norm[2]).value, norm[3]
     d.c_transposed = 1 if c_transposed_batch else 0
     d.c_batch_rows = c_transposed_batch
     Cm = torch.empty((M, n_out), dtype=A.dtype, device=A.device) if out is None else out

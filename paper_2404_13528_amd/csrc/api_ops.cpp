@@ -49,6 +49,13 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   if (g.c_cols_on && (g.c_transposed || g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU)) return fail(SM_ERR_UNSUPPORTED, "%s: column-splitting store with a gated activation or transposed store", who);
   if (g.a_gran > 0 && (g.act != SM_ACT_NONE || g.rope_cols)) return fail(SM_ERR_UNSUPPORTED, "%s: activation or RoPE with an unfolded A operand", who);
   if (gated && g.rope_cols) return fail(SM_ERR_UNSUPPORTED, "%s: RoPE with a gated activation", who);
+  if (g.norm) {
+    if (g.norm != 1 && g.norm != 2) return fail(SM_ERR_INVALID_ARG, "%s: unknown norm %d", who, g.norm);
+    if (gated || g.rope_cols || g.a_gran > 0) return fail(SM_ERR_UNSUPPORTED, "%s: a folded norm goes with activation none or GELU only, without RoPE or an unfolded A", who);
+    if (!g.norm_gamma || !aligned16(g.norm_gamma) || (g.norm_beta && !aligned16(g.norm_beta)))
+      return fail(SM_ERR_INVALID_ARG, "%s: folded norm needs a 16-byte aligned gamma (and beta, if given)", who);
+    if (!(g.norm_eps > 0.f)) return fail(SM_ERR_INVALID_ARG, "%s: folded norm needs eps > 0", who);
+  }
   if (g.rope_cols) {
     if (g.rope_dim < 64 || g.rope_dim % 64 || g.rope_cols % g.rope_dim || g.rope_cols > g.N || g.rope_seq < 1)
       return fail(SM_ERR_SHAPE, "%s: RoPE needs head size a multiple of 64 and whole heads", who);
@@ -58,7 +65,7 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
     return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
   if ((int64_t)g.N * g.ldw > INT32_MAX * 16LL) return fail(SM_ERR_UNSUPPORTED, "%s: weight too large", who);
   char label[128];
-  snprintf(label, sizeof(label), "gemm_%s[%lld,%d,%d]%s%s%s", g.dtype == SM_F32 ? "f32" : "bf16", (long long)g.M, g.N, g.K,
+  snprintf(label, sizeof(label), "%sgemm_%s[%lld,%d,%d]%s%s%s", g.norm == 1 ? "ln+" : (g.norm == 2 ? "rms+" : ""), g.dtype == SM_F32 ? "f32" : "bf16", (long long)g.M, g.N, g.K,
            g.act == SM_ACT_GELU ? "+gelu" : (g.act ? "+glu" : ""), g.residual ? "+res" : "", g.c_rows.identity ? "" : "+scatter");
   Timed tm(label, stream);
   int rc = launch_gemm(g, stream);
@@ -136,6 +143,7 @@ extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, 
   g.M = d->M; g.N = d->N; g.K = d->K; g.dtype = d->dtype; g.act = d->act;
   g.rope_cols = d->rope_cols; g.rope_dim = d->rope_dim; g.rope_seq = d->rope_seq; g.rope_base = d->rope_base;
   g.c_transposed = d->c_transposed; g.c_batch_rows = d->c_batch_rows; g.ldw = d->K;
+  g.norm = d->norm; g.norm_eps = d->norm_eps; g.norm_gamma = d->norm_gamma; g.norm_beta = d->norm_beta;
   const int n_out = (d->act == SM_ACT_SWIGLU || d->act == SM_ACT_GEGLU) ? d->N / 2 : d->N;
   int rc = rows_of(a_map, d->M, d->K, d->K, &g.a_rows, "sm_linear(A)");
   if (rc == SM_ERR_UNSUPPORTED && a_map && d->K % 4 == 0) {

@@ -28,6 +28,8 @@ struct SwinPlan {
   // elided: what sm_layout_plan decided for the block's operator graph
   RowProg ln1_store;     // natural token row -> row offset in the window-major tensor
   RowProg proj_store;    // window-major row -> row offset in the natural tensor
+  RowProg x_gather;      // window-major row -> row offset in the natural tensor, roll included: the A-load of QKV when
+                         // LayerNorm-1 is folded into it (the map LayerNorm's store would have applied, read side)
   int64_t qkv_base[3], qkv_stride[3][3], o_stride[3];   // q, k, v and o as strided views [B_, h, N, d]
   // explicit
   bool has_roll;
@@ -122,6 +124,7 @@ std::shared_ptr<SwinPlan> swin_plan(const sm_swin_cfg& c, std::string* err) {
     if (!m || !m->affine(&obase, st8) || st8[3] != 1 || obase != 0) { *err = "attention output is not a strided view"; return nullptr; }
     for (int j = 0; j < 3; ++j) p->o_stride[j] = st8[j];
   }
+  if (!make_rows({B, H, W, C}, chains::window_partition(B, H, W, C, w, s), &p->x_gather, err)) return nullptr;
   // explicit: one copy per transformation that moves data
   p->has_roll = s != 0;
   if (s) {
@@ -162,15 +165,23 @@ int run_norm(const void* x, const void* g, const void* b, void* y, int64_t rows,
   return norm_checked(a, stream, "norm");
 }
 
+// ln_g != null: LayerNorm (gamma ln_g, beta ln_b, eps) of A's rows folded into the load
 int run_gemm(const void* A, const void* W, const void* bias, const void* res, void* C, int64_t M, int N, int K, int dtype,
-             int act, const RowProg* a_rows, const RowProg* c_rows, void* stream) {
+             int act, const RowProg* a_rows, const RowProg* c_rows, void* stream,
+             const void* ln_g = nullptr, const void* ln_b = nullptr, float ln_eps = 0.f) {
   GemmArgs g; std::memset(&g, 0, sizeof(g));
   g.A = A; g.W = W; g.bias = bias; g.residual = res; g.C = C; g.M = M; g.N = N; g.K = K; g.dtype = dtype; g.act = act; g.ldw = K;
+  if (ln_g) { g.norm = 1; g.norm_gamma = ln_g; g.norm_beta = ln_b; g.norm_eps = ln_eps; }
   const int n_out = (act == SM_ACT_SWIGLU || act == SM_ACT_GEGLU) ? N / 2 : N;
   g.a_rows = a_rows ? *a_rows : identity_rows(K);
   g.c_rows = c_rows ? *c_rows : identity_rows(n_out);
   return gemm_checked(g, stream, "linear");
 }
+
+// A LayerNorm is folded into the Linear that consumes it where that is faster than two kernels: the folded Linear
+// stages A through registers (slower per tile than the LDS-DMA path) and repeats the norm per column tile, so it
+// wins only while the Linear has few column tiles (measured: up to N = 512).
+bool fold_norm(int n_cols) { return n_cols <= 512; }
 
 }  // namespace
 
@@ -208,8 +219,12 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
 
   if (mode == SM_ELIDED) {
     void* bufA = base; void* qkv = base + tc; void* bufO = base + 4 * tc; void* x1 = base + 5 * tc; void* hid = base + 6 * tc;
-    if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, bufA, T, C, eps, 0, dt, nullptr, 1, &plan->ln1_store, stream))) return rc;
-    if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    if (fold_norm(3 * C)) {
+      if ((rc = run_gemm(x, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, &plan->x_gather, nullptr, stream, wt->ln1_g, wt->ln1_b, eps))) return rc;
+    } else {
+      if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, bufA, T, C, eps, 0, dt, nullptr, 1, &plan->ln1_store, stream))) return rc;
+      if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    }
     const size_t es = dtype_size(dt);
     for (int i = 0; i < 3; ++i) {
       ad.q_stride[i] = plan->qkv_stride[0][i]; ad.k_stride[i] = plan->qkv_stride[1][i]; ad.v_stride[i] = plan->qkv_stride[2][i];
@@ -218,19 +233,27 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
     if ((rc = attention_checked(ad, (char*)qkv + plan->qkv_base[0] * es, (char*)qkv + plan->qkv_base[1] * es, (char*)qkv + plan->qkv_base[2] * es,
                                 bufO, wt->rpb_table, stream, "window attention"))) return rc;
     if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
-    if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, bufA, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
-    if ((rc = run_gemm(bufA, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;
+    if (fold_norm(c->mlp_ratio * C)) {
+      if ((rc = run_gemm(x1, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream, wt->ln2_g, wt->ln2_b, eps))) return rc;
+    } else {
+      if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, bufA, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+      if ((rc = run_gemm(bufA, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;
+    }
     if ((rc = run_gemm(hid, wt->w2, wt->b2, x1, y, T, C, c->mlp_ratio * C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
     return SM_OK;
   }
 
   void* s0 = base; void* s1 = base + tc; void* s2 = base + 2 * tc; void* s3 = base + 3 * tc;
   void* qkv = base + 4 * tc; void* qkvp = base + 7 * tc; void* x1 = base + 10 * tc; void* hid = base + 11 * tc;
-  if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
-  void* cur = s0;
-  if (plan->has_roll) { if ((rc = copy_launch(plan->roll, s0, s1, dt, stream))) return rc; cur = s1; }
+  // (a row-wise norm commutes with the row permutations that follow it: where LayerNorm-1 is folded into QKV the
+  // copies move x itself)
+  const bool f1 = fold_norm(3 * C);
+  const void* cur = x;
+  if (!f1) { if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc; cur = s0; }
+  if (plan->has_roll) { if ((rc = copy_launch(plan->roll, cur, s1, dt, stream))) return rc; cur = s1; }
   if ((rc = copy_launch(plan->partition, cur, s2, dt, stream))) return rc;
-  if ((rc = run_gemm(s2, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+  if ((rc = run_gemm(s2, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream,
+                     f1 ? wt->ln1_g : nullptr, wt->ln1_b, eps))) return rc;
   if ((rc = copy_launch(plan->head_split, qkv, qkvp, dt, stream))) return rc;          // [3, B_, h, N, d]
   ad.q_stride[0] = ad.k_stride[0] = ad.v_stride[0] = ad.o_stride[0] = (int64_t)h * N * d;
   ad.q_stride[1] = ad.k_stride[1] = ad.v_stride[1] = ad.o_stride[1] = (int64_t)N * d;
@@ -245,8 +268,12 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
   } else {
     if ((rc = copy_launch(plan->reverse, s2, x1, dt, stream, x))) return rc;
   }
-  if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
-  if ((rc = run_gemm(s0, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;
+  if (fold_norm(c->mlp_ratio * C)) {
+    if ((rc = run_gemm(x1, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream, wt->ln2_g, wt->ln2_b, eps))) return rc;
+  } else {
+    if ((rc = run_norm(x1, wt->ln2_g, wt->ln2_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
+    if ((rc = run_gemm(s0, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream))) return rc;
+  }
   if ((rc = run_gemm(hid, wt->w2, wt->b2, x1, y, T, C, c->mlp_ratio * C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
   return SM_OK;
 }

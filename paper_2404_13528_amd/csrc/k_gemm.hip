@@ -101,7 +101,9 @@ enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
 // LDS latency of step j+1 hides behind the MFMAs of step j.
 // WM = waves along M (2 or 4): the workgroup has 2 * WM waves and a tile of 32 * MI * WM rows.  The 8-wave shape
 // (256 x 128) halves the L2 -> LDS traffic per flop of the 4-wave one and is used where the grid is large enough.
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM, int NS>
+// LNF (register path): LayerNorm / RMSNorm of A's rows folded into the load: row statistics in the prologue, the
+// chunks normalised between their arrival in registers and the LDS store.
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM, int NS, bool LNF>
 __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm, TileOrder ts) {
   const SM_KARG GemmArgs* gk = kernarg_ptr<GemmArgs>();      // g is the first argument
   constexpr int VEC = Elem<T>::VEC;
@@ -282,6 +284,63 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     u32x4 ra[2][2 * MI], rb[2][4];
     bool kok[2] = {true, true};      // chunk of the staged tile lies inside K (zeroed when stored otherwise)
     const u32x4 zero = {0u, 0u, 0u, 0u};
+    // folded norm: statistics of this thread's rows (the eight threads of a row each sum their chunks, then add up)
+    float ln_mean[2 * MI], ln_rstd[2 * MI];
+    u32x4 rg[2], rbt[2];             // gamma / beta chunk of the staged tile
+    auto unpack8 = [&](const u32x4& v, float* f) {
+      if constexpr (VEC == 8) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { f[2 * e] = __uint_as_float(v[e] << 16); f[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u); }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(v[e]);
+      }
+    };
+    if constexpr (LNF) {
+      const int nkt = (g.K + BK - 1) / BK;
+      float acc1[2 * MI];
+#pragma unroll
+      for (int i = 0; i < 2 * MI; ++i) acc1[i] = 0.f;
+      if (g.norm == 1) {
+        for (int t = 0; t < nkt; ++t) {
+          const int k0 = t * BK;
+          if (k0 + lc * VEC < g.K) {
+#pragma unroll
+            for (int i = 0; i < 2 * MI; ++i) {
+              float f[VEC];
+              unpack8(*(const u32x4*)(a_ptr[i] + k0), f);
+#pragma unroll
+              for (int e = 0; e < VEC; ++e) acc1[i] += f[e];
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 2 * MI; ++i) {
+        float v = acc1[i];
+        v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); v += __shfl_xor(v, 4, 64);
+        ln_mean[i] = v / (float)g.K;         // 0 for RMSNorm
+        acc1[i] = 0.f;
+      }
+      for (int t = 0; t < nkt; ++t) {        // second pass over rows that are in cache by now
+        const int k0 = t * BK;
+        if (k0 + lc * VEC < g.K) {
+#pragma unroll
+          for (int i = 0; i < 2 * MI; ++i) {
+            float f[VEC];
+            unpack8(*(const u32x4*)(a_ptr[i] + k0), f);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { const float d = f[e] - ln_mean[i]; acc1[i] += d * d; }
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 2 * MI; ++i) {
+        float v = acc1[i];
+        v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); v += __shfl_xor(v, 4, 64);
+        ln_rstd[i] = rsqrtf(v / (float)g.K + g.norm_eps);
+      }
+    }
     auto load_tile = [&](int k0, auto SET) {
       constexpr int S = decltype(SET)::value;
       const bool k_ok = k0 + lc * VEC < g.K;
@@ -302,18 +361,42 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
           }
         }
       } else {
-        const int ks = k_ok ? k0 : 0;                          // a chunk past K is loaded from chunk 0 and zeroed
+        const int ks = k_ok ? k0 : -lc * VEC;                  // a chunk past K is loaded from the row's first chunk and zeroed
 #pragma unroll
         for (int i = 0; i < 2 * MI; ++i) ra[S][i] = *(const u32x4*)(a_ptr[i] + ks);
       }
-      const int ks = k_ok ? k0 : 0;
+      const int ks = k_ok ? k0 : -lc * VEC;
 #pragma unroll
       for (int i = 0; i < 4; ++i) rb[S][i] = *(const u32x4*)(b_ptr[i] + ks);
+      if constexpr (LNF) {
+        rg[S] = *(const u32x4*)((const T*)g.norm_gamma + ks + lc * VEC);
+        rbt[S] = g.norm_beta ? *(const u32x4*)((const T*)g.norm_beta + ks + lc * VEC) : zero;
+      }
     };
     auto store_tile = [&](int buf, auto SET) {
       constexpr int S = decltype(SET)::value;
       u32x4* a_l = lds + buf * (A_SLOTS + B_SLOTS);
       u32x4* b_l = a_l + A_SLOTS;
+      if constexpr (LNF) {
+        float gf[VEC], bf[VEC];
+        unpack8(rg[S], gf);
+        unpack8(rbt[S], bf);
+#pragma unroll
+        for (int i = 0; i < 2 * MI; ++i) {
+          float f[VEC];
+          unpack8(ra[S][i], f);
+          const float sc_ = ln_rstd[i], sh_ = -ln_mean[i] * ln_rstd[i];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) f[e] = fmaf(fmaf(f[e], sc_, sh_), gf[e], bf[e]);
+          if constexpr (VEC == 8) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { const f32x2 pr = {f[2 * e], f[2 * e + 1]}; ra[S][i][e] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2)); }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ra[S][i][e] = __float_as_uint(f[e]);
+          }
+        }
+      }
 #pragma unroll
       for (int i = 0; i < 2 * MI; ++i) { const int r = lr + 32 * i; a_l[r * 8 + (lc ^ ((r >> 1) & 7))] = kok[S] ? ra[S][i] : zero; }
 #pragma unroll
@@ -534,7 +617,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
   if constexpr (MI == 2) epilogue_rows(std::integral_constant<int, 1>{});
 }
 
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM = 2, int NS = 2>
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM = 2, int NS = 2, bool LNF = false>
 static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   constexpr int BM = 32 * MI * WM;
   const int tiles_n = (g.N + 127) / 128;
@@ -555,9 +638,9 @@ static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   // row groups pay where the operand panels are long (they then exceed what the L2 keeps between tiles); with short
   // panels the plain row-major order inside a strip fetched less (measured on the K = 384 shapes)
   ts.group = g.K >= 1024 ? (int)std::min<int64_t>(4, tiles_m) : 1;
-  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS, LNF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return (int)attr;
-  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, ts);
+  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS, LNF><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, ts);
   return (int)hipGetLastError();
 }
 
@@ -578,6 +661,9 @@ static int gemm_launch_dma(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
 
 template <typename T, int MI, int EPI, bool AGRAN>
 static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+  if constexpr (!AGRAN && (EPI == EPI_PLAIN || EPI == EPI_GELU)) {
+    if (g.norm) return gemm_launch2<T, MI, EPI, false, false, 2, 2, true>(g, cm, s);      // checked by the caller: only these epilogues
+  }
   if constexpr (sizeof(T) == 2 && !AGRAN) {
     if (g.K % 64 == 0) {
       if (g_force_rows == 256 || g_force_rows == 128) {

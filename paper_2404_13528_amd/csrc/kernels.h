@@ -44,6 +44,10 @@ struct GemmArgs {
   int c_cols_on;                // 1: output column n is stored at c_rows(r) + c_cols(n) (a store that splits the
   RowProg c_cols;               //    column dimension, e.g. into heads)
   int c_gran;                   // c_cols takes n / c_gran and the store adds n % c_gran: 1, or the 16-byte vector width
+  int norm;                     // 1 LayerNorm, 2 RMSNorm of every row of A over K, applied as the tile is staged (the norm
+  float norm_eps;               //   that precedes the Linear, folded into its load); gamma / beta have K elements,
+  const void* norm_gamma;       //   beta may be null
+  const void* norm_beta;
   int a_gran;                   // > 0: A's K axis is contiguous only in granules of a_gran (= 4) elements;
   RowProg a_cols;               //      offset(r, k) = a_rows(r) + a_cols(k / a_gran) + k % a_gran
 };

@@ -290,3 +290,23 @@ def test_timing_calibration_labels():
         sm.timing_enable(False)
     assert rep["empty_kernel"][0] == 8 and rep["empty_pair"][0] == 8
     assert rep["empty_kernel"][1] > 0.0
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", ["layer", "rms"])
+@pytest.mark.parametrize("M,N,K", [(70, 96, 96), (300, 288, 384), (129, 130, 200), (1000, 384, 40)])
+def test_linear_with_folded_norm(dtype, kind, M, N, K):
+    # the norm that precedes a Linear, folded into its A-load: same result as norm then Linear (K that ends inside
+    # a 64-wide tile and K below one tile included); with a row gather on A and GELU
+    if dtype == torch.bfloat16 and (N % 2 or K % 8):
+        pytest.skip("vector width")
+    A = draw((M, K), 70, dtype, 2.0, 0.7)
+    W = draw((N, K), 71, dtype, K ** -0.5)
+    b = draw((N,), 72, dtype)
+    g = draw((K,), 73, dtype, 0.2, 1.0)
+    be = draw((K,), 74, dtype, 0.2)
+    n = O.layer_norm(to_np(A), to_np(g), to_np(be)) if kind == "layer" else O.rms_norm(to_np(A), to_np(g))
+    want = O.gelu(O.linear(n, to_np(W), to_np(b)))
+    scale = float(np.abs(want).max()) + 1.0
+    got = sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype), act="gelu", norm=(kind, dev(g, dtype), dev(be, dtype) if kind == "layer" else None, 1e-5))
+    assert_close(got, want, dtype, kind + " norm folded into the Linear", scale)
