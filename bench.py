@@ -38,7 +38,7 @@ MEASURED_TRAFFIC = {
 def kernel_model(label, e=2):
     """Algorithmic bytes and flops of one launch, from the kernel label (tensor reads + writes at
     kernel-per-op granularity with fused epilogues; weights and bias included)."""
-    m = re.match(r"gemm_\w+\[(\d+),(\d+),(\d+)\](.*)", label)
+    m = re.match(r"(?:ln\+|rms\+)?gemm_\w+\[(\d+),(\d+),(\d+)\](.*)", label)
     if m:
         M, N, K = int(m.group(1)), int(m.group(2)), int(m.group(3))
         n_out = N // 2 if "+glu" in m.group(4) else N
