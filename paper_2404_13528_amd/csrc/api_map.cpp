@@ -63,6 +63,7 @@ int map_vector_width(const sm_map& m, int esize) {
 }  // namespace sm
 
 extern "C" int sm_gather_mapped(const sm_map* m, const void* src, void* dst, int dtype, int on_device, void* stream) {
+  if (m && m->numel() == 0) return SM_OK;                    // an empty view: nothing to move
   if (!m || !src || !dst) return fail(SM_ERR_INVALID_ARG, "sm_gather_mapped: null argument");
   if (!dtype_ok(dtype)) return fail(SM_ERR_INVALID_ARG, "sm_gather_mapped: unknown dtype %d", dtype);
   const int es = (int)dtype_size(dtype);

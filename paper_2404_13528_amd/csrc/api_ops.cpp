@@ -20,6 +20,7 @@ int rows_of(const sm_map* m, int64_t rows, int64_t inner, int64_t identity_ld, R
 }
 
 int norm_checked(NormArgs& a, void* stream, const char* who) {
+  if (a.rows == 0 && a.C >= 1 && dtype_ok(a.dtype)) return SM_OK;      // nothing to do: no pointer is looked at, nothing is launched
   if (!a.x || !a.gamma || !a.y) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
   if (!dtype_ok(a.dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
   const int vec = a.dtype == SM_F32 ? 4 : 8;
@@ -38,6 +39,7 @@ int norm_checked(NormArgs& a, void* stream, const char* who) {
 }
 
 int gemm_checked(GemmArgs& g, void* stream, const char* who) {
+  if (g.M == 0 && g.N >= 1 && g.K >= 1 && dtype_ok(g.dtype)) return SM_OK;      // no rows: nothing is launched
   if (!g.A || !g.W || !g.C) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
   if (!dtype_ok(g.dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
   const int vec = g.dtype == SM_F32 ? 4 : 8;

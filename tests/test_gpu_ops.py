@@ -310,3 +310,13 @@ def test_linear_with_folded_norm(dtype, kind, M, N, K):
     scale = float(np.abs(want).max()) + 1.0
     got = sm.linear(dev(A, dtype), dev(W, dtype), dev(b, dtype), act="gelu", norm=(kind, dev(g, dtype), dev(be, dtype) if kind == "layer" else None, 1e-5))
     assert_close(got, want, dtype, kind + " norm folded into the Linear", scale)
+
+
+def test_empty_inputs_are_no_ops():
+    # zero rows: success, nothing launched (the operand pointers of an empty tensor are null)
+    dtype = torch.bfloat16
+    g = torch.ones(96, dtype=dtype, device="cuda")
+    x0 = torch.empty((0, 96), dtype=dtype, device="cuda")
+    assert sm.norm(x0, g, g).shape == (0, 96)
+    W = torch.ones((64, 96), dtype=dtype, device="cuda")
+    assert sm.linear(x0, W, M=0).shape == (0, 64)
