@@ -190,9 +190,16 @@ template <int DK, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh) {
   constexpr int DB = (DK + 1) / 2;           // 32-wide output column blocks
-  constexpr int P = 2 * DK + 1;              // row pitch in 16-byte chunks
-  constexpr int TILE = 64 * P;               // chunks per operand tile
-  extern __shared__ au32x4 fl_lds[];         // [2 stages][K, V][TILE]
+  // Row pitches in 16-byte chunks, chosen for the 64-bank LDS.  K rows are read whole-chunk by 16 consecutive rows
+  // at a time (ds_read_b128): an odd pitch spreads them over all banks.  V rows are read by the transposing load,
+  // four rows of 64 contiguous bytes at a time: those tile the 256 bytes of banks when the pitch is 64 or 192 bytes
+  // modulo 256, i.e. 4 or 12 chunks modulo 16 (the odd pitch measured 59 % of the kernel's LDS cycles as conflicts).
+  constexpr int P = 2 * DK + 1;
+  constexpr int PV = DK <= 2 ? 4 : (DK == 3 ? 7 : (DK <= 6 ? 12 : 20));      // DK = 3 (rows of 5 or 6 chunks): the odd pitch, where
+                                                                            // 12 would double the tile for rows half empty (measured slower)
+  constexpr int TILE = 64 * P, TILEV = 64 * PV;      // chunks per K tile, per V tile
+  constexpr int STG = TILE + TILEV;                  // chunks per stage
+  extern __shared__ au32x4 fl_lds[];                 // [2 stages][K tile, V tile]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   // (batch, head) fastest: the workgroups that share K and V follow each other at a distance of nbh, which
   // keeps them on one XCD (one L2) whenever nbh is a multiple of 8.  Causal: the first half of the ranks takes
@@ -210,22 +217,34 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
   const int chv = a.d >> 3;                  // valid chunks per row
 
   // loader: wave-load i covers chunks [64 i, 64 i + 64) of a tile; wave w issues loads w, w + 4, ...
-  constexpr int NLW = (P + 3) / 4;
-  int ld_row[NLW], ld_col[NLW];
+  constexpr int NLW = (P + 3) / 4, NLV = (PV + 3) / 4;
+  int ld_row[NLW], ld_col[NLW], lv_row[NLV], lv_col[NLV];
 #pragma unroll
   for (int i = 0; i < NLW; ++i) {
     const int s = (wave + 4 * i) * 64 + lane;
     ld_row[i] = s / P;
     ld_col[i] = min(s - ld_row[i] * P, chv - 1) * 8;      // pad chunks repeat the last valid one (finite data)
   }
+#pragma unroll
+  for (int i = 0; i < NLV; ++i) {
+    const int s = (wave + 4 * i) * 64 + lane;
+    lv_row[i] = s / PV;
+    lv_col[i] = (s - lv_row[i] * PV) * 8;                 // slots past the head size are not loaded: what the V^T reads
+  }                                                       // find there only reaches output rows that are never stored
   auto issue = [&](int kt) {
-    au32x4* st = fl_lds + (kt & 1) * 2 * TILE;
+    au32x4* st = fl_lds + (kt & 1) * STG;
 #pragma unroll
     for (int i = 0; i < NLW; ++i) {
       if (wave + 4 * i < P) {                // wave-uniform
         const int64_t key = min(kt * 64 + ld_row[i], a.nk - 1);    // rows past the end repeat the last key (masked below)
         __builtin_amdgcn_global_load_lds(SM_GPTR_(kp + key * a.k_stride[2] + ld_col[i]), SM_LPTR_(st + (wave + 4 * i) * 64), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(SM_GPTR_(vp + key * a.v_stride[2] + ld_col[i]), SM_LPTR_(st + TILE + (wave + 4 * i) * 64), 16, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NLV; ++i) {
+      if (wave + 4 * i < PV && lv_col[i] < a.d) {
+        const int64_t key = min(kt * 64 + lv_row[i], a.nk - 1);
+        __builtin_amdgcn_global_load_lds(SM_GPTR_(vp + key * a.v_stride[2] + lv_col[i]), SM_LPTR_(st + TILE + (wave + 4 * i) * 64), 16, 0, 0);
       }
     }
   };
@@ -254,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
   const float sc = a.scale * 1.4426950408889634f;
   // per-lane LDS offsets (bytes): K fragment row l32, chunk hf; V^T fragment rows 4 hf + j, columns 16 eb + 4 aa
   const unsigned k_lane = (unsigned)(l32 * P + hf) * 16u;
-  const unsigned v_lane = (unsigned)((4 * hf + ((lane & 15) >> 2)) * P * 16 + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+  const unsigned v_lane = (unsigned)((4 * hf + ((lane & 15) >> 2)) * PV * 16 + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
 
   for (int kt = 0; kt < n_kt; ++kt) {
     __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0): this wave's part of tile kt is in LDS
@@ -262,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
     if (kt + 1 < n_kt) issue(kt + 1);
     const int j0 = kt * 64;
     if (CAUSAL && j0 > q0 + 31) continue;    // wave-uniform: every key of the tile lies after every query of the wave
-    const char* kt_l = (const char*)(fl_lds + (kt & 1) * 2 * TILE);
+    const char* kt_l = (const char*)(fl_lds + (kt & 1) * STG);
     const char* vt_l = kt_l + TILE * 16;
     f32x16_t s[2];
 #pragma unroll
@@ -322,9 +341,9 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
       for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const char* base = vt_l + v_lane + ((32 * jb + 16 * ks2) * P * 16 + 64 * db);
+          const char* base = vt_l + v_lane + ((32 * jb + 16 * ks2) * PV * 16 + 64 * db);
           const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(base));
-          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(base + 8 * P * 16));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(base + 8 * PV * 16));
           const s16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf[jb][ks2]), oacc[db], 0, 0, 0);
         }
@@ -555,7 +574,7 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     bf16_t* oo = (bf16_t*)o;
     const dim3 grid((unsigned)((long)n_qt * nbh)), block(256);
 #define FLASH(DK_) do { \
-      const size_t smem = 4 * 64 * (2 * DK_ + 1) * 16 + 64;      /* + one chunk: the last V^T read of an odd DK_ runs past its row */ \
+      const size_t smem = 2 * 64 * ((2 * DK_ + 1) + (DK_ <= 2 ? 4 : (DK_ == 3 ? 7 : (DK_ <= 6 ? 12 : 20)))) * 16 + 64;      /* two stages of a K tile and a V tile */ \
       static const hipError_t attr_f = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
       static const hipError_t attr_c = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
       if (attr_f != hipSuccess || attr_c != hipSuccess) return (int)(attr_f != hipSuccess ? attr_f : attr_c); \
