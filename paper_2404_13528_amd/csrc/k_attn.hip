@@ -4,15 +4,18 @@
 // QK^T, Softmax and AV as separate operators and names tiled attention as
 // complementary (Sec. 6); here they are one ILD & Variable kernel.
 //
-// bf16 path (matrix cores): one wave owns 32 queries and walks the keys in
-// blocks of 32 with an online softmax.  Scores are computed transposed,
-// S^T = K Q^T, so that a lane holds one query (column) and 16 keys (rows):
-// row max / sum are in-lane reductions plus one cross-half shuffle, the
-// probabilities are already in the register layout the next MFMA wants as its
-// B operand (O^T = V^T P^T), and the running rescale of O^T is lane-local.
-// Window attention (Swin) adds the relative-position bias gathered from its
-// table and the shifted-window mask computed from the window's position: no
-// bias or mask tensor is ever materialised.
+// bf16 paths (matrix cores).  Scores are computed transposed, S^T = K Q^T, so
+// that a lane holds one query (column) and 16 keys (rows): row max / sum are
+// in-lane reductions plus one cross-half shuffle, the probabilities are already
+// in the register layout the next MFMA wants as its B operand (O^T = V^T P^T),
+// and the running rescale of O^T is lane-local.  Three kernels share that
+// layout: attn_flash_kernel (global attention: K / V tiles through LDS, shared
+// by the four waves of a workgroup), attn_window32_kernel (Swin windows of at
+// most 64 tokens, head size 32) and attn_bf16_kernel (the general fallback: one
+// wave per 32 queries, operands straight from global memory).  Window attention
+// adds the relative-position bias gathered from its table and the
+// shifted-window mask computed from the window's position: no bias or mask
+// tensor is ever materialised.
 //
 // fp32 path (window attention only): plain FMA kernel, one workgroup per
 // (window, head), K / V / scores in LDS.

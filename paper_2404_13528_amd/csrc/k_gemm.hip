@@ -5,14 +5,14 @@
 // row r of C / the residual (scatter side) are evaluated once per tile, outside
 // the K loop, so the inner loop is plain 16-byte loads -> LDS -> MFMA.
 //
-// Tile: BM x 128 outputs per workgroup of 4 waves (2 x 2), BM = 64 * MI; each
-// wave owns MI x 2 MFMA blocks of 32 x 32.  A K-tile is 128 bytes per row
-// (64 bf16 / 32 fp32), staged through LDS in 16-byte chunks with an XOR swizzle
-// (chunk c of row r sits in slot c ^ ((r >> 1) & 7)): the LDS has 64 banks of 4 bytes, a ds_read_b128 is served
-// 16 lanes (256 bytes) at a time, two rows span the banks once, so the sixteen consecutive rows read together must
-// put their chunk at eight different positions per row parity (the r & 7 form, right for 32 banks, measured half of
-// all LDS cycles as bank conflicts).  Global loads of tile k+1 are issued before
-// the MFMAs of tile k (register double buffering) and two LDS buffers alternate.
+// Tile: BM x 128 outputs per workgroup of 2 * WM waves (WM x 2), BM = 32 * MI * WM; each wave owns MI x 2 MFMA
+// blocks of 32 x 32.  A K-tile is 128 bytes per row (64 bf16 / 32 fp32), held in LDS in 16-byte chunks with an XOR
+// swizzle (chunk c of row r sits in slot c ^ ((r >> 1) & 7)): the LDS has 64 banks of 4 bytes, a ds_read_b128 is
+// served 16 lanes (256 bytes) at a time, two rows span the banks once, so the sixteen consecutive rows read together
+// must put their chunk at eight different positions per row parity (the r & 7 form, right for 32 banks, measured
+// half of all LDS cycles as bank conflicts).  Two ways into LDS: straight from global memory (LDS-DMA, bf16 with
+// K % 64 == 0: the fast path, see gemm_kernel) or through registers, two K-tiles in flight (fp32, ragged K, the
+// unfolded A of the patch embedding, and the folded norm, which transforms A on the way).
 //
 // Column pairing for gated activations and RoPE is done by permuting the
 // logical column order of a wave's 64-column span (which W row feeds which
