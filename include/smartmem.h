@@ -215,6 +215,29 @@ typedef struct {
 int sm_linear(const sm_linear_desc*, const void* A, const void* W, const void* bias, const void* residual,
               void* C, const sm_map* a_map, const sm_map* c_map, void* stream);
 
+/* Fused two-layer MLP  Y = residual + gelu(norm(X) . W1^T + b1) . W2^T + b2  in one kernel, the hidden activation kept
+ * in registers (an extension next to the paper's path: the paper keeps two MatMuls apart, Table 5; here the largest
+ * intermediate of a transformer block, [M, hidden], never reaches memory).  bf16 only.
+ * The kernel reads the two weight matrices in the order its matrix-core operands want them (Sec. 3.2.2's rule that
+ * the producer writes the layout the consumer reads best, applied to constants): sm_mlp_pack writes W1 [hidden, C]
+ * and W2 [C, hidden] (row-major, device) into `packed` (device, 2 * hidden * C elements, 16-byte aligned, owned by
+ * the caller); call it once per weight pair, and again after the weights change.
+ * sm_mlp_fused: X [M, C], b1 [hidden], b2 [C], residual (nullable) and Y [M, C] are device pointers, 16-byte
+ * aligned.  norm = 1: LayerNorm over C of every row of X first (gamma, beta [C], device; rounded to bf16 as sm_norm
+ * would store it).  The hidden activation is rounded to bf16 before the second product, as the two-kernel path
+ * stores it.  x_map / y_map (nullable): row maps as in sm_linear (the residual is read through y_map).
+ * sm_mlp_fused_supported: 1 if a shape has a kernel (C in {128, 256, 384}, hidden a multiple of 32 up to 16384,
+ * bf16); other shapes return SM_ERR_UNSUPPORTED from both calls and nothing is enqueued. */
+typedef struct {
+  int64_t M; int32_t C, hidden, dtype;
+  int32_t norm; float norm_eps;
+  const void* norm_gamma; const void* norm_beta;
+} sm_mlp_desc;
+int sm_mlp_fused_supported(int C, int hidden, int dtype);
+int sm_mlp_pack(const void* W1, const void* W2, int C, int hidden, int dtype, void* packed, void* stream);
+int sm_mlp_fused(const sm_mlp_desc*, const void* X, const void* packed, const void* b1, const void* b2,
+                 const void* residual, void* Y, const sm_map* x_map, const sm_map* y_map, void* stream);
+
 /* Fused attention O = softmax(scale * Q K^T + bias + mask) V per (batch, head).
  * Q, K, V, O are 4-D strided views [nb, heads, n, d] (element strides, innermost
  * stride 1) so that head split / merge permutes are address arithmetic.
@@ -240,7 +263,7 @@ int sm_attention(const sm_attention_desc*, const void* q, const void* k, const v
 /* One Swin block on x [B, H*W, C] -> y [B, H*W, C]:
  * LayerNorm -> (roll, window partition) -> QKV Linear -> window attention ->
  * proj Linear -> (reverse, roll back) -> +x -> LayerNorm -> MLP (GELU) -> +.
- * SM_ELIDED: 7 kernels, the layout transformations are folded into their
+ * SM_ELIDED: 7 kernels (fewer where a norm is folded into the next Linear or the MLP is fused), the layout transformations are folded into their
  * neighbours' addressing as planned by sm_layout_plan.  SM_EXPLICIT: the same
  * 7 kernels with identity maps plus one copy kernel per transformation that
  * moves data (the baseline the paper's Table 1 calls explicit). */
@@ -248,6 +271,8 @@ typedef struct { int32_t B, H, W, C, heads, window, shift, mlp_ratio, dtype; flo
 typedef struct {
   const void *ln1_g, *ln1_b, *wqkv, *bqkv, *rpb_table, *wproj, *bproj,
              *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+  const void* mlp_packed;       /* nullable: sm_mlp_pack(w1, w2); with it (and a shape sm_mlp_fused_supported accepts)
+                                   LayerNorm-2, FC1 + GELU and FC2 + residual run as the one fused MLP kernel */
 } sm_swin_weights;
 size_t sm_swin_block_workspace_bytes(const sm_swin_cfg*, int mode);
 int sm_swin_block(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y,
@@ -279,8 +304,8 @@ int sm_attn_block(const sm_attn_cfg*, const void* const* weights, const void* x,
  * than one window), patch merging between stages (2x2 gather folded into the
  * LayerNorm's load), optional head (LayerNorm, mean over tokens, Linear).
  * weights: device pointers in forward order: embed {w, b, ln_g, ln_b} if
- * has_embed; per stage: per block the 13 pointers of sm_swin_weights in
- * declaration order, then (between stages) merge {ln_g, ln_b, w}; head
+ * has_embed; per stage: per block the 14 pointers of sm_swin_weights in
+ * declaration order (mlp_packed may be null), then (between stages) merge {ln_g, ln_b, w}; head
  * {ln_g, ln_b, w, b} if has_head.
  * x: image [B, in_ch, img, img] if has_embed else tokens [B, H0*W0, C0].
  * y: logits [B, n_cls] if has_head else tokens of the last stage.

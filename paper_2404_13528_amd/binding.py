@@ -67,7 +67,14 @@ SWIN_WEIGHT_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rpb_table", "wproj", "bp
 
 
 class SwinWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in SWIN_WEIGHT_NAMES]
+    _fields_ = [(n, C.c_void_p) for n in SWIN_WEIGHT_NAMES + ("mlp_packed",)]
+
+
+def _packed_mlp(p, Cc, mlp_ratio, dtype, fuse_mlp):
+    """The block's MLP weights in the fused kernel's order (a new tensor), or None where there is no such kernel."""
+    if not fuse_mlp or not mlp_fused_supported(Cc, mlp_ratio * Cc, dtype):
+        return None
+    return mlp_pack(p["w1"], p["w2"])
 
 
 class AttnCfg(C.Structure):
@@ -284,6 +291,43 @@ def linear(A, W, bias=None, residual=None, act="none", rope=None, a_map=None, c_
     return Cm
 
 
+def mlp_fused_supported(C_, hidden, dtype):
+    import torch
+    code = dtype if isinstance(dtype, int) else (SM_BF16 if dtype == torch.bfloat16 else SM_F32)
+    return bool(lib().sm_mlp_fused_supported(int(C_), int(hidden), code))
+
+
+class MlpDesc(C.Structure):
+    _fields_ = [("M", C.c_int64), ("C", C.c_int32), ("hidden", C.c_int32), ("dtype", C.c_int32),
+                ("norm", C.c_int32), ("norm_eps", C.c_float), ("norm_gamma", C.c_void_p), ("norm_beta", C.c_void_p)]
+
+
+def mlp_pack(W1, W2, out=None, stream=None):
+    """W1 [hidden, C] and W2 [C, hidden] in the fused MLP kernel's operand order (one tensor of 2 * hidden * C)."""
+    import torch
+    hidden, Cc = W1.shape
+    packed = torch.empty(2 * hidden * Cc, dtype=W1.dtype, device=W1.device) if out is None else out
+    check(lib().sm_mlp_pack(_ptr(W1), _ptr(W2), int(Cc), int(hidden), _dt(W1), _ptr(packed), _stream(stream)), "sm_mlp_pack")
+    return packed
+
+
+def mlp_fused(X, packed, b1, b2, residual=None, norm=None, x_map=None, y_map=None, out=None, M=None, stream=None):
+    """Y = residual + gelu(norm(X) . W1^T + b1) . W2^T + b2 in one kernel (bf16); packed = mlp_pack(W1, W2);
+    norm = (gamma, beta, eps): LayerNorm of X's rows folded in."""
+    import torch
+    hidden, Cc = b1.numel(), b2.numel()
+    if M is None:
+        M = X.numel() // Cc
+    d = MlpDesc()
+    d.M, d.C, d.hidden, d.dtype = M, Cc, hidden, _dt(X)
+    if norm:
+        d.norm, d.norm_gamma, d.norm_beta, d.norm_eps = 1, _ptr(norm[0]).value, _ptr(norm[1]).value, norm[2]
+    Y = torch.empty((M, Cc), dtype=X.dtype, device=X.device) if out is None else out
+    check(lib().sm_mlp_fused(C.byref(d), _ptr(X), _ptr(packed), _ptr(b1), _ptr(b2), _ptr(residual), _ptr(Y),
+                             x_map.h if x_map else None, y_map.h if y_map else None, _stream(stream)), "sm_mlp_fused")
+    return Y
+
+
 def attention(q, k, v, kind="full", scale=None, out=None, rpb_table=None, window=0, shift=0, H=0, W=0,
               shape=None, q_stride=None, k_stride=None, v_stride=None, o_stride=None, stream=None):
     """q, k, v: 4-D tensors [nb, heads, n, d] (any strides with unit innermost stride), or raw
@@ -322,13 +366,17 @@ def launch_counts():
 class SwinBlock:
     """One Swin block; owns its workspace tensor (allocated through torch, once)."""
 
-    def __init__(self, B, H, W, Cc, heads, window, shift, params, dtype, mode=SM_ELIDED, mlp_ratio=4, eps=1e-5):
+    def __init__(self, B, H, W, Cc, heads, window, shift, params, dtype, mode=SM_ELIDED, mlp_ratio=4, eps=1e-5,
+                 fuse_mlp=True):
         import torch
         self.cfg = SwinCfg(B, H, W, Cc, heads, window, shift, mlp_ratio,
                            SM_F32 if dtype == torch.float32 else SM_BF16, eps)
         self.mode = mode
         self.params = params           # keeps the device tensors alive
-        self.w = SwinWeights(*[params[n].data_ptr() for n in SWIN_WEIGHT_NAMES])
+        # the MLP weights are packed here, once: later in-place changes of w1 / w2 need a new SwinBlock
+        self.packed = _packed_mlp(params, Cc, mlp_ratio, dtype, fuse_mlp)
+        self.w = SwinWeights(*([params[n].data_ptr() for n in SWIN_WEIGHT_NAMES] +
+                               [self.packed.data_ptr() if self.packed is not None else None]))
         n = lib().sm_swin_block_workspace_bytes(C.byref(self.cfg), mode)
         if n == 0:
             raise SmError("sm_swin_block_workspace_bytes: " + lib().sm_last_error().decode())
@@ -348,7 +396,7 @@ class SwinChain:
     device tensors; for a bare stage pass {"stages": [[block params...]]}."""
 
     def __init__(self, B, stages, window, net, dtype, mode=SM_ELIDED, img=0, patch=4, in_ch=3, n_cls=0,
-                 mlp_ratio=4, eps=1e-5):
+                 mlp_ratio=4, eps=1e-5, fuse_mlp=True):
         import torch
         d = ChainDesc()
         d.B, d.dtype, d.window, d.mlp_ratio, d.eps = B, (SM_F32 if dtype == torch.float32 else SM_BF16), window, mlp_ratio, eps
@@ -365,13 +413,14 @@ class SwinChain:
             ptrs += [net["embed"][k] for k in ("w", "b", "ln_g", "ln_b")]
         for si, blocks in enumerate(net["stages"]):
             for p in blocks:
-                ptrs += [p[k] for k in SWIN_WEIGHT_NAMES]
+                # (MLP weights packed once, here: later in-place changes of w1 / w2 need a new SwinChain)
+                ptrs += [p[k] for k in SWIN_WEIGHT_NAMES] + [_packed_mlp(p, stages[si][0], mlp_ratio, dtype, fuse_mlp)]
             if si + 1 < len(net["stages"]):
                 ptrs += [net["merges"][si][k] for k in ("ln_g", "ln_b", "w")]
         if d.has_head:
             ptrs += [net["head"][k] for k in ("ln_g", "ln_b", "w", "b")]
         self._keep = ptrs
-        self.wptr = (C.c_void_p * len(ptrs))(*[t.data_ptr() for t in ptrs])
+        self.wptr = (C.c_void_p * len(ptrs))(*[t.data_ptr() if t is not None else None for t in ptrs])
         n = lib().sm_run_chain_workspace_bytes(C.byref(d), mode)
         if n == 0:
             raise SmError("sm_run_chain_workspace_bytes: " + lib().sm_last_error().decode())

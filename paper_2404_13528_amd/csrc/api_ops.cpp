@@ -175,6 +175,60 @@ extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, 
   return gemm_checked(g, stream, "sm_linear");
 }
 
+namespace sm {
+int mlp_checked(MlpArgs& a, void* stream, const char* who) {
+  if (!mlp_fused_supported(a.C, a.Hd, SM_BF16)) return fail(SM_ERR_UNSUPPORTED, "%s: no fused MLP kernel for C = %d, hidden = %d", who, a.C, a.Hd);
+  if (a.M < 0) return fail(SM_ERR_SHAPE, "%s: negative row count", who);
+  if (a.norm != 0 && a.norm != 1) return fail(SM_ERR_INVALID_ARG, "%s: unknown norm %d", who, a.norm);
+  if (a.M == 0) return SM_OK;
+  if (!a.X || !a.Wp || !a.b1 || !a.b2 || !a.Y) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
+  if (!aligned16(a.X) || !aligned16(a.Wp) || !aligned16(a.b1) || !aligned16(a.b2) || !aligned16(a.Y) || (a.residual && !aligned16(a.residual)))
+    return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  if (a.norm) {
+    if (!a.norm_gamma || !a.norm_beta || !aligned16(a.norm_gamma) || !aligned16(a.norm_beta))
+      return fail(SM_ERR_INVALID_ARG, "%s: folded LayerNorm needs 16-byte aligned gamma and beta", who);
+    if (!(a.norm_eps > 0.f)) return fail(SM_ERR_INVALID_ARG, "%s: folded LayerNorm needs eps > 0", who);
+  }
+  if ((a.M + 31) / 32 > 0x7fffffff) return fail(SM_ERR_SHAPE, "%s: too many rows", who);
+  char label[96];
+  std::snprintf(label, sizeof label, "%smlp_bf16[%lld,%d,%d]", a.norm ? "ln+" : "", (long long)a.M, a.Hd, a.C);
+  Timed tm(label, stream);
+  const int rc = launch_mlp_fused(a, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
+  count_compute(1);
+  return SM_OK;
+}
+}  // namespace sm
+
+extern "C" int sm_mlp_fused_supported(int C, int hidden, int dtype) { return sm::mlp_fused_supported(C, hidden, dtype) ? 1 : 0; }
+
+extern "C" int sm_mlp_pack(const void* W1, const void* W2, int C, int hidden, int dtype, void* packed, void* stream) {
+  if (!dtype_ok(dtype)) return fail(SM_ERR_INVALID_ARG, "sm_mlp_pack: unknown dtype");
+  if (!sm::mlp_fused_supported(C, hidden, dtype)) return fail(SM_ERR_UNSUPPORTED, "sm_mlp_pack: no fused MLP kernel for C = %d, hidden = %d, dtype %d", C, hidden, dtype);
+  if (!W1 || !W2 || !packed) return fail(SM_ERR_INVALID_ARG, "sm_mlp_pack: null pointer");
+  if (!aligned16(W1) || !aligned16(W2) || !aligned16(packed)) return fail(SM_ERR_INVALID_ARG, "sm_mlp_pack: pointers must be 16-byte aligned");
+  Timed tm("mlp_pack", stream);
+  const int rc = launch_mlp_pack(W1, W2, C, hidden, packed, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "sm_mlp_pack: launch failed (hip error %d)", rc);
+  return SM_OK;
+}
+
+extern "C" int sm_mlp_fused(const sm_mlp_desc* d, const void* X, const void* packed, const void* b1, const void* b2,
+                            const void* residual, void* Y, const sm_map* x_map, const sm_map* y_map, void* stream) {
+  if (!d) return fail(SM_ERR_INVALID_ARG, "sm_mlp_fused: null descriptor");
+  if (!dtype_ok(d->dtype)) return fail(SM_ERR_INVALID_ARG, "sm_mlp_fused: unknown dtype");
+  if (!sm::mlp_fused_supported(d->C, d->hidden, d->dtype))
+    return fail(SM_ERR_UNSUPPORTED, "sm_mlp_fused: no kernel for C = %d, hidden = %d, dtype %d", d->C, d->hidden, d->dtype);
+  MlpArgs a; std::memset(&a, 0, sizeof(a));
+  a.X = X; a.Wp = packed; a.b1 = b1; a.b2 = b2; a.residual = residual; a.Y = Y; a.M = d->M; a.C = d->C; a.Hd = d->hidden;
+  a.norm = d->norm; a.norm_eps = d->norm_eps; a.norm_gamma = d->norm_gamma; a.norm_beta = d->norm_beta;
+  int rc = rows_of(x_map, d->M, d->C, d->C, &a.x_rows, "sm_mlp_fused(X)");
+  if (rc) return rc;
+  rc = rows_of(y_map, d->M, d->C, d->C, &a.y_rows, "sm_mlp_fused(Y)");
+  if (rc) return rc;
+  return mlp_checked(a, stream, "sm_mlp_fused");
+}
+
 extern "C" int sm_attention(const sm_attention_desc* d, const void* q, const void* k, const void* v, void* o,
                             const void* rpb_table, void* stream) {
   if (!d) return fail(SM_ERR_INVALID_ARG, "sm_attention: null descriptor");

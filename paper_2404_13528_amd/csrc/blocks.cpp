@@ -183,6 +183,19 @@ int run_gemm(const void* A, const void* W, const void* bias, const void* res, vo
 // wins only while the Linear has few column tiles (measured: up to N = 512).
 bool fold_norm(int n_cols) { return n_cols <= 512; }
 
+// LayerNorm-2 + FC1 + GELU + FC2 + residual as the fused MLP kernel, when the caller packed the weights for it
+bool mlp_is_fused(const sm_swin_cfg& c, const sm_swin_weights* wt) {
+  return wt->mlp_packed && mlp_fused_supported(c.C, c.mlp_ratio * c.C, c.dtype);
+}
+int run_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* x1, void* y, int64_t T, void* stream) {
+  MlpArgs a; std::memset(&a, 0, sizeof(a));
+  a.X = x1; a.Wp = wt->mlp_packed; a.b1 = wt->b1; a.b2 = wt->b2; a.residual = x1; a.Y = y;
+  a.M = T; a.C = c.C; a.Hd = c.mlp_ratio * c.C;
+  a.norm = 1; a.norm_eps = c.eps; a.norm_gamma = wt->ln2_g; a.norm_beta = wt->ln2_b;
+  a.x_rows = identity_rows(c.C); a.y_rows = identity_rows(c.C);
+  return mlp_checked(a, stream, "sm_swin_block(mlp)");
+}
+
 }  // namespace
 
 extern "C" size_t sm_swin_block_workspace_bytes(const sm_swin_cfg* c, int mode) {
@@ -233,6 +246,7 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
     if ((rc = attention_checked(ad, (char*)qkv + plan->qkv_base[0] * es, (char*)qkv + plan->qkv_base[1] * es, (char*)qkv + plan->qkv_base[2] * es,
                                 bufO, wt->rpb_table, stream, "window attention"))) return rc;
     if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
+    if (mlp_is_fused(*c, wt)) return run_mlp_fused(*c, wt, x1, y, T, stream);
     if (fold_norm(c->mlp_ratio * C)) {
       if ((rc = run_gemm(x1, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream, wt->ln2_g, wt->ln2_b, eps))) return rc;
     } else {
@@ -268,6 +282,7 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
   } else {
     if ((rc = copy_launch(plan->reverse, s2, x1, dt, stream, x))) return rc;
   }
+  if (mlp_is_fused(*c, wt)) return run_mlp_fused(*c, wt, x1, y, T, stream);
   if (fold_norm(c->mlp_ratio * C)) {
     if ((rc = run_gemm(x1, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream, wt->ln2_g, wt->ln2_b, eps))) return rc;
   } else {
@@ -350,7 +365,7 @@ int check_chain(const sm_chain_desc* c, const char* who) {
 
 int chain_weight_count(const sm_chain_desc* c) {
   int n = c->has_embed ? 4 : 0;
-  for (int s = 0; s < c->n_stages; ++s) n += 13 * c->stages[s].depth + (s + 1 < c->n_stages ? 3 : 0);
+  for (int s = 0; s < c->n_stages; ++s) n += 14 * c->stages[s].depth + (s + 1 < c->n_stages ? 3 : 0);
   return n + (c->has_head ? 4 : 0);
 }
 
@@ -381,7 +396,18 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
   if (!weights || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: null pointer");
   if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: unknown mode %d", mode);
   if (n_weights != chain_weight_count(c)) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: %d weight pointers given, %d expected", n_weights, chain_weight_count(c));
-  for (int i = 0; i < n_weights; ++i) if (!weights[i] || !aligned16(weights[i])) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: weight %d is null or misaligned", i);
+  {
+    // every pointer is required except a block's fourteenth (the packed MLP weights)
+    std::vector<char> optional((size_t)n_weights, 0);
+    int at = c->has_embed ? 4 : 0;
+    for (int s = 0; s < c->n_stages; ++s) {
+      for (int k = 0; k < c->stages[s].depth; ++k) { optional[(size_t)at + 13] = 1; at += 14; }
+      if (s + 1 < c->n_stages) at += 3;
+    }
+    for (int i = 0; i < n_weights; ++i)
+      if ((!weights[i] && !optional[(size_t)i]) || !aligned16(weights[i]))
+        return fail(SM_ERR_INVALID_ARG, "sm_run_chain: weight %d is null or misaligned", i);
+  }
   const ChainSizes z = chain_sizes(c, mode);
   if (ws_bytes < z.total) return fail(SM_ERR_WORKSPACE, "sm_run_chain: workspace of %zu bytes, %zu needed", ws_bytes, z.total);
   if (!aligned16(x) || !aligned16(y) || !aligned16(ws) || (y_feat && !aligned16(y_feat))) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: pointers must be 16-byte aligned");
@@ -439,7 +465,7 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
       sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, shift, c->mlp_ratio, dt, c->eps};
       sm_swin_weights bw;
       std::memcpy(&bw, wp, sizeof(bw));
-      wp += 13;
+      wp += 14;
       const bool final_out = last_stage && k + 1 == st.depth && !c->has_head;
       void* out = final_out ? y : act[flip];
       if ((rc = sm_swin_block(&bc, &bw, cur, out, blk_ws, z.block, mode, stream))) return rc;

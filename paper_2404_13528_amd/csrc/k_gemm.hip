@@ -64,21 +64,6 @@ __device__ __forceinline__ float erf_as(float x) {
   return copysignf(r, x);
 }
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erf_as(x * 0.70710678118654752f)); }
-// bf16 outputs: erf(x / sqrt 2) as an odd polynomial of degree 13 on the clamped argument (|error| < 1.4e-4, i.e.
-// |GELU error| < 2.6e-4, a fifteenth of a bf16 ulp at 1): seven FMAs and no transcendental instruction
-__device__ __forceinline__ float gelu_poly(float x) {
-  const float xc = __builtin_amdgcn_fmed3f(x, -3.8183766f, 3.8183766f);
-  const float u = xc * xc;
-  float p = 7.157552710e-08f;
-  p = fmaf(p, u, -4.470385145e-06f);
-  p = fmaf(p, u, 1.201538955e-04f);
-  p = fmaf(p, u, -1.853696382e-03f);
-  p = fmaf(p, u, 1.859850362e-02f);
-  p = fmaf(p, u, -1.313855874e-01f);
-  p = fmaf(p, u, 7.973302013e-01f);
-  const float hx = 0.5f * x;
-  return fmaf(hx, p * xc, hx);
-}
 template <typename T> __device__ __forceinline__ float gelu_t(float x) {
   if constexpr (sizeof(T) == 2) return gelu_poly(x);
   else return gelu_erf(x);

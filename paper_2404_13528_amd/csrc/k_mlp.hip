@@ -1,0 +1,324 @@
+// Fused MLP: Y = residual + W2 . gelu(W1 . norm(x) + b1) + b2 per token, the hidden activation never leaving the
+// registers.  Not an operator pair of the paper's tables (two ILD & Variable operators are kept apart there):
+// it is the deeper fusion next to the layout path, where the hidden tensor is the largest intermediate of a block.
+//
+// Shape of the work: a workgroup of four waves owns 32 tokens and all C output features.  The hidden dimension
+// is cut into slices of 32 units and dealt round-robin to the waves; for its slice a wave forms
+//   H^T[32 hidden, tokens] = W1[slice, :] . X^T        (C / 16 MFMAs, X fragments from LDS)
+// applies bias + GELU in registers, and feeds the result, still in registers, as the second operand of
+//   Y^T[C, tokens] += W2[:, slice] . H                  (C / 16 MFMAs)
+// so a wave holds a partial Y^T over its slices (split-K across waves) and the four partials are added through
+// LDS once, at the end, in a fixed order.  No weight element is used twice inside a workgroup, so the weights go
+// straight from L2 into MFMA operand registers (no LDS staging, no barrier in the main loop), each fragment
+// register being refilled for the wave's next slice right after the MFMA that consumed it: every load has a whole
+// slice (2 * C / 16 MFMAs) to arrive.
+//
+// Weight layout (the paper's principle that a producer writes the layout its consumer reads best, Sec. 3.2.2, applied
+// to constants: done once by mlp_pack_kernel): an MFMA operand fragment is 64 lanes x 16 bytes taken from 32 rows, 32
+// bytes per row; read from the row-major matrix every such load touches 32 cache lines for a quarter of their
+// bytes (measured: 76 us against 33 us for M = 6272, C = 384, hidden 1536).  Packed, a fragment is 1 KiB
+// contiguous in lane order:
+//   W1 fragment (slice sc, step kk) at index sc * C/16 + kk:        lane (l32, hf) = W1[32 sc + rho(l32)][16 kk + 8 hf ..+7]
+//   W2 fragment (slice sc, block t, step s) at (sc * C/32 + t) * 2 + s: lane (l32, hf) = W2[32 t + l32][32 sc + 16 s + 8 hf ..+7]
+// rho assigns the accumulator rows of the first product to hidden units in the order that makes the eight values a
+// lane holds for one 16-wide step of the second product eight consecutive hidden units: accumulator row
+// 8b + 4h + i (b < 4, h < 2, i < 4) is hidden unit 16 (b >> 1) + 8h + 4 (b & 1) + i of the slice.
+#include <type_traits>
+#include "device_common.h"
+#include "kernels.h"
+
+namespace sm {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 mlp_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float mlp_f32x16;
+typedef unsigned int mlp_u32x4 __attribute__((ext_vector_type(4)));
+typedef float mlp_f32x4 __attribute__((ext_vector_type(4)));
+typedef float mlp_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 mlp_bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned mlp_pack2(float a, float b) {
+  const mlp_f32x2 p = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(p, mlp_bf16x2));
+}
+__device__ __forceinline__ void mlp_unpack8(mlp_u32x4 v, float* f) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { f[2 * e] = __uint_as_float(v[e] << 16); f[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u); }
+}
+__device__ __forceinline__ int mlp_rho(int r) { return 16 * (r >> 4) + 8 * ((r >> 2) & 1) + 4 * ((r >> 3) & 1) + (r & 3); }
+
+// one thread per 16-byte chunk of the packed buffer: [W1 fragments | W2 fragments]
+__global__ void mlp_pack_kernel(const bf16_t* W1, const bf16_t* W2, mlp_u32x4* packed, int C, int Hd) {
+  const int KK = C / 16, T = C / 32;
+  const int64_t n1 = (int64_t)Hd * C / 8;
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= 2 * n1) return;
+  const int64_t q = o < n1 ? o : o - n1;
+  const int lane = (int)(q & 63), l32 = lane & 31, hf = lane >> 5;
+  const int64_t frag = q >> 6;
+  const bf16_t* src;
+  if (o < n1) {
+    const int sc = (int)(frag / KK), kk = (int)(frag - (int64_t)sc * KK);
+    src = W1 + (int64_t)(32 * sc + mlp_rho(l32)) * C + 16 * kk + 8 * hf;
+  } else {
+    const int s = (int)(frag & 1);
+    const int64_t ft = frag >> 1;
+    const int sc = (int)(ft / T), t = (int)(ft - (int64_t)sc * T);
+    src = W2 + (int64_t)(32 * t + l32) * Hd + 32 * sc + 16 * s + 8 * hf;
+  }
+  packed[o] = *(const mlp_u32x4*)src;
+}
+
+constexpr int MLP_RP = 36;       // floats per token row of a 32 x 32 partial tile in LDS (144 bytes: conflict-free 16-byte writes)
+
+template <int C>
+__global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
+  constexpr int KK = C / 16;            // 16-wide steps of the first product
+  constexpr int T = C / 32;             // 32-row blocks of Y^T
+  constexpr int BM = 32;
+  constexpr int XS = C / 8;             // 16-byte slots per token row
+  constexpr int XP = XS + 1;            // odd pitch: the fragment reads of 16 tokens hit 16 different bank groups
+  static_assert(T % 4 == 0, "C must be a multiple of 128");
+  const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                                  // [BM][XP]
+  float* red = (float*)(smem_raw + (size_t)BM * XP * 16);                 // [4 waves][4 blocks][32][MLP_RP]
+  mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + (size_t)BM * XP * 16 + (size_t)4 * 4 * 32 * MLP_RP * 4);   // [Hd / 8]
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int64_t row0 = (int64_t)blockIdx.x * BM;
+  const bf16_t* X = (const bf16_t*)g.X;
+  const int Hd = g.Hd;
+  const int nsub = Hd >> 5;
+  const char* W1p = (const char*)g.Wp;                                    // fragments of 1 KiB, see the file header
+  const char* W2p = W1p + (size_t)Hd * C * 2;
+
+  // the wave's first slice of weights is requested before anything else
+  mlp_u32x4 w1[KK], w2[T][2];
+  const int sc0 = w < nsub ? w : 0;     // a wave without a slice (hidden < 128) computes nothing but loads in bounds
+  {
+    const unsigned o1 = (unsigned)(sc0 * KK) * 1024u + lane * 16u;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) w1[kk] = *(const mlp_u32x4*)(W1p + o1 + kk * 1024);
+    const unsigned o2 = (unsigned)(sc0 * T * 2) * 1024u + lane * 16u;
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) w2[t][s] = *(const mlp_u32x4*)(W2p + o2 + (t * 2 + s) * 1024);
+  }
+
+  // X tile -> LDS (rows past M as zeros)
+  for (int s = tid; s < BM * XS; s += 256) {
+    const int r = s / XS, c = s - r * XS;
+    const int64_t row = row0 + r;
+    mlp_u32x4 v = {0u, 0u, 0u, 0u};
+    if (row < g.M) v = *(const mlp_u32x4*)(X + (g.x_rows.identity ? row * g.x_rows.ld : eval_rows_k(&gk->x_rows, row)) + c * 8);
+    x_l[r * XP + c] = v;
+  }
+  // the first bias as well: a global load inside the main loop would be waited for in issue order, behind the
+  // whole weight prefetch
+  for (int s = tid; s < Hd / 8; s += 256) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
+  __syncthreads();
+
+  if (g.norm) {
+    // LayerNorm of the tile's rows in place (the norm that precedes the MLP, folded): eight lanes per token,
+    // two-pass fp32 statistics, the result rounded to bf16 as a separate norm kernel would have stored it
+    const int r = tid >> 3, p = tid & 7;
+    mlp_u32x4* xr = x_l + r * XP;
+    float sum = 0.f;
+    for (int c = p; c < XS; c += 8) {
+      float f[8];
+      mlp_unpack8(xr[c], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += f[e];
+    }
+    sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64); sum += __shfl_xor(sum, 4, 64);
+    const float mean = sum / (float)C;
+    float var = 0.f;
+    for (int c = p; c < XS; c += 8) {
+      float f[8];
+      mlp_unpack8(xr[c], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; var += d * d; }
+    }
+    var += __shfl_xor(var, 1, 64); var += __shfl_xor(var, 2, 64); var += __shfl_xor(var, 4, 64);
+    const float rstd = rsqrtf(var / (float)C + g.norm_eps), sh = -mean * rstd;
+    const mlp_u32x4* gam = (const mlp_u32x4*)g.norm_gamma;
+    const mlp_u32x4* bet = (const mlp_u32x4*)g.norm_beta;
+    for (int c = p; c < XS; c += 8) {
+      float f[8], gf[8], bf[8];
+      mlp_unpack8(xr[c], f);
+      mlp_unpack8(gam[c], gf);
+      mlp_unpack8(bet[c], bf);
+      mlp_u32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        o[e] = mlp_pack2(fmaf(fmaf(f[2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
+      xr[c] = o;
+    }
+    __syncthreads();
+  }
+
+  mlp_f32x16 out[T];
+#pragma unroll
+  for (int t = 0; t < T; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) out[t][e] = 0.f;
+
+  for (int sc = w; sc < nsub; sc += 4) {
+    const int nx = sc + 4 < nsub ? sc + 4 : sc;          // the last slice reloads itself: no branch around the prefetch
+    int xo = l32 * XP + hf;                              // opaque per slice: the X fragments are re-read from LDS every
+    asm volatile("" : "+v"(xo));                         // time instead of being hoisted into (and spilled from) registers
+    const mlp_u32x4 bias_v = b1_l[sc * 4 + hf];
+    const mlp_u32x4 bias_w = b1_l[sc * 4 + 2 + hf];
+    mlp_f32x16 h;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) h[e] = 0.f;
+    {
+      const unsigned o1 = (unsigned)(nx * KK) * 1024u + lane * 16u;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const mlp_u32x4 xf = x_l[xo + 2 * kk];
+        h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, xf), h, 0, 0, 0);
+        w1[kk] = *(const mlp_u32x4*)(W1p + o1 + kk * 1024);
+      }
+    }
+    // bias + GELU, rounded to bf16 as a stored hidden activation would be; step s of the second product takes
+    // accumulator blocks 2s and 2s + 1 = hidden units 16s + 8 hf + 0..7 of the slice
+    float bf_[16];
+    mlp_unpack8(bias_v, bf_);
+    mlp_unpack8(bias_w, bf_ + 8);
+    mlp_u32x4 hfr[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a = gelu_poly(h[8 * s + 2 * e] + bf_[8 * s + 2 * e]);
+        const float b = gelu_poly(h[8 * s + 2 * e + 1] + bf_[8 * s + 2 * e + 1]);
+        hfr[s][e] = mlp_pack2(a, b);
+      }
+    {
+      const unsigned o2 = (unsigned)(nx * T * 2) * 1024u + lane * 16u;
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          out[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w2[t][s]), __builtin_bit_cast(mlp_bf16x8, hfr[s]), out[t], 0, 0, 0);
+          w2[t][s] = *(const mlp_u32x4*)(W2p + o2 + (t * 2 + s) * 1024);
+        }
+    }
+    // issue order of the slice: every MFMA is followed by the load that refills its weight register (left alone, the
+    // scheduler gathers all loads at the end of the slice, where their latency is exposed at the top of the next)
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * T; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+  }
+
+  // The four partial Y^T are added through LDS, four row blocks at a time: every wave writes its four blocks as
+  // [token][feature] fp32 tiles, then wave w owns block 4 gi + w: sums the partials in wave order, adds bias and
+  // residual and stores 16 consecutive features per lane.  Bias and residual are requested before the first
+  // exchange so that their latency is not paid once per round.
+  const bf16_t* R = (const bf16_t*)g.residual;
+  bf16_t* Y = (bf16_t*)g.Y;
+  const int tk = lane >> 1, hh = lane & 1;
+  const int64_t row = row0 + tk;
+  const bool row_ok = row < g.M;
+  const int64_t ro = row_ok ? (g.y_rows.identity ? row * g.y_rows.ld : eval_rows_k(&gk->y_rows, row)) : 0;
+  mlp_u32x4 rres[T / 4][2], rb2[T / 4][2];
+#pragma unroll
+  for (int gi = 0; gi < T / 4; ++gi) {
+    const int cb = (4 * gi + w) * 32 + 16 * hh;          // first of this lane's 16 features
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      rb2[gi][q] = *(const mlp_u32x4*)((const bf16_t*)g.b2 + cb + 8 * q);
+      rres[gi][q] = mlp_u32x4{0u, 0u, 0u, 0u};
+      if (R && row_ok) rres[gi][q] = *(const mlp_u32x4*)(R + ro + cb + 8 * q);
+    }
+  }
+#pragma unroll
+  for (int gi = 0; gi < T / 4; ++gi) {
+    if (gi) __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float* tile = red + (size_t)((w * 4 + j) * 32) * MLP_RP;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const mlp_f32x4 v = {out[4 * gi + j][4 * b], out[4 * gi + j][4 * b + 1], out[4 * gi + j][4 * b + 2], out[4 * gi + j][4 * b + 3]};
+        *(mlp_f32x4*)(tile + l32 * MLP_RP + 8 * b + 4 * hf) = v;
+      }
+    }
+    __syncthreads();
+    float acc[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+      const float* tile = red + (size_t)((ww * 4 + w) * 32) * MLP_RP + tk * MLP_RP + 16 * hh;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const mlp_f32x4 v = *(const mlp_f32x4*)(tile + 4 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[4 * q + e] += v[e];
+      }
+    }
+    if (row_ok) {
+      const int cb = (4 * gi + w) * 32 + 16 * hh;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        float bb[8], rr[8];
+        mlp_unpack8(rb2[gi][q], bb);
+        mlp_unpack8(rres[gi][q], rr);
+        mlp_u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)      // product + bias + residual in fp32, rounded to bf16 once, as the Linear's epilogue does
+          o[e] = mlp_pack2(acc[8 * q + 2 * e] + bb[2 * e] + rr[2 * e], acc[8 * q + 2 * e + 1] + bb[2 * e + 1] + rr[2 * e + 1]);
+        *(mlp_u32x4*)(Y + ro + cb + 8 * q) = o;
+      }
+    }
+  }
+}
+
+static size_t mlp_smem(int C, int Hd) { return (size_t)32 * (C / 8 + 1) * 16 + (size_t)4 * 4 * 32 * MLP_RP * 4 + (size_t)Hd * 2; }
+
+template <int C>
+static int mlp_launch(const MlpArgs& g, void* stream) {
+  const size_t smem = mlp_smem(C, g.Hd);
+  static size_t allowed = 0;          // raised on demand: the attribute is per kernel, the hidden size varies
+  if (smem > allowed) {
+    const hipError_t e = hipFuncSetAttribute((const void*)mlp_fused_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return (int)e;
+    allowed = smem;
+  }
+  const int64_t n_wg = (g.M + 31) / 32;
+  mlp_fused_kernel<C><<<dim3((unsigned)n_wg), dim3(256), smem, (hipStream_t)stream>>>(g);
+  return (int)hipGetLastError();
+}
+
+bool mlp_fused_supported(int C, int Hd, int dtype) {
+  return dtype == SM_BF16 && (C == 128 || C == 256 || C == 384) && Hd >= 32 && Hd % 32 == 0 && Hd <= 16384;
+}
+
+int launch_mlp_pack(const void* W1, const void* W2, int C, int Hd, void* packed, void* stream) {
+  const int64_t n = 2 * ((int64_t)Hd * C / 8);
+  mlp_pack_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>((const bf16_t*)W1, (const bf16_t*)W2, (mlp_u32x4*)packed, C, Hd);
+  return (int)hipGetLastError();
+}
+
+int launch_mlp_fused(const MlpArgs& g, void* stream) {
+  switch (g.C) {
+    case 128: return mlp_launch<128>(g, stream);
+    case 256: return mlp_launch<256>(g, stream);
+    case 384: return mlp_launch<384>(g, stream);
+  }
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace sm

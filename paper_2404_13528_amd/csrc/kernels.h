@@ -54,6 +54,18 @@ struct GemmArgs {
 int launch_gemm(const GemmArgs& a, void* stream);
 int gemm_tuning(int tile_rows, int stages);      // 0 = automatic; -1 on values the kernel has no variant for
 
+// Fused MLP (bf16): Y = residual + W2 . gelu(W1 . norm(x) + b1) + b2 per token.  Wp: W1 [Hd, C] and W2 [C, Hd] packed
+// by launch_mlp_pack into MFMA fragment order (2 * Hd * C elements).
+struct MlpArgs {
+  const void* X; const void* Wp; const void* b1; const void* b2; const void* residual; void* Y;
+  int64_t M; int C, Hd;
+  int norm; float norm_eps; const void* norm_gamma; const void* norm_beta;     // norm = 1: LayerNorm of X's rows first
+  RowProg x_rows, y_rows;       // row r of X; row r of Y and of the residual
+};
+bool mlp_fused_supported(int C, int Hd, int dtype);
+int launch_mlp_pack(const void* W1, const void* W2, int C, int Hd, void* packed, void* stream);
+int launch_mlp_fused(const MlpArgs& a, void* stream);
+
 int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,
                      const void* rpb_table, void* stream);
 
@@ -67,6 +79,7 @@ namespace sm {
 int rows_of(const sm_map* m, int64_t rows, int64_t inner, int64_t identity_ld, RowProg* out, const char* who);
 int norm_checked(NormArgs& a, void* stream, const char* who);
 int gemm_checked(GemmArgs& g, void* stream, const char* who);
+int mlp_checked(MlpArgs& a, void* stream, const char* who);
 int attention_checked(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table,
                       void* stream, const char* who);
 int map_vector_width(const sm_map& m, int esize);

@@ -320,3 +320,63 @@ def test_empty_inputs_are_no_ops():
     assert sm.norm(x0, g, g).shape == (0, 96)
     W = torch.ones((64, 96), dtype=dtype, device="cuda")
     assert sm.linear(x0, W, M=0).shape == (0, 64)
+
+
+@pytest.mark.parametrize("M,C,Hd", [(32, 128, 512), (70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (45, 384, 160)])
+@pytest.mark.parametrize("with_res,with_norm", [(True, False), (False, False), (True, True)])
+def test_mlp_fused(M, C, Hd, with_res, with_norm):
+    # (LayerNorm +) FC1 + GELU + FC2 (+ residual) in one kernel against the oracle's operators; row counts that end
+    # inside a 32-token tile, hidden sizes that leave waves with unequal (or no) slices
+    dtype = torch.bfloat16
+    X = draw((M, C), 80, dtype, 2.0, 0.7)
+    W1 = draw((Hd, C), 81, dtype, C ** -0.5)
+    b1 = draw((Hd,), 82, dtype, 0.5)
+    W2 = draw((C, Hd), 83, dtype, Hd ** -0.5)
+    b2 = draw((C,), 84, dtype, 0.5)
+    R = draw((M, C), 85, dtype, 1.0)
+    g = draw((C,), 91, dtype, 0.2, 1.0)
+    be = draw((C,), 92, dtype, 0.2)
+    xin = O.layer_norm(to_np(X), to_np(g), to_np(be)) if with_norm else to_np(X)
+    hid = O.gelu(O.linear(xin, to_np(W1), to_np(b1)))
+    want = O.linear(hid, to_np(W2), to_np(b2)) + (to_np(R) if with_res else 0.0)
+    assert sm.mlp_fused_supported(C, Hd, dtype)
+    packed = sm.mlp_pack(dev(W1, dtype), dev(W2, dtype))
+    got = sm.mlp_fused(dev(X, dtype), packed, dev(b1, dtype), dev(b2, dtype), dev(R, dtype) if with_res else None,
+                       norm=(dev(g, dtype), dev(be, dtype), 1e-5) if with_norm else None)
+    assert_close(got, want, dtype, "fused MLP", float(np.abs(want).max()) + 1.0)
+
+
+def test_mlp_pack_is_a_permutation_of_the_weights():
+    # bit-exact: the packed buffer holds every weight element exactly once (checked as sorted multisets of 16-byte
+    # chunks' sums being equal is too weak: compare sorted raw values)
+    dtype = torch.bfloat16
+    W1, W2 = dev(draw((160, 128), 93, dtype), dtype), dev(draw((128, 160), 94, dtype), dtype)
+    packed = sm.mlp_pack(W1, W2)
+    n = W1.numel()
+    a = torch.sort(packed[:n].view(torch.int16).cpu().flatten()).values
+    b = torch.sort(W1.view(torch.int16).cpu().flatten()).values
+    assert torch.equal(a, b)
+    a = torch.sort(packed[n:].view(torch.int16).cpu().flatten()).values
+    b = torch.sort(W2.view(torch.int16).cpu().flatten()).values
+    assert torch.equal(a, b)
+
+
+def test_mlp_fused_row_maps_and_unsupported_shapes():
+    dtype = torch.bfloat16
+    M, C, Hd = 4 * 49, 128, 256
+    X = draw((M, C), 86, dtype)
+    W1, b1 = draw((Hd, C), 87, dtype, C ** -0.5), draw((Hd,), 88, dtype, 0.3)
+    W2, b2 = draw((C, Hd), 89, dtype, Hd ** -0.5), draw((C,), 90, dtype, 0.3)
+    # X read through a window partition with roll
+    chain_in = V.window_partition_chain(1, 14, 14, C, 7, 3)
+    xm = sm.Map.create((1, 14, 14, C), chain_in)
+    xin = V.apply_chain(to_np(X).reshape(1, 14, 14, C), chain_in).reshape(M, C)
+    want = O.linear(O.gelu(O.linear(xin, to_np(W1), to_np(b1))), to_np(W2), to_np(b2))
+    packed = sm.mlp_pack(dev(W1, dtype), dev(W2, dtype))
+    got = sm.mlp_fused(dev(X, dtype), packed, dev(b1, dtype), dev(b2, dtype), x_map=xm)
+    assert_close(got, want, dtype, "fused MLP with a mapped X", float(np.abs(want).max()) + 1.0)
+    assert not sm.mlp_fused_supported(96, 384, dtype)
+    assert not sm.mlp_fused_supported(128, 100, dtype)
+    assert not sm.mlp_fused_supported(128, 512, torch.float32)
+    with pytest.raises(sm.SmError):
+        sm.mlp_pack(dev(draw((384, 96), 2, dtype), dtype), dev(draw((96, 384), 4, dtype), dtype))

@@ -31,18 +31,20 @@ def net_dev(net, dtype):
 
 
 @pytest.mark.parametrize("mode", MODES)
-def test_config2_stage3_chain_full_size(mode):
+@pytest.mark.parametrize("fuse_mlp", [True, False])
+def test_config2_stage3_chain_full_size(mode, fuse_mlp):
     B, H, W, C, h, w, depth = 32, 14, 14, 384, 12, 7, 6
     x, blocks = Wl.swin_stage_case(B, H, W, C, h, w, depth)
     net = {"stages": [blocks]}
-    chain = sm.SwinChain(B, [(C, h, depth, H, W)], w, net_dev(net, torch.bfloat16), torch.bfloat16, mode)
+    chain = sm.SwinChain(B, [(C, h, depth, H, W)], w, net_dev(net, torch.bfloat16), torch.bfloat16, mode, fuse_mlp=fuse_mlp)
     y = chain(dev(x, torch.bfloat16))
     torch.cuda.synchronize()
     want = swin.swin_stage(to_np(x), net_np(net)["stages"][0], H, W, w, h)
     got = to_np(y)
     assert rel_l2(got, want) <= 2e-2
     assert rel_l2(got - to_np(x), want - to_np(x)) <= 3e-2
-    assert sm.launch_counts() == ((42, 0) if mode == sm.SM_ELIDED else (42, 3 * 4 + 3 * 6))
+    n = 30 if fuse_mlp else 42          # per block: LayerNorm-2, FC1, FC2 become one kernel
+    assert sm.launch_counts() == ((n, 0) if mode == sm.SM_ELIDED else (n, 3 * 4 + 3 * 6))
 
 
 def small_net_case(dtype, mode):
