@@ -207,6 +207,8 @@ typedef struct {
   float norm_eps;
   const void* norm_gamma;       /* [K], device; required when norm != 0 */
   const void* norm_beta;        /* [K], device; nullable (ignored by RMSNorm) */
+  int32_t w_packed;             /* 1: W was rewritten by sm_linear_pack (see there); selects the kernel that streams the
+                                   weight into registers */
 } sm_linear_desc;
 /* a_map / c_map (nullable): maps with view shape [M, K] / natural output shape
  * [M, Nout] whose last dimension is contiguous: row r of A is read at
@@ -214,6 +216,16 @@ typedef struct {
  * is read at the same offset.  bias, residual nullable. */
 int sm_linear(const sm_linear_desc*, const void* A, const void* W, const void* bias, const void* residual,
               void* C, const sm_map* a_map, const sm_map* c_map, void* stream);
+/* Weight layout for short reduction dimensions (Sec. 3.2.2's rule, the producer writes the layout its consumer reads
+ * best, applied to a constant): for bf16, K in {128, 256, 384} and N a multiple of 32 (sm_linear_pack_supported),
+ * sm_linear_pack rewrites W [N, K] into `packed` (device, N * K elements, 16-byte aligned, caller-owned) in the order
+ * of the matrix-core operand fragments.  sm_linear with w_packed = 1 and that buffer as W then runs a kernel in which
+ * a workgroup keeps 32 rows of A in LDS for all N outputs and the weight streams from L2 straight into registers: no
+ * K-loop barriers, and a LayerNorm (norm = 1, beta required) costs one pass over the resident tile.  It pays where
+ * M is small (one or two rounds of workgroups of the tiled kernel).  Restrictions with w_packed: activation none or
+ * GELU, no RoPE, no transposed store, row maps only (a map that splits columns returns SM_ERR_UNSUPPORTED). */
+int sm_linear_pack_supported(int N, int K, int dtype);
+int sm_linear_pack(const void* W, int N, int K, int dtype, void* packed, void* stream);
 
 /* Fused two-layer MLP  Y = residual + gelu(norm(X) . W1^T + b1) . W2^T + b2  in one kernel, the hidden activation kept
  * in registers (an extension next to the paper's path: the paper keeps two MatMuls apart, Table 5; here the largest

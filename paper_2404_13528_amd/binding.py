@@ -46,7 +46,8 @@ class LinearDesc(C.Structure):
     _fields_ = [("M", C.c_int64), ("N", C.c_int32), ("K", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
                 ("rope_cols", C.c_int32), ("rope_dim", C.c_int32), ("rope_seq", C.c_int32), ("rope_base", C.c_float),
                 ("c_transposed", C.c_int32), ("c_batch_rows", C.c_int64),
-                ("norm", C.c_int32), ("norm_eps", C.c_float), ("norm_gamma", C.c_void_p), ("norm_beta", C.c_void_p)]
+                ("norm", C.c_int32), ("norm_eps", C.c_float), ("norm_gamma", C.c_void_p), ("norm_beta", C.c_void_p),
+                ("w_packed", C.c_int32)]
 
 
 class AttentionDesc(C.Structure):
@@ -267,10 +268,25 @@ def groupnorm(x, gamma, beta, G, eps=1e-6, tokens_out=False, split=False, stream
     return y
 
 
+def linear_pack_supported(N, K, dtype):
+    import torch
+    code = dtype if isinstance(dtype, int) else (SM_BF16 if dtype == torch.bfloat16 else SM_F32)
+    return bool(lib().sm_linear_pack_supported(int(N), int(K), code))
+
+
+def linear_pack(W, stream=None):
+    """W [N, K] in the operand order of the packed-weight Linear kernel (same shape, new tensor)."""
+    import torch
+    packed = torch.empty_like(W)
+    check(lib().sm_linear_pack(_ptr(W), int(W.shape[0]), int(W.shape[1]), _dt(W), _ptr(packed), _stream(stream)), "sm_linear_pack")
+    return packed
+
+
 def linear(A, W, bias=None, residual=None, act="none", rope=None, a_map=None, c_map=None,
-           c_transposed_batch=0, out=None, M=None, norm=None, stream=None):
+           c_transposed_batch=0, out=None, M=None, norm=None, packed=False, stream=None):
     """C = epilogue(A . W^T).  rope = (rope_cols, rope_dim, seq, base) or None.
-    norm = ("layer" | "rms", gamma, beta or None, eps): that norm of A's rows folded into the load."""
+    norm = ("layer" | "rms", gamma, beta or None, eps): that norm of A's rows folded into the load.
+    packed: W is linear_pack(W)."""
     import torch
     N, K = W.shape
     if M is None:
@@ -285,6 +301,7 @@ def linear(A, W, bias=None, residual=None, act="none", rope=None, a_map=None, c_
         d.norm_gamma, d.norm_beta, d.norm_eps = _ptr(norm[1]).value, _ptr(norm[2]).value, norm[3]
     d.c_transposed = 1 if c_transposed_batch else 0
     d.c_batch_rows = c_transposed_batch
+    d.w_packed = 1 if packed else 0
     Cm = torch.empty((M, n_out), dtype=A.dtype, device=A.device) if out is None else out
     check(lib().sm_linear(C.byref(d), _ptr(A), _ptr(W), _ptr(bias), _ptr(residual), _ptr(Cm),
                           a_map.h if a_map else None, c_map.h if c_map else None, _stream(stream)), "sm_linear")

@@ -137,9 +137,62 @@ extern "C" int sm_groupnorm(const void* x, const void* gamma, const void* beta, 
   return SM_OK;
 }
 
+namespace sm {
+int lin32_checked(Lin32Args& a, void* stream, const char* who) {
+  if (!lin32_supported(a.N, a.K, SM_BF16)) return fail(SM_ERR_UNSUPPORTED, "%s: no packed-weight kernel for N = %d, K = %d", who, a.N, a.K);
+  if (a.M < 0) return fail(SM_ERR_SHAPE, "%s: negative row count", who);
+  if (a.act != SM_ACT_NONE && a.act != SM_ACT_GELU) return fail(SM_ERR_UNSUPPORTED, "%s: packed weights go with activation none or GELU", who);
+  if (a.norm != 0 && a.norm != 1) return fail(SM_ERR_UNSUPPORTED, "%s: packed weights go with no norm or LayerNorm", who);
+  if (a.M == 0) return SM_OK;
+  if (!a.X || !a.Wp || !a.Y) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
+  if (!aligned16(a.X) || !aligned16(a.Wp) || !aligned16(a.Y) || (a.bias && !aligned16(a.bias)) || (a.residual && !aligned16(a.residual)))
+    return fail(SM_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  if (a.norm) {
+    if (!a.norm_gamma || !a.norm_beta || !aligned16(a.norm_gamma) || !aligned16(a.norm_beta))
+      return fail(SM_ERR_INVALID_ARG, "%s: folded LayerNorm needs 16-byte aligned gamma and beta", who);
+    if (!(a.norm_eps > 0.f)) return fail(SM_ERR_INVALID_ARG, "%s: folded LayerNorm needs eps > 0", who);
+  }
+  if ((a.M + 31) / 32 > 0x7fffffff) return fail(SM_ERR_SHAPE, "%s: too many rows", who);
+  char label[128];
+  std::snprintf(label, sizeof label, "%spgemm_bf16[%lld,%d,%d]%s%s%s", a.norm ? "ln+" : "", (long long)a.M, a.N, a.K,
+                a.act == SM_ACT_GELU ? "+gelu" : "", a.residual ? "+res" : "", a.y_rows.identity ? "" : "+scatter");
+  Timed tm(label, stream);
+  const int rc = launch_lin32(a, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
+  count_compute(1);
+  return SM_OK;
+}
+}  // namespace sm
+
+extern "C" int sm_linear_pack_supported(int N, int K, int dtype) { return sm::lin32_supported(N, K, dtype) ? 1 : 0; }
+
+extern "C" int sm_linear_pack(const void* W, int N, int K, int dtype, void* packed, void* stream) {
+  if (!dtype_ok(dtype)) return fail(SM_ERR_INVALID_ARG, "sm_linear_pack: unknown dtype");
+  if (!sm::lin32_supported(N, K, dtype)) return fail(SM_ERR_UNSUPPORTED, "sm_linear_pack: no packed-weight kernel for N = %d, K = %d, dtype %d", N, K, dtype);
+  if (!W || !packed) return fail(SM_ERR_INVALID_ARG, "sm_linear_pack: null pointer");
+  if (!aligned16(W) || !aligned16(packed)) return fail(SM_ERR_INVALID_ARG, "sm_linear_pack: pointers must be 16-byte aligned");
+  Timed tm("linear_pack", stream);
+  const int rc = launch_lin_pack(W, N, K, packed, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "sm_linear_pack: launch failed (hip error %d)", rc);
+  return SM_OK;
+}
+
 extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, const void* bias, const void* residual,
                          void* C, const sm_map* a_map, const sm_map* c_map, void* stream) {
   if (!d) return fail(SM_ERR_INVALID_ARG, "sm_linear: null descriptor");
+  if (d->w_packed) {
+    if (!dtype_ok(d->dtype)) return fail(SM_ERR_INVALID_ARG, "sm_linear: unknown dtype");
+    if (!sm::lin32_supported(d->N, d->K, d->dtype)) return fail(SM_ERR_UNSUPPORTED, "sm_linear: no packed-weight kernel for N = %d, K = %d, dtype %d", d->N, d->K, d->dtype);
+    if (d->rope_cols || d->c_transposed) return fail(SM_ERR_UNSUPPORTED, "sm_linear: packed weights go without RoPE and transposed stores");
+    Lin32Args a; std::memset(&a, 0, sizeof(a));
+    a.X = A; a.Wp = W; a.bias = bias; a.residual = residual; a.Y = C; a.M = d->M; a.N = d->N; a.K = d->K; a.act = d->act;
+    a.norm = d->norm; a.norm_eps = d->norm_eps; a.norm_gamma = d->norm_gamma; a.norm_beta = d->norm_beta;
+    int rc = rows_of(a_map, d->M, d->K, d->K, &a.x_rows, "sm_linear(A)");
+    if (rc) return rc;
+    rc = rows_of(c_map, d->M, d->N, d->N, &a.y_rows, "sm_linear(C)");
+    if (rc) return rc;
+    return lin32_checked(a, stream, "sm_linear");
+  }
   GemmArgs g; std::memset(&g, 0, sizeof(g));
   g.A = A; g.W = W; g.bias = bias; g.residual = residual; g.C = C;
   g.M = d->M; g.N = d->N; g.K = d->K; g.dtype = d->dtype; g.act = d->act;

@@ -68,6 +68,58 @@ __global__ void mlp_pack_kernel(const bf16_t* W1, const bf16_t* W2, mlp_u32x4* p
   packed[o] = *(const mlp_u32x4*)src;
 }
 
+// X tile of 32 token rows -> LDS, rows at an odd pitch of 16-byte slots (rows past M as zeros); 256 threads
+template <int C>
+__device__ __forceinline__ void mlp_load_x_tile(mlp_u32x4* x_l, const bf16_t* X, int64_t row0, int64_t M, int ident, int64_t ld,
+                                                const SM_KARG RowProg* rows) {
+  constexpr int XS = C / 8, XP = XS + 1;
+  for (int s = threadIdx.x; s < 32 * XS; s += 256) {
+    const int r = s / XS, c = s - r * XS;
+    const int64_t row = row0 + r;
+    mlp_u32x4 v = {0u, 0u, 0u, 0u};
+    if (row < M) v = *(const mlp_u32x4*)(X + (ident ? row * ld : eval_rows_k(rows, row)) + c * 8);
+    x_l[r * XP + c] = v;
+  }
+}
+
+// LayerNorm of the tile's rows in place (the norm that precedes the product, folded): eight lanes per token,
+// two-pass fp32 statistics, the result rounded to bf16 as a separate norm kernel would have stored it
+template <int C>
+__device__ __forceinline__ void mlp_norm_x_tile(mlp_u32x4* x_l, float eps, const mlp_u32x4* gam, const mlp_u32x4* bet) {
+  constexpr int XS = C / 8, XP = XS + 1;
+  const int r = threadIdx.x >> 3, p = threadIdx.x & 7;
+  mlp_u32x4* xr = x_l + r * XP;
+  float sum = 0.f;
+  for (int c = p; c < XS; c += 8) {
+    float f[8];
+    mlp_unpack8(xr[c], f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sum += f[e];
+  }
+  sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64); sum += __shfl_xor(sum, 4, 64);
+  const float mean = sum / (float)C;
+  float var = 0.f;
+  for (int c = p; c < XS; c += 8) {
+    float f[8];
+    mlp_unpack8(xr[c], f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; var += d * d; }
+  }
+  var += __shfl_xor(var, 1, 64); var += __shfl_xor(var, 2, 64); var += __shfl_xor(var, 4, 64);
+  const float rstd = rsqrtf(var / (float)C + eps), sh = -mean * rstd;
+  for (int c = p; c < XS; c += 8) {
+    float f[8], gf[8], bf[8];
+    mlp_unpack8(xr[c], f);
+    mlp_unpack8(gam[c], gf);
+    mlp_unpack8(bet[c], bf);
+    mlp_u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      o[e] = mlp_pack2(fmaf(fmaf(f[2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
+    xr[c] = o;
+  }
+}
+
 constexpr int MLP_RP = 36;       // floats per token row of a 32 x 32 partial tile in LDS (144 bytes: conflict-free 16-byte writes)
 
 template <int C>
@@ -84,7 +136,8 @@ __global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
   float* red = (float*)(smem_raw + (size_t)BM * XP * 16);                 // [4 waves][4 blocks][32][MLP_RP]
   mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + (size_t)BM * XP * 16 + (size_t)4 * 4 * 32 * MLP_RP * 4);   // [Hd / 8]
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index as a scalar: slice bases become scalar addresses
   const int64_t row0 = (int64_t)blockIdx.x * BM;
   const bf16_t* X = (const bf16_t*)g.X;
   const int Hd = g.Hd;
@@ -106,55 +159,13 @@ __global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
       for (int s = 0; s < 2; ++s) w2[t][s] = *(const mlp_u32x4*)(W2p + o2 + (t * 2 + s) * 1024);
   }
 
-  // X tile -> LDS (rows past M as zeros)
-  for (int s = tid; s < BM * XS; s += 256) {
-    const int r = s / XS, c = s - r * XS;
-    const int64_t row = row0 + r;
-    mlp_u32x4 v = {0u, 0u, 0u, 0u};
-    if (row < g.M) v = *(const mlp_u32x4*)(X + (g.x_rows.identity ? row * g.x_rows.ld : eval_rows_k(&gk->x_rows, row)) + c * 8);
-    x_l[r * XP + c] = v;
-  }
+  mlp_load_x_tile<C>(x_l, X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
   // the first bias as well: a global load inside the main loop would be waited for in issue order, behind the
   // whole weight prefetch
   for (int s = tid; s < Hd / 8; s += 256) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
   __syncthreads();
-
   if (g.norm) {
-    // LayerNorm of the tile's rows in place (the norm that precedes the MLP, folded): eight lanes per token,
-    // two-pass fp32 statistics, the result rounded to bf16 as a separate norm kernel would have stored it
-    const int r = tid >> 3, p = tid & 7;
-    mlp_u32x4* xr = x_l + r * XP;
-    float sum = 0.f;
-    for (int c = p; c < XS; c += 8) {
-      float f[8];
-      mlp_unpack8(xr[c], f);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) sum += f[e];
-    }
-    sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64); sum += __shfl_xor(sum, 4, 64);
-    const float mean = sum / (float)C;
-    float var = 0.f;
-    for (int c = p; c < XS; c += 8) {
-      float f[8];
-      mlp_unpack8(xr[c], f);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; var += d * d; }
-    }
-    var += __shfl_xor(var, 1, 64); var += __shfl_xor(var, 2, 64); var += __shfl_xor(var, 4, 64);
-    const float rstd = rsqrtf(var / (float)C + g.norm_eps), sh = -mean * rstd;
-    const mlp_u32x4* gam = (const mlp_u32x4*)g.norm_gamma;
-    const mlp_u32x4* bet = (const mlp_u32x4*)g.norm_beta;
-    for (int c = p; c < XS; c += 8) {
-      float f[8], gf[8], bf[8];
-      mlp_unpack8(xr[c], f);
-      mlp_unpack8(gam[c], gf);
-      mlp_unpack8(bet[c], bf);
-      mlp_u32x4 o;
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        o[e] = mlp_pack2(fmaf(fmaf(f[2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
-      xr[c] = o;
-    }
+    mlp_norm_x_tile<C>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
     __syncthreads();
   }
 
@@ -317,6 +328,164 @@ int launch_mlp_fused(const MlpArgs& g, void* stream) {
     case 128: return mlp_launch<128>(g, stream);
     case 256: return mlp_launch<256>(g, stream);
     case 384: return mlp_launch<384>(g, stream);
+  }
+  return (int)hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Linear for a short reduction dimension (K = C in {128, 256, 384}), Y = act(norm(X) . W^T + b) (+ residual): the first
+// half of the kernel above on its own.  A workgroup owns 32 token rows, whose K elements stay in LDS for all N outputs;
+// the N / 32 row slices of W are dealt round-robin to the four waves and stream from L2 straight into MFMA operand
+// registers (packed by lin_pack_kernel: fragment (slice sc, step kk) at sc * K/16 + kk, lane (l32, hf) =
+// W[32 sc + l32][16 kk + 8 hf ..+7]); every wave finishes its 32 x 32 outputs in registers and stores them: no
+// barrier after the prologue.  Against the tiled kernel of k_gemm.hip this trades L2 -> CU traffic (W once per 32
+// rows) for the absence of K-loop barriers and of a separate norm kernel.  Measured (with LayerNorm, against norm
+// kernel + tiled kernel resp. the tiled kernel's own folded norm): 200704 x 384 x 128: 69 us against 89;
+// 50176 x 768 x 256: 55 against 71; 6272 x 1152 x 384: 26 against 26.  The block executors do not use it.
+template <int C, bool RES>
+__global__ __launch_bounds__(256, 1) void lin32_kernel(Lin32Args g) {
+  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1;
+  const SM_KARG Lin32Args* gk = kernarg_ptr<Lin32Args>();
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                                  // [32][XP]
+  mlp_u32x4* b_l = (mlp_u32x4*)(smem_raw + (size_t)32 * XP * 16);         // [N / 8]
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index as a scalar: slice bases become scalar addresses
+  const int64_t row0 = (int64_t)blockIdx.x * 32;
+  const int nsub = g.N >> 5;
+  const char* Wp = (const char*)g.Wp;
+
+  mlp_u32x4 w1[KK];
+  {
+    const char* wb = Wp + (size_t)((w < nsub ? w : 0) * KK) * 1024u;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) w1[kk] = *(const mlp_u32x4*)(wb + kk * 1024 + lane * 16u);
+  }
+  mlp_load_x_tile<C>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  for (int s = tid; s < g.N / 8; s += 256) b_l[s] = g.bias ? ((const mlp_u32x4*)g.bias)[s] : mlp_u32x4{0u, 0u, 0u, 0u};
+  __syncthreads();
+  if (g.norm) {
+    mlp_norm_x_tile<C>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
+    __syncthreads();
+  }
+
+  // the lane's X fragments do not depend on the slice: they stay in registers (K / 4 of them; the kernel fits two
+  // workgroups per CU with them)
+  mlp_u32x4 xf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) xf[kk] = x_l[l32 * XP + hf + 2 * kk];
+  const int64_t row = row0 + l32;                 // the lane's token: accumulator column
+  const bool row_ok = row < g.M;
+  const int64_t rowc = row_ok ? row : g.M - 1;    // lanes past M read the last row's residual and store nothing
+  const int64_t ro = g.y_rows.identity ? rowc * g.y_rows.ld : eval_rows_k(&gk->y_rows, rowc);
+  const bf16_t* R = (const bf16_t*)g.residual;
+  bf16_t* Y = (bf16_t*)g.Y;
+  const bool gelu_on = g.act == SM_ACT_GELU;
+  // the slice loop is one basic block up to the final masked store, so that the issue order below holds; loads
+  // that the epilogue needs are issued before the slice's weight prefetch (vector loads return in issue order)
+  for (int sc = w; sc < nsub; sc += 4) {
+    const int nx = sc + 4 < nsub ? sc + 4 : sc;
+    const mlp_u32x4 bias_v = b_l[sc * 4 + hf];          // features 8 hf ..+7 and 16 + 8 hf ..+7 of the slice: the two
+    const mlp_u32x4 bias_w = b_l[sc * 4 + 2 + hf];      // runs this lane stores
+    mlp_u32x4 res[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+    if constexpr (RES) {
+      res[0] = *(const mlp_u32x4*)(R + ro + sc * 32 + hf * 8);
+      res[1] = *(const mlp_u32x4*)(R + ro + sc * 32 + 16 + hf * 8);
+    }
+    mlp_f32x16 h;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) h[e] = 0.f;
+    const char* wb = Wp + (size_t)(nx * KK) * 1024u;      // scalar
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, xf[kk]), h, 0, 0, 0);
+      w1[kk] = *(const mlp_u32x4*)(wb + kk * 1024 + lane * 16u);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    // accumulator register 4b + i of lane (token, hf) is feature 8b + 4 hf + i: one v_permlane32_swap per value pair
+    // gives each lane eight consecutive features (run 2 gp + hf of the slice's four runs of eight)
+    mlp_u32x4 outv[2];
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp) {
+      float v[8], bb[8], rr[8];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(h[8 * gp + j]), __float_as_uint(h[8 * gp + 4 + j]), false, false);
+        v[j] = __uint_as_float(sw[0]);
+        v[4 + j] = __uint_as_float(sw[1]);
+      }
+      mlp_unpack8(gp ? bias_w : bias_v, bb);
+      mlp_unpack8(res[gp], rr);
+      mlp_u32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float a = v[2 * e] + bb[2 * e], b = v[2 * e + 1] + bb[2 * e + 1];
+        const float ga = gelu_poly(a), gb = gelu_poly(b);
+        a = gelu_on ? ga : a;
+        b = gelu_on ? gb : b;
+        o[e] = mlp_pack2(a + rr[2 * e], b + rr[2 * e + 1]);
+      }
+      outv[gp] = o;
+    }
+    if (row_ok) {
+      // Written as assembly so that the compiler's wait-count bookkeeping sees loads only: with stores pending next to
+      // loads it stops counting and waits for everything (vmcnt 0) at the top of the next slice, which exposes the
+      // latency of the whole weight prefetch.  Its counts stay safe: it may wait for up to two operations more than
+      // needed, never fewer (loads return in issue order among themselves).
+      bf16_t* yp = Y + ro + sc * 32 + hf * 8;
+      asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:32\n\ts_nop 2"
+                   :: "v"(yp), "v"(outv[0]), "v"(outv[1]) : "memory");
+    }
+  }
+}
+
+__global__ void lin_pack_kernel(const bf16_t* W, mlp_u32x4* packed, int N, int K) {
+  const int KK = K / 16;
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= (int64_t)N * K / 8) return;
+  const int lane = (int)(o & 63), l32 = lane & 31, hf = lane >> 5;
+  const int64_t frag = o >> 6;
+  const int sc = (int)(frag / KK), kk = (int)(frag - (int64_t)sc * KK);
+  packed[o] = *(const mlp_u32x4*)(W + (int64_t)(32 * sc + l32) * K + 16 * kk + 8 * hf);
+}
+
+template <int C, bool RES>
+static int lin32_launch2(const Lin32Args& g, void* stream) {
+  const size_t smem = (size_t)32 * (C / 8 + 1) * 16 + (size_t)g.N * 2;
+  static size_t allowed = 0;
+  if (smem > allowed) {
+    const hipError_t e = hipFuncSetAttribute((const void*)lin32_kernel<C, RES>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return (int)e;
+    allowed = smem;
+  }
+  lin32_kernel<C, RES><<<dim3((unsigned)((g.M + 31) / 32)), dim3(256), smem, (hipStream_t)stream>>>(g);
+  return (int)hipGetLastError();
+}
+template <int C>
+static int lin32_launch(const Lin32Args& g, void* stream) {
+  return g.residual ? lin32_launch2<C, true>(g, stream) : lin32_launch2<C, false>(g, stream);
+}
+
+bool lin32_supported(int N, int K, int dtype) {
+  return dtype == SM_BF16 && (K == 128 || K == 256 || K == 384) && N >= 32 && N % 32 == 0 && N <= 16384;
+}
+
+int launch_lin_pack(const void* W, int N, int K, void* packed, void* stream) {
+  const int64_t n = (int64_t)N * K / 8;
+  lin_pack_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>((const bf16_t*)W, (mlp_u32x4*)packed, N, K);
+  return (int)hipGetLastError();
+}
+
+int launch_lin32(const Lin32Args& g, void* stream) {
+  switch (g.K) {
+    case 128: return lin32_launch<128>(g, stream);
+    case 256: return lin32_launch<256>(g, stream);
+    case 384: return lin32_launch<384>(g, stream);
   }
   return (int)hipErrorInvalidValue;
 }

@@ -66,6 +66,18 @@ bool mlp_fused_supported(int C, int Hd, int dtype);
 int launch_mlp_pack(const void* W1, const void* W2, int C, int Hd, void* packed, void* stream);
 int launch_mlp_fused(const MlpArgs& a, void* stream);
 
+// Linear for K in {128, 256, 384} (bf16) with the weight streamed into registers: Y = act(norm(X) . W^T + bias) (+ residual).
+// Wp: W [N, K] packed by launch_lin_pack.  act: SM_ACT_NONE or SM_ACT_GELU.
+struct Lin32Args {
+  const void* X; const void* Wp; const void* bias; const void* residual; void* Y;
+  int64_t M; int N, K; int act;
+  int norm; float norm_eps; const void* norm_gamma; const void* norm_beta;
+  RowProg x_rows, y_rows;       // row r of X; row r of Y and of the residual (pitch N when identity)
+};
+bool lin32_supported(int N, int K, int dtype);
+int launch_lin_pack(const void* W, int N, int K, void* packed, void* stream);
+int launch_lin32(const Lin32Args& a, void* stream);
+
 int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,
                      const void* rpb_table, void* stream);
 
@@ -80,6 +92,7 @@ int rows_of(const sm_map* m, int64_t rows, int64_t inner, int64_t identity_ld, R
 int norm_checked(NormArgs& a, void* stream, const char* who);
 int gemm_checked(GemmArgs& g, void* stream, const char* who);
 int mlp_checked(MlpArgs& a, void* stream, const char* who);
+int lin32_checked(Lin32Args& a, void* stream, const char* who);
 int attention_checked(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table,
                       void* stream, const char* who);
 int map_vector_width(const sm_map& m, int esize);

@@ -380,3 +380,49 @@ def test_mlp_fused_row_maps_and_unsupported_shapes():
     assert not sm.mlp_fused_supported(128, 512, torch.float32)
     with pytest.raises(sm.SmError):
         sm.mlp_pack(dev(draw((384, 96), 2, dtype), dtype), dev(draw((96, 384), 4, dtype), dtype))
+
+
+@pytest.mark.parametrize("M,N,K", [(32, 128, 128), (70, 96, 128), (200, 1152, 384), (6272, 384, 384), (45, 160, 256)])
+@pytest.mark.parametrize("variant", ["plain", "gelu", "res", "ln+res"])
+def test_linear_with_packed_weight(M, N, K, variant):
+    # the kernel that streams a packed weight into registers against the oracle: row counts that end inside a 32-row
+    # tile, column counts that leave waves with unequal (or no) slices; bias, GELU, residual, folded LayerNorm
+    dtype = torch.bfloat16
+    A = draw((M, K), 100, dtype, 2.0, 0.7)
+    W = draw((N, K), 101, dtype, K ** -0.5)
+    b = draw((N,), 102, dtype, 0.5)
+    R = draw((M, N), 103, dtype)
+    g, be = draw((K,), 104, dtype, 0.2, 1.0), draw((K,), 105, dtype, 0.2)
+    xin = O.layer_norm(to_np(A), to_np(g), to_np(be)) if "ln" in variant else to_np(A)
+    want = O.linear(xin, to_np(W), to_np(b))
+    if variant == "gelu":
+        want = O.gelu(want)
+    if "res" in variant:
+        want = want + to_np(R)
+    assert sm.linear_pack_supported(N, K, dtype)
+    Wp = sm.linear_pack(dev(W, dtype))
+    assert torch.equal(torch.sort(Wp.view(torch.int16).flatten()).values, torch.sort(dev(W, dtype).view(torch.int16).flatten()).values)
+    got = sm.linear(dev(A, dtype), Wp, dev(b, dtype), residual=dev(R, dtype) if "res" in variant else None,
+                    act="gelu" if variant == "gelu" else "none",
+                    norm=("layer", dev(g, dtype), dev(be, dtype), 1e-5) if "ln" in variant else None, packed=True)
+    assert_close(got, want, dtype, "packed-weight Linear " + variant, float(np.abs(want).max()) + 1.0)
+
+
+def test_linear_with_packed_weight_row_maps_and_refusals():
+    dtype = torch.bfloat16
+    C = 128
+    M = 4 * 49
+    A = draw((M, C), 106, dtype)
+    W, b = draw((96, C), 107, dtype, C ** -0.5), draw((96,), 108, dtype, 0.3)
+    chain_in = V.window_partition_chain(1, 14, 14, C, 7, 3)
+    am = sm.Map.create((1, 14, 14, C), chain_in)
+    xin = V.apply_chain(to_np(A).reshape(1, 14, 14, C), chain_in).reshape(M, C)
+    want = O.linear(xin, to_np(W), to_np(b))
+    Wp = sm.linear_pack(dev(W, dtype))
+    got = sm.linear(dev(A, dtype), Wp, dev(b, dtype), a_map=am, packed=True)
+    assert_close(got, want, dtype, "packed-weight Linear with a gathered A", float(np.abs(want).max()) + 1.0)
+    assert not sm.linear_pack_supported(96, 96, dtype)
+    assert not sm.linear_pack_supported(100, 128, dtype)
+    assert not sm.linear_pack_supported(128, 128, torch.float32)
+    with pytest.raises(sm.SmError):
+        sm.linear(dev(A, dtype), Wp, dev(b, dtype), act="swiglu", packed=True)
