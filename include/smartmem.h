@@ -244,8 +244,15 @@ typedef struct {
   int64_t M; int32_t C, hidden, dtype;
   int32_t norm; float norm_eps;
   const void* norm_gamma; const void* norm_beta;
+  /* proj_packed != null: the Linear in front of the MLP's residual stream runs in the same kernel (a transformer
+   * block's attention output projection): x1 = X . Wproj^T + proj_bias + proj_residual, then
+   * Y = x1 + MLP(norm(x1)); x1 (rounded to bf16) never reaches memory.  proj_packed = sm_linear_pack of
+   * Wproj [C, C]; proj_bias [C]; proj_residual [M, C] is read through y_map like Y is written; the `residual`
+   * argument is ignored.  Needs three token tiles in LDS: sm_mlp_proj_supported says whether a shape fits. */
+  const void* proj_packed; const void* proj_bias; const void* proj_residual;
 } sm_mlp_desc;
 int sm_mlp_fused_supported(int C, int hidden, int dtype);
+int sm_mlp_proj_supported(int C, int hidden, int dtype);
 int sm_mlp_pack(const void* W1, const void* W2, int C, int hidden, int dtype, void* packed, void* stream);
 int sm_mlp_fused(const sm_mlp_desc*, const void* X, const void* packed, const void* b1, const void* b2,
                  const void* residual, void* Y, const sm_map* x_map, const sm_map* y_map, void* stream);
@@ -285,6 +292,10 @@ typedef struct {
              *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
   const void* mlp_packed;       /* nullable: sm_mlp_pack(w1, w2); with it (and a shape sm_mlp_fused_supported accepts)
                                    LayerNorm-2, FC1 + GELU and FC2 + residual run as the one fused MLP kernel */
+  const void* proj_packed;      /* nullable: sm_linear_pack(wproj); with it and mlp_packed (and a shape
+                                   sm_mlp_proj_supported accepts), SM_ELIDED also runs the output projection, its
+                                   window-reverse store and the first residual inside that kernel.  SM_EXPLICIT cannot:
+                                   its materialised reverse copy sits between the projection and the residual */
 } sm_swin_weights;
 size_t sm_swin_block_workspace_bytes(const sm_swin_cfg*, int mode);
 int sm_swin_block(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y,
@@ -316,8 +327,8 @@ int sm_attn_block(const sm_attn_cfg*, const void* const* weights, const void* x,
  * than one window), patch merging between stages (2x2 gather folded into the
  * LayerNorm's load), optional head (LayerNorm, mean over tokens, Linear).
  * weights: device pointers in forward order: embed {w, b, ln_g, ln_b} if
- * has_embed; per stage: per block the 14 pointers of sm_swin_weights in
- * declaration order (mlp_packed may be null), then (between stages) merge {ln_g, ln_b, w}; head
+ * has_embed; per stage: per block the 15 pointers of sm_swin_weights in
+ * declaration order (mlp_packed and proj_packed may be null), then (between stages) merge {ln_g, ln_b, w}; head
  * {ln_g, ln_b, w, b} if has_head.
  * x: image [B, in_ch, img, img] if has_embed else tokens [B, H0*W0, C0].
  * y: logits [B, n_cls] if has_head else tokens of the last stage.

@@ -68,14 +68,18 @@ SWIN_WEIGHT_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rpb_table", "wproj", "bp
 
 
 class SwinWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in SWIN_WEIGHT_NAMES + ("mlp_packed",)]
+    _fields_ = [(n, C.c_void_p) for n in SWIN_WEIGHT_NAMES + ("mlp_packed", "proj_packed")]
 
 
 def _packed_mlp(p, Cc, mlp_ratio, dtype, fuse_mlp):
-    """The block's MLP weights in the fused kernel's order (a new tensor), or None where there is no such kernel."""
+    """[MLP weights, projection weight] of a block in the fused kernels' order (new tensors), None where there is no
+    such kernel.  fuse_mlp: False (none), "mlp" (the MLP only) or True (the output projection as well)."""
+    import torch
     if not fuse_mlp or not mlp_fused_supported(Cc, mlp_ratio * Cc, dtype):
-        return None
-    return mlp_pack(p["w1"], p["w2"])
+        return [None, None]
+    code = SM_BF16 if dtype == torch.bfloat16 else SM_F32
+    proj = fuse_mlp is True and bool(lib().sm_mlp_proj_supported(int(Cc), int(mlp_ratio * Cc), code))
+    return [mlp_pack(p["w1"], p["w2"]), linear_pack(p["wproj"]) if proj else None]
 
 
 class AttnCfg(C.Structure):
@@ -316,7 +320,8 @@ def mlp_fused_supported(C_, hidden, dtype):
 
 class MlpDesc(C.Structure):
     _fields_ = [("M", C.c_int64), ("C", C.c_int32), ("hidden", C.c_int32), ("dtype", C.c_int32),
-                ("norm", C.c_int32), ("norm_eps", C.c_float), ("norm_gamma", C.c_void_p), ("norm_beta", C.c_void_p)]
+                ("norm", C.c_int32), ("norm_eps", C.c_float), ("norm_gamma", C.c_void_p), ("norm_beta", C.c_void_p),
+                ("proj_packed", C.c_void_p), ("proj_bias", C.c_void_p), ("proj_residual", C.c_void_p)]
 
 
 def mlp_pack(W1, W2, out=None, stream=None):
@@ -328,9 +333,10 @@ def mlp_pack(W1, W2, out=None, stream=None):
     return packed
 
 
-def mlp_fused(X, packed, b1, b2, residual=None, norm=None, x_map=None, y_map=None, out=None, M=None, stream=None):
+def mlp_fused(X, packed, b1, b2, residual=None, norm=None, proj=None, x_map=None, y_map=None, out=None, M=None, stream=None):
     """Y = residual + gelu(norm(X) . W1^T + b1) . W2^T + b2 in one kernel (bf16); packed = mlp_pack(W1, W2);
-    norm = (gamma, beta, eps): LayerNorm of X's rows folded in."""
+    norm = (gamma, beta, eps): LayerNorm of X's rows folded in.
+    proj = (linear_pack(Wproj), bias, residual0): x1 = X . Wproj^T + bias + residual0 first, the MLP works on x1."""
     import torch
     hidden, Cc = b1.numel(), b2.numel()
     if M is None:
@@ -339,6 +345,8 @@ def mlp_fused(X, packed, b1, b2, residual=None, norm=None, x_map=None, y_map=Non
     d.M, d.C, d.hidden, d.dtype = M, Cc, hidden, _dt(X)
     if norm:
         d.norm, d.norm_gamma, d.norm_beta, d.norm_eps = 1, _ptr(norm[0]).value, _ptr(norm[1]).value, norm[2]
+    if proj:
+        d.proj_packed, d.proj_bias, d.proj_residual = _ptr(proj[0]).value, _ptr(proj[1]).value, _ptr(proj[2]).value
     Y = torch.empty((M, Cc), dtype=X.dtype, device=X.device) if out is None else out
     check(lib().sm_mlp_fused(C.byref(d), _ptr(X), _ptr(packed), _ptr(b1), _ptr(b2), _ptr(residual), _ptr(Y),
                              x_map.h if x_map else None, y_map.h if y_map else None, _stream(stream)), "sm_mlp_fused")
@@ -393,7 +401,7 @@ class SwinBlock:
         # the MLP weights are packed here, once: later in-place changes of w1 / w2 need a new SwinBlock
         self.packed = _packed_mlp(params, Cc, mlp_ratio, dtype, fuse_mlp)
         self.w = SwinWeights(*([params[n].data_ptr() for n in SWIN_WEIGHT_NAMES] +
-                               [self.packed.data_ptr() if self.packed is not None else None]))
+                               [t.data_ptr() if t is not None else None for t in self.packed]))
         n = lib().sm_swin_block_workspace_bytes(C.byref(self.cfg), mode)
         if n == 0:
             raise SmError("sm_swin_block_workspace_bytes: " + lib().sm_last_error().decode())
@@ -431,7 +439,7 @@ class SwinChain:
         for si, blocks in enumerate(net["stages"]):
             for p in blocks:
                 # (MLP weights packed once, here: later in-place changes of w1 / w2 need a new SwinChain)
-                ptrs += [p[k] for k in SWIN_WEIGHT_NAMES] + [_packed_mlp(p, stages[si][0], mlp_ratio, dtype, fuse_mlp)]
+                ptrs += [p[k] for k in SWIN_WEIGHT_NAMES] + _packed_mlp(p, stages[si][0], mlp_ratio, dtype, fuse_mlp)
             if si + 1 < len(net["stages"]):
                 ptrs += [net["merges"][si][k] for k in ("ln_g", "ln_b", "w")]
         if d.has_head:

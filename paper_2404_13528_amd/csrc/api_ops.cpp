@@ -242,9 +242,14 @@ int mlp_checked(MlpArgs& a, void* stream, const char* who) {
       return fail(SM_ERR_INVALID_ARG, "%s: folded LayerNorm needs 16-byte aligned gamma and beta", who);
     if (!(a.norm_eps > 0.f)) return fail(SM_ERR_INVALID_ARG, "%s: folded LayerNorm needs eps > 0", who);
   }
+  if (a.Wproj_p) {
+    if (!mlp_proj_supported(a.C, a.Hd, SM_BF16)) return fail(SM_ERR_UNSUPPORTED, "%s: projection + MLP does not fit the LDS for C = %d, hidden = %d", who, a.C, a.Hd);
+    if (!a.bproj || !a.resid0 || !aligned16(a.Wproj_p) || !aligned16(a.bproj) || !aligned16(a.resid0))
+      return fail(SM_ERR_INVALID_ARG, "%s: the fused projection needs 16-byte aligned packed weight, bias and residual", who);
+  }
   if ((a.M + 31) / 32 > 0x7fffffff) return fail(SM_ERR_SHAPE, "%s: too many rows", who);
   char label[96];
-  std::snprintf(label, sizeof label, "%smlp_bf16[%lld,%d,%d]", a.norm ? "ln+" : "", (long long)a.M, a.Hd, a.C);
+  std::snprintf(label, sizeof label, "%s%smlp_bf16[%lld,%d,%d]", a.Wproj_p ? "proj+" : "", a.norm ? "ln+" : "", (long long)a.M, a.Hd, a.C);
   Timed tm(label, stream);
   const int rc = launch_mlp_fused(a, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
@@ -254,6 +259,7 @@ int mlp_checked(MlpArgs& a, void* stream, const char* who) {
 }  // namespace sm
 
 extern "C" int sm_mlp_fused_supported(int C, int hidden, int dtype) { return sm::mlp_fused_supported(C, hidden, dtype) ? 1 : 0; }
+extern "C" int sm_mlp_proj_supported(int C, int hidden, int dtype) { return sm::mlp_proj_supported(C, hidden, dtype) ? 1 : 0; }
 
 extern "C" int sm_mlp_pack(const void* W1, const void* W2, int C, int hidden, int dtype, void* packed, void* stream) {
   if (!dtype_ok(dtype)) return fail(SM_ERR_INVALID_ARG, "sm_mlp_pack: unknown dtype");
@@ -275,6 +281,7 @@ extern "C" int sm_mlp_fused(const sm_mlp_desc* d, const void* X, const void* pac
   MlpArgs a; std::memset(&a, 0, sizeof(a));
   a.X = X; a.Wp = packed; a.b1 = b1; a.b2 = b2; a.residual = residual; a.Y = Y; a.M = d->M; a.C = d->C; a.Hd = d->hidden;
   a.norm = d->norm; a.norm_eps = d->norm_eps; a.norm_gamma = d->norm_gamma; a.norm_beta = d->norm_beta;
+  a.Wproj_p = d->proj_packed; a.bproj = d->proj_bias; a.resid0 = d->proj_residual;
   int rc = rows_of(x_map, d->M, d->C, d->C, &a.x_rows, "sm_mlp_fused(X)");
   if (rc) return rc;
   rc = rows_of(y_map, d->M, d->C, d->C, &a.y_rows, "sm_mlp_fused(Y)");

@@ -187,6 +187,20 @@ bool fold_norm(int n_cols) { return n_cols <= 512; }
 bool mlp_is_fused(const sm_swin_cfg& c, const sm_swin_weights* wt) {
   return wt->mlp_packed && mlp_fused_supported(c.C, c.mlp_ratio * c.C, c.dtype);
 }
+// ... and the output projection with its window-reverse store and the first residual in front of it (elided mode)
+bool proj_is_fused(const sm_swin_cfg& c, const sm_swin_weights* wt) {
+  return wt->proj_packed && wt->mlp_packed && mlp_proj_supported(c.C, c.mlp_ratio * c.C, c.dtype);
+}
+int run_proj_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* attn_out, const void* x, void* y, int64_t T,
+                       const RowProg& store, void* stream) {
+  MlpArgs a; std::memset(&a, 0, sizeof(a));
+  a.X = attn_out; a.Wp = wt->mlp_packed; a.b1 = wt->b1; a.b2 = wt->b2; a.Y = y;
+  a.M = T; a.C = c.C; a.Hd = c.mlp_ratio * c.C;
+  a.norm = 1; a.norm_eps = c.eps; a.norm_gamma = wt->ln2_g; a.norm_beta = wt->ln2_b;
+  a.Wproj_p = wt->proj_packed; a.bproj = wt->bproj; a.resid0 = x;
+  a.x_rows = identity_rows(c.C); a.y_rows = store;
+  return mlp_checked(a, stream, "sm_swin_block(proj+mlp)");
+}
 int run_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* x1, void* y, int64_t T, void* stream) {
   MlpArgs a; std::memset(&a, 0, sizeof(a));
   a.X = x1; a.Wp = wt->mlp_packed; a.b1 = wt->b1; a.b2 = wt->b2; a.residual = x1; a.Y = y;
@@ -245,6 +259,7 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
     }
     if ((rc = attention_checked(ad, (char*)qkv + plan->qkv_base[0] * es, (char*)qkv + plan->qkv_base[1] * es, (char*)qkv + plan->qkv_base[2] * es,
                                 bufO, wt->rpb_table, stream, "window attention"))) return rc;
+    if (proj_is_fused(*c, wt)) return run_proj_mlp_fused(*c, wt, bufO, x, y, T, plan->proj_store, stream);
     if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
     if (mlp_is_fused(*c, wt)) return run_mlp_fused(*c, wt, x1, y, T, stream);
     if (fold_norm(c->mlp_ratio * C)) {
@@ -365,7 +380,7 @@ int check_chain(const sm_chain_desc* c, const char* who) {
 
 int chain_weight_count(const sm_chain_desc* c) {
   int n = c->has_embed ? 4 : 0;
-  for (int s = 0; s < c->n_stages; ++s) n += 14 * c->stages[s].depth + (s + 1 < c->n_stages ? 3 : 0);
+  for (int s = 0; s < c->n_stages; ++s) n += 15 * c->stages[s].depth + (s + 1 < c->n_stages ? 3 : 0);
   return n + (c->has_head ? 4 : 0);
 }
 
@@ -397,11 +412,11 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
   if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: unknown mode %d", mode);
   if (n_weights != chain_weight_count(c)) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: %d weight pointers given, %d expected", n_weights, chain_weight_count(c));
   {
-    // every pointer is required except a block's fourteenth (the packed MLP weights)
+    // every pointer is required except a block's last two (the packed MLP and projection weights)
     std::vector<char> optional((size_t)n_weights, 0);
     int at = c->has_embed ? 4 : 0;
     for (int s = 0; s < c->n_stages; ++s) {
-      for (int k = 0; k < c->stages[s].depth; ++k) { optional[(size_t)at + 13] = 1; at += 14; }
+      for (int k = 0; k < c->stages[s].depth; ++k) { optional[(size_t)at + 13] = optional[(size_t)at + 14] = 1; at += 15; }
       if (s + 1 < c->n_stages) at += 3;
     }
     for (int i = 0; i < n_weights; ++i)
@@ -465,7 +480,7 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
       sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, shift, c->mlp_ratio, dt, c->eps};
       sm_swin_weights bw;
       std::memcpy(&bw, wp, sizeof(bw));
-      wp += 14;
+      wp += 15;
       const bool final_out = last_stage && k + 1 == st.depth && !c->has_head;
       void* out = final_out ? y : act[flip];
       if ((rc = sm_swin_block(&bc, &bw, cur, out, blk_ws, z.block, mode, stream))) return rc;

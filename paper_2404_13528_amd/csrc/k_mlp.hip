@@ -122,19 +122,30 @@ __device__ __forceinline__ void mlp_norm_x_tile(mlp_u32x4* x_l, float eps, const
 
 constexpr int MLP_RP = 36;       // floats per token row of a 32 x 32 partial tile in LDS (144 bytes: conflict-free 16-byte writes)
 
-template <int C>
+// PROJ: the Linear that precedes the MLP's residual stream is computed here as well (a transformer block's attention
+// output projection): x1 = A . Wp^T + bp + x0 for the tile's 32 tokens, x0 read (and Y written) through y_rows, then
+// Y = x1 + MLP(LayerNorm(x1)).  x1 never reaches memory: a normalised copy feeds the first product from LDS, a plain
+// copy in LDS is the final residual.  The projection's weight (packed like lin_pack_kernel's) streams through the
+// same registers as W1, three (C / 128) slices of 32 output features per wave, and the last slice's refill is
+// already the MLP's first W1 slice.
+template <int C, bool PROJ>
 __global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
   constexpr int KK = C / 16;            // 16-wide steps of the first product
   constexpr int T = C / 32;             // 32-row blocks of Y^T
   constexpr int BM = 32;
   constexpr int XS = C / 8;             // 16-byte slots per token row
   constexpr int XP = XS + 1;            // odd pitch: the fragment reads of 16 tokens hit 16 different bank groups
+  constexpr size_t TILE = (size_t)BM * XP * 16;
   static_assert(T % 4 == 0, "C must be a multiple of 128");
   const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                                  // [BM][XP]
-  float* red = (float*)(smem_raw + (size_t)BM * XP * 16);                 // [4 waves][4 blocks][32][MLP_RP]
-  mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + (size_t)BM * XP * 16 + (size_t)4 * 4 * 32 * MLP_RP * 4);   // [Hd / 8]
+  // PROJ: [A tile | x1 normalised | x1 plain | partial sums | b1 | bp]; else [X tile | partial sums | b1]
+  mlp_u32x4* a_l = (mlp_u32x4*)smem_raw;
+  mlp_u32x4* x_l = (mlp_u32x4*)(smem_raw + (PROJ ? TILE : 0));            // [BM][XP]
+  mlp_u32x4* r_l = (mlp_u32x4*)(smem_raw + 2 * TILE);                     // PROJ only
+  float* red = (float*)(smem_raw + (PROJ ? 3 : 1) * TILE);                // [4 waves][4 blocks][32][MLP_RP]
+  mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + (PROJ ? 3 : 1) * TILE + (size_t)4 * 4 * 32 * MLP_RP * 4);   // [Hd / 8]
+  mlp_u32x4* bp_l = b1_l + g.Hd / 8;                                      // PROJ only: [C / 8]
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index as a scalar: slice bases become scalar addresses
@@ -149,9 +160,10 @@ __global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
   mlp_u32x4 w1[KK], w2[T][2];
   const int sc0 = w < nsub ? w : 0;     // a wave without a slice (hidden < 128) computes nothing but loads in bounds
   {
-    const unsigned o1 = (unsigned)(sc0 * KK) * 1024u + lane * 16u;
+    const unsigned o1 = PROJ ? (unsigned)(w * KK) * 1024u + lane * 16u : (unsigned)(sc0 * KK) * 1024u + lane * 16u;
+    const char* first = PROJ ? (const char*)g.Wproj_p : W1p;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) w1[kk] = *(const mlp_u32x4*)(W1p + o1 + kk * 1024);
+    for (int kk = 0; kk < KK; ++kk) w1[kk] = *(const mlp_u32x4*)(first + o1 + kk * 1024);
     const unsigned o2 = (unsigned)(sc0 * T * 2) * 1024u + lane * 16u;
 #pragma unroll
     for (int t = 0; t < T; ++t)
@@ -159,11 +171,65 @@ __global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
       for (int s = 0; s < 2; ++s) w2[t][s] = *(const mlp_u32x4*)(W2p + o2 + (t * 2 + s) * 1024);
   }
 
-  mlp_load_x_tile<C>(x_l, X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  mlp_load_x_tile<C>(PROJ ? a_l : x_l, X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
   // the first bias as well: a global load inside the main loop would be waited for in issue order, behind the
   // whole weight prefetch
   for (int s = tid; s < Hd / 8; s += 256) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
+  if constexpr (PROJ) for (int s = tid; s < XS; s += 256) bp_l[s] = ((const mlp_u32x4*)g.bproj)[s];
   __syncthreads();
+
+  if constexpr (PROJ) {
+    const int64_t prow = row0 + l32 < g.M ? row0 + l32 : g.M - 1;        // lanes past M read the last row's residual
+    const int64_t ro0 = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
+    const bf16_t* R0 = (const bf16_t*)g.resid0;
+#pragma unroll
+    for (int j = 0; j < T / 4; ++j) {
+      const int sc = w + 4 * j;                                           // 32 output features of the projection
+      // loads the epilogue needs go out before the slice's weight refill (vector loads return in issue order)
+      const mlp_u32x4 res0 = *(const mlp_u32x4*)(R0 + ro0 + sc * 32 + hf * 8);
+      const mlp_u32x4 res1 = *(const mlp_u32x4*)(R0 + ro0 + sc * 32 + 16 + hf * 8);
+      const mlp_u32x4 bias_v = bp_l[sc * 4 + hf], bias_w = bp_l[sc * 4 + 2 + hf];
+      const char* nxt = j + 1 < T / 4 ? (const char*)g.Wproj_p + (size_t)((sc + 4) * KK) * 1024u : W1p + (size_t)(sc0 * KK) * 1024u;
+      int ao = l32 * XP + hf;                       // opaque per slice: the A fragments are re-read from LDS instead of
+      asm volatile("" : "+v"(ao));                  // being kept in (and spilled from) registers across the slices
+      mlp_f32x16 h;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) h[e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const mlp_u32x4 af = a_l[ao + 2 * kk];
+        h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, af), h, 0, 0, 0);
+        w1[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lane * 16u);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      // accumulator register 4b + i of lane (token, hf) is feature 8b + 4 hf + i of the slice: one v_permlane32_swap
+      // per value pair gives the lane eight consecutive features (run 2 gp + hf of the slice's four)
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) {
+        float v[8], bb[8], rr[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(h[8 * gp + q]), __float_as_uint(h[8 * gp + 4 + q]), false, false);
+          v[q] = __uint_as_float(sw[0]);
+          v[4 + q] = __uint_as_float(sw[1]);
+        }
+        mlp_unpack8(gp ? bias_w : bias_v, bb);
+        mlp_unpack8(gp ? res1 : res0, rr);
+        mlp_u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = mlp_pack2(v[2 * e] + bb[2 * e] + rr[2 * e], v[2 * e + 1] + bb[2 * e + 1] + rr[2 * e + 1]);
+        x_l[l32 * XP + sc * 4 + 2 * gp + hf] = o;        // x1 rounded to bf16, as the separate Linear stores it
+        r_l[l32 * XP + sc * 4 + 2 * gp + hf] = o;
+      }
+    }
+    __syncthreads();
+  }
   if (g.norm) {
     mlp_norm_x_tile<C>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
     __syncthreads();
@@ -251,7 +317,8 @@ __global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
     for (int q = 0; q < 2; ++q) {
       rb2[gi][q] = *(const mlp_u32x4*)((const bf16_t*)g.b2 + cb + 8 * q);
       rres[gi][q] = mlp_u32x4{0u, 0u, 0u, 0u};
-      if (R && row_ok) rres[gi][q] = *(const mlp_u32x4*)(R + ro + cb + 8 * q);
+      if constexpr (PROJ) rres[gi][q] = r_l[tk * XP + cb / 8 + q];
+      else if (R && row_ok) rres[gi][q] = *(const mlp_u32x4*)(R + ro + cb + 8 * q);
     }
   }
 #pragma unroll
@@ -297,21 +364,31 @@ __global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
   }
 }
 
-static size_t mlp_smem(int C, int Hd) { return (size_t)32 * (C / 8 + 1) * 16 + (size_t)4 * 4 * 32 * MLP_RP * 4 + (size_t)Hd * 2; }
+static size_t mlp_smem(int C, int Hd, bool proj) {
+  const size_t tile = (size_t)32 * (C / 8 + 1) * 16;
+  return (proj ? 3 : 1) * tile + (size_t)4 * 4 * 32 * MLP_RP * 4 + (size_t)Hd * 2 + (proj ? (size_t)C * 2 : 0);
+}
 
-template <int C>
-static int mlp_launch(const MlpArgs& g, void* stream) {
-  const size_t smem = mlp_smem(C, g.Hd);
+template <int C, bool PROJ>
+static int mlp_launch2(const MlpArgs& g, void* stream) {
+  const size_t smem = mlp_smem(C, g.Hd, PROJ);
   static size_t allowed = 0;          // raised on demand: the attribute is per kernel, the hidden size varies
   if (smem > allowed) {
-    const hipError_t e = hipFuncSetAttribute((const void*)mlp_fused_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    const hipError_t e = hipFuncSetAttribute((const void*)mlp_fused_kernel<C, PROJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return (int)e;
     allowed = smem;
   }
   const int64_t n_wg = (g.M + 31) / 32;
-  mlp_fused_kernel<C><<<dim3((unsigned)n_wg), dim3(256), smem, (hipStream_t)stream>>>(g);
+  mlp_fused_kernel<C, PROJ><<<dim3((unsigned)n_wg), dim3(256), smem, (hipStream_t)stream>>>(g);
   return (int)hipGetLastError();
 }
+template <int C>
+static int mlp_launch(const MlpArgs& g, void* stream) {
+  return g.Wproj_p ? mlp_launch2<C, true>(g, stream) : mlp_launch2<C, false>(g, stream);
+}
+
+// LDS capacity: the projection variant holds three token tiles
+bool mlp_proj_supported(int C, int Hd, int dtype) { return mlp_fused_supported(C, Hd, dtype) && mlp_smem(C, Hd, true) <= 160 * 1024; }
 
 bool mlp_fused_supported(int C, int Hd, int dtype) {
   return dtype == SM_BF16 && (C == 128 || C == 256 || C == 384) && Hd >= 32 && Hd % 32 == 0 && Hd <= 16384;

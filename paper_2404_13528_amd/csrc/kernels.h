@@ -60,9 +60,13 @@ struct MlpArgs {
   const void* X; const void* Wp; const void* b1; const void* b2; const void* residual; void* Y;
   int64_t M; int C, Hd;
   int norm; float norm_eps; const void* norm_gamma; const void* norm_beta;     // norm = 1: LayerNorm of X's rows first
+  // Wproj_p != null: X is the input of a projection, x1 = X . Wproj^T + bproj + resid0 (resid0 read through y_rows),
+  // and the MLP (with its norm and residual) works on x1; Wproj [C, C] packed by launch_lin_pack; `residual` unused
+  const void* Wproj_p; const void* bproj; const void* resid0;
   RowProg x_rows, y_rows;       // row r of X; row r of Y and of the residual
 };
 bool mlp_fused_supported(int C, int Hd, int dtype);
+bool mlp_proj_supported(int C, int Hd, int dtype);
 int launch_mlp_pack(const void* W1, const void* W2, int C, int Hd, void* packed, void* stream);
 int launch_mlp_fused(const MlpArgs& a, void* stream);
 

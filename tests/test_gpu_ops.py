@@ -426,3 +426,47 @@ def test_linear_with_packed_weight_row_maps_and_refusals():
     assert not sm.linear_pack_supported(128, 128, torch.float32)
     with pytest.raises(sm.SmError):
         sm.linear(dev(A, dtype), Wp, dev(b, dtype), act="swiglu", packed=True)
+
+
+@pytest.mark.parametrize("M,C,Hd", [(70, 128, 96), (200, 256, 1024), (6272, 384, 1536)])
+def test_mlp_fused_with_projection(M, C, Hd):
+    # x1 = A . Wp^T + bp + x0, y = x1 + MLP(LayerNorm(x1)) in one kernel; x0 read and y written through a row map
+    dtype = torch.bfloat16
+    A = draw((M, C), 110, dtype, 1.0)
+    Wp, bp = draw((C, C), 111, dtype, C ** -0.5), draw((C,), 112, dtype, 0.5)
+    x0 = draw((M, C), 113, dtype, 1.0)
+    W1, b1 = draw((Hd, C), 114, dtype, C ** -0.5), draw((Hd,), 115, dtype, 0.5)
+    W2, b2 = draw((C, Hd), 116, dtype, Hd ** -0.5), draw((C,), 117, dtype, 0.5)
+    g, be = draw((C,), 118, dtype, 0.2, 1.0), draw((C,), 119, dtype, 0.2)
+    x1 = O.linear(to_np(A), to_np(Wp), to_np(bp)) + to_np(x0)
+    hid = O.gelu(O.linear(O.layer_norm(x1, to_np(g), to_np(be)), to_np(W1), to_np(b1)))
+    want = x1 + O.linear(hid, to_np(W2), to_np(b2))
+    assert sm.lib().sm_mlp_proj_supported(C, Hd, sm.SM_BF16)
+    got = sm.mlp_fused(dev(A, dtype), sm.mlp_pack(dev(W1, dtype), dev(W2, dtype)), dev(b1, dtype), dev(b2, dtype),
+                       norm=(dev(g, dtype), dev(be, dtype), 1e-5),
+                       proj=(sm.linear_pack(dev(Wp, dtype)), dev(bp, dtype), dev(x0, dtype)))
+    assert_close(got, want, dtype, "projection + fused MLP", float(np.abs(want).max()) + 1.0)
+
+
+def test_mlp_fused_with_projection_scattered_rows():
+    # the window-reverse store (with roll) as the row map of the residual read and of the output
+    dtype = torch.bfloat16
+    C, Hd, M = 128, 256, 4 * 49
+    A = draw((M, C), 120, dtype)
+    Wp, bp = draw((C, C), 121, dtype, C ** -0.5), draw((C,), 122, dtype, 0.3)
+    x0 = draw((M, C), 123, dtype)
+    W1, b1 = draw((Hd, C), 124, dtype, C ** -0.5), draw((Hd,), 125, dtype, 0.3)
+    W2, b2 = draw((C, Hd), 126, dtype, Hd ** -0.5), draw((C,), 127, dtype, 0.3)
+    g, be = draw((C,), 128, dtype, 0.2, 1.0), draw((C,), 129, dtype, 0.2)
+    rev = V.window_reverse_chain(1, 14, 14, C, 7, 3)
+    # row r of the window-major result lands where the reverse chain puts it: as a gather, natural = reverse(window-major)
+    x1_win = O.linear(to_np(A), to_np(Wp), to_np(bp))
+    x1 = V.apply_chain(x1_win.reshape(4, 49, C), rev).reshape(M, C) + to_np(x0)
+    hid = O.gelu(O.linear(O.layer_norm(x1, to_np(g), to_np(be)), to_np(W1), to_np(b1)))
+    want = x1 + O.linear(hid, to_np(W2), to_np(b2))
+    part = V.window_partition_chain(1, 14, 14, C, 7, 3)      # offset in the natural tensor of window-major row r
+    ym = sm.Map.create((1, 14, 14, C), part)
+    got = sm.mlp_fused(dev(A, dtype), sm.mlp_pack(dev(W1, dtype), dev(W2, dtype)), dev(b1, dtype), dev(b2, dtype),
+                       norm=(dev(g, dtype), dev(be, dtype), 1e-5),
+                       proj=(sm.linear_pack(dev(Wp, dtype)), dev(bp, dtype), dev(x0, dtype)), y_map=ym)
+    assert_close(got, want, dtype, "projection + fused MLP through the window-reverse store", float(np.abs(want).max()) + 1.0)

@@ -14,11 +14,12 @@ pytestmark = pytest.mark.gpu
 MODES = [sm.SM_ELIDED, sm.SM_EXPLICIT]
 
 
-def n_compute(C, mlp=4, fused=False):
+def n_compute(C, mlp=4, fused=False, mode=None):
     """Compute kernels of a block: seven, minus a LayerNorm for each Linear narrow enough (N <= 512) to take it folded;
-    with the fused MLP kernel LayerNorm-2, FC1 and FC2 are one."""
+    with the fused MLP kernel LayerNorm-2, FC1 and FC2 are one ("mlp"), and in elided mode the output projection
+    joins them (True)."""
     if fused:
-        return 5 - (3 * C <= 512)
+        return 5 - (3 * C <= 512) - (fused is True and mode == sm.SM_ELIDED)
     return 7 - (3 * C <= 512) - (mlp * C <= 512)
 
 
@@ -65,16 +66,16 @@ def test_wrong_shift_or_bias_is_detected_by_the_tolerance():
 
 
 @pytest.mark.parametrize("mode", MODES)
-@pytest.mark.parametrize("fuse_mlp", [True, False])
+@pytest.mark.parametrize("fuse_mlp", [True, "mlp", False])
 def test_config2_block_bf16_full_size(mode, fuse_mlp):
     got, want, x, counts = run_block(32, 14, 14, 384, 12, 7, 3, torch.bfloat16, mode, fuse_mlp=fuse_mlp)
     assert rel_l2(got, want) <= 2e-2
     assert rel_l2(got - x, want - x) <= 3e-2
-    assert counts == (n_compute(384, fused=fuse_mlp), 0 if mode == sm.SM_ELIDED else 6)
+    assert counts == (n_compute(384, fused=fuse_mlp, mode=mode), 0 if mode == sm.SM_ELIDED else 6)
 
 
 @pytest.mark.parametrize("mode", MODES)
-@pytest.mark.parametrize("fuse_mlp", [True, False])
+@pytest.mark.parametrize("fuse_mlp", [True, "mlp", False])
 @pytest.mark.parametrize("C,h", [(128, 4), (256, 8)])
 def test_small_block_stress_weights_fused_mlp_shapes(C, h, fuse_mlp, mode):
     # widths the fused MLP kernel covers, with and without it; a token count (2 * 14 * 21 = 588) that ends inside
@@ -82,7 +83,7 @@ def test_small_block_stress_weights_fused_mlp_shapes(C, h, fuse_mlp, mode):
     got, want, x, counts = run_block(2, 14, 21, C, h, 7, 3, torch.bfloat16, mode, seed=6, std=0.1, fuse_mlp=fuse_mlp)
     assert rel_l2(got, want) <= 2e-2
     assert rel_l2(got - x, want - x) <= 3e-2
-    assert counts == (n_compute(C, fused=fuse_mlp), 0 if mode == sm.SM_ELIDED else 6)
+    assert counts == (n_compute(C, fused=fuse_mlp, mode=mode), 0 if mode == sm.SM_ELIDED else 6)
 
 
 def test_errors_before_launch():
