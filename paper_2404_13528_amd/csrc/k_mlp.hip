@@ -48,7 +48,7 @@ __device__ __forceinline__ int mlp_rho(int r) { return 16 * (r >> 4) + 8 * ((r >
 
 // one thread per 16-byte chunk of the packed buffer: [W1 fragments | W2 fragments]
 __global__ void mlp_pack_kernel(const bf16_t* W1, const bf16_t* W2, mlp_u32x4* packed, int C, int Hd) {
-  const int KK = C / 16, T = C / 32;
+  const int KK = C / 16, nsub = Hd / 32;
   const int64_t n1 = (int64_t)Hd * C / 8;
   const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (o >= 2 * n1) return;
@@ -58,22 +58,22 @@ __global__ void mlp_pack_kernel(const bf16_t* W1, const bf16_t* W2, mlp_u32x4* p
   const bf16_t* src;
   if (o < n1) {
     const int sc = (int)(frag / KK), kk = (int)(frag - (int64_t)sc * KK);
-    src = W1 + (int64_t)(32 * sc + mlp_rho(l32)) * C + 16 * kk + 8 * hf;
+    src = W1 + (int64_t)(32 * sc + l32) * C + 16 * kk + 8 * hf;
   } else {
     const int s = (int)(frag & 1);
     const int64_t ft = frag >> 1;
-    const int sc = (int)(ft / T), t = (int)(ft - (int64_t)sc * T);
+    const int t = (int)(ft / nsub), sc = (int)(ft - (int64_t)t * nsub);
     src = W2 + (int64_t)(32 * t + l32) * Hd + 32 * sc + 16 * s + 8 * hf;
   }
   packed[o] = *(const mlp_u32x4*)src;
 }
 
 // X tile of 32 token rows -> LDS, rows at an odd pitch of 16-byte slots (rows past M as zeros); 256 threads
-template <int C>
+template <int C, int NTHR = 256>
 __device__ __forceinline__ void mlp_load_x_tile(mlp_u32x4* x_l, const bf16_t* X, int64_t row0, int64_t M, int ident, int64_t ld,
                                                 const SM_KARG RowProg* rows) {
   constexpr int XS = C / 8, XP = XS + 1;
-  for (int s = threadIdx.x; s < 32 * XS; s += 256) {
+  for (int s = threadIdx.x; s < 32 * XS; s += NTHR) {
     const int r = s / XS, c = s - r * XS;
     const int64_t row = row0 + r;
     mlp_u32x4 v = {0u, 0u, 0u, 0u};
@@ -87,6 +87,7 @@ __device__ __forceinline__ void mlp_load_x_tile(mlp_u32x4* x_l, const bf16_t* X,
 template <int C>
 __device__ __forceinline__ void mlp_norm_x_tile(mlp_u32x4* x_l, float eps, const mlp_u32x4* gam, const mlp_u32x4* bet) {
   constexpr int XS = C / 8, XP = XS + 1;
+  if (threadIdx.x >= 256) return;               // 256 threads do it (eight per token); no barrier inside
   const int r = threadIdx.x >> 3, p = threadIdx.x & 7;
   mlp_u32x4* xr = x_l + r * XP;
   float sum = 0.f;
@@ -120,253 +121,212 @@ __device__ __forceinline__ void mlp_norm_x_tile(mlp_u32x4* x_l, float eps, const
   }
 }
 
-constexpr int MLP_RP = 36;       // floats per token row of a 32 x 32 partial tile in LDS (144 bytes: conflict-free 16-byte writes)
+// bias, optional GELU, optional residual of one 32 x 32 accumulator: register 4b + i of lane (token, hf) is row
+// 8b + 4 hf + i of the block; one v_permlane32_swap per value pair gives the lane eight consecutive rows (run
+// 2 gp + hf of the block's four), packed to bf16 in outv[gp]
+__device__ __forceinline__ void mlp_finish(const mlp_f32x16& h, const mlp_u32x4& bias_v, const mlp_u32x4& bias_w, const mlp_u32x4* res,
+                                           bool gelu_on, mlp_u32x4* outv) {
+#pragma unroll
+  for (int gp = 0; gp < 2; ++gp) {
+    float v[8], bb[8], rr[8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(h[8 * gp + q]), __float_as_uint(h[8 * gp + 4 + q]), false, false);
+      v[q] = __uint_as_float(sw[0]);
+      v[4 + q] = __uint_as_float(sw[1]);
+    }
+    mlp_unpack8(gp ? bias_w : bias_v, bb);
+    mlp_unpack8(res[gp], rr);
+    mlp_u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float a = v[2 * e] + bb[2 * e], b = v[2 * e + 1] + bb[2 * e + 1];
+      const float ga = gelu_poly(a), gb = gelu_poly(b);
+      a = gelu_on ? ga : a;
+      b = gelu_on ? gb : b;
+      o[e] = mlp_pack2(a + rr[2 * e], b + rr[2 * e + 1]);
+    }
+    outv[gp] = o;
+  }
+}
 
 // PROJ: the Linear that precedes the MLP's residual stream is computed here as well (a transformer block's attention
 // output projection): x1 = A . Wp^T + bp + x0 for the tile's 32 tokens, x0 read (and Y written) through y_rows, then
 // Y = x1 + MLP(LayerNorm(x1)).  x1 never reaches memory: a normalised copy feeds the first product from LDS, a plain
-// copy in LDS is the final residual.  The projection's weight (packed like lin_pack_kernel's) streams through the
-// same registers as W1, three (C / 128) slices of 32 output features per wave, and the last slice's refill is
-// already the MLP's first W1 slice.
+// copy in LDS is the final residual.
 template <int C, bool PROJ>
-__global__ __launch_bounds__(256, 1) void mlp_fused_kernel(MlpArgs g) {
+__global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) {
   constexpr int KK = C / 16;            // 16-wide steps of the first product
-  constexpr int T = C / 32;             // 32-row blocks of Y^T
-  constexpr int BM = 32;
+  constexpr int KH = KK / 2;            // W1 fragments in flight per wave (half a slice)
+  constexpr int T = C / 32;             // 32-row blocks of Y^T = waves of the workgroup
+  constexpr int NTHR = 64 * T;
   constexpr int XS = C / 8;             // 16-byte slots per token row
   constexpr int XP = XS + 1;            // odd pitch: the fragment reads of 16 tokens hit 16 different bank groups
-  constexpr size_t TILE = (size_t)BM * XP * 16;
-  static_assert(T % 4 == 0, "C must be a multiple of 128");
+  constexpr int HP = 4 * T + 1;         // the same for a round's hidden tile (T slices of 32 = 4 slots each)
+  constexpr size_t TILE = (size_t)32 * XP * 16, HTILE = (size_t)32 * HP * 16;
   const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  // PROJ: [A tile | x1 normalised | x1 plain | partial sums | b1 | bp]; else [X tile | partial sums | b1]
+  // PROJ: [A tile | x1 normalised | x1 plain | H x 2 | b1 | bp]; else [X tile | H x 2 | b1]
   mlp_u32x4* a_l = (mlp_u32x4*)smem_raw;
-  mlp_u32x4* x_l = (mlp_u32x4*)(smem_raw + (PROJ ? TILE : 0));            // [BM][XP]
+  mlp_u32x4* x_l = (mlp_u32x4*)(smem_raw + (PROJ ? TILE : 0));            // [32][XP]
   mlp_u32x4* r_l = (mlp_u32x4*)(smem_raw + 2 * TILE);                     // PROJ only
-  float* red = (float*)(smem_raw + (PROJ ? 3 : 1) * TILE);                // [4 waves][4 blocks][32][MLP_RP]
-  mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + (PROJ ? 3 : 1) * TILE + (size_t)4 * 4 * 32 * MLP_RP * 4);   // [Hd / 8]
+  mlp_u32x4* h_l = (mlp_u32x4*)(smem_raw + (PROJ ? 3 : 1) * TILE);        // [2][32][HP]
+  mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + (PROJ ? 3 : 1) * TILE + 2 * HTILE);   // [Hd / 8]
   mlp_u32x4* bp_l = b1_l + g.Hd / 8;                                      // PROJ only: [C / 8]
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index as a scalar: slice bases become scalar addresses
-  const int64_t row0 = (int64_t)blockIdx.x * BM;
-  const bf16_t* X = (const bf16_t*)g.X;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index as a scalar: fragment bases become scalar addresses
+  const int64_t row0 = (int64_t)blockIdx.x * 32;
   const int Hd = g.Hd;
   const int nsub = Hd >> 5;
+  const int rounds = (nsub + T - 1) / T;
   const char* W1p = (const char*)g.Wp;                                    // fragments of 1 KiB, see the file header
-  const char* W2p = W1p + (size_t)Hd * C * 2;
+  const char* W2p = W1p + (size_t)Hd * C * 2 + (size_t)w * nsub * 2048;   // this wave's row block: (slice, step) in order
+  const unsigned lo = lane * 16u;
 
-  // the wave's first slice of weights is requested before anything else
-  mlp_u32x4 w1[KK], w2[T][2];
-  const int sc0 = w < nsub ? w : 0;     // a wave without a slice (hidden < 128) computes nothing but loads in bounds
+  // the wave's first fragments are requested before anything else
+  mlp_u32x4 w1[KH], w2[T];
+  const int sc0 = w < nsub ? w : nsub - 1;      // (a wave past the last slice works on a copy of it and contributes zeros)
   {
-    const unsigned o1 = PROJ ? (unsigned)(w * KK) * 1024u + lane * 16u : (unsigned)(sc0 * KK) * 1024u + lane * 16u;
-    const char* first = PROJ ? (const char*)g.Wproj_p : W1p;
+    const char* first = PROJ ? (const char*)g.Wproj_p + (size_t)(w * KK) * 1024u : W1p + (size_t)(sc0 * KK) * 1024u;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) w1[kk] = *(const mlp_u32x4*)(first + o1 + kk * 1024);
-    const unsigned o2 = (unsigned)(sc0 * T * 2) * 1024u + lane * 16u;
+    for (int kk = 0; kk < KH; ++kk) w1[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
 #pragma unroll
-    for (int t = 0; t < T; ++t)
-#pragma unroll
-      for (int s = 0; s < 2; ++s) w2[t][s] = *(const mlp_u32x4*)(W2p + o2 + (t * 2 + s) * 1024);
+    for (int i = 0; i < T; ++i) w2[i] = *(const mlp_u32x4*)(W2p + (size_t)(i < 2 * nsub ? i : (i & 1) + 2 * (nsub - 1)) * 1024u + lo);
   }
 
-  mlp_load_x_tile<C>(PROJ ? a_l : x_l, X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
-  // the first bias as well: a global load inside the main loop would be waited for in issue order, behind the
-  // whole weight prefetch
-  for (int s = tid; s < Hd / 8; s += 256) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
-  if constexpr (PROJ) for (int s = tid; s < XS; s += 256) bp_l[s] = ((const mlp_u32x4*)g.bproj)[s];
+  mlp_load_x_tile<C, NTHR>(PROJ ? a_l : x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  for (int s = tid; s < Hd / 8; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
+  if constexpr (PROJ) for (int s = tid; s < XS; s += NTHR) bp_l[s] = ((const mlp_u32x4*)g.bproj)[s];
   __syncthreads();
 
+  const int64_t prow = row0 + l32 < g.M ? row0 + l32 : g.M - 1;          // lanes past M read the last row and store nothing
+  const bool row_ok = row0 + l32 < g.M;
+  const int64_t ro = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
+  const int fo = w * 32 + hf * 8;                                         // first of the lane's features in the wave's block
+
+  mlp_u32x4 resid[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};              // residual of the final sum (lane's two runs of eight)
   if constexpr (PROJ) {
-    const int64_t prow = row0 + l32 < g.M ? row0 + l32 : g.M - 1;        // lanes past M read the last row's residual
-    const int64_t ro0 = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
+    // wave w forms features 32 w ..+31 of x1
     const bf16_t* R0 = (const bf16_t*)g.resid0;
-#pragma unroll
-    for (int j = 0; j < T / 4; ++j) {
-      const int sc = w + 4 * j;                                           // 32 output features of the projection
-      // loads the epilogue needs go out before the slice's weight refill (vector loads return in issue order)
-      const mlp_u32x4 res0 = *(const mlp_u32x4*)(R0 + ro0 + sc * 32 + hf * 8);
-      const mlp_u32x4 res1 = *(const mlp_u32x4*)(R0 + ro0 + sc * 32 + 16 + hf * 8);
-      const mlp_u32x4 bias_v = bp_l[sc * 4 + hf], bias_w = bp_l[sc * 4 + 2 + hf];
-      const char* nxt = j + 1 < T / 4 ? (const char*)g.Wproj_p + (size_t)((sc + 4) * KK) * 1024u : W1p + (size_t)(sc0 * KK) * 1024u;
-      int ao = l32 * XP + hf;                       // opaque per slice: the A fragments are re-read from LDS instead of
-      asm volatile("" : "+v"(ao));                  // being kept in (and spilled from) registers across the slices
-      mlp_f32x16 h;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) h[e] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const mlp_u32x4 af = a_l[ao + 2 * kk];
-        h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, af), h, 0, 0, 0);
-        w1[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lane * 16u);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      // accumulator register 4b + i of lane (token, hf) is feature 8b + 4 hf + i of the slice: one v_permlane32_swap
-      // per value pair gives the lane eight consecutive features (run 2 gp + hf of the slice's four)
-#pragma unroll
-      for (int gp = 0; gp < 2; ++gp) {
-        float v[8], bb[8], rr[8];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(h[8 * gp + q]), __float_as_uint(h[8 * gp + 4 + q]), false, false);
-          v[q] = __uint_as_float(sw[0]);
-          v[4 + q] = __uint_as_float(sw[1]);
-        }
-        mlp_unpack8(gp ? bias_w : bias_v, bb);
-        mlp_unpack8(gp ? res1 : res0, rr);
-        mlp_u32x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = mlp_pack2(v[2 * e] + bb[2 * e] + rr[2 * e], v[2 * e + 1] + bb[2 * e + 1] + rr[2 * e + 1]);
-        x_l[l32 * XP + sc * 4 + 2 * gp + hf] = o;        // x1 rounded to bf16, as the separate Linear stores it
-        r_l[l32 * XP + sc * 4 + 2 * gp + hf] = o;
-      }
-    }
-    __syncthreads();
-  }
-  if (g.norm) {
-    mlp_norm_x_tile<C>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
-    __syncthreads();
-  }
-
-  mlp_f32x16 out[T];
-#pragma unroll
-  for (int t = 0; t < T; ++t)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) out[t][e] = 0.f;
-
-  for (int sc = w; sc < nsub; sc += 4) {
-    const int nx = sc + 4 < nsub ? sc + 4 : sc;          // the last slice reloads itself: no branch around the prefetch
-    int xo = l32 * XP + hf;                              // opaque per slice: the X fragments are re-read from LDS every
-    asm volatile("" : "+v"(xo));                         // time instead of being hoisted into (and spilled from) registers
-    const mlp_u32x4 bias_v = b1_l[sc * 4 + hf];
-    const mlp_u32x4 bias_w = b1_l[sc * 4 + 2 + hf];
+    const mlp_u32x4 res[2] = {*(const mlp_u32x4*)(R0 + ro + fo), *(const mlp_u32x4*)(R0 + ro + fo + 16)};
+    const mlp_u32x4 bias_v = bp_l[w * 4 + hf], bias_w = bp_l[w * 4 + 2 + hf];
+    const char* cur = (const char*)g.Wproj_p + (size_t)(w * KK) * 1024u;
+    const char* nxt = W1p + (size_t)(sc0 * KK) * 1024u;
+    int ao = l32 * XP + hf;
+    asm volatile("" : "+v"(ao));
     mlp_f32x16 h;
 #pragma unroll
     for (int e = 0; e < 16; ++e) h[e] = 0.f;
-    {
-      const unsigned o1 = (unsigned)(nx * KK) * 1024u + lane * 16u;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const mlp_u32x4 xf = x_l[xo + 2 * kk];
-        h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, xf), h, 0, 0, 0);
-        w1[kk] = *(const mlp_u32x4*)(W1p + o1 + kk * 1024);
-      }
+    for (int kk = 0; kk < KK; ++kk) {
+      const mlp_u32x4 af = a_l[ao + 2 * kk];
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk % KH]), __builtin_bit_cast(mlp_bf16x8, af), h, 0, 0, 0);
+      w1[kk % KH] = kk < KH ? *(const mlp_u32x4*)(cur + (kk + KH) * 1024 + lo) : *(const mlp_u32x4*)(nxt + (kk - KH) * 1024 + lo);
     }
-    // bias + GELU, rounded to bf16 as a stored hidden activation would be; step s of the second product takes
-    // accumulator blocks 2s and 2s + 1 = hidden units 16s + 8 hf + 0..7 of the slice
-    float bf_[16];
-    mlp_unpack8(bias_v, bf_);
-    mlp_unpack8(bias_w, bf_ + 8);
-    mlp_u32x4 hfr[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float a = gelu_poly(h[8 * s + 2 * e] + bf_[8 * s + 2 * e]);
-        const float b = gelu_poly(h[8 * s + 2 * e + 1] + bf_[8 * s + 2 * e + 1]);
-        hfr[s][e] = mlp_pack2(a, b);
-      }
-    {
-      const unsigned o2 = (unsigned)(nx * T * 2) * 1024u + lane * 16u;
-#pragma unroll
-      for (int t = 0; t < T; ++t)
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          out[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w2[t][s]), __builtin_bit_cast(mlp_bf16x8, hfr[s]), out[t], 0, 0, 0);
-          w2[t][s] = *(const mlp_u32x4*)(W2p + o2 + (t * 2 + s) * 1024);
-        }
-    }
-    // issue order of the slice: every MFMA is followed by the load that refills its weight register (left alone, the
-    // scheduler gathers all loads at the end of the slice, where their latency is exposed at the top of the next)
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);        // LDS fragment reads run three steps ahead of their MFMA
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
+    mlp_finish(h, bias_v, bias_w, res, false, resid);          // x1 rounded to bf16, as the separate Linear stores it
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp) {
+      x_l[l32 * XP + w * 4 + 2 * gp + hf] = resid[gp];
+      r_l[l32 * XP + w * 4 + 2 * gp + hf] = resid[gp];
+    }
+    __syncthreads();
+  } else if (g.residual) {
+    const bf16_t* R = (const bf16_t*)g.residual;
+    resid[0] = *(const mlp_u32x4*)(R + ro + fo);
+    resid[1] = *(const mlp_u32x4*)(R + ro + fo + 16);
+  }
+  if (g.norm) {
+    mlp_norm_x_tile<C>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
+    __syncthreads();
+  }
+
+  mlp_f32x16 out;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) out[e] = 0.f;
+  const mlp_u32x4 zero4[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+
+  for (int r = 0; r < rounds; ++r) {
+    // ---- first product: this wave's slice of the round -> H (bias, GELU, bf16) into LDS
+    const int sc = r * T + w;
+    const bool sc_ok = sc < nsub;
+    const int scc = sc_ok ? sc : nsub - 1;
+    const int nsc = sc + T < nsub ? sc + T : scc;
+    int xo = l32 * XP + hf;                              // opaque per round: the X fragments are re-read from LDS instead
+    asm volatile("" : "+v"(xo));                         // of being hoisted into (and spilled from) registers
+    const mlp_u32x4 bias_v = b1_l[scc * 4 + hf], bias_w = b1_l[scc * 4 + 2 + hf];
+    const char* cur = W1p + (size_t)(scc * KK) * 1024u;  // scalar
+    const char* nxt = W1p + (size_t)(nsc * KK) * 1024u;
+    mlp_f32x16 h;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) h[e] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const mlp_u32x4 xf = x_l[xo + 2 * kk];
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk % KH]), __builtin_bit_cast(mlp_bf16x8, xf), h, 0, 0, 0);
+      w1[kk % KH] = kk < KH ? *(const mlp_u32x4*)(cur + (kk + KH) * 1024 + lo) : *(const mlp_u32x4*)(nxt + (kk - KH) * 1024 + lo);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);        // LDS fragment reads run three steps ahead of their MFMA
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    mlp_u32x4 hv[2];
+    mlp_finish(h, bias_v, bias_w, zero4, true, hv);
+    mlp_u32x4* hb = h_l + (r & 1) * (32 * HP);
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp) hb[l32 * HP + w * 4 + 2 * gp + hf] = sc_ok ? hv[gp] : zero4[0];     // past the last slice: zeros
+    __syncthreads();
+    // ---- second product: this wave's 32 output features over the round's T slices.  One barrier per round: the
+    // other H buffer is written next, and nobody writes this one again before the barrier after that
+    const int s0 = r * T;                                                   // first slice of the round
+    const int rem = nsub - s0;                                              // slices of W2 from this round's first to the end (>= 1)
+    int ho = l32 * HP + hf;
+    asm volatile("" : "+v"(ho));
+    const char* cur2 = W2p + (size_t)s0 * 2048u;
+#pragma unroll
+    for (int i = 0; i < 2 * T; ++i) {                                       // i = 2 * (slice of the round) + step
+      const mlp_u32x4 hfg = hb[ho + 2 * i];
+      out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w2[i % T]), __builtin_bit_cast(mlp_bf16x8, hfg), out, 0, 0, 0);
+      // refill: second half of this round's fragments, then the first half of the next round's; past the end of
+      // W2 the last valid fragment pair is read again (its H is zero)
+      const int fi = i + T;                                                 // fragment index relative to this round's first
+      const int fc = fi < 2 * rem ? fi : (fi & 1) + 2 * (rem - 1);
+      w2[i % T] = *(const mlp_u32x4*)(cur2 + (size_t)fc * 1024u + lo);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
 #pragma unroll
     for (int i = 0; i < 2 * T; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
   }
 
-  // The four partial Y^T are added through LDS, four row blocks at a time: every wave writes its four blocks as
-  // [token][feature] fp32 tiles, then wave w owns block 4 gi + w: sums the partials in wave order, adds bias and
-  // residual and stores 16 consecutive features per lane.  Bias and residual are requested before the first
-  // exchange so that their latency is not paid once per round.
-  const bf16_t* R = (const bf16_t*)g.residual;
-  bf16_t* Y = (bf16_t*)g.Y;
-  const int tk = lane >> 1, hh = lane & 1;
-  const int64_t row = row0 + tk;
-  const bool row_ok = row < g.M;
-  const int64_t ro = row_ok ? (g.y_rows.identity ? row * g.y_rows.ld : eval_rows_k(&gk->y_rows, row)) : 0;
-  mlp_u32x4 rres[T / 4][2], rb2[T / 4][2];
-#pragma unroll
-  for (int gi = 0; gi < T / 4; ++gi) {
-    const int cb = (4 * gi + w) * 32 + 16 * hh;          // first of this lane's 16 features
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      rb2[gi][q] = *(const mlp_u32x4*)((const bf16_t*)g.b2 + cb + 8 * q);
-      rres[gi][q] = mlp_u32x4{0u, 0u, 0u, 0u};
-      if constexpr (PROJ) rres[gi][q] = r_l[tk * XP + cb / 8 + q];
-      else if (R && row_ok) rres[gi][q] = *(const mlp_u32x4*)(R + ro + cb + 8 * q);
-    }
-  }
-#pragma unroll
-  for (int gi = 0; gi < T / 4; ++gi) {
-    if (gi) __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float* tile = red + (size_t)((w * 4 + j) * 32) * MLP_RP;
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const mlp_f32x4 v = {out[4 * gi + j][4 * b], out[4 * gi + j][4 * b + 1], out[4 * gi + j][4 * b + 2], out[4 * gi + j][4 * b + 3]};
-        *(mlp_f32x4*)(tile + l32 * MLP_RP + 8 * b + 4 * hf) = v;
-      }
-    }
-    __syncthreads();
-    float acc[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < 4; ++ww) {
-      const float* tile = red + (size_t)((ww * 4 + w) * 32) * MLP_RP + tk * MLP_RP + 16 * hh;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const mlp_f32x4 v = *(const mlp_f32x4*)(tile + 4 * q);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[4 * q + e] += v[e];
-      }
-    }
-    if (row_ok) {
-      const int cb = (4 * gi + w) * 32 + 16 * hh;
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        float bb[8], rr[8];
-        mlp_unpack8(rb2[gi][q], bb);
-        mlp_unpack8(rres[gi][q], rr);
-        mlp_u32x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)      // product + bias + residual in fp32, rounded to bf16 once, as the Linear's epilogue does
-          o[e] = mlp_pack2(acc[8 * q + 2 * e] + bb[2 * e] + rr[2 * e], acc[8 * q + 2 * e + 1] + bb[2 * e + 1] + rr[2 * e + 1]);
-        *(mlp_u32x4*)(Y + ro + cb + 8 * q) = o;
-      }
-    }
+  // every wave holds its 32 features of Y^T complete: bias, residual, two 16-byte stores per lane
+  if constexpr (PROJ) { resid[0] = r_l[l32 * XP + w * 4 + hf]; resid[1] = r_l[l32 * XP + w * 4 + 2 + hf]; }
+  const mlp_u32x4 b2v = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo), b2w = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo + 16);
+  mlp_u32x4 yv[2];
+  mlp_finish(out, b2v, b2w, resid, false, yv);
+  if (row_ok) {
+    bf16_t* Y = (bf16_t*)g.Y;
+    *(mlp_u32x4*)(Y + ro + fo) = yv[0];
+    *(mlp_u32x4*)(Y + ro + fo + 16) = yv[1];
   }
 }
 
 static size_t mlp_smem(int C, int Hd, bool proj) {
-  const size_t tile = (size_t)32 * (C / 8 + 1) * 16;
-  return (proj ? 3 : 1) * tile + (size_t)4 * 4 * 32 * MLP_RP * 4 + (size_t)Hd * 2 + (proj ? (size_t)C * 2 : 0);
+  const size_t tile = (size_t)32 * (C / 8 + 1) * 16, htile = (size_t)32 * (C / 8 + 1) * 16;
+  return (proj ? 3 : 1) * tile + 2 * htile + (size_t)Hd * 2 + (proj ? (size_t)C * 2 : 0);
 }
 
 template <int C, bool PROJ>
@@ -379,7 +339,7 @@ static int mlp_launch2(const MlpArgs& g, void* stream) {
     allowed = smem;
   }
   const int64_t n_wg = (g.M + 31) / 32;
-  mlp_fused_kernel<C, PROJ><<<dim3((unsigned)n_wg), dim3(256), smem, (hipStream_t)stream>>>(g);
+  mlp_fused_kernel<C, PROJ><<<dim3((unsigned)n_wg), dim3(64 * (C / 32)), smem, (hipStream_t)stream>>>(g);
   return (int)hipGetLastError();
 }
 template <int C>
