@@ -3,8 +3,8 @@
 Workload (benchmark configs[1]): Swin stage-3 chain, bf16, B=32, 14x14
 tokens, C=384, 12 heads, window 7, 6 blocks alternating shift 0/3, MLP ratio 4;
 seeded synthetic inputs resident in HBM before the timed region.  One step =
-one pass of the whole chain (30 kernels in elided mode: per block LayerNorm, QKV, window attention,
-proj + residual, fused LayerNorm + MLP + residual) over one batch.
+one pass of the whole chain (24 kernels in elided mode: per block LayerNorm, QKV, window attention, and one
+kernel for proj + residual + LayerNorm + MLP + residual; the explicit chain runs 30 + 30 copies) over one batch.
 
 Prints ONE JSON line: whole-job throughput (images/s) of the elided chain, the
 explicit-transpose baseline chain timed the same way, per-kernel durations
@@ -28,21 +28,25 @@ PEAK_BF16 = 2.5e15         # FLOP/s dense bf16 MFMA, MI355X published
 # copy-kernel calibration described in the design doc); filled from profiles/, None = not measured.
 MEASURED_TRAFFIC = {
     # profiles/swin_stage3_chain_b32_hbm_counters.md: (FETCH_SIZE KiB x 2.000 + WRITE_SIZE KiB x 1.000) x 1024
-    "ln+mlp_bf16[6272,1536,384]": int((11703.5 * 2.0 + 4704.0) * 1024),
-    "gemm_bf16[6272,1152,384]": int((6443.5 * 2.0 + 14119.7) * 1024),
-    "gemm_bf16[6272,384,384]+res+scatter": int((4969.6 * 2.0 + 4704.0) * 1024),
+    "proj+ln+mlp_bf16[6272,1536,384]": int((15196.3 * 2.0 + 4704.0) * 1024),
+    "ln+mlp_bf16[6272,1536,384]": int((11668.2 * 2.0 + 4704.0) * 1024),
+    "gemm_bf16[6272,1152,384]": int((6443.5 * 2.0 + 14113.0) * 1024),
+    "gemm_bf16[6272,384,384]+res": int((3787.0 * 2.0 + 4704.0) * 1024),
     "attention_window_bf16[128,12,49,49,32]": int((7137.5 * 2.0 + 4704.0) * 1024),
-    "layernorm_bf16[6272,384]+scatter": int((2449.6 * 2.0 + 4704.0) * 1024),
+    "layernorm_bf16[6272,384]+scatter": int((2449.5 * 2.0 + 4704.0) * 1024),
+    "layernorm_bf16[6272,384]": int((2449.5 * 2.0 + 4704.0) * 1024),
 }
 
 
 def kernel_model(label, e=2):
     """Algorithmic bytes and flops of one launch, from the kernel label (tensor reads + writes at
     kernel-per-op granularity with fused epilogues; weights and bias included)."""
-    m = re.match(r"(ln\+)?mlp_\w+\[(\d+),(\d+),(\d+)\]", label)
-    if m:      # fused MLP: X and the residual read, Y written, both weights, biases (and the norm's vectors)
-        M, Hd, C = int(m.group(2)), int(m.group(3)), int(m.group(4))
-        return (3 * M * C + 2 * Hd * C + Hd + C + (2 * C if m.group(1) else 0)) * e, 4.0 * M * Hd * C
+    m = re.match(r"(proj\+)?(ln\+)?mlp_\w+\[(\d+),(\d+),(\d+)\]", label)
+    if m:      # fused MLP: X and the residual read, Y written, both weights, biases (and the norm's vectors);
+        #        with the projection in front: its [C, C] weight and bias as well (A, x0 read, Y written)
+        M, Hd, C = int(m.group(3)), int(m.group(4)), int(m.group(5))
+        by = 3 * M * C + 2 * Hd * C + Hd + C + (2 * C if m.group(2) else 0) + (C * C + C if m.group(1) else 0)
+        return by * e, 4.0 * M * Hd * C + (2.0 * M * C * C if m.group(1) else 0.0)
     m = re.match(r"(?:ln\+|rms\+)?p?gemm_\w+\[(\d+),(\d+),(\d+)\](.*)", label)
     if m:
         M, N, K = int(m.group(1)), int(m.group(2)), int(m.group(3))

@@ -1,28 +1,27 @@
 // Fused MLP: Y = residual + W2 . gelu(W1 . norm(x) + b1) + b2 per token, the hidden activation never leaving the
-// registers.  Not an operator pair of the paper's tables (two ILD & Variable operators are kept apart there):
+// compute unit.  Not an operator pair of the paper's tables (two ILD & Variable operators are kept apart there):
 // it is the deeper fusion next to the layout path, where the hidden tensor is the largest intermediate of a block.
 //
-// Shape of the work: a workgroup of four waves owns 32 tokens and all C output features.  The hidden dimension
-// is cut into slices of 32 units and dealt round-robin to the waves; for its slice a wave forms
-//   H^T[32 hidden, tokens] = W1[slice, :] . X^T        (C / 16 MFMAs, X fragments from LDS)
-// applies bias + GELU in registers, and feeds the result, still in registers, as the second operand of
-//   Y^T[C, tokens] += W2[:, slice] . H                  (C / 16 MFMAs)
-// so a wave holds a partial Y^T over its slices (split-K across waves) and the four partials are added through
-// LDS once, at the end, in a fixed order.  No weight element is used twice inside a workgroup, so the weights go
-// straight from L2 into MFMA operand registers (no LDS staging, no barrier in the main loop), each fragment
-// register being refilled for the wave's next slice right after the MFMA that consumed it: every load has a whole
-// slice (2 * C / 16 MFMAs) to arrive.
+// Shape of the work: a workgroup owns 32 tokens and has one wave per 32 output features (T = C / 32 waves).  The
+// token tile (normalised in place when the norm is folded) stays in LDS.  The hidden dimension is processed in rounds
+// of T slices of 32 units.  In a round, wave w first forms its slice
+//   H^T[32 hidden, 32 tokens] = W1[slice, :] . X^T        (C / 16 MFMAs, X fragments from LDS)
+// applies bias + GELU in registers and writes the bf16 result into the round's hidden tile in LDS; after one barrier it
+// accumulates its own output block over the whole round,
+//   Y^T[32 features, 32 tokens] += W2[block, round's hidden] . H        (2 T MFMAs, H fragments from LDS)
+// so no partial sums are exchanged and a wave needs 16 accumulator registers per product.  The hidden tile is
+// double-buffered: one barrier per round.  No weight element is used twice inside a workgroup, so the weights go
+// straight from L2 into MFMA operand registers (no LDS staging), half a slice ahead, each fragment register being
+// refilled right after the MFMA that consumed it.
 //
 // Weight layout (the paper's principle that a producer writes the layout its consumer reads best, Sec. 3.2.2, applied
 // to constants: done once by mlp_pack_kernel): an MFMA operand fragment is 64 lanes x 16 bytes taken from 32 rows, 32
 // bytes per row; read from the row-major matrix every such load touches 32 cache lines for a quarter of their
-// bytes (measured: 76 us against 33 us for M = 6272, C = 384, hidden 1536).  Packed, a fragment is 1 KiB
-// contiguous in lane order:
-//   W1 fragment (slice sc, step kk) at index sc * C/16 + kk:        lane (l32, hf) = W1[32 sc + rho(l32)][16 kk + 8 hf ..+7]
-//   W2 fragment (slice sc, block t, step s) at (sc * C/32 + t) * 2 + s: lane (l32, hf) = W2[32 t + l32][32 sc + 16 s + 8 hf ..+7]
-// rho assigns the accumulator rows of the first product to hidden units in the order that makes the eight values a
-// lane holds for one 16-wide step of the second product eight consecutive hidden units: accumulator row
-// 8b + 4h + i (b < 4, h < 2, i < 4) is hidden unit 16 (b >> 1) + 8h + 4 (b & 1) + i of the slice.
+// bytes (measured on an earlier form of this kernel: 76 us against 33 us for M = 6272, C = 384, hidden 1536).
+// Packed, a fragment is 1 KiB contiguous in lane order, and each wave's fragments follow each other in the order it
+// uses them:
+//   W1 fragment (slice sc, step kk) at index sc * C/16 + kk:            lane (l32, hf) = W1[32 sc + l32][16 kk + 8 hf ..+7]
+//   W2 fragment (block t, slice sc, step s) at (t * hidden/32 + sc) * 2 + s: lane (l32, hf) = W2[32 t + l32][32 sc + 16 s + 8 hf ..+7]
 #include <type_traits>
 #include "device_common.h"
 #include "kernels.h"
@@ -44,7 +43,6 @@ __device__ __forceinline__ void mlp_unpack8(mlp_u32x4 v, float* f) {
 #pragma unroll
   for (int e = 0; e < 4; ++e) { f[2 * e] = __uint_as_float(v[e] << 16); f[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u); }
 }
-__device__ __forceinline__ int mlp_rho(int r) { return 16 * (r >> 4) + 8 * ((r >> 2) & 1) + 4 * ((r >> 3) & 1) + (r & 3); }
 
 // one thread per 16-byte chunk of the packed buffer: [W1 fragments | W2 fragments]
 __global__ void mlp_pack_kernel(const bf16_t* W1, const bf16_t* W2, mlp_u32x4* packed, int C, int Hd) {
@@ -238,10 +236,6 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
       r_l[l32 * XP + w * 4 + 2 * gp + hf] = resid[gp];
     }
     __syncthreads();
-  } else if (g.residual) {
-    const bf16_t* R = (const bf16_t*)g.residual;
-    resid[0] = *(const mlp_u32x4*)(R + ro + fo);
-    resid[1] = *(const mlp_u32x4*)(R + ro + fo + 16);
   }
   if (g.norm) {
     mlp_norm_x_tile<C>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
@@ -314,6 +308,11 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 
   // every wave holds its 32 features of Y^T complete: bias, residual, two 16-byte stores per lane
   if constexpr (PROJ) { resid[0] = r_l[l32 * XP + w * 4 + hf]; resid[1] = r_l[l32 * XP + w * 4 + 2 + hf]; }
+  else if (g.residual) {          // (asked for here, not before the rounds: eight more live registers there mean spills)
+    const bf16_t* R = (const bf16_t*)g.residual;
+    resid[0] = *(const mlp_u32x4*)(R + ro + fo);
+    resid[1] = *(const mlp_u32x4*)(R + ro + fo + 16);
+  }
   const mlp_u32x4 b2v = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo), b2w = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo + 16);
   mlp_u32x4 yv[2];
   mlp_finish(out, b2v, b2w, resid, false, yv);
@@ -371,7 +370,7 @@ int launch_mlp_fused(const MlpArgs& g, void* stream) {
 
 // ---------------------------------------------------------------------------------------------------------------
 // Linear for a short reduction dimension (K = C in {128, 256, 384}), Y = act(norm(X) . W^T + b) (+ residual): the first
-// half of the kernel above on its own.  A workgroup owns 32 token rows, whose K elements stay in LDS for all N outputs;
+// product of the kernel above on its own, with four waves.  A workgroup owns 32 token rows, whose K elements stay in LDS for all N outputs;
 // the N / 32 row slices of W are dealt round-robin to the four waves and stream from L2 straight into MFMA operand
 // registers (packed by lin_pack_kernel: fragment (slice sc, step kk) at sc * K/16 + kk, lane (l32, hf) =
 // W[32 sc + l32][16 kk + 8 hf ..+7]); every wave finishes its 32 x 32 outputs in registers and stores them: no
@@ -444,31 +443,8 @@ __global__ __launch_bounds__(256, 1) void lin32_kernel(Lin32Args g) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
-    // accumulator register 4b + i of lane (token, hf) is feature 8b + 4 hf + i: one v_permlane32_swap per value pair
-    // gives each lane eight consecutive features (run 2 gp + hf of the slice's four runs of eight)
     mlp_u32x4 outv[2];
-#pragma unroll
-    for (int gp = 0; gp < 2; ++gp) {
-      float v[8], bb[8], rr[8];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(h[8 * gp + j]), __float_as_uint(h[8 * gp + 4 + j]), false, false);
-        v[j] = __uint_as_float(sw[0]);
-        v[4 + j] = __uint_as_float(sw[1]);
-      }
-      mlp_unpack8(gp ? bias_w : bias_v, bb);
-      mlp_unpack8(res[gp], rr);
-      mlp_u32x4 o;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float a = v[2 * e] + bb[2 * e], b = v[2 * e + 1] + bb[2 * e + 1];
-        const float ga = gelu_poly(a), gb = gelu_poly(b);
-        a = gelu_on ? ga : a;
-        b = gelu_on ? gb : b;
-        o[e] = mlp_pack2(a + rr[2 * e], b + rr[2 * e + 1]);
-      }
-      outv[gp] = o;
-    }
+    mlp_finish(h, bias_v, bias_w, res, gelu_on, outv);
     if (row_ok) {
       // Written as assembly so that the compiler's wait-count bookkeeping sees loads only: with stores pending next to
       // loads it stops counting and waits for everything (vmcnt 0) at the top of the next slice, which exposes the
