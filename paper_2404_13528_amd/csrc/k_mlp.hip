@@ -378,9 +378,12 @@ int launch_mlp_fused(const MlpArgs& g, void* stream) {
 // rows) for the absence of K-loop barriers and of a separate norm kernel.  Measured (with LayerNorm, against norm
 // kernel + tiled kernel resp. the tiled kernel's own folded norm): 200704 x 384 x 128: 69 us against 89;
 // 50176 x 768 x 256: 55 against 71; 6272 x 1152 x 384: 26 against 26.  The block executors do not use it.
-template <int C, bool RES>
-__global__ __launch_bounds__(256, 1) void lin32_kernel(Lin32Args g) {
-  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1;
+// NW waves per workgroup: 4 (two workgroups per CU, X fragments in registers: large grids) or C / 32 (one workgroup
+// per CU with three waves per SIMD at C = 384, X fragments re-read from LDS: grids of about one workgroup per CU)
+template <int C, bool RES, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void lin32_kernel(Lin32Args g) {
+  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NTHR = 64 * NW;
+  constexpr bool XREG = NW <= 4;
   const SM_KARG Lin32Args* gk = kernarg_ptr<Lin32Args>();
   extern __shared__ __align__(16) unsigned char smem_raw[];
   mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                                  // [32][XP]
@@ -397,19 +400,20 @@ __global__ __launch_bounds__(256, 1) void lin32_kernel(Lin32Args g) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) w1[kk] = *(const mlp_u32x4*)(wb + kk * 1024 + lane * 16u);
   }
-  mlp_load_x_tile<C>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
-  for (int s = tid; s < g.N / 8; s += 256) b_l[s] = g.bias ? ((const mlp_u32x4*)g.bias)[s] : mlp_u32x4{0u, 0u, 0u, 0u};
+  mlp_load_x_tile<C, NTHR>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  for (int s = tid; s < g.N / 8; s += NTHR) b_l[s] = g.bias ? ((const mlp_u32x4*)g.bias)[s] : mlp_u32x4{0u, 0u, 0u, 0u};
   __syncthreads();
   if (g.norm) {
     mlp_norm_x_tile<C>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
     __syncthreads();
   }
 
-  // the lane's X fragments do not depend on the slice: they stay in registers (K / 4 of them; the kernel fits two
-  // workgroups per CU with them)
-  mlp_u32x4 xf[KK];
+  // the lane's X fragments do not depend on the slice: with four waves they stay in registers (K / 4 of them)
+  mlp_u32x4 xf[XREG ? KK : 1];
+  if constexpr (XREG) {
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) xf[kk] = x_l[l32 * XP + hf + 2 * kk];
+    for (int kk = 0; kk < KK; ++kk) xf[kk] = x_l[l32 * XP + hf + 2 * kk];
+  }
   const int64_t row = row0 + l32;                 // the lane's token: accumulator column
   const bool row_ok = row < g.M;
   const int64_t rowc = row_ok ? row : g.M - 1;    // lanes past M read the last row's residual and store nothing
@@ -419,8 +423,10 @@ __global__ __launch_bounds__(256, 1) void lin32_kernel(Lin32Args g) {
   const bool gelu_on = g.act == SM_ACT_GELU;
   // the slice loop is one basic block up to the final masked store, so that the issue order below holds; loads
   // that the epilogue needs are issued before the slice's weight prefetch (vector loads return in issue order)
-  for (int sc = w; sc < nsub; sc += 4) {
-    const int nx = sc + 4 < nsub ? sc + 4 : sc;
+  for (int sc = w; sc < nsub; sc += NW) {
+    const int nx = sc + NW < nsub ? sc + NW : sc;
+    int xo = l32 * XP + hf;
+    if constexpr (!XREG) asm volatile("" : "+v"(xo));   // opaque per slice: fragments re-read from LDS, not kept in registers
     const mlp_u32x4 bias_v = b_l[sc * 4 + hf];          // features 8 hf ..+7 and 16 + 8 hf ..+7 of the slice: the two
     const mlp_u32x4 bias_w = b_l[sc * 4 + 2 + hf];      // runs this lane stores
     mlp_u32x4 res[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
@@ -434,14 +440,16 @@ __global__ __launch_bounds__(256, 1) void lin32_kernel(Lin32Args g) {
     const char* wb = Wp + (size_t)(nx * KK) * 1024u;      // scalar
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, xf[kk]), h, 0, 0, 0);
+      const mlp_u32x4 xv = XREG ? xf[XREG ? kk : 0] : x_l[xo + 2 * kk];
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, xv), h, 0, 0, 0);
       w1[kk] = *(const mlp_u32x4*)(wb + kk * 1024 + lane * 16u);
     }
-    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, XREG ? 2 : 5, 0);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      if constexpr (!XREG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     mlp_u32x4 outv[2];
     mlp_finish(h, bias_v, bias_w, res, gelu_on, outv);
@@ -467,17 +475,23 @@ __global__ void lin_pack_kernel(const bf16_t* W, mlp_u32x4* packed, int N, int K
   packed[o] = *(const mlp_u32x4*)(W + (int64_t)(32 * sc + l32) * K + 16 * kk + 8 * hf);
 }
 
-template <int C, bool RES>
-static int lin32_launch2(const Lin32Args& g, void* stream) {
+template <int C, bool RES, int NW>
+static int lin32_launch3(const Lin32Args& g, void* stream) {
   const size_t smem = (size_t)32 * (C / 8 + 1) * 16 + (size_t)g.N * 2;
   static size_t allowed = 0;
   if (smem > allowed) {
-    const hipError_t e = hipFuncSetAttribute((const void*)lin32_kernel<C, RES>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    const hipError_t e = hipFuncSetAttribute((const void*)lin32_kernel<C, RES, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return (int)e;
     allowed = smem;
   }
-  lin32_kernel<C, RES><<<dim3((unsigned)((g.M + 31) / 32)), dim3(256), smem, (hipStream_t)stream>>>(g);
+  lin32_kernel<C, RES, NW><<<dim3((unsigned)((g.M + 31) / 32)), dim3(64 * NW), smem, (hipStream_t)stream>>>(g);
   return (int)hipGetLastError();
+}
+template <int C, bool RES>
+static int lin32_launch2(const Lin32Args& g, void* stream) {
+  // few workgroups (about one per CU) and enough slices to go round: C / 32 waves each
+  if constexpr (C / 32 > 4) { if ((g.M + 31) / 32 <= 512 && g.N / 32 >= C / 32) return lin32_launch3<C, RES, C / 32>(g, stream); }
+  return lin32_launch3<C, RES, 4>(g, stream);
 }
 template <int C>
 static int lin32_launch(const Lin32Args& g, void* stream) {
