@@ -69,6 +69,57 @@ def kernel_model(label, e=2):
     return 0, 0.0
 
 
+def fold_microbench(sm, torch, steps, warmup):
+    """A transposition between two MatMuls, T = X . W1^T then Y = T^T . W2^T, three ways (the paper's micro-experiment
+    "version a optimises reads, version b optimises writes", Sec. 3.2.2, for the MatMul operator):
+    write_fold: the producer stores T transposed (strided stores), the consumer reads K-contiguous rows;
+    read_fold:  the producer stores T as it comes, the consumer reads it transposed in place (K-strided loads);
+    explicit:   the producer stores T as it comes, a copy kernel transposes it, the consumer reads the copy."""
+    dt = torch.bfloat16
+    out = {"experiment": "read- versus write-side folding of a transposition between two Linears (bf16)", "cases": []}
+    for (M, N, K, N2) in ((2048, 2048, 512, 512), (6272, 1536, 384, 384)):
+        g = torch.Generator().manual_seed(7)
+        X = torch.randn(M, K, generator=g).to(dt).cuda()
+        W1 = (torch.randn(N, K, generator=g) * K ** -0.5).to(dt).cuda()
+        W2 = (torch.randn(N2, M, generator=g) * M ** -0.5).to(dt).cuda()
+        T = torch.empty(M * N, dtype=dt, device="cuda")
+        T2 = torch.empty(N, M, dtype=dt, device="cuda")
+        Y = torch.empty(N, N2, dtype=dt, device="cuda")
+        tmap = sm.Map.create((M, N), [("permute", (1, 0))])          # view [N, M] of T [M, N]
+
+        def write_fold():
+            sm.linear(X, W1, c_transposed_batch=M, out=T)             # T stored as [N, M]
+            sm.linear(T, W2, out=Y, M=N)
+
+        def read_fold():
+            sm.linear(X, W1, out=T)
+            sm.linear(T, W2, a_map=tmap, out=Y, M=N)
+
+        def explicit():
+            sm.linear(X, W1, out=T)
+            tmap.gather(T.view(M, N), out=T2)
+            sm.linear(T2, W2, out=Y, M=N)
+
+        res, ref = {}, None
+        for name, fn in (("write_fold", write_fold), ("read_fold", read_fold), ("explicit", explicit)):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            res[name + "_us"] = round((time.perf_counter() - t0) / steps * 1e6, 2)
+            y = Y.float().clone()
+            ref = y if ref is None else ref
+            res[name + "_max_diff"] = float((y - ref).abs().max())
+        res.update(shape={"M": M, "N": N, "K": K, "N2": N2},
+                   read_over_write=round(res["read_fold_us"] / res["write_fold_us"], 3),
+                   explicit_over_write=round(res["explicit_us"] / res["write_fold_us"], 3))
+        out["cases"].append(res)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +128,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an identity sm_gather_mapped copy of 256 MiB three times (counter calibration for rocprofv3 --pmc)")
+    ap.add_argument("--fold-microbench", action="store_true",
+                    help="instead of the chain: the read-versus-write folding micro-experiment of Sec. 3.2.2 on the mapped Linear")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % a.gpus, file=sys.stderr)
@@ -85,6 +138,10 @@ def main():
     import numpy as np
     import torch
     from paper_2404_13528_amd import binding as sm, workloads as Wl
+
+    if a.fold_microbench:
+        print(json.dumps(fold_microbench(sm, torch, a.steps, a.warmup)))
+        return
 
     B, H, W, C, h, w, depth = 32, 14, 14, 384, 12, 7, 6
     dtype = torch.bfloat16

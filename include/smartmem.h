@@ -213,7 +213,12 @@ typedef struct {
 /* a_map / c_map (nullable): maps with view shape [M, K] / natural output shape
  * [M, Nout] whose last dimension is contiguous: row r of A is read at
  * a_map(r, 0); row r of the result is written at c_map(r, 0) and the residual
- * is read at the same offset.  bias, residual nullable. */
+ * is read at the same offset.  bias, residual nullable.
+ * An a_map whose last dimension is contiguous only in granules of 4 (an unfold)
+ * or not at all (a transposed operand) is accepted when its offset separates
+ * into a row part and a column part; the second case loads one element at a
+ * time: the consumer-side ("read") folding that Sec. 3.2.2 advises against,
+ * kept so that it can be measured against the producer-side fold (c_transposed). */
 int sm_linear(const sm_linear_desc*, const void* A, const void* W, const void* bias, const void* residual,
               void* C, const sm_map* a_map, const sm_map* c_map, void* stream);
 /* Weight layout for short reduction dimensions (Sec. 3.2.2's rule, the producer writes the layout its consumer reads

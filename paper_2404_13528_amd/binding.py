@@ -233,11 +233,11 @@ class Map:
                                      dt, 0, None), "sm_gather_mapped")
         return dst
 
-    def gather(self, src, stream=None):
-        """torch device tensor in, new torch device tensor out (HIP kernel)."""
+    def gather(self, src, out=None, stream=None):
+        """torch device tensor in, torch device tensor out (HIP kernel)."""
         import torch
         assert src.is_cuda and src.is_contiguous()
-        dst = torch.empty(self.shape, dtype=src.dtype, device=src.device)
+        dst = torch.empty(self.shape, dtype=src.dtype, device=src.device) if out is None else out
         check(lib().sm_gather_mapped(self.h, _ptr(src), _ptr(dst), _dt(src), 1, _stream(stream)), "sm_gather_mapped")
         return dst
 

@@ -201,11 +201,13 @@ extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, 
   g.norm = d->norm; g.norm_eps = d->norm_eps; g.norm_gamma = d->norm_gamma; g.norm_beta = d->norm_beta;
   const int n_out = (d->act == SM_ACT_SWIGLU || d->act == SM_ACT_GEGLU) ? d->N / 2 : d->N;
   int rc = rows_of(a_map, d->M, d->K, d->K, &g.a_rows, "sm_linear(A)");
-  if (rc == SM_ERR_UNSUPPORTED && a_map && d->K % 4 == 0) {
-    // K contiguous only in granules of 4 (an unfold): separable row + column programs
+  if (rc == SM_ERR_UNSUPPORTED && a_map) {
+    // K contiguous only in granules of 4 (an unfold), or not at all (a transposed operand read in place, one element
+    // per load: correct, and as slow as Sec. 3.2.2 says a sub-optimal read is): separable row + column programs
     std::string err;
-    if (!a_map->compile_rows_cols(4, &g.a_rows, &g.a_cols, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_linear(A): %s", err.c_str());
-    g.a_gran = 4;
+    if (d->K % 4 == 0 && a_map->compile_rows_cols(4, &g.a_rows, &g.a_cols, &err)) g.a_gran = 4;
+    else if (a_map->compile_rows_cols(1, &g.a_rows, &g.a_cols, &err)) g.a_gran = 1;
+    else return fail(SM_ERR_UNSUPPORTED, "sm_linear(A): %s", err.c_str());
     rc = SM_OK;
   }
   if (rc) return rc;

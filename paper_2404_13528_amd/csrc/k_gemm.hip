@@ -331,6 +331,23 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
       const bool k_ok = k0 + lc * VEC < g.K;
       kok[S] = k_ok;
       if constexpr (AGRAN) {
+        if (g.a_gran == 1) {
+          // K not contiguous at all (e.g. a transposed operand read in place, the "sub-optimal read" of Sec. 3.2.2):
+          // every element of the chunk is addressed through the column program and loaded on its own
+          int64_t ce[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) ce[e] = eval_rows_k(&gk->a_cols, k_ok ? k0 + lc * VEC + e : 0);
+#pragma unroll
+          for (int i = 0; i < 2 * MI; ++i) {
+            const T* base = a_ptr[i] - lc * VEC;
+            if constexpr (VEC == 4) {
+              ra[S][i] = u32x4{__float_as_uint(base[ce[0]]), __float_as_uint(base[ce[1]]), __float_as_uint(base[ce[2]]), __float_as_uint(base[ce[3]])};
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) ra[S][i][e] = (unsigned)base[ce[2 * e]] | ((unsigned)base[ce[2 * e + 1]] << 16);
+            }
+          }
+        } else {
         // K contiguous only in granules of 4 elements (an unfold folded into the load): the chunk is one
         // (fp32) or two (bf16) granules, each addressed through the column program
         const int kq = (k0 + lc * VEC) / 4;
@@ -344,6 +361,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
             const u32x2 lo = *(const u32x2*)(base + c0), hi = *(const u32x2*)(base + c1);
             ra[S][i] = u32x4{lo.x, lo.y, hi.x, hi.y};
           }
+        }
         }
       } else {
         const int ks = k_ok ? k0 : -lc * VEC;                  // a chunk past K is loaded from the row's first chunk and zeroed

@@ -48,7 +48,7 @@ struct GemmArgs {
   float norm_eps;               //   that precedes the Linear, folded into its load); gamma / beta have K elements,
   const void* norm_gamma;       //   beta may be null
   const void* norm_beta;
-  int a_gran;                   // > 0: A's K axis is contiguous only in granules of a_gran (= 4) elements;
+  int a_gran;                   // > 0: A's K axis is contiguous only in granules of a_gran (4 or 1) elements;
   RowProg a_cols;               //      offset(r, k) = a_rows(r) + a_cols(k / a_gran) + k % a_gran
 };
 int launch_gemm(const GemmArgs& a, void* stream);

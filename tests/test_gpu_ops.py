@@ -470,3 +470,18 @@ def test_mlp_fused_with_projection_scattered_rows():
                        norm=(dev(g, dtype), dev(be, dtype), 1e-5),
                        proj=(sm.linear_pack(dev(Wp, dtype)), dev(bp, dtype), dev(x0, dtype)), y_map=ym)
     assert_close(got, want, dtype, "projection + fused MLP through the window-reverse store", float(np.abs(want).max()) + 1.0)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("M,N,K", [(70, 96, 64), (300, 130, 200), (64, 64, 8)])
+def test_linear_reads_a_transposed_operand_in_place(dtype, M, N, K):
+    # A stored as [K, M] (K not contiguous at all): the transposition folded into the Linear's load, element by element
+    if dtype == torch.bfloat16 and N % 2:
+        pytest.skip("vector width")
+    At = draw((K, M), 130, dtype)                  # the producer's layout
+    W = draw((N, K), 131, dtype, K ** -0.5)
+    b = draw((N,), 132, dtype, 0.5)
+    want = O.linear(to_np(At).T, to_np(W), to_np(b))
+    am = sm.Map.create((K, M), [("permute", (1, 0))])
+    got = sm.linear(dev(At, dtype), dev(W, dtype), dev(b, dtype), a_map=am, M=M)
+    assert_close(got, want, dtype, "Linear over a transposed A", float(np.abs(want).max()) + 1.0)
