@@ -191,14 +191,36 @@ bool mlp_is_fused(const sm_swin_cfg& c, const sm_swin_weights* wt) {
 bool proj_is_fused(const sm_swin_cfg& c, const sm_swin_weights* wt) {
   return wt->proj_packed && wt->mlp_packed && mlp_proj_supported(c.C, c.mlp_ratio * c.C, c.dtype);
 }
+// Where the row at window-major position r of a block with shift c.shift goes in the window-major tensor of a block
+// with shift next_shift: the composed map reverse(next) then partition(this), read as a store (Sec. 3.2.1: two runs of
+// layout operators between two surviving operators collapse into one index expression)
+std::map<Key, std::shared_ptr<RowProg>> g_next_store;
+std::shared_ptr<RowProg> next_norm_store(const sm_swin_cfg& c, int next_shift, std::string* err) {
+  Key key{{c.B, c.H, c.W, c.C, c.window, c.shift, next_shift, c.dtype}};
+  std::lock_guard<std::mutex> lock(g_mu);
+  auto it = g_next_store.find(key);
+  if (it != g_next_store.end()) return it->second;
+  const int64_t B = c.B, H = c.H, W = c.W, C = c.C, w = c.window;
+  std::vector<sm_view_op> ch = chains::window_reverse(B, H, W, C, w, next_shift);
+  for (auto& op : chains::window_partition(B, H, W, C, w, c.shift)) ch.push_back(op);
+  auto p = std::make_shared<RowProg>();
+  if (!make_rows({B * (H / w) * (W / w), w * w, C}, ch, p.get(), err)) return nullptr;      // (attaches the row table)
+  g_next_store[key] = p;
+  return p;
+}
+
+// LayerNorm-1 of the block that follows in a chain, emitted by this block's last kernel as a second output (window-major,
+// i.e. through the following block's own partition map) into the workspace slot that block reads its QKV input from
+struct NextNorm { const void* gamma; const void* beta; RowProg store; };
 int run_proj_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* attn_out, const void* x, void* y, int64_t T,
-                       const RowProg& store, void* stream) {
+                       const RowProg& store, const NextNorm* next, void* next_out, void* stream) {
   MlpArgs a; std::memset(&a, 0, sizeof(a));
   a.X = attn_out; a.Wp = wt->mlp_packed; a.b1 = wt->b1; a.b2 = wt->b2; a.Y = y;
   a.M = T; a.C = c.C; a.Hd = c.mlp_ratio * c.C;
   a.norm = 1; a.norm_eps = c.eps; a.norm_gamma = wt->ln2_g; a.norm_beta = wt->ln2_b;
   a.Wproj_p = wt->proj_packed; a.bproj = wt->bproj; a.resid0 = x;
   a.x_rows = identity_rows(c.C); a.y_rows = store;
+  if (next) { a.Y2 = next_out; a.ln2_gamma = next->gamma; a.ln2_beta = next->beta; a.ln2_eps = c.eps; a.y2_rows = next->store; }
   return mlp_checked(a, stream, "sm_swin_block(proj+mlp)");
 }
 int run_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* x1, void* y, int64_t T, void* stream) {
@@ -219,8 +241,21 @@ extern "C" size_t sm_swin_block_workspace_bytes(const sm_swin_cfg* c, int mode) 
   return tc * units;
 }
 
+namespace {
+int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y, void* ws, size_t ws_bytes, int mode,
+                    void* stream, const NextNorm* next, bool ln1_done);
+}
+
 extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y,
                              void* ws, size_t ws_bytes, int mode, void* stream) {
+  return swin_block_impl(c, wt, x, y, ws, ws_bytes, mode, stream, nullptr, false);
+}
+
+namespace {
+// next (elided mode, projection + MLP fused only): also emit the following block's LayerNorm-1 into this workspace's
+// first slot; ln1_done: that slot already holds this block's LayerNorm-1 output (the previous block emitted it)
+int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y, void* ws, size_t ws_bytes, int mode,
+                    void* stream, const NextNorm* next, bool ln1_done) {
   int rc = check_swin(c, "sm_swin_block");
   if (rc) return rc;
   if (!wt || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: null pointer");
@@ -246,7 +281,9 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
 
   if (mode == SM_ELIDED) {
     void* bufA = base; void* qkv = base + tc; void* bufO = base + 4 * tc; void* x1 = base + 5 * tc; void* hid = base + 6 * tc;
-    if (fold_norm(3 * C)) {
+    if (ln1_done) {
+      if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    } else if (fold_norm(3 * C)) {
       if ((rc = run_gemm(x, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, &plan->x_gather, nullptr, stream, wt->ln1_g, wt->ln1_b, eps))) return rc;
     } else {
       if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, bufA, T, C, eps, 0, dt, nullptr, 1, &plan->ln1_store, stream))) return rc;
@@ -259,7 +296,8 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
     }
     if ((rc = attention_checked(ad, (char*)qkv + plan->qkv_base[0] * es, (char*)qkv + plan->qkv_base[1] * es, (char*)qkv + plan->qkv_base[2] * es,
                                 bufO, wt->rpb_table, stream, "window attention"))) return rc;
-    if (proj_is_fused(*c, wt)) return run_proj_mlp_fused(*c, wt, bufO, x, y, T, plan->proj_store, stream);
+    if (proj_is_fused(*c, wt)) return run_proj_mlp_fused(*c, wt, bufO, x, y, T, plan->proj_store, next, bufA, stream);
+    if (next) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: the next block's norm can only be emitted by the fused projection + MLP kernel");
     if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
     if (mlp_is_fused(*c, wt)) return run_mlp_fused(*c, wt, x1, y, T, stream);
     if (fold_norm(c->mlp_ratio * C)) {
@@ -272,6 +310,7 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
     return SM_OK;
   }
 
+  if (next || ln1_done) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: cross-block norm emission is an elided-mode path");
   void* s0 = base; void* s1 = base + tc; void* s2 = base + 2 * tc; void* s3 = base + 3 * tc;
   void* qkv = base + 4 * tc; void* qkvp = base + 7 * tc; void* x1 = base + 10 * tc; void* hid = base + 11 * tc;
   // (a row-wise norm commutes with the row permutations that follow it: where LayerNorm-1 is folded into QKV the
@@ -307,6 +346,7 @@ extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, co
   if ((rc = run_gemm(hid, wt->w2, wt->b2, x1, y, T, C, c->mlp_ratio * C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
   return SM_OK;
 }
+}  // namespace
 
 // ---------------------------------------------------------------------------
 // sm_run_chain
@@ -475,6 +515,7 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
   for (int s = 0; s < c->n_stages; ++s) {
     const sm_stage_desc& st = c->stages[s];
     const bool last_stage = s + 1 == c->n_stages;
+    bool ln1_done = false;
     for (int k = 0; k < st.depth; ++k) {
       const int shift = (k % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0;
       sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, shift, c->mlp_ratio, dt, c->eps};
@@ -483,7 +524,21 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
       wp += 15;
       const bool final_out = last_stage && k + 1 == st.depth && !c->has_head;
       void* out = final_out ? y : act[flip];
-      if ((rc = sm_swin_block(&bc, &bw, cur, out, blk_ws, z.block, mode, stream))) return rc;
+      // within a stage, elided, with the projection + MLP kernel: that kernel also writes the next block's LayerNorm-1
+      // (through the next block's own partition map), and the next block starts at its QKV Linear
+      NextNorm nn; const NextNorm* next = nullptr;
+      if (mode == SM_ELIDED && k + 1 < st.depth && proj_is_fused(bc, &bw) && !fold_norm(3 * st.C)) {
+        const int nshift = ((k + 1) % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0;
+        std::string err;
+        auto nstore = next_norm_store(bc, nshift, &err);
+        if (!nstore) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
+        sm_swin_weights nw;
+        std::memcpy(&nw, wp, sizeof(nw));
+        nn.gamma = nw.ln1_g; nn.beta = nw.ln1_b; nn.store = *nstore;
+        next = &nn;
+      }
+      if ((rc = swin_block_impl(&bc, &bw, cur, out, blk_ws, z.block, mode, stream, next, ln1_done))) return rc;
+      ln1_done = next != nullptr;
       tally();
       cur = out; flip ^= 1;
     }

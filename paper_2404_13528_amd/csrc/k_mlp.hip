@@ -152,7 +152,9 @@ __device__ __forceinline__ void mlp_finish(const mlp_f32x16& h, const mlp_u32x4&
 // output projection): x1 = A . Wp^T + bp + x0 for the tile's 32 tokens, x0 read (and Y written) through y_rows, then
 // Y = x1 + MLP(LayerNorm(x1)).  x1 never reaches memory: a normalised copy feeds the first product from LDS, a plain
 // copy in LDS is the final residual.
-template <int C, bool PROJ>
+// LNOUT: a second output, LayerNorm(Y) with its own gamma / beta, stored through its own row map: the norm that opens
+// the next block, computed while the rows are still in registers (statistics over the C / 32 waves through LDS).
+template <int C, bool PROJ, bool LNOUT>
 __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) {
   constexpr int KK = C / 16;            // 16-wide steps of the first product
   constexpr int KH = KK / 2;            // W1 fragments in flight per wave (half a slice)
@@ -171,6 +173,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   mlp_u32x4* h_l = (mlp_u32x4*)(smem_raw + (PROJ ? 3 : 1) * TILE);        // [2][32][HP]
   mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + (PROJ ? 3 : 1) * TILE + 2 * HTILE);   // [Hd / 8]
   mlp_u32x4* bp_l = b1_l + g.Hd / 8;                                      // PROJ only: [C / 8]
+  float* st_l = (float*)(b1_l + g.Hd / 8 + (PROJ ? XS : 0));              // LNOUT only: [2][T][32] row statistics
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index as a scalar: fragment bases become scalar addresses
@@ -321,33 +324,78 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     *(mlp_u32x4*)(Y + ro + fo) = yv[0];
     *(mlp_u32x4*)(Y + ro + fo + 16) = yv[1];
   }
+  if constexpr (LNOUT) {
+    // two-pass fp32 statistics of the bf16 row, as the norm kernel would compute them from the stored Y: a lane holds
+    // 16 of its token's features, its partner lane (other hf) 16 more, the other waves the rest
+    const int64_t ro2 = g.y2_rows.identity ? prow * g.y2_rows.ld : eval_rows_k(&gk->y2_rows, prow);
+    const mlp_u32x4 gv[2] = {*(const mlp_u32x4*)((const bf16_t*)g.ln2_gamma + fo), *(const mlp_u32x4*)((const bf16_t*)g.ln2_gamma + fo + 16)};
+    const mlp_u32x4 bv[2] = {*(const mlp_u32x4*)((const bf16_t*)g.ln2_beta + fo), *(const mlp_u32x4*)((const bf16_t*)g.ln2_beta + fo + 16)};
+    float f[16];
+    mlp_unpack8(yv[0], f);
+    mlp_unpack8(yv[1], f + 8);
+    float sum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += f[e];
+    sum += __shfl_xor(sum, 32, 64);
+    if (hf == 0) st_l[w * 32 + l32] = sum;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < T; ++ww) tot += st_l[ww * 32 + l32];
+    const float mean = tot / (float)C;
+    float var = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { const float d = f[e] - mean; var += d * d; }
+    var += __shfl_xor(var, 32, 64);
+    if (hf == 0) st_l[(T + w) * 32 + l32] = var;
+    __syncthreads();
+    tot = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < T; ++ww) tot += st_l[(T + ww) * 32 + l32];
+    const float rstd = rsqrtf(tot / (float)C + g.ln2_eps), sh = -mean * rstd;
+    if (row_ok) {
+      bf16_t* Y2 = (bf16_t*)g.Y2;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        float gf[8], bf[8];
+        mlp_unpack8(gv[q], gf);
+        mlp_unpack8(bv[q], bf);
+        mlp_u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          o[e] = mlp_pack2(fmaf(fmaf(f[8 * q + 2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[8 * q + 2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
+        *(mlp_u32x4*)(Y2 + ro2 + fo + 16 * q) = o;
+      }
+    }
+  }
 }
 
-static size_t mlp_smem(int C, int Hd, bool proj) {
+static size_t mlp_smem(int C, int Hd, bool proj, bool lnout) {
   const size_t tile = (size_t)32 * (C / 8 + 1) * 16, htile = (size_t)32 * (C / 8 + 1) * 16;
-  return (proj ? 3 : 1) * tile + 2 * htile + (size_t)Hd * 2 + (proj ? (size_t)C * 2 : 0);
+  return (proj ? 3 : 1) * tile + 2 * htile + (size_t)Hd * 2 + (proj ? (size_t)C * 2 : 0) + (lnout ? (size_t)2 * (C / 32) * 32 * 4 : 0);
 }
 
-template <int C, bool PROJ>
-static int mlp_launch2(const MlpArgs& g, void* stream) {
-  const size_t smem = mlp_smem(C, g.Hd, PROJ);
+template <int C, bool PROJ, bool LNOUT>
+static int mlp_launch3(const MlpArgs& g, void* stream) {
+  const size_t smem = mlp_smem(C, g.Hd, PROJ, LNOUT);
   static size_t allowed = 0;          // raised on demand: the attribute is per kernel, the hidden size varies
   if (smem > allowed) {
-    const hipError_t e = hipFuncSetAttribute((const void*)mlp_fused_kernel<C, PROJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    const hipError_t e = hipFuncSetAttribute((const void*)mlp_fused_kernel<C, PROJ, LNOUT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return (int)e;
     allowed = smem;
   }
   const int64_t n_wg = (g.M + 31) / 32;
-  mlp_fused_kernel<C, PROJ><<<dim3((unsigned)n_wg), dim3(64 * (C / 32)), smem, (hipStream_t)stream>>>(g);
+  mlp_fused_kernel<C, PROJ, LNOUT><<<dim3((unsigned)n_wg), dim3(64 * (C / 32)), smem, (hipStream_t)stream>>>(g);
   return (int)hipGetLastError();
 }
 template <int C>
 static int mlp_launch(const MlpArgs& g, void* stream) {
-  return g.Wproj_p ? mlp_launch2<C, true>(g, stream) : mlp_launch2<C, false>(g, stream);
+  if (g.Wproj_p) return g.Y2 ? mlp_launch3<C, true, true>(g, stream) : mlp_launch3<C, true, false>(g, stream);
+  return g.Y2 ? mlp_launch3<C, false, true>(g, stream) : mlp_launch3<C, false, false>(g, stream);
 }
 
 // LDS capacity: the projection variant holds three token tiles
-bool mlp_proj_supported(int C, int Hd, int dtype) { return mlp_fused_supported(C, Hd, dtype) && mlp_smem(C, Hd, true) <= 160 * 1024; }
+bool mlp_proj_supported(int C, int Hd, int dtype) { return mlp_fused_supported(C, Hd, dtype) && mlp_smem(C, Hd, true, true) <= 160 * 1024; }
 
 bool mlp_fused_supported(int C, int Hd, int dtype) {
   return dtype == SM_BF16 && (C == 128 || C == 256 || C == 384) && Hd >= 32 && Hd % 32 == 0 && Hd <= 16384;

@@ -63,7 +63,11 @@ struct MlpArgs {
   // Wproj_p != null: X is the input of a projection, x1 = X . Wproj^T + bproj + resid0 (resid0 read through y_rows),
   // and the MLP (with its norm and residual) works on x1; Wproj [C, C] packed by launch_lin_pack; `residual` unused
   const void* Wproj_p; const void* bproj; const void* resid0;
+  // Y2 != null: a second output Y2 = LayerNorm(Y; ln2_gamma, ln2_beta, ln2_eps), row r stored at y2_rows(r) (the norm
+  // that opens the next block, taken while the rows are in registers)
+  void* Y2; const void* ln2_gamma; const void* ln2_beta; float ln2_eps;
   RowProg x_rows, y_rows;       // row r of X; row r of Y and of the residual
+  RowProg y2_rows;
 };
 bool mlp_fused_supported(int C, int Hd, int dtype);
 bool mlp_proj_supported(int C, int Hd, int dtype);
