@@ -3,9 +3,9 @@
 Workload (benchmark configs[1]): Swin stage-3 chain, bf16, B=32, 14x14
 tokens, C=384, 12 heads, window 7, 6 blocks alternating shift 0/3, MLP ratio 4;
 seeded synthetic inputs resident in HBM before the timed region.  One step =
-one pass of the whole chain (19 kernels in elided mode: per block QKV, window attention, and one kernel for
-proj + residual + LayerNorm + MLP + residual + the next block's LayerNorm, plus the first block's LayerNorm; the
-explicit chain runs 30 + 30 copies) over one batch.
+one pass of the whole chain (14 kernels in elided mode: per block window attention and one kernel for
+proj + residual + LayerNorm + MLP + residual + the next block's LayerNorm and QKV, plus the first block's LayerNorm
+and QKV; the explicit chain runs 30 + 30 copies) over one batch.
 
 Prints ONE JSON line: whole-job throughput (images/s) of the elided chain, the
 explicit-transpose baseline chain timed the same way, per-kernel durations
@@ -42,14 +42,18 @@ MEASURED_TRAFFIC = {
 def kernel_model(label, e=2):
     """Algorithmic bytes and flops of one launch, from the kernel label (tensor reads + writes at
     kernel-per-op granularity with fused epilogues; weights and bias included)."""
-    m = re.match(r"(proj\+)?(ln\+)?mlp_\w+\[(\d+),(\d+),(\d+)\](\+ln)?", label)
+    m = re.match(r"(proj\+)?(ln\+)?mlp_\w+\[(\d+),(\d+),(\d+)\](\+ln)?(\+qkv)?", label)
     if m:      # fused MLP: X and the residual read, Y written, both weights, biases (and the norm's vectors);
         #        with the projection in front: its [C, C] weight and bias as well (A, x0 read, Y written);
         #        "+ln": the next block's LayerNorm as a second output
         M, Hd, C = int(m.group(3)), int(m.group(4)), int(m.group(5))
         by = 3 * M * C + 2 * Hd * C + Hd + C + (2 * C if m.group(2) else 0) + (C * C + C if m.group(1) else 0)
-        by += (M * C + 2 * C) if m.group(6) else 0
-        return by * e, 4.0 * M * Hd * C + (2.0 * M * C * C if m.group(1) else 0.0)
+        by += (M * C + 2 * C) if m.group(6) and not m.group(7) else 0
+        fl = 4.0 * M * Hd * C + (2.0 * M * C * C if m.group(1) else 0.0)
+        if m.group(7):      # ... and the next block's QKV Linear on that norm: its weight, bias and [M, 3C] output
+            by += 2 * C + 3 * C * C + 3 * C + 3 * M * C
+            fl += 6.0 * M * C * C
+        return by * e, fl
     m = re.match(r"(?:ln\+|rms\+)?p?gemm_\w+\[(\d+),(\d+),(\d+)\](.*)", label)
     if m:
         M, N, K = int(m.group(1)), int(m.group(2)), int(m.group(3))

@@ -301,6 +301,9 @@ typedef struct {
                                    sm_mlp_proj_supported accepts), SM_ELIDED also runs the output projection, its
                                    window-reverse store and the first residual inside that kernel.  SM_EXPLICIT cannot:
                                    its materialised reverse copy sits between the projection and the residual */
+  const void* qkv_packed;       /* nullable: sm_linear_pack(wqkv); used by sm_run_chain only (SM_ELIDED, inside a stage,
+                                   when the previous block runs the fused projection + MLP kernel): that kernel then also
+                                   computes this block's LayerNorm-1 and QKV Linear, and this block starts at attention */
 } sm_swin_weights;
 size_t sm_swin_block_workspace_bytes(const sm_swin_cfg*, int mode);
 int sm_swin_block(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y,
@@ -332,8 +335,8 @@ int sm_attn_block(const sm_attn_cfg*, const void* const* weights, const void* x,
  * than one window), patch merging between stages (2x2 gather folded into the
  * LayerNorm's load), optional head (LayerNorm, mean over tokens, Linear).
  * weights: device pointers in forward order: embed {w, b, ln_g, ln_b} if
- * has_embed; per stage: per block the 15 pointers of sm_swin_weights in
- * declaration order (mlp_packed and proj_packed may be null), then (between stages) merge {ln_g, ln_b, w}; head
+ * has_embed; per stage: per block the 16 pointers of sm_swin_weights in
+ * declaration order (mlp_packed, proj_packed and qkv_packed may be null), then (between stages) merge {ln_g, ln_b, w}; head
  * {ln_g, ln_b, w, b} if has_head.
  * x: image [B, in_ch, img, img] if has_embed else tokens [B, H0*W0, C0].
  * y: logits [B, n_cls] if has_head else tokens of the last stage.

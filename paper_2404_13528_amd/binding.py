@@ -68,18 +68,18 @@ SWIN_WEIGHT_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rpb_table", "wproj", "bp
 
 
 class SwinWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in SWIN_WEIGHT_NAMES + ("mlp_packed", "proj_packed")]
+    _fields_ = [(n, C.c_void_p) for n in SWIN_WEIGHT_NAMES + ("mlp_packed", "proj_packed", "qkv_packed")]
 
 
 def _packed_mlp(p, Cc, mlp_ratio, dtype, fuse_mlp):
-    """[MLP weights, projection weight] of a block in the fused kernels' order (new tensors), None where there is no
+    """[MLP weights, projection weight, QKV weight] of a block in the fused kernels' order (new tensors), None where there is no
     such kernel.  fuse_mlp: False (none), "mlp" (the MLP only) or True (the output projection as well)."""
     import torch
     if not fuse_mlp or not mlp_fused_supported(Cc, mlp_ratio * Cc, dtype):
-        return [None, None]
+        return [None, None, None]
     code = SM_BF16 if dtype == torch.bfloat16 else SM_F32
     proj = fuse_mlp is True and bool(lib().sm_mlp_proj_supported(int(Cc), int(mlp_ratio * Cc), code))
-    return [mlp_pack(p["w1"], p["w2"]), linear_pack(p["wproj"]) if proj else None]
+    return [mlp_pack(p["w1"], p["w2"]), linear_pack(p["wproj"]) if proj else None, linear_pack(p["wqkv"]) if proj else None]
 
 
 class AttnCfg(C.Structure):

@@ -251,9 +251,12 @@ int mlp_checked(MlpArgs& a, void* stream, const char* who) {
   }
   if (a.Y2 && (!a.ln2_gamma || !a.ln2_beta || !aligned16(a.Y2) || !aligned16(a.ln2_gamma) || !aligned16(a.ln2_beta) || !(a.ln2_eps > 0.f)))
     return fail(SM_ERR_INVALID_ARG, "%s: the second (normalised) output needs 16-byte aligned output, gamma, beta and eps > 0", who);
+  if (a.Wq_p && (!a.Wproj_p || !a.Y2 || !a.bq || !aligned16(a.Wq_p) || !aligned16(a.bq) || a.Hd < 3 * a.C))
+    return fail(SM_ERR_INVALID_ARG, "%s: the following Linear needs the fused projection, the normalised output's arguments, a 16-byte aligned packed weight and bias, and hidden >= 3 C", who);
   if ((a.M + 31) / 32 > 0x7fffffff) return fail(SM_ERR_SHAPE, "%s: too many rows", who);
   char label[96];
-  std::snprintf(label, sizeof label, "%s%smlp_bf16[%lld,%d,%d]%s", a.Wproj_p ? "proj+" : "", a.norm ? "ln+" : "", (long long)a.M, a.Hd, a.C, a.Y2 ? "+ln" : "");
+  std::snprintf(label, sizeof label, "%s%smlp_bf16[%lld,%d,%d]%s", a.Wproj_p ? "proj+" : "", a.norm ? "ln+" : "", (long long)a.M, a.Hd, a.C,
+                a.Wq_p ? "+ln+qkv" : (a.Y2 ? "+ln" : ""));
   Timed tm(label, stream);
   const int rc = launch_mlp_fused(a, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);

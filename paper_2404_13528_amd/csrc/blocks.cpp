@@ -211,16 +211,19 @@ std::shared_ptr<RowProg> next_norm_store(const sm_swin_cfg& c, int next_shift, s
 
 // LayerNorm-1 of the block that follows in a chain, emitted by this block's last kernel as a second output (window-major,
 // i.e. through the following block's own partition map) into the workspace slot that block reads its QKV input from
-struct NextNorm { const void* gamma; const void* beta; RowProg store; };
+struct NextNorm { const void* gamma; const void* beta; RowProg store; const void* wq_p; const void* bq; };   // wq_p: ... and its QKV Linear
 int run_proj_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* attn_out, const void* x, void* y, int64_t T,
-                       const RowProg& store, const NextNorm* next, void* next_out, void* stream) {
+                       const RowProg& store, const NextNorm* next, void* next_out, void* stream) {      // next_out: norm or QKV slot
   MlpArgs a; std::memset(&a, 0, sizeof(a));
   a.X = attn_out; a.Wp = wt->mlp_packed; a.b1 = wt->b1; a.b2 = wt->b2; a.Y = y;
   a.M = T; a.C = c.C; a.Hd = c.mlp_ratio * c.C;
   a.norm = 1; a.norm_eps = c.eps; a.norm_gamma = wt->ln2_g; a.norm_beta = wt->ln2_b;
   a.Wproj_p = wt->proj_packed; a.bproj = wt->bproj; a.resid0 = x;
   a.x_rows = identity_rows(c.C); a.y_rows = store;
-  if (next) { a.Y2 = next_out; a.ln2_gamma = next->gamma; a.ln2_beta = next->beta; a.ln2_eps = c.eps; a.y2_rows = next->store; }
+  if (next) {
+    a.Y2 = next_out; a.ln2_gamma = next->gamma; a.ln2_beta = next->beta; a.ln2_eps = c.eps; a.y2_rows = next->store;
+    a.Wq_p = next->wq_p; a.bq = next->bq;
+  }
   return mlp_checked(a, stream, "sm_swin_block(proj+mlp)");
 }
 int run_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* x1, void* y, int64_t T, void* stream) {
@@ -243,19 +246,20 @@ extern "C" size_t sm_swin_block_workspace_bytes(const sm_swin_cfg* c, int mode) 
 
 namespace {
 int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y, void* ws, size_t ws_bytes, int mode,
-                    void* stream, const NextNorm* next, bool ln1_done);
+                    void* stream, const NextNorm* next, int pre);
 }
 
 extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y,
                              void* ws, size_t ws_bytes, int mode, void* stream) {
-  return swin_block_impl(c, wt, x, y, ws, ws_bytes, mode, stream, nullptr, false);
+  return swin_block_impl(c, wt, x, y, ws, ws_bytes, mode, stream, nullptr, 0);
 }
 
 namespace {
 // next (elided mode, projection + MLP fused only): also emit the following block's LayerNorm-1 into this workspace's
-// first slot; ln1_done: that slot already holds this block's LayerNorm-1 output (the previous block emitted it)
+// first slot, or (next->wq_p) its QKV Linear's output into the QKV slot; pre = 1: the first slot already holds this
+// block's LayerNorm-1 output, pre = 2: the QKV slot already holds this block's QKV (the previous block emitted it)
 int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y, void* ws, size_t ws_bytes, int mode,
-                    void* stream, const NextNorm* next, bool ln1_done) {
+                    void* stream, const NextNorm* next, int pre) {
   int rc = check_swin(c, "sm_swin_block");
   if (rc) return rc;
   if (!wt || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: null pointer");
@@ -281,7 +285,9 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
 
   if (mode == SM_ELIDED) {
     void* bufA = base; void* qkv = base + tc; void* bufO = base + 4 * tc; void* x1 = base + 5 * tc; void* hid = base + 6 * tc;
-    if (ln1_done) {
+    if (pre == 2) {
+      // nothing: the QKV slot is filled
+    } else if (pre == 1) {
       if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
     } else if (fold_norm(3 * C)) {
       if ((rc = run_gemm(x, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, &plan->x_gather, nullptr, stream, wt->ln1_g, wt->ln1_b, eps))) return rc;
@@ -296,7 +302,7 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
     }
     if ((rc = attention_checked(ad, (char*)qkv + plan->qkv_base[0] * es, (char*)qkv + plan->qkv_base[1] * es, (char*)qkv + plan->qkv_base[2] * es,
                                 bufO, wt->rpb_table, stream, "window attention"))) return rc;
-    if (proj_is_fused(*c, wt)) return run_proj_mlp_fused(*c, wt, bufO, x, y, T, plan->proj_store, next, bufA, stream);
+    if (proj_is_fused(*c, wt)) return run_proj_mlp_fused(*c, wt, bufO, x, y, T, plan->proj_store, next, next && next->wq_p ? qkv : bufA, stream);
     if (next) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: the next block's norm can only be emitted by the fused projection + MLP kernel");
     if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
     if (mlp_is_fused(*c, wt)) return run_mlp_fused(*c, wt, x1, y, T, stream);
@@ -310,7 +316,7 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
     return SM_OK;
   }
 
-  if (next || ln1_done) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: cross-block norm emission is an elided-mode path");
+  if (next || pre) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: cross-block norm emission is an elided-mode path");
   void* s0 = base; void* s1 = base + tc; void* s2 = base + 2 * tc; void* s3 = base + 3 * tc;
   void* qkv = base + 4 * tc; void* qkvp = base + 7 * tc; void* x1 = base + 10 * tc; void* hid = base + 11 * tc;
   // (a row-wise norm commutes with the row permutations that follow it: where LayerNorm-1 is folded into QKV the
@@ -420,7 +426,7 @@ int check_chain(const sm_chain_desc* c, const char* who) {
 
 int chain_weight_count(const sm_chain_desc* c) {
   int n = c->has_embed ? 4 : 0;
-  for (int s = 0; s < c->n_stages; ++s) n += 15 * c->stages[s].depth + (s + 1 < c->n_stages ? 3 : 0);
+  for (int s = 0; s < c->n_stages; ++s) n += 16 * c->stages[s].depth + (s + 1 < c->n_stages ? 3 : 0);
   return n + (c->has_head ? 4 : 0);
 }
 
@@ -452,11 +458,11 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
   if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: unknown mode %d", mode);
   if (n_weights != chain_weight_count(c)) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: %d weight pointers given, %d expected", n_weights, chain_weight_count(c));
   {
-    // every pointer is required except a block's last two (the packed MLP and projection weights)
+    // every pointer is required except a block's last three (the packed MLP, projection and QKV weights)
     std::vector<char> optional((size_t)n_weights, 0);
     int at = c->has_embed ? 4 : 0;
     for (int s = 0; s < c->n_stages; ++s) {
-      for (int k = 0; k < c->stages[s].depth; ++k) { optional[(size_t)at + 13] = optional[(size_t)at + 14] = 1; at += 15; }
+      for (int k = 0; k < c->stages[s].depth; ++k) { optional[(size_t)at + 13] = optional[(size_t)at + 14] = optional[(size_t)at + 15] = 1; at += 16; }
       if (s + 1 < c->n_stages) at += 3;
     }
     for (int i = 0; i < n_weights; ++i)
@@ -515,13 +521,13 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
   for (int s = 0; s < c->n_stages; ++s) {
     const sm_stage_desc& st = c->stages[s];
     const bool last_stage = s + 1 == c->n_stages;
-    bool ln1_done = false;
+    int pre = 0;
     for (int k = 0; k < st.depth; ++k) {
       const int shift = (k % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0;
       sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, shift, c->mlp_ratio, dt, c->eps};
       sm_swin_weights bw;
       std::memcpy(&bw, wp, sizeof(bw));
-      wp += 15;
+      wp += 16;
       const bool final_out = last_stage && k + 1 == st.depth && !c->has_head;
       void* out = final_out ? y : act[flip];
       // within a stage, elided, with the projection + MLP kernel: that kernel also writes the next block's LayerNorm-1
@@ -535,10 +541,12 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
         sm_swin_weights nw;
         std::memcpy(&nw, wp, sizeof(nw));
         nn.gamma = nw.ln1_g; nn.beta = nw.ln1_b; nn.store = *nstore;
+        const bool with_qkv = nw.qkv_packed && c->mlp_ratio >= 3;      // (the kernel keeps the QKV bias where the first MLP bias was)
+        nn.wq_p = with_qkv ? nw.qkv_packed : nullptr; nn.bq = nw.bqkv;
         next = &nn;
       }
-      if ((rc = swin_block_impl(&bc, &bw, cur, out, blk_ws, z.block, mode, stream, next, ln1_done))) return rc;
-      ln1_done = next != nullptr;
+      if ((rc = swin_block_impl(&bc, &bw, cur, out, blk_ws, z.block, mode, stream, next, pre))) return rc;
+      pre = next ? (next->wq_p ? 2 : 1) : 0;
       tally();
       cur = out; flip ^= 1;
     }

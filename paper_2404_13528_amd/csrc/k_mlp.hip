@@ -152,9 +152,11 @@ __device__ __forceinline__ void mlp_finish(const mlp_f32x16& h, const mlp_u32x4&
 // output projection): x1 = A . Wp^T + bp + x0 for the tile's 32 tokens, x0 read (and Y written) through y_rows, then
 // Y = x1 + MLP(LayerNorm(x1)).  x1 never reaches memory: a normalised copy feeds the first product from LDS, a plain
 // copy in LDS is the final residual.
-// LNOUT: a second output, LayerNorm(Y) with its own gamma / beta, stored through its own row map: the norm that opens
+// LNOUT = 1: a second output, LayerNorm(Y) with its own gamma / beta, stored through its own row map: the norm that opens
 // the next block, computed while the rows are still in registers (statistics over the C / 32 waves through LDS).
-template <int C, bool PROJ, bool LNOUT>
+// LNOUT = 2 (with PROJ): that norm stays in LDS and the Linear that follows it (the next block's QKV, N = 3 C, packed
+// like lin_pack_kernel's) runs here too, three slices of 32 outputs per wave, stored through the same row map.
+template <int C, bool PROJ, int LNOUT>
 __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) {
   constexpr int KK = C / 16;            // 16-wide steps of the first product
   constexpr int KH = KK / 2;            // W1 fragments in flight per wave (half a slice)
@@ -309,6 +311,11 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     }
   }
 
+  if constexpr (LNOUT == 2) {       // first fragments of the Linear that follows, under the epilogue below
+    const char* first = (const char*)g.Wq_p + (size_t)(w * KK) * 1024u;
+#pragma unroll
+    for (int kk = 0; kk < KH; ++kk) w1[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
+  }
   // every wave holds its 32 features of Y^T complete: bias, residual, two 16-byte stores per lane
   if constexpr (PROJ) { resid[0] = r_l[l32 * XP + w * 4 + hf]; resid[1] = r_l[l32 * XP + w * 4 + 2 + hf]; }
   else if (g.residual) {          // (asked for here, not before the rounds: eight more live registers there mean spills)
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     *(mlp_u32x4*)(Y + ro + fo) = yv[0];
     *(mlp_u32x4*)(Y + ro + fo + 16) = yv[1];
   }
-  if constexpr (LNOUT) {
+  if constexpr (LNOUT != 0) {
     // two-pass fp32 statistics of the bf16 row, as the norm kernel would compute them from the stored Y: a lane holds
     // 16 of its token's features, its partner lane (other hf) 16 more, the other waves the rest
     const int64_t ro2 = g.y2_rows.identity ? prow * g.y2_rows.ld : eval_rows_k(&gk->y2_rows, prow);
@@ -353,18 +360,65 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 #pragma unroll
     for (int ww = 0; ww < T; ++ww) tot += st_l[(T + ww) * 32 + l32];
     const float rstd = rsqrtf(tot / (float)C + g.ln2_eps), sh = -mean * rstd;
-    if (row_ok) {
-      bf16_t* Y2 = (bf16_t*)g.Y2;
+    mlp_u32x4 nv[2];
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        float gf[8], bf[8];
-        mlp_unpack8(gv[q], gf);
-        mlp_unpack8(bv[q], bf);
-        mlp_u32x4 o;
+    for (int q = 0; q < 2; ++q) {
+      float gf[8], bf[8];
+      mlp_unpack8(gv[q], gf);
+      mlp_unpack8(bv[q], bf);
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          o[e] = mlp_pack2(fmaf(fmaf(f[8 * q + 2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[8 * q + 2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
-        *(mlp_u32x4*)(Y2 + ro2 + fo + 16 * q) = o;
+      for (int e = 0; e < 4; ++e)
+        nv[q][e] = mlp_pack2(fmaf(fmaf(f[8 * q + 2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[8 * q + 2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
+    }
+    if constexpr (LNOUT == 1) {
+      if (row_ok) {
+        bf16_t* Y2 = (bf16_t*)g.Y2;
+        *(mlp_u32x4*)(Y2 + ro2 + fo) = nv[0];
+        *(mlp_u32x4*)(Y2 + ro2 + fo + 16) = nv[1];
+      }
+    } else {
+      static_assert(LNOUT != 2 || PROJ, "the fused following Linear needs the projection variant's spare LDS tile");
+      // the normalised tile (bf16, as a norm kernel would have stored it) into the A tile's LDS, the following
+      // Linear's bias over the first bias (both dead by now), then wave w forms outputs 32 (w + T j) ..+31, j < 3
+      mlp_u32x4* n_l = a_l;
+      n_l[l32 * XP + w * 4 + hf] = nv[0];
+      n_l[l32 * XP + w * 4 + 2 + hf] = nv[1];
+      for (int s = tid; s < 3 * XS; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.bq)[s];
+      __syncthreads();
+      bf16_t* Q = (bf16_t*)g.Y2;
+      const int64_t qo = ro2 * 3;                       // same row map, rows three times as long
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int sc = w + T * j;
+        const mlp_u32x4 bias_v = b1_l[sc * 4 + hf], bias_w = b1_l[sc * 4 + 2 + hf];
+        const char* cur = (const char*)g.Wq_p + (size_t)(sc * KK) * 1024u;
+        const char* nxt = (const char*)g.Wq_p + (size_t)((j < 2 ? sc + T : sc) * KK) * 1024u;
+        int no = l32 * XP + hf;
+        asm volatile("" : "+v"(no));
+        mlp_f32x16 h;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) h[e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const mlp_u32x4 nf = n_l[no + 2 * kk];
+          h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk % KH]), __builtin_bit_cast(mlp_bf16x8, nf), h, 0, 0, 0);
+          w1[kk % KH] = kk < KH ? *(const mlp_u32x4*)(cur + (kk + KH) * 1024 + lo) : *(const mlp_u32x4*)(nxt + (kk - KH) * 1024 + lo);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        mlp_u32x4 qv[2];
+        mlp_finish(h, bias_v, bias_w, zero4, false, qv);
+        if (row_ok) {
+          // (assembly: with stores pending next to loads the compiler's wait counting falls back to waiting for all
+          // of them before the next slice's first fragment; its counts stay safe, see lin32_kernel)
+          bf16_t* qp = Q + qo + sc * 32 + hf * 8;
+          asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:32\n\ts_nop 2" :: "v"(qp), "v"(qv[0]), "v"(qv[1]) : "memory");
+        }
       }
     }
   }
@@ -375,9 +429,9 @@ static size_t mlp_smem(int C, int Hd, bool proj, bool lnout) {
   return (proj ? 3 : 1) * tile + 2 * htile + (size_t)Hd * 2 + (proj ? (size_t)C * 2 : 0) + (lnout ? (size_t)2 * (C / 32) * 32 * 4 : 0);
 }
 
-template <int C, bool PROJ, bool LNOUT>
+template <int C, bool PROJ, int LNOUT>
 static int mlp_launch3(const MlpArgs& g, void* stream) {
-  const size_t smem = mlp_smem(C, g.Hd, PROJ, LNOUT);
+  const size_t smem = mlp_smem(C, g.Hd, PROJ, LNOUT != 0);
   static size_t allowed = 0;          // raised on demand: the attribute is per kernel, the hidden size varies
   if (smem > allowed) {
     const hipError_t e = hipFuncSetAttribute((const void*)mlp_fused_kernel<C, PROJ, LNOUT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -390,8 +444,12 @@ static int mlp_launch3(const MlpArgs& g, void* stream) {
 }
 template <int C>
 static int mlp_launch(const MlpArgs& g, void* stream) {
-  if (g.Wproj_p) return g.Y2 ? mlp_launch3<C, true, true>(g, stream) : mlp_launch3<C, true, false>(g, stream);
-  return g.Y2 ? mlp_launch3<C, false, true>(g, stream) : mlp_launch3<C, false, false>(g, stream);
+  if (g.Wproj_p) {
+    if (g.Y2 && g.Wq_p) return g.Hd >= 3 * C ? mlp_launch3<C, true, 2>(g, stream) : (int)hipErrorInvalidValue;   // (the following bias reuses the first bias's LDS)
+    return g.Y2 ? mlp_launch3<C, true, 1>(g, stream) : mlp_launch3<C, true, 0>(g, stream);
+  }
+  if (g.Wq_p) return (int)hipErrorInvalidValue;
+  return g.Y2 ? mlp_launch3<C, false, 1>(g, stream) : mlp_launch3<C, false, 0>(g, stream);
 }
 
 // LDS capacity: the projection variant holds three token tiles

@@ -66,6 +66,9 @@ struct MlpArgs {
   // Y2 != null: a second output Y2 = LayerNorm(Y; ln2_gamma, ln2_beta, ln2_eps), row r stored at y2_rows(r) (the norm
   // that opens the next block, taken while the rows are in registers)
   void* Y2; const void* ln2_gamma; const void* ln2_beta; float ln2_eps;
+  // Wq_p != null (with Wproj_p): Y2 is not that norm but the Linear that follows it, Y2 = LayerNorm(Y) . Wq^T + bq with
+  // Wq [3 C, C] packed by launch_lin_pack, bq [3 C]; row r stored at 3 * y2_rows(r)
+  const void* Wq_p; const void* bq;
   RowProg x_rows, y_rows;       // row r of X; row r of Y and of the residual
   RowProg y2_rows;
 };

@@ -44,8 +44,8 @@ def test_config2_stage3_chain_full_size(mode, fuse_mlp):
     assert rel_l2(got, want) <= 2e-2
     assert rel_l2(got - to_np(x), want - to_np(x)) <= 3e-2
     # per block: LayerNorm-2, FC1, FC2 become one kernel; elided, the output projection joins them
-    # and also writes the next block's LayerNorm-1 (one LayerNorm kernel left, the first block's)
-    n = 42 if not fuse_mlp else (19 if fuse_mlp is True and mode == sm.SM_ELIDED else 30)
+    # and also computes the next block's LayerNorm-1 and QKV (one LayerNorm and one QKV kernel left, the first block's)
+    n = 42 if not fuse_mlp else (14 if fuse_mlp is True and mode == sm.SM_ELIDED else 30)
     assert sm.launch_counts() == ((n, 0) if mode == sm.SM_ELIDED else (n, 3 * 4 + 3 * 6))
 
 
