@@ -11,8 +11,9 @@
 //   Y^T[32 features, 32 tokens] += W2[block, round's hidden] . H        (2 T MFMAs, H fragments from LDS)
 // so no partial sums are exchanged and a wave needs 16 accumulator registers per product.  The hidden tile is
 // double-buffered: one barrier per round.  No weight element is used twice inside a workgroup, so the weights go
-// straight from L2 into MFMA operand registers (no LDS staging), half a slice ahead, each fragment register being
-// refilled right after the MFMA that consumed it.
+// straight from L2 into MFMA operand registers (no LDS staging): one set of C / 16 fragment registers carries the
+// wave's whole weight stream, each register refilled, right after the MFMA that read it, with the fragment the next
+// product needs at the same position, so every load has a full product (C / 16 MFMAs) to arrive.
 //
 // Weight layout (the paper's principle that a producer writes the layout its consumer reads best, Sec. 3.2.2, applied
 // to constants: done once by mlp_pack_kernel): an MFMA operand fragment is 64 lanes x 16 bytes taken from 32 rows, 32
@@ -159,7 +160,6 @@ __device__ __forceinline__ void mlp_finish(const mlp_f32x16& h, const mlp_u32x4&
 template <int C, bool PROJ, int LNOUT>
 __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) {
   constexpr int KK = C / 16;            // 16-wide steps of the first product
-  constexpr int KH = KK / 2;            // W1 fragments in flight per wave (half a slice)
   constexpr int T = C / 32;             // 32-row blocks of Y^T = waves of the workgroup
   constexpr int NTHR = 64 * T;
   constexpr int XS = C / 8;             // 16-byte slots per token row
@@ -187,15 +187,16 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   const char* W2p = W1p + (size_t)Hd * C * 2 + (size_t)w * nsub * 2048;   // this wave's row block: (slice, step) in order
   const unsigned lo = lane * 16u;
 
-  // the wave's first fragments are requested before anything else
-  mlp_u32x4 w1[KH], w2[T];
+  // One set of C / 16 fragment registers carries the whole weight stream of the wave: a product of C / 16 MFMAs
+  // consumes them in order, and each is refilled, right after the MFMA that read it, with the fragment the NEXT
+  // product needs at the same position (first product -> this round's W2 fragments -> next round's W1 slice -> ...):
+  // every load has a full product to arrive and the compiler's wait is one constant count.
+  mlp_u32x4 wf[KK];
   const int sc0 = w < nsub ? w : nsub - 1;      // (a wave past the last slice works on a copy of it and contributes zeros)
   {
     const char* first = PROJ ? (const char*)g.Wproj_p + (size_t)(w * KK) * 1024u : W1p + (size_t)(sc0 * KK) * 1024u;
 #pragma unroll
-    for (int kk = 0; kk < KH; ++kk) w1[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
-#pragma unroll
-    for (int i = 0; i < T; ++i) w2[i] = *(const mlp_u32x4*)(W2p + (size_t)(i < 2 * nsub ? i : (i & 1) + 2 * (nsub - 1)) * 1024u + lo);
+    for (int kk = 0; kk < KK; ++kk) wf[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
   }
 
   mlp_load_x_tile<C, NTHR>(PROJ ? a_l : x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
@@ -214,7 +215,6 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     const bf16_t* R0 = (const bf16_t*)g.resid0;
     const mlp_u32x4 res[2] = {*(const mlp_u32x4*)(R0 + ro + fo), *(const mlp_u32x4*)(R0 + ro + fo + 16)};
     const mlp_u32x4 bias_v = bp_l[w * 4 + hf], bias_w = bp_l[w * 4 + 2 + hf];
-    const char* cur = (const char*)g.Wproj_p + (size_t)(w * KK) * 1024u;
     const char* nxt = W1p + (size_t)(sc0 * KK) * 1024u;
     int ao = l32 * XP + hf;
     asm volatile("" : "+v"(ao));
@@ -224,8 +224,8 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const mlp_u32x4 af = a_l[ao + 2 * kk];
-      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk % KH]), __builtin_bit_cast(mlp_bf16x8, af), h, 0, 0, 0);
-      w1[kk % KH] = kk < KH ? *(const mlp_u32x4*)(cur + (kk + KH) * 1024 + lo) : *(const mlp_u32x4*)(nxt + (kk - KH) * 1024 + lo);
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, af), h, 0, 0, 0);
+      wf[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lo);
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);        // LDS fragment reads run three steps ahead of their MFMA
 #pragma unroll
@@ -261,16 +261,18 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     int xo = l32 * XP + hf;                              // opaque per round: the X fragments are re-read from LDS instead
     asm volatile("" : "+v"(xo));                         // of being hoisted into (and spilled from) registers
     const mlp_u32x4 bias_v = b1_l[scc * 4 + hf], bias_w = b1_l[scc * 4 + 2 + hf];
-    const char* cur = W1p + (size_t)(scc * KK) * 1024u;  // scalar
-    const char* nxt = W1p + (size_t)(nsc * KK) * 1024u;
+    const int s0 = r * T;                                // first slice of the round
+    const int rem = nsub - s0;                           // slices of W2 from this round's first to the end (>= 1)
+    const char* cur2 = W2p + (size_t)s0 * 2048u;         // scalar: this round's W2 fragments of this wave, (slice, step) in order
     mlp_f32x16 h;
 #pragma unroll
     for (int e = 0; e < 16; ++e) h[e] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const mlp_u32x4 xf = x_l[xo + 2 * kk];
-      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk % KH]), __builtin_bit_cast(mlp_bf16x8, xf), h, 0, 0, 0);
-      w1[kk % KH] = kk < KH ? *(const mlp_u32x4*)(cur + (kk + KH) * 1024 + lo) : *(const mlp_u32x4*)(nxt + (kk - KH) * 1024 + lo);
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, xf), h, 0, 0, 0);
+      // refill with the second product's fragment kk of this round; past the end of W2 the last valid pair again (its H is zero)
+      wf[kk] = *(const mlp_u32x4*)(cur2 + (size_t)(kk < 2 * rem ? kk : (kk & 1) + 2 * (rem - 1)) * 1024u + lo);
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);        // LDS fragment reads run three steps ahead of their MFMA
 #pragma unroll
@@ -287,20 +289,14 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     __syncthreads();
     // ---- second product: this wave's 32 output features over the round's T slices.  One barrier per round: the
     // other H buffer is written next, and nobody writes this one again before the barrier after that
-    const int s0 = r * T;                                                   // first slice of the round
-    const int rem = nsub - s0;                                              // slices of W2 from this round's first to the end (>= 1)
     int ho = l32 * HP + hf;
     asm volatile("" : "+v"(ho));
-    const char* cur2 = W2p + (size_t)s0 * 2048u;
+    const char* nxt = W1p + (size_t)(nsc * KK) * 1024u;                     // the wave's slice of the next round
 #pragma unroll
     for (int i = 0; i < 2 * T; ++i) {                                       // i = 2 * (slice of the round) + step
       const mlp_u32x4 hfg = hb[ho + 2 * i];
-      out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w2[i % T]), __builtin_bit_cast(mlp_bf16x8, hfg), out, 0, 0, 0);
-      // refill: second half of this round's fragments, then the first half of the next round's; past the end of
-      // W2 the last valid fragment pair is read again (its H is zero)
-      const int fi = i + T;                                                 // fragment index relative to this round's first
-      const int fc = fi < 2 * rem ? fi : (fi & 1) + 2 * (rem - 1);
-      w2[i % T] = *(const mlp_u32x4*)(cur2 + (size_t)fc * 1024u + lo);
+      out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[i]), __builtin_bit_cast(mlp_bf16x8, hfg), out, 0, 0, 0);
+      wf[i] = *(const mlp_u32x4*)(nxt + i * 1024 + lo);                     // (after the last round: a copy of the last slice, unused)
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
 #pragma unroll
@@ -314,7 +310,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   if constexpr (LNOUT == 2) {       // first fragments of the Linear that follows, under the epilogue below
     const char* first = (const char*)g.Wq_p + (size_t)(w * KK) * 1024u;
 #pragma unroll
-    for (int kk = 0; kk < KH; ++kk) w1[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
+    for (int kk = 0; kk < KK; ++kk) wf[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
   }
   // every wave holds its 32 features of Y^T complete: bias, residual, two 16-byte stores per lane
   if constexpr (PROJ) { resid[0] = r_l[l32 * XP + w * 4 + hf]; resid[1] = r_l[l32 * XP + w * 4 + 2 + hf]; }
@@ -391,7 +387,6 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
       for (int j = 0; j < 3; ++j) {
         const int sc = w + T * j;
         const mlp_u32x4 bias_v = b1_l[sc * 4 + hf], bias_w = b1_l[sc * 4 + 2 + hf];
-        const char* cur = (const char*)g.Wq_p + (size_t)(sc * KK) * 1024u;
         const char* nxt = (const char*)g.Wq_p + (size_t)((j < 2 ? sc + T : sc) * KK) * 1024u;
         int no = l32 * XP + hf;
         asm volatile("" : "+v"(no));
@@ -401,8 +396,8 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
           const mlp_u32x4 nf = n_l[no + 2 * kk];
-          h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk % KH]), __builtin_bit_cast(mlp_bf16x8, nf), h, 0, 0, 0);
-          w1[kk % KH] = kk < KH ? *(const mlp_u32x4*)(cur + (kk + KH) * 1024 + lo) : *(const mlp_u32x4*)(nxt + (kk - KH) * 1024 + lo);
+          h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, nf), h, 0, 0, 0);
+          if (j < 2) wf[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lo);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
 #pragma unroll
