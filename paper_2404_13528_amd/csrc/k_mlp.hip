@@ -221,11 +221,12 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     mlp_f32x16 h;
 #pragma unroll
     for (int e = 0; e < 16; ++e) h[e] = 0.f;
+    mlp_u32x4 fb[3] = {a_l[ao], a_l[ao + 2], a_l[ao + 4]};       // LDS fragments three steps ahead of their MFMA
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      const mlp_u32x4 af = a_l[ao + 2 * kk];
-      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, af), h, 0, 0, 0);
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, fb[kk % 3]), h, 0, 0, 0);
       wf[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lo);
+      if (kk + 3 < KK) fb[kk % 3] = a_l[ao + 2 * (kk + 3)];
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);        // LDS fragment reads run three steps ahead of their MFMA
 #pragma unroll
@@ -260,17 +261,17 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     const int nsc = sc + T < nsub ? sc + T : scc;
     int xo = l32 * XP + hf;                              // opaque per round: the X fragments are re-read from LDS instead
     asm volatile("" : "+v"(xo));                         // of being hoisted into (and spilled from) registers
-    const mlp_u32x4 bias_v = b1_l[scc * 4 + hf], bias_w = b1_l[scc * 4 + 2 + hf];
     const int s0 = r * T;                                // first slice of the round
     const int rem = nsub - s0;                           // slices of W2 from this round's first to the end (>= 1)
     const char* cur2 = W2p + (size_t)s0 * 2048u;         // scalar: this round's W2 fragments of this wave, (slice, step) in order
     mlp_f32x16 h;
 #pragma unroll
     for (int e = 0; e < 16; ++e) h[e] = 0.f;
+    mlp_u32x4 fb[3] = {x_l[xo], x_l[xo + 2], x_l[xo + 4]};        // LDS fragments three steps ahead of their MFMA
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      const mlp_u32x4 xf = x_l[xo + 2 * kk];
-      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, xf), h, 0, 0, 0);
+      h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, fb[kk % 3]), h, 0, 0, 0);
+      if (kk + 3 < KK) fb[kk % 3] = x_l[xo + 2 * (kk + 3)];
       // refill with the second product's fragment kk of this round; past the end of W2 the last valid pair again (its H is zero)
       wf[kk] = *(const mlp_u32x4*)(cur2 + (size_t)(kk < 2 * rem ? kk : (kk & 1) + 2 * (rem - 1)) * 1024u + lo);
     }
@@ -282,6 +283,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     mlp_u32x4 hv[2];
+    const mlp_u32x4 bias_v = b1_l[scc * 4 + hf], bias_w = b1_l[scc * 4 + 2 + hf];
     mlp_finish(h, bias_v, bias_w, zero4, true, hv);
     mlp_u32x4* hb = h_l + (r & 1) * (32 * HP);
 #pragma unroll
@@ -292,10 +294,11 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     int ho = l32 * HP + hf;
     asm volatile("" : "+v"(ho));
     const char* nxt = W1p + (size_t)(nsc * KK) * 1024u;                     // the wave's slice of the next round
+    mlp_u32x4 gb[3] = {hb[ho], hb[ho + 2], hb[ho + 4]};
 #pragma unroll
     for (int i = 0; i < 2 * T; ++i) {                                       // i = 2 * (slice of the round) + step
-      const mlp_u32x4 hfg = hb[ho + 2 * i];
-      out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[i]), __builtin_bit_cast(mlp_bf16x8, hfg), out, 0, 0, 0);
+      out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[i]), __builtin_bit_cast(mlp_bf16x8, gb[i % 3]), out, 0, 0, 0);
+      if (i + 3 < 2 * T) gb[i % 3] = hb[ho + 2 * (i + 3)];
       wf[i] = *(const mlp_u32x4*)(nxt + i * 1024 + lo);                     // (after the last round: a copy of the last slice, unused)
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
@@ -393,10 +396,11 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
         mlp_f32x16 h;
 #pragma unroll
         for (int e = 0; e < 16; ++e) h[e] = 0.f;
+        mlp_u32x4 fb[3] = {n_l[no], n_l[no + 2], n_l[no + 4]};
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-          const mlp_u32x4 nf = n_l[no + 2 * kk];
-          h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, nf), h, 0, 0, 0);
+          h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, fb[kk % 3]), h, 0, 0, 0);
+          if (kk + 3 < KK) fb[kk % 3] = n_l[no + 2 * (kk + 3)];
           if (j < 2) wf[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lo);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
