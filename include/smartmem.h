@@ -340,7 +340,11 @@ int sm_attn_block(const sm_attn_cfg*, const void* const* weights, const void* x,
  * {ln_g, ln_b, w, b} if has_head.
  * x: image [B, in_ch, img, img] if has_embed else tokens [B, H0*W0, C0].
  * y: logits [B, n_cls] if has_head else tokens of the last stage.
- * y_feat (nullable): the normalised feature map [B, L_last, C_last] before pooling. */
+ * y_feat (nullable): the normalised feature map [B, L_last, C_last] before pooling.
+ * Inside a stage, SM_ELIDED, with a block's three packed weights given, a block costs two kernels: window attention,
+ * and one kernel for projection + residual + LayerNorm-2 + MLP + residual that also computes the next block's
+ * LayerNorm-1 and QKV Linear (stored through the composition of this block's window-reverse map and the next block's
+ * partition map); the first block of a stage runs its own LayerNorm-1 and QKV. */
 typedef struct { int32_t C, heads, depth, H, W; } sm_stage_desc;
 typedef struct {
   int32_t B, dtype, window, mlp_ratio;

@@ -49,15 +49,15 @@ def test_config2_stage3_chain_full_size(mode, fuse_mlp):
     assert sm.launch_counts() == ((n, 0) if mode == sm.SM_ELIDED else (n, 3 * 4 + 3 * 6))
 
 
-def small_net_case(dtype, mode):
-    B, img, embed, depths, heads, w, ncls = 2, 112, 32, (2, 2), (1, 2), 7, 24
+def small_net_case(dtype, mode, embed=32, heads=(1, 2), fuse_mlp=True):
+    B, img, depths, w, ncls = 2, 112, (2, 2), 7, 24
     image, net = Wl.swin_net_case(B, img=img, embed=embed, depths=depths, heads=heads, w=w, n_cls=ncls,
                                   bf16=(dtype == torch.bfloat16))
     stages, H, C = [], img // 4, embed
     for dep, hh in zip(depths, heads):
         stages.append((C, hh, dep, H, H))
         H, C = H // 2, C * 2
-    chain = sm.SwinChain(B, stages, w, net_dev(net, dtype), dtype, mode, img=img, n_cls=ncls)
+    chain = sm.SwinChain(B, stages, w, net_dev(net, dtype), dtype, mode, img=img, n_cls=ncls, fuse_mlp=fuse_mlp)
     logits, feat = chain(dev(image, dtype), want_feat=True)
     torch.cuda.synchronize()
     f_want, l_want = swin.swin_net(to_np(image), net_np(net), 4, w, heads)
@@ -72,6 +72,19 @@ def test_small_net_embed_merge_head(dtype, mode):
         assert np.abs(f - fw).max() <= 1e-4 * max(1.0, np.abs(fw).max()) and np.abs(l - lw).max() <= 1e-4
     else:
         assert rel_l2(f, fw) <= 2e-2 and rel_l2(l, lw) <= 2e-2
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("fuse_mlp", [True, "mlp", False])
+def test_small_net_with_fused_kernel_widths(mode, fuse_mlp):
+    # stage widths 128 and 256: the fused MLP / projection kernels are in play, and in the second stage (elided, fully
+    # fused) block 0 also computes block 1's LayerNorm-1 and QKV through the composed reverse / shifted-partition map
+    f, fw, l, lw = small_net_case(torch.bfloat16, mode, embed=128, heads=(4, 8), fuse_mlp=fuse_mlp)
+    assert rel_l2(f, fw) <= 2e-2 and rel_l2(l, lw) <= 2e-2
+    if mode == sm.SM_ELIDED:
+        # embed 2 + stage 1 (LayerNorm-1 folded into QKV: 3C <= 512) + merge 2 + stage 2 + head 3
+        per_stage = {True: (2 * 3, 4 + 2), "mlp": (2 * 4, 2 * 5), False: (2 * 5, 2 * 7)}[fuse_mlp]
+        assert sm.launch_counts()[0] == 2 + per_stage[0] + 2 + per_stage[1] + 3
 
 
 def test_config3_swin_b_full_size():
