@@ -183,9 +183,13 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   const int Hd = g.Hd;
   const int nsub = Hd >> 5;
   const int rounds = (nsub + T - 1) / T;
-  const char* W1p = (const char*)g.Wp;                                    // fragments of 1 KiB, see the file header
-  const char* W2p = W1p + (size_t)Hd * C * 2 + (size_t)w * nsub * 2048;   // this wave's row block: (slice, step) in order
-  const unsigned lo = lane * 16u;
+  // Weight fragments (1 KiB each, see the file header) are fetched with buffer loads: the descriptor and the fragment's
+  // offset are scalar, the only vector operand is the lane's 16 bytes within the fragment, so no address arithmetic
+  // touches the vector registers (and a fragment index past the end would read zeros instead of faulting).
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wp), 0, 4 * Hd * C, 0x00020000);
+  const int W2o = 2 * Hd * C + w * nsub * 2048;                           // byte offset of this wave's W2 row block: (slice, step) in order
+  const int lo = lane * 16;
+  auto wload = [&](const __amdgpu_buffer_rsrc_t& r, int soff) __attribute__((always_inline)) { return __builtin_amdgcn_raw_buffer_load_b128(r, lo, soff, 0); };
 
   // One set of C / 16 fragment registers carries the whole weight stream of the wave: a product of C / 16 MFMAs
   // consumes them in order, and each is refilled, right after the MFMA that read it, with the fragment the NEXT
@@ -193,11 +197,11 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   // every load has a full product to arrive and the compiler's wait is one constant count.
   mlp_u32x4 wf[KK];
   const int sc0 = w < nsub ? w : nsub - 1;      // (a wave past the last slice works on a copy of it and contributes zeros)
-  {
-    const char* first = PROJ ? (const char*)g.Wproj_p + (size_t)(w * KK) * 1024u : W1p + (size_t)(sc0 * KK) * 1024u;
+  __amdgpu_buffer_rsrc_t rp = rw, rq = rw;
+  if constexpr (PROJ) rp = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wproj_p), 0, 2 * C * C, 0x00020000);
+  if constexpr (LNOUT == 2) rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wq_p), 0, 6 * C * C, 0x00020000);
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) wf[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
-  }
+  for (int kk = 0; kk < KK; ++kk) wf[kk] = PROJ ? wload(rp, (w * KK + kk) * 1024) : wload(rw, (sc0 * KK + kk) * 1024);
 
   mlp_load_x_tile<C, NTHR>(PROJ ? a_l : x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
   for (int s = tid; s < Hd / 8; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
@@ -215,7 +219,6 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     const bf16_t* R0 = (const bf16_t*)g.resid0;
     const mlp_u32x4 res[2] = {*(const mlp_u32x4*)(R0 + ro + fo), *(const mlp_u32x4*)(R0 + ro + fo + 16)};
     const mlp_u32x4 bias_v = bp_l[w * 4 + hf], bias_w = bp_l[w * 4 + 2 + hf];
-    const char* nxt = W1p + (size_t)(sc0 * KK) * 1024u;
     int ao = l32 * XP + hf;
     asm volatile("" : "+v"(ao));
     mlp_f32x16 h;
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, fb[kk % 3]), h, 0, 0, 0);
-      wf[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lo);
+      wf[kk] = wload(rw, (sc0 * KK + kk) * 1024);
       if (kk + 3 < KK) fb[kk % 3] = a_l[ao + 2 * (kk + 3)];
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);        // LDS fragment reads run three steps ahead of their MFMA
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     asm volatile("" : "+v"(xo));                         // of being hoisted into (and spilled from) registers
     const int s0 = r * T;                                // first slice of the round
     const int rem = nsub - s0;                           // slices of W2 from this round's first to the end (>= 1)
-    const char* cur2 = W2p + (size_t)s0 * 2048u;         // scalar: this round's W2 fragments of this wave, (slice, step) in order
+    const int cur2 = W2o + s0 * 2048;                    // scalar: this round's W2 fragments of this wave, (slice, step) in order
     mlp_f32x16 h;
 #pragma unroll
     for (int e = 0; e < 16; ++e) h[e] = 0.f;
@@ -273,7 +276,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
       h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, fb[kk % 3]), h, 0, 0, 0);
       if (kk + 3 < KK) fb[kk % 3] = x_l[xo + 2 * (kk + 3)];
       // refill with the second product's fragment kk of this round; past the end of W2 the last valid pair again (its H is zero)
-      wf[kk] = *(const mlp_u32x4*)(cur2 + (size_t)(kk < 2 * rem ? kk : (kk & 1) + 2 * (rem - 1)) * 1024u + lo);
+      wf[kk] = wload(rw, cur2 + (kk < 2 * rem ? kk : (kk & 1) + 2 * (rem - 1)) * 1024);
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);        // LDS fragment reads run three steps ahead of their MFMA
 #pragma unroll
@@ -293,13 +296,12 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
     // other H buffer is written next, and nobody writes this one again before the barrier after that
     int ho = l32 * HP + hf;
     asm volatile("" : "+v"(ho));
-    const char* nxt = W1p + (size_t)(nsc * KK) * 1024u;                     // the wave's slice of the next round
     mlp_u32x4 gb[3] = {hb[ho], hb[ho + 2], hb[ho + 4]};
 #pragma unroll
     for (int i = 0; i < 2 * T; ++i) {                                       // i = 2 * (slice of the round) + step
       out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[i]), __builtin_bit_cast(mlp_bf16x8, gb[i % 3]), out, 0, 0, 0);
       if (i + 3 < 2 * T) gb[i % 3] = hb[ho + 2 * (i + 3)];
-      wf[i] = *(const mlp_u32x4*)(nxt + i * 1024 + lo);                     // (after the last round: a copy of the last slice, unused)
+      wf[i] = wload(rw, (nsc * KK + i) * 1024);                             // the wave's slice of the next round (after the last: a copy, unused)
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
 #pragma unroll
@@ -311,9 +313,8 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   }
 
   if constexpr (LNOUT == 2) {       // first fragments of the Linear that follows, under the epilogue below
-    const char* first = (const char*)g.Wq_p + (size_t)(w * KK) * 1024u;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) wf[kk] = *(const mlp_u32x4*)(first + kk * 1024 + lo);
+    for (int kk = 0; kk < KK; ++kk) wf[kk] = wload(rq, (w * KK + kk) * 1024);
   }
   // every wave holds its 32 features of Y^T complete: bias, residual, two 16-byte stores per lane
   if constexpr (PROJ) { resid[0] = r_l[l32 * XP + w * 4 + hf]; resid[1] = r_l[l32 * XP + w * 4 + 2 + hf]; }
@@ -390,7 +391,6 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
       for (int j = 0; j < 3; ++j) {
         const int sc = w + T * j;
         const mlp_u32x4 bias_v = b1_l[sc * 4 + hf], bias_w = b1_l[sc * 4 + 2 + hf];
-        const char* nxt = (const char*)g.Wq_p + (size_t)((j < 2 ? sc + T : sc) * KK) * 1024u;
         int no = l32 * XP + hf;
         asm volatile("" : "+v"(no));
         mlp_f32x16 h;
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
         for (int kk = 0; kk < KK; ++kk) {
           h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, wf[kk]), __builtin_bit_cast(mlp_bf16x8, fb[kk % 3]), h, 0, 0, 0);
           if (kk + 3 < KK) fb[kk % 3] = n_l[no + 2 * (kk + 3)];
-          if (j < 2) wf[kk] = *(const mlp_u32x4*)(nxt + kk * 1024 + lo);
+          if (j < 2) wf[kk] = wload(rq, ((sc + T) * KK + kk) * 1024);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
 #pragma unroll
