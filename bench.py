@@ -29,9 +29,9 @@ PEAK_BF16 = 2.5e15         # FLOP/s dense bf16 MFMA, MI355X published
 # copy-kernel calibration described in the design doc); filled from profiles/, None = not measured.
 MEASURED_TRAFFIC = {
     # profiles/swin_stage3_chain_b32_hbm_counters.md: (FETCH_SIZE KiB x 2.000 + WRITE_SIZE KiB x 1.000) x 1024
-    "proj+ln+mlp_bf16[6272,1536,384]+ln+qkv": int((18718.1 * 2.0 + 18816.0) * 1024),
-    "proj+ln+mlp_bf16[6272,1536,384]": int((15193.8 * 2.0 + 4704.0) * 1024),
-    "ln+mlp_bf16[6272,1536,384]": int((11662.4 * 2.0 + 4704.0) * 1024),
+    "proj+ln+mlp_bf16[6272,1536,384]+ln+qkv": int((18726.1 * 2.0 + 18816.1) * 1024),
+    "proj+ln+mlp_bf16[6272,1536,384]": int((15194.2 * 2.0 + 4704.0) * 1024),
+    "ln+mlp_bf16[6272,1536,384]": int((11666.8 * 2.0 + 4704.0) * 1024),
     "gemm_bf16[6272,1152,384]": int((6443.5 * 2.0 + 14113.2) * 1024),
     "gemm_bf16[6272,384,384]+res": int((3784.5 * 2.0 + 4704.0) * 1024),
     "attention_window_bf16[128,12,49,49,32]": int((7137.5 * 2.0 + 4704.0) * 1024),
