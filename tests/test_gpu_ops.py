@@ -320,6 +320,11 @@ def test_empty_inputs_are_no_ops():
     assert sm.norm(x0, g, g).shape == (0, 96)
     W = torch.ones((64, 96), dtype=dtype, device="cuda")
     assert sm.linear(x0, W, M=0).shape == (0, 64)
+    x1 = torch.empty((0, 128), dtype=dtype, device="cuda")
+    W1, W2 = torch.ones((256, 128), dtype=dtype, device="cuda"), torch.ones((128, 256), dtype=dtype, device="cuda")
+    b1, b2 = torch.ones(256, dtype=dtype, device="cuda"), torch.ones(128, dtype=dtype, device="cuda")
+    assert sm.mlp_fused(x1, sm.mlp_pack(W1, W2), b1, b2, M=0).shape == (0, 128)
+    assert sm.linear(x1, sm.linear_pack(W1), b1, M=0, packed=True).shape == (0, 256)
 
 
 @pytest.mark.parametrize("M,C,Hd", [(32, 128, 512), (70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (45, 384, 160)])
