@@ -26,7 +26,7 @@ PEAK_HBM = 8.0e12          # B/s, MI355X published
 PEAK_BF16 = 2.5e15         # FLOP/s dense bf16 MFMA, MI355X published
 
 # HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (bytes, scaled by the
-# copy-kernel calibration described in the design doc); filled from profiles/, None = not measured.
+# calibration against an identity copy of known size, --calibrate-copy); filled from profiles/, None = not measured.
 MEASURED_TRAFFIC = {
     # profiles/swin_stage3_chain_b32_hbm_counters.md: (FETCH_SIZE KiB x 2.000 + WRITE_SIZE KiB x 1.000) x 1024
     "proj+ln+mlp_bf16[6272,1536,384]+ln+qkv": int((18726.1 * 2.0 + 18816.1) * 1024),

@@ -5,4 +5,4 @@ sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 
 def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run under gpurun)")
+    config.addinivalue_line("markers", "gpu: needs a real MI355X")
