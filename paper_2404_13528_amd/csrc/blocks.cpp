@@ -533,13 +533,16 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
       // within a stage, elided, with the projection + MLP kernel: that kernel also writes the next block's LayerNorm-1
       // (through the next block's own partition map), and the next block starts at its QKV Linear
       NextNorm nn; const NextNorm* next = nullptr;
-      if (mode == SM_ELIDED && k + 1 < st.depth && proj_is_fused(bc, &bw) && !fold_norm(3 * st.C)) {
+      sm_swin_weights nwt;
+      if (k + 1 < st.depth) std::memcpy(&nwt, wp, sizeof(nwt));
+      // (where LayerNorm-1 is folded into the QKV Linear's load, C <= 170, only the norm + QKV form applies)
+      if (mode == SM_ELIDED && k + 1 < st.depth && proj_is_fused(bc, &bw) &&
+          (!fold_norm(3 * st.C) || (nwt.qkv_packed && c->mlp_ratio >= 3))) {
         const int nshift = ((k + 1) % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0;
         std::string err;
         auto nstore = next_norm_store(bc, nshift, &err);
         if (!nstore) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
-        sm_swin_weights nw;
-        std::memcpy(&nw, wp, sizeof(nw));
+        const sm_swin_weights& nw = nwt;
         nn.gamma = nw.ln1_g; nn.beta = nw.ln1_b; nn.store = *nstore;
         const bool with_qkv = nw.qkv_packed && c->mlp_ratio >= 3;      // (the kernel keeps the QKV bias where the first MLP bias was)
         nn.wq_p = with_qkv ? nw.qkv_packed : nullptr; nn.bq = nw.bqkv;

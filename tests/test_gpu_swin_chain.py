@@ -82,8 +82,9 @@ def test_small_net_with_fused_kernel_widths(mode, fuse_mlp):
     f, fw, l, lw = small_net_case(torch.bfloat16, mode, embed=128, heads=(4, 8), fuse_mlp=fuse_mlp)
     assert rel_l2(f, fw) <= 2e-2 and rel_l2(l, lw) <= 2e-2
     if mode == sm.SM_ELIDED:
-        # embed 2 + stage 1 (LayerNorm-1 folded into QKV: 3C <= 512) + merge 2 + stage 2 + head 3
-        per_stage = {True: (2 * 3, 4 + 2), "mlp": (2 * 4, 2 * 5), False: (2 * 5, 2 * 7)}[fuse_mlp]
+        # embed 2 + stage 1 (LayerNorm-1 folded into QKV: 3C <= 512) + merge 2 + stage 2 + head 3; fully fused, the
+        # second block of either stage starts at its attention kernel
+        per_stage = {True: (3 + 2, 4 + 2), "mlp": (2 * 4, 2 * 5), False: (2 * 5, 2 * 7)}[fuse_mlp]
         assert sm.launch_counts()[0] == 2 + per_stage[0] + 2 + per_stage[1] + 3
 
 
