@@ -3,9 +3,9 @@
 Workload (benchmark configs[1]): Swin stage-3 chain, bf16, B=32, 14x14
 tokens, C=384, 12 heads, window 7, 6 blocks alternating shift 0/3, MLP ratio 4;
 seeded synthetic inputs resident in HBM before the timed region.  One step =
-one pass of the whole chain (14 kernels in elided mode: per block window attention and one kernel for
-proj + residual + LayerNorm + MLP + residual + the next block's LayerNorm and QKV, plus the first block's LayerNorm
-and QKV; the explicit chain runs 30 + 30 copies) over one batch.
+one pass of the whole chain (13 kernels in elided mode: per block window attention and one kernel for
+proj + residual + LayerNorm + MLP + residual + the next block's LayerNorm and QKV, plus the first block's LayerNorm +
+QKV kernel; the explicit chain runs 30 + 30 copies) over one batch.
 
 Prints ONE JSON line: whole-job throughput (images/s) of the elided chain, the
 explicit-transpose baseline chain timed the same way, per-kernel durations

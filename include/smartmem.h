@@ -301,9 +301,10 @@ typedef struct {
                                    sm_mlp_proj_supported accepts), SM_ELIDED also runs the output projection, its
                                    window-reverse store and the first residual inside that kernel.  SM_EXPLICIT cannot:
                                    its materialised reverse copy sits between the projection and the residual */
-  const void* qkv_packed;       /* nullable: sm_linear_pack(wqkv); used by sm_run_chain only (SM_ELIDED, inside a stage,
-                                   when the previous block runs the fused projection + MLP kernel): that kernel then also
-                                   computes this block's LayerNorm-1 and QKV Linear, and this block starts at attention */
+  const void* qkv_packed;       /* nullable: sm_linear_pack(wqkv); SM_ELIDED only.  LayerNorm-1 and the QKV Linear then
+                                   run as one packed-weight kernel; in sm_run_chain, inside a stage, when the previous
+                                   block runs the fused projection + MLP kernel, that kernel computes them instead and
+                                   this block starts at attention */
 } sm_swin_weights;
 size_t sm_swin_block_workspace_bytes(const sm_swin_cfg*, int mode);
 int sm_swin_block(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y,

@@ -289,6 +289,14 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
       // nothing: the QKV slot is filled
     } else if (pre == 1) {
       if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
+    } else if (wt->qkv_packed && lin32_supported(3 * C, C, dt)) {
+      // LayerNorm-1 + QKV as one packed-weight Linear: x's rows gathered in window-major order (roll included), the
+      // tile normalised in LDS, the weight streamed
+      Lin32Args a; std::memset(&a, 0, sizeof(a));
+      a.X = x; a.Wp = wt->qkv_packed; a.bias = wt->bqkv; a.Y = qkv; a.M = T; a.N = 3 * C; a.K = C; a.act = SM_ACT_NONE;
+      a.norm = 1; a.norm_eps = eps; a.norm_gamma = wt->ln1_g; a.norm_beta = wt->ln1_b;
+      a.x_rows = plan->x_gather; a.y_rows = identity_rows(3 * C);
+      if ((rc = lin32_checked(a, stream, "sm_swin_block(ln1+qkv)"))) return rc;
     } else if (fold_norm(3 * C)) {
       if ((rc = run_gemm(x, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, &plan->x_gather, nullptr, stream, wt->ln1_g, wt->ln1_b, eps))) return rc;
     } else {

@@ -482,7 +482,7 @@ int launch_mlp_fused(const MlpArgs& g, void* stream) {
 // barrier after the prologue.  Against the tiled kernel of k_gemm.hip this trades L2 -> CU traffic (W once per 32
 // rows) for the absence of K-loop barriers and of a separate norm kernel.  Measured (with LayerNorm, against norm
 // kernel + tiled kernel resp. the tiled kernel's own folded norm): 200704 x 384 x 128: 69 us against 89;
-// 50176 x 768 x 256: 55 against 71; 6272 x 1152 x 384: 26 against 26.  The block executors do not use it.
+// 50176 x 768 x 256: 55 against 71; 6272 x 1152 x 384: 23.7 against 26.
 // NW waves per workgroup: 4 (two workgroups per CU, X fragments in registers: large grids) or C / 32 (one workgroup
 // per CU with three waves per SIMD at C = 384, X fragments re-read from LDS: grids of about one workgroup per CU)
 template <int C, bool RES, int NW>

@@ -16,10 +16,12 @@ MODES = [sm.SM_ELIDED, sm.SM_EXPLICIT]
 
 def n_compute(C, mlp=4, fused=False, mode=None):
     """Compute kernels of a block: seven, minus a LayerNorm for each Linear narrow enough (N <= 512) to take it folded;
-    with the fused MLP kernel LayerNorm-2, FC1 and FC2 are one ("mlp"), and in elided mode the output projection
-    joins them (True)."""
+    with the fused MLP kernel LayerNorm-2, FC1 and FC2 are one ("mlp"); True: in elided mode the output projection
+    joins them and LayerNorm-1 + QKV are one packed-weight Linear."""
+    if fused is True and mode == sm.SM_ELIDED:
+        return 3          # LayerNorm-1 + QKV (packed-weight Linear), attention, projection + MLP
     if fused:
-        return 5 - (3 * C <= 512) - (fused is True and mode == sm.SM_ELIDED)
+        return 5 - (3 * C <= 512)
     return 7 - (3 * C <= 512) - (mlp * C <= 512)
 
 

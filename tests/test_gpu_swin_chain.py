@@ -44,8 +44,8 @@ def test_config2_stage3_chain_full_size(mode, fuse_mlp):
     assert rel_l2(got, want) <= 2e-2
     assert rel_l2(got - to_np(x), want - to_np(x)) <= 3e-2
     # per block: LayerNorm-2, FC1, FC2 become one kernel; elided, the output projection joins them
-    # and also computes the next block's LayerNorm-1 and QKV (one LayerNorm and one QKV kernel left, the first block's)
-    n = 42 if not fuse_mlp else (14 if fuse_mlp is True and mode == sm.SM_ELIDED else 30)
+    # and also computes the next block's LayerNorm-1 and QKV (the first block's run as one packed-weight Linear)
+    n = 42 if not fuse_mlp else (13 if fuse_mlp is True and mode == sm.SM_ELIDED else 30)
     assert sm.launch_counts() == ((n, 0) if mode == sm.SM_ELIDED else (n, 3 * 4 + 3 * 6))
 
 
@@ -82,9 +82,9 @@ def test_small_net_with_fused_kernel_widths(mode, fuse_mlp):
     f, fw, l, lw = small_net_case(torch.bfloat16, mode, embed=128, heads=(4, 8), fuse_mlp=fuse_mlp)
     assert rel_l2(f, fw) <= 2e-2 and rel_l2(l, lw) <= 2e-2
     if mode == sm.SM_ELIDED:
-        # embed 2 + stage 1 (LayerNorm-1 folded into QKV: 3C <= 512) + merge 2 + stage 2 + head 3; fully fused, the
-        # second block of either stage starts at its attention kernel
-        per_stage = {True: (3 + 2, 4 + 2), "mlp": (2 * 4, 2 * 5), False: (2 * 5, 2 * 7)}[fuse_mlp]
+        # embed 2 + stage 1 (LayerNorm-1 folded into QKV: 3C <= 512) + merge 2 + stage 2 + head 3; fully fused, a
+        # stage's first block is three kernels and its second starts at its attention kernel
+        per_stage = {True: (3 + 2, 3 + 2), "mlp": (2 * 4, 2 * 5), False: (2 * 5, 2 * 7)}[fuse_mlp]
         assert sm.launch_counts()[0] == 2 + per_stage[0] + 2 + per_stage[1] + 3
 
 
