@@ -32,7 +32,8 @@ MEASURED_TRAFFIC = {
     "proj+ln+mlp_bf16[6272,1536,384]+ln+qkv": int((18726.1 * 2.0 + 18816.1) * 1024),
     "proj+ln+mlp_bf16[6272,1536,384]": int((15194.2 * 2.0 + 4704.0) * 1024),
     "ln+mlp_bf16[6272,1536,384]": int((11666.8 * 2.0 + 4704.0) * 1024),
-    "gemm_bf16[6272,1152,384]": int((6443.5 * 2.0 + 14113.2) * 1024),
+    "ln+pgemm_bf16[6272,1152,384]": int((5892.6 * 2.0 + 14115.9) * 1024),
+    "gemm_bf16[6272,1152,384]": int((6443.5 * 2.0 + 14114.2) * 1024),
     "gemm_bf16[6272,384,384]+res": int((3784.5 * 2.0 + 4704.0) * 1024),
     "attention_window_bf16[128,12,49,49,32]": int((7137.5 * 2.0 + 4704.0) * 1024),
     "layernorm_bf16[6272,384]+scatter": int((2432.1 * 2.0 + 4704.0) * 1024),
