@@ -226,8 +226,8 @@ int sm_linear(const sm_linear_desc*, const void* A, const void* W, const void* b
  * sm_linear_pack rewrites W [N, K] into `packed` (device, N * K elements, 16-byte aligned, caller-owned) in the order
  * of the matrix-core operand fragments.  sm_linear with w_packed = 1 and that buffer as W then runs a kernel in which
  * a workgroup keeps 32 rows of A in LDS for all N outputs and the weight streams from L2 straight into registers: no
- * K-loop barriers, and a LayerNorm (norm = 1, beta required) costs one pass over the resident tile.  It pays where
- * M is small (one or two rounds of workgroups of the tiled kernel).  Restrictions with w_packed: activation none or
+ * K-loop barriers, and a LayerNorm (norm = 1, beta required) costs one pass over the resident tile.  It pays most with
+ * a folded LayerNorm and a short K against many rows (no norm kernel, no K-loop barriers).  Restrictions with w_packed: activation none or
  * GELU, no RoPE, no transposed store, row maps only (a map that splits columns returns SM_ERR_UNSUPPORTED). */
 int sm_linear_pack_supported(int N, int K, int dtype);
 int sm_linear_pack(const void* W, int N, int K, int dtype, void* packed, void* stream);
