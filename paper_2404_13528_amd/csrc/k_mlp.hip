@@ -499,12 +499,13 @@ __global__ __launch_bounds__(64 * NW, 1) void lin32_kernel(Lin32Args g) {
   const int nsub = g.N >> 5;
   const char* Wp = (const char*)g.Wp;
 
+  // weight fragments by buffer loads: descriptor and fragment offset scalar, the lane's 16 bytes the only vector operand
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wp), 0, 2 * g.N * C, 0x00020000);
+  const int lo = lane * 16;
+  (void)Wp;
   mlp_u32x4 w1[KK];
-  {
-    const char* wb = Wp + (size_t)((w < nsub ? w : 0) * KK) * 1024u;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) w1[kk] = *(const mlp_u32x4*)(wb + kk * 1024 + lane * 16u);
-  }
+  for (int kk = 0; kk < KK; ++kk) w1[kk] = __builtin_amdgcn_raw_buffer_load_b128(rw, lo, ((w < nsub ? w : 0) * KK + kk) * 1024, 0);
   mlp_load_x_tile<C, NTHR>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
   for (int s = tid; s < g.N / 8; s += NTHR) b_l[s] = g.bias ? ((const mlp_u32x4*)g.bias)[s] : mlp_u32x4{0u, 0u, 0u, 0u};
   __syncthreads();
@@ -542,12 +543,13 @@ __global__ __launch_bounds__(64 * NW, 1) void lin32_kernel(Lin32Args g) {
     mlp_f32x16 h;
 #pragma unroll
     for (int e = 0; e < 16; ++e) h[e] = 0.f;
-    const char* wb = Wp + (size_t)(nx * KK) * 1024u;      // scalar
+    mlp_u32x4 fb[3] = {x_l[xo], x_l[xo + 2], x_l[xo + 4]};      // (!XREG) LDS fragments three steps ahead of their MFMA
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      const mlp_u32x4 xv = XREG ? xf[XREG ? kk : 0] : x_l[xo + 2 * kk];
+      const mlp_u32x4 xv = XREG ? xf[XREG ? kk : 0] : fb[kk % 3];
       h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mlp_bf16x8, w1[kk]), __builtin_bit_cast(mlp_bf16x8, xv), h, 0, 0, 0);
-      w1[kk] = *(const mlp_u32x4*)(wb + kk * 1024 + lane * 16u);
+      w1[kk] = __builtin_amdgcn_raw_buffer_load_b128(rw, lo, (nx * KK + kk) * 1024, 0);
+      if (!XREG && kk + 3 < KK) fb[kk % 3] = x_l[xo + 2 * (kk + 3)];
     }
     __builtin_amdgcn_sched_group_barrier(0x100, XREG ? 2 : 5, 0);
 #pragma unroll
