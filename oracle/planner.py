@@ -1,310 +1,229 @@
-"""Layout planner: operator classification (Table 3), pairwise action and
-outcome tables (Tables 5, 6), elimination / fusion to a fixpoint (Sec. 3.2,
-"all preserved operators are ILD & Variable"), and reduction-dimension layout
-selection (Sec. 3.2.2, local rule + global rule with k directly indexable
-dimensions, redundant copies beyond k).
+"""Layout planner, written as the paper states it (TEST INFRASTRUCTURE ONLY).
 
-Graph: tensors = list of shapes; ops = list of dicts
-    {"kind": str, "in": [tensor ids], "out": tensor id, "attr": {...}}
-in topological order.  ILD & Variable ops carry attr["red"] = list with the
-reduction axis of each operand (None where an operand has none).
+Sec. 3.1: every operator is one of four groups (Table 3; definitions Table 4).
+Sec. 3.2: look at one producer -> consumer pair at a time, take its action from
+Table 5 (keep both / try fuse / eliminate 2nd / eliminate 1st / eliminate both),
+give the survivor the type of Table 6, and repeat over rounds until no pair
+changes; then "all preserved operators are ILD & Variable" (Sec. 3.2.2).
+Sec. 3.2.2: every stored tensor gets the layout its consumers' reduction
+dimensions ask for: the first k distinct ones innermost, one more copy for every
+further k (k = number of directly indexable memory dimensions).
 
-Readings where the paper is silent:
-  * Operators the paper does not list are classified by the Table 4
-    definitions (see GROUP_OF).
-  * A run of Fixed operators between two Variable operators can be absorbed
-    by either side (Table 5 offers both "Eliminate 2nd" and "Eliminate 1st").
-    Write side (the producer's store) is taken when every consumer of the
-    producer's tensor sees it through the same run and the run is a bijection
-    (no Slice / Gather); otherwise each consumer's load absorbs its own run.
-    This follows "sub-optimally writing beats sub-optimally reading".
-  * A Fixed run with no Variable operator on either side is materialised.
-  * k = 1 on linear memory; copies = ceil(distinct requested dims / k).
+Graph: tensors = list of shapes; ops = list of {"kind", "in": [tensor ids],
+"out": tensor id, "attr": {...}} in topological order; ILD & Variable operators
+carry attr["red"] = reduction axis per operand (None where an operand has none).
+
+READINGS: where the paper leaves a choice, it is written down here as data.
 """
 import math
+import numpy as np
+from . import views as V
 
 ILD_VAR, ILI_VAR, ILD_FIX, ILI_FIX = "ILD_VAR", "ILI_VAR", "ILD_FIX", "ILI_FIX"
-GROUPS = (ILD_VAR, ILI_VAR, ILD_FIX, ILI_FIX)
-
+GROUPS = (ILD_VAR, ILI_VAR, ILD_FIX, ILI_FIX)          # decreasing "optimization complexity" (Sec. 3.2)
 GROUP_OF = {
-    # Table 3
-    "CONV": ILD_VAR, "MATMUL": ILD_VAR, "LAYERNORM": ILD_VAR, "SOFTMAX": ILD_VAR,
+    "CONV": ILD_VAR, "MATMUL": ILD_VAR, "LAYERNORM": ILD_VAR, "SOFTMAX": ILD_VAR,      # Table 3
     "RESHAPE": ILD_FIX, "TRANSPOSE": ILD_FIX, "DTOS": ILD_FIX, "STOD": ILD_FIX,
-    "UNARY": ILI_VAR, "ADD": ILI_VAR,
-    "GATHER": ILI_FIX, "SLICE": ILI_FIX,
-    # classified by the Table 4 definitions (not listed in the paper)
+    "UNARY": ILI_VAR, "ADD": ILI_VAR, "GATHER": ILI_FIX, "SLICE": ILI_FIX,
+    # not listed in the paper; placed by the Table 4 definitions
     "GROUPNORM": ILD_VAR, "RMSNORM": ILD_VAR, "ATTENTION": ILD_VAR, "REDUCE": ILD_VAR,
-    "MUL": ILI_VAR, "BIAS": ILI_VAR, "ROPE": ILI_VAR,
-    "ROLL": ILI_FIX, "CONCAT": ILI_FIX,
+    "MUL": ILI_VAR, "BIAS": ILI_VAR, "ROPE": ILI_VAR, "ROLL": ILI_FIX, "CONCAT": ILI_FIX,
 }
-
-KEEP_BOTH, TRY_FUSE, ELIM_2ND, ELIM_1ST, ELIM_BOTH = (
-    "KEEP_BOTH", "TRY_FUSE", "ELIM_2ND", "ELIM_1ST", "ELIM_BOTH")
+KEEP_BOTH, TRY_FUSE, ELIM_2ND, ELIM_1ST, ELIM_BOTH = "KEEP_BOTH", "TRY_FUSE", "ELIM_2ND", "ELIM_1ST", "ELIM_BOTH"
 SEARCH_BOTH, SEARCH_FUSED, SEARCH_1ST, SEARCH_2ND, NO_SEARCH = (
     "SEARCH_BOTH", "SEARCH_FUSED", "SEARCH_1ST", "SEARCH_2ND", "NO_SEARCH")
+_V, _F = (ILD_VAR, ILI_VAR), (ILD_FIX, ILI_FIX)
+TABLE5 = {(a, b): (KEEP_BOTH if a == b == ILD_VAR else TRY_FUSE) if a in _V and b in _V else
+          ELIM_2ND if a in _V else ELIM_1ST if b in _V else ELIM_BOTH for a in GROUPS for b in GROUPS}
+TABLE6 = {}
+for (_a, _b), _act in TABLE5.items():
+    _kept = {KEEP_BOTH: ILD_VAR, TRY_FUSE: min(_a, _b, key=GROUPS.index), ELIM_2ND: _a, ELIM_1ST: _b, ELIM_BOTH: None}[_act]
+    _how = {KEEP_BOTH: SEARCH_BOTH, TRY_FUSE: SEARCH_FUSED, ELIM_2ND: SEARCH_1ST, ELIM_1ST: SEARCH_2ND, ELIM_BOTH: NO_SEARCH}[_act]
+    TABLE6[(_a, _b)] = (_kept, _how if _kept == ILD_VAR else NO_SEARCH)   # "layout search only happens for pairs involving ILD & Variable"
 
-
-def _is_var(g):
-    return g in (ILD_VAR, ILI_VAR)
+READINGS = {
+    # Table 5 ranks its actions "from low to high" opportunity; a round takes the highest one that applies.
+    "action_priority": (ELIM_BOTH, ELIM_2ND, ELIM_1ST, TRY_FUSE),
+    # Among pairs with the same action: consumers in graph order, the latest producer of a consumer first.
+    "pair_order": "consumer ascending, producer descending",
+    # "Eliminate 2nd" rewrites the first operator's store, and one stored tensor has one layout: it needs the
+    # Fixed operator to be the only reader of that tensor and to be invertible (a store map is the inverse of
+    # the run).  Otherwise Table 5's other cell applies: the run goes into the load of what follows it.
+    "store_side_needs": ("sole_consumer", "bijective"),
+    # A run that nothing reads (graph output) has no second operator: its Variable producer stores it as well.
+    "output_run": "store",
+    # Fusion legality is DNNFusion's and is not re-derived; required here: the merged node stays acyclic.
+    "fuse_needs": ("no_other_path",),
+    # A Fixed operator that never meets a Variable operator is run as a copy.
+    "orphan_run": "materialised",
+}
 
 
 def pair_action(first, second):
-    """Table 5."""
-    if _is_var(first) and _is_var(second):
-        return KEEP_BOTH if (first == ILD_VAR and second == ILD_VAR) else TRY_FUSE
-    if _is_var(first):
-        return ELIM_2ND
-    if _is_var(second):
-        return ELIM_1ST
-    return ELIM_BOTH
+    return TABLE5[(first, second)]
 
 
 def pair_outcome(first, second):
-    """Table 6: (resulting group or None for N/A, layout search policy)."""
-    a = pair_action(first, second)
-    if a == KEEP_BOTH:
-        return ILD_VAR, SEARCH_BOTH
-    if a == TRY_FUSE:
-        if ILD_VAR in (first, second):
-            return ILD_VAR, SEARCH_FUSED
-        return ILI_VAR, NO_SEARCH
-    if a == ELIM_2ND:                     # the first operator is preserved
-        return first, (SEARCH_1ST if first == ILD_VAR else NO_SEARCH)
-    if a == ELIM_1ST:                     # the second operator is preserved
-        return second, (SEARCH_2ND if second == ILD_VAR else NO_SEARCH)
-    return None, NO_SEARCH
+    return TABLE6[(first, second)]
 
 
 def _view_of(op, tensors):
-    k = op["kind"]
-    a = op.get("attr", {})
-    if k == "RESHAPE":
-        return ("reshape", tuple(tensors[op["out"]]))
-    if k == "TRANSPOSE":
-        return ("permute", tuple(a["perm"]))
-    if k == "ROLL":
-        return ("roll", a["axis"], a["shift"])
-    if k == "SLICE":
-        return ("slice", a["axis"], a["start"], a["stop"], a.get("step", 1))
-    return ("opaque", k)
+    k, a = op["kind"], op.get("attr", {})
+    return {"RESHAPE": lambda: ("reshape", tuple(tensors[op["out"]])), "TRANSPOSE": lambda: ("permute", tuple(a["perm"])),
+            "ROLL": lambda: ("roll", a["axis"], a["shift"]),
+            "SLICE": lambda: ("slice", a["axis"], a["start"], a["stop"], a.get("step", 1))}.get(k, lambda: ("opaque", k))()
 
 
-def _invert_chain(chain, src_shape):
-    """Chain that undoes `chain` (which starts from src_shape); None if not a bijection."""
-    shapes = [tuple(src_shape)]
+def _inverse(chain, src_shape):
+    """The chain that undoes `chain`; None unless every step is a bijection."""
+    inv, shape = [], tuple(src_shape)
     for v in chain:
-        s = shapes[-1]
         if v[0] == "reshape":
-            shapes.append(tuple(v[1]))
+            inv.insert(0, ("reshape", shape)); shape = tuple(v[1])
         elif v[0] == "permute":
-            shapes.append(tuple(s[p] for p in v[1]))
+            inv.insert(0, ("permute", tuple(int(i) for i in np.argsort(v[1])))); shape = tuple(shape[p] for p in v[1])
         elif v[0] == "roll":
-            shapes.append(s)
+            inv.insert(0, ("roll", v[1], -v[2]))
         else:
             return None
-    inv = []
-    for v, s_before in zip(reversed(chain), reversed(shapes[:-1])):
-        if v[0] == "reshape":
-            inv.append(("reshape", s_before))
-        elif v[0] == "permute":
-            p = v[1]
-            ip = [0] * len(p)
-            for k_, pk in enumerate(p):
-                ip[pk] = k_
-            inv.append(("permute", tuple(ip)))
-        else:
-            inv.append(("roll", v[1], -v[2]))
     return inv
 
 
 def plan(tensors, ops, k=1):
     n = len(ops)
     group = [GROUP_OF[o["kind"]] for o in ops]
-    producer = {o["out"]: i for i, o in enumerate(ops)}
-    consumers = {}
-    for i, o in enumerate(ops):
-        for slot, t in enumerate(o["in"]):
-            consumers.setdefault(t, []).append((i, slot))
-
-    status = [("kept",)] * n
+    assert all(len(o["in"]) == 1 for o, g in zip(ops, group) if g in _F), "Fixed operators with several inputs are not planned"
+    view = [_view_of(o, tensors) for o in ops]
+    alive = set(range(n))                       # operators not eliminated
+    node = list(range(n))                       # operator -> the operator its fused node is named after
+    ntype = list(group)                         # type of the node named i (Table 6 as nodes merge)
+    # per operand: [tensor read now, views pending on the load, the operators those views were]
+    ins = [[[t, [], []] for t in o["in"]] for o in ops]
+    # per operator: what it stores, as [tensor, views pending on the store, the operators those views were]
+    outs = [[[o["out"], [], []]] for o in ops]
     action = [None] * n
-    node_group = list(group)
 
-    # ---- step 1: Fixed-Fixed pairs ("Eliminate both"): runs of Fixed ops
-    # collapse into one pending view chain per consumer edge.
-    def run_back(t):
-        """Walk from tensor t back through Fixed ops; (stored tensor, chain, ops in run)."""
-        chain, run = [], []
-        while t in producer and not _is_var(group[producer[t]]):
-            i = producer[t]
-            chain.insert(0, _view_of(ops[i], tensors))
-            run.insert(0, i)
-            t = ops[i]["in"][0]
-        return t, chain, run
+    def producer(t):
+        return next((i for i in sorted(alive) for e in outs[i] if e[0] == t), None)
 
-    load_chain = {}     # (consumer op, slot) -> (stored tensor, chain, run)
-    for i, o in enumerate(ops):
-        if not _is_var(group[i]):
-            continue
-        for slot, t in enumerate(o["in"]):
-            src, chain, run = run_back(t)
-            if run:
-                load_chain[(i, slot)] = (src, chain, run)
-    out_runs = {}       # graph outputs reached through a Fixed run
-    for i, o in enumerate(ops):
-        if not _is_var(group[i]) and o["out"] not in consumers:
-            src, chain, run = run_back(o["out"])
-            out_runs[o["out"]] = (src, chain, run)
-    for i in range(n):
-        if _is_var(group[i]):
-            continue
-        t_in = ops[i]["in"][0]
-        prev_fixed = t_in in producer and not _is_var(group[producer[t_in]])
-        next_fixed = any(not _is_var(group[c]) for c, _ in consumers.get(ops[i]["out"], []))
-        if prev_fixed or next_fixed:
-            action[i] = ELIM_BOTH
+    def readers(t):
+        return [(c, s) for c in sorted(alive) for s, e in enumerate(ins[c]) if e[0] == t]
 
-    # ---- step 2: absorb each run into a Variable neighbour.
-    store_chain = {}    # producer op -> (chain, inverse chain, final tensor id, run)
-    by_src = {}
-    for key, (src, chain, run) in load_chain.items():
-        by_src.setdefault(src, []).append((key, chain, run))
-    for t_out, (src, chain, run) in out_runs.items():
-        by_src.setdefault(src, []).append((None, chain, run))
-    for src, uses in by_src.items():
-        direct = [c for c in consumers.get(src, []) if _is_var(group[c[0]])]
-        chains = {tuple(ch) for _, ch, _ in uses}
-        inv = _invert_chain(uses[0][1], tensors[src]) if src in producer else None
-        write_side = (src in producer and not direct and len(chains) == 1 and inv is not None)
-        if write_side:
-            p = producer[src]
-            final_t = ops[uses[0][2][-1]]["out"]
-            store_chain[p] = (uses[0][1], inv, final_t, uses[0][2])
-            for key, _, run in uses:
-                for f in run:
-                    status[f] = ("eliminated", p, "store")
-                    action[f] = action[f] or ELIM_2ND
-                if key is not None:
-                    del load_chain[key]
-        else:
-            for key, _, run in uses:
-                if key is None:
-                    for f in run:
-                        if src in producer:      # Variable producer, non-bijective run
-                            status[f] = ("eliminated", producer[src], "store")
-                            action[f] = action[f] or ELIM_2ND
-                        else:
-                            status[f] = ("materialised",)
-                    continue
-                for f in run:
-                    status[f] = ("eliminated", key[0], "load")
-                    action[f] = action[f] or ELIM_1ST
+    def pairs():                                # (first, second, operand slot) in READINGS["pair_order"]
+        ps = [(producer(e[0]), c, s) for c in sorted(alive) for s, e in enumerate(ins[c])]
+        return sorted((p for p in ps if p[0] is not None and node[p[0]] != node[p[1]]), key=lambda p: (p[1], -p[0], p[2]))
 
-    # ---- step 3: fuse ILI & Variable ops into a neighbour until none is left
-    # next to a Variable op ("Try fuse"); the merged node takes the Table 6 type.
-    root = list(range(n))
+    def other_path(a, b):                       # can node a reach node b through a third node?
+        nxt = lambda x: {node[c] for i in alive if node[i] == x for e in outs[i] for c, _ in readers(e[0])} - {x}
+        todo, seen = list(nxt(a) - {b}), set()
+        while todo:
+            x = todo.pop()
+            if x == b:
+                return True
+            if x not in seen:
+                seen.add(x); todo += list(nxt(x))
+        return False
 
-    def find(i):
-        while root[i] != i:
-            i = root[i]
-        return i
+    def applies(act, p, c, s):
+        if TABLE5[(ntype[node[p]], ntype[node[c]])] != act:
+            return False
+        if act == ELIM_2ND:
+            t = ins[c][0][0]
+            held = {"sole_consumer": len(readers(t)) == 1,
+                    "bijective": _inverse(ins[c][0][1] + [view[c]], tensors[t]) is not None}
+            output_run = READINGS["output_run"] == "store" and not readers(ops[c]["out"])
+            return output_run or all(held[r] for r in READINGS["store_side_needs"])
+        if act == TRY_FUSE:
+            return not other_path(node[p], node[c])
+        return True
 
-    def var_producers(i):
-        res = []
-        for slot, t in enumerate(ops[i]["in"]):
-            if (i, slot) in load_chain:
-                t = load_chain[(i, slot)][0]
-            elif t in producer and not _is_var(group[producer[t]]):
-                # reached through a run absorbed on the write side
-                t = run_back(t)[0]
-            if t in producer:
-                res.append(find(producer[t]))
-        return res
+    def apply(act, p, c, s):
+        if act in (ELIM_BOTH, ELIM_1ST):        # the first operator's view moves onto the second's load
+            e, f = ins[c][s], ins[p][0]
+            ins[c][s] = [f[0], f[1] + [view[p]] + e[1], f[2] + [p] + e[2]]
+            if not readers(ops[p]["out"]):
+                alive.discard(p)
+            for i in ((p, c) if act == ELIM_BOTH else (p,)):
+                action[i] = action[i] or act
+        elif act == ELIM_2ND:                   # the second operator's view moves onto the first's store
+            t, chain, run = ins[c][0]
+            e = next(e for e in outs[p] if e[0] == t)
+            new = [ops[c]["out"], e[1] + chain + [view[c]], e[2] + run + [c]]
+            if len(readers(t)) == 1:
+                outs[p][outs[p].index(e)] = new
+            else:
+                outs[p].append(new)             # an output run beside other readers: one more stored tensor
+            alive.discard(c)
+            action[c] = action[c] or act
+        else:                                   # fuse: the node of lower complexity joins the other (tie: the first stays)
+            a, b = node[p], node[c]
+            keep, lose = (a, b) if GROUPS.index(ntype[a]) <= GROUPS.index(ntype[b]) else (b, a)
+            ntype[keep] = TABLE6[(ntype[a], ntype[b])][0]
+            for i in range(n):
+                if node[i] == lose:
+                    node[i] = keep
+                    action[i] = action[i] or TRY_FUSE
 
     changed = True
-    while changed:
+    while changed:                              # rounds, until no pair changes
         changed = False
-        for i in range(n):
-            if group[i] != ILI_VAR or status[i][0] != "kept":
-                continue
-            prods = [q for q in var_producers(i) if q != i]
-            if prods:
-                tgt = max(prods)                     # the latest producer: epilogue fusion
-            else:
-                cons = [find(c) for c, _ in consumers.get(ops[i]["out"], []) if _is_var(group[c])]
-                cons = [q for q in cons if q != i]
-                if not cons:
-                    continue
-                tgt = min(cons)                      # prologue fusion
-            res, _ = pair_outcome(node_group[tgt], ILI_VAR)
-            status[i] = ("fused", tgt)
-            action[i] = TRY_FUSE
-            node_group[tgt] = res
-            root[i] = tgt
-            changed = True
+        for act in READINGS["action_priority"]:
+            hit = next((q for q in pairs() if applies(act, *q)), None)
+            if hit:
+                apply(act, *hit)
+                changed = True
+                break
 
-    for i in range(n):
-        if status[i][0] == "kept" and action[i] is None:
-            action[i] = KEEP_BOTH                     # a preserved operator is reported as kept
-        if status[i][0] == "eliminated":              # absorbed by the merged node's root
-            status[i] = ("eliminated", find(status[i][1]), status[i][2])
-    store_chain = {find(p_): v for p_, v in store_chain.items()}
-
-    # ---- step 4: reduction-dimension layout selection for every stored tensor.
-    from . import views as V
-    import numpy as np
-    layouts = {}
-    for t, shape in enumerate(tensors):
-        uses = []
-        if t in producer and status[producer[t]][0] == "eliminated" and \
-                t not in [sc[2] for sc in store_chain.values()]:
-            continue                                  # a view that is never stored
-        for (c, slot) in consumers.get(t, []):
-            if group[c] != ILD_VAR or (c, slot) in load_chain:
-                continue
-            red = ops[c].get("attr", {}).get("red", [None] * len(ops[c]["in"]))[slot]
-            if red is not None:
-                uses.append((c, slot, [], red))
-        for (c, slot), (src, chain, run) in load_chain.items():
-            if src == t and group[c] == ILD_VAR:
-                red = ops[c].get("attr", {}).get("red", [None] * len(ops[c]["in"]))[slot]
-                if red is not None:
-                    uses.append((c, slot, chain, red))
-        if not uses:
+    # ---- report
+    status = [None] * n
+    absorbers = [[] for _ in range(n)]
+    load_chain, store_chain = {}, {}
+    for i in sorted(alive):
+        if group[i] in _F:                      # READINGS["orphan_run"]: never met a Variable operator
+            for f in ins[i][0][2] + [i]:
+                absorbers[f].append(("materialised",))
             continue
-        requested = []           # (stride in t's natural storage, extent), in consumer order
-        for c, slot, chain, red in sorted(uses, key=lambda u: (u[0], u[1])):
-            m = V.index_map(shape, chain)
-            red = red % m.ndim
-            ext = m.shape[red]
-            if ext > 1:
-                a = np.take(m, 0, axis=red).reshape(-1)[0]
-                b = np.take(m, 1, axis=red).reshape(-1)[0]
-                stride = int(b - a)
-            else:
-                stride = 1
-            if (stride, ext) not in requested:
-                requested.append((stride, ext))
-        nat = [int(np.prod(shape[d + 1:])) for d in range(len(shape))]
+        status[i] = ("kept",) if node[i] == i else ("fused", node[i])
+        action[i] = action[i] or KEEP_BOTH
+        for s, (t, chain, run) in enumerate(ins[i]):
+            if run:
+                load_chain[(i, s)] = (t, chain, run)
+                for f in run:
+                    absorbers[f].append(("eliminated", node[i], "load"))
+        for t, chain, run in outs[i]:
+            if run:
+                first = ops[i]["out"]
+                store_chain.setdefault(node[i], (chain, _inverse(chain, tensors[first]), t, run))
+                for f in run:
+                    absorbers[f].append(("eliminated", node[i], "store"))
+    for f in range(n):
+        if status[f] is None:
+            status[f] = absorbers[f][-1]
 
-        def dim_of(stride):
-            for d in range(len(shape)):
-                if nat[d] <= stride < nat[d] * shape[d]:
-                    return d
-            return len(shape) - 1
-        red_dims = []
-        for stride, _ in requested:
-            d = dim_of(stride)
-            if d not in red_dims:
-                red_dims.append(d)
-        n_copies = max(1, math.ceil(len(red_dims) / k))
-        inner = red_dims[:k]
-        order = [d for d in range(len(shape)) if d not in inner] + list(reversed(inner))
-        layouts[t] = {"requested": requested, "red_dims": red_dims,
-                      "dim_order": order, "n_copies": n_copies}
-
-    return {"group": group, "status": status, "action": action,
-            "node_group": node_group, "load_chain": load_chain,
+    # ---- Sec. 3.2.2: reduction-dimension layout selection for every tensor an ILD & Variable operator reads
+    wanted = {}
+    for c in sorted(alive):
+        red = ops[c].get("attr", {}).get("red") or []
+        for s, axis in enumerate(red):
+            if group[c] != ILD_VAR or axis is None:
+                continue
+            t, chain, _ = ins[c][s]
+            if any(v[0] == "opaque" for v in chain):
+                continue                        # read through a Gather: no static index expression, nothing to ask for
+            m = V.index_map(tensors[t], chain)
+            line = np.moveaxis(m, axis % m.ndim, 0).reshape(m.shape[axis % m.ndim], -1)[:, 0]
+            coords = np.array(np.unravel_index(line, tensors[t]))           # stored coordinates along the reduction axis
+            moves = (np.diff(coords, axis=1) != 0).sum(axis=1)              # how often each stored dimension changes
+            d = int(len(moves) - 1 - np.argmax(moves[::-1])) if moves.any() else len(tensors[t]) - 1
+            if d not in wanted.setdefault(t, []):
+                wanted[t].append(d)
+    layouts = {}
+    for t, red_dims in wanted.items():
+        inner = red_dims[:k]                    # the first k requested dimensions are made directly indexable
+        layouts[t] = {"red_dims": red_dims, "n_copies": max(1, math.ceil(len(red_dims) / k)),
+                      "dim_order": [d for d in range(len(tensors[t])) if d not in inner] + inner[::-1]}
+    return {"group": group, "status": status, "action": action, "absorbers": absorbers,
+            "node_group": [ntype[i] for i in range(n)], "load_chain": load_chain,
             "store_chain": store_chain, "layouts": layouts}
 
 

@@ -243,3 +243,62 @@ def fig4_graph(D1=6, D2=4, D3=8):
     g.op("REDUCE", [t], (D2, D3), name="reduce_p", red=[0])
     g.op("CONV", [t], (D1, D2, 4), name="conv", red=[2])
     return g
+
+
+def random_graph(seed, max_ops=12):
+    """A seeded random operator DAG over all four operator groups (planner tests): small static shapes,
+    operators reading any earlier tensor, so producers with several consumers, runs of layout operators of
+    any length, element-wise operators with one or two Variable producers and graph outputs behind layout
+    runs all occur."""
+    import random
+    rnd = random.Random(seed)
+    g = Graph()
+    pool = [g.tensor(rnd.choice([(4, 6), (2, 3, 4), (6, 4), (2, 2, 6)])) for _ in range(rnd.randint(1, 2))]
+    kinds = ["MATMUL", "LAYERNORM", "REDUCE", "UNARY", "BIAS", "ADD", "MUL",
+             "RESHAPE", "TRANSPOSE", "ROLL", "SLICE", "RESHAPE", "TRANSPOSE", "GATHER"]
+    for _ in range(rnd.randint(2, max_ops)):
+        t = rnd.choice(pool[-4:]) if rnd.random() < 0.75 else rnd.choice(pool)
+        s = g.tensors[t]
+        kind = rnd.choice(kinds)
+        if kind in ("ADD", "MUL"):
+            same = [u for u in pool if u != t and g.tensors[u] == s]
+            if not same:
+                kind = "UNARY"
+            else:
+                pool.append(g.op(kind, [t, rnd.choice(same)], s))
+                continue
+        if kind == "MATMUL":
+            pool.append(g.op("MATMUL", [t], s[:-1] + (rnd.choice([s[-1], 2, 5]),), red=[len(s) - 1]))
+        elif kind == "LAYERNORM":
+            pool.append(g.op("LAYERNORM", [t], s, red=[len(s) - 1]))
+        elif kind == "REDUCE":
+            ax = rnd.randrange(len(s))
+            pool.append(g.op("REDUCE", [t], tuple(e if i != ax else 1 for i, e in enumerate(s)), red=[ax]))
+        elif kind in ("UNARY", "BIAS", "GATHER"):
+            pool.append(g.op(kind, [t], s))
+        elif kind == "RESHAPE":
+            n = 1
+            for e in s:
+                n *= e
+            shapes = [sh for sh in [(n,), (2, n // 2), (n // 2, 2), (n // 4, 2, 2), (2, 2, n // 4), (3, n // 3), (n // 6, 2, 3)]
+                      if all(isinstance(e, int) and e >= 1 for e in sh) and _prod(sh) == n]
+            pool.append(g.reshape(t, rnd.choice(shapes)))
+        elif kind == "TRANSPOSE":
+            perm = list(range(len(s)))
+            rnd.shuffle(perm)
+            pool.append(g.transpose(t, perm))
+        elif kind == "ROLL":
+            ax = rnd.randrange(len(s))
+            pool.append(g.roll(t, ax, rnd.randint(-s[ax], s[ax])))
+        else:
+            ax = rnd.randrange(len(s))
+            a = rnd.randrange(s[ax])
+            pool.append(g.slice(t, ax, a, rnd.randint(a + 1, s[ax])))
+    return g
+
+
+def _prod(sh):
+    n = 1
+    for e in sh:
+        n *= e
+    return n
