@@ -12,12 +12,20 @@
  *     No exception crosses this boundary.
  *   - "device pointer": memory of the current HIP device, owned by the caller,
  *     16-byte aligned.  "host pointer": ordinary process memory.
- *   - The library never allocates or frees device memory and never
- *     synchronises: all device work is enqueued on the hipStream_t passed as
- *     `void* stream` (NULL = the default stream).  Scratch memory comes from the
+ *   - No entry point allocates, frees or copies device memory, and none
+ *     synchronises: all device work is kernels enqueued on the hipStream_t passed
+ *     as `void* stream` (NULL = the default stream), so any call, a first call
+ *     included, may be captured into a HIP graph.  Scratch memory comes from the
  *     caller as `ws` / `ws_bytes`; the matching *_workspace_bytes() call gives
- *     the size needed.  An undersized workspace returns SM_ERR_WORKSPACE before
- *     anything is launched.
+ *     the size needed (activation buffers plus the per-row offset tables of the
+ *     call's index maps, which the executors fill with small kernels at the
+ *     start of every call; nothing in `ws` has to survive between calls).  An
+ *     undersized workspace returns SM_ERR_WORKSPACE before anything is launched.
+ *     The executors keep the plans of the configurations they have seen in a
+ *     bounded, mutex-guarded cache of host objects.  Two exceptions, both
+ *     diagnostics a caller switches on: sm_timing_enable() brackets launches
+ *     with HIP events and sm_timing_report() waits for them; sm_gemm_tuning()
+ *     sets a process-wide tile override for sweeps.
  *   - Opaque handles (sm_map, sm_plan) are host objects created and destroyed by
  *     the library.  Descriptor structs are plain data owned by the caller and
  *     copied during the call.
@@ -95,15 +103,20 @@ int sm_pair_outcome(int first_group, int second_group, int* result_group, int* s
 /* Plans a producer-consumer operator graph: classifies every operator
  * (Table 3), merges Fixed-Fixed pairs, absorbs every run of Fixed operators
  * into the store of the preceding Variable operator or the load of the
- * following one (Table 5; write side when every consumer sees the same
- * bijective run, Sec. 3.2.2), fuses ILI&Variable operators into a neighbour
- * until only ILD&Variable operators survive, then selects the layout of every
- * stored tensor from its consumers' reduction dimensions with k directly
- * indexable dimensions (k = 1 on linear HBM; k = 2 reproduces the 2.5D case).
- * Host only.  *out is owned by the library until sm_plan_destroy. */
+ * following one (Table 5; write side when the run is the only reader of the
+ * producer's tensor and is a bijection, Sec. 3.2.2; a run nothing reads is
+ * stored by its producer as one more output), fuses ILI&Variable operators
+ * pair by pair (consumers in graph order, latest producer first, never closing
+ * a cycle) until only ILD&Variable operators survive, then selects the layout
+ * of every stored tensor from its consumers' reduction dimensions with k
+ * directly indexable dimensions (k = 1 on linear HBM; k = 2 reproduces the 2.5D
+ * case).  Layout operators with several inputs (Concat) are not planned:
+ * SM_ERR_UNSUPPORTED.  Host only.  *out is owned by the library until
+ * sm_plan_destroy. */
 int sm_layout_plan(const sm_tensor_desc* tensors, int n_tensors, const sm_op_desc* ops, int n_ops,
                    int k, sm_plan** out);
-/* Per operator: group, the Table 5 action that decided it, its status (SM_KEPT..),
+/* Per operator: group, the Table 5 action that decided it (-1 for a layout
+ * operator that met no other operator), its status (SM_KEPT..),
  * the surviving operator that absorbed it (itself when kept, -1 when
  * materialised) and the group of the merged node (Table 6). Any out pointer
  * may be NULL. */
@@ -121,7 +134,9 @@ int sm_plan_load_map(const sm_plan*, int consumer_op, int operand, const sm_map*
 /* Map applied by surviving operator `producer_op` when it stores its result:
  * natural output index -> element offset in the tensor it stores
  * (*stored_tensor, the output of the last absorbed operator).  NULL when the
- * result is stored as computed. */
+ * result is stored as computed, or when the absorbed run is no bijection (a
+ * graph output behind a Slice: *stored_tensor still names it).  A node that
+ * stores several mapped tensors reports the first. */
 int sm_plan_store_map(const sm_plan*, int producer_op, const sm_map** borrowed, int* stored_tensor);
 void sm_plan_destroy(sm_plan*);
 
@@ -159,7 +174,9 @@ int sm_map_affine(const sm_map*, int64_t* base, int64_t* strides /* SM_MAX_RANK 
 int sm_map_describe(const sm_map*, char* buf, int n);
 void sm_map_destroy(sm_map*);
 
-/* dst[o] = src[map(o)] for every view element o; dst is contiguous with the
+/* The layout copy the paper removes (Sec. 2.2 "explicit" transformations;
+ * Table 1 column "Exp."), kept as the materialised form of a composed map:
+ * dst[o] = src[map(o)] for every view element o; dst is contiguous with the
  * view's shape.  on_device = 0: host pointers, executed on the host;
  * on_device = 1: device pointers, one HIP kernel on `stream`.  This is the
  * materialised form of an eliminated transformation (a test instrument and the
@@ -170,14 +187,19 @@ int sm_gather_mapped(const sm_map*, const void* src, void* dst, int dtype, int o
 /* Single operators with mapped operands (device pointers)                    */
 /* ------------------------------------------------------------------------ */
 
-/* y = LayerNorm(x) over the last dimension C of x [rows, C] (fp32 statistics,
+/* An ILD & Variable operator of Table 3 (LayerNorm) whose store takes a
+ * composed map ("Eliminate 2nd", Table 5; Sec. 3.2.1).
+ * y = LayerNorm(x) over the last dimension C of x [rows, C] (fp32 statistics,
  * biased variance).  rms != 0: RMSNorm (no mean subtraction, beta ignored).
  * store_map (nullable): a map with view shape [rows, C] (or any shape with
  * rows*C elements whose last dimension is C) giving the offset in y of each
  * natural output element; its last dimension must be contiguous. */
 int sm_norm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows, int C, float eps,
             int rms, int dtype, const sm_map* store_map, void* stream);
-/* GroupNorm over x NCHW [B, C, H, W] with G groups.  tokens_out = 0: y is NCHW;
+/* ILD & Variable by the definitions of Table 4 (the InstanceNorm example of
+ * Fig. 1(b) is the same family); its output layout follows its consumer's
+ * reduction dimension (Sec. 3.2.2).
+ * GroupNorm over x NCHW [B, C, H, W] with G groups.  tokens_out = 0: y is NCHW;
  * tokens_out = 1: y is written token-major [B, H*W, C] (the layout a following
  * MatMul over C prefers).  stats_scratch (nullable): device memory for 2 * B * G
  * floats; with it the work runs as two fully parallel kernels (statistics, then
@@ -262,7 +284,10 @@ int sm_mlp_pack(const void* W1, const void* W2, int C, int hidden, int dtype, vo
 int sm_mlp_fused(const sm_mlp_desc*, const void* X, const void* packed, const void* b1, const void* b2,
                  const void* residual, void* Y, const sm_map* x_map, const sm_map* y_map, void* stream);
 
-/* Fused attention O = softmax(scale * Q K^T + bias + mask) V per (batch, head).
+/* MatMul + Softmax + MatMul of Table 3 as one ILD & Variable operator whose loads
+ * and store take the head split / merge maps (Sec. 3.2.1; the paper keeps the
+ * three apart and names tiled attention as complementary, Sec. 6).
+ * Fused attention O = softmax(scale * Q K^T + bias + mask) V per (batch, head).
  * Q, K, V, O are 4-D strided views [nb, heads, n, d] (element strides, innermost
  * stride 1) so that head split / merge permutes are address arithmetic.
  * kind: SM_ATT_FULL, SM_ATT_CAUSAL (key j visible to query i iff j <= i), or
@@ -284,7 +309,12 @@ int sm_attention(const sm_attention_desc*, const void* q, const void* k, const v
 /* Block and chain executors                                                  */
 /* ------------------------------------------------------------------------ */
 
-/* One Swin block on x [B, H*W, C] -> y [B, H*W, C]:
+/* The Swin block of Table 7 executed as Sec. 3.2 plans it: the executor writes
+ * the block down as an operator graph, calls sm_layout_plan, and launches one
+ * kernel per surviving ILD & Variable operator with the planned load / store
+ * maps (SM_ELIDED), or the explicit chain the paper starts from (SM_EXPLICIT,
+ * Table 1 "Exp.").  ws: sm_swin_block_workspace_bytes(cfg, mode) bytes.
+ * One Swin block on x [B, H*W, C] -> y [B, H*W, C]:
  * LayerNorm -> (roll, window partition) -> QKV Linear -> window attention ->
  * proj Linear -> (reverse, roll back) -> +x -> LayerNorm -> MLP (GELU) -> +.
  * SM_ELIDED: 7 kernels (fewer where a norm is folded into the next Linear or the MLP is fused), the layout transformations are folded into their
@@ -310,11 +340,14 @@ size_t sm_swin_block_workspace_bytes(const sm_swin_cfg*, int mode);
 int sm_swin_block(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y,
                   void* ws, size_t ws_bytes, int mode, void* stream);
 
-/* Llama-style decoder layer (prefill) or diffusion-UNet spatial-transformer
+/* The global-attention blocks of Table 7 (a Pythia / Llama-style decoder layer,
+ * an SD-UNet spatial transformer) planned and executed the same way (Sec. 3.2):
+ * head split / merge permutes and the NCHW <-> token rearrangement become load /
+ * store maps of the attention and Linear kernels.
+ * Llama-style decoder layer (prefill) or diffusion-UNet spatial-transformer
  * block.  weights: array of device pointers in this order
- *   SM_ATTN_LLAMA (9): rms1_g, wqkv [3E, E] (rows q | k | v), wo, rms2_g,
+ *   SM_ATTN_LLAMA (6): rms1_g, wqkv [3E, E] (rows q | k | v), wo, rms2_g,
  *                      w_gate_up [2F, E] (rows gate | up), wdown [E, F]
- *                      -- 6 pointers: {rms1_g, wqkv, wo, rms2_g, w_gate_up, wdown}
  *   SM_ATTN_SD (23): gn_g, gn_b, win, bin, ln1_g, ln1_b, a1_wqkv [3C, C], a1_wo, a1_bo,
  *                    ln2_g, ln2_b, a2_wq, a2_wkv [2C, Dc], a2_wo, a2_bo, ln3_g, ln3_b,
  *                    ff_w1 [2F, C], ff_b1, ff_w2, ff_b2, wout, bout
@@ -330,7 +363,9 @@ size_t sm_attn_block_workspace_bytes(const sm_attn_cfg*, int mode);
 int sm_attn_block(const sm_attn_cfg*, const void* const* weights, const void* x, const void* context,
                   void* y, void* ws, size_t ws_bytes, int mode, void* stream);
 
-/* A Swin chain: optional patch embedding (NCHW image, patch x patch stride
+/* A whole producer-consumer chain (Sec. 3.2: elimination and fusion alternate
+ * over rounds, so removed layout operators leave compute operators adjacent):
+ * A Swin chain: optional patch embedding (NCHW image, patch x patch stride
  * patch unfold folded into the Linear's A addressing), stages of blocks
  * (block k of a stage shifts by window/2 when k is odd and the stage is larger
  * than one window), patch merging between stages (2x2 gather folded into the

@@ -177,7 +177,7 @@ def plan(tensors, ops, k=1):
     # ---- report
     status = [None] * n
     absorbers = [[] for _ in range(n)]
-    load_chain, store_chain = {}, {}
+    load_chain, store_chain, stores = {}, {}, {}
     for i in sorted(alive):
         if group[i] in _F:                      # READINGS["orphan_run"]: never met a Variable operator
             for f in ins[i][0][2] + [i]:
@@ -193,7 +193,9 @@ def plan(tensors, ops, k=1):
         for t, chain, run in outs[i]:
             if run:
                 first = ops[i]["out"]
-                store_chain.setdefault(node[i], (chain, _inverse(chain, tensors[first]), t, run))
+                entry = (chain, _inverse(chain, tensors[first]), t, run)
+                stores.setdefault(node[i], []).append(entry)     # every mapped store of the node
+                store_chain.setdefault(node[i], entry)           # the first of them
                 for f in run:
                     absorbers[f].append(("eliminated", node[i], "store"))
     for f in range(n):
@@ -224,7 +226,7 @@ def plan(tensors, ops, k=1):
                       "dim_order": [d for d in range(len(tensors[t])) if d not in inner] + inner[::-1]}
     return {"group": group, "status": status, "action": action, "absorbers": absorbers,
             "node_group": [ntype[i] for i in range(n)], "load_chain": load_chain,
-            "store_chain": store_chain, "layouts": layouts}
+            "store_chain": store_chain, "stores": stores, "layouts": layouts}
 
 
 def surviving(plan_result):

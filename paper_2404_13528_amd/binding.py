@@ -541,7 +541,7 @@ class Plan:
     def op(self, i):
         g, a, s, by, ng = C.c_int(), C.c_int(), C.c_int(), C.c_int(), C.c_int()
         check(lib().sm_plan_op(self.h, i, C.byref(g), C.byref(a), C.byref(s), C.byref(by), C.byref(ng)), "sm_plan_op")
-        return {"group": GROUPS[g.value], "action": ACTIONS[a.value], "status": STATUS[s.value],
+        return {"group": GROUPS[g.value], "action": ACTIONS[a.value] if a.value >= 0 else None, "status": STATUS[s.value],
                 "absorbed_by": by.value, "node_group": GROUPS[ng.value]}
 
     def tensor(self, t):

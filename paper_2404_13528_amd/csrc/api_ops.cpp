@@ -50,7 +50,7 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   if (gated && (g.N % 64)) return fail(SM_ERR_SHAPE, "%s: gated activations need N / 2 to be a multiple of 32", who);
   if (g.c_cols_on && (g.c_transposed || g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU)) return fail(SM_ERR_UNSUPPORTED, "%s: column-splitting store with a gated activation or transposed store", who);
   if (g.a_gran > 0 && (g.act != SM_ACT_NONE || g.rope_cols)) return fail(SM_ERR_UNSUPPORTED, "%s: activation or RoPE with an unfolded A operand", who);
-  if (gated && g.rope_cols) return fail(SM_ERR_UNSUPPORTED, "%s: RoPE with a gated activation", who);
+  if (g.act != SM_ACT_NONE && g.rope_cols) return fail(SM_ERR_UNSUPPORTED, "%s: RoPE goes with no activation (the RoPE epilogue applies none)", who);
   if (g.norm) {
     if (g.norm != 1 && g.norm != 2) return fail(SM_ERR_INVALID_ARG, "%s: unknown norm %d", who, g.norm);
     if (gated || g.rope_cols || g.a_gran > 0) return fail(SM_ERR_UNSUPPORTED, "%s: a folded norm goes with activation none or GELU only, without RoPE or an unfolded A", who);

@@ -31,6 +31,8 @@ struct AttnPlan {
   bool q2_scatter; int q2_gran; RowProg q2_rows, q2_cols;     // cross attention: q's Linear stores head-major when the planner says so
   Copy split_qkv, merge_o, to_tokens, split_q2, split_kv2, merge_o2, to_nchw;
   int n_kept, n_layout, n_eliminated;
+  TableRegion el_tables, ex_tables;     // row-offset tables of the elided maps / of the explicit copies
+  const TableRegion& tables(int mode) const { return mode == SM_EXPLICIT ? ex_tables : el_tables; }
 };
 
 struct Key { int v[12]; bool operator<(const Key& o) const { return std::memcmp(v, o.v, sizeof(v)) < 0; } };
@@ -180,7 +182,8 @@ std::shared_ptr<AttnPlan> attn_plan(const sm_attn_cfg& c, std::string* err) {
         p->q2_gran = 1;
         if (!qm->compile_rows_cols(1, &p->q2_rows, &p->q2_cols, err)) return nullptr;
       }
-      if (!attach_row_table(&p->q2_rows, (int64_t)B * S, err) || !attach_row_table(&p->q2_cols, E / p->q2_gran, err)) return nullptr;
+      p->el_tables.add(&p->q2_rows, (int64_t)B * S, (int64_t)B * S * E);
+      p->el_tables.add(&p->q2_cols, E / p->q2_gran, (int64_t)B * S * E);
       p->q2_scatter = true;
     }
     // GroupNorm must have been told to store token-major (its consumer reduces over C), proj_out to store NCHW
@@ -192,16 +195,17 @@ std::shared_ptr<AttnPlan> attn_plan(const sm_attn_cfg& c, std::string* err) {
   }
   // explicit mode: copies
   std::vector<sm_view_op> qkv_split{chains::reshape({B, S, 3, h, d}), chains::permute({2, 0, 3, 1, 4})};
-  if (!make_copy({B, S, 3 * E}, qkv_split, es, &p->split_qkv, err)) return nullptr;
-  if (!make_copy({B, h, S, d}, chains::head_merge(B, S, h, d), es, &p->merge_o, err)) return nullptr;
+  if (!make_copy({B, S, 3 * E}, qkv_split, es, &p->ex_tables, &p->split_qkv, err)) return nullptr;
+  if (!make_copy({B, h, S, d}, chains::head_merge(B, S, h, d), es, &p->ex_tables, &p->merge_o, err)) return nullptr;
   if (c.kind == SM_ATTN_SD) {
-    if (!make_copy({B, E, S}, {chains::permute({0, 2, 1})}, es, &p->to_tokens, err)) return nullptr;
-    if (!make_copy({B, S, E}, {chains::permute({0, 2, 1})}, es, &p->to_nchw, err)) return nullptr;
-    if (!make_copy({B, S, E}, chains::head_split(B, S, h, d), es, &p->split_q2, err)) return nullptr;
+    if (!make_copy({B, E, S}, {chains::permute({0, 2, 1})}, es, &p->ex_tables, &p->to_tokens, err)) return nullptr;
+    if (!make_copy({B, S, E}, {chains::permute({0, 2, 1})}, es, &p->ex_tables, &p->to_nchw, err)) return nullptr;
+    if (!make_copy({B, S, E}, chains::head_split(B, S, h, d), es, &p->ex_tables, &p->split_q2, err)) return nullptr;
     std::vector<sm_view_op> kv_split{chains::reshape({B, c.Sc, 2, h, d}), chains::permute({2, 0, 3, 1, 4})};
-    if (!make_copy({B, c.Sc, 2 * E}, kv_split, es, &p->split_kv2, err)) return nullptr;
+    if (!make_copy({B, c.Sc, 2 * E}, kv_split, es, &p->ex_tables, &p->split_kv2, err)) return nullptr;
     p->merge_o2 = p->merge_o;
   }
+  if (g_plans.size() >= 64) g_plans.clear();      // host objects only; entries in use stay alive through their shared_ptr
   g_plans[key] = p;
   return p;
 }
@@ -273,7 +277,11 @@ View4 contiguous_view(int64_t h, int64_t S, int64_t d, int64_t base = 0) { View4
 
 extern "C" size_t sm_attn_block_workspace_bytes(const sm_attn_cfg* c, int mode) {
   if (check_cfg(c, "sm_attn_block_workspace_bytes") != SM_OK) return 0;
-  return sizes(c, mode).total;
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) { set_error("sm_attn_block_workspace_bytes: unknown mode %d", mode); return 0; }
+  std::string err;
+  auto plan = attn_plan(*c, &err);
+  if (!plan) { set_error("sm_attn_block_workspace_bytes: %s", err.c_str()); return 0; }
+  return sizes(c, mode).total + plan->tables(mode).bytes;
 }
 
 extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const void* x, const void* context,
@@ -286,12 +294,16 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
   const int nw = c->kind == SM_ATTN_LLAMA ? 6 : 23;
   for (int i = 0; i < nw; ++i) if (!w[i] || !aligned16(w[i])) return fail(SM_ERR_INVALID_ARG, "sm_attn_block: weight %d is null or misaligned", i);
   const Sizes z = sizes(c, mode);
-  if (ws_bytes < z.total) return fail(SM_ERR_WORKSPACE, "sm_attn_block: workspace of %zu bytes, %zu needed", ws_bytes, z.total);
   if (!aligned16(x) || !aligned16(y) || !aligned16(ws) || (context && !aligned16(context))) return fail(SM_ERR_INVALID_ARG, "sm_attn_block: pointers must be 16-byte aligned");
   std::string err;
   auto plan = attn_plan(*c, &err);
   if (!plan) return fail(SM_ERR_UNSUPPORTED, "sm_attn_block: %s", err.c_str());
+  const size_t need = z.total + plan->tables(mode).bytes;
+  if (ws_bytes < need) return fail(SM_ERR_WORKSPACE, "sm_attn_block: workspace of %zu bytes, %zu needed", ws_bytes, need);
   count_reset();
+  // the row-offset tables of this call's maps, behind the activation buffers, before the first kernel
+  const void* tables = (char*)ws + z.total;
+  if ((rc = fill_tables(plan->tables(mode), (char*)ws + z.total, stream, ~0ull))) return rc;
   const int dt = c->dtype, B = c->B, S = c->S, E = c->E, h = c->heads, d = E / h, F = c->F;
   const int64_t T = (int64_t)B * S;
   char* base = (char*)ws;
@@ -310,10 +322,10 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
     if (el) {
       if ((rc = attention(SM_ATT_CAUSAL, dt, B, h, S, S, d, plan->q1, plan->k1, plan->v1, plan->o1, qkv, qkv, qkv, o, stream))) return rc;
     } else {
-      if ((rc = copy_launch(plan->split_qkv, qkv, qkvp, dt, stream))) return rc;
+      if ((rc = copy_launch(plan->split_qkv, tables, qkv, qkvp, dt, stream))) return rc;
       const View4 cq = contiguous_view(h, S, d, 0), ck = contiguous_view(h, S, d, T * E), cv = contiguous_view(h, S, d, 2 * T * E);
       if ((rc = attention(SM_ATT_CAUSAL, dt, B, h, S, S, d, cq, ck, cv, cq, qkvp, qkvp, qkvp, op, stream))) return rc;
-      if ((rc = copy_launch(plan->merge_o, op, o, dt, stream))) return rc;
+      if ((rc = copy_launch(plan->merge_o, tables, op, o, dt, stream))) return rc;
     }
     if ((rc = gemm(o, w[2], nullptr, x, r1, T, E, E, dt, SM_ACT_NONE, stream))) return rc;
     if ((rc = norm(r1, w[3], nullptr, n, T, E, c->eps_norm, 1, dt, stream))) return rc;
@@ -331,17 +343,17 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
     if (lrc) return fail(SM_ERR_DEVICE, "sm_attn_block: GroupNorm launch failed (hip error %d)", lrc);
   }
   count_compute(groupnorm_launches(ga));
-  if (!el) { if ((rc = copy_launch(plan->to_tokens, extra, o, dt, stream))) return rc; }
+  if (!el) { if ((rc = copy_launch(plan->to_tokens, tables, extra, o, dt, stream))) return rc; }
   if ((rc = gemm(o, w[2], w[3], nullptr, r1, T, E, E, dt, SM_ACT_NONE, stream))) return rc;                     // proj_in -> t0
   if ((rc = norm(r1, w[4], w[5], n, T, E, c->eps_norm, 0, dt, stream))) return rc;
   if ((rc = gemm(n, w[6], nullptr, nullptr, qkv, T, 3 * E, E, dt, SM_ACT_NONE, stream))) return rc;
   if (el) {
     if ((rc = attention(SM_ATT_FULL, dt, B, h, S, S, d, plan->q1, plan->k1, plan->v1, plan->o1, qkv, qkv, qkv, o, stream))) return rc;
   } else {
-    if ((rc = copy_launch(plan->split_qkv, qkv, qkvp, dt, stream))) return rc;
+    if ((rc = copy_launch(plan->split_qkv, tables, qkv, qkvp, dt, stream))) return rc;
     const View4 cq = contiguous_view(h, S, d, 0), ck = contiguous_view(h, S, d, T * E), cv = contiguous_view(h, S, d, 2 * T * E);
     if ((rc = attention(SM_ATT_FULL, dt, B, h, S, S, d, cq, ck, cv, cq, qkvp, qkvp, qkvp, op, stream))) return rc;
-    if ((rc = copy_launch(plan->merge_o, op, o, dt, stream))) return rc;
+    if ((rc = copy_launch(plan->merge_o, tables, op, o, dt, stream))) return rc;
   }
   if ((rc = gemm(o, w[7], w[8], r1, r2, T, E, E, dt, SM_ACT_NONE, stream))) return rc;                          // t1
   if ((rc = norm(r2, w[9], w[10], n, T, E, c->eps_norm, 0, dt, stream))) return rc;
@@ -349,18 +361,18 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
     GemmArgs gq; std::memset(&gq, 0, sizeof(gq));
     gq.A = n; gq.W = w[11]; gq.C = qkv; gq.M = T; gq.N = E; gq.K = E; gq.dtype = dt; gq.ldw = E;
     gq.a_rows = identity_rows(E); gq.c_rows = identity_rows(E);
-    if (el && plan->q2_scatter) { gq.c_rows = plan->q2_rows; gq.c_cols = plan->q2_cols; gq.c_cols_on = 1; gq.c_gran = plan->q2_gran; }
+    if (el && plan->q2_scatter) { gq.c_rows = bound(plan->q2_rows, tables); gq.c_cols = bound(plan->q2_cols, tables); gq.c_cols_on = 1; gq.c_gran = plan->q2_gran; }
     if ((rc = gemm_checked(gq, stream, "linear"))) return rc;
   }
   if ((rc = gemm(context, w[12], nullptr, nullptr, kv, (int64_t)B * Sc, 2 * E, c->Dc, dt, SM_ACT_NONE, stream))) return rc;
   if (el) {
     if ((rc = attention(SM_ATT_FULL, dt, B, h, S, Sc, d, plan->q2, plan->k2, plan->v2, plan->o2, qkv, kv, kv, o, stream))) return rc;
   } else {
-    if ((rc = copy_launch(plan->split_q2, qkv, qkvp, dt, stream))) return rc;
-    if ((rc = copy_launch(plan->split_kv2, kv, kvp, dt, stream))) return rc;
+    if ((rc = copy_launch(plan->split_q2, tables, qkv, qkvp, dt, stream))) return rc;
+    if ((rc = copy_launch(plan->split_kv2, tables, kv, kvp, dt, stream))) return rc;
     const View4 cq = contiguous_view(h, S, d, 0), ck = contiguous_view(h, Sc, d, 0), cv = contiguous_view(h, Sc, d, (int64_t)B * Sc * E);
     if ((rc = attention(SM_ATT_FULL, dt, B, h, S, Sc, d, cq, ck, cv, cq, qkvp, kvp, kvp, op, stream))) return rc;
-    if ((rc = copy_launch(plan->merge_o2, op, o, dt, stream))) return rc;
+    if ((rc = copy_launch(plan->merge_o2, tables, op, o, dt, stream))) return rc;
   }
   if ((rc = gemm(o, w[13], w[14], r2, r3, T, E, E, dt, SM_ACT_NONE, stream))) return rc;                        // t2
   if ((rc = norm(r3, w[15], w[16], n, T, E, c->eps_norm, 0, dt, stream))) return rc;
@@ -370,7 +382,7 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
     if ((rc = gemm(r1, w[21], w[22], x, y, T, E, E, dt, SM_ACT_NONE, stream, 0, 0, 0, 0.f, S))) return rc;       // NCHW store + x
   } else {
     if ((rc = gemm(r1, w[21], w[22], nullptr, o, T, E, E, dt, SM_ACT_NONE, stream))) return rc;
-    if ((rc = copy_launch(plan->to_nchw, o, y, dt, stream, x))) return rc;
+    if ((rc = copy_launch(plan->to_nchw, tables, o, y, dt, stream, x))) return rc;
   }
   return SM_OK;
 }

@@ -3,8 +3,10 @@
 // Each executor asks the composer for the maps of the layout transformations
 // in its operator chain and hands them to the kernels (elided mode), or runs
 // one copy kernel per transformation that moves data (explicit mode: Reshape
-// is metadata only on linear memory, paper Sec. 2.3).  Plans are cached per
-// configuration; the cache is guarded by a mutex.
+// is metadata only on linear memory, paper Sec. 2.3).  Plans are host memory
+// only and are cached per configuration (a bounded cache behind a mutex); the
+// per-row offset tables of their maps live in the caller's workspace and are
+// filled on the caller's stream at the start of every call.
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -35,6 +37,8 @@ struct SwinPlan {
   bool has_roll;
   Copy roll, partition, head_split, head_merge, reverse, unroll;
   int n_layout_ops, n_eliminated;
+  TableRegion el_tables, ex_tables;   // row-offset tables of the elided maps / of the explicit copies
+  const TableRegion& tables(int mode) const { return mode == SM_EXPLICIT ? ex_tables : el_tables; }
 };
 
 struct Key {
@@ -44,12 +48,18 @@ struct Key {
 
 std::mutex g_mu;
 std::map<Key, std::shared_ptr<SwinPlan>> g_swin;
+// plans are small host objects; a cache that has seen many configurations starts over (entries in use stay alive
+// through their shared_ptr)
+constexpr size_t kMaxCachedPlans = 64;
+template <typename M> void bound_cache(M& m) { if (m.size() >= kMaxCachedPlans) m.clear(); }
 
-bool make_rows(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, RowProg* out, std::string* err) {
+int64_t numel_of(const std::vector<int64_t>& s) { int64_t n = 1; for (auto e : s) n *= e; return n; }
+
+bool make_rows(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, TableRegion* tables, RowProg* out, std::string* err) {
   sm_map* m = nullptr;
   if (map_create(src, chain.data(), (int)chain.size(), &m, err) != SM_OK) return false;
-  bool ok = m->compile_rows(out, err);
-  ok = ok && attach_row_table(out, m->numel() / m->shape.back(), err);
+  const bool ok = m->compile_rows(out, err);
+  if (ok) tables->add(out, m->numel() / m->shape.back(), numel_of(src));
   delete m;
   return ok;
 }
@@ -108,10 +118,10 @@ std::shared_ptr<SwinPlan> swin_plan(const sm_swin_cfg& c, std::string* err) {
     const sm_map* m = nullptr;
     sm_plan_store_map(plan, g.find("ln1"), &m, nullptr);
     if (!m || !m->compile_rows(&p->ln1_store, err)) { if (!m) *err = "no store map planned for LayerNorm"; return nullptr; }
-    if (!attach_row_table(&p->ln1_store, B * H * W, err)) return nullptr;
+    p->el_tables.add(&p->ln1_store, B * H * W, B * H * W * C);
     sm_plan_store_map(plan, g.find("proj"), &m, nullptr);
     if (!m || !m->compile_rows(&p->proj_store, err)) { if (!m) *err = "no store map planned for proj"; return nullptr; }
-    if (!attach_row_table(&p->proj_store, B_ * N, err)) return nullptr;
+    p->el_tables.add(&p->proj_store, B_ * N, B * H * W * C);
     const int attn = g.find("attn");
     int64_t st8[SM_MAX_RANK];
     for (int k = 0; k < 3; ++k) {
@@ -124,17 +134,18 @@ std::shared_ptr<SwinPlan> swin_plan(const sm_swin_cfg& c, std::string* err) {
     if (!m || !m->affine(&obase, st8) || st8[3] != 1 || obase != 0) { *err = "attention output is not a strided view"; return nullptr; }
     for (int j = 0; j < 3; ++j) p->o_stride[j] = st8[j];
   }
-  if (!make_rows({B, H, W, C}, chains::window_partition(B, H, W, C, w, s), &p->x_gather, err)) return nullptr;
+  if (!make_rows({B, H, W, C}, chains::window_partition(B, H, W, C, w, s), &p->el_tables, &p->x_gather, err)) return nullptr;
   // explicit: one copy per transformation that moves data
   p->has_roll = s != 0;
   if (s) {
-    if (!make_copy({B, H, W, C}, chains::roll2(-s), es, &p->roll, err)) return nullptr;
-    if (!make_copy({B, H, W, C}, chains::roll2(s), es, &p->unroll, err)) return nullptr;
+    if (!make_copy({B, H, W, C}, chains::roll2(-s), es, &p->ex_tables, &p->roll, err)) return nullptr;
+    if (!make_copy({B, H, W, C}, chains::roll2(s), es, &p->ex_tables, &p->unroll, err)) return nullptr;
   }
-  if (!make_copy({B, H, W, C}, chains::window_partition(B, H, W, C, w, 0), es, &p->partition, err)) return nullptr;
-  if (!make_copy({B_, N, C}, chains::window_reverse(B, H, W, C, w, 0), es, &p->reverse, err)) return nullptr;
-  if (!make_copy({B_, N, 3 * C}, chains::qkv_split(B_, N, h, d), es, &p->head_split, err)) return nullptr;
-  if (!make_copy({B_, h, N, d}, chains::head_merge(B_, N, h, d), es, &p->head_merge, err)) return nullptr;
+  if (!make_copy({B, H, W, C}, chains::window_partition(B, H, W, C, w, 0), es, &p->ex_tables, &p->partition, err)) return nullptr;
+  if (!make_copy({B_, N, C}, chains::window_reverse(B, H, W, C, w, 0), es, &p->ex_tables, &p->reverse, err)) return nullptr;
+  if (!make_copy({B_, N, 3 * C}, chains::qkv_split(B_, N, h, d), es, &p->ex_tables, &p->head_split, err)) return nullptr;
+  if (!make_copy({B_, h, N, d}, chains::head_merge(B_, N, h, d), es, &p->ex_tables, &p->head_merge, err)) return nullptr;
+  bound_cache(g_swin);
   g_swin[key] = p;
   return p;
 }
@@ -194,8 +205,9 @@ bool proj_is_fused(const sm_swin_cfg& c, const sm_swin_weights* wt) {
 // Where the row at window-major position r of a block with shift c.shift goes in the window-major tensor of a block
 // with shift next_shift: the composed map reverse(next) then partition(this), read as a store (Sec. 3.2.1: two runs of
 // layout operators between two surviving operators collapse into one index expression)
-std::map<Key, std::shared_ptr<RowProg>> g_next_store;
-std::shared_ptr<RowProg> next_norm_store(const sm_swin_cfg& c, int next_shift, std::string* err) {
+struct NextStore { RowProg rows; TableRegion tables; };
+std::map<Key, std::shared_ptr<NextStore>> g_next_store;
+std::shared_ptr<NextStore> next_norm_store(const sm_swin_cfg& c, int next_shift, std::string* err) {
   Key key{{c.B, c.H, c.W, c.C, c.window, c.shift, next_shift, c.dtype}};
   std::lock_guard<std::mutex> lock(g_mu);
   auto it = g_next_store.find(key);
@@ -203,14 +215,25 @@ std::shared_ptr<RowProg> next_norm_store(const sm_swin_cfg& c, int next_shift, s
   const int64_t B = c.B, H = c.H, W = c.W, C = c.C, w = c.window;
   std::vector<sm_view_op> ch = chains::window_reverse(B, H, W, C, w, next_shift);
   for (auto& op : chains::window_partition(B, H, W, C, w, c.shift)) ch.push_back(op);
-  auto p = std::make_shared<RowProg>();
-  if (!make_rows({B * (H / w) * (W / w), w * w, C}, ch, p.get(), err)) return nullptr;      // (attaches the row table)
+  auto p = std::make_shared<NextStore>();
+  if (!make_rows({B * (H / w) * (W / w), w * w, C}, ch, &p->tables, &p->rows, err)) return nullptr;
+  bound_cache(g_next_store);
   g_next_store[key] = p;
   return p;
 }
 
 // LayerNorm-1 of the block that follows in a chain, emitted by this block's last kernel as a second output (window-major,
 // i.e. through the following block's own partition map) into the workspace slot that block reads its QKV input from
+// which of a plan's elided tables (el_tables items, in the order swin_plan adds them: LayerNorm-1 store, projection
+// store, x gather) the block's kernels read: the projection's always, one of the other two unless the block's QKV
+// input was produced by the block before it (pre)
+enum { TBL_LN1_STORE = 1, TBL_PROJ_STORE = 2, TBL_X_GATHER = 4 };
+uint64_t el_tables_needed(const sm_swin_cfg& c, const sm_swin_weights* wt, int pre) {
+  uint64_t need = TBL_PROJ_STORE;
+  if (pre == 0) need |= ((wt->qkv_packed && lin32_supported(3 * c.C, c.C, c.dtype)) || fold_norm(3 * c.C)) ? TBL_X_GATHER : TBL_LN1_STORE;
+  return need;
+}
+
 struct NextNorm { const void* gamma; const void* beta; RowProg store; const void* wq_p; const void* bq; };   // wq_p: ... and its QKV Linear
 int run_proj_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* attn_out, const void* x, void* y, int64_t T,
                        const RowProg& store, const NextNorm* next, void* next_out, void* stream) {      // next_out: norm or QKV slot
@@ -237,40 +260,57 @@ int run_mlp_fused(const sm_swin_cfg& c, const sm_swin_weights* wt, const void* x
 
 }  // namespace
 
-extern "C" size_t sm_swin_block_workspace_bytes(const sm_swin_cfg* c, int mode) {
-  if (check_swin(c, "sm_swin_block_workspace_bytes") != SM_OK) return 0;
+namespace {
+// activation buffers of one block (without its row-offset tables)
+size_t swin_act_bytes(const sm_swin_cfg* c, int mode) {
   const size_t tc = align256((size_t)c->B * c->H * c->W * c->C * dtype_size(c->dtype));
   const size_t units = mode == SM_EXPLICIT ? 4 + 3 + 3 + 1 + c->mlp_ratio : 1 + 3 + 1 + 1 + c->mlp_ratio;
   return tc * units;
 }
-
-namespace {
 int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y, void* ws, size_t ws_bytes, int mode,
-                    void* stream, const NextNorm* next, int pre);
+                    void* stream, const NextNorm* next, int pre, const void* tables);
+}
+
+extern "C" size_t sm_swin_block_workspace_bytes(const sm_swin_cfg* c, int mode) {
+  if (check_swin(c, "sm_swin_block_workspace_bytes") != SM_OK) return 0;
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) { set_error("sm_swin_block_workspace_bytes: unknown mode %d", mode); return 0; }
+  std::string err;
+  auto plan = swin_plan(*c, &err);
+  if (!plan) { set_error("sm_swin_block_workspace_bytes: %s", err.c_str()); return 0; }
+  return swin_act_bytes(c, mode) + plan->tables(mode).bytes;
 }
 
 extern "C" int sm_swin_block(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y,
                              void* ws, size_t ws_bytes, int mode, void* stream) {
-  return swin_block_impl(c, wt, x, y, ws, ws_bytes, mode, stream, nullptr, 0);
+  return swin_block_impl(c, wt, x, y, ws, ws_bytes, mode, stream, nullptr, 0, nullptr);
 }
 
 namespace {
 // next (elided mode, projection + MLP fused only): also emit the following block's LayerNorm-1 into this workspace's
 // first slot, or (next->wq_p) its QKV Linear's output into the QKV slot; pre = 1: the first slot already holds this
-// block's LayerNorm-1 output, pre = 2: the QKV slot already holds this block's QKV (the previous block emitted it)
+// block's LayerNorm-1 output, pre = 2: the QKV slot already holds this block's QKV (the previous block emitted it).
+// tables: where the plan's row-offset tables for `mode` were already filled on this stream (the chain executor fills
+// them once per stage and shift); null: they go behind the activation buffers of ws and are filled here
 int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void* x, void* y, void* ws, size_t ws_bytes, int mode,
-                    void* stream, const NextNorm* next, int pre) {
+                    void* stream, const NextNorm* next, int pre, const void* tables) {
   int rc = check_swin(c, "sm_swin_block");
   if (rc) return rc;
   if (!wt || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: null pointer");
   if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: unknown mode %d", mode);
-  if (ws_bytes < sm_swin_block_workspace_bytes(c, mode))
-    return fail(SM_ERR_WORKSPACE, "sm_swin_block: workspace of %zu bytes, %zu needed", ws_bytes, sm_swin_block_workspace_bytes(c, mode));
   if (!aligned16(x) || !aligned16(y) || !aligned16(ws)) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: pointers must be 16-byte aligned");
   std::string err;
   auto plan = swin_plan(*c, &err);
   if (!plan) return fail(SM_ERR_UNSUPPORTED, "sm_swin_block: %s", err.c_str());
+  const size_t need = swin_act_bytes(c, mode) + (tables ? 0 : plan->tables(mode).bytes);
+  if (ws_bytes < need) return fail(SM_ERR_WORKSPACE, "sm_swin_block: workspace of %zu bytes, %zu needed", ws_bytes, need);
   count_reset();
+  if (!tables) {
+    void* region = (char*)ws + swin_act_bytes(c, mode);
+    if ((rc = fill_tables(plan->tables(mode), region, stream, mode == SM_ELIDED ? el_tables_needed(*c, wt, pre) : ~0ull))) return rc;
+    tables = region;
+  }
+  const RowProg ln1_store = bound(plan->ln1_store, tables), proj_store = bound(plan->proj_store, tables),
+                x_gather = bound(plan->x_gather, tables);
   const int64_t T = (int64_t)c->B * c->H * c->W;
   const int C = c->C, h = c->heads, w = c->window, N = w * w, d = C / h, dt = c->dtype;
   const int64_t B_ = T / N;
@@ -295,12 +335,12 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
       Lin32Args a; std::memset(&a, 0, sizeof(a));
       a.X = x; a.Wp = wt->qkv_packed; a.bias = wt->bqkv; a.Y = qkv; a.M = T; a.N = 3 * C; a.K = C; a.act = SM_ACT_NONE;
       a.norm = 1; a.norm_eps = eps; a.norm_gamma = wt->ln1_g; a.norm_beta = wt->ln1_b;
-      a.x_rows = plan->x_gather; a.y_rows = identity_rows(3 * C);
+      a.x_rows = x_gather; a.y_rows = identity_rows(3 * C);
       if ((rc = lin32_checked(a, stream, "sm_swin_block(ln1+qkv)"))) return rc;
     } else if (fold_norm(3 * C)) {
-      if ((rc = run_gemm(x, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, &plan->x_gather, nullptr, stream, wt->ln1_g, wt->ln1_b, eps))) return rc;
+      if ((rc = run_gemm(x, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, &x_gather, nullptr, stream, wt->ln1_g, wt->ln1_b, eps))) return rc;
     } else {
-      if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, bufA, T, C, eps, 0, dt, nullptr, 1, &plan->ln1_store, stream))) return rc;
+      if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, bufA, T, C, eps, 0, dt, nullptr, 1, &ln1_store, stream))) return rc;
       if ((rc = run_gemm(bufA, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
     }
     const size_t es = dtype_size(dt);
@@ -310,9 +350,9 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
     }
     if ((rc = attention_checked(ad, (char*)qkv + plan->qkv_base[0] * es, (char*)qkv + plan->qkv_base[1] * es, (char*)qkv + plan->qkv_base[2] * es,
                                 bufO, wt->rpb_table, stream, "window attention"))) return rc;
-    if (proj_is_fused(*c, wt)) return run_proj_mlp_fused(*c, wt, bufO, x, y, T, plan->proj_store, next, next && next->wq_p ? qkv : bufA, stream);
+    if (proj_is_fused(*c, wt)) return run_proj_mlp_fused(*c, wt, bufO, x, y, T, proj_store, next, next && next->wq_p ? qkv : bufA, stream);
     if (next) return fail(SM_ERR_INVALID_ARG, "sm_swin_block: the next block's norm can only be emitted by the fused projection + MLP kernel");
-    if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &plan->proj_store, stream))) return rc;
+    if ((rc = run_gemm(bufO, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, nullptr, &proj_store, stream))) return rc;
     if (mlp_is_fused(*c, wt)) return run_mlp_fused(*c, wt, x1, y, T, stream);
     if (fold_norm(c->mlp_ratio * C)) {
       if ((rc = run_gemm(x1, wt->w1, wt->b1, nullptr, hid, T, c->mlp_ratio * C, C, dt, SM_ACT_GELU, nullptr, nullptr, stream, wt->ln2_g, wt->ln2_b, eps))) return rc;
@@ -332,23 +372,23 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
   const bool f1 = fold_norm(3 * C);
   const void* cur = x;
   if (!f1) { if ((rc = run_norm(x, wt->ln1_g, wt->ln1_b, s0, T, C, eps, 0, dt, nullptr, 1, nullptr, stream))) return rc; cur = s0; }
-  if (plan->has_roll) { if ((rc = copy_launch(plan->roll, cur, s1, dt, stream))) return rc; cur = s1; }
-  if ((rc = copy_launch(plan->partition, cur, s2, dt, stream))) return rc;
+  if (plan->has_roll) { if ((rc = copy_launch(plan->roll, tables, cur, s1, dt, stream))) return rc; cur = s1; }
+  if ((rc = copy_launch(plan->partition, tables, cur, s2, dt, stream))) return rc;
   if ((rc = run_gemm(s2, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream,
                      f1 ? wt->ln1_g : nullptr, wt->ln1_b, eps))) return rc;
-  if ((rc = copy_launch(plan->head_split, qkv, qkvp, dt, stream))) return rc;          // [3, B_, h, N, d]
+  if ((rc = copy_launch(plan->head_split, tables, qkv, qkvp, dt, stream))) return rc;          // [3, B_, h, N, d]
   ad.q_stride[0] = ad.k_stride[0] = ad.v_stride[0] = ad.o_stride[0] = (int64_t)h * N * d;
   ad.q_stride[1] = ad.k_stride[1] = ad.v_stride[1] = ad.o_stride[1] = (int64_t)N * d;
   ad.q_stride[2] = ad.k_stride[2] = ad.v_stride[2] = ad.o_stride[2] = d;
   const size_t part = (size_t)T * C * dtype_size(dt);
   if ((rc = attention_checked(ad, qkvp, (char*)qkvp + part, (char*)qkvp + 2 * part, s0, wt->rpb_table, stream, "window attention"))) return rc;
-  if ((rc = copy_launch(plan->head_merge, s0, s1, dt, stream))) return rc;             // [B_, N, C]
+  if ((rc = copy_launch(plan->head_merge, tables, s0, s1, dt, stream))) return rc;             // [B_, N, C]
   if ((rc = run_gemm(s1, wt->wproj, wt->bproj, nullptr, s2, T, C, C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
   if (plan->has_roll) {
-    if ((rc = copy_launch(plan->reverse, s2, s3, dt, stream))) return rc;
-    if ((rc = copy_launch(plan->unroll, s3, x1, dt, stream, x))) return rc;            // + residual
+    if ((rc = copy_launch(plan->reverse, tables, s2, s3, dt, stream))) return rc;
+    if ((rc = copy_launch(plan->unroll, tables, s3, x1, dt, stream, x))) return rc;            // + residual
   } else {
-    if ((rc = copy_launch(plan->reverse, s2, x1, dt, stream, x))) return rc;
+    if ((rc = copy_launch(plan->reverse, tables, s2, x1, dt, stream, x))) return rc;
   }
   if (mlp_is_fused(*c, wt)) return run_mlp_fused(*c, wt, x1, y, T, stream);
   if (fold_norm(c->mlp_ratio * C)) {
@@ -367,8 +407,8 @@ int swin_block_impl(const sm_swin_cfg* c, const sm_swin_weights* wt, const void*
 // ---------------------------------------------------------------------------
 namespace {
 
-struct MergePlan { RowProg ln_load; Copy gather; };
-struct EmbedPlan { RowProg a_rows, a_cols; Copy unfold; };
+struct MergePlan { RowProg ln_load; Copy gather; TableRegion tables; };
+struct EmbedPlan { RowProg a_rows, a_cols; Copy unfold; TableRegion tables; };
 std::map<Key, std::shared_ptr<MergePlan>> g_merge;
 std::map<Key, std::shared_ptr<EmbedPlan>> g_embed;
 
@@ -381,8 +421,9 @@ std::shared_ptr<MergePlan> merge_plan(int B, int H, int W, int C, int dtype, std
   // LayerNorm's load absorbs the 2x2 gather: a logical row of 4C is four segments of C
   std::vector<sm_view_op> ch = chains::patch_merge(B, H, W, C);
   ch.push_back(chains::reshape({(int64_t)B * (H / 2) * (W / 2) * 4, C}));
-  if (!make_rows({B, H, W, C}, ch, &p->ln_load, err)) return nullptr;
-  if (!make_copy({B, H, W, C}, chains::patch_merge(B, H, W, C), (int)dtype_size(dtype), &p->gather, err)) return nullptr;
+  if (!make_rows({B, H, W, C}, ch, &p->tables, &p->ln_load, err)) return nullptr;
+  if (!make_copy({B, H, W, C}, chains::patch_merge(B, H, W, C), (int)dtype_size(dtype), &p->tables, &p->gather, err)) return nullptr;
+  bound_cache(g_merge);
   g_merge[key] = p;
   return p;
 }
@@ -397,11 +438,12 @@ std::shared_ptr<EmbedPlan> embed_plan(int B, int Cin, int img, int patch, int dt
   std::vector<sm_view_op> ch = chains::patch_embed(B, Cin, img, img, patch);
   if (map_create({B, Cin, img, img}, ch.data(), (int)ch.size(), &m, err) != SM_OK) return nullptr;
   bool ok = m->compile_rows_cols(4, &p->a_rows, &p->a_cols, err);
-  const int64_t kk = m->shape.back();
-  ok = ok && attach_row_table(&p->a_rows, m->numel() / kk, err) && attach_row_table(&p->a_cols, kk / 4, err);
+  const int64_t kk = m->shape.back(), src_numel = (int64_t)B * Cin * img * img;
+  if (ok) { p->tables.add(&p->a_rows, m->numel() / kk, src_numel); p->tables.add(&p->a_cols, kk / 4, src_numel); }
   delete m;
-  ok = ok && make_copy({B, Cin, img, img}, ch, (int)dtype_size(dtype), &p->unfold, err);
+  ok = ok && make_copy({B, Cin, img, img}, ch, (int)dtype_size(dtype), &p->tables, &p->unfold, err);
   if (!ok) return nullptr;
+  bound_cache(g_embed);
   g_embed[key] = p;
   return p;
 }
@@ -438,24 +480,65 @@ int chain_weight_count(const sm_chain_desc* c) {
   return n + (c->has_head ? 4 : 0);
 }
 
-struct ChainSizes { size_t act, block, total; };
-ChainSizes chain_sizes(const sm_chain_desc* c, int mode) {
-  ChainSizes z{0, 0, 0};
+// Everything a chain call needs to know before its first launch: the plans of every stage (host objects) and where
+// each plan's row-offset tables lie in the workspace: [block buffers | activation ping | pong | table regions ...]
+struct ChainLayout {
+  size_t act = 0, block = 0, total = 0;
+  std::shared_ptr<EmbedPlan> embed; size_t embed_off = 0;
+  struct Stage {
+    std::shared_ptr<SwinPlan> plan[2]; size_t plan_off[2];       // [0] blocks without shift, [1] shifted blocks (if any)
+    std::shared_ptr<NextStore> next[2]; size_t next_off[2];      // elided: store of the block after a [0] / [1] block
+    std::shared_ptr<MergePlan> merge; size_t merge_off;
+  };
+  std::vector<Stage> stages;
+};
+int shift_of(const sm_chain_desc* c, const sm_stage_desc& st, int k) { return (k % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0; }
+
+bool chain_layout(const sm_chain_desc* c, int mode, ChainLayout* L, std::string* err) {
+  const int dt = c->dtype;
   for (int s = 0; s < c->n_stages; ++s) {
     const sm_stage_desc& st = c->stages[s];
-    sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, 0, c->mlp_ratio, c->dtype, c->eps};
-    z.block = std::max(z.block, sm_swin_block_workspace_bytes(&bc, mode));
-    z.act = std::max(z.act, align256((size_t)c->B * st.H * st.W * st.C * dtype_size(c->dtype)));
+    sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, 0, c->mlp_ratio, dt, c->eps};
+    L->block = std::max(L->block, swin_act_bytes(&bc, mode));
+    L->act = std::max(L->act, align256((size_t)c->B * st.H * st.W * st.C * dtype_size(dt)));
   }
-  z.total = z.block + 2 * z.act;
-  return z;
+  size_t at = L->block + 2 * L->act;
+  if (c->has_embed) {
+    if (!(L->embed = embed_plan(c->B, c->in_ch, c->img, c->patch, dt, err))) return false;
+    L->embed_off = at; at += L->embed->tables.bytes;
+  }
+  L->stages.resize((size_t)c->n_stages);
+  for (int s = 0; s < c->n_stages; ++s) {
+    const sm_stage_desc& st = c->stages[s];
+    ChainLayout::Stage& S = L->stages[(size_t)s];
+    const bool shifts = st.depth > 1 && shift_of(c, st, 1) != 0;
+    for (int sh = 0; sh < (shifts ? 2 : 1); ++sh) {
+      sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, sh ? c->window / 2 : 0, c->mlp_ratio, dt, c->eps};
+      if (!(S.plan[sh] = swin_plan(bc, err))) return false;
+      S.plan_off[sh] = at; at += S.plan[sh]->tables(mode).bytes;
+      if (mode == SM_ELIDED && st.depth > 1) {
+        const int nshift = shifts && !sh ? c->window / 2 : 0;
+        if (!(S.next[sh] = next_norm_store(bc, nshift, err))) return false;
+        S.next_off[sh] = at; at += S.next[sh]->tables.bytes;
+      }
+    }
+    if (s + 1 < c->n_stages) {
+      if (!(S.merge = merge_plan(c->B, st.H, st.W, st.C, dt, err))) return false;
+      S.merge_off = at; at += S.merge->tables.bytes;
+    }
+  }
+  L->total = at;
+  return true;
 }
 
 }  // namespace
 
 extern "C" size_t sm_run_chain_workspace_bytes(const sm_chain_desc* c, int mode) {
   if (check_chain(c, "sm_run_chain_workspace_bytes") != SM_OK) return 0;
-  return chain_sizes(c, mode).total;
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) { set_error("sm_run_chain_workspace_bytes: unknown mode %d", mode); return 0; }
+  ChainLayout L; std::string err;
+  if (!chain_layout(c, mode, &L, &err)) { set_error("sm_run_chain_workspace_bytes: %s", err.c_str()); return 0; }
+  return L.total;
 }
 
 extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, int n_weights, const void* x,
@@ -477,32 +560,63 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
       if ((!weights[i] && !optional[(size_t)i]) || !aligned16(weights[i]))
         return fail(SM_ERR_INVALID_ARG, "sm_run_chain: weight %d is null or misaligned", i);
   }
-  const ChainSizes z = chain_sizes(c, mode);
+  // build every plan before the first launch so that an unsupported shape enqueues nothing
+  ChainLayout z; std::string err;
+  if (!chain_layout(c, mode, &z, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
   if (ws_bytes < z.total) return fail(SM_ERR_WORKSPACE, "sm_run_chain: workspace of %zu bytes, %zu needed", ws_bytes, z.total);
   if (!aligned16(x) || !aligned16(y) || !aligned16(ws) || (y_feat && !aligned16(y_feat))) return fail(SM_ERR_INVALID_ARG, "sm_run_chain: pointers must be 16-byte aligned");
-  // build every plan before the first launch so that an unsupported shape enqueues nothing
-  std::string err;
   const int dt = c->dtype;
-  std::shared_ptr<EmbedPlan> ep;
-  std::vector<std::shared_ptr<MergePlan>> mp;
-  if (c->has_embed && !(ep = embed_plan(c->B, c->in_ch, c->img, c->patch, dt, &err))) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
-  for (int s = 0; s < c->n_stages; ++s) {
-    const sm_stage_desc& st = c->stages[s];
-    for (int sh = 0; sh < 2; ++sh) {
-      sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, sh ? c->window / 2 : 0, c->mlp_ratio, dt, c->eps};
-      if (!swin_plan(bc, &err)) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
-    }
-    if (s + 1 < c->n_stages) {
-      mp.push_back(merge_plan(c->B, st.H, st.W, st.C, dt, &err));
-      if (!mp.back()) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
+  // first pass, no launches: what each block hands to the next one, hence which tables are read at all
+  struct BlockStep { bool next; bool next_qkv; int pre; };
+  std::vector<std::vector<BlockStep>> steps((size_t)c->n_stages);
+  std::vector<uint64_t> need[2];
+  need[0].assign((size_t)c->n_stages, 0); need[1].assign((size_t)c->n_stages, 0);
+  std::vector<char> need_next[2];
+  need_next[0].assign((size_t)c->n_stages, 0); need_next[1].assign((size_t)c->n_stages, 0);
+  {
+    const void* const* wq = weights + (c->has_embed ? 4 : 0);
+    for (int s = 0; s < c->n_stages; ++s) {
+      const sm_stage_desc& st = c->stages[s];
+      int pre = 0;
+      for (int k = 0; k < st.depth; ++k) {
+        const int shift = shift_of(c, st, k), sh = shift ? 1 : 0;
+        sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, shift, c->mlp_ratio, dt, c->eps};
+        sm_swin_weights bw, nwt;
+        std::memcpy(&bw, wq, sizeof(bw));
+        wq += 16;
+        BlockStep b{false, false, pre};
+        // within a stage, elided, with the projection + MLP kernel: that kernel also writes the next block's
+        // LayerNorm-1 (through the next block's own partition map) or its QKV, and the next block starts there
+        // (where LayerNorm-1 is folded into the QKV Linear's load, C <= 170, only the norm + QKV form applies)
+        if (mode == SM_ELIDED && k + 1 < st.depth && proj_is_fused(bc, &bw)) {
+          std::memcpy(&nwt, wq, sizeof(nwt));
+          const bool with_qkv = nwt.qkv_packed && c->mlp_ratio >= 3;    // (the kernel keeps the QKV bias where the first MLP bias was)
+          if (!fold_norm(3 * st.C) || with_qkv) { b.next = true; b.next_qkv = with_qkv; }
+        }
+        need[sh][(size_t)s] |= mode == SM_ELIDED ? el_tables_needed(bc, &bw, pre) : ~0ull;
+        if (b.next) need_next[sh][(size_t)s] = 1;
+        pre = b.next ? (b.next_qkv ? 2 : 1) : 0;
+        steps[(size_t)s].push_back(b);
+      }
+      if (s + 1 < c->n_stages) wq += 3;
     }
   }
   char* base = (char*)ws;
+  count_reset();
+  // the row-offset tables of every map the chain reads, before its first kernel
+  if (z.embed && (rc = fill_tables(z.embed->tables, base + z.embed_off, stream, mode == SM_ELIDED ? 3ull : ~3ull))) return rc;   // A rows + columns | the unfold copy
+  for (int s = 0; s < c->n_stages; ++s) {
+    const ChainLayout::Stage& S = z.stages[(size_t)s];
+    for (int sh = 0; sh < 2; ++sh) {
+      if (S.plan[sh] && need[sh][(size_t)s] && (rc = fill_tables(S.plan[sh]->tables(mode), base + S.plan_off[sh], stream, need[sh][(size_t)s]))) return rc;
+      if (S.next[sh] && need_next[sh][(size_t)s] && (rc = fill_tables(S.next[sh]->tables, base + S.next_off[sh], stream, ~0ull))) return rc;
+    }
+    if (S.merge && (rc = fill_tables(S.merge->tables, base + S.merge_off, stream, mode == SM_ELIDED ? 1ull : ~1ull))) return rc;      // LayerNorm's gather | the copy
+  }
   void* blk_ws = base;
   void* act[2] = {base + z.block, base + z.block + z.act};
   int n_compute = 0, n_copy = 0;
   auto tally = [&]() { int a, b; counts(&a, &b); n_compute += a; n_copy += b; count_reset(); };
-  count_reset();
   const void* const* wp = weights;
   const void* cur = x;
   int flip = 0;
@@ -514,11 +628,12 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
     if (mode == SM_ELIDED) {
       GemmArgs g; std::memset(&g, 0, sizeof(g));
       g.A = x; g.W = wp[0]; g.bias = wp[1]; g.C = tmp; g.M = T; g.N = st.C; g.K = K; g.dtype = dt; g.ldw = K;
-      g.a_rows = ep->a_rows; g.a_cols = ep->a_cols; g.a_gran = 4; g.c_rows = identity_rows(st.C);
+      const void* tb = base + z.embed_off;
+      g.a_rows = bound(z.embed->a_rows, tb); g.a_cols = bound(z.embed->a_cols, tb); g.a_gran = 4; g.c_rows = identity_rows(st.C);
       if ((rc = gemm_checked(g, stream, "patch embedding"))) return rc;
     } else {
       void* unf = (char*)blk_ws + align256((size_t)T * st.C * dtype_size(dt));
-      if ((rc = copy_launch(ep->unfold, x, unf, dt, stream))) return rc;
+      if ((rc = copy_launch(z.embed->unfold, base + z.embed_off, x, unf, dt, stream))) return rc;
       if ((rc = run_gemm(unf, wp[0], wp[1], nullptr, tmp, T, st.C, K, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;
     }
     if ((rc = run_norm(tmp, wp[2], wp[3], act[flip], T, st.C, c->eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
@@ -529,46 +644,37 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
   for (int s = 0; s < c->n_stages; ++s) {
     const sm_stage_desc& st = c->stages[s];
     const bool last_stage = s + 1 == c->n_stages;
-    int pre = 0;
+    const ChainLayout::Stage& S = z.stages[(size_t)s];
     for (int k = 0; k < st.depth; ++k) {
-      const int shift = (k % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0;
+      const int shift = shift_of(c, st, k), sh = shift ? 1 : 0;
+      const BlockStep& step = steps[(size_t)s][(size_t)k];
       sm_swin_cfg bc{c->B, st.H, st.W, st.C, st.heads, c->window, shift, c->mlp_ratio, dt, c->eps};
       sm_swin_weights bw;
       std::memcpy(&bw, wp, sizeof(bw));
       wp += 16;
       const bool final_out = last_stage && k + 1 == st.depth && !c->has_head;
       void* out = final_out ? y : act[flip];
-      // within a stage, elided, with the projection + MLP kernel: that kernel also writes the next block's LayerNorm-1
-      // (through the next block's own partition map), and the next block starts at its QKV Linear
       NextNorm nn; const NextNorm* next = nullptr;
-      sm_swin_weights nwt;
-      if (k + 1 < st.depth) std::memcpy(&nwt, wp, sizeof(nwt));
-      // (where LayerNorm-1 is folded into the QKV Linear's load, C <= 170, only the norm + QKV form applies)
-      if (mode == SM_ELIDED && k + 1 < st.depth && proj_is_fused(bc, &bw) &&
-          (!fold_norm(3 * st.C) || (nwt.qkv_packed && c->mlp_ratio >= 3))) {
-        const int nshift = ((k + 1) % 2 == 1 && std::min(st.H, st.W) > c->window) ? c->window / 2 : 0;
-        std::string err;
-        auto nstore = next_norm_store(bc, nshift, &err);
-        if (!nstore) return fail(SM_ERR_UNSUPPORTED, "sm_run_chain: %s", err.c_str());
-        const sm_swin_weights& nw = nwt;
-        nn.gamma = nw.ln1_g; nn.beta = nw.ln1_b; nn.store = *nstore;
-        const bool with_qkv = nw.qkv_packed && c->mlp_ratio >= 3;      // (the kernel keeps the QKV bias where the first MLP bias was)
-        nn.wq_p = with_qkv ? nw.qkv_packed : nullptr; nn.bq = nw.bqkv;
+      if (step.next) {
+        sm_swin_weights nw;
+        std::memcpy(&nw, wp, sizeof(nw));
+        nn.gamma = nw.ln1_g; nn.beta = nw.ln1_b; nn.store = bound(S.next[sh]->rows, base + S.next_off[sh]);
+        nn.wq_p = step.next_qkv ? nw.qkv_packed : nullptr; nn.bq = nw.bqkv;
         next = &nn;
       }
-      if ((rc = swin_block_impl(&bc, &bw, cur, out, blk_ws, z.block, mode, stream, next, pre))) return rc;
-      pre = next ? (next->wq_p ? 2 : 1) : 0;
+      if ((rc = swin_block_impl(&bc, &bw, cur, out, blk_ws, z.block, mode, stream, next, step.pre, base + S.plan_off[sh]))) return rc;
       tally();
       cur = out; flip ^= 1;
     }
     if (!last_stage) {
       const int64_t T4 = (int64_t)c->B * (st.H / 2) * (st.W / 2);
       void* normed = blk_ws;
+      const RowProg merge_load = bound(S.merge->ln_load, base + S.merge_off);
       if (mode == SM_ELIDED) {
-        if ((rc = run_norm(cur, wp[0], wp[1], normed, T4, 4 * st.C, c->eps, 0, dt, &mp[s]->ln_load, 4, nullptr, stream))) return rc;
+        if ((rc = run_norm(cur, wp[0], wp[1], normed, T4, 4 * st.C, c->eps, 0, dt, &merge_load, 4, nullptr, stream))) return rc;
       } else {
         void* gathered = (char*)blk_ws + align256((size_t)T4 * 4 * st.C * dtype_size(dt));
-        if ((rc = copy_launch(mp[s]->gather, cur, gathered, dt, stream))) return rc;
+        if ((rc = copy_launch(S.merge->gather, base + S.merge_off, cur, gathered, dt, stream))) return rc;
         if ((rc = run_norm(gathered, wp[0], wp[1], normed, T4, 4 * st.C, c->eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
       }
       if ((rc = run_gemm(normed, wp[2], nullptr, nullptr, act[flip], T4, 2 * st.C, 4 * st.C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;

@@ -5,7 +5,7 @@
 
 namespace sm {
 
-bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, int esize, Copy* out, std::string* err) {
+bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, int esize, TableRegion* tables, Copy* out, std::string* err) {
   sm_map* m = nullptr;
   if (map_create(src, chain.data(), (int)chain.size(), &m, err) != SM_OK) return false;
   bool ok = m->compile(&out->prog, err);
@@ -19,19 +19,21 @@ bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& c
       m->compile_rows(&out->rows, &why)) {
     out->n_rows = out->numel / inner;
     out->inner = (int)inner;
-    ok = attach_row_table(&out->rows, out->n_rows, err);
-    out->by_rows = ok && (out->rows.identity || out->rows.table);
+    int64_t src_numel = 1;
+    for (auto e : src) src_numel *= e;
+    tables->add(&out->rows, out->n_rows, src_numel);
+    out->by_rows = out->rows.identity || out->rows.table_off;
   }
   delete m;
   return ok;
 }
 
-int copy_launch(const Copy& cp, const void* src, void* dst, int dtype, void* stream, const void* addend) {
+int copy_launch(const Copy& cp, const void* region, const void* src, void* dst, int dtype, void* stream, const void* addend) {
   char label[64];
   snprintf(label, sizeof(label), "copy_%s[%lld]%s", dtype == SM_F32 ? "f32" : "bf16", (long long)cp.numel, addend ? "+add" : "");
   Timed tm(label, stream);
   int rc;
-  if (cp.by_rows) rc = launch_gather_rows(cp.rows, cp.n_rows, cp.inner, src, addend, dst, dtype, stream);
+  if (cp.by_rows) rc = launch_gather_rows(bound(cp.rows, region), cp.n_rows, cp.inner, src, addend, dst, dtype, stream);
   else rc = addend ? launch_gather_add(cp.prog, cp.numel, cp.vec, src, addend, dst, dtype, stream)
                    : launch_gather(cp.prog, cp.numel, cp.vec, src, dst, (int)dtype_size(dtype), stream);
   if (rc) return fail(SM_ERR_DEVICE, "copy kernel launch failed (hip error %d)", rc);

@@ -14,8 +14,10 @@ struct Copy {
   bool by_rows; RowProg rows; int64_t n_rows; int inner;   // row form: rows of `inner` contiguous elements
 };
 
-bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, int esize, Copy* out, std::string* err);
-// dst = src gathered through the copy's map (+ addend, element-wise, when given); counts as one copy kernel
-int copy_launch(const Copy& cp, const void* src, void* dst, int dtype, void* stream, const void* addend = nullptr);
+// tables: the region the copy's row-offset table gets a slot in
+bool make_copy(const std::vector<int64_t>& src, const std::vector<sm_view_op>& chain, int esize, TableRegion* tables, Copy* out, std::string* err);
+// dst = src gathered through the copy's map (+ addend, element-wise, when given); counts as one copy kernel.
+// region: where `tables` was filled for this call
+int copy_launch(const Copy& cp, const void* region, const void* src, void* dst, int dtype, void* stream, const void* addend = nullptr);
 
 }  // namespace sm

@@ -52,7 +52,9 @@ struct RowProg {
   int32_t n_atoms; int32_t nterm; int32_t pad;
   int64_t ld;              // identity only
   int64_t c0;
-  const int32_t* table;    // device memory or null: the program evaluated for rows 0 .. n-1 (attach_row_table)
+  const int32_t* table;    // device memory or null: the program evaluated for rows 0 .. n-1; kernels read one word per
+                           // row instead of interpreting the program
+  int64_t table_off;       // host bookkeeping: byte offset + 1 of that table inside its plan's table region, 0 = no table
   int32_t t_atom[PROG_MAX_FINAL];
   int64_t t_coef[PROG_MAX_FINAL];
   ProgAtom atoms[PROG_MAX_ATOMS];
@@ -89,8 +91,23 @@ RowProg identity_rows(int64_t ld);
 // x / d == umulhi(x, *mul) >> *sh for 0 <= x < 2^31 and d > 1 (d <= 1: both zero, callers test d)
 void magic(int64_t d, uint32_t* mul, uint32_t* sh);
 int64_t eval_rows_host(const RowProg& p, int64_t r);
-// Evaluates the program for rows 0 .. n_rows-1 on the host and leaves the offsets in device memory that lives
-// until the process ends (plans are cached for that long); kernels then read one word per row instead of
-// interpreting the program.  No table (and success) for identity programs and for offsets beyond 31 bits.
-bool attach_row_table(RowProg* p, int64_t n_rows, std::string* err);
+// Per-row offset tables.  A plan (host memory only) lists the row programs that want a table and gives each a slot
+// in a "table region"; the executor places the region in the caller's workspace, fills it on the caller's stream
+// with one small kernel per table (fill_tables) at the start of every call, and hands kernels copies of the
+// programs whose `table` points into it (bound).  Nothing is allocated and nothing outlives the call.
+struct TableRegion {
+  struct Item { RowProg prog; int64_t n_rows; size_t off; };
+  std::vector<Item> items;
+  size_t bytes = 0;
+  // gives p a slot when every offset fits 31 bits (src_numel = elements of the tensor the offsets point into);
+  // identity programs need none
+  void add(RowProg* p, int64_t n_rows, int64_t src_numel);
+};
+// which: bit i set = fill the i-th added program's table (tables no kernel of the call reads can be left out)
+int fill_tables(const TableRegion& r, void* region, void* stream, uint64_t which);     // SM_OK or SM_ERR_DEVICE
+inline RowProg bound(const RowProg& p, const void* region) {
+  RowProg q = p;
+  q.table = (p.table_off && region) ? (const int32_t*)((const char*)region + (p.table_off - 1)) : nullptr;
+  return q;
+}
 }

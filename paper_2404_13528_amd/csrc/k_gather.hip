@@ -85,6 +85,20 @@ int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const voi
   return (int)hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void fill_rows_kernel(RowProg prog, int64_t n_rows, int32_t* __restrict__ table) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_rows) return;
+  table[r] = (int32_t)eval_rows_k(kernarg_ptr<RowProg>(), r);      // prog is the first argument; its own table is null
+}
+int launch_fill_rows(const RowProg& prog, int64_t n_rows, int32_t* table, void* stream) {
+  if (n_rows <= 0) return 0;
+  if (n_rows >= (1LL << 31)) return (int)hipErrorInvalidValue;
+  RowProg p = prog;
+  p.table = nullptr;
+  fill_rows_kernel<<<dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(p, n_rows, table);
+  return (int)hipGetLastError();
+}
+
 __global__ void empty_kernel() {}
 int launch_empty(void* stream) {
   empty_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>();

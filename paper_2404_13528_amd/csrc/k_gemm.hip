@@ -18,6 +18,7 @@
 // logical column order of a wave's 64-column span (which W row feeds which
 // MFMA block), so that the two partners sit in the same lane: the Slice /
 // chunk operators of SwiGLU / GEGLU and the half-split of RoPE cost nothing.
+#include <atomic>
 #include <algorithm>
 #include <type_traits>
 #include "device_common.h"
@@ -647,7 +648,7 @@ static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
-static int g_force_rows = 0, g_force_stages = 0;       // sm_gemm_tuning
+static std::atomic<int> g_force_rows{0}, g_force_stages{0};       // sm_gemm_tuning (a process-wide sweep hook)
 
 // Two stages (one K-tile in flight) unless the tuning hook asks for more: within a chain of kernels the operands
 // arrive from the memory-side cache, a workgroup's K step is bound by its own issue and fragment-read latencies

@@ -23,6 +23,7 @@
 // uses them:
 //   W1 fragment (slice sc, step kk) at index sc * C/16 + kk:            lane (l32, hf) = W1[32 sc + l32][16 kk + 8 hf ..+7]
 //   W2 fragment (block t, slice sc, step s) at (t * hidden/32 + sc) * 2 + s: lane (l32, hf) = W2[32 t + l32][32 sc + 16 s + 8 hf ..+7]
+#include <atomic>
 #include <type_traits>
 #include "device_common.h"
 #include "kernels.h"
@@ -431,11 +432,11 @@ static size_t mlp_smem(int C, int Hd, bool proj, bool lnout) {
 template <int C, bool PROJ, int LNOUT>
 static int mlp_launch3(const MlpArgs& g, void* stream) {
   const size_t smem = mlp_smem(C, g.Hd, PROJ, LNOUT != 0);
-  static size_t allowed = 0;          // raised on demand: the attribute is per kernel, the hidden size varies
-  if (smem > allowed) {
+  static std::atomic<size_t> allowed{0};   // raised on demand: the attribute is per kernel, the hidden size varies
+  if (smem > allowed.load()) {
     const hipError_t e = hipFuncSetAttribute((const void*)mlp_fused_kernel<C, PROJ, LNOUT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return (int)e;
-    allowed = smem;
+    allowed.store(smem);
   }
   const int64_t n_wg = (g.M + 31) / 32;
   mlp_fused_kernel<C, PROJ, LNOUT><<<dim3((unsigned)n_wg), dim3(64 * (C / 32)), smem, (hipStream_t)stream>>>(g);
@@ -585,11 +586,11 @@ __global__ void lin_pack_kernel(const bf16_t* W, mlp_u32x4* packed, int N, int K
 template <int C, bool RES, int NW>
 static int lin32_launch3(const Lin32Args& g, void* stream) {
   const size_t smem = (size_t)32 * (C / 8 + 1) * 16 + (size_t)g.N * 2;
-  static size_t allowed = 0;
-  if (smem > allowed) {
+  static std::atomic<size_t> allowed{0};
+  if (smem > allowed.load()) {
     const hipError_t e = hipFuncSetAttribute((const void*)lin32_kernel<C, RES, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return (int)e;
-    allowed = smem;
+    allowed.store(smem);
   }
   lin32_kernel<C, RES, NW><<<dim3((unsigned)((g.M + 31) / 32)), dim3(64 * NW), smem, (hipStream_t)stream>>>(g);
   return (int)hipGetLastError();

@@ -18,6 +18,9 @@ int launch_empty(void* stream);
 // row copies: dst row r (inner contiguous elements) = src[rows(r) ...] (+ addend row r); rows(r) keeps 16-byte alignment
 int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const void* src, const void* addend, void* dst, int dtype, void* stream);
 
+// table[r] = offset of row r under `prog` (interpreted), r < n_rows: fills one per-row offset table
+int launch_fill_rows(const RowProg& prog, int64_t n_rows, int32_t* table, void* stream);
+
 struct NormArgs {
   const void* x; const void* gamma; const void* beta; void* y;
   int64_t rows; int C; float eps; int rms; int dtype;

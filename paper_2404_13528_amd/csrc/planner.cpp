@@ -5,16 +5,25 @@
 // left, and reduction-dimension layout selection with k directly indexable
 // dimensions (Sec. 3.2.2).  Host only.
 //
+// The paper rewrites one producer -> consumer pair at a time over rounds; this
+// planner reaches the same fixpoint in passes over whole runs: (1) every maximal
+// run of Fixed operators behind a stored tensor is collected per reader
+// (Fixed-Fixed pairs: "Eliminate both"), (2) each run goes to a store or a load,
+// (3) ILI & Variable operators are merged into neighbours with a union-find.
+//
 // Readings where the paper leaves a choice:
-//  - a run of Fixed operators between Variable operators goes to the write side
-//    (producer's store) when the producer's tensor has no direct Variable
-//    consumer, every consumer sees it through the same run and the run is a
-//    bijection (Reshape / Transpose / Roll only); otherwise each consumer's
-//    load absorbs its own run ("sub-optimally writing beats sub-optimally
-//    reading", Sec. 3.2.2);
-//  - a run with no Variable operator on either side is materialised;
-//  - an ILI & Variable operator fuses into its latest Variable producer
-//    (epilogue), or, if it has none, into its first Variable consumer.
+//  - a run goes to the write side (its producer's store, "Eliminate 2nd") when
+//    it is the only reader of the producer's tensor and is a bijection (Reshape
+//    / Transpose / Roll only): one stored tensor has one layout, and a store
+//    map is the inverse of the run ("sub-optimally writing beats sub-optimally
+//    reading", Sec. 3.2.2); otherwise each reader's load absorbs its own run
+//    ("Eliminate 1st");
+//  - a run that nothing reads (a graph output) is stored by its Variable
+//    producer as one more output; without such a producer it is materialised;
+//  - "Try fuse" pairs are taken with consumers in graph order and a consumer's
+//    latest producer first; the node of lower optimisation complexity joins the
+//    other (Table 6; on a tie the first operator stays); a merge that would make
+//    the node feed itself through a third one is not legal.
 #include <algorithm>
 #include <map>
 #include <memory>
@@ -87,17 +96,6 @@ sm_view_op view_of(const sm_plan& p, const sm_op_desc& op) {
   return v;
 }
 
-bool same_view(const sm_view_op& a, const sm_view_op& b) {
-  if (a.kind != b.kind || a.n != b.n) return false;
-  for (int i = 0; i < a.n; ++i) if (a.arg[i] != b.arg[i]) return false;
-  return true;
-}
-bool same_chain(const std::vector<sm_view_op>& a, const std::vector<sm_view_op>& b) {
-  if (a.size() != b.size()) return false;
-  for (size_t i = 0; i < a.size(); ++i) if (!same_view(a[i], b[i])) return false;
-  return true;
-}
-
 // chain that undoes `chain` applied to a tensor of shape src; false if not a bijection
 bool invert_chain(const std::vector<sm_view_op>& chain, const std::vector<int64_t>& src, std::vector<sm_view_op>* inv) {
   std::vector<std::vector<int64_t>> shapes{src};
@@ -159,9 +157,9 @@ extern "C" int sm_layout_plan(const sm_tensor_desc* tensors, int n_tensors, cons
     const sm_op_desc& o = ops[i];
     if (!known_kind(o.kind)) return fail(SM_ERR_INVALID_ARG, "sm_layout_plan: operator %d has unknown kind %d", i, o.kind);
     if (o.n_in < 1 || o.n_in > 4 || o.out < 0 || o.out >= n_tensors) return fail(SM_ERR_INVALID_ARG, "sm_layout_plan: operator %d is malformed", i);
+    if (!is_var(group_of(o.kind)) && o.n_in != 1) return fail(SM_ERR_UNSUPPORTED, "sm_layout_plan: operator %d: layout operators with several inputs are not planned", i);
     for (int s = 0; s < o.n_in; ++s) {
       if (o.in[s] < 0 || o.in[s] >= n_tensors) return fail(SM_ERR_INVALID_ARG, "sm_layout_plan: operator %d reads tensor %d", i, o.in[s]);
-      if (producer.count(o.in[s]) == 0 && false) {}
       if (producer.count(o.in[s]) && producer[o.in[s]] >= i) return fail(SM_ERR_INVALID_ARG, "sm_layout_plan: operators are not in topological order");
       consumers[o.in[s]].push_back({i, s});
     }
@@ -212,97 +210,129 @@ extern "C" int sm_layout_plan(const sm_tensor_desc* tensors, int n_tensors, cons
   // ---- absorb every run into a Variable neighbour
   std::map<int, std::vector<sm_view_op>> load_chain_of;   // key consumer*8+slot
   std::map<int, int> load_src;
-  std::map<int, std::pair<int, std::vector<sm_view_op>>> store_of;   // producer -> (final tensor, forward chain)
+  struct Store { int prod, final_t; std::vector<sm_view_op> chain; bool composable; };
+  std::vector<Store> main_store, extra_store;              // a producer's own store / further outputs behind a run
+  auto to_store = [&](const Use& u, int prod) {
+    for (int f : u.run.ops) {
+      p->status[f] = SM_ELIMINATED_STORE; p->absorbed_by[f] = prod;
+      if (p->action[f] < 0) p->action[f] = SM_ELIM_2ND;
+    }
+  };
   for (auto& kv : by_src) {
     const int src = kv.first;
-    std::vector<Use>& uses = kv.second;
-    bool direct = false;
-    for (auto& c : consumers[src]) direct |= is_var(p->group[c.first]);
-    bool all_same = true, composable = true;
-    for (auto& u : uses) { all_same &= same_chain(u.run.chain, uses[0].run.chain); composable &= u.run.composable; }
-    std::vector<sm_view_op> inv;
     const bool has_prod = producer.count(src) > 0;
-    const bool bijective = composable && has_prod && invert_chain(uses[0].run.chain, p->tensors[src], &inv);
-    if (has_prod && !direct && all_same && bijective) {
-      const int prod = producer[src];
-      store_of[prod] = {ops[uses[0].run.ops.back()].out, uses[0].run.chain};
-      for (auto& u : uses)
-        for (int f : u.run.ops) {
-          p->status[f] = SM_ELIMINATED_STORE; p->absorbed_by[f] = prod;
-          if (p->action[f] < 0) p->action[f] = SM_ELIM_2ND;
-        }
+    std::vector<Use> uses;                                  // the runs something reads
+    for (auto& u : kv.second) {
+      if (u.consumer >= 0) { uses.push_back(u); continue; }
+      if (has_prod) {                                       // a run nothing reads: its producer stores it as well
+        to_store(u, producer[src]);
+        extra_store.push_back({producer[src], ops[u.run.ops.back()].out, u.run.chain, u.run.composable});
+      } else {
+        for (int f : u.run.ops) { p->status[f] = SM_MATERIALISED; p->absorbed_by[f] = -1; }
+      }
+    }
+    if (uses.empty()) continue;
+    bool direct = false;                                    // somebody reads the stored tensor as it is
+    for (auto& c : consumers[src]) direct |= is_var(p->group[c.first]);
+    bool one_run = true, composable = true;                 // one stored tensor has one layout
+    for (auto& u : uses) { one_run &= u.run.ops == uses[0].run.ops; composable &= u.run.composable; }
+    std::vector<sm_view_op> inv;
+    if (has_prod && !direct && one_run && composable && invert_chain(uses[0].run.chain, p->tensors[src], &inv)) {
+      to_store(uses[0], producer[src]);
+      main_store.push_back({producer[src], ops[uses[0].run.ops.back()].out, uses[0].run.chain, true});
     } else {
       for (auto& u : uses) {
-        if (u.consumer < 0) {
-          for (int f : u.run.ops) {
-            if (has_prod) { p->status[f] = SM_ELIMINATED_STORE; p->absorbed_by[f] = producer[src]; if (p->action[f] < 0) p->action[f] = SM_ELIM_2ND; }
-            else { p->status[f] = SM_MATERIALISED; p->absorbed_by[f] = -1; }
-          }
-          continue;
-        }
         for (int f : u.run.ops) {
           p->status[f] = SM_ELIMINATED_LOAD; p->absorbed_by[f] = u.consumer;
           if (p->action[f] < 0) p->action[f] = SM_ELIM_1ST;
         }
-        if (u.run.composable) { load_chain_of[u.consumer * 8 + u.slot] = u.run.chain; load_src[u.consumer * 8 + u.slot] = src; }
+        load_src[u.consumer * 8 + u.slot] = src;
+        if (u.run.composable) load_chain_of[u.consumer * 8 + u.slot] = u.run.chain;
       }
     }
   }
 
-  // ---- fuse ILI & Variable operators into a neighbour ("Try fuse")
+  // ---- "Try fuse": pair by pair (consumers in graph order, a consumer's latest producer first), the node of
+  // lower optimisation complexity joins the other (Table 6), as long as the merged node does not feed itself
   std::vector<int> root(n);
   for (int i = 0; i < n; ++i) root[i] = i;
   auto find = [&](int i) { while (root[i] != i) i = root[i]; return i; };
-  bool changed = true;
-  while (changed) {
+  auto stored_source = [&](int t) { return fixed_op(t) ? run_back(t).src : t; };
+  auto feeds_through_third = [&](int a, int b) {          // a path a ~> b that does not use an a -> b edge
+    std::vector<int> todo; std::set<int> seen;
+    auto push_next = [&](int x, bool skip_b) {
+      for (int c = 0; c < n; ++c) {
+        if (!is_var(p->group[c]) || find(c) == x) continue;
+        for (int s2 = 0; s2 < ops[c].n_in; ++s2) {
+          const int t = stored_source(ops[c].in[s2]);
+          if (producer.count(t) && is_var(p->group[producer[t]]) && find(producer[t]) == x && !(skip_b && find(c) == b)) todo.push_back(find(c));
+        }
+      }
+    };
+    push_next(a, true);
+    while (!todo.empty()) {
+      const int x = todo.back(); todo.pop_back();
+      if (x == b) return true;
+      if (seen.insert(x).second) push_next(x, false);
+    }
+    return false;
+  };
+  for (bool changed = true; changed;) {
     changed = false;
-    for (int i = 0; i < n; ++i) {
-      if (p->group[i] != SM_ILI_VAR || p->status[i] != SM_KEPT) continue;
-      int target = -1;
-      for (int s = 0; s < ops[i].n_in; ++s) {
-        int t = ops[i].in[s];
-        if (fixed_op(t)) t = run_back(t).src;
-        if (producer.count(t)) { const int q = find(producer[t]); if (q != i) target = std::max(target, q); }
+    for (int c = 0; c < n && !changed; ++c) {
+      if (!is_var(p->group[c])) continue;
+      std::vector<int> prods;
+      for (int s2 = 0; s2 < ops[c].n_in; ++s2) {
+        const int t = stored_source(ops[c].in[s2]);
+        if (producer.count(t) && is_var(p->group[producer[t]])) prods.push_back(producer[t]);
       }
-      if (target < 0) {
-        for (auto& c : consumers[ops[i].out])
-          if (is_var(p->group[c.first])) { const int q = find(c.first); if (q != i && (target < 0 || q < target)) target = q; }
-        if (target < 0) continue;
+      std::sort(prods.rbegin(), prods.rend());
+      for (int q : prods) {
+        const int a = find(q), b = find(c);
+        if (a == b || action_of(p->node_group[a], p->node_group[b]) != SM_TRY_FUSE || feeds_through_third(a, b)) continue;
+        const int keep = p->node_group[a] <= p->node_group[b] ? a : b, lose = keep == a ? b : a;
+        int res, search;
+        outcome_of(p->node_group[a], p->node_group[b], &res, &search);
+        p->node_group[keep] = res;
+        root[lose] = keep;
+        changed = true;
+        break;
       }
-      int res, search;
-      outcome_of(p->node_group[target], SM_ILI_VAR, &res, &search);
-      p->status[i] = SM_FUSED; p->absorbed_by[i] = target; p->action[i] = SM_TRY_FUSE;
-      p->node_group[target] = res;
-      root[i] = target;
-      changed = true;
     }
   }
   for (int i = 0; i < n; ++i) {
-    if (p->status[i] == SM_KEPT && p->group[i] == SM_ILD_VAR && p->action[i] < 0) p->action[i] = SM_KEEP_BOTH;
-    if (p->status[i] == SM_KEPT && p->action[i] < 0) p->action[i] = SM_KEEP_BOTH;
-    if (p->status[i] == SM_ELIMINATED_STORE || p->status[i] == SM_ELIMINATED_LOAD || p->status[i] == SM_FUSED)
+    if (is_var(p->group[i])) {
+      const int r = find(i);
+      p->status[i] = r == i ? SM_KEPT : SM_FUSED;
+      p->absorbed_by[i] = r;
+      p->action[i] = r == i ? SM_KEEP_BOTH : SM_TRY_FUSE;
+    } else if (p->status[i] == SM_ELIMINATED_STORE || p->status[i] == SM_ELIMINATED_LOAD) {
       p->absorbed_by[i] = find(p->absorbed_by[i]);
+    }
   }
 
   // ---- compose the maps
   std::string err;
-  for (auto& kv : load_chain_of) {
+  for (auto& kv : load_src) {
     sm_map* m = nullptr;
-    const int src = load_src[kv.first];
-    if (map_create(p->tensors[src], kv.second.data(), (int)kv.second.size(), &m, &err) != SM_OK)
+    auto ch = load_chain_of.find(kv.first);
+    if (ch != load_chain_of.end() &&
+        map_create(p->tensors[kv.second], ch->second.data(), (int)ch->second.size(), &m, &err) != SM_OK)
       return fail(SM_ERR_SHAPE, "sm_layout_plan: load map of operator %d: %s", kv.first / 8, err.c_str());
-    p->load[{kv.first / 8, kv.first % 8}] = {src, m};
+    p->load[{kv.first / 8, kv.first % 8}] = {kv.second, m};
   }
   std::set<int> stored_final;
-  for (auto& kv : store_of) {
+  main_store.insert(main_store.end(), extra_store.begin(), extra_store.end());
+  std::stable_sort(main_store.begin(), main_store.end(), [](const Store& x, const Store& y) { return x.prod < y.prod; });
+  for (auto& st : main_store) {
+    stored_final.insert(st.final_t);
+    if (p->store.count(find(st.prod))) continue;           // sm_plan_store_map reports a node's first mapped store
     std::vector<sm_view_op> inv;
-    const int prod = kv.first, final_t = kv.second.first;
-    invert_chain(kv.second.second, p->tensors[ops[prod].out], &inv);
     sm_map* m = nullptr;
-    if (map_create(p->tensors[final_t], inv.data(), (int)inv.size(), &m, &err) != SM_OK)
-      return fail(SM_ERR_SHAPE, "sm_layout_plan: store map of operator %d: %s", prod, err.c_str());
-    p->store[find(prod)] = {final_t, m};
-    stored_final.insert(final_t);
+    if (st.composable && invert_chain(st.chain, p->tensors[ops[st.prod].out], &inv) &&
+        map_create(p->tensors[st.final_t], inv.data(), (int)inv.size(), &m, &err) != SM_OK)
+      return fail(SM_ERR_SHAPE, "sm_layout_plan: store map of operator %d: %s", st.prod, err.c_str());
+    p->store[find(st.prod)] = {st.final_t, m};
   }
 
   // ---- reduction-dimension layout selection (local rule per edge, global rule per tensor)
@@ -311,24 +341,28 @@ extern "C" int sm_layout_plan(const sm_tensor_desc* tensors, int n_tensors, cons
         !stored_final.count(t)) continue;                 // a view that is never stored
     const std::vector<int64_t>& shape = p->tensors[t];
     const int rank = (int)shape.size();
-    std::vector<std::pair<int64_t, int64_t>> requested;    // (stride in the natural storage, extent), consumer order
+    std::vector<int64_t> nat(rank, 1);
+    for (int d = rank - 2; d >= 0; --d) nat[d] = nat[d + 1] * shape[d + 1];
+    sm_plan::Layout lay;                                    // requested dimensions in consumer order
     auto request = [&](const sm_map* m, const std::vector<int64_t>& vshape, int64_t red) {
       const int vr = (int)vshape.size();
       if (red < 0) red += vr;
       if (red < 0 || red >= vr) return;
-      int64_t stride = 1;
-      if (vshape[red] > 1) {
-        if (m) {
-          std::vector<int64_t> idx(vr, 0);
-          const int64_t a = m->at(idx.data());
-          idx[red] = 1;
-          stride = m->at(idx.data()) - a;
-        } else {
-          for (int d = red + 1; d < vr; ++d) stride *= vshape[d];
-        }
+      // the stored dimension that moves most often while walking along the reduction axis (the innermost of
+      // them on a tie: a reduction over merged dimensions asks for the fastest one); extent 1 asks for nothing
+      int dim = rank - 1;
+      std::vector<int64_t> moves(rank, 0), idx(vr, 0);
+      int64_t prev = 0;
+      for (int64_t i = 0; i < vshape[red]; ++i) {
+        idx[red] = i;
+        int64_t off = 0;
+        if (m) off = m->at(idx.data());
+        else for (int d = 0; d < vr; ++d) off = off * vshape[d] + idx[d];
+        if (i > 0) for (int d = 0; d < rank; ++d) moves[d] += (off / nat[d]) % shape[d] != (prev / nat[d]) % shape[d];
+        prev = off;
       }
-      std::pair<int64_t, int64_t> rq{stride, vshape[red]};
-      if (std::find(requested.begin(), requested.end(), rq) == requested.end()) requested.push_back(rq);
+      for (int d = 0; d < rank; ++d) if (moves[d] > 0 && moves[d] >= moves[dim]) dim = d;
+      if (std::find(lay.red_dims.begin(), lay.red_dims.end(), dim) == lay.red_dims.end()) lay.red_dims.push_back(dim);
     };
     for (int c = 0; c < n; ++c) {
       if (p->group[c] != SM_ILD_VAR) continue;
@@ -336,21 +370,13 @@ extern "C" int sm_layout_plan(const sm_tensor_desc* tensors, int n_tensors, cons
         const int64_t red = s < ops[c].n_attr ? ops[c].attr[s] : -1;
         auto it = p->load.find({c, s});
         if (it != p->load.end()) {
-          if (it->second.stored_tensor == t && red >= 0) request(it->second.map, it->second.map->shape, red);
+          if (it->second.map && it->second.stored_tensor == t && red >= 0) request(it->second.map, it->second.map->shape, red);
         } else if (ops[c].in[s] == t && red >= 0) {
           request(nullptr, shape, red);
         }
       }
     }
-    if (requested.empty()) continue;
-    std::vector<int64_t> nat(rank, 1);
-    for (int d = rank - 2; d >= 0; --d) nat[d] = nat[d + 1] * shape[d + 1];
-    sm_plan::Layout lay;
-    for (auto& rq : requested) {
-      int dim = rank - 1;
-      for (int d = 0; d < rank; ++d) if (nat[d] <= rq.first && rq.first < nat[d] * shape[d]) { dim = d; break; }
-      if (std::find(lay.red_dims.begin(), lay.red_dims.end(), dim) == lay.red_dims.end()) lay.red_dims.push_back(dim);
-    }
+    if (lay.red_dims.empty()) continue;
     lay.n_copies = std::max(1, ((int)lay.red_dims.size() + k - 1) / k);
     std::vector<int> inner(lay.red_dims.begin(), lay.red_dims.begin() + std::min<size_t>(k, lay.red_dims.size()));
     for (int d = 0; d < rank; ++d) if (std::find(inner.begin(), inner.end(), d) == inner.end()) lay.dim_order.push_back(d);

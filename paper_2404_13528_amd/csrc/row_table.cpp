@@ -1,31 +1,30 @@
-// Per-row offset tables of compiled row programs (the composed index map of paper Sec. 3.2.1 evaluated once,
-// when a plan is built, instead of once per row and kernel launch).
-#include <hip/hip_runtime_api.h>
+// Per-row offset tables of compiled row programs: the composed index map of paper Sec. 3.2.1 evaluated once per
+// call by a small kernel, into the caller's workspace, instead of once per row inside every kernel of the chain.
 #include <cstdint>
-#include <string>
-#include <vector>
+#include "common.h"
 #include "index_map.h"
+#include "kernels.h"
 
 namespace sm {
 
-bool attach_row_table(RowProg* p, int64_t n_rows, std::string* err) {
+void TableRegion::add(RowProg* p, int64_t n_rows, int64_t src_numel) {
   p->table = nullptr;
-  if (p->identity || n_rows <= 0) return true;
-  std::vector<int32_t> host((size_t)n_rows);
-  for (int64_t r = 0; r < n_rows; ++r) {
-    const int64_t off = eval_rows_host(*p, r);
-    if (off < 0 || off > INT32_MAX) return true;         // kernels fall back to interpreting the program
-    host[(size_t)r] = (int32_t)off;
+  p->table_off = 0;
+  if (p->identity || n_rows <= 0 || src_numel > INT32_MAX) return;     // kernels interpret the program
+  p->table_off = (int64_t)bytes + 1;
+  items.push_back({*p, n_rows, bytes});
+  bytes += ((size_t)n_rows * sizeof(int32_t) + 255) & ~(size_t)255;
+}
+
+int fill_tables(const TableRegion& r, void* region, void* stream, uint64_t which) {
+  for (size_t i = 0; i < r.items.size(); ++i) {
+    if (i < 64 && !((which >> i) & 1)) continue;
+    const auto& it = r.items[i];
+    Timed tm("fill_row_table", stream);
+    const int rc = launch_fill_rows(it.prog, it.n_rows, (int32_t*)((char*)region + it.off), stream);
+    if (rc) return fail(SM_ERR_DEVICE, "row-table fill kernel launch failed (hip error %d)", rc);
   }
-  void* dev = nullptr;
-  if (hipMalloc(&dev, host.size() * sizeof(int32_t)) != hipSuccess) { *err = "out of device memory for a row-offset table"; return false; }
-  if (hipMemcpy(dev, host.data(), host.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) {
-    (void)hipFree(dev);
-    *err = "copy of a row-offset table to the device failed";
-    return false;
-  }
-  p->table = (const int32_t*)dev;
-  return true;
+  return SM_OK;
 }
 
 }  // namespace sm
