@@ -340,6 +340,19 @@ size_t sm_swin_block_workspace_bytes(const sm_swin_cfg*, int mode);
 int sm_swin_block(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y,
                   void* ws, size_t ws_bytes, int mode, void* stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): sm_swin_block with the library's own
+ * workspace, a static device array of SM_STATIC_WS_BYTES (one copy per GPU the
+ * library runs on, held until the process ends).  Same arguments, results and
+ * errors as sm_swin_block without ws / ws_bytes; a block that needs more than
+ * the static buffer returns SM_ERR_WORKSPACE and launches nothing.  Calls no
+ * allocating routine.  All calls on one GPU share the buffer: calls that overlap
+ * on one GPU (two streams, two threads) race; calls in stream order do not, and
+ * nothing in the buffer has to be cleared between them. */
+#define SM_STATIC_WS_BYTES (32u << 20)
+size_t sm_swin_block_static_max_bytes(void);
+int sm_swin_block_static(const sm_swin_cfg*, const sm_swin_weights*, const void* x, void* y, int mode, void* stream);
+
 /* The global-attention blocks of Table 7 (a Pythia / Llama-style decoder layer,
  * an SD-UNet spatial transformer) planned and executed the same way (Sec. 3.2):
  * head split / merge permutes and the NCHW <-> token rearrangement become load /

@@ -108,7 +108,8 @@ def lib():
         L = C.CDLL(LIB_PATH, mode=C.RTLD_GLOBAL)
         L.sm_last_error.restype = C.c_char_p
         L.sm_map_numel.restype = C.c_int64
-        for f in ("sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes"):
+        for f in ("sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes",
+                  "sm_swin_block_static_max_bytes"):
             getattr(L, f).restype = C.c_size_t
         _lib = L
     return _lib
@@ -413,6 +414,15 @@ class SwinBlock:
         check(lib().sm_swin_block(C.byref(self.cfg), C.byref(self.w), _ptr(x), _ptr(y), _ptr(self.ws),
                                   C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_swin_block")
         return y
+
+
+def swin_block_static(block, x, out=None, stream=None):
+    """sm_swin_block_static: `block`'s call (a SwinBlock) on the library's static workspace instead of block.ws."""
+    import torch
+    y = torch.empty_like(x) if out is None else out
+    check(lib().sm_swin_block_static(C.byref(block.cfg), C.byref(block.w), _ptr(x), _ptr(y), block.mode, _stream(stream)),
+          "sm_swin_block_static")
+    return y
 
 
 class SwinChain:
