@@ -416,6 +416,26 @@ class SwinBlock:
         return y
 
 
+def swin_block_intermediates(block):
+    """Diagnostic view of an elided SwinBlock's workspace after a call made with fuse_mlp=False (one kernel per
+    surviving operator): the stored intermediates in the layouts the plan gave them.  qkv and o are window-major
+    ([B*nW, N, 3C] / [B*nW, N, C]: LayerNorm-1's store absorbed roll + partition), x1 and hid are in token order."""
+    c = block.cfg
+    T, Cc, N = c.B * c.H * c.W, c.C, c.window * c.window
+    es = 4 if c.dtype == SM_F32 else 2
+    tc = (T * Cc * es + 255) // 256 * 256
+    import torch
+    dt = torch.float32 if c.dtype == SM_F32 else torch.bfloat16
+
+    def view(off_units, shape):
+        n = 1
+        for e in shape:
+            n *= e
+        return block.ws[off_units * tc: off_units * tc + n * es].view(dt).view(*shape)
+    return {"qkv": view(1, (T // N, N, 3 * Cc)), "o": view(4, (T // N, N, Cc)), "x1": view(5, (c.B, c.H * c.W, Cc)),
+            "hid": view(6, (c.B, c.H * c.W, c.mlp_ratio * Cc))}
+
+
 def swin_block_static(block, x, out=None, stream=None):
     """sm_swin_block_static: `block`'s call (a SwinBlock) on the library's static workspace instead of block.ws."""
     import torch

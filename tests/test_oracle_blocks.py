@@ -205,3 +205,24 @@ def test_swin_net_runs_and_matches_stagewise_composition():
     x = swin.swin_block(x, netn["stages"][1][0], 7, 7, 7, 4, 0)
     x = swin.swin_block(x, netn["stages"][1][1], 7, 7, 7, 4, 0)     # 7x7 stage never shifts
     assert np.allclose(O.layer_norm(x, netn["head"]["ln_g"], netn["head"]["ln_b"]), f)
+
+
+def test_swin_net_head_against_torch_library():
+    # the pooled head (LayerNorm, mean over tokens, Linear + bias) re-assembled from torch CPU library routines on
+    # the oracle's own last-stage output, at two weight scales; the logits are compared in value, not in shape
+    for std in (0.02, 0.3):
+        dr = Wl.Draw(seed=3, std=std)
+        x = dr.normal(2, 49, 32).double()
+        hp = {"ln_g": dr.gain(32).double(), "ln_b": dr.weight(32).double(), "w": dr.weight(5, 32).double(), "b": dr.weight(5).double()}
+        f_t = torch.nn.functional.layer_norm(x, (32,), hp["ln_g"], hp["ln_b"], 1e-5)
+        l_t = torch.nn.functional.linear(torch.nn.functional.adaptive_avg_pool1d(f_t.transpose(1, 2), 1).squeeze(-1), hp["w"], hp["b"])
+        net = {"embed": None, "stages": [], "merges": [], "head": {k: v.numpy() for k, v in hp.items()}}
+        # swin_net's tail on a given token tensor: run it with no stages by handing the tokens in as the "embedding"
+        orig = swin.patch_embed
+        swin.patch_embed = lambda img, p, patch: x.numpy()
+        try:
+            f, logits = swin.swin_net(np.zeros((2, 3, 28, 28)), net, 4, 7, ())
+        finally:
+            swin.patch_embed = orig
+        assert np.abs(f - f_t.numpy()).max() < 1e-10 and np.abs(logits - l_t.numpy()).max() < 1e-10
+        assert np.abs(logits).max() > 1e-3          # the comparison is not vacuous

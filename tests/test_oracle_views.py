@@ -114,3 +114,39 @@ def test_patch_embed_unfold_and_nchw_tokens():
     t = V.apply_chain(img, V.nchw_to_tokens_chain(B, Cin, H, W))
     assert t[1, 5, 2] == img[1, 2, 5 // W, 5 % W]
     assert np.array_equal(V.apply_chain(t, V.tokens_to_nchw_chain(B, Cin, H, W)), img)
+
+
+def test_slice_brute_force_and_library():
+    a = np.random.default_rng(1).standard_normal((3, 7, 5))
+    for axis, start, stop, step in [(0, 1, 3, 1), (1, 0, 7, 2), (1, 2, 6, 3), (2, 4, 5, 1), (2, 0, 5, 1)]:
+        got = V.slice_(a, axis, start, stop, step)
+        n = len(range(start, stop, step))
+        assert got.shape == tuple(n if k == axis else s for k, s in enumerate(a.shape))
+        for idx in itertools.product(*[range(s) for s in got.shape]):      # out[.., i, ..] = in[.., start + i*step, ..]
+            src = list(idx)
+            src[axis] = start + idx[axis] * step
+            assert got[idx] == a[tuple(src)]
+        lib = torch.index_select(torch.from_numpy(a), axis, torch.arange(start, stop, step)).numpy()
+        assert np.array_equal(got, lib)
+    # through a chain: the q / k / v split is a slice of the permuted QKV tensor
+    iota = V.index_map((2, 4, 12), [("reshape", (2, 4, 3, 2, 2)), ("permute", (2, 0, 3, 1, 4)), ("slice", 0, 1, 2, 1)])
+    assert iota.shape == (1, 2, 2, 4, 2)
+    assert iota[0, 1, 1, 3, 1] == ((1 * 4 + 3) * 12) + (1 * 2 + 1) * 2 + 1
+
+
+def test_concat_brute_force_and_library():
+    rng = np.random.default_rng(2)
+    parts = [rng.standard_normal((2, k, 3)) for k in (1, 4, 2)]
+    got = V.concat(parts, 1)
+    assert got.shape == (2, 7, 3)
+    at = 0
+    for p in parts:                     # every part lands, in order, at its running offset along the axis
+        for idx in itertools.product(*[range(s) for s in p.shape]):
+            assert got[idx[0], at + idx[1], idx[2]] == p[idx]
+        at += p.shape[1]
+    assert np.array_equal(got, torch.cat([torch.from_numpy(p) for p in parts], 1).numpy())
+    # slice then concat along the same axis is the identity; a roll is a concat of two slices (Table 3: Slice,
+    # Gather are the ILI & Fixed operators a cyclic shift is exported as)
+    a = rng.standard_normal((3, 6))
+    assert np.array_equal(V.concat([V.slice_(a, 1, 0, 2), V.slice_(a, 1, 2, 6)], 1), a)
+    assert np.array_equal(V.concat([V.slice_(a, 1, 2, 6), V.slice_(a, 1, 0, 2)], 1), V.roll(a, 1, -2))
