@@ -1,16 +1,20 @@
 """Benchmark of the layout-elided hot path on one MI355X.
 
-Workload (benchmark configs[1]): Swin stage-3 chain, bf16, B=32, 14x14
-tokens, C=384, 12 heads, window 7, 6 blocks alternating shift 0/3, MLP ratio 4;
-seeded synthetic inputs resident in HBM before the timed region.  One step =
-one pass of the whole chain (13 kernels in elided mode: per block window attention and one kernel for
-proj + residual + LayerNorm + MLP + residual + the next block's LayerNorm and QKV, plus the first block's LayerNorm +
-QKV kernel; the explicit chain runs 30 + 30 copies) over one batch.
+Headline workload (benchmark configs[2], the largest single-GPU one): the full Swin-B-shaped net at 224x224,
+bf16, B=64, patch 4, embed 128, depths (2,2,18,2), heads (4,8,16,32), window 7, patch merging between stages;
+seeded synthetic image and random-init weights, resident in HBM before the timed region.  One step = one pass of
+the whole chain (sm_run_chain, SM_ELIDED) over one batch of 64 images.
 
-Prints ONE JSON line: whole-job throughput (images/s) of the elided chain, the
-explicit-transpose baseline chain timed the same way, per-kernel durations
-measured with HIP events on the launch stream, the roofline of the dominant
-kernel, and the CPU oracle timed on the host cores.
+Prints ONE JSON line.  `value` = images/s of that chain.  `configs` holds, for each of the five configurations of
+the benchmark spec, every variant timed the same way (elided / explicit-transpose chain, and for the Swin chains the
+kernel-per-operator form beside the fused one, so that layout elimination and kernel fusion are reported apart):
+ms per step, throughput, algorithmic HBM bytes, the per-kernel table from HIP events on the launch stream, the
+dominant kernel and its roofline.  `roofline` (top level) is the headline chain's dominant kernel; `cpu_baseline`
+is the CPU oracle on a bounded sample of the headline workload.
+
+  python bench.py                       all five configurations (about two minutes)
+  python bench.py --config 3            one configuration (1-based, as in the benchmark's list)
+  python bench.py --fold-microbench     the read- versus write-side folding micro-experiment (Sec. 3.2.2)
 """
 import argparse
 import json
@@ -24,26 +28,30 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM = 8.0e12          # B/s, MI355X published
 PEAK_BF16 = 2.5e15         # FLOP/s dense bf16 MFMA, MI355X published
-
-# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (bytes, scaled by the
-# calibration against an identity copy of known size, --calibrate-copy); filled from profiles/, None = not measured.
-MEASURED_TRAFFIC = {
-    # profiles/swin_stage3_chain_b32_hbm_counters.md: (FETCH_SIZE KiB x 2.000 + WRITE_SIZE KiB x 1.000) x 1024
-    "proj+ln+mlp_bf16[6272,1536,384]+ln+qkv": int((18726.1 * 2.0 + 18816.1) * 1024),
-    "proj+ln+mlp_bf16[6272,1536,384]": int((15194.2 * 2.0 + 4704.0) * 1024),
-    "ln+mlp_bf16[6272,1536,384]": int((11666.8 * 2.0 + 4704.0) * 1024),
-    "ln+pgemm_bf16[6272,1152,384]": int((5892.6 * 2.0 + 14115.9) * 1024),
-    "gemm_bf16[6272,1152,384]": int((6443.5 * 2.0 + 14114.2) * 1024),
-    "gemm_bf16[6272,384,384]+res": int((3784.5 * 2.0 + 4704.0) * 1024),
-    "attention_window_bf16[128,12,49,49,32]": int((7137.5 * 2.0 + 4704.0) * 1024),
-    "layernorm_bf16[6272,384]+scatter": int((2432.1 * 2.0 + 4704.0) * 1024),
-    "layernorm_bf16[6272,384]": int((2432.1 * 2.0 + 4704.0) * 1024),
-}
+PEAK_F32 = 157.3e12        # FLOP/s fp32 (matrix and vector), MI355X published
 
 
-def kernel_model(label, e=2):
-    """Algorithmic bytes and flops of one launch, from the kernel label (tensor reads + writes at
-    kernel-per-op granularity with fused epilogues; weights and bias included)."""
+def measured_traffic():
+    """HBM bytes per launch from the committed rocprofv3 --pmc summaries (profiles/*_hbm_counters.md): table rows
+    `| bench label | FETCH_SIZE KiB | WRITE_SIZE KiB | bytes |`, bytes = the two counters scaled by what they read for
+    an identity copy of known size (factors stated in each file)."""
+    out = {}
+    pdir = os.path.join(ROOT, "profiles")
+    for f in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not f.endswith("_hbm_counters.md"):
+            continue
+        for line in open(os.path.join(pdir, f)):
+            m = re.match(r"\|\s*`([^`]+)`\s*\|\s*([\d.]+)\s*\|\s*([\d.]+)\s*\|\s*(\d+)\s*\|", line)
+            if m:
+                out[m.group(1)] = int(m.group(4))
+    return out
+
+
+def kernel_model(label):
+    """Algorithmic bytes and flops of one launch, from the kernel's timing label: tensor reads + writes at
+    kernel-per-operator granularity with fused epilogues, weights and bias included; flops 2MNK for a Linear,
+    4 nq nk d per (batch, head) for attention (halved when causal)."""
+    e = 4 if "_f32" in label else 2
     m = re.match(r"(proj\+)?(ln\+)?mlp_\w+\[(\d+),(\d+),(\d+)\](\+ln)?(\+qkv)?", label)
     if m:      # fused MLP: X and the residual read, Y written, both weights, biases (and the norm's vectors);
         #        with the projection in front: its [C, C] weight and bias as well (A, x0 read, Y written);
@@ -66,7 +74,7 @@ def kernel_model(label, e=2):
     if m:
         R, C = int(m.group(2)), int(m.group(3))
         return (2 * R * C + 2 * C) * e, 8.0 * R * C
-    m = re.match(r"attention_(\w+)_\w+\[(\d+),(\d+),(\d+),(\d+),(\d+)\]", label)
+    m = re.match(r"attention_(\w+?)_\w+\[(\d+),(\d+),(\d+),(\d+),(\d+)\]", label)
     if m:
         nb, h, nq, nk, d = [int(m.group(i)) for i in range(2, 7)]
         fl = 4.0 * nb * h * nq * nk * d * (0.5 if m.group(1) == "causal" else 1.0)
@@ -75,7 +83,31 @@ def kernel_model(label, e=2):
     if m:
         n = int(m.group(1))
         return (3 if "+add" in m.group(2) else 2) * n * e, 0.0
+    m = re.match(r"groupnorm_\w+\[(\d+),(\d+),(\d+),(\d+)\]", label)
+    if m:      # statistics pass reads x, apply pass reads x and writes y
+        B, C, HW = int(m.group(1)), int(m.group(2)), int(m.group(3))
+        return 3 * B * C * HW * e, 10.0 * B * C * HW
+    m = re.match(r"mean_tokens_\w+\[(\d+),(\d+),(\d+)\]", label)
+    if m:
+        B, L, C = int(m.group(1)), int(m.group(2)), int(m.group(3))
+        return (B * L * C + B * C) * e, float(B * L * C)
+    m = re.match(r"fill_row_table\[(\d+)\]", label)
+    if m:
+        return 4 * int(m.group(1)), 0.0
     return 0, 0.0
+
+
+def roofline_of(row, traffic):
+    peak_f = PEAK_F32 if "_f32" in row["kernel"] else PEAK_BF16
+    t_hbm, t_mfma = row["alg_bytes"] / PEAK_HBM, row["flops"] / peak_f
+    if t_mfma >= t_hbm:
+        r = {"bound": "mfma", "achieved": row["TFLOPs"], "peak": peak_f * 1e-12, "unit": "TFLOP/s"}
+    else:
+        r = {"bound": "hbm", "achieved": row["GBps"], "peak": PEAK_HBM * 1e-9, "unit": "GB/s"}
+    r["frac"] = round(r["achieved"] / r["peak"], 4)
+    r["traffic"] = traffic.get(row["kernel"])
+    r["kernel"], r["avg_us"] = row["kernel"], row["avg_us"]
+    return r
 
 
 def fold_microbench(sm, torch, steps, warmup):
@@ -129,22 +161,133 @@ def fold_microbench(sm, torch, steps, warmup):
     return out
 
 
+SWIN_B = dict(depths=(2, 2, 18, 2), heads=(4, 8, 16, 32), embed=128, img=224, w=7)
+
+
+def build_config(k, sm, torch, Wl):
+    """-> (description, unit, units per step, {variant name: callable running one step}, oracle sample or None).
+    Variants: "elided" and "explicit" always; Swin chains add "elided_per_op" / "explicit_per_op" (one kernel per
+    surviving operator, fuse_mlp=False) so that elimination (per_op pair) and fusion (elided vs elided_per_op) are
+    measured apart."""
+    bf = torch.bfloat16
+    dev = lambda p, dt: {n: v.to(dt).cuda() for n, v in p.items()}
+    if k == 1:
+        B, H, W, C, h, w, s = 1, 56, 56, 96, 3, 7, 3
+        x, p = Wl.swin_block_case(B, H, W, C, h, w, seed=0)
+        dp, xd = dev(p, torch.float32), x.cuda()
+        y = torch.empty_like(xd)
+        blk = {n: sm.SwinBlock(B, H, W, C, h, w, s, dp, torch.float32, m) for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
+        return ("configs[0]: one Swin block, fp32, B=1, 56x56 tokens, C=96, 3 heads, window 7, shift 3", "images/s", B,
+                {n: (lambda b=b: b(xd, out=y)) for n, b in blk.items()}, None, "f32")
+    if k == 2:
+        B, H, W, C, h, w, depth = 32, 14, 14, 384, 12, 7, 6
+        x, blocks = Wl.swin_stage_case(B, H, W, C, h, w, depth)
+        net = {"stages": [[dev(p, bf) for p in blocks]]}
+        xd = x.to(bf).cuda()
+        y = torch.empty_like(xd)
+        var = {}
+        for n, m, f in (("elided", sm.SM_ELIDED, True), ("explicit", sm.SM_EXPLICIT, True),
+                        ("elided_per_op", sm.SM_ELIDED, False), ("explicit_per_op", sm.SM_EXPLICIT, False)):
+            ch = sm.SwinChain(B, [(C, h, depth, H, W)], w, net, bf, m, fuse_mlp=f)
+            var[n] = (lambda ch=ch: ch(xd, out=y))
+        return ("configs[1]: Swin stage-3 chain, bf16, B=32, 14x14 tokens, C=384, 12 heads, window 7, 6 blocks shift 0/3, MLP 4x",
+                "images/s", B, var, None, "bf16")
+    if k == 3:
+        B = 64
+        image, net = Wl.swin_net_case(B, img=SWIN_B["img"], embed=SWIN_B["embed"], depths=SWIN_B["depths"], heads=SWIN_B["heads"], w=SWIN_B["w"])
+        dnet = {"embed": dev(net["embed"], bf), "stages": [[dev(p, bf) for p in st] for st in net["stages"]],
+                "merges": [dev(m, bf) for m in net["merges"]], "head": dev(net["head"], bf)}
+        stages, H, C = [], SWIN_B["img"] // 4, SWIN_B["embed"]
+        for dep, hh in zip(SWIN_B["depths"], SWIN_B["heads"]):
+            stages.append((C, hh, dep, H, H))
+            H, C = H // 2, C * 2
+        xd = image.to(bf).cuda()
+        var = {}
+        for n, m, f in (("elided", sm.SM_ELIDED, True), ("explicit", sm.SM_EXPLICIT, True),
+                        ("elided_per_op", sm.SM_ELIDED, False), ("explicit_per_op", sm.SM_EXPLICIT, False)):
+            ch = sm.SwinChain(B, stages, SWIN_B["w"], dnet, bf, m, img=SWIN_B["img"], n_cls=1000, fuse_mlp=f)
+            y = torch.empty(B, 1000, dtype=bf, device="cuda")
+            var[n] = (lambda ch=ch, y=y: ch(xd, out=y))
+        return ("configs[2]: full Swin-B-shaped net at 224x224, bf16, B=64, patch 4, embed 128, depths (2,2,18,2), heads (4,8,16,32), "
+                "window 7, patch merging, head 1000 classes", "images/s", B, var, (image, net), "bf16")
+    if k == 4:
+        B, S, E, h, F = 1, 2048, 4096, 32, 11008
+        x, p = Wl.llama_case(B, S, E, F)
+        dp, xd = dev(p, bf), x.to(bf).cuda()
+        y = torch.empty_like(xd)
+        blk = {n: sm.AttnBlock("llama", dp, bf, m, B=B, S=S, E=E, heads=h, F=F) for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
+        return ("configs[3]: Llama-style decoder layer prefill, bf16, B=1, seq 2048, hidden 4096, 32 heads x 128, RoPE, causal, SwiGLU 11008",
+                "tokens/s", B * S, {n: (lambda b=b: b(xd, out=y)) for n, b in blk.items()}, None, "bf16")
+    if k == 5:
+        B, C, H, W, Sc, Dc, F, G, h = 2, 320, 64, 64, 77, 768, 1280, 32, 8
+        x, ctx, p = Wl.sd_case(B, C, H, W, Sc, Dc, F)
+        dp, xd, cd = dev(p, bf), x.to(bf).cuda(), ctx.to(bf).cuda()
+        y = torch.empty_like(xd)
+        blk = {n: sm.AttnBlock("sd", dp, bf, m, B=B, E=C, heads=h, F=F, Hs=H, Ws=W, groups=G, Sc=Sc, Dc=Dc)
+               for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
+        return ("configs[4]: diffusion-UNet spatial transformer block, bf16, B=2, latent 64x64x320 NCHW, GroupNorm 32, self-attn 8 heads "
+                "over 4096 tokens, cross-attn to 77x768, GEGLU 1280", "images/s", B,
+                {n: (lambda b=b: b(xd, cd, out=y)) for n, b in blk.items()}, None, "bf16")
+    raise ValueError(k)
+
+
+def measure(run, steps, warmup, sm, torch, traffic):
+    """Times `steps` calls between two synchronisations, then the same calls with per-launch HIP events."""
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    ev_steps = min(steps, 20)
+    sm.timing_enable(True)
+    for _ in range(ev_steps):
+        run()
+    sm.timing_calibrate(64)        # what an event pair adds to a kernel's own run time
+    torch.cuda.synchronize()
+    rep = sm.timing_report()
+    sm.timing_enable(False)
+    n, ms = rep.pop("empty_kernel")
+    n2, ms2 = rep.pop("empty_pair")
+    calib = {"empty_kernel_us": round(ms / n * 1e3, 3), "empty_pair_us": round(ms2 / n2 * 1e3, 3)}
+    # avg_us: HIP-event time around each launch on the launch stream.  It contains the dispatch and the event records
+    # themselves: a profiler's kernel duration is 2 to 3 us shorter (event_calibration: an event pair around an empty
+    # kernel and around nothing)
+    rows = []
+    for label, (n, ms) in rep.items():
+        by, fl = kernel_model(label)
+        us = ms / n * 1e3
+        rows.append({"kernel": label, "launches_per_step": round(n / ev_steps, 2), "avg_us": round(us, 3), "alg_bytes": by, "flops": fl,
+                     "GBps": round(by / us * 1e-3, 1), "TFLOPs": round(fl / us * 1e-6, 1)})
+    dom = max(rows, key=lambda r: r["avg_us"] * r["launches_per_step"])
+    return {"ms_per_step": round(sec * 1e3, 4),
+            "alg_bytes_per_step": int(sum(r["alg_bytes"] * r["launches_per_step"] for r in rows)),
+            "flops_per_step": sum(r["flops"] * r["launches_per_step"] for r in rows),
+            "launches_per_step": round(sum(r["launches_per_step"] for r in rows), 1),
+            "kernel_us_per_step": round(sum(r["avg_us"] * r["launches_per_step"] for r in rows), 2),
+            "roofline": roofline_of(dom, traffic), "event_calibration": calib, "kernels": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json; 0 = all five")
+    ap.add_argument("--variants", default="", help="comma-separated subset of the variants (elided, explicit, elided_per_op, explicit_per_op)")
+    ap.add_argument("--kernels", action="store_true", help="include every variant's per-kernel table in the JSON line (long)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an identity sm_gather_mapped copy of 256 MiB three times (counter calibration for rocprofv3 --pmc)")
     ap.add_argument("--fold-microbench", action="store_true",
-                    help="instead of the chain: the read-versus-write folding micro-experiment of Sec. 3.2.2 on the mapped Linear")
+                    help="instead of the chains: the read-versus-write folding micro-experiment of Sec. 3.2.2 on the mapped Linear")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % a.gpus, file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_2404_13528_amd import binding as sm, workloads as Wl
 
@@ -152,115 +295,84 @@ def main():
         print(json.dumps(fold_microbench(sm, torch, a.steps, a.warmup)))
         return
 
-    B, H, W, C, h, w, depth = 32, 14, 14, 384, 12, 7, 6
-    dtype = torch.bfloat16
-    x, blocks = Wl.swin_stage_case(B, H, W, C, h, w, depth)
-    dev_blocks = [{k: v.to(dtype).cuda() for k, v in p.items()} for p in blocks]
-    xd = x.to(dtype).cuda()
-    chains = {name: sm.SwinChain(B, [(C, h, depth, H, W)], w, {"stages": [dev_blocks]}, dtype, mode)
-              for name, mode in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
-    y = torch.empty_like(xd)
-    stream = torch.cuda.current_stream()
-
-    def timed(chain):
-        for _ in range(a.warmup):
-            chain(xd, out=y, stream=stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(a.steps):
-            chain(xd, out=y, stream=stream)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / a.steps
-
-    def kernels(chain):
-        sm.timing_enable(True)
-        for _ in range(a.steps):
-            chain(xd, out=y, stream=stream)
-        sm.timing_calibrate(64, stream=stream)        # what an event pair adds to a kernel's own run time
-        torch.cuda.synchronize()
-        rep = sm.timing_report()
-        sm.timing_enable(False)
-        n, ms = rep.pop("empty_kernel")
-        n2, ms2 = rep.pop("empty_pair")
-        return rep, {"empty_kernel_us": round(ms / n * 1e3, 3), "empty_pair_us": round(ms2 / n2 * 1e3, 3)}
-
     if a.calibrate_copy:
         n = 128 * 1024 * 1024                         # bf16 elements: 256 MiB read + 256 MiB written per launch
-        src = torch.zeros(n, dtype=dtype, device="cuda")
+        src = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
         ident = sm.Map.create((n // 1024, 1024), [])
         for _ in range(3):
-            ident.gather(src.view(n // 1024, 1024), stream=stream)
+            ident.gather(src.view(n // 1024, 1024))
         torch.cuda.synchronize()
         del src
 
-    sec = {name: timed(c) for name, c in chains.items()}
-    rep, overhead_us = {}, {}
-    for name, c in chains.items():
-        rep[name], overhead_us[name] = kernels(c)
+    traffic = measured_traffic()
+    HEAD = 3
+    which = [a.config] if a.config else [3, 1, 2, 4, 5]
+    want = [v for v in a.variants.split(",") if v]
+    configs, oracle_sample, calib = {}, None, None
+    for k in which:
+        desc, unit, units, variants, sample, dtype = build_config(k, sm, torch, Wl)
+        if sample is not None:
+            oracle_sample = sample
+        entry = {"workload": desc, "unit": unit, "dtype": dtype, "variants": {}}
+        for name, run in variants.items():
+            if want and name not in want:
+                continue
+            r = measure(run, a.steps, a.warmup, sm, torch, traffic)
+            r["value"] = round(units / (r["ms_per_step"] * 1e-3), 1)
+            calib = r.pop("event_calibration")
+            if not a.kernels:
+                del r["kernels"]
+            entry["variants"][name] = r
+        v = entry["variants"]
+        if "elided" in v and "explicit" in v:
+            entry["elided_vs_explicit"] = {"speedup": round(v["explicit"]["ms_per_step"] / v["elided"]["ms_per_step"], 3),
+                                           "alg_bytes_ratio": round(v["explicit"]["alg_bytes_per_step"] / v["elided"]["alg_bytes_per_step"], 3)}
+        if "elided_per_op" in v and "explicit_per_op" in v:     # layout elimination alone (Sec. 4.3's breakdown): same kernels, copies removed
+            entry["elimination_only"] = {"speedup": round(v["explicit_per_op"]["ms_per_step"] / v["elided_per_op"]["ms_per_step"], 3),
+                                         "alg_bytes_ratio": round(v["explicit_per_op"]["alg_bytes_per_step"] / v["elided_per_op"]["alg_bytes_per_step"], 3)}
+        if "elided" in v and "elided_per_op" in v:               # what the deeper fusion adds on top of elimination
+            entry["fusion_on_top"] = {"speedup": round(v["elided_per_op"]["ms_per_step"] / v["elided"]["ms_per_step"], 3),
+                                      "alg_bytes_ratio": round(v["elided_per_op"]["alg_bytes_per_step"] / v["elided"]["alg_bytes_per_step"], 3)}
+        configs["config%d" % k] = entry
+        del variants
+        torch.cuda.empty_cache()
 
-    def table(r):
-        # avg_us: HIP-event time around each launch on the launch stream.  It contains the dispatch and the event
-        # records themselves: a profiler's kernel duration is 2.5 to 3 us shorter (see event_calibration below for
-        # what an event pair measures around an empty kernel and around nothing)
-        rows = []
-        for label, (n, ms) in r.items():
-            by, fl = kernel_model(label)
-            us = ms / n * 1e3
-            rows.append({"kernel": label, "launches_per_step": n // a.steps, "avg_us": round(us, 3),
-                         "alg_bytes": by, "flops": fl,
-                         "GBps": round(by / us * 1e-3, 1), "TFLOPs": round(fl / us * 1e-6, 1)})
-        return rows
-
-    tab = table(rep["elided"])
-    dom = max(tab, key=lambda r: r["avg_us"] * r["launches_per_step"])
-    t_hbm, t_mfma = dom["alg_bytes"] / PEAK_HBM, dom["flops"] / PEAK_BF16
-    if t_mfma >= t_hbm:
-        roof = {"bound": "mfma", "achieved": dom["TFLOPs"], "peak": PEAK_BF16 * 1e-12, "unit": "TFLOP/s"}
-    else:
-        roof = {"bound": "hbm", "achieved": dom["GBps"], "peak": PEAK_HBM * 1e-9, "unit": "GB/s"}
-    roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
-    roof["traffic"] = MEASURED_TRAFFIC.get(dom["kernel"])
-    roof["kernel"] = dom["kernel"]
-    roof["avg_us"] = dom["avg_us"]
-
-    alg_bytes = {name: sum(kernel_model(l)[0] * (n // a.steps) for l, (n, _) in r.items()) for name, r in rep.items()}
-    kern_us = {name: sum(ms for _, ms in r.values()) / a.steps * 1e3 for name, r in rep.items()}
-
+    hk = HEAD if ("config%d" % HEAD) in configs else which[0]
+    head = configs["config%d" % hk]
+    hv = head["variants"].get("elided") or next(iter(head["variants"].values()))
     out = {
         "metric": "Swin/attention block images(tokens)/s + HBM bytes vs explicit-transpose chain",
-        "value": round(B / sec["elided"], 1), "unit": "images/s",
+        "value": hv["value"], "unit": head["unit"],
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": round(sec["elided"] * 1e3, 4),
+        "ms_per_step": hv["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: Swin stage-3 chain, B=32, 14x14 tokens, C=384, 12 heads, window 7, "
-                               "6 blocks shift 0/3, MLP 4x", "mode": "elided", "global_batch": B},
-        "explicit_chain": {"images_per_s": round(B / sec["explicit"], 1), "ms_per_step": round(sec["explicit"] * 1e3, 4),
-                           "alg_bytes_per_step": alg_bytes["explicit"], "kernel_us_per_step": round(kern_us["explicit"], 2)},
-        "elided_chain": {"alg_bytes_per_step": alg_bytes["elided"], "kernel_us_per_step": round(kern_us["elided"], 2),
-                         "speedup_vs_explicit": round(sec["explicit"] / sec["elided"], 3),
-                         "bytes_ratio_explicit_over_elided": round(alg_bytes["explicit"] / alg_bytes["elided"], 3)},
-        "roofline": roof,
-        "event_calibration": overhead_us["elided"],
-        "kernels": tab,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "mode": "elided"},
+        "roofline": hv["roofline"],
+        "event_calibration": calib,
+        "alg_bytes_are": "modelled from the shapes (kernel_model), not counters; roofline.traffic is the counter figure where profiles/ has one",
+        "configs": configs,
     }
 
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and oracle_sample is not None:
         from oracle import swin
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count()
-        xn = x.double().numpy()
-        pn = [{k: v.double().numpy() for k, v in p.items()} for p in blocks]
-        reps, t0 = 0, time.perf_counter()
-        while reps < 2 or time.perf_counter() - t0 < 10.0:          # about 10 s of host work
-            swin.swin_stage(xn, pn, H, W, w, h)
-            reps += 1
+        image, net = oracle_sample
+        nn = {"embed": {k: v.double().numpy() for k, v in net["embed"].items()},
+              "stages": [[{k: v.double().numpy() for k, v in p.items()} for p in st] for st in net["stages"]],
+              "merges": [{k: v.double().numpy() for k, v in m.items()} for m in net["merges"]],
+              "head": {k: v.double().numpy() for k, v in net["head"].items()}}
+        n_img, t0 = 0, time.perf_counter()
+        while n_img < 2 or (time.perf_counter() - t0 < 12.0 and n_img < 64):          # about 12 s of host work
+            swin.swin_net(image[n_img:n_img + 2].double().numpy(), nn, 4, SWIN_B["w"], SWIN_B["heads"])
+            n_img += 2
         dt = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(B * reps / dt, 2), "unit": "images/s", "cores": cores, "kind": "oracle",
-                               "sample": "the full workload %d times (32 images through 6 blocks each), float64 numpy, %.2f s" % (reps, dt)}
+        out["cpu_baseline"] = {"value": round(n_img / dt, 3), "unit": "images/s", "cores": cores, "kind": "oracle",
+                               "sample": "%d of the 64 images of the headline workload through the whole net, two at a time, float64 numpy, %.2f s" % (n_img, dt)}
     print(json.dumps(out))
 
 

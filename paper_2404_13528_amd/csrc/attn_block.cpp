@@ -338,7 +338,9 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
   const int Sc = c->Sc;
   GroupNormArgs ga{x, w[0], w[1], el ? o : extra, B, E, S, c->groups, c->eps_gn, el ? 1 : 0, dt, (float*)(kvp + z.ctx)};
   {
-    Timed tm("groupnorm", stream);
+    char label[64];
+    snprintf(label, sizeof(label), "groupnorm_bf16[%d,%d,%d,%d]", B, E, S, c->groups);
+    Timed tm(label, stream);
     int lrc = launch_groupnorm(ga, stream);
     if (lrc) return fail(SM_ERR_DEVICE, "sm_attn_block: GroupNorm launch failed (hip error %d)", lrc);
   }

@@ -690,7 +690,9 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
     if ((rc = run_norm(cur, wp[0], wp[1], feat, (int64_t)c->B * L, st.C, c->eps, 0, dt, nullptr, 1, nullptr, stream))) return rc;
     void* pooled = blk_ws;
     int lrc;
-    { Timed tm("mean_tokens", stream); lrc = launch_mean_tokens(feat, pooled, c->B, L, st.C, dt, stream); }
+    char label[64];
+    snprintf(label, sizeof(label), "mean_tokens_%s[%d,%d,%d]", dt == SM_F32 ? "f32" : "bf16", c->B, L, st.C);
+    { Timed tm(label, stream); lrc = launch_mean_tokens(feat, pooled, c->B, L, st.C, dt, stream); }
     if (lrc) return fail(SM_ERR_DEVICE, "sm_run_chain: mean launch failed (hip error %d)", lrc);
     count_compute();
     if ((rc = run_gemm(pooled, wp[2], wp[3], nullptr, y, c->B, c->n_cls, st.C, dt, SM_ACT_NONE, nullptr, nullptr, stream))) return rc;

@@ -1,6 +1,7 @@
 // Per-row offset tables of compiled row programs: the composed index map of paper Sec. 3.2.1 evaluated once per
 // call by a small kernel, into the caller's workspace, instead of once per row inside every kernel of the chain.
 #include <cstdint>
+#include <cstdio>
 #include "common.h"
 #include "index_map.h"
 #include "kernels.h"
@@ -20,7 +21,9 @@ int fill_tables(const TableRegion& r, void* region, void* stream, uint64_t which
   for (size_t i = 0; i < r.items.size(); ++i) {
     if (i < 64 && !((which >> i) & 1)) continue;
     const auto& it = r.items[i];
-    Timed tm("fill_row_table", stream);
+    char label[48];
+    snprintf(label, sizeof(label), "fill_row_table[%lld]", (long long)it.n_rows);
+    Timed tm(label, stream);
     const int rc = launch_fill_rows(it.prog, it.n_rows, (int32_t*)((char*)region + it.off), stream);
     if (rc) return fail(SM_ERR_DEVICE, "row-table fill kernel launch failed (hip error %d)", rc);
   }
