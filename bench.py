@@ -231,8 +231,17 @@ def build_config(k, sm, torch, Wl):
     raise ValueError(k)
 
 
-def measure(run, steps, warmup, sm, torch, traffic):
-    """Times `steps` calls between two synchronisations, then the same calls with per-launch HIP events."""
+def measure(run, steps, warmup, sm, torch, traffic, tune):
+    """Times `steps` calls between two synchronisations, then the same calls with per-launch HIP events.  tune: first
+    one labelled pass to learn the chain's Linear shapes and the tuner on each of them (outside the timed region)."""
+    tuned = None
+    if tune:
+        sm.timing_enable(True)
+        run()
+        torch.cuda.synchronize()
+        labels = list(sm.timing_report().keys())
+        sm.timing_enable(False)
+        tuned = [t for t in sm.autotune_from_labels(labels, iters=10) if t["tile_rows"]]
     for _ in range(warmup):
         run()
     torch.cuda.synchronize()
@@ -267,7 +276,9 @@ def measure(run, steps, warmup, sm, torch, traffic):
             "flops_per_step": sum(r["flops"] * r["launches_per_step"] for r in rows),
             "launches_per_step": round(sum(r["launches_per_step"] for r in rows), 1),
             "kernel_us_per_step": round(sum(r["avg_us"] * r["launches_per_step"] for r in rows), 2),
-            "roofline": roofline_of(dom, traffic), "event_calibration": calib, "kernels": rows}
+            "roofline": roofline_of(dom, traffic), "event_calibration": calib, "kernels": rows,
+            "tuned_linears": None if tuned is None else [{"shape": list(t["shape"]), "tile_rows": t["tile_rows"], "stages": t["stages"],
+                                                          "us": t["best_us"], "default_us": t["default_us"]} for t in tuned]}
 
 
 def main():
@@ -278,6 +289,8 @@ def main():
     ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json; 0 = all five")
     ap.add_argument("--variants", default="", help="comma-separated subset of the variants (elided, explicit, elided_per_op, explicit_per_op)")
     ap.add_argument("--kernels", action="store_true", help="include every variant's per-kernel table in the JSON line (long)")
+    ap.add_argument("--no-autotune", action="store_true",
+                    help="skip the tuner (sm_linear_autotune on every tiled-Linear shape of a chain before it is timed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an identity sm_gather_mapped copy of 256 MiB three times (counter calibration for rocprofv3 --pmc)")
@@ -317,7 +330,7 @@ def main():
         for name, run in variants.items():
             if want and name not in want:
                 continue
-            r = measure(run, a.steps, a.warmup, sm, torch, traffic)
+            r = measure(run, a.steps, a.warmup, sm, torch, traffic, not a.no_autotune)
             r["value"] = round(units / (r["ms_per_step"] * 1e-3), 1)
             calib = r.pop("event_calibration")
             if not a.kernels:

@@ -422,6 +422,18 @@ int sm_timing_report(char* buf, int n);
  * kernel's own execution time (dispatch and completion), to be subtracted when comparing with a profiler. */
 int sm_timing_calibrate(int n, void* stream);
 
+/* The tuner (Sec. 3.3 "Other optimizations": the paper tunes block dimensions, unrolling and tiling with a genetic
+ * search; this kernel's space is small enough to walk completely).  Times every (tile height x pipeline stages)
+ * variant of the tiled Linear on the caller's operands (device pointers as for sm_linear, identity maps), `iters`
+ * launches each between two HIP events on `stream`, and remembers the fastest for the shape (M, N, K, dtype,
+ * epilogue): every later sm_linear / executor launch of that shape in this process uses it.  A set-up call like
+ * sm_linear_pack, and unlike the other entry points it creates events and SYNCHRONISES with the stream; C is
+ * overwritten with the Linear's result.  *tile_rows = *stages = 0: the built-in choice won (a variant has to be 3 %
+ * faster) or the shape has a single variant (fp32, K not a multiple of 64).  sm_linear_autotune_clear forgets all. */
+int sm_linear_autotune(const sm_linear_desc*, const void* A, const void* W, const void* bias, const void* residual,
+                       void* C, int iters, void* stream, int* tile_rows, int* stages, float* best_us, float* default_us);
+void sm_linear_autotune_clear(void);
+
 /* Tuning hook for benchmarks: overrides the tile and pipeline choice of the bf16 Linear kernel for the calling
  * process.  tile_rows: 0 (automatic), 64, 128 or 256 output rows per workgroup; stages: 0 (automatic) or 2..4
  * K-tiles resident in LDS.  Returns SM_ERR_INVALID_ARG for other values.  Results do not depend on the choice. */

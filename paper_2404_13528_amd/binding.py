@@ -325,6 +325,48 @@ class MlpDesc(C.Structure):
                 ("proj_packed", C.c_void_p), ("proj_bias", C.c_void_p), ("proj_residual", C.c_void_p)]
 
 
+def linear_autotune(M, N, K, act="none", residual=False, rope=None, dtype=None, iters=20, stream=None):
+    """sm_linear_autotune on scratch operands of the given shape (values do not affect the timing): the fastest tile
+    variant is remembered by the library for every later Linear of that shape.  Returns a dict."""
+    import torch
+    dt = torch.bfloat16 if dtype is None else dtype
+    g = torch.Generator(device="cpu").manual_seed(1)
+    A = (torch.randn(M, K, generator=g) * 0.5).to(dt).cuda()
+    W = (torch.randn(N, K, generator=g) * K ** -0.5).to(dt).cuda()
+    n_out = N // 2 if act in ("swiglu", "geglu") else N
+    bias = torch.zeros(N, dtype=dt, device="cuda")
+    R = torch.zeros(M, n_out, dtype=dt, device="cuda") if residual else None
+    Cm = torch.empty(M, n_out, dtype=dt, device="cuda")
+    d = LinearDesc()
+    d.M, d.N, d.K, d.dtype, d.act = M, N, K, _dt(A), ACT[act]
+    if rope:
+        d.rope_cols, d.rope_dim, d.rope_seq, d.rope_base = rope
+    rows, stages, best, default = C.c_int(), C.c_int(), C.c_float(), C.c_float()
+    check(lib().sm_linear_autotune(C.byref(d), _ptr(A), _ptr(W), _ptr(bias), _ptr(R), _ptr(Cm), int(iters), _stream(stream),
+                                   C.byref(rows), C.byref(stages), C.byref(best), C.byref(default)), "sm_linear_autotune")
+    return {"shape": (M, N, K), "act": act, "residual": residual, "tile_rows": rows.value, "stages": stages.value,
+            "best_us": round(best.value, 2), "default_us": round(default.value, 2)}
+
+
+def autotune_from_labels(labels, iters=20):
+    """Tunes every distinct tiled-Linear shape among the kernel labels of a timing report (sm.timing_report() keys:
+    `gemm_bf16[M,N,K]+gelu+res...`): the way to tune a whole chain without knowing how its executor is built."""
+    import re
+    seen, out = set(), []
+    for l in labels:
+        m = re.match(r"gemm_bf16\[(\d+),(\d+),(\d+)\](.*)", l)
+        if not m:
+            continue
+        M, N, K, tail = int(m.group(1)), int(m.group(2)), int(m.group(3)), m.group(4)
+        key = (M, N, K, "+gelu" in tail, "+glu" in tail, "+res" in tail)
+        if key in seen or K % 64:
+            continue
+        seen.add(key)
+        act = "gelu" if "+gelu" in tail else ("swiglu" if "+glu" in tail else "none")
+        out.append(linear_autotune(M, N, K, act=act, residual="+res" in tail, iters=iters))
+    return out
+
+
 def mlp_pack(W1, W2, out=None, stream=None):
     """W1 [hidden, C] and W2 [C, hidden] in the fused MLP kernel's operand order (one tensor of 2 * hidden * C)."""
     import torch

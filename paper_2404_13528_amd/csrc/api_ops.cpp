@@ -302,6 +302,27 @@ extern "C" int sm_attention(const sm_attention_desc* d, const void* q, const voi
   return attention_checked(*d, q, k, v, o, rpb_table, stream, "sm_attention");
 }
 
+extern "C" int sm_linear_autotune(const sm_linear_desc* d, const void* A, const void* W, const void* bias, const void* residual,
+                                  void* C, int iters, void* stream, int* tile_rows, int* stages, float* best_us, float* default_us) {
+  if (!d || !tile_rows || !stages || !best_us || !default_us) return fail(SM_ERR_INVALID_ARG, "sm_linear_autotune: null pointer");
+  if (iters < 1 || iters > 1000) return fail(SM_ERR_INVALID_ARG, "sm_linear_autotune: iters must be 1..1000");
+  if (d->w_packed || d->norm || d->c_transposed) return fail(SM_ERR_UNSUPPORTED, "sm_linear_autotune: the plain tiled Linear only (no packed weight, folded norm or transposed store)");
+  // one ordinary, fully checked call first: bad arguments are refused here and nothing below runs on them
+  int rc = sm_linear(d, A, W, bias, residual, C, nullptr, nullptr, stream);
+  if (rc) return rc;
+  GemmArgs g; std::memset(&g, 0, sizeof(g));
+  g.A = A; g.W = W; g.bias = bias; g.residual = residual; g.C = C;
+  g.M = d->M; g.N = d->N; g.K = d->K; g.dtype = d->dtype; g.act = d->act;
+  g.rope_cols = d->rope_cols; g.rope_dim = d->rope_dim; g.rope_seq = d->rope_seq; g.rope_base = d->rope_base; g.ldw = d->K;
+  const int n_out = (d->act == SM_ACT_SWIGLU || d->act == SM_ACT_GEGLU) ? d->N / 2 : d->N;
+  g.a_rows = identity_rows(d->K); g.c_rows = identity_rows(n_out);
+  rc = sm::gemm_autotune(g, iters, stream, tile_rows, stages, best_us, default_us);
+  if (rc == -2) { *tile_rows = *stages = 0; *best_us = *default_us = 0.f; return SM_OK; }      // a shape with one variant: nothing to choose
+  if (rc) return fail(SM_ERR_DEVICE, "sm_linear_autotune: timing failed (hip error %d)", rc);
+  return SM_OK;
+}
+extern "C" void sm_linear_autotune_clear(void) { sm::gemm_autotune_clear(); }
+
 extern "C" int sm_gemm_tuning(int tile_rows, int stages) {
   if (sm::gemm_tuning(tile_rows, stages)) return sm::fail(SM_ERR_INVALID_ARG, "sm_gemm_tuning: tile_rows must be 0, 64, 128 or 256 and stages 0 or 2..4");
   return SM_OK;

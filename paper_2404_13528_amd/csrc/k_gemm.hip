@@ -19,6 +19,9 @@
 // MFMA block), so that the two partners sit in the same lane: the Slice /
 // chunk operators of SwiGLU / GEGLU and the half-split of RoPE cost nothing.
 #include <atomic>
+#include <map>
+#include <mutex>
+#include <tuple>
 #include <algorithm>
 #include <type_traits>
 #include "device_common.h"
@@ -649,70 +652,91 @@ static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
 }
 
 static std::atomic<int> g_force_rows{0}, g_force_stages{0};       // sm_gemm_tuning (a process-wide sweep hook)
+// tile height and stage count of one launch: 0 = the built-in choice.  Comes from sm_gemm_tuning (all shapes) or from
+// the table sm_linear_autotune filled for this shape.
+struct Tune { int rows, stages; };
 
 // Two stages (one K-tile in flight) unless the tuning hook asks for more: within a chain of kernels the operands
 // arrive from the memory-side cache, a workgroup's K step is bound by its own issue and fragment-read latencies
 // rather than by the tile's arrival, and every further stage costs a resident workgroup per CU.
 template <typename T, int MI, int EPI, int WM>
-static int gemm_launch_dma(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+static int gemm_launch_dma(const GemmArgs& g, const ColMap& cm, hipStream_t s, Tune tn) {
   constexpr int BM = 32 * MI * WM;
   const int64_t stage = (BM + 128) * 128;
-  const int ns = g_force_stages ? std::min<int>(g_force_stages, (int)((160 * 1024) / stage)) : 2;
+  const int ns = tn.stages ? std::min<int>(tn.stages, (int)((160 * 1024) / stage)) : 2;
   if (ns == 4) return gemm_launch2<T, MI, EPI, false, true, WM, 4>(g, cm, s);
   if (ns == 3) return gemm_launch2<T, MI, EPI, false, true, WM, 3>(g, cm, s);
   return gemm_launch2<T, MI, EPI, false, true, WM, 2>(g, cm, s);
 }
 
 template <typename T, int MI, int EPI, bool AGRAN>
-static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+static int gemm_launch(const GemmArgs& g, const ColMap& cm, hipStream_t s, Tune tn) {
   if constexpr (!AGRAN && (EPI == EPI_PLAIN || EPI == EPI_GELU)) {
     if (g.norm) return gemm_launch2<T, MI, EPI, false, false, 2, 2, true>(g, cm, s);      // checked by the caller: only these epilogues
   }
   if constexpr (sizeof(T) == 2 && !AGRAN) {
     if (g.K % 64 == 0) {
-      if (g_force_rows == 256 || g_force_rows == 128) {
-        if constexpr (MI == 2) return g_force_rows == 256 ? gemm_launch_dma<T, 2, EPI, 4>(g, cm, s) : gemm_launch_dma<T, 2, EPI, 2>(g, cm, s);
-      } else if (g_force_rows == 64) {
-        if constexpr (MI == 1) return gemm_launch_dma<T, 1, EPI, 2>(g, cm, s);
+      if (tn.rows == 256 || tn.rows == 128) {
+        if constexpr (MI == 2) return tn.rows == 256 ? gemm_launch_dma<T, 2, EPI, 4>(g, cm, s, tn) : gemm_launch_dma<T, 2, EPI, 2>(g, cm, s, tn);
+      } else if (tn.rows == 64) {
+        if constexpr (MI == 1) return gemm_launch_dma<T, 1, EPI, 2>(g, cm, s, tn);
       }
       if constexpr (MI == 2) {
         // 256 x 128 tiles when they fill the chip (one 8-wave workgroup per CU) about as well as the smaller ones; with a
         // short K loop only on grids of several rounds, where their lower L2 -> LDS traffic per flop pays
         const int64_t t256 = ((g.M + 255) / 256) * ((g.N + 127) / 128);
         const int64_t rounds = (t256 + 255) / 256;
-        if (t256 >= (g.K >= 1024 ? 200 : 512) && (double)t256 / (double)(rounds * 256) >= 0.8) return gemm_launch_dma<T, 2, EPI, 4>(g, cm, s);
+        if (t256 >= (g.K >= 1024 ? 200 : 512) && (double)t256 / (double)(rounds * 256) >= 0.8) return gemm_launch_dma<T, 2, EPI, 4>(g, cm, s, tn);
       }
-      return gemm_launch_dma<T, MI, EPI, 2>(g, cm, s);
+      return gemm_launch_dma<T, MI, EPI, 2>(g, cm, s, tn);
     }
   }
   return gemm_launch2<T, MI, EPI, AGRAN, false>(g, cm, s);
 }
 
 template <typename T, int MI>
-static int gemm_pick_epi(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
-  if (g.a_gran > 0) return gemm_launch<T, MI, EPI_PLAIN, true>(g, cm, s);     // checked by the caller: no activation with an unfold
-  if (cm.mode == 1) return gemm_launch<T, MI, EPI_GLU, false>(g, cm, s);
-  if (cm.mode == 2) return gemm_launch<T, MI, EPI_ROPE, false>(g, cm, s);
-  if (g.act == SM_ACT_GELU) return gemm_launch<T, MI, EPI_GELU, false>(g, cm, s);
-  return gemm_launch<T, MI, EPI_PLAIN, false>(g, cm, s);
+static int gemm_pick_epi(const GemmArgs& g, const ColMap& cm, hipStream_t s, Tune tn) {
+  if (g.a_gran > 0) return gemm_launch<T, MI, EPI_PLAIN, true>(g, cm, s, tn);     // checked by the caller: no activation with an unfold
+  if (cm.mode == 1) return gemm_launch<T, MI, EPI_GLU, false>(g, cm, s, tn);
+  if (cm.mode == 2) return gemm_launch<T, MI, EPI_ROPE, false>(g, cm, s, tn);
+  if (g.act == SM_ACT_GELU) return gemm_launch<T, MI, EPI_GELU, false>(g, cm, s, tn);
+  return gemm_launch<T, MI, EPI_PLAIN, false>(g, cm, s, tn);
 }
+
+// Shapes sm_linear_autotune has measured: (M, N, K, element type, epilogue class) -> the fastest (tile rows, stages)
+struct TuneKey {
+  int64_t M; int N, K, dtype, epi;
+  bool operator<(const TuneKey& o) const { return std::tie(M, N, K, dtype, epi) < std::tie(o.M, o.N, o.K, o.dtype, o.epi); }
+};
+static std::mutex g_tune_mu;
+static std::map<TuneKey, Tune> g_tuned;
+static TuneKey tune_key(const GemmArgs& g) {
+  return TuneKey{g.M, g.N, g.K, g.dtype, g.act * 4 + (g.residual ? 2 : 0) + (g.rope_cols ? 1 : 0)};
+}
+static bool tunable(const GemmArgs& g) { return g.dtype == SM_BF16 && g.K % 64 == 0 && g.a_gran == 0 && !g.norm; }
 
 template <typename T>
 static int gemm_dispatch(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
-  if (g_force_rows) return g_force_rows >= 128 ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
+  Tune tn{g_force_rows, g_force_stages};
+  if (!tn.rows && !tn.stages && tunable(g)) {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    auto it = g_tuned.find(tune_key(g));
+    if (it != g_tuned.end()) tn = it->second;
+  }
+  if (tn.rows) return tn.rows >= 128 ? gemm_pick_epi<T, 2>(g, cm, s, tn) : gemm_pick_epi<T, 1>(g, cm, s, tn);
   // Tile height.  Large grids (several rounds of residency whatever the tile): the 128-row tile, or the 256-row one
   // where gemm_launch finds that it fills the chip.  Small grids are decided by rounds of residency (256 CUs hold
   // 768 workgroups of the 64-row tile, 512 of the 128-row one) times the time a workgroup lives: a fixed part plus
   // its K steps, both measured on the chip (microseconds; the 128-row step moves twice the rows in about twice the time,
   // so the smaller tile wins unless it needs an extra round).
-  const int64_t tn = (g.N + 127) / 128;
-  const int64_t t128 = ((g.M + 127) / 128) * tn, t64 = ((g.M + 63) / 64) * tn;
-  if (t128 >= 1024) return gemm_pick_epi<T, 2>(g, cm, s);
+  const int64_t tcols = (g.N + 127) / 128;
+  const int64_t t128 = ((g.M + 127) / 128) * tcols, t64 = ((g.M + 63) / 64) * tcols;
+  if (t128 >= 1024) return gemm_pick_epi<T, 2>(g, cm, s, tn);
   const double nk = (double)((g.K + 63) / 64);
   double cost64 = (double)((t64 + 767) / 768) * (3.0 + 0.78 * nk), cost128 = (double)((t128 + 511) / 512) * (3.6 + 1.6 * nk);
   // long K loops: the tile's L2 -> LDS traffic per flop decides, the 64-row tile being about 0.6 as efficient per row
   if (nk > 16) { cost64 = (double)((t64 + 767) / 768) * 1.2; cost128 = (double)((t128 + 511) / 512) * 2.0; }
-  return cost128 <= cost64 ? gemm_pick_epi<T, 2>(g, cm, s) : gemm_pick_epi<T, 1>(g, cm, s);
+  return cost128 <= cost64 ? gemm_pick_epi<T, 2>(g, cm, s, tn) : gemm_pick_epi<T, 1>(g, cm, s, tn);
 }
 
 int launch_gemm(const GemmArgs& g, void* stream) {
@@ -729,5 +753,46 @@ int gemm_tuning(int tile_rows, int stages) {
   g_force_rows = tile_rows; g_force_stages = stages;
   return 0;
 }
+
+// The tuner (paper Sec. 3.3 "Other optimizations": an auto-tuner picks tiling and unrolling per kernel; here the
+// search space is small enough to be walked completely): every tile height x stage count the kernel has, timed on the
+// caller's operands with HIP events; the fastest is remembered for the shape.  0 in *rows / *stages = the built-in choice won.
+int gemm_autotune(const GemmArgs& g, int iters, void* stream, int* rows, int* stages, float* best_us, float* default_us) {
+  if (!tunable(g)) return -2;
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return -1;
+  if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return -1; }
+  { std::lock_guard<std::mutex> lock(g_tune_mu); g_tuned.erase(tune_key(g)); }
+  const int cand_rows[] = {0, 64, 128, 256};
+  Tune best{0, 0};
+  float best_t = 1e30f, def_t = 0.f;
+  int rc = 0;
+  for (int ri = 0; ri < 4 && rc == 0; ++ri) {
+    for (int st = (ri == 0 ? 0 : 2); st <= (ri == 0 ? 0 : 4) && rc == 0; ++st) {
+      const Tune tn{cand_rows[ri], st};
+      if (tn.rows) { std::lock_guard<std::mutex> lock(g_tune_mu); g_tuned[tune_key(g)] = tn; }
+      for (int w = 0; w < 2 && rc == 0; ++w) rc = launch_gemm(g, stream);
+      if (rc == 0 && hipEventRecord(a, s) != hipSuccess) rc = -1;
+      for (int i = 0; i < iters && rc == 0; ++i) rc = launch_gemm(g, stream);
+      if (rc == 0 && (hipEventRecord(b, s) != hipSuccess || hipEventSynchronize(b) != hipSuccess)) rc = -1;
+      float ms = 0.f;
+      if (rc == 0 && hipEventElapsedTime(&ms, a, b) != hipSuccess) rc = -1;
+      const float us = ms * 1e3f / (float)iters;
+      if (ri == 0) def_t = us;
+      if (rc == 0 && us < best_t * (ri == 0 ? 1.f : 0.97f)) { best_t = us; best = tn; }     // a candidate has to win by 3 %
+    }
+  }
+  (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+  {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    g_tuned.erase(tune_key(g));
+    if (rc == 0 && best.rows) g_tuned[tune_key(g)] = best;
+  }
+  if (rc) return rc;
+  *rows = best.rows; *stages = best.stages; *best_us = best_t; *default_us = def_t;
+  return 0;
+}
+void gemm_autotune_clear() { std::lock_guard<std::mutex> lock(g_tune_mu); g_tuned.clear(); }
 
 }  // namespace sm

@@ -56,6 +56,10 @@ struct GemmArgs {
 };
 int launch_gemm(const GemmArgs& a, void* stream);
 int gemm_tuning(int tile_rows, int stages);      // 0 = automatic; -1 on values the kernel has no variant for
+// times every (tile rows, stages) variant on g's operands and remembers the fastest for g's shape; synchronises.
+// 0 ok, -2 shape has no variants (not the bf16 LDS-DMA path), other: hip error
+int gemm_autotune(const GemmArgs& g, int iters, void* stream, int* rows, int* stages, float* best_us, float* default_us);
+void gemm_autotune_clear();
 
 // Fused MLP (bf16): Y = residual + W2 . gelu(W1 . norm(x) + b1) + b2 per token.  Wp: W1 [Hd, C] and W2 [C, Hd] packed
 // by launch_mlp_pack into MFMA fragment order (2 * Hd * C elements).
