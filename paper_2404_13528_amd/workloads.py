@@ -93,6 +93,17 @@ def llama_case(B, S, E, F, seed=0, bf16=True, std=STD, in_std=1.0):
     return x, p
 
 
+def vit_case(B, S, E, h, F, seed=0, bf16=True, std=STD, in_std=1.0):
+    dr = Draw(seed, bf16, std)
+    x = dr.normal(B, S, E, std=in_std)
+    p = {"ln1_g": dr.gain(E), "ln1_b": dr.weight(E),
+         "wqkv": dr.weight(3 * E, E), "bqkv": dr.weight(3 * E),
+         "wo": dr.weight(E, E), "bo": dr.weight(E),
+         "ln2_g": dr.gain(E), "ln2_b": dr.weight(E),
+         "w1": dr.weight(F, E), "b1": dr.weight(F), "w2": dr.weight(E, F), "b2": dr.weight(E)}
+    return x, p
+
+
 def sd_case(B, C, H, W, Sc, Dc, F, seed=0, bf16=True, std=STD, in_std=1.0):
     dr = Draw(seed, bf16, std)
     x = dr.normal(B, C, H, W, std=in_std)

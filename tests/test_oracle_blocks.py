@@ -226,3 +226,31 @@ def test_swin_net_head_against_torch_library():
             swin.patch_embed = orig
         assert np.abs(f - f_t.numpy()).max() < 1e-10 and np.abs(logits - l_t.numpy()).max() < 1e-10
         assert np.abs(logits).max() > 1e-3          # the comparison is not vacuous
+
+
+def torch_vit(x, p, h):
+    B, S, E = x.shape
+    d = E // h
+    n = F.layer_norm(x, (E,), p["ln1_g"], p["ln1_b"], 1e-5)
+    q, k, v = F.linear(n, p["wqkv"], p["bqkv"]).view(B, S, 3, h, d).permute(2, 0, 3, 1, 4)
+    o = F.scaled_dot_product_attention(q, k, v).transpose(1, 2).reshape(B, S, E)
+    x = x + F.linear(o, p["wo"], p["bo"])
+    return x + F.linear(F.gelu(F.linear(F.layer_norm(x, (E,), p["ln2_g"], p["ln2_b"], 1e-5), p["w1"], p["b1"])), p["w2"], p["b2"])
+
+
+@pytest.mark.parametrize("std", [0.02, 0.2])
+def test_vit_block_vs_torch_chain(std):
+    from oracle import vit
+    x, p = Wl.vit_case(2, 19, 48, 4, 80, seed=2, bf16=False, std=std)
+    got = vit.vit_block(x.double().numpy(), npd(p), 4, want_all=True)
+    ref = torch_vit(x.double(), td(p), 4).numpy()
+    assert np.abs(got["y"] - ref).max() < 1e-10
+    assert np.abs(got["P"].sum(-1) - 1).max() < 1e-12                    # global softmax rows sum to 1
+    # one token, one head: attention is the identity on v, so the block is two residual MLP-like maps with a closed form
+    x1, p1 = Wl.vit_case(1, 1, 16, 1, 32, seed=3, bf16=False, std=0.3)
+    xn, pn = x1.double().numpy(), npd(p1)
+    n1 = O.layer_norm(xn, pn["ln1_g"], pn["ln1_b"])
+    v = (n1 @ pn["wqkv"].T + pn["bqkv"])[..., 32:]
+    x1_ = xn + v @ pn["wo"].T + pn["bo"]
+    want = x1_ + O.gelu(O.layer_norm(x1_, pn["ln2_g"], pn["ln2_b"]) @ pn["w1"].T + pn["b1"]) @ pn["w2"].T + pn["b2"]
+    assert np.abs(vit.vit_block(xn, pn, 1) - want).max() < 1e-12
