@@ -228,6 +228,14 @@ def build_config(k, sm, torch, Wl):
         return ("configs[4]: diffusion-UNet spatial transformer block, bf16, B=2, latent 64x64x320 NCHW, GroupNorm 32, self-attn 8 heads "
                 "over 4096 tokens, cross-attn to 77x768, GEGLU 1280", "images/s", B,
                 {n: (lambda b=b: b(xd, cd, out=y)) for n, b in blk.items()}, None, "bf16")
+    if k == 6:     # a second workload from the paper's model list (Tables 1, 7), beyond the benchmark's five
+        B, S, E, h, F = 32, 197, 768, 12, 3072
+        x, p = Wl.vit_case(B, S, E, h, F)
+        dp, xd = dev(p, bf), x.to(bf).cuda()
+        y = torch.empty_like(xd)
+        blk = {n: sm.AttnBlock("vit", dp, bf, m, B=B, S=S, E=E, heads=h, F=F) for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
+        return ("extra: ViT-B/16 encoder block, bf16, B=32, 197 tokens, 768 wide, 12 heads x 64, global attention, GELU MLP 3072",
+                "images/s", B, {n: (lambda b=b: b(xd, out=y)) for n, b in blk.items()}, None, "bf16")
     raise ValueError(k)
 
 
@@ -286,7 +294,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json; 0 = all five")
+    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json (6: the extra ViT block); 0 = all")
     ap.add_argument("--variants", default="", help="comma-separated subset of the variants (elided, explicit, elided_per_op, explicit_per_op)")
     ap.add_argument("--kernels", action="store_true", help="include every variant's per-kernel table in the JSON line (long)")
     ap.add_argument("--no-autotune", action="store_true",
@@ -319,7 +327,7 @@ def main():
 
     traffic = measured_traffic()
     HEAD = 3
-    which = [a.config] if a.config else [3, 1, 2, 4, 5]
+    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6]
     want = [v for v in a.variants.split(",") if v]
     configs, oracle_sample, calib = {}, None, None
     for k in which:

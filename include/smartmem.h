@@ -364,8 +364,10 @@ int sm_swin_block_static(const sm_swin_cfg*, const sm_swin_weights*, const void*
  *   SM_ATTN_SD (23): gn_g, gn_b, win, bin, ln1_g, ln1_b, a1_wqkv [3C, C], a1_wo, a1_bo,
  *                    ln2_g, ln2_b, a2_wq, a2_wkv [2C, Dc], a2_wo, a2_bo, ln3_g, ln3_b,
  *                    ff_w1 [2F, C], ff_b1, ff_w2, ff_b2, wout, bout
- * x: LLAMA [B, S, E]; SD NCHW [B, C, Hs, Ws]; context: SD only, [B, Sc, Dc]. */
-enum { SM_ATTN_LLAMA = 0, SM_ATTN_SD = 1 };
+ *   SM_ATTN_VIT (12): a ViT encoder block (pre-norm, global attention over all S tokens, GELU MLP of width F):
+ *                     ln1_g, ln1_b, wqkv [3E, E], bqkv, wo, bo, ln2_g, ln2_b, w1 [F, E], b1, w2 [E, F], b2
+ * x: LLAMA, VIT [B, S, E]; SD NCHW [B, C, Hs, Ws]; context: SD only, [B, Sc, Dc]. */
+enum { SM_ATTN_LLAMA = 0, SM_ATTN_SD = 1, SM_ATTN_VIT = 2 };
 typedef struct {
   int32_t kind, dtype;
   int32_t B, S, E, heads, F;          /* LLAMA: S tokens, E hidden; SD: S = Hs*Ws, E = C channels */

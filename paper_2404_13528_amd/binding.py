@@ -643,7 +643,7 @@ class Plan:
 
 
 class AttnBlock:
-    """sm_attn_block: kind "llama" or "sd".  params follow workloads.llama_case / sd_case (device tensors);
+    """sm_attn_block: kind "llama", "sd" or "vit".  params follow workloads.llama_case / sd_case (device tensors);
     the fused weight matrices the library takes (q|k|v, gate|up, k|v) are concatenated here, once."""
 
     def __init__(self, kind, params, dtype, mode=SM_ELIDED, B=1, S=0, E=0, heads=1, F=0, Hs=0, Ws=0, groups=32, Sc=0, Dc=0,
@@ -654,6 +654,9 @@ class AttnBlock:
             ws = [p["rms1_g"], torch.cat([p["wq"], p["wk"], p["wv"]], 0).contiguous(), p["wo"], p["rms2_g"],
                   torch.cat([p["wgate"], p["wup"]], 0).contiguous(), p["wdown"]]
             k = 0
+        elif kind == "vit":
+            ws = [p[n] for n in ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")]
+            k = 2
         else:
             ws = [p["gn_g"], p["gn_b"], p["win"], p["bin"], p["ln1_g"], p["ln1_b"],
                   torch.cat([p["a1_wq"], p["a1_wk"], p["a1_wv"]], 0).contiguous(), p["a1_wo"], p["a1_bo"],

@@ -90,12 +90,12 @@ bool count_plan(const sm_plan* plan, const GraphB& g, AttnPlan* p) {
 }
 
 // multi-head attention sub-graph: xq [B, Sq, E], xkv [B, Sk, Ekv]; fused_qkv: one MatMul then slices
-int mha_graph(GraphB& g, int xq, int xkv, int64_t B, int64_t Sq, int64_t Sk, int64_t E, int64_t h, bool self, bool rope, const char* name, bool out_bias) {
+int mha_graph(GraphB& g, int xq, int xkv, int64_t B, int64_t Sq, int64_t Sk, int64_t E, int64_t h, bool self, bool rope, const char* name, bool out_bias, bool qkv_bias = false) {
   const int64_t d = E / h;
   std::vector<int> parts;
   auto split = [&](int t, int64_t S) { t = g.reshape(t, {B, S, h, d}); return g.transpose(t, {0, 2, 1, 3}); };
   if (self) {
-    const int qkv = g.linear(xq, 3 * E, "qkv", false);
+    const int qkv = g.linear(xq, 3 * E, "qkv", qkv_bias);
     for (int k = 0; k < 3; ++k) {
       int u = split(g.slice(qkv, 2, k * E, (k + 1) * E), Sq);
       if (rope && k < 2) u = g.op(SM_OP_ROPE, {u}, {B, h, Sq, d}, "rope");
@@ -134,6 +134,17 @@ std::shared_ptr<AttnPlan> attn_plan(const sm_attn_cfg& c, std::string* err) {
     t = g.op(SM_OP_MUL, {ga, up}, {B, S, F}, "swiglu");
     t = g.linear(t, E, "down", false);
     g.op(SM_OP_ADD, {h1, t}, {B, S, E}, "res2");
+    expect_kept = 7;
+  } else if (c.kind == SM_ATTN_VIT) {
+    const int x = g.tensor({B, S, E});
+    int t = g.op(SM_OP_LAYERNORM, {x}, {B, S, E}, "ln1", {2});
+    t = mha_graph(g, t, t, B, S, S, E, h, true, false, "attn1", true, true);
+    const int x1 = g.op(SM_OP_ADD, {x, t}, {B, S, E}, "res1");
+    t = g.op(SM_OP_LAYERNORM, {x1}, {B, S, E}, "ln2", {2});
+    t = g.linear(t, F, "fc1", true);
+    t = g.op(SM_OP_UNARY, {t}, {B, S, F}, "gelu");
+    t = g.linear(t, E, "fc2", true);
+    g.op(SM_OP_ADD, {x1, t}, {B, S, E}, "res2");
     expect_kept = 7;
   } else {
     const int64_t Hs = c.Hs, Ws = c.Ws;
@@ -212,7 +223,7 @@ std::shared_ptr<AttnPlan> attn_plan(const sm_attn_cfg& c, std::string* err) {
 
 int check_cfg(const sm_attn_cfg* c, const char* who) {
   if (!c) return fail(SM_ERR_INVALID_ARG, "%s: null configuration", who);
-  if (c->kind != SM_ATTN_LLAMA && c->kind != SM_ATTN_SD) return fail(SM_ERR_INVALID_ARG, "%s: unknown kind %d", who, c->kind);
+  if (c->kind != SM_ATTN_LLAMA && c->kind != SM_ATTN_SD && c->kind != SM_ATTN_VIT) return fail(SM_ERR_INVALID_ARG, "%s: unknown kind %d", who, c->kind);
   if (c->dtype != SM_BF16) return fail(SM_ERR_UNSUPPORTED, "%s: bf16 only", who);
   if (c->B < 1 || c->S < 1 || c->E < 1 || c->heads < 1 || c->F < 1 || c->E % c->heads) return fail(SM_ERR_SHAPE, "%s: bad shape", who);
   const int d = c->E / c->heads;
@@ -291,7 +302,7 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
   if (!w || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_attn_block: null pointer");
   if (c->kind == SM_ATTN_SD && !context) return fail(SM_ERR_INVALID_ARG, "sm_attn_block: the spatial transformer needs a context");
   if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_attn_block: unknown mode %d", mode);
-  const int nw = c->kind == SM_ATTN_LLAMA ? 6 : 23;
+  const int nw = c->kind == SM_ATTN_LLAMA ? 6 : (c->kind == SM_ATTN_VIT ? 12 : 23);
   for (int i = 0; i < nw; ++i) if (!w[i] || !aligned16(w[i])) return fail(SM_ERR_INVALID_ARG, "sm_attn_block: weight %d is null or misaligned", i);
   const Sizes z = sizes(c, mode);
   if (!aligned16(x) || !aligned16(y) || !aligned16(ws) || (context && !aligned16(context))) return fail(SM_ERR_INVALID_ARG, "sm_attn_block: pointers must be 16-byte aligned");
@@ -331,6 +342,25 @@ extern "C" int sm_attn_block(const sm_attn_cfg* c, const void* const* w, const v
     if ((rc = norm(r1, w[3], nullptr, n, T, E, c->eps_norm, 1, dt, stream))) return rc;
     if ((rc = gemm(n, w[4], nullptr, nullptr, act, T, 2 * F, E, dt, SM_ACT_SWIGLU, stream))) return rc;
     if ((rc = gemm(act, w[5], nullptr, r1, y, T, E, F, dt, SM_ACT_NONE, stream))) return rc;
+    return SM_OK;
+  }
+
+  if (c->kind == SM_ATTN_VIT) {
+    // w: ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2
+    if ((rc = norm(x, w[0], w[1], n, T, E, c->eps_norm, 0, dt, stream))) return rc;
+    if ((rc = gemm(n, w[2], w[3], nullptr, qkv, T, 3 * E, E, dt, SM_ACT_NONE, stream))) return rc;
+    if (el) {
+      if ((rc = attention(SM_ATT_FULL, dt, B, h, S, S, d, plan->q1, plan->k1, plan->v1, plan->o1, qkv, qkv, qkv, o, stream))) return rc;
+    } else {
+      if ((rc = copy_launch(plan->split_qkv, tables, qkv, qkvp, dt, stream))) return rc;
+      const View4 cq = contiguous_view(h, S, d, 0), ck = contiguous_view(h, S, d, T * E), cv = contiguous_view(h, S, d, 2 * T * E);
+      if ((rc = attention(SM_ATT_FULL, dt, B, h, S, S, d, cq, ck, cv, cq, qkvp, qkvp, qkvp, op, stream))) return rc;
+      if ((rc = copy_launch(plan->merge_o, tables, op, o, dt, stream))) return rc;
+    }
+    if ((rc = gemm(o, w[4], w[5], x, r1, T, E, E, dt, SM_ACT_NONE, stream))) return rc;
+    if ((rc = norm(r1, w[6], w[7], n, T, E, c->eps_norm, 0, dt, stream))) return rc;
+    if ((rc = gemm(n, w[8], w[9], nullptr, act, T, F, E, dt, SM_ACT_GELU, stream))) return rc;
+    if ((rc = gemm(act, w[10], w[11], r1, y, T, E, F, dt, SM_ACT_NONE, stream))) return rc;
     return SM_OK;
   }
 

@@ -80,3 +80,27 @@ def test_sd_small_stress(mode, H, W):
 def test_config5_sd_block_full_size(mode):
     got, want, x, _ = run_sd(2, 320, 64, 64, 77, 768, 1280, 32, 8, mode)
     assert_bf16_close(got, want, "block output", x=x)
+
+
+def run_vit(B, S, E, h, F, mode, std=0.02, seed=0):
+    from oracle import vit
+    x, p = Wl.vit_case(B, S, E, h, F, seed=seed, std=std)
+    blk = sm.AttnBlock("vit", dev_params(p, BF), BF, mode, B=B, S=S, E=E, heads=h, F=F)
+    y = blk(dev(x, BF))
+    torch.cuda.synchronize()
+    return to_np(y), vit.vit_block(to_np(x), np_params(p), h), to_np(x), sm.launch_counts()
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_vit_small_stress(mode):
+    # 197 tokens (14 x 14 patches + class token: ragged against every tile), O(1) logits
+    got, want, x, counts = run_vit(2, 197, 128, 2, 256, mode, std=0.1, seed=4)
+    assert_bf16_close(got, want, "ViT block", x=x)
+    assert counts == ((7, 0) if mode == sm.SM_ELIDED else (7, 2))
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_vit_b16_block_full_size(mode):
+    # ViT-B/16 at 224 x 224 (the paper's ViT row, Table 7): 197 tokens, 768 wide, 12 heads, MLP 3072; B = 32
+    got, want, x, _ = run_vit(32, 197, 768, 12, 3072, mode)
+    assert_bf16_close(got, want, "ViT-B block", x=x)
