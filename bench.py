@@ -68,7 +68,7 @@ def kernel_model(label):
     if m:
         M, N, K = int(m.group(1)), int(m.group(2)), int(m.group(3))
         n_out = N // 2 if "+glu" in m.group(4) else N
-        by = (M * K + N * K + N + M * n_out + (M * n_out if "+res" in m.group(4) else 0)) * e
+        by = (M * K + N * K + N + M * n_out + (M * n_out if "+res" in m.group(4) else 0) + (M * n_out if "+copy2" in m.group(4) else 0)) * e
         return by, 2.0 * M * N * K
     m = re.match(r"(layernorm|rmsnorm)_\w+\[(\d+),(\d+)\]", label)
     if m:
@@ -91,6 +91,10 @@ def kernel_model(label):
     if m:
         B, L, C = int(m.group(1)), int(m.group(2)), int(m.group(3))
         return (B * L * C + B * C) * e, float(B * L * C)
+    m = re.match(r"reduce_(last|first)_\w+\[(\d+),(\d+)\]", label)
+    if m:
+        r, n = int(m.group(2)), int(m.group(3))
+        return (r * n + r) * e, float(r * n)
     m = re.match(r"fill_row_table\[(\d+)\]", label)
     if m:
         return 4 * int(m.group(1)), 0.0
@@ -236,6 +240,16 @@ def build_config(k, sm, torch, Wl):
         blk = {n: sm.AttnBlock("vit", dp, bf, m, B=B, S=S, E=E, heads=h, F=F) for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
         return ("extra: ViT-B/16 encoder block, bf16, B=32, 197 tokens, 768 wide, 12 heads x 64, global attention, GELU MLP 3072",
                 "images/s", B, {n: (lambda b=b: b(xd, out=y)) for n, b in blk.items()}, None, "bf16")
+    if k == 7:     # the multi-consumer example of Sec. 3.2.2 (Fig. 4) with its redundant copy executed
+        D1, D2, D3, Kin, Cout = 512, 64, 256, 256, 64
+        a, w, wc = Wl.fanout_case(D1, D2, D3, Kin, Cout)
+        ad, wd, wcd = a.to(bf).cuda(), w.to(bf).cuda(), wc.to(bf).cuda()
+        gs = {"elided": sm.FanoutGraph(D1, D2, D3, Kin, Cout, bf, sm.SM_ELIDED, 1),          # two stored layouts (k = 1)
+              "elided_one_layout": sm.FanoutGraph(D1, D2, D3, Kin, Cout, bf, sm.SM_ELIDED, 2),
+              "explicit": sm.FanoutGraph(D1, D2, D3, Kin, Cout, bf, sm.SM_EXPLICIT, 1)}
+        return ("extra: Fig. 4 graph MatMul -> Transpose -> Reshape -> {Reduce D3, Reduce' D1, Conv D3}, bf16, D1=512, D2=64, D3=256, "
+                "Kin=256, Cout=64; redundant copy of %d bytes with k=1" % gs["elided"].plan["copy_bytes"], "graphs/s", 1,
+                {n: (lambda g=g: g(ad, wd, wcd)) for n, g in gs.items()}, None, "bf16")
     raise ValueError(k)
 
 
@@ -327,7 +341,7 @@ def main():
 
     traffic = measured_traffic()
     HEAD = 3
-    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6]
+    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6, 7]
     want = [v for v in a.variants.split(",") if v]
     configs, oracle_sample, calib = {}, None, None
     for k in which:

@@ -408,6 +408,24 @@ size_t sm_run_chain_workspace_bytes(const sm_chain_desc*, int mode);
 int sm_run_chain(const sm_chain_desc*, const void* const* weights, int n_weights, const void* x,
                  void* y, void* y_feat, void* ws, size_t ws_bytes, int mode, void* stream);
 
+/* The multi-consumer example of the paper's global layout selection (Sec. 3.2.2, Fig. 4; memory cost of redundant
+ * copies: Sec. 4.6), executed: T = A . W^T [D2*D3, D1] -> Transpose -> Reshape [D1, D2, D3] -> three consumers,
+ *   reduce   [D1, D2]       = sum over D3,
+ *   reduce_p [D2, D3]       = sum over D1,
+ *   conv     [D1, D2, Cout] = contraction over D3 with wconv [Cout, D3].
+ * The graph is planned with sm_layout_plan and k directly indexable dimensions.  SM_ELIDED: Transpose and Reshape
+ * are eliminated into the MatMul's store; the consumers request two reduction dimensions, so with k = 1 the MatMul
+ * keeps two copies of its result (one epilogue, two stores), each consumer reading the one whose innermost
+ * dimension is its own; with k = 2 a single layout serves all three (Reduce' then reads with a stride on linear
+ * memory).  SM_EXPLICIT: the Transpose runs as a copy kernel.  a [D2*D3, Kin], w [D1, Kin], wconv [Cout, D3]; device
+ * pointers; Kin, D1, D3 multiples of the 16-byte vector.  sm_fanout_graph_plan reports what the planner decided and
+ * what one redundant copy costs in bytes. */
+typedef struct { int32_t dtype, D1, D2, D3, Kin, Cout, k; } sm_fanout_cfg;
+int sm_fanout_graph_plan(const sm_fanout_cfg*, int* n_copies, int* red_dims /* 2 */, int* n_red, size_t* copy_bytes);
+size_t sm_fanout_graph_workspace_bytes(const sm_fanout_cfg*, int mode);
+int sm_fanout_graph(const sm_fanout_cfg*, const void* a, const void* w, const void* wconv, void* reduce_out,
+                    void* reduce_p_out, void* conv_out, void* ws, size_t ws_bytes, int mode, void* stream);
+
 /* Number of kernels the last sm_swin_block / sm_attn_block / sm_run_chain call
  * of this thread enqueued, split into compute and copy kernels. */
 int sm_last_launch_counts(int* n_compute, int* n_copy);

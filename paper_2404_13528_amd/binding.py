@@ -108,7 +108,7 @@ def lib():
         L = C.CDLL(LIB_PATH, mode=C.RTLD_GLOBAL)
         L.sm_last_error.restype = C.c_char_p
         L.sm_map_numel.restype = C.c_int64
-        for f in ("sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes",
+        for f in ("sm_fanout_graph_workspace_bytes", "sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes",
                   "sm_swin_block_static_max_bytes"):
             getattr(L, f).restype = C.c_size_t
         _lib = L
@@ -640,6 +640,38 @@ class Plan:
         if self.h and _lib is not None:
             _lib.sm_plan_destroy(self.h)
             self.h = None
+
+
+class FanoutCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("dtype", "D1", "D2", "D3", "Kin", "Cout", "k")]
+
+
+class FanoutGraph:
+    """sm_fanout_graph: the Fig. 4 multi-consumer graph (MatMul -> Transpose -> Reshape -> Reduce, Reduce', Conv)."""
+
+    def __init__(self, D1, D2, D3, Kin, Cout, dtype, mode=SM_ELIDED, k=1):
+        import torch
+        self.cfg = FanoutCfg(SM_F32 if dtype == torch.float32 else SM_BF16, D1, D2, D3, Kin, Cout, k)
+        self.mode, self.dtype = mode, dtype
+        n = lib().sm_fanout_graph_workspace_bytes(C.byref(self.cfg), mode)
+        if n == 0:
+            raise SmError("sm_fanout_graph_workspace_bytes: " + lib().sm_last_error().decode())
+        self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        nc, nr, cb = C.c_int(), C.c_int(), C.c_size_t()
+        rd = (C.c_int * 2)()
+        check(lib().sm_fanout_graph_plan(C.byref(self.cfg), C.byref(nc), rd, C.byref(nr), C.byref(cb)), "sm_fanout_graph_plan")
+        self.plan = {"n_copies": nc.value, "red_dims": [rd[i] for i in range(nr.value)], "copy_bytes": cb.value,
+                     "workspace_bytes": n}
+
+    def __call__(self, a, w, wconv, stream=None):
+        import torch
+        c = self.cfg
+        r = torch.empty(c.D1, c.D2, dtype=self.dtype, device="cuda")
+        rp = torch.empty(c.D2, c.D3, dtype=self.dtype, device="cuda")
+        cv = torch.empty(c.D1, c.D2, c.Cout, dtype=self.dtype, device="cuda")
+        check(lib().sm_fanout_graph(C.byref(c), _ptr(a), _ptr(w), _ptr(wconv), _ptr(r), _ptr(rp), _ptr(cv), _ptr(self.ws),
+                                    C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_fanout_graph")
+        return r, rp, cv
 
 
 class AttnBlock:

@@ -51,6 +51,8 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   if (g.c_cols_on && (g.c_transposed || g.act == SM_ACT_SWIGLU || g.act == SM_ACT_GEGLU)) return fail(SM_ERR_UNSUPPORTED, "%s: column-splitting store with a gated activation or transposed store", who);
   if (g.a_gran > 0 && (g.act != SM_ACT_NONE || g.rope_cols)) return fail(SM_ERR_UNSUPPORTED, "%s: activation or RoPE with an unfolded A operand", who);
   if (g.act != SM_ACT_NONE && g.rope_cols) return fail(SM_ERR_UNSUPPORTED, "%s: RoPE goes with no activation (the RoPE epilogue applies none)", who);
+  if (g.C2 && (g.residual || g.c_transposed || g.c_cols_on || gated || !aligned16(g.C2)))
+    return fail(SM_ERR_UNSUPPORTED, "%s: a second (column-major) copy goes with a plain store only", who);
   if (g.norm) {
     if (g.norm != 1 && g.norm != 2) return fail(SM_ERR_INVALID_ARG, "%s: unknown norm %d", who, g.norm);
     if (gated || g.rope_cols || g.a_gran > 0) return fail(SM_ERR_UNSUPPORTED, "%s: a folded norm goes with activation none or GELU only, without RoPE or an unfolded A", who);
@@ -68,7 +70,8 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   if ((int64_t)g.N * g.ldw > INT32_MAX * 16LL) return fail(SM_ERR_UNSUPPORTED, "%s: weight too large", who);
   char label[128];
   snprintf(label, sizeof(label), "%sgemm_%s[%lld,%d,%d]%s%s%s", g.norm == 1 ? "ln+" : (g.norm == 2 ? "rms+" : ""), g.dtype == SM_F32 ? "f32" : "bf16", (long long)g.M, g.N, g.K,
-           g.act == SM_ACT_GELU ? "+gelu" : (g.act ? "+glu" : ""), g.residual ? "+res" : "", g.c_rows.identity ? "" : "+scatter");
+           g.act == SM_ACT_GELU ? "+gelu" : (g.act ? "+glu" : ""), g.residual ? "+res" : "", g.c_rows.identity ? "" : (g.C2 ? "+copy2" : "+scatter"));
+  if (g.C2 && g.c_rows.identity) { const size_t n = strlen(label); snprintf(label + n, sizeof(label) - n, "+copy2"); }
   Timed tm(label, stream);
   int rc = launch_gemm(g, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);

@@ -517,8 +517,15 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     }
   }
   // VEC values w[] for columns col .. col + VEC - 1 of row r (output offset of the row: ro)
+  int64_t cur_row = 0;               // the row the chunk belongs to (set by epilogue_rows), for the second copy
   auto store_chunk = [&](bool row_ok, int64_t ro, int col, const float* w) __attribute__((always_inline)) {
     if (!row_ok || col >= n_out) return;
+    if (g.C2) {                      // the other layout: column-major, consecutive lanes (rows) write consecutive elements
+      T* C2 = (T*)g.C2;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (col + e < n_out) Elem<T>::st(C2 + (int64_t)(col + e) * g.M + cur_row, w[e]);
+    }
     if (g.c_transposed) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e)
@@ -588,6 +595,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     constexpr int mi = decltype(MI_)::value;
     const int64_t r = m0 + (wm * MI + mi) * 32 + l32;
     const bool row_ok = r < g.M;
+    cur_row = r;
     int64_t ro = 0;
     if (row_ok) {
       if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; ro = bi * g.c_batch_rows * n_out + (r - bi * g.c_batch_rows); }

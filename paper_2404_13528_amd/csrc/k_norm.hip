@@ -341,4 +341,56 @@ int launch_mean_tokens(const void* x, void* y, int B, int L, int C, int dtype, v
   return (int)hipGetLastError();
 }
 
+// ---- Reduce (sum), fp32 accumulation.  reduce_last: one wave per row of n contiguous elements (the reduction
+// dimension innermost: 16-byte loads when the row length allows).  reduce_first: one thread per inner element,
+// walking the outermost dimension (coalesced across threads, strided per thread).
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_last_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t rows, int n) {
+  constexpr int VEC = Elem<T>::VEC;
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const T* p = x + r * n;
+  float s = 0.f;
+  if (n % VEC == 0) {
+    typedef unsigned int v4 __attribute__((ext_vector_type(4)));
+    for (int c = lane * VEC; c < n; c += 64 * VEC) {
+      const v4 v = *(const v4*)(p + c);
+      if constexpr (VEC == 8) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += __uint_as_float(v[e] << 16) + __uint_as_float(v[e] & 0xffff0000u);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += __uint_as_float(v[e]);
+      }
+    }
+  } else {
+    for (int c = lane; c < n; c += 64) s += Elem<T>::ld(p + c);
+  }
+  s = wave_sum(s);
+  if (lane == 0) Elem<T>::st(y + r, s);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_first_kernel(const T* __restrict__ x, T* __restrict__ y, int n_outer, int64_t inner) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= inner) return;
+  float s = 0.f;
+  for (int o = 0; o < n_outer; ++o) s += Elem<T>::ld(x + (int64_t)o * inner + i);
+  Elem<T>::st(y + i, s);
+}
+int launch_reduce_last(const void* x, void* y, int64_t rows, int n, int dtype, void* stream) {
+  if (rows <= 0) return 0;
+  dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+  if (dtype == SM_F32) reduce_last_kernel<float><<<grid, block, 0, (hipStream_t)stream>>>((const float*)x, (float*)y, rows, n);
+  else reduce_last_kernel<bf16_t><<<grid, block, 0, (hipStream_t)stream>>>((const bf16_t*)x, (bf16_t*)y, rows, n);
+  return (int)hipGetLastError();
+}
+int launch_reduce_first(const void* x, void* y, int n_outer, int64_t inner, int dtype, void* stream) {
+  if (inner <= 0) return 0;
+  dim3 grid((unsigned)((inner + 255) / 256)), block(256);
+  if (dtype == SM_F32) reduce_first_kernel<float><<<grid, block, 0, (hipStream_t)stream>>>((const float*)x, (float*)y, n_outer, inner);
+  else reduce_first_kernel<bf16_t><<<grid, block, 0, (hipStream_t)stream>>>((const bf16_t*)x, (bf16_t*)y, n_outer, inner);
+  return (int)hipGetLastError();
+}
+
 }  // namespace sm

@@ -53,7 +53,8 @@ struct GemmArgs {
   const void* norm_beta;
   int a_gran;                   // > 0: A's K axis is contiguous only in granules of a_gran (4 or 1) elements;
   RowProg a_cols;               //      offset(r, k) = a_rows(r) + a_cols(k / a_gran) + k % a_gran
-};
+  void* C2;                     // non-null: a second copy of the result in the other layout, C2[n * M + r] = C[r][n]
+};                              //   (the redundant copy a producer keeps for consumers with another reduction dimension)
 int launch_gemm(const GemmArgs& a, void* stream);
 int gemm_tuning(int tile_rows, int stages);      // 0 = automatic; -1 on values the kernel has no variant for
 // times every (tile rows, stages) variant on g's operands and remembers the fastest for g's shape; synchronises.
@@ -98,6 +99,11 @@ int launch_lin32(const Lin32Args& a, void* stream);
 
 int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,
                      const void* rpb_table, void* stream);
+
+// y[r] = sum over the n contiguous elements of row r (fp32 accumulation): a Reduce whose reduction dimension is innermost
+int launch_reduce_last(const void* x, void* y, int64_t rows, int n, int dtype, void* stream);
+// y[i] = sum over o < n_outer of x[o * inner + i]: a Reduce over the outermost dimension of a [n_outer, inner] tensor
+int launch_reduce_first(const void* x, void* y, int n_outer, int64_t inner, int dtype, void* stream);
 
 // mean over tokens: x [B, L, C] -> y [B, C]
 int launch_mean_tokens(const void* x, void* y, int B, int L, int C, int dtype, void* stream);

@@ -104,6 +104,15 @@ def vit_case(B, S, E, h, F, seed=0, bf16=True, std=STD, in_std=1.0):
     return x, p
 
 
+def fanout_case(D1, D2, D3, Kin, Cout, seed=0, bf16=True):
+    """Operands of the Fig. 4 graph: activations N(0,1), weights scaled so that every output is O(1)."""
+    dr = Draw(seed, bf16)
+    a = dr.normal(D2 * D3, Kin)
+    w = dr.normal(D1, Kin, std=Kin ** -0.5)
+    wc = dr.normal(Cout, D3, std=D3 ** -0.5)
+    return a, w, wc
+
+
 def sd_case(B, C, H, W, Sc, Dc, F, seed=0, bf16=True, std=STD, in_std=1.0):
     dr = Draw(seed, bf16, std)
     x = dr.normal(B, C, H, W, std=in_std)
