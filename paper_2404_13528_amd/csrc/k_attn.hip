@@ -376,6 +376,10 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
 // V fragments and the bias values are read; the bias index is a difference of a per-query and a per-key term, the
 // shift mask a comparison of two region ids, both prepared once per wave.  The softmax works on base-2 logits:
 // scale and table are multiplied by log2 e on the way in.
+// BOTH: one wave per (window, head) that works through both query blocks in turn (K, V, the table column and the
+// per-key terms fetched once): half as many waves with a longer chain each, for grids of several rounds of residency,
+// where the rounds, not the chain, set the time.
+template <bool BOTH>
 __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                             const bf16_t* __restrict__ table, long total_waves) {
@@ -385,12 +389,12 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, hf = lane >> 5;
   const unsigned wid = blockIdx.x * 4u + wave;       // < 2^31: checked by the launcher
   if ((long)wid >= total_waves) return;              // whole waves leave; no workgroup barrier is used below
-  const int qb = (int)(wid & 1u);
-  const unsigned pair = wid >> 1;
+  const int qb0 = BOTH ? 0 : (int)(wid & 1u);
+  const unsigned pair = BOTH ? wid : wid >> 1;
   const int b = (int)(pair / (unsigned)a.heads);
   const int hh = (int)(pair - (unsigned)b * (unsigned)a.heads);
   const int w = a.window, n = a.nq, tw = 2 * w - 1;
-  if (32 * qb >= n) return;                          // a window of at most 32 tokens has no second query block
+  if (32 * qb0 >= n) return;                         // a window of at most 32 tokens has no second query block
   const bf16_t* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
   const bf16_t* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
   const bf16_t* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
@@ -398,13 +402,15 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
   const au32x4 zero = {0u, 0u, 0u, 0u};
   constexpr float LOG2E = 1.4426950408889634f;
   // ---- all global loads first
-  au32x4 qf[2], kf[2][2], vrow[4];
+  constexpr int NQB = BOTH ? 2 : 1;
+  au32x4 qfa[NQB][2], kf[2][2], vrow[4];
   unsigned short tv[4];
-  const int qi = 32 * qb + l32;                      // this lane's query
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     const int e = 16 * ks + 8 * hf;
-    qf[ks] = *(const au32x4*)(qp + (int64_t)min(qi, n - 1) * a.q_stride[2] + e);
+#pragma unroll
+    for (int qq = 0; qq < NQB; ++qq)
+      qfa[qq][ks] = *(const au32x4*)(qp + (int64_t)min(32 * (qb0 + qq) + l32, n - 1) * a.q_stride[2] + e);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       const int j = 32 * kb + l32;
@@ -430,10 +436,6 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
     if (a.shift > 0) info |= (3 * region(wy * w + yj, a.H, w, a.shift) + region(wx * w + xj, a.W, w, a.shift)) << 16;
     k_lds[wave][j] = info;
   }
-  // per-query terms
-  const int yi = (int)(((float)qi + 0.5f) * inv_w), xi = qi - yi * w;
-  const int qa = yi * tw + xi + (w - 1) * 2 * w;
-  const int rq = a.shift > 0 ? 3 * region(wy * w + yi, a.H, w, a.shift) + region(wx * w + xi, a.W, w, a.shift) : 0;
   __builtin_amdgcn_sched_barrier(0);                 // the index terms above are computed while the loads are in flight
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
@@ -441,6 +443,19 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
     *(au32x4*)(&v_lds[wave][c * 8]) = vrow[t];
     t_lds[wave][lane + 64 * t] = bf2f(tv[t]) * LOG2E;
   }
+  __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0): this wave's LDS writes are done (wave-private data)
+  const float sc2 = a.scale * LOG2E;
+  const bool shifted = a.shift > 0;                  // wave-uniform
+#pragma unroll
+  for (int qq = 0; qq < NQB; ++qq) {
+  const int qb = qb0 + qq;
+  if (32 * qb >= n) break;
+  const int qi = 32 * qb + l32;                      // this lane's query
+  const au32x4* qf = qfa[qq];
+  // per-query terms
+  const int yi = (int)(((float)qi + 0.5f) * inv_w), xi = qi - yi * w;
+  const int qa = yi * tw + xi + (w - 1) * 2 * w;
+  const int rq = a.shift > 0 ? 3 * region(wy * w + yi, a.H, w, a.shift) + region(wx * w + xi, a.W, w, a.shift) : 0;
   // ---- S^T[kb] = K_kb Q^T
   f32x16_t s[2];
 #pragma unroll
@@ -451,10 +466,7 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
     for (int ks = 0; ks < 2; ++ks)
       s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[kb][ks]), __builtin_bit_cast(bf16x8_t, qf[ks]), s[kb], 0, 0, 0);
   }
-  __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0): this wave's LDS writes are done (wave-private data)
   // ---- bias, mask, softmax for this lane's query (keys: 16 per block in this lane, the other 16 in lane ^ 32)
-  const float sc2 = a.scale * LOG2E;
-  const bool shifted = a.shift > 0;                  // wave-uniform
   float mx = -INFINITY;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
@@ -501,13 +513,15 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
       }
       oacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf), __builtin_bit_cast(bf16x8_t, pf[kb][ks2]), oacc, 0, 0, 0);
     }
-  if (qi >= n) return;
+  if (qi < n) {
 #pragma unroll
-  for (int g4 = 0; g4 < 4; ++g4) {
-    const int e = g4 * 8 + hf * 4;
-    const f32x2_t x0 = {oacc[4 * g4] * inv, oacc[4 * g4 + 1] * inv}, x1 = {oacc[4 * g4 + 2] * inv, oacc[4 * g4 + 3] * inv};
-    *(uint2*)(op + (int64_t)qi * a.o_stride[2] + e) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
-                                                                __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int e = g4 * 8 + hf * 4;
+      const f32x2_t x0 = {oacc[4 * g4] * inv, oacc[4 * g4 + 1] * inv}, x1 = {oacc[4 * g4 + 2] * inv, oacc[4 * g4 + 3] * inv};
+      *(uint2*)(op + (int64_t)qi * a.o_stride[2] + e) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
+                                                                  __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
+    }
+  }
   }
 }
 
@@ -565,10 +579,17 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     return (int)hipGetLastError();
   }
   if (d.kind == SM_ATT_WINDOW && d.d == 32 && d.nq <= 64 && d.window <= 8) {
-    const long waves = 2L * d.nb * d.heads;           // one per (window, head, query block)
+    long waves = 2L * d.nb * d.heads;                 // one per (window, head, query block)
     if (waves >= (1L << 31)) return (int)hipErrorInvalidValue;
-    attn_window32_kernel<<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
-                                                                                (bf16_t*)o, (const bf16_t*)rpb_table, waves);
+    // 256 CUs hold 20 of these waves each: beyond one round of residency a wave takes both query blocks
+    if (waves > 256L * 20 && d.nq > 32) {
+      waves /= 2;
+      attn_window32_kernel<true><<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                                        (bf16_t*)o, (const bf16_t*)rpb_table, waves);
+    } else {
+      attn_window32_kernel<false><<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                                         (bf16_t*)o, (const bf16_t*)rpb_table, waves);
+    }
     return (int)hipGetLastError();
   }
   if (d.kind != SM_ATT_WINDOW && d.scale > 0.f) {
