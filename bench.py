@@ -95,9 +95,9 @@ def kernel_model(label):
     if m:
         r, n = int(m.group(2)), int(m.group(3))
         return (r * n + r) * e, float(r * n)
-    m = re.match(r"fill_row_table\[(\d+)\]", label)
+    m = re.match(r"fill_row_tables?\[(\d+)\]", label)
     if m:
-        return 4 * int(m.group(1)), 0.0
+        return (4 * int(m.group(1)) if "table[" in label else 0), 0.0
     return 0, 0.0
 
 

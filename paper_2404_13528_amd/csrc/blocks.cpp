@@ -604,15 +604,17 @@ extern "C" int sm_run_chain(const sm_chain_desc* c, const void* const* weights, 
   char* base = (char*)ws;
   count_reset();
   // the row-offset tables of every map the chain reads, before its first kernel
-  if (z.embed && (rc = fill_tables(z.embed->tables, base + z.embed_off, stream, mode == SM_ELIDED ? 3ull : ~3ull))) return rc;   // A rows + columns | the unfold copy
+  TableFiller filler(stream);
+  if (z.embed && (rc = filler.add(z.embed->tables, base + z.embed_off, mode == SM_ELIDED ? 3ull : ~3ull))) return rc;   // A rows + columns | the unfold copy
   for (int s = 0; s < c->n_stages; ++s) {
     const ChainLayout::Stage& S = z.stages[(size_t)s];
     for (int sh = 0; sh < 2; ++sh) {
-      if (S.plan[sh] && need[sh][(size_t)s] && (rc = fill_tables(S.plan[sh]->tables(mode), base + S.plan_off[sh], stream, need[sh][(size_t)s]))) return rc;
-      if (S.next[sh] && need_next[sh][(size_t)s] && (rc = fill_tables(S.next[sh]->tables, base + S.next_off[sh], stream, ~0ull))) return rc;
+      if (S.plan[sh] && need[sh][(size_t)s] && (rc = filler.add(S.plan[sh]->tables(mode), base + S.plan_off[sh], need[sh][(size_t)s]))) return rc;
+      if (S.next[sh] && need_next[sh][(size_t)s] && (rc = filler.add(S.next[sh]->tables, base + S.next_off[sh], ~0ull))) return rc;
     }
-    if (S.merge && (rc = fill_tables(S.merge->tables, base + S.merge_off, stream, mode == SM_ELIDED ? 1ull : ~1ull))) return rc;      // LayerNorm's gather | the copy
+    if (S.merge && (rc = filler.add(S.merge->tables, base + S.merge_off, mode == SM_ELIDED ? 1ull : ~1ull))) return rc;      // LayerNorm's gather | the copy
   }
+  if ((rc = filler.flush())) return rc;
   void* blk_ws = base;
   void* act[2] = {base + z.block, base + z.block + z.act};
   int n_compute = 0, n_copy = 0;

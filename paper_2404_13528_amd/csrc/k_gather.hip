@@ -99,6 +99,63 @@ int launch_fill_rows(const RowProg& prog, int64_t n_rows, int32_t* table, void* 
   return (int)hipGetLastError();
 }
 
+// packed program: [n_atoms, nterm, c0 lo, c0 hi], per atom [div, mod, c0, nterm, div_mul, div_sh, mod_mul, mod_sh,
+// nterm x (t_atom, t_coef)], then nterm x (t_atom, coef lo, coef hi)
+int fill_pack(const RowProg& p, int32_t* w, int room) {
+  int n = 4;
+  for (int i = 0; i < p.n_atoms; ++i) n += 8 + 2 * p.atoms[i].nterm;
+  n += 3 * p.nterm;
+  if (n > room) return -1;
+  int o = 0;
+  w[o++] = p.n_atoms; w[o++] = p.nterm; w[o++] = (int32_t)(uint32_t)(p.c0 & 0xffffffff); w[o++] = (int32_t)(p.c0 >> 32);
+  for (int i = 0; i < p.n_atoms; ++i) {
+    const ProgAtom& a = p.atoms[i];
+    w[o++] = a.div; w[o++] = a.mod; w[o++] = a.c0; w[o++] = a.nterm;
+    w[o++] = (int32_t)a.div_mul; w[o++] = (int32_t)a.div_sh; w[o++] = (int32_t)a.mod_mul; w[o++] = (int32_t)a.mod_sh;
+    for (int t = 0; t < a.nterm; ++t) { w[o++] = a.t_atom[t]; w[o++] = a.t_coef[t]; }
+  }
+  for (int t = 0; t < p.nterm; ++t) { w[o++] = p.t_atom[t]; w[o++] = (int32_t)(uint32_t)(p.t_coef[t] & 0xffffffff); w[o++] = (int32_t)(p.t_coef[t] >> 32); }
+  return o;
+}
+__global__ __launch_bounds__(256) void fill_batch_kernel(FillBatch b) {
+  const SM_KARG FillBatch* bk = kernarg_ptr<FillBatch>();
+  int job = 0;
+  for (int j = 1; j < bk->n_jobs; ++j) if ((int)blockIdx.x >= bk->first_block[j]) job = j;       // wave-uniform
+  const int64_t r = (int64_t)((int)blockIdx.x - bk->first_block[job]) * 256 + threadIdx.x;
+  if (r >= bk->n_rows[job]) return;
+  const SM_KARG int32_t* w = bk->words + bk->word_off[job];
+  const int n_atoms = w[0], nterm = w[1];
+  int64_t off = (int64_t)(uint32_t)w[2] | ((int64_t)w[3] << 32);
+  i32x16 val = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  int o = 4;
+  for (int i = 0; i < n_atoms; ++i) {
+    const int div = w[o], mod = w[o + 1], nt = w[o + 3];
+    int x = w[o + 2];
+    const unsigned div_mul = (unsigned)w[o + 4], div_sh = (unsigned)w[o + 5], mod_mul = (unsigned)w[o + 6], mod_sh = (unsigned)w[o + 7];
+    o += 8;
+    for (int t = 0; t < nt; ++t) {
+      const int id = w[o + 2 * t];
+      x += w[o + 2 * t + 1] * (id < 0 ? (int)r : val[id & 15]);
+    }
+    o += 2 * nt;
+    if (div > 1) x = (int)(__umulhi((unsigned)x, div_mul) >> div_sh);
+    if (mod > 1) x -= (int)(__umulhi((unsigned)x, mod_mul) >> mod_sh) * mod;
+    else if (mod == 1) x = 0;
+    val[i & 15] = x;
+  }
+  for (int t = 0; t < nterm; ++t) {
+    const int id = w[o + 3 * t];
+    const int64_t coef = (int64_t)(uint32_t)w[o + 3 * t + 1] | ((int64_t)w[o + 3 * t + 2] << 32);
+    off += coef * (int64_t)(id < 0 ? (int)r : val[id & 15]);
+  }
+  ((int32_t*)bk->dst[job])[r] = (int32_t)off;
+}
+int launch_fill_batch(const FillBatch& b, void* stream) {
+  if (b.n_jobs <= 0 || b.total_blocks <= 0) return 0;
+  fill_batch_kernel<<<dim3((unsigned)b.total_blocks), dim3(256), 0, (hipStream_t)stream>>>(b);
+  return (int)hipGetLastError();
+}
+
 __global__ void empty_kernel() {}
 int launch_empty(void* stream) {
   empty_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>();

@@ -20,6 +20,26 @@ int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const voi
 
 // table[r] = offset of row r under `prog` (interpreted), r < n_rows: fills one per-row offset table
 int launch_fill_rows(const RowProg& prog, int64_t n_rows, int32_t* table, void* stream);
+// Several tables in one launch: the programs travel in the kernel-argument segment in a packed form (only the atoms
+// and terms a program has), at most FILL_MAX_JOBS tables and FILL_MAX_WORDS words per launch.
+constexpr int FILL_MAX_JOBS = 8, FILL_MAX_WORDS = 800;
+struct FillBatch {
+  int32_t n_jobs, total_blocks;
+  int64_t dst[FILL_MAX_JOBS];
+  int32_t n_rows[FILL_MAX_JOBS], first_block[FILL_MAX_JOBS], word_off[FILL_MAX_JOBS];
+  int32_t words[FILL_MAX_WORDS];
+};
+int fill_pack(const RowProg& p, int32_t* words, int room);      // words used, or -1 if the program does not fit in `room`
+int launch_fill_batch(const FillBatch& b, void* stream);
+// collects the tables of several regions (a chain's plans) into as few fill launches as possible
+class TableFiller {
+ public:
+  explicit TableFiller(void* stream) : stream_(stream), used_(0) { b_.n_jobs = 0; b_.total_blocks = 0; }
+  int add(const TableRegion& r, void* region, uint64_t which);      // SM_OK or an error; may launch when a batch fills up
+  int flush();
+ private:
+  FillBatch b_; void* stream_; int used_;
+};
 
 struct NormArgs {
   const void* x; const void* gamma; const void* beta; void* y;
