@@ -19,6 +19,7 @@
 //
 // fp32 path (window attention only): plain FMA kernel, one workgroup per
 // (window, head), K / V / scores in LDS.
+#include <type_traits>
 #include "device_common.h"
 #include "kernels.h"
 
@@ -53,7 +54,7 @@ __device__ __forceinline__ float window_term(const WinGeom& g, const T* table, i
 }
 
 template <int DK, int DB, int KIND>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                         const bf16_t* __restrict__ table, int n_qblk, long total_waves) {
   const int lane = threadIdx.x & 63, l32 = lane & 31, hf = lane >> 5;
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
 // per-key terms fetched once): half as many waves with a longer chain each, for grids of several rounds of residency,
 // where the rounds, not the chain, set the time.
 template <bool BOTH>
-__global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(256, 2) void attn_window32_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                             const bf16_t* __restrict__ table, long total_waves) {
   __shared__ bf16_t v_lds[4][64 * 32];
@@ -525,6 +526,230 @@ __global__ __launch_bounds__(256) void attn_window32_kernel(sm_attention_desc a,
   }
 }
 
+// Windows of 7 x 7 tokens, head size 32 (every Swin configuration).  Two things bound the general window kernel
+// above at these sizes, neither of them HBM: the texture path (its loads and stores put the rows of a head slice in
+// adjacent lanes, four cache lines per lane quad) and the vector ALU (index arithmetic per score).  This variant
+//   * moves Q, K, V and O between global memory and LDS in 16-byte pieces with the four pieces of a row's 64-byte
+//     head slice in adjacent lanes, and reads the MFMA fragments from LDS (rows at a pitch of 80 bytes);
+//   * deals the keys to the MFMA rows so that the half-wave hf owns the window rows y with y & 1 == hf, in "slot"
+//     order s = (y >> 1) * 7 + x (28 slots per half, 4 of them padding in the even half, 11 in the odd one): a
+//     lane's 16 scores of key block kb are slots 16 kb .. 16 kb + 15 of its own half.  Then the relative-position
+//     index of (query, slot) is a per-lane base minus a compile-time constant, i.e. one LDS read with an immediate
+//     offset from the head's table column (pre-multiplied by log2 e); padding is known at compile time (slots >=
+//     28) or per half-wave (odd half, slots 21 .. 27); the shifted-window mask is a 64-bit "same region" set per
+//     query (two ballots over the keys), tested at constant bit positions, and only in the windows of the last row
+//     or column, the only ones whose tokens lie in more than one region;
+//   * keeps V transposed in LDS ([half][channel][slot]), so that a V^T fragment is one 16-byte read, shared by
+//     both query blocks.
+// All LDS data is private to its wave (the LDS queue keeps a wave's accesses in order): no workgroup barrier.
+template <bool BOTH>
+__global__ __launch_bounds__(256, 4) void attn_window7_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                           const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
+                                                           const bf16_t* __restrict__ table, long total_waves) {
+  constexpr int RP = 80;                             // bytes per staged row: 64 + 16 keeps 16-byte reads of adjacent rows on distinct banks
+  constexpr int PITCH = 40;                          // slots per channel row of V^T: 32 + 8, keeps the 16-byte reads aligned
+  constexpr int TPAD = 16, TLEN = 208;               // the table column sits at [TPAD, TPAD + 169); padded slots read around it
+  // per wave: Q rows [0, 3920) and K rows [K_OFF, K_OFF + 3920) first, then V^T in [0, 5120), then the O rows in [0, 5120)
+  constexpr int K_OFF = 3968, T_OFF = 7936, WAVE_BYTES = T_OFF + TLEN * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * WAVE_BYTES];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, l32 = lane & 31, hf = lane >> 5;      // wave: scalar
+  const unsigned wid = blockIdx.x * 4u + wave;       // < 2^31: checked by the launcher
+  if ((long)wid >= total_waves) return;              // whole waves leave
+  const int qb0 = BOTH ? 0 : (int)(wid & 1u);
+  const unsigned pair = BOTH ? wid : wid >> 1;
+  const int b = (int)(pair / (unsigned)a.heads);
+  const int hh = (int)(pair - (unsigned)b * (unsigned)a.heads);
+  const bf16_t* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
+  const bf16_t* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
+  const bf16_t* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
+  bf16_t* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
+  const int qs = (int)a.q_stride[2], ksd = (int)a.k_stride[2], vs = (int)a.v_stride[2], os = (int)a.o_stride[2];      // < 2^24: checked by the launcher
+  const au32x4 zero = {0u, 0u, 0u, 0u};
+  constexpr float LOG2E = 1.4426950408889634f;
+  constexpr int NQB = BOTH ? 2 : 1, QP = BOTH ? 4 : 2;      // query blocks of this wave; 64-lane rounds of 16-byte pieces that cover its query rows
+  unsigned char* L = lds_all + wave * WAVE_BYTES;
+  // ---- all global loads first: piece c = lane + 64 t is channels 8 (c & 3) .. of row c >> 2 (196 pieces per tensor)
+  au32x4 qv[QP], kv[4], vv[4];
+  unsigned short tv[3];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int c = lane + 64 * t, row = min(c >> 2, 48), part = c & 3;
+    kv[t] = *(const au32x4*)(kp + (row * ksd + part * 8));
+    vv[t] = *(const au32x4*)(vp + (row * vs + part * 8));
+    if (t < QP) qv[t] = *(const au32x4*)(qp + (min(32 * qb0 + (c >> 2), 48) * qs + part * 8));
+  }
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    const int ti = lane + 64 * t;
+    tv[t] = ti < 169 ? table[ti * a.heads + hh] : (unsigned short)0;
+  }
+  // ---- index terms while the loads are in flight.  (n * 37) >> 8 == n / 7 for 0 <= n < 56.
+  int krow[2];
+  bool kok[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {                   // the key whose K row is MFMA row l32 of block kb
+    const int s = 16 * kb + (l32 >> 3) * 4 + (l32 & 3), hk = (l32 >> 2) & 1;
+    const int g = (s * 37) >> 8, y = 2 * g + hk;
+    kok[kb] = s < 28 && y < 7;
+    krow[kb] = kok[kb] ? y * 7 + (s - 7 * g) : 0;
+  }
+  int vdst[4];                                       // element index in V^T of this lane's piece t, channel part * 8
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int c = lane + 64 * t;                     // the 196 real pieces, then the 60 pieces of the 15 padded slots
+    const bool real = c < 196;
+    const int row = c >> 2, part = c & 3;
+    const int y = (row * 37) >> 8, x = row - 7 * y;
+    const int zs = (c - 196) >> 2;
+    const int hk = real ? (y & 1) : (zs < 4 ? 0 : 1);
+    const int s = real ? (y >> 1) * 7 + x : (zs < 4 ? 28 + zs : 17 + zs);
+    vdst[t] = (hk * 32 + part * 8) * PITCH + s;
+  }
+  const int nWx = a.W / 7, nWy = a.H / 7, nW = nWy * nWx, win = b % nW, wy = win / nWx, wx = win - wy * nWx;
+  const bool edge = a.shift > 0 && (wy == nWy - 1 || wx == nWx - 1);      // wave-uniform: elsewhere all tokens share region 0
+  unsigned long long my = ~0ull, mxm = ~0ull;
+  int ry0 = 0, rx0 = 0;
+  if (edge) {
+    const int j = min(lane, 48), yj = (j * 37) >> 8, xj = j - 7 * yj;
+    ry0 = region(wy * 7, a.H, 7, a.shift); rx0 = region(wx * 7, a.W, 7, a.shift);
+    my = __ballot(region(wy * 7 + yj, a.H, 7, a.shift) == ry0);
+    mxm = __ballot(region(wx * 7 + xj, a.W, 7, a.shift) == rx0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- Q and K rows and the table column into LDS, the MFMA fragments out of it
+  float* tw = (float*)(L + T_OFF);
+  if (lane < TPAD) tw[lane] = 0.f;
+#pragma unroll
+  for (int t = 0; t < 3; ++t) tw[TPAD + lane + 64 * t] = bf2f(tv[t]) * LOG2E;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int c = lane + 64 * t, off = (c >> 2) * RP + (c & 3) * 16;
+    if (c < 196) {
+      *(au32x4*)(L + K_OFF + off) = kv[t];
+      if (t < QP) *(au32x4*)(L + off) = qv[t];         // rows past the window's last repeat it (never stored)
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  au32x4 qfa[NQB][2], kf[2][2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+    for (int qq = 0; qq < NQB; ++qq) qfa[qq][ks] = *(const au32x4*)(L + min(32 * qq + l32, BOTH ? 48 : 31) * RP + (2 * ks + hf) * 16);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      kf[kb][ks] = *(const au32x4*)(L + K_OFF + krow[kb] * RP + (2 * ks + hf) * 16);
+      if (!kok[kb]) kf[kb][ks] = zero;
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  // ---- V transposed over the Q / K rows, its fragments out
+  bf16_t* vt = (bf16_t*)L;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    if (lane + 64 * t >= 196) vv[t] = zero;          // padded keys must contribute exact zeros
+#pragma unroll
+    for (int u = 0; u < 8; ++u) vt[vdst[t] + u * PITCH] = (bf16_t)(vv[t][u >> 1] >> (16 * (u & 1)));
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  au32x4 vf[2][2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) vf[kb][ks2] = *(const au32x4*)(vt + (hf * 32 + l32) * PITCH + 16 * kb + 8 * ks2);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const float sc2 = a.scale * LOG2E;
+  auto queries = [&](auto edge_c) {
+  constexpr bool EDGE = decltype(edge_c)::value;
+#pragma unroll
+  for (int qq = 0; qq < NQB; ++qq) {
+    const int qi = 32 * (qb0 + qq) + l32;            // this lane's query
+    const int qc = min(qi, 48), yi = (qc * 37) >> 8, xi = qc - 7 * yi;
+    const float* tq = tw + (yi * 13 + xi + TPAD - 13 * hf);      // + 84 - (26 g + x) per slot, all >= 0
+    // ---- S^T[kb] = K_kb Q^T
+    f32x16_t s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[kb][ks]), __builtin_bit_cast(bf16x8_t, qfa[qq][ks]), s[kb], 0, 0, 0);
+    }
+    // ---- bias, mask, softmax for this lane's query (28 slots here, the other half's 28 in lane ^ 32)
+    unsigned same_lo = ~0u, same_hi = ~0u;
+    if (EDGE) {
+      const bool ysame = region(wy * 7 + yi, a.H, 7, a.shift) == ry0, xsame = region(wx * 7 + xi, a.W, 7, a.shift) == rx0;
+      const unsigned long long same = ((ysame ? my : ~my) & (xsame ? mxm : ~mxm)) >> (7 * hf);
+      same_lo = (unsigned)same; same_hi = (unsigned)(same >> 32);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int sl = 16 * kb + i;
+        if (sl >= 28) continue;
+        const int g = sl / 7, x7 = sl - 7 * g;
+        float x = fmaf(s[kb][i], sc2, tq[84 - (26 * g + x7)]);
+        if (EDGE) {
+          const int bit = 14 * g + x7;               // the key's natural index, less 7 hf
+          const unsigned wd = bit < 32 ? same_lo : same_hi;
+          if (!((wd >> (bit & 31)) & 1u)) x += -100.f * LOG2E;
+        }
+        if (g == 3 && hf) x = -INFINITY;             // window row 7 does not exist
+        s[kb][i] = x;
+        mx = fmaxf(mx, x);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    au32x4 pf[2][2];
+    float sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        unsigned pw = 0u;
+        if (16 * kb + i < 28) {
+          const float p0 = __builtin_amdgcn_exp2f(s[kb][i] - mx), p1 = __builtin_amdgcn_exp2f(s[kb][i + 1] - mx);
+          const f32x2_t pp = {p0, p1};
+          pw = __builtin_bit_cast(unsigned, __builtin_convertvector(pp, bf16x2_t));
+          sum += p0 + p1;
+        }
+        pf[kb][i >> 3][(i >> 1) & 3] = pw;
+      }
+    sum += __shfl_xor(sum, 32, 64);
+    const float inv = 1.f / sum;
+    // ---- O^T = V^T P^T, then this lane's 4 x 4 channels of its query's row into the LDS copy of O
+    f32x16_t oacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[i] = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+        oacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[kb][ks2]), __builtin_bit_cast(bf16x8_t, pf[kb][ks2]), oacc, 0, 0, 0);
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const f32x2_t x0 = {oacc[4 * g4] * inv, oacc[4 * g4 + 1] * inv}, x1 = {oacc[4 * g4 + 2] * inv, oacc[4 * g4 + 3] * inv};
+      *(uint2*)(L + (32 * qq + l32) * RP + g4 * 16 + hf * 8) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
+                                                                          __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
+    }
+  }
+  };
+  if (edge) queries(std::true_type{}); else queries(std::false_type{});      // a scalar branch: edge is wave-uniform
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  // ---- O rows out, 64 contiguous bytes per lane quad
+#pragma unroll
+  for (int t = 0; t < QP; ++t) {
+    const int c = lane + 64 * t, row = 32 * qb0 + (c >> 2);
+    if (row < 49) *(au32x4*)(op + (row * os + (c & 3) * 8)) = *(const au32x4*)(L + (c >> 2) * RP + (c & 3) * 16);
+  }
+}
+
 // fp32 window attention: nq, nk <= 64, d <= 64.  One workgroup of 64 threads
 // per (window, head); thread i owns query i.
 __global__ __launch_bounds__(64) void attn_window_f32_kernel(sm_attention_desc a, const float* __restrict__ q, const float* __restrict__ k,
@@ -582,6 +807,18 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     long waves = 2L * d.nb * d.heads;                 // one per (window, head, query block)
     if (waves >= (1L << 31)) return (int)hipErrorInvalidValue;
     // 256 CUs hold 20 of these waves each: beyond one round of residency a wave takes both query blocks
+    const int64_t smax = 1 << 24;
+    if (d.window == 7 && d.nq == 49 && d.nk == 49 && d.q_stride[2] < smax && d.k_stride[2] < smax && d.v_stride[2] < smax && d.o_stride[2] < smax) {
+      if (waves > 256L * 20) {
+        waves /= 2;
+        attn_window7_kernel<true><<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                                         (bf16_t*)o, (const bf16_t*)rpb_table, waves);
+      } else {
+        attn_window7_kernel<false><<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                                          (bf16_t*)o, (const bf16_t*)rpb_table, waves);
+      }
+      return (int)hipGetLastError();
+    }
     if (waves > 256L * 20 && d.nq > 32) {
       waves /= 2;
       attn_window32_kernel<true><<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s>>>(d, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,

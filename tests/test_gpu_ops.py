@@ -145,10 +145,18 @@ def test_linear_transposed_store():
     assert_close(out, want, dtype, "NCHW store")
 
 
+# 7 x 7 windows below and above the wave count at which one wave takes both query blocks (interior, last-row,
+# last-column and corner windows in each), and other window sizes (the general window kernel)
+WINDOW_CASES = [(2, 14, 21, 96, 3, 7, 3), (43, 28, 28, 128, 4, 7, 3), (2, 8, 12, 64, 2, 4, 2), (1, 16, 24, 64, 2, 8, 4)]
+
+
 @pytest.mark.parametrize("dtype", DT)
-@pytest.mark.parametrize("s", [0, 3])
-def test_window_attention_in_place_qkv(dtype, s):
-    B, H, W, C, h, w = 2, 14, 21, 96, 3, 7
+@pytest.mark.parametrize("shifted", [False, True])
+@pytest.mark.parametrize("B,H,W,C,h,w,shift", WINDOW_CASES)
+def test_window_attention_in_place_qkv(dtype, shifted, B, H, W, C, h, w, shift):
+    if dtype == torch.float32 and B > 8:
+        pytest.skip("the fp32 kernel does not depend on the wave count")
+    s = shift if shifted else 0
     N, d = w * w, C // h
     B_ = B * (H // w) * (W // w)
     qkv = draw((B_, N, 3 * C), 27, dtype)               # O(1) logits
