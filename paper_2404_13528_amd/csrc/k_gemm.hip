@@ -92,9 +92,27 @@ enum { EPI_PLAIN = 0, EPI_GELU = 1, EPI_GLU = 2, EPI_ROPE = 3 };
 // (256 x 128) halves the L2 -> LDS traffic per flop of the 4-wave one and is used where the grid is large enough.
 // LNF (register path): LayerNorm / RMSNorm of A's rows folded into the load: row statistics in the prologue, the
 // chunks normalised between their arrival in registers and the LDS store.
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM, int NS, bool LNF>
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM, int NS, bool LNF, bool GEN>
 __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm, TileOrder ts) {
   const SM_KARG GemmArgs* gk = kernarg_ptr<GemmArgs>();      // g is the first argument
+  // The kernel-argument fields that the per-tile code needs, read once and pinned in scalar registers.  Left to
+  // itself the compiler re-reads them from the argument segment where they are used: one scalar load and one wait
+  // each, strung one after the other by the branches between them, at every tile boundary.
+#define SM_PIN(x) asm volatile("" : "+s"(x))
+  int a_ident = g.a_rows.identity, c_ident = g.c_rows.identity, n_cols = g.N, c_cols_on = g.c_cols_on;
+  int64_t a_ld = g.a_rows.ld, c_ld = g.c_rows.ld, m_rows = g.M;
+  const int32_t* a_tab = g.a_rows.table;
+  const int32_t* c_tab = g.c_rows.table;
+  const void* bias_p = g.bias;
+  const void* res_p = g.residual;
+  void* c_p = g.C;
+  SM_PIN(a_ident); SM_PIN(c_ident); SM_PIN(n_cols); SM_PIN(c_cols_on); SM_PIN(a_ld); SM_PIN(c_ld); SM_PIN(m_rows);
+  SM_PIN(a_tab); SM_PIN(c_tab); SM_PIN(bias_p); SM_PIN(res_p); SM_PIN(c_p);
+  int64_t ldw = g.ldw;
+  SM_PIN(ldw);
+  SM_PIN(cm.mode); SM_PIN(cm.half); SM_PIN(cm.rope_cols); SM_PIN(cm.rope_dim);
+  SM_PIN(ts.tiles_m); SM_PIN(ts.tiles_n); SM_PIN(ts.strip); SM_PIN(ts.group);
+#undef SM_PIN
   constexpr int VEC = Elem<T>::VEC;
   constexpr int BM = 32 * MI * WM, BN = 128, BK = 8 * VEC;
   constexpr int A_SLOTS = BM * 8, B_SLOTS = BN * 8;
@@ -107,34 +125,43 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
   // the grid is cut into strips of `ts.strip` column tiles, as many strips as make the sum of the XCDs' A and W
   // panels smallest), and (2) inside a strip the tiles that are resident together form blocks of `ts.group` row
   // tiles by several column tiles rather than one long row, which shares both operands' panels between them.
-  const int n_tiles = gridDim.x;
-  const int xcd = blockIdx.x & 7, q8 = n_tiles >> 3, r8 = n_tiles & 7;
-  const int t = xcd * q8 + min(xcd, r8) + (blockIdx.x >> 3);          // XCD x owns q8 (+1 if x < r8) consecutive positions
+  // The grid may be smaller than the tile count (a multiple of 8 then): the workgroup takes the virtual block ids
+  // blockIdx.x, + gridDim.x, ..., which all fall to its own XCD, in the order of that XCD's run.
+  const int n_tiles = ts.tiles_m * ts.tiles_n;
+  const int q8 = n_tiles >> 3, r8 = n_tiles & 7;
   const int strip_tiles = ts.strip * ts.tiles_m;
-  const int sidx = min(t / strip_tiles, (ts.tiles_n - 1) / ts.strip);
-  const int rem = t - sidx * strip_tiles;
-  const int sw = min(ts.strip, ts.tiles_n - sidx * ts.strip);         // width of this strip
-  const int gidx = rem / (ts.group * sw), r2 = rem - gidx * ts.group * sw;
-  const int gh = min(ts.group, ts.tiles_m - gidx * ts.group);         // height of this group of rows
-  const int gcol = r2 / gh;
-  const int tile_m = gidx * ts.group + (r2 - gcol * gh), tile_n = sidx * ts.strip + gcol;
-  const int64_t m0 = (int64_t)tile_m * BM;
-  const int n0 = tile_n * BN;
+  auto decode = [&](int vb_, int64_t& m0_, int& n0_) {
+    const int xcd = vb_ & 7;
+    const int t = xcd * q8 + min(xcd, r8) + (vb_ >> 3);          // XCD x owns q8 (+1 if x < r8) consecutive positions
+    const int sidx = min(t / strip_tiles, (ts.tiles_n - 1) / ts.strip);
+    const int rem = t - sidx * strip_tiles;
+    const int sw = min(ts.strip, ts.tiles_n - sidx * ts.strip);         // width of this strip
+    const int gidx = rem / (ts.group * sw), r2 = rem - gidx * ts.group * sw;
+    const int gh = min(ts.group, ts.tiles_m - gidx * ts.group);         // height of this group of rows
+    const int gcol = r2 / gh;
+    m0_ = (int64_t)(gidx * ts.group + (r2 - gcol * gh)) * BM;
+    n0_ = (sidx * ts.strip + gcol) * BN;
+  };
+  int vb = blockIdx.x;
+  int64_t m0;
+  int n0;
+  decode(vb, m0, n0);
   const T* A = (const T*)g.A;
   const T* W = (const T*)g.W;
-  const int span0 = n0 + wn * 64;                    // logical start of this wave's 64 columns
-  const int pcb[2] = {phys_col(cm, span0), phys_col(cm, span0 + 32)};      // W row / bias index of a block's first column
-  // The bias words of this lane's columns (runs of four: 8 or 16 bytes each) are requested first of all, so that
-  // they are older than every K-tile load (the tile waits below count loads in issue order) and long since there
-  // when the epilogue unpacks them.
+  int span0, pcb[2];                                 // logical start of this wave's 64 columns; W row / bias index of a block's first column
+  auto set_cols = [&]() { span0 = n0 + wn * 64; pcb[0] = phys_col(cm, span0); pcb[1] = phys_col(cm, span0 + 32); };
+  set_cols();
+  // The bias words of this lane's columns (runs of four: 8 or 16 bytes each) are requested at the start of a tile;
+  // the tile waits of the K loop (which count loads in issue order) have long since covered them when the epilogue
+  // unpacks them.
   constexpr int BW = VEC == 8 ? 2 : 4;
   unsigned braw[2][4][BW];
-  {
+  auto load_bias = [&]() {
     // unconditional loads (no select on the loaded words, which would make the prologue wait for them): without a
     // bias, or where a run is cut by the end of the columns, a valid address is read and the words are not used
-    const bool bias_vec = g.bias && g.N >= 4;
-    const T* bp = bias_vec ? (const T*)g.bias : W;
-    const int pmax = bias_vec ? ((g.N - 4) & ~3) : 0;
+    const bool bias_vec = bias_p && n_cols >= 4;
+    const T* bp = bias_vec ? (const T*)bias_p : W;
+    const int pmax = bias_vec ? ((n_cols - 4) & ~3) : 0;
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
@@ -145,15 +172,290 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
       }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-  }
+  };
+  load_bias();
+  // output offsets of this lane's MI rows (INT64_MIN past the last row), also requested at the start of the tile:
+  // with a row table they are loads, and nothing in the epilogue should have to wait for them
+  int64_t ro_t[MI];
+  auto load_out_rows = [&]() {
+    int rt[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int64_t r = m0 + (wm * MI + mi) * 32 + l32;
+      if (c_ident) ro_t[mi] = r * c_ld;
+      else if (c_tab) rt[mi] = c_tab[min(r, m_rows - 1)];
+      else ro_t[mi] = eval_rows_k(&gk->c_rows, min(r, m_rows - 1));
+    }
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int64_t r = m0 + (wm * MI + mi) * 32 + l32;
+      if (!c_ident && c_tab) ro_t[mi] = (int64_t)rt[mi];
+      if (r >= m_rows) ro_t[mi] = INT64_MIN;
+    }
+  };
+  load_out_rows();
 
   f32x16_t acc[MI][2];
+  auto zero_acc = [&]() {
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+  };
+  zero_acc();
+
+  // s_free: a stage nobody reads or fills any more; synced: a workgroup barrier has been passed since its last read
+  auto epilogue = [&](int s_free, bool synced) __attribute__((always_inline)) {
+  // ---- epilogue, in registers.  acc[mi][ni][i] is the output of row m0 + (wm MI + mi) 32 + l32 and logical
+  // column span0 + 32 ni + cl(i), cl(i) = 8 (i / 4) + 4 hf + i % 4.  A block of 32 logical columns is a run of 32
+  // physical columns in every column order (identity, gated halves, RoPE halves).
+  T* C = (T*)c_p;
+  const T* R = (const T*)res_p;
+  const int n_out = EPI == EPI_GLU ? cm.half : n_cols;
+  float bv[2][16];
+  if constexpr (!GEN) {              // whole runs of four inside the columns, or columns that are never stored
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const unsigned b0 = bias_p ? braw[ni][g4][0] : 0u, b1 = bias_p ? braw[ni][g4][1] : 0u;
+        bv[ni][4 * g4] = __uint_as_float(b0 << 16); bv[ni][4 * g4 + 1] = __uint_as_float(b0 & 0xffff0000u);
+        bv[ni][4 * g4 + 2] = __uint_as_float(b1 << 16); bv[ni][4 * g4 + 3] = __uint_as_float(b1 & 0xffff0000u);
+      }
+  } else {
+    const T* bias = (const T*)bias_p;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int pc = pcb[ni] + g4 * 8 + hf * 4;
+        if (bias && pc + 4 <= n_cols) {
+          if constexpr (VEC == 8) {
+            const unsigned b0 = braw[ni][g4][0], b1 = braw[ni][g4][1];
+            bv[ni][4 * g4] = __uint_as_float(b0 << 16); bv[ni][4 * g4 + 1] = __uint_as_float(b0 & 0xffff0000u);
+            bv[ni][4 * g4 + 2] = __uint_as_float(b1 << 16); bv[ni][4 * g4 + 3] = __uint_as_float(b1 & 0xffff0000u);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[ni][4 * g4 + j] = __uint_as_float(braw[ni][g4][j]);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) bv[ni][4 * g4 + j] = (bias && pc + j < n_cols) ? Elem<T>::ld(bias + pc + j) : 0.f;
+        }
+      }
+  }
+  float theta[16];
+  const bool rope = EPI == EPI_ROPE && span0 < cm.rope_cols;
+  if (rope) {
+    const float l2b = log2f(g.rope_base);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int e = (pcb[0] + (i >> 2) * 8 + hf * 4 + (i & 3)) % cm.rope_dim;      // index of the pair, < rope_dim / 2
+      theta[i] = exp2f(-2.f * (float)e / (float)cm.rope_dim * l2b);
+    }
+  }
+  if constexpr (!GEN) {
+    // The fast store (the launcher has checked: bf16, row-major, no second copy, the column count and every row /
+    // column offset a multiple of 8 elements).  The wave's 32 rows x (one or two blocks of 32 columns) go through LDS
+    // (free of K-tiles by now, a private region per wave) and leave as 16-byte pieces with the pieces of a row in
+    // adjacent lanes: a store instruction then writes whole 64- or 128-byte runs of a few rows instead of 32 bytes of
+    // each of 32 rows, which costs the texture path four cache lines per lane quad and the L2 four times the write
+    // requests.  The residual is read in the same pattern and added, in fp32, to the bf16-rounded value.  The code
+    // is kept short on purpose: a workgroup runs it once per tile, out of a cold instruction cache.
+    constexpr int NBLK = EPI == EPI_GLU ? 1 : 2, ROWB = NBLK * 64, RPITCH = ROWB + 16;      // the pad holds the row's output offset
+    constexpr int CPR = NBLK * 4, RPI = 64 / CPR;    // 16-byte pieces per row, rows per 64-lane round
+    unsigned char* wreg = (unsigned char*)(lds + s_free * (A_SLOTS + B_SLOTS)) + wave * (32 * RPITCH);
+    if (!synced) __syncthreads();                    // every wave has read its last K-tile fragments
+    auto rows_fast = [&](auto MI_) __attribute__((always_inline)) {
+      constexpr int mi = decltype(MI_)::value;
+      const int64_t r = m0 + (wm * MI + mi) * 32 + l32;
+      const int64_t ro = ro_t[mi];
+      float v0[16], v1[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { v0[i] = acc[mi][0][i] + bv[0][i]; v1[i] = acc[mi][1][i] + bv[1][i]; }
+      if constexpr (EPI == EPI_GLU) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v0[i] = g.act == SM_ACT_SWIGLU ? silu_f(v0[i]) * v1[i] : v0[i] * gelu_t<T>(v1[i]);
+      } else if constexpr (EPI == EPI_GELU) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { v0[i] = gelu_t<T>(v0[i]); v1[i] = gelu_t<T>(v1[i]); }
+      } else if constexpr (EPI == EPI_ROPE) {
+        if (rope) {
+          const float pos = (float)(r % g.rope_seq);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            float sn, cs;
+            sincosf(pos * theta[i], &sn, &cs);
+            const float a = v0[i], b = v1[i];
+            v0[i] = a * cs - b * sn;
+            v1[i] = b * cs + a * sn;
+          }
+        }
+      }
+#pragma unroll
+      for (int nb = 0; nb < NBLK; ++nb) {
+        const float* v = nb ? v1 : v0;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {           // columns 8 g4 + 4 hf .. + 3 of the block
+          const f32x2 p0 = {v[4 * g4], v[4 * g4 + 1]}, p1 = {v[4 * g4 + 2], v[4 * g4 + 3]};
+          *(u32x2*)(wreg + l32 * RPITCH + nb * 64 + g4 * 16 + hf * 8) =
+              u32x2{__builtin_bit_cast(unsigned, __builtin_convertvector(p0, bf16x2)), __builtin_bit_cast(unsigned, __builtin_convertvector(p1, bf16x2))};
+        }
+      }
+      if (hf == 0) *(int64_t*)(wreg + l32 * RPITCH + ROWB) = ro;
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // wave-private data: the LDS queue keeps a wave's accesses in order
+      __builtin_amdgcn_wave_barrier();
+      // all LDS reads, then all residual loads, then the stores: one latency each, not one per round
+      constexpr int NIT = 32 / RPI;
+      const int c = lane % CPR, col = pcb[c >> 2] + (c & 3) * 8;
+      const int64_t coff = c_cols_on ? eval_rows_k(&gk->c_cols, col >> 3) : (int64_t)col;
+      u32x4 d[NIT], rr[NIT];
+      int64_t off[NIT];
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int rl = it * RPI + lane / CPR;
+        d[it] = *(const u32x4*)(wreg + rl * RPITCH + c * 16);
+        const int64_t ro2 = *(const int64_t*)(wreg + rl * RPITCH + ROWB);
+        off[it] = (ro2 == INT64_MIN || col >= n_out) ? INT64_MIN : ro2 + coff;
+      }
+      if (R) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) rr[it] = *(const u32x4*)(R + (off[it] == INT64_MIN ? 0 : off[it]));      // element 0: a valid address, not used
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const f32x2 pr = {__uint_as_float(d[it][e] << 16) + __uint_as_float(rr[it][e] << 16), __uint_as_float(d[it][e] & 0xffff0000u) + __uint_as_float(rr[it][e] & 0xffff0000u)};
+            d[it][e] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2));
+          }
+      }
+#pragma unroll
+      for (int it = 0; it < NIT; ++it)
+        if (off[it] != INT64_MIN) *(u32x4*)(C + off[it]) = d[it];
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    };
+    rows_fast(std::integral_constant<int, 0>{});
+    if constexpr (MI == 2) rows_fast(std::integral_constant<int, 1>{});
+  } else {
+  // VEC values w[] for columns col .. col + VEC - 1 of row r (output offset of the row: ro)
+  int64_t cur_row = 0;               // the row the chunk belongs to (set by epilogue_rows), for the second copy
+  auto store_chunk = [&](bool row_ok, int64_t ro, int col, const float* w) __attribute__((always_inline)) {
+    if (!row_ok || col >= n_out) return;
+    if (g.C2) {                      // the other layout: column-major, consecutive lanes (rows) write consecutive elements
+      T* C2 = (T*)g.C2;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (col + e < n_out) Elem<T>::st(C2 + (int64_t)(col + e) * g.M + cur_row, w[e]);
+    }
+    if (g.c_transposed) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (col + e < n_out) {
+          const int64_t off = ro + (int64_t)(col + e) * g.c_batch_rows;
+          Elem<T>::st(C + off, R ? w[e] + Elem<T>::ld(R + off) : w[e]);
+        }
+      return;
+    }
+    const bool whole = col + VEC <= n_out && (!g.c_cols_on || g.c_gran == VEC);
+    const int64_t off = ro + (g.c_cols_on ? (g.c_gran == VEC ? eval_rows_k(&gk->c_cols, col / VEC) : 0) : col);
+    if (whole && (off & (VEC - 1)) == 0) {
+      float v[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[e] = w[e];
+      if (R) {
+        const u32x4 rr = *(const u32x4*)(R + off);
+        if constexpr (VEC == 8) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(rr[e] << 16); v[2 * e + 1] += __uint_as_float(rr[e] & 0xffff0000u); }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(rr[e]);
+        }
+      }
+      u32x4 out;
+      if constexpr (VEC == 8) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { const f32x2 pr = {v[2 * e], v[2 * e + 1]}; out[e] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2)); }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(v[e]);
+      }
+      *(u32x4*)(C + off) = out;
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (col + e < n_out) {
+          int64_t oe = off + e;
+          if (g.c_cols_on && g.c_gran != VEC) oe = ro + eval_rows_k(&gk->c_cols, col + e);
+          Elem<T>::st(C + oe, R ? w[e] + Elem<T>::ld(R + oe) : w[e]);
+        }
+    }
+  };
+  // one block of 32 output columns starting at ocb: a lane's sixteen values -> chunks of VEC consecutive columns
+  auto store_block = [&](bool row_ok, int64_t ro, int ocb, const float* v) __attribute__((always_inline)) {
+    if constexpr (VEC == 8) {
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) {
+        // lanes l and l + 32 own the same row: the lower one gives its second run of four and takes the partner's
+        // first, so that it holds columns 16 gp .. 16 gp + 7 and the partner 16 gp + 8 .. 16 gp + 15
+        float w[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * gp + j]), __float_as_uint(v[8 * gp + 4 + j]), false, false);
+          w[j] = __uint_as_float(sw.x);
+          w[4 + j] = __uint_as_float(sw.y);
+        }
+        store_chunk(row_ok, ro, ocb + (2 * gp + hf) * 8, w);
+      }
+    } else {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) store_chunk(row_ok, ro, ocb + g4 * 8 + hf * 4, v + 4 * g4);
+    }
+  };
+  auto epilogue_rows = [&](auto MI_) __attribute__((always_inline)) {
+    constexpr int mi = decltype(MI_)::value;
+    const int64_t r = m0 + (wm * MI + mi) * 32 + l32;
+    const bool row_ok = r < g.M;
+    cur_row = r;
+    int64_t ro = 0;
+    if (row_ok) {
+      if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; ro = bi * g.c_batch_rows * n_out + (r - bi * g.c_batch_rows); }
+      else ro = g.c_rows.identity ? r * g.c_rows.ld : eval_rows_k(&gk->c_rows, r);
+    }
+    float v0[16], v1[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { v0[i] = acc[mi][0][i] + bv[0][i]; v1[i] = acc[mi][1][i] + bv[1][i]; }
+    if constexpr (EPI == EPI_GLU) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v0[i] = g.act == SM_ACT_SWIGLU ? silu_f(v0[i]) * v1[i] : v0[i] * gelu_t<T>(v1[i]);
+      store_block(row_ok, ro, pcb[0], v0);
+    } else {
+      if constexpr (EPI == EPI_GELU) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { v0[i] = gelu_t<T>(v0[i]); v1[i] = gelu_t<T>(v1[i]); }
+      }
+      if (EPI == EPI_ROPE && rope) {
+        const float pos = (float)(r % g.rope_seq);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float sn, cs;
+          sincosf(pos * theta[i], &sn, &cs);
+          const float a = v0[i], b = v1[i];
+          v0[i] = a * cs - b * sn;
+          v1[i] = b * cs + a * sn;
+        }
+      }
+      store_block(row_ok, ro, pcb[0], v0);
+      store_block(row_ok, ro, pcb[1], v1);
+    }
+  };
+  epilogue_rows(std::integral_constant<int, 0>{});
+  if constexpr (MI == 2) epilogue_rows(std::integral_constant<int, 1>{});
+  }
+  };
 
   if constexpr (DMA) {
     // wave-load i of this wave fills rows g8*8 .. g8*8+7 of a tile (1 KiB, 64 consecutive 16-byte slots):
@@ -162,18 +464,32 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     const int lrow = lane >> 3, lpos = lane & 7;
     const T* a_src[LA];
     const T* b_src[LB];
+    // the A rows of a tile: their offsets are requested early (pre: with a row table they are loads) and turned into
+    // this lane's source pointers when the tile's first K-tiles are issued (fin)
+    int a_off32[LA];
+    auto src_pre = [&](int64_t m0_) {
+      if (!a_ident && a_tab) {
 #pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int rr = (wave * LA + i) * 8 + lrow;
-      const int64_t r = min(m0 + rr, g.M - 1);       // rows past M repeat the last row: their outputs are never stored
-      a_src[i] = A + (g.a_rows.identity ? r * g.a_rows.ld : eval_rows_k(&gk->a_rows, r)) + (lpos ^ ((rr >> 1) & 7)) * VEC;
-    }
+        for (int i = 0; i < LA; ++i) a_off32[i] = a_tab[min(m0_ + (wave * LA + i) * 8 + lrow, m_rows - 1)];
+      }
+    };
+    auto src_fin = [&](int64_t m0_, int n0_) {
 #pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int rr = (wave * LB + i) * 8 + lrow;
-      const int n = min(n0 + rr, g.N - 1);
-      b_src[i] = W + (int64_t)phys_col(cm, n) * g.ldw + (lpos ^ ((rr >> 1) & 7)) * VEC;
-    }
+      for (int i = 0; i < LA; ++i) {
+        const int rr = (wave * LA + i) * 8 + lrow;
+        const int64_t r = min(m0_ + rr, m_rows - 1);   // rows past M repeat the last row: their outputs are never stored
+        const int64_t ao = a_ident ? r * a_ld : (a_tab ? (int64_t)a_off32[i] : eval_rows_k(&gk->a_rows, r));
+        a_src[i] = A + ao + (lpos ^ ((rr >> 1) & 7)) * VEC;
+      }
+#pragma unroll
+      for (int i = 0; i < LB; ++i) {
+        const int rr = (wave * LB + i) * 8 + lrow;
+        const int n = min(n0_ + rr, n_cols - 1);
+        b_src[i] = W + (int64_t)phys_col(cm, n) * ldw + (lpos ^ ((rr >> 1) & 7)) * VEC;
+      }
+    };
+    src_pre(m0);
+    src_fin(m0, n0);
     auto issue = [&](int kt, int stage) {
       u32x4* st = lds + stage * STAGE;
       const int k0 = kt * BK;
@@ -233,25 +549,53 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t)
       if (t < nk) issue(t, t);
-    int kt = 0, sc = 0;                            // sc = stage of tile kt
-    for (; kt + (NS - 1) < nk; ++kt) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPT) : "memory");
-      __builtin_amdgcn_s_barrier();
-      issue(kt + NS - 1, sc == 0 ? NS - 1 : sc - 1);
-      compute(sc);
-      sc = sc == NS - 1 ? 0 : sc + 1;
-    }
-    // the last NS - 1 tiles (fewer if K is short): nothing left to issue, the wait count shrinks with the tiles in flight
-#pragma unroll
-    for (int left = NS - 2; left >= 0; --left) {
-      if (nk > left) {
-        if (left == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
-        else if (left == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int sc = 0;                                    // stage of the K-tile about to be multiplied
+    for (;;) {
+      // this workgroup's next tile: its A-row offsets are requested now and arrive behind the K loop
+      const int vb_n = vb + (int)gridDim.x;
+      const bool more = vb_n < n_tiles;
+      int64_t m0_n = 0;
+      int n0_n = 0;
+      if (more) { decode(vb_n, m0_n, n0_n); src_pre(m0_n); }
+      int kt = 0;
+      for (; kt + (NS - 1) < nk; ++kt) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPT) : "memory");
         __builtin_amdgcn_s_barrier();
+        issue(kt + NS - 1, sc == 0 ? NS - 1 : sc - 1);
         compute(sc);
         sc = sc == NS - 1 ? 0 : sc + 1;
       }
+      // the last NS - 1 tiles (fewer if K is short): nothing left to issue, the wait count shrinks with the tiles in flight
+#pragma unroll
+      for (int left = NS - 2; left >= 0; --left) {
+        if (nk > left) {
+          if (left == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+          else if (left == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
+          else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          compute(sc);
+          sc = sc == NS - 1 ? 0 : sc + 1;
+        }
+      }
+      // The next output tile of this workgroup: its first K-tiles are requested before the epilogue of this one, into
+      // the stages sc .. sc + NS - 2 (all read for the last time before the barrier below); the epilogue shuffles
+      // through the remaining stage, the last one multiplied, and its stores drain while the next tile's loads
+      // arrive.  (The waits above count those stores as well: they are older than every load they wait for, so the
+      // counts stay on the safe side.)
+      __syncthreads();
+      if (more) {
+        src_fin(m0_n, n0_n);
+#pragma unroll
+        for (int t = 0; t < NS - 1; ++t)
+          if (t < nk) issue(t, sc + t >= NS ? sc + t - NS : sc + t);
+      }
+      epilogue(sc == 0 ? NS - 1 : sc - 1, true);
+      if (!more) break;
+      vb = vb_n; m0 = m0_n; n0 = n0_n;
+      set_cols();
+      load_bias();
+      load_out_rows();
+      zero_acc();
     }
   } else {
     // global -> register staging, two K-tiles in flight (register sets 0 and 1)
@@ -477,163 +821,11 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     }
   }
 
-  // ---- epilogue, in registers.  acc[mi][ni][i] is the output of row m0 + (wm MI + mi) 32 + l32 and logical
-  // column span0 + 32 ni + cl(i), cl(i) = 8 (i / 4) + 4 hf + i % 4.  A block of 32 logical columns is a run of 32
-  // physical columns in every column order (identity, gated halves, RoPE halves).
-  T* C = (T*)g.C;
-  const T* R = (const T*)g.residual;
-  const int n_out = EPI == EPI_GLU ? cm.half : g.N;
-  float bv[2][16];
-  {
-    const T* bias = (const T*)g.bias;
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int pc = pcb[ni] + g4 * 8 + hf * 4;
-        if (bias && pc + 4 <= g.N) {
-          if constexpr (VEC == 8) {
-            const unsigned b0 = braw[ni][g4][0], b1 = braw[ni][g4][1];
-            bv[ni][4 * g4] = __uint_as_float(b0 << 16); bv[ni][4 * g4 + 1] = __uint_as_float(b0 & 0xffff0000u);
-            bv[ni][4 * g4 + 2] = __uint_as_float(b1 << 16); bv[ni][4 * g4 + 3] = __uint_as_float(b1 & 0xffff0000u);
-          } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[ni][4 * g4 + j] = __uint_as_float(braw[ni][g4][j]);
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) bv[ni][4 * g4 + j] = (bias && pc + j < g.N) ? Elem<T>::ld(bias + pc + j) : 0.f;
-        }
-      }
-  }
-  float theta[16];
-  const bool rope = EPI == EPI_ROPE && span0 < cm.rope_cols;
-  if (rope) {
-    const float l2b = log2f(g.rope_base);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int e = (pcb[0] + (i >> 2) * 8 + hf * 4 + (i & 3)) % cm.rope_dim;      // index of the pair, < rope_dim / 2
-      theta[i] = exp2f(-2.f * (float)e / (float)cm.rope_dim * l2b);
-    }
-  }
-  // VEC values w[] for columns col .. col + VEC - 1 of row r (output offset of the row: ro)
-  int64_t cur_row = 0;               // the row the chunk belongs to (set by epilogue_rows), for the second copy
-  auto store_chunk = [&](bool row_ok, int64_t ro, int col, const float* w) __attribute__((always_inline)) {
-    if (!row_ok || col >= n_out) return;
-    if (g.C2) {                      // the other layout: column-major, consecutive lanes (rows) write consecutive elements
-      T* C2 = (T*)g.C2;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        if (col + e < n_out) Elem<T>::st(C2 + (int64_t)(col + e) * g.M + cur_row, w[e]);
-    }
-    if (g.c_transposed) {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        if (col + e < n_out) {
-          const int64_t off = ro + (int64_t)(col + e) * g.c_batch_rows;
-          Elem<T>::st(C + off, R ? w[e] + Elem<T>::ld(R + off) : w[e]);
-        }
-      return;
-    }
-    const bool whole = col + VEC <= n_out && (!g.c_cols_on || g.c_gran == VEC);
-    const int64_t off = ro + (g.c_cols_on ? (g.c_gran == VEC ? eval_rows_k(&gk->c_cols, col / VEC) : 0) : col);
-    if (whole && (off & (VEC - 1)) == 0) {
-      float v[VEC];
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) v[e] = w[e];
-      if (R) {
-        const u32x4 rr = *(const u32x4*)(R + off);
-        if constexpr (VEC == 8) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(rr[e] << 16); v[2 * e + 1] += __uint_as_float(rr[e] & 0xffff0000u); }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(rr[e]);
-        }
-      }
-      u32x4 out;
-      if constexpr (VEC == 8) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { const f32x2 pr = {v[2 * e], v[2 * e + 1]}; out[e] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2)); }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(v[e]);
-      }
-      *(u32x4*)(C + off) = out;
-    } else {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        if (col + e < n_out) {
-          int64_t oe = off + e;
-          if (g.c_cols_on && g.c_gran != VEC) oe = ro + eval_rows_k(&gk->c_cols, col + e);
-          Elem<T>::st(C + oe, R ? w[e] + Elem<T>::ld(R + oe) : w[e]);
-        }
-    }
-  };
-  // one block of 32 output columns starting at ocb: a lane's sixteen values -> chunks of VEC consecutive columns
-  auto store_block = [&](bool row_ok, int64_t ro, int ocb, const float* v) __attribute__((always_inline)) {
-    if constexpr (VEC == 8) {
-#pragma unroll
-      for (int gp = 0; gp < 2; ++gp) {
-        // lanes l and l + 32 own the same row: the lower one gives its second run of four and takes the partner's
-        // first, so that it holds columns 16 gp .. 16 gp + 7 and the partner 16 gp + 8 .. 16 gp + 15
-        float w[8];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[8 * gp + j]), __float_as_uint(v[8 * gp + 4 + j]), false, false);
-          w[j] = __uint_as_float(sw.x);
-          w[4 + j] = __uint_as_float(sw.y);
-        }
-        store_chunk(row_ok, ro, ocb + (2 * gp + hf) * 8, w);
-      }
-    } else {
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) store_chunk(row_ok, ro, ocb + g4 * 8 + hf * 4, v + 4 * g4);
-    }
-  };
-  auto epilogue_rows = [&](auto MI_) __attribute__((always_inline)) {
-    constexpr int mi = decltype(MI_)::value;
-    const int64_t r = m0 + (wm * MI + mi) * 32 + l32;
-    const bool row_ok = r < g.M;
-    cur_row = r;
-    int64_t ro = 0;
-    if (row_ok) {
-      if (g.c_transposed) { const int64_t bi = r / g.c_batch_rows; ro = bi * g.c_batch_rows * n_out + (r - bi * g.c_batch_rows); }
-      else ro = g.c_rows.identity ? r * g.c_rows.ld : eval_rows_k(&gk->c_rows, r);
-    }
-    float v0[16], v1[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { v0[i] = acc[mi][0][i] + bv[0][i]; v1[i] = acc[mi][1][i] + bv[1][i]; }
-    if constexpr (EPI == EPI_GLU) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) v0[i] = g.act == SM_ACT_SWIGLU ? silu_f(v0[i]) * v1[i] : v0[i] * gelu_t<T>(v1[i]);
-      store_block(row_ok, ro, pcb[0], v0);
-    } else {
-      if constexpr (EPI == EPI_GELU) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { v0[i] = gelu_t<T>(v0[i]); v1[i] = gelu_t<T>(v1[i]); }
-      }
-      if (EPI == EPI_ROPE && rope) {
-        const float pos = (float)(r % g.rope_seq);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          float sn, cs;
-          sincosf(pos * theta[i], &sn, &cs);
-          const float a = v0[i], b = v1[i];
-          v0[i] = a * cs - b * sn;
-          v1[i] = b * cs + a * sn;
-        }
-      }
-      store_block(row_ok, ro, pcb[0], v0);
-      store_block(row_ok, ro, pcb[1], v1);
-    }
-  };
-  epilogue_rows(std::integral_constant<int, 0>{});
-  if constexpr (MI == 2) epilogue_rows(std::integral_constant<int, 1>{});
+  if constexpr (!DMA) epilogue(0, false);
 }
 
-template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM = 2, int NS = 2, bool LNF = false>
-static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM, int NS, bool LNF, bool GEN>
+static int gemm_launch3(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   constexpr int BM = 32 * MI * WM;
   const int tiles_n = (g.N + 127) / 128;
   const int64_t tiles_m = (g.M + BM - 1) / BM;
@@ -653,10 +845,44 @@ static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
   // row groups pay where the operand panels are long (they then exceed what the L2 keeps between tiles); with short
   // panels the plain row-major order inside a strip fetched less (measured on the K = 384 shapes)
   ts.group = g.K >= 1024 ? (int)std::min<int64_t>(4, tiles_m) : 1;
-  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS, LNF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS, LNF, GEN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return (int)attr;
-  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS, LNF><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(128 * WM), smem, s>>>(g, cm, ts);
+  int64_t grid = tiles_m * tiles_n;
+  if constexpr (DMA) {
+    // as many workgroups as are resident at once (a multiple of 8, so that a workgroup's tiles stay on its XCD): each
+    // walks through its share of the tiles, prefetching across the tile boundary
+    static const int resident = [&]() {
+      int per_cu = 0, cus = 0, dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+          hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS, LNF, GEN>, 128 * WM, smem) != hipSuccess)
+        return 0;
+      return (per_cu * cus) & ~7;
+    }();
+    if (resident >= 8 && grid > resident) grid = resident;
+  }
+  gemm_kernel<T, MI, EPI, AGRAN, DMA, WM, NS, LNF, GEN><<<dim3((unsigned)grid), dim3(128 * WM), smem, s>>>(g, cm, ts);
   return (int)hipGetLastError();
+}
+
+// every offset the program yields is a multiple of `vec` elements (sufficient: its constant and coefficients are)
+static bool rows_vec_aligned(const RowProg& p, int vec) {
+  if (p.identity) return p.ld % vec == 0;
+  if (p.c0 % vec) return false;
+  for (int t = 0; t < p.nterm; ++t)
+    if (p.t_coef[t] % vec) return false;
+  return true;
+}
+
+// The short epilogue (whole 16-byte pieces, shuffled through LDS) where the store allows it; the general one otherwise.
+template <typename T, int MI, int EPI, bool AGRAN, bool DMA, int WM = 2, int NS = 2, bool LNF = false>
+static int gemm_launch2(const GemmArgs& g, const ColMap& cm, hipStream_t s) {
+  if constexpr (sizeof(T) == 2) {
+    const int n_out = EPI == EPI_GLU ? cm.half : g.N;
+    const bool fast = !g.C2 && !g.c_transposed && n_out % 8 == 0 && g.N % 8 == 0 && rows_vec_aligned(g.c_rows, 8) &&
+                      (!g.c_cols_on || (g.c_gran == 8 && rows_vec_aligned(g.c_cols, 8)));
+    if (fast) return gemm_launch3<T, MI, EPI, AGRAN, DMA, WM, NS, LNF, false>(g, cm, s);
+  }
+  return gemm_launch3<T, MI, EPI, AGRAN, DMA, WM, NS, LNF, true>(g, cm, s);
 }
 
 static std::atomic<int> g_force_rows{0}, g_force_stages{0};       // sm_gemm_tuning (a process-wide sweep hook)
