@@ -276,6 +276,8 @@ def measure(run, steps, warmup, sm, torch, traffic, tune):
     sm.timing_enable(True)
     for _ in range(ev_steps):
         run()
+    seq = sm.timing_sequence()
+    seq = seq[:len(seq) // ev_steps]      # one pass: the launch order a profiler's dispatch list is matched against
     sm.timing_calibrate(64)        # what an event pair adds to a kernel's own run time
     torch.cuda.synchronize()
     rep = sm.timing_report()
@@ -298,7 +300,7 @@ def measure(run, steps, warmup, sm, torch, traffic, tune):
             "flops_per_step": sum(r["flops"] * r["launches_per_step"] for r in rows),
             "launches_per_step": round(sum(r["launches_per_step"] for r in rows), 1),
             "kernel_us_per_step": round(sum(r["avg_us"] * r["launches_per_step"] for r in rows), 2),
-            "roofline": roofline_of(dom, traffic), "event_calibration": calib, "kernels": rows,
+            "roofline": roofline_of(dom, traffic), "event_calibration": calib, "kernels": rows, "launch_sequence": seq,
             "tuned_linears": None if tuned is None else [{"shape": list(t["shape"]), "tile_rows": t["tile_rows"], "stages": t["stages"],
                                                           "us": t["best_us"], "default_us": t["default_us"]} for t in tuned]}
 
@@ -357,6 +359,7 @@ def main():
             calib = r.pop("event_calibration")
             if not a.kernels:
                 del r["kernels"]
+                del r["launch_sequence"]
             entry["variants"][name] = r
         v = entry["variants"]
         if "elided" in v and "explicit" in v:

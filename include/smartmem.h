@@ -437,6 +437,9 @@ int sm_last_launch_counts(int* n_compute, int* n_copy);
  * "label<TAB>launches<TAB>total_ms", into buf (host pointer, n bytes). */
 int sm_timing_enable(int on);
 int sm_timing_report(char* buf, int n);
+/* the labels of the launches recorded since sm_timing_enable(1), in launch order, one per line (host buffer; a label
+ * stands for one kernel, sm_groupnorm's two-kernel form for two): lets a profiler's dispatch list be matched to them */
+int sm_timing_sequence(char* buf, int n);
 /* Launches n (1..1024) empty kernels on `stream`, each recorded like any other launch under the label
  * "empty_kernel" (only while timing is enabled): their average is what an event pair measures on top of a
  * kernel's own execution time (dispatch and completion), to be subtracted when comparing with a profiler. */

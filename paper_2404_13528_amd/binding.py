@@ -549,6 +549,13 @@ def timing_calibrate(n=64, stream=None):
     check(lib().sm_timing_calibrate(int(n), _stream(stream)), "sm_timing_calibrate")
 
 
+def timing_sequence():
+    """Labels of the recorded launches in launch order."""
+    buf = C.create_string_buffer(1 << 22)
+    check(lib().sm_timing_sequence(buf, len(buf)), "sm_timing_sequence")
+    return [l for l in buf.value.decode().split("\n") if l]
+
+
 def timing_report():
     """{label: (launches, total_ms)} of the launches since timing_enable(True), in first-launch order."""
     buf = C.create_string_buffer(1 << 16)

@@ -70,10 +70,19 @@ int timing_report(char* buf, int n) {
   std::memcpy(buf, out.c_str(), out.size() + 1);
   return SM_OK;
 }
+int timing_sequence(char* buf, int n) {
+  std::lock_guard<std::mutex> lock(t_mu);
+  std::string out;
+  for (auto& r : t_recs) { out += r.label; out += '\n'; }
+  if ((int)out.size() + 1 > n) return fail(SM_ERR_INVALID_ARG, "sm_timing_sequence: buffer of %d bytes, %zu needed", n, out.size() + 1);
+  std::memcpy(buf, out.c_str(), out.size() + 1);
+  return SM_OK;
+}
 }  // namespace sm
 
 extern "C" const char* sm_last_error(void) { return sm::last_error(); }
 extern "C" int sm_abi_version(void) { return 1; }
 extern "C" int sm_last_launch_counts(int* n_compute, int* n_copy) { return sm::counts(n_compute, n_copy); }
 extern "C" int sm_timing_enable(int on) { return sm::timing_enable(on); }
+extern "C" int sm_timing_sequence(char* buf, int n) { if (!buf || n < 1) return sm::fail(SM_ERR_INVALID_ARG, "sm_timing_sequence: bad buffer"); return sm::timing_sequence(buf, n); }
 extern "C" int sm_timing_report(char* buf, int n) { if (!buf || n < 1) return sm::fail(SM_ERR_INVALID_ARG, "sm_timing_report: bad buffer"); return sm::timing_report(buf, n); }

@@ -21,6 +21,7 @@ int counts(int* a, int* b);
 // events on its stream; sm_timing_report sums them per label.
 int timing_enable(int on);
 int timing_report(char* buf, int n);
+int timing_sequence(char* buf, int n);      // the labels of the recorded launches in launch order, one per line
 struct Timed {
   Timed(const char* label, void* stream);
   ~Timed();

@@ -490,13 +490,17 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
     };
     src_pre(m0);
     src_fin(m0, n0);
-    auto issue = [&](int kt, int stage) {
+    // quarter `part` (0 .. 3) of the wave-loads of K-tile kt into `stage`; part < 0: all of them
+    auto issue = [&](int kt, int stage, int part = -1) __attribute__((always_inline)) {
       u32x4* st = lds + stage * STAGE;
       const int k0 = kt * BK;
+      constexpr int LPT_ = LA + LB;
 #pragma unroll
-      for (int i = 0; i < LA; ++i) __builtin_amdgcn_global_load_lds(SM_GPTR(a_src[i] + k0), SM_LPTR(st + (wave * LA + i) * 64), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < LB; ++i) __builtin_amdgcn_global_load_lds(SM_GPTR(b_src[i] + k0), SM_LPTR(st + A_SLOTS + (wave * LB + i) * 64), 16, 0, 0);
+      for (int i = 0; i < LPT_; ++i) {
+        if (part >= 0 && i * 4 / LPT_ != part) continue;
+        if (i < LA) __builtin_amdgcn_global_load_lds(SM_GPTR(a_src[i] + k0), SM_LPTR(st + (wave * LA + i) * 64), 16, 0, 0);
+        else __builtin_amdgcn_global_load_lds(SM_GPTR(b_src[i - LA] + k0), SM_LPTR(st + A_SLOTS + (wave * LB + (i - LA)) * 64), 16, 0, 0);
+      }
     };
     unsigned fa_addr[MI], fb_addr[2];
     int fa_x[MI], fb_x[2];
@@ -517,7 +521,10 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
         asm volatile("ds_read_b128 %0, %1" : "=v"(fb[ni]) : "v"(ad));
       }
     };
-    auto compute = [&](int stage) {
+    // The wave-loads of the K-tile that refills `fill_stage` go out a quarter at a time between the MFMA groups: the
+    // L1 -> LDS path takes about as long for a tile's bytes as the matrix cores for its flops (64 bytes a clock against
+    // 64 flops a byte at 128 x 128), and a wave that issues its loads in one go sits in the full queue, MFMA-less.
+    auto compute = [&](int stage, int fill_kt = -1, int fill_stage = 0) __attribute__((always_inline)) {
       const unsigned sbase = (unsigned)(stage * STAGE * 16);
       u32x4 fa[2][MI], fb[2][2];
       read_frags(sbase, 0, fa[0], fb[0]);
@@ -539,6 +546,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
           for (int ni = 0; ni < 2; ++ni)
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb[cur][ni]),
                                                                   __builtin_bit_cast(bf16x8_t, fa[cur][mi]), acc[mi][ni], 0, 0, 0);
+        if (fill_kt >= 0) issue(fill_kt, fill_stage, j);
       }
     };
     // NS stages, tiles kt+1 .. kt+NS-2 in flight while tile kt is multiplied.  Per tile: wait until this wave's part
@@ -561,8 +569,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
       for (; kt + (NS - 1) < nk; ++kt) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPT) : "memory");
         __builtin_amdgcn_s_barrier();
-        issue(kt + NS - 1, sc == 0 ? NS - 1 : sc - 1);
-        compute(sc);
+        compute(sc, kt + NS - 1, sc == 0 ? NS - 1 : sc - 1);
         sc = sc == NS - 1 ? 0 : sc + 1;
       }
       // the last NS - 1 tiles (fewer if K is short): nothing left to issue, the wait count shrinks with the tiles in flight
