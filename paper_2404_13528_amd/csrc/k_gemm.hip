@@ -126,7 +126,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
   constexpr int BM = 32 * MI * WM, BN = 128, BK = 8 * VEC;
   constexpr int A_SLOTS = BM * 8, B_SLOTS = BN * 8;
   extern __shared__ u32x4 lds[];                     // [stages][A_SLOTS + B_SLOTS]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave: a scalar
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, hf = lane >> 5;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The tiles are put in an order in which
@@ -258,13 +258,15 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
   float theta[16];
   const bool rope = EPI == EPI_ROPE && span0 < cm.rope_cols;
   if (rope) {
-    const float l2b = log2f(g.rope_base);
+    // index of the pair, < rope_dim / 2: the block's 32 columns lie inside one half of a head (rope_dim is a multiple
+    // of 64), so one scalar remainder serves the wave
+    const int e0 = __builtin_amdgcn_readfirstlane(pcb[0]) % cm.rope_dim;
+    const float k2 = -2.f / (float)cm.rope_dim * log2f(g.rope_base);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int e = (pcb[0] + (i >> 2) * 8 + hf * 4 + (i & 3)) % cm.rope_dim;      // index of the pair, < rope_dim / 2
-      theta[i] = exp2f(-2.f * (float)e / (float)cm.rope_dim * l2b) * 0.15915494309189535f;      // revolutions per position
-    }
+    for (int i = 0; i < 16; ++i)
+      theta[i] = exp2f((float)(e0 + (i >> 2) * 8 + hf * 4 + (i & 3)) * k2) * 0.15915494309189535f;      // revolutions per position
   }
+  const unsigned rope_m0 = EPI == EPI_ROPE ? (unsigned)(m0 % g.rope_seq) : 0u;      // position of the tile's first row (scalar)
   if constexpr (!GEN) {
     // The fast store (the launcher has checked: bf16, row-major, no second copy, the column count and every row /
     // column offset a multiple of 8 elements).  The wave's 32 rows x (one or two blocks of 32 columns) go through LDS
@@ -292,7 +294,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
         for (int i = 0; i < 16; ++i) { v0[i] = gelu_t<T>(v0[i]); v1[i] = gelu_t<T>(v1[i]); }
       } else if constexpr (EPI == EPI_ROPE) {
         if (rope) {
-          const float pos = (float)(r % g.rope_seq);
+          const float pos = (float)((rope_m0 + (unsigned)((wm * MI + mi) * 32 + l32)) % (unsigned)g.rope_seq);
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             float sn, cs;
@@ -447,7 +449,7 @@ __global__ __launch_bounds__(128 * WM, 2) void gemm_kernel(GemmArgs g, ColMap cm
         for (int i = 0; i < 16; ++i) { v0[i] = gelu_t<T>(v0[i]); v1[i] = gelu_t<T>(v1[i]); }
       }
       if (EPI == EPI_ROPE && rope) {
-        const float pos = (float)(r % g.rope_seq);
+        const float pos = (float)((rope_m0 + (unsigned)((wm * MI + mi) * 32 + l32)) % (unsigned)g.rope_seq);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           float sn, cs;

@@ -72,13 +72,31 @@ __global__ void mlp_pack_kernel(const bf16_t* W1, const bf16_t* W2, mlp_u32x4* p
 template <int C, int NTHR = 256>
 __device__ __forceinline__ void mlp_load_x_tile(mlp_u32x4* x_l, const bf16_t* X, int64_t row0, int64_t M, int ident, int64_t ld,
                                                 const SM_KARG RowProg* rows) {
-  constexpr int XS = C / 8, XP = XS + 1;
-  for (int s = threadIdx.x; s < 32 * XS; s += NTHR) {
-    const int r = s / XS, c = s - r * XS;
-    const int64_t row = row0 + r;
-    mlp_u32x4 v = {0u, 0u, 0u, 0u};
-    if (row < M) v = *(const mlp_u32x4*)(X + (ident ? row * ld : eval_rows_k(rows, row)) + c * 8);
-    x_l[r * XP + c] = v;
+  constexpr int XS = C / 8, XP = XS + 1, NIT = (32 * XS + NTHR - 1) / NTHR;
+  // three passes, so that the offset lookups (a table load each, where the rows go through one) are in flight together,
+  // and then the data loads: one latency each instead of one per chunk
+  const int32_t* tab = ident ? nullptr : rows->table;
+  int64_t off[NIT];
+  int toff[NIT];
+#pragma unroll
+  for (int i = 0; i < NIT; ++i) {
+    const int s = threadIdx.x + i * NTHR, r = s / XS;
+    const int64_t row = min(row0 + min(r, 31), M - 1);
+    if (ident) off[i] = row * ld;
+    else if (tab) toff[i] = tab[row];
+    else off[i] = eval_rows_k(rows, row);
+  }
+  mlp_u32x4 v[NIT];
+#pragma unroll
+  for (int i = 0; i < NIT; ++i) {
+    const int s = threadIdx.x + i * NTHR, r = s / XS, c = s - r * XS;
+    if (!ident && tab) off[i] = (int64_t)toff[i];
+    v[i] = *(const mlp_u32x4*)(X + off[i] + (s < 32 * XS ? c : 0) * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < NIT; ++i) {
+    const int s = threadIdx.x + i * NTHR, r = s / XS, c = s - r * XS;
+    if (s < 32 * XS) x_l[r * XP + c] = row0 + r < M ? v[i] : mlp_u32x4{0u, 0u, 0u, 0u};
   }
 }
 
@@ -204,14 +222,18 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) wf[kk] = PROJ ? wload(rp, (w * KK + kk) * 1024) : wload(rw, (sc0 * KK + kk) * 1024);
 
+  // the lane's output-row offsets (table lookups, where the rows are mapped) are requested before the tile's loads,
+  // not where they are first used
+  const int64_t prow = row0 + l32 < g.M ? row0 + l32 : g.M - 1;          // lanes past M read the last row and store nothing
+  const bool row_ok = row0 + l32 < g.M;
+  const int64_t ro = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
+  int64_t ro2 = 0;
+  if constexpr (LNOUT != 0) ro2 = g.y2_rows.identity ? prow * g.y2_rows.ld : eval_rows_k(&gk->y2_rows, prow);
   mlp_load_x_tile<C, NTHR>(PROJ ? a_l : x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
   for (int s = tid; s < Hd / 8; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
   if constexpr (PROJ) for (int s = tid; s < XS; s += NTHR) bp_l[s] = ((const mlp_u32x4*)g.bproj)[s];
   __syncthreads();
 
-  const int64_t prow = row0 + l32 < g.M ? row0 + l32 : g.M - 1;          // lanes past M read the last row and store nothing
-  const bool row_ok = row0 + l32 < g.M;
-  const int64_t ro = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
   const int fo = w * 32 + hf * 8;                                         // first of the lane's features in the wave's block
 
   mlp_u32x4 resid[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};              // residual of the final sum (lane's two runs of eight)
@@ -335,7 +357,6 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   if constexpr (LNOUT != 0) {
     // two-pass fp32 statistics of the bf16 row, as the norm kernel would compute them from the stored Y: a lane holds
     // 16 of its token's features, its partner lane (other hf) 16 more, the other waves the rest
-    const int64_t ro2 = g.y2_rows.identity ? prow * g.y2_rows.ld : eval_rows_k(&gk->y2_rows, prow);
     const mlp_u32x4 gv[2] = {*(const mlp_u32x4*)((const bf16_t*)g.ln2_gamma + fo), *(const mlp_u32x4*)((const bf16_t*)g.ln2_gamma + fo + 16)};
     const mlp_u32x4 bv[2] = {*(const mlp_u32x4*)((const bf16_t*)g.ln2_beta + fo), *(const mlp_u32x4*)((const bf16_t*)g.ln2_beta + fo + 16)};
     float f[16];

@@ -45,18 +45,39 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t row0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
   if (row0 >= a.rows) return;
-  const int nchunk = a.C / VEC;
-  const int seg_chunks = nchunk / a.nseg;
+  // The kernel-argument fields used below, read together and pinned in scalar registers: fetched where they are used
+  // they cost one scalar load and one wait each, strung out by the branches between them, before the first data load.
+#define SM_PIN(x) asm volatile("" : "+s"(x))
+  int l_ident = a.load.identity, s_ident = a.store.identity, nseg = a.nseg, n_ch = a.C, rms = a.rms;
+  int64_t n_rows = a.rows, l_ld = a.load.ld, s_ld = a.store.ld;
+  const int32_t* l_tab = a.load.table;
+  const int32_t* s_tab = a.store.table;
+  float eps = a.eps;
+  SM_PIN(l_ident); SM_PIN(s_ident); SM_PIN(nseg); SM_PIN(n_ch); SM_PIN(rms); SM_PIN(n_rows); SM_PIN(l_ld); SM_PIN(s_ld);
+  SM_PIN(l_tab); SM_PIN(s_tab); SM_PIN(eps);
+#undef SM_PIN
+  const int nchunk = n_ch / VEC;
+  const int seg_chunks = nchunk / nseg;
   const T* x = (const T*)a.x;
-  // row offsets first: the index programs are evaluated out of line, before any data register is live
+  // row offsets first.  With offset tables all lookups of the wave's rows (load and store side) are in flight together;
+  // the index programs, where there is no table, are evaluated out of line before any data register is live.
   int64_t seg_off[RPW], out_off[RPW];
+  int lt[RPW], st[RPW];
 #pragma unroll
   for (int r = 0; r < RPW; ++r) {
-    const int64_t row = min(row0 + r, a.rows - 1);          // a clamped duplicate row is computed and not stored
-    // segment base offsets: lane j < nseg evaluates segment j, broadcast below
-    if (a.load.identity) seg_off[r] = (row * a.nseg + min(lane, a.nseg - 1)) * a.load.ld;
-    else seg_off[r] = eval_rows_k(&ak->load, row * a.nseg + min(lane, a.nseg - 1));
-    out_off[r] = a.store.identity ? row * a.store.ld : eval_rows_k(&ak->store, row);
+    const int64_t row = min(row0 + r, n_rows - 1);          // a clamped duplicate row is computed and not stored
+    const int64_t li = row * nseg + min(lane, nseg - 1);    // segment base offsets: lane j < nseg evaluates segment j, broadcast below
+    if (l_ident) seg_off[r] = li * l_ld;
+    else if (l_tab) lt[r] = l_tab[li];
+    else seg_off[r] = eval_rows_k(&ak->load, li);
+    if (s_ident) out_off[r] = row * s_ld;
+    else if (s_tab) st[r] = s_tab[row];
+    else out_off[r] = eval_rows_k(&ak->store, row);
+  }
+#pragma unroll
+  for (int r = 0; r < RPW; ++r) {
+    if (!l_ident && l_tab) seg_off[r] = (int64_t)lt[r];
+    if (!s_ident && s_tab) out_off[r] = (int64_t)st[r];
   }
   float v[RPW][MAXCH][VEC];
   float sum[RPW];
@@ -78,6 +99,16 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
       }
     }
   }
+  // gamma and beta ride along with the data loads instead of waiting behind the reductions
+  const T* g = (const T*)a.gamma;
+  const T* bta = (const T*)a.beta;
+  V graw[MAXCH], braw[MAXCH];
+#pragma unroll
+  for (int i = 0; i < MAXCH; ++i) {
+    const int ch = min(lane + 64 * i, nchunk - 1);
+    graw[i] = *(const V*)(g + ch * VEC);
+    braw[i] = *(const V*)((!rms && bta ? bta : g) + ch * VEC);
+  }
   float mean[RPW], rstd[RPW];
 #pragma unroll
   for (int r = 0; r < RPW; ++r) {
@@ -87,7 +118,7 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
       for (int e = 0; e < VEC; ++e) sum[r] += v[r][i][e];
   }
 #pragma unroll
-  for (int r = 0; r < RPW; ++r) mean[r] = a.rms ? 0.f : wave_sum(sum[r]) / (float)a.C;
+  for (int r = 0; r < RPW; ++r) mean[r] = rms ? 0.f : wave_sum(sum[r]) / (float)n_ch;
 #pragma unroll
   for (int r = 0; r < RPW; ++r) {
     float ss = 0.f;
@@ -100,17 +131,15 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
     sum[r] = ss;
   }
 #pragma unroll
-  for (int r = 0; r < RPW; ++r) rstd[r] = rsqrtf(wave_sum(sum[r]) / (float)a.C + a.eps);
+  for (int r = 0; r < RPW; ++r) rstd[r] = rsqrtf(wave_sum(sum[r]) / (float)n_ch + eps);
   T* y = (T*)a.y;
-  const T* g = (const T*)a.gamma;
-  const T* bta = (const T*)a.beta;
 #pragma unroll
   for (int i = 0; i < MAXCH; ++i) {
     const int ch = lane + 64 * i;
     if (ch >= nchunk) continue;
     float gg[VEC], bb[VEC];
-    unpack<T>(*(const V*)(g + ch * VEC), gg);
-    if (!a.rms && bta) unpack<T>(*(const V*)(bta + ch * VEC), bb);
+    unpack<T>(graw[i], gg);
+    if (!rms && bta) unpack<T>(braw[i], bb);
     else {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) bb[e] = 0.f;
@@ -118,7 +147,7 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
       const int64_t row = row0 + r;
-      if (row >= a.rows) continue;
+      if (row >= n_rows) continue;
       const int64_t obase = out_off[r];
       float o[VEC];
 #pragma unroll
