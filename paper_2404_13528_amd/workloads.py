@@ -104,6 +104,22 @@ def vit_case(B, S, E, h, F, seed=0, bf16=True, std=STD, in_std=1.0):
     return x, p
 
 
+def neox_decode_case(B, E, h, L, F, seed=0, bf16=True, std=STD, in_std=1.0):
+    """One decode step of a GPT-NeoX / Pythia-style layer: the new token's hidden state x [B, E], the layer's
+    parameters, and key / value caches [B, h, L, d] of L earlier tokens (O(1) entries, like projected activations)."""
+    dr = Draw(seed, bf16, std)
+    d = E // h
+    x = dr.normal(B, E, std=in_std)
+    p = {"ln1_g": dr.gain(E), "ln1_b": dr.weight(E),
+         "wqkv": dr.weight(3 * E, E), "bqkv": dr.weight(3 * E),
+         "wdense": dr.weight(E, E), "bdense": dr.weight(E),
+         "ln2_g": dr.gain(E), "ln2_b": dr.weight(E),
+         "w1": dr.weight(F, E), "b1": dr.weight(F), "w2": dr.weight(E, F), "b2": dr.weight(E)}
+    k_cache = dr.normal(B, h, L, d, std=in_std)
+    v_cache = dr.normal(B, h, L, d, std=in_std)
+    return x, p, k_cache, v_cache
+
+
 def fanout_case(D1, D2, D3, Kin, Cout, seed=0, bf16=True):
     """Operands of the Fig. 4 graph: activations N(0,1), weights scaled so that every output is O(1)."""
     dr = Draw(seed, bf16)
