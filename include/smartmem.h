@@ -378,6 +378,38 @@ size_t sm_attn_block_workspace_bytes(const sm_attn_cfg*, int mode);
 int sm_attn_block(const sm_attn_cfg*, const void* const* weights, const void* x, const void* context,
                   void* y, void* ws, size_t ws_bytes, int mode, void* stream);
 
+/* A GPT-NeoX / Pythia-style layer at a decode step (Table 7's decoder-only model at one new token per sequence:
+ * every Linear is a matrix-vector product bound by its weight stream, so a materialised layout operator costs
+ * relatively most; Sec. 3.2.1 elimination, Sec. 3.2.2 producer-writes-the-consumer's-layout).  bf16 only.
+ *   y = x + dense(attention(q, [K; k], [V; v])) + W2 gelu(W1 LN2(x) + b1) + b2,   [q | k | v] = Wqkv LN1(x) + bqkv
+ * with Wqkv's 3E output features ordered [head][q | k | v][d], the rotary embedding (half-split pairs (i, i + rot/2),
+ * theta_i = rope_base^(-2i/rot), position L) on the first `rot` features of every query and key head, softmax scale
+ * d^-1/2 over the L cached tokens and the new one, erf GELU, LayerNorm eps `eps`.
+ * x, y: device [B, E].  Weights: device pointers; the four matrices in the fragment order sm_linear_pack writes
+ * (wqkv_p from [3E, E], wdense_p from [E, E], w1_p from [F, E], w2_p from [E, F]); vectors as stored.
+ * k_cache, v_cache: device [B, heads, cache_pitch, d], tokens 0 .. L-1 valid (keys already rotated).
+ *   SM_ELIDED: cache_pitch > L; the new key / value rows are written at token L of k_cache / v_cache by the
+ *     Linear that produces them (the Concat is its store address), the query is read in place from that Linear's
+ *     result, the attention output is stored head-merged; k_out, v_out must be NULL.  Three kernels.
+ *   SM_EXPLICIT: every Slice / Permute / Concat / Reshape of the exported graph that moves data is a copy kernel:
+ *     k_out, v_out: device [B, heads, L + 1, d] receive the grown caches (k_cache / v_cache are only read).
+ * Limits: B <= 32, E a multiple of 64 (<= 8192), d in {64, 128, 256}, F a multiple of 64, rot in {0, 32, 64}.
+ * Workspace from sm_decode_step_workspace_bytes; nothing in it has to survive between calls.  Calls on one stream
+ * are ordered; calls that share a workspace on different streams race. */
+typedef struct {
+  int32_t dtype, B, E, heads, F, rot, L, cache_pitch;
+  float rope_base, eps;
+} sm_decode_cfg;
+typedef struct {
+  const void *ln1_g, *ln1_b, *wqkv_p, *bqkv, *wdense_p, *bdense, *ln2_g, *ln2_b, *w1_p, *b1, *w2_p, *b2;
+} sm_decode_weights;
+/* W [N, K] (bf16, N a multiple of 32, K of 16) rewritten into `packed` (device, N * K elements, caller-owned) in the
+ * fragment order of sm_linear_pack, without that call's limits on K: the layout sm_decode_step reads. */
+int sm_decode_pack(const void* W, int N, int K, int dtype, void* packed, void* stream);
+size_t sm_decode_step_workspace_bytes(const sm_decode_cfg*, int mode);
+int sm_decode_step(const sm_decode_cfg*, const sm_decode_weights*, const void* x, void* k_cache, void* v_cache,
+                   void* y, void* k_out, void* v_out, void* ws, size_t ws_bytes, int mode, void* stream);
+
 /* A whole producer-consumer chain (Sec. 3.2: elimination and fusion alternate
  * over rounds, so removed layout operators leave compute operators adjacent):
  * A Swin chain: optional patch embedding (NCHW image, patch x patch stride

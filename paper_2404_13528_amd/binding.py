@@ -109,7 +109,7 @@ def lib():
         L.sm_last_error.restype = C.c_char_p
         L.sm_map_numel.restype = C.c_int64
         for f in ("sm_fanout_graph_workspace_bytes", "sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes",
-                  "sm_swin_block_static_max_bytes"):
+                  "sm_swin_block_static_max_bytes", "sm_decode_step_workspace_bytes"):
             getattr(L, f).restype = C.c_size_t
         _lib = L
     return _lib
@@ -679,6 +679,62 @@ class FanoutGraph:
         check(lib().sm_fanout_graph(C.byref(c), _ptr(a), _ptr(w), _ptr(wconv), _ptr(r), _ptr(rp), _ptr(cv), _ptr(self.ws),
                                     C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_fanout_graph")
         return r, rp, cv
+
+
+class DecodeCfg(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("B", C.c_int32), ("E", C.c_int32), ("heads", C.c_int32), ("F", C.c_int32),
+                ("rot", C.c_int32), ("L", C.c_int32), ("cache_pitch", C.c_int32), ("rope_base", C.c_float), ("eps", C.c_float)]
+
+
+class DecodeWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("ln1_g", "ln1_b", "wqkv_p", "bqkv", "wdense_p", "bdense", "ln2_g", "ln2_b",
+                                          "w1_p", "b1", "w2_p", "b2")]
+
+
+def decode_pack(W, stream=None):
+    """W [N, K] in matrix-core fragment order (same shape, new tensor): the weight layout of sm_decode_step."""
+    import torch
+    packed = torch.empty_like(W)
+    check(lib().sm_decode_pack(_ptr(W), int(W.shape[0]), int(W.shape[1]), _dt(W), _ptr(packed), _stream(stream)), "sm_decode_pack")
+    return packed
+
+
+class DecodeStep:
+    """sm_decode_step.  params follow workloads.neox_decode_case (device tensors, bf16); the four matrices are packed
+    here, once (an in-place change of a matrix afterwards needs a new object).  Elided: k_cache / v_cache
+    [B, heads, cache_pitch, d] are appended to in place at token L.  Explicit: returns the grown caches as new tensors."""
+
+    def __init__(self, params, B, E, heads, F, rot, mode=SM_ELIDED, rope_base=10000.0, eps=1e-5):
+        import torch
+        p = params
+        self._keep = {k: (decode_pack(p[k]) if k in ("wqkv", "wdense", "w1", "w2") else p[k]) for k in
+                      ("ln1_g", "ln1_b", "wqkv", "bqkv", "wdense", "bdense", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")}
+        k = self._keep
+        self.w = DecodeWeights(*[k[n].data_ptr() for n in ("ln1_g", "ln1_b", "wqkv", "bqkv", "wdense", "bdense", "ln2_g",
+                                                            "ln2_b", "w1", "b1", "w2", "b2")])
+        self.B, self.E, self.heads, self.F, self.rot, self.mode = B, E, heads, F, rot, mode
+        self.rope_base, self.eps = rope_base, eps
+        self.ws = None
+
+    def __call__(self, x, k_cache, v_cache, L, stream=None):
+        import torch
+        d = self.E // self.heads
+        cfg = DecodeCfg(SM_BF16, self.B, self.E, self.heads, self.F, self.rot, int(L), int(k_cache.shape[2]),
+                        self.rope_base, self.eps)
+        n = lib().sm_decode_step_workspace_bytes(C.byref(cfg), self.mode)
+        if n == 0:
+            raise SmError("sm_decode_step_workspace_bytes: " + lib().sm_last_error().decode())
+        if self.ws is None or self.ws.numel() < n:
+            self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        ko = vo = None
+        if self.mode == SM_EXPLICIT:
+            ko = torch.empty(self.B, self.heads, L + 1, d, dtype=x.dtype, device=x.device)
+            vo = torch.empty_like(ko)
+        check(lib().sm_decode_step(C.byref(cfg), C.byref(self.w), _ptr(x), _ptr(k_cache), _ptr(v_cache), _ptr(y), _ptr(ko),
+                                   _ptr(vo), _ptr(self.ws), C.c_size_t(self.ws.numel()), self.mode, _stream(stream)),
+              "sm_decode_step")
+        return (y, ko, vo) if self.mode == SM_EXPLICIT else y
 
 
 class AttnBlock:

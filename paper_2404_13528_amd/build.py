@@ -30,17 +30,28 @@ def build(force=True, jobs=8, verbose=False):
     cpps, hips = sources()
     hdr_m = max(os.path.getmtime(os.path.join(d, f)) for d in (CSRC, os.path.join(HERE, "..", "include"))
                 for f in os.listdir(d) if f.endswith(".h"))
+
+    def newest_dep(obj, src):
+        """mtime of the newest file the object was built from (the compiler's dependency file), else of any header"""
+        dep = obj + ".d"
+        if not os.path.exists(dep):
+            return max(os.path.getmtime(src), hdr_m)
+        words = open(dep).read().replace("\\\n", " ").split()[1:]
+        try:
+            return max(os.path.getmtime(w) for w in words if not w.startswith("/opt/") and not w.startswith("/usr/"))
+        except OSError:
+            return float("inf")
     cmds, objs = [], []
     for n in cpps + hips:
         src = os.path.join(CSRC, n)
         obj = os.path.join(OBJ, n + ".o")
         objs.append(obj)
-        if not force and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), hdr_m):
+        if not force and os.path.exists(obj) and os.path.getmtime(obj) > newest_dep(obj, src):
             continue
         if n.endswith(".hip"):
-            cmds.append([HIPCC, "-x", "hip"] + COMMON + HIPFLAGS + ["-c", src, "-o", obj])
+            cmds.append([HIPCC, "-x", "hip"] + COMMON + HIPFLAGS + ["-MD", "-MF", obj + ".d", "-c", src, "-o", obj])
         else:
-            cmds.append([HIPCC, "-x", "c++", "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__"] + COMMON + ["-c", src, "-o", obj])
+            cmds.append([HIPCC, "-x", "c++", "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__"] + COMMON + ["-MD", "-MF", obj + ".d", "-c", src, "-o", obj])
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         for w in ex.map(_compile, cmds):
             if verbose and w.strip():

@@ -180,6 +180,17 @@ extern "C" int sm_linear_pack(const void* W, int N, int K, int dtype, void* pack
   return SM_OK;
 }
 
+extern "C" int sm_decode_pack(const void* W, int N, int K, int dtype, void* packed, void* stream) {
+  if (dtype != SM_BF16) return fail(SM_ERR_UNSUPPORTED, "sm_decode_pack: bf16 only");
+  if (N < 32 || N % 32 || K < 16 || K % 16) return fail(SM_ERR_SHAPE, "sm_decode_pack: N must be a multiple of 32 and K of 16 (N = %d, K = %d)", N, K);
+  if (!W || !packed) return fail(SM_ERR_INVALID_ARG, "sm_decode_pack: null pointer");
+  if (!aligned16(W) || !aligned16(packed)) return fail(SM_ERR_INVALID_ARG, "sm_decode_pack: pointers must be 16-byte aligned");
+  Timed tm("decode_pack", stream);
+  const int rc = launch_lin_pack(W, N, K, packed, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "sm_decode_pack: launch failed (hip error %d)", rc);
+  return SM_OK;
+}
+
 extern "C" int sm_linear(const sm_linear_desc* d, const void* A, const void* W, const void* bias, const void* residual,
                          void* C, const sm_map* a_map, const sm_map* c_map, void* stream) {
   if (!d) return fail(SM_ERR_INVALID_ARG, "sm_linear: null descriptor");

@@ -18,12 +18,11 @@
 #include "index_map.h"
 #include "kernels.h"
 #include "plan_chains.h"
+#include "plan_views.h"
 
 using namespace sm;
 
 namespace {
-
-struct View4 { int64_t base; int64_t stride[3]; };
 
 struct AttnPlan {
   View4 q1, k1, v1, o1;        // self attention operands as [B, h, S, d] views of their stored tensors
@@ -285,6 +284,11 @@ int attention(int kind, int dt, int B, int h, int nq, int nk, int d, const View4
 View4 contiguous_view(int64_t h, int64_t S, int64_t d, int64_t base = 0) { View4 v; v.base = base; v.stride[0] = h * S * d; v.stride[1] = S * d; v.stride[2] = d; return v; }
 
 }  // namespace
+
+namespace sm {
+bool plan_operand_view(const sm_plan* plan, const GraphB& g, int op, int slot, View4* v, std::string* err) { return operand_view(plan, g, op, slot, v, err); }
+bool plan_output_view(const sm_plan* plan, const GraphB& g, int op, View4* v, std::string* err) { return output_view(plan, g, op, v, err); }
+}
 
 extern "C" size_t sm_attn_block_workspace_bytes(const sm_attn_cfg* c, int mode) {
   if (check_cfg(c, "sm_attn_block_workspace_bytes") != SM_OK) return 0;

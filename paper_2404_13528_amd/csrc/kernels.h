@@ -117,6 +117,37 @@ bool lin32_supported(int N, int K, int dtype);
 int launch_lin_pack(const void* W, int N, int K, void* packed, void* stream);
 int launch_lin32(const Lin32Args& a, void* stream);
 
+// Decode step (k_decode.hip): bf16, at most 32 tokens, weights packed by launch_lin_pack.
+struct DecodeInArgs {
+  const unsigned short* x;                      // [B, E]
+  const unsigned short *ln1_g, *ln1_b, *ln2_g, *ln2_b; float eps;
+  const void *wqkv_p_, *w1_p_;                  // packed [3E, E] (rows ordered [head][q | k | v][d]) and [F, E]
+  const unsigned short *bqkv, *b1;
+  int B, E, h, d, F, rot, L; float rope_base;   // L: position of the new token (= number of cached tokens)
+  unsigned short* dst[3]; int64_t dst_b[3], dst_h[3];   // feature e of head hh of token b of q / k / v goes to dst[t][b * dst_b[t] + hh * dst_h[t] + e]
+  unsigned short* hid;                          // [B, F]
+  int* counters; int n_counters;                // zeroed here for the two kernels that follow
+};
+struct DecodeAttnArgs {
+  const unsigned short* q; int64_t q_b, q_h;    // query row of (b, hh) at q[b * q_b + hh * q_h]
+  const unsigned short *K, *V; int64_t kv_b, kv_h;      // key row t of (b, hh) at K[b * kv_b + hh * kv_h + t * d]
+  unsigned short* o; int64_t o_b, o_h;
+  float* part; int* counters;                   // [B * h][splits][d + 2] floats; one counter per (b, hh), zero on entry
+  int B, h, d, n_keys; float scale_log2e;
+};
+struct DecodeOutArgs {
+  const unsigned short *o, *hid, *x; unsigned short* y;   // [B, E], [B, F], [B, E], [B, E]
+  const void *wdense_p_, *w2_p_; const unsigned short *bdense, *b2;
+  float* part; int* counters;                   // [splits][B][E] floats; one counter per 32 output features, zero on entry
+  int B, E, F;
+};
+size_t decode_in_smem(int B, int E);
+int launch_decode_in(const DecodeInArgs& a, void* stream);
+int launch_decode_attn(const DecodeAttnArgs& a, int nsplit, void* stream);
+int launch_decode_out(const DecodeOutArgs& a, int nks, void* stream);
+// out [BH, L + 1, d] = Concat(cache [BH rows of pitch cache_bh_elems][L, d], fresh [BH, d]) along the token axis
+int launch_decode_concat(const void* cache, int64_t cache_bh_elems, const void* fresh, void* out, int BH, int L, int d, void* stream);
+
 int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,
                      const void* rpb_table, void* stream);
 
