@@ -64,6 +64,18 @@ def kernel_model(label):
             by += 2 * C + 3 * C * C + 3 * C + 3 * M * C
             fl += 6.0 * M * C * C
         return by * e, fl
+    m = re.match(r"decode_(ln\+qkv\+rope\|ln\+fc1\+gelu|dense\+fc2\+res)_bf16\[(\d+),(\d+),(\d+)\]", label)
+    if m:      # skinny Linears of the decode step: the weight once, the token rows in and out, biases / norm vectors
+        B, N, K = int(m.group(2)), int(m.group(3)), int(m.group(4))
+        extra = 4 * K if m.group(1).startswith("ln") else (N + B * N)          # two norms' gamma / beta | second bias, residual
+        return (N * K + N + B * K + B * N + extra) * e, 2.0 * B * N * K
+    m = re.match(r"decode_attention_bf16\[(\d+),(\d+),(\d+),(\d+)\]", label)
+    if m:
+        B, h, n, d = [int(m.group(i)) for i in range(1, 5)]
+        return B * h * (2 * n * d + 2 * d) * e, 4.0 * B * h * n * d
+    m = re.match(r"concat_bf16\[(\d+),(\d+),(\d+)\]", label)
+    if m:
+        return 2 * int(m.group(1)) * int(m.group(2)) * int(m.group(3)) * e, 0.0
     m = re.match(r"(?:ln\+|rms\+)?p?gemm_\w+\[(\d+),(\d+),(\d+)\](.*)", label)
     if m:
         M, N, K = int(m.group(1)), int(m.group(2)), int(m.group(3))
@@ -250,6 +262,18 @@ def build_config(k, sm, torch, Wl):
         return ("extra: Fig. 4 graph MatMul -> Transpose -> Reshape -> {Reduce D3, Reduce' D1, Conv D3}, bf16, D1=512, D2=64, D3=256, "
                 "Kin=256, Cout=64; redundant copy of %d bytes with k=1" % gs["elided"].plan["copy_bytes"], "graphs/s", 1,
                 {n: (lambda g=g: g(ad, wd, wcd)) for n, g in gs.items()}, None, "bf16")
+    if k == 8:     # the paper's decoder-only model (Pythia, Table 7) at a decode step: every Linear is a matrix-vector product
+        B, E, h, L, F, rot = 8, 2048, 8, 2047, 8192, 64
+        d = E // h
+        x, p, kc, vc = Wl.neox_decode_case(B, E, h, L, F)
+        dp, xd = dev(p, bf), x.to(bf).cuda()
+        kbuf = torch.zeros(B, h, L + 1, d, dtype=bf, device="cuda")
+        vbuf = torch.zeros_like(kbuf)
+        kbuf[:, :, :L], vbuf[:, :, :L] = kc.to(bf).cuda(), vc.to(bf).cuda()
+        st = {n: sm.DecodeStep(dp, B, E, h, F, rot, m) for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
+        return ("extra: Pythia-1B-shaped layer at a decode step, bf16, B=8 sequences, 1 new token each, hidden 2048, 8 heads x 256, "
+                "64 rotary features, 2047 cached tokens, GELU MLP 8192, parallel residual", "tokens/s", B,
+                {n: (lambda s_=s_: s_(xd, kbuf, vbuf, L)) for n, s_ in st.items()}, None, "bf16")
     raise ValueError(k)
 
 
@@ -310,7 +334,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json (6: the extra ViT block); 0 = all")
+    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json (6: ViT block, 7: Fig. 4 graph, 8: decode step); 0 = all")
     ap.add_argument("--variants", default="", help="comma-separated subset of the variants (elided, explicit, elided_per_op, explicit_per_op)")
     ap.add_argument("--kernels", action="store_true", help="include every variant's per-kernel table in the JSON line (long)")
     ap.add_argument("--no-autotune", action="store_true",
@@ -343,7 +367,7 @@ def main():
 
     traffic = measured_traffic()
     HEAD = 3
-    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6, 7]
+    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6, 7, 8]
     want = [v for v in a.variants.split(",") if v]
     configs, oracle_sample, calib = {}, None, None
     for k in which:

@@ -24,6 +24,8 @@
 
 using namespace sm;
 
+namespace sm { int decode_attn_block(int d); int decode_counter_stride(); }      // keys of one block of the attention kernel (k_decode.hip)
+
 namespace {
 
 struct DecodePlan {
@@ -104,18 +106,17 @@ int check_cfg(const sm_decode_cfg* c, const char* who) {
 
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 int attn_splits(const sm_decode_cfg& c) {
-  // enough workgroups for every CU several times over, chunks of at least 64 keys and at most 8192 (the LDS score tile)
-  const int bh = c.B * c.heads, n = c.L + 1;
-  int s = (1024 + bh - 1) / bh;
-  s = std::min(s, (n + 63) / 64);
-  s = std::max(s, (n + 8191) / 8192);
-  return std::max(1, std::min(s, 64));
+  // about two workgroups per CU, each with at least two blocks of keys
+  const int bh = c.B * c.heads, block = decode_attn_block(c.E / c.heads), blocks = (c.L + 1 + block - 1) / block;
+  int s = (512 + bh - 1) / bh;
+  s = std::min(s, std::max(1, blocks / 2));
+  return std::max(1, std::min(s, 256));
 }
 int out_splits(const sm_decode_cfg& c) {
   const int slices = c.E / 32, steps = (c.E + c.F) / 16;
-  int s = (1024 + slices - 1) / slices;
-  s = std::min(s, std::max(1, steps / 32));          // at least 8 steps per wave
-  return std::max(1, std::min(s, 64));
+  int s = (256 + slices - 1) / slices;
+  s = std::min(s, std::max(1, steps / 32));          // at least 16 steps per wave
+  return std::max(2, std::min(s, 64));               // at least one split for each of the two matrices
 }
 
 struct Sizes { size_t qkv, hid, o, part_a, part_o, counters, small, total; };
@@ -127,7 +128,7 @@ Sizes sizes(const sm_decode_cfg& c, int mode) {
   z.o = align256(B * E * 2);
   z.part_a = align256(B * h * attn_splits(c) * (d + 2) * sizeof(float));
   z.part_o = align256((size_t)out_splits(c) * B * E * sizeof(float));
-  z.counters = align256((B * h + E / 32) * sizeof(int));
+  z.counters = align256((B * h + E / 32) * decode_counter_stride() * sizeof(int));
   z.small = mode == SM_EXPLICIT ? 5 * z.o : 0;       // q, new k, new v, unmerged output, spare
   z.total = z.qkv + z.hid + z.o + z.part_a + z.part_o + z.counters + z.small;
   return z;
@@ -233,7 +234,7 @@ extern "C" int sm_decode_step(const sm_decode_cfg* c, const sm_decode_weights* w
   DecodeOutArgs u; std::memset(&u, 0, sizeof(u));
   u.o = o; u.hid = hid; u.x = (const unsigned short*)x; u.y = (unsigned short*)y;
   u.wdense_p_ = w->wdense_p; u.w2_p_ = w->w2_p; u.bdense = (const unsigned short*)w->bdense; u.b2 = (const unsigned short*)w->b2;
-  u.part = part_o; u.counters = counters + B * h; u.B = B; u.E = E; u.F = F;
+  u.part = part_o; u.counters = counters + (size_t)B * h * decode_counter_stride(); u.B = B; u.E = E; u.F = F;
   {
     snprintf(label, sizeof(label), "decode_dense+fc2+res_bf16[%d,%d,%d]", B, E, E + F);
     Timed tm(label, stream);

@@ -140,6 +140,7 @@ struct DecodeOutArgs {
   const void *wdense_p_, *w2_p_; const unsigned short *bdense, *b2;
   float* part; int* counters;                   // [splits][B][E] floats; one counter per 32 output features, zero on entry
   int B, E, F;
+  int n_dense, per_max;                         // set by the launcher: K splits given to Wdense, most steps of any split
 };
 size_t decode_in_smem(int B, int E);
 int launch_decode_in(const DecodeInArgs& a, void* stream);
