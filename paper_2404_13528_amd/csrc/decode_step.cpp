@@ -24,7 +24,7 @@
 
 using namespace sm;
 
-namespace sm { int decode_attn_block(int d); int decode_counter_stride(); }      // keys of one block of the attention kernel (k_decode.hip)
+namespace sm { int decode_attn_block(int d); int decode_counter_stride(); size_t decode_out_smem(int B, int E, int F, int nks); }      // keys of one block of the attention kernel (k_decode.hip)
 
 namespace {
 
@@ -101,6 +101,7 @@ int check_cfg(const sm_decode_cfg* c, const char* who) {
   if (c->rot != 0 && c->rot != 32 && c->rot != 64) return fail(SM_ERR_SHAPE, "%s: rotary features must be 0, 32 or 64", who);
   if (c->L < 0 || c->cache_pitch < c->L) return fail(SM_ERR_SHAPE, "%s: the cache pitch must cover the cached tokens", who);
   if (decode_in_smem(c->B, c->E) > 160 * 1024) return fail(SM_ERR_SHAPE, "%s: B x E too large for the LDS token tile", who);
+  if (decode_out_smem(c->B, c->E, c->F, 64) > 48 * 1024) return fail(SM_ERR_SHAPE, "%s: B x (E + F) too large for the last kernel's LDS tile", who);
   return SM_OK;
 }
 
@@ -116,7 +117,9 @@ int out_splits(const sm_decode_cfg& c) {
   const int slices = c.E / 32, steps = (c.E + c.F) / 16;
   int s = (256 + slices - 1) / slices;
   s = std::min(s, std::max(1, steps / 32));          // at least 16 steps per wave
-  return std::max(2, std::min(s, 64));               // at least one split for each of the two matrices
+  s = std::max(2, std::min(s, 64));                  // at least one split for each of the two matrices
+  while (s < 64 && decode_out_smem(c.B, c.E, c.F, s) > 48 * 1024) ++s;      // a split's activation rows must fit its LDS tile
+  return s;
 }
 
 struct Sizes { size_t qkv, hid, o, part_a, part_o, counters, small, total; };

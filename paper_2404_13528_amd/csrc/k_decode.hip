@@ -499,13 +499,24 @@ int launch_decode_attn(const DecodeAttnArgs& a, int nsplit, void* stream) {
   return (int)hipGetLastError();
 }
 
+// K splits given to Wdense (the rest go to W2), the most steps any split gets, and the LDS bytes of its activation rows
+static void decode_out_plan(int B, int E, int F, int nks, int* n_dense, int* per_max, size_t* smem) {
+  const int KE = E / 16, KF = F / 16;
+  *n_dense = std::max(1, std::min(nks - 1, (int)((int64_t)nks * KE / (KE + KF))));
+  *per_max = std::max((KE + *n_dense - 1) / *n_dense, (KF + (nks - *n_dense) - 1) / (nks - *n_dense));
+  *smem = (size_t)B * (*per_max * 16 + 8) * 2;
+}
+size_t decode_out_smem(int B, int E, int F, int nks) {
+  int nd, pm; size_t smem;
+  decode_out_plan(B, E, F, nks, &nd, &pm, &smem);
+  return smem;
+}
+
 int launch_decode_out(const DecodeOutArgs& a0, int nks, void* stream) {
   if (nks < 2) return (int)hipErrorInvalidValue;
   DecodeOutArgs a = a0;
-  const int KE = a.E / 16, KF = a.F / 16;
-  a.n_dense = std::max(1, std::min(nks - 1, (int)((int64_t)nks * KE / (KE + KF))));
-  a.per_max = std::max((KE + a.n_dense - 1) / a.n_dense, (KF + (nks - a.n_dense) - 1) / (nks - a.n_dense));
-  const size_t smem = (size_t)a.B * (a.per_max * 16 + 8) * 2;
+  size_t smem;
+  decode_out_plan(a.B, a.E, a.F, nks, &a.n_dense, &a.per_max, &smem);
   if (smem > 48 * 1024) return (int)hipErrorInvalidValue;
   decode_out_kernel<<<dim3((unsigned)(a.E / 32), (unsigned)nks), dim3(256), smem, (hipStream_t)stream>>>(a);
   return (int)hipGetLastError();

@@ -102,10 +102,10 @@ __device__ __forceinline__ void mlp_load_x_tile(mlp_u32x4* x_l, const bf16_t* X,
 
 // LayerNorm of the tile's rows in place (the norm that precedes the product, folded): eight lanes per token,
 // two-pass fp32 statistics, the result rounded to bf16 as a separate norm kernel would have stored it
-template <int C>
+template <int C, int NTOK = 32>
 __device__ __forceinline__ void mlp_norm_x_tile(mlp_u32x4* x_l, float eps, const mlp_u32x4* gam, const mlp_u32x4* bet) {
   constexpr int XS = C / 8, XP = XS + 1;
-  if (threadIdx.x >= 256) return;               // 256 threads do it (eight per token); no barrier inside
+  if (threadIdx.x >= 8 * NTOK) return;          // eight threads per token; no barrier inside
   const int r = threadIdx.x >> 3, p = threadIdx.x & 7;
   mlp_u32x4* xr = x_l + r * XP;
   float sum = 0.f;
@@ -445,6 +445,173 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// The fused MLP for wide rows (C = 512): Y = residual + W2 . gelu(W1 . LayerNorm(x) + b1) + b2 with a tile of 64 tokens
+// per workgroup and eight waves, each owning 64 output features.  With 32 tokens every weight fragment feeds one MFMA
+// and the stream of fragments from L2 sets the pace; here a fragment of W1 feeds two MFMAs (the two token blocks) and
+// in the second product two weight fragments and two hidden fragments feed four, so per MFMA half a KiB comes from L2
+// and half a KiB from LDS.  Rounds of 256 hidden units: wave w forms slice 8 r + w of the round (32 hidden units x 64
+// tokens: bias, GELU, bf16 into the round's hidden tile in LDS, double-buffered, one barrier per round), then adds
+// the round to its 64 x 64 block of Y^T.  Same packed weight layout as the kernel above (mlp_pack_kernel).  The weight
+// stream of a wave (32 fragments of W1, then 32 of W2 in (step, feature block) order, per round) runs through a ring
+// of 16 fragment registers: each is refilled, right after the MFMAs that read it, with the fragment 16 places on.
+template <int C>
+__global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
+  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = 8, RING = 16;
+  constexpr int HP = 4 * NW + 1;                        // slots of a token's row of the round's hidden tile (+1: odd pitch)
+  constexpr int PER = KK + 4 * NW;                      // fragments of a wave's stream per round: W1 slice, then W2
+  constexpr size_t TILE = (size_t)64 * XP * 16, HTILE = (size_t)64 * HP * 16;
+  static_assert(KK % RING == 0 && (4 * NW) % RING == 0, "the ring position of a fragment must be a compile-time constant");
+  const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                               // [64][XP] token tile, normalised in place
+  mlp_u32x4* h_l = (mlp_u32x4*)(smem_raw + TILE);                      // [2][64][HP]
+  mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + TILE + 2 * HTILE);         // [Hd / 8]
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t row0 = (int64_t)blockIdx.x * 64;
+  const int Hd = g.Hd, nsub = Hd >> 5, rounds = nsub / NW;
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wp), 0, 4 * Hd * C, 0x00020000);
+  const int lo = lane * 16;
+  auto wload = [&](int soff) __attribute__((always_inline)) { return __builtin_amdgcn_raw_buffer_load_b128(rw, lo, soff, 0); };
+  // byte offset of fragment s of the wave's stream in round r (s may run into the next round; past the last round the
+  // last one again: loaded, never used)
+  auto foff = [&](int r, int s) __attribute__((always_inline)) -> int {
+    if (s >= PER) { r += 1; s -= PER; }
+    r = r < rounds ? r : rounds - 1;
+    if (s < KK) return ((NW * r + w) * KK + s) * 1024;
+    const int j = s - KK;                               // second product: step j / 2 of the round, feature block j % 2
+    return 2 * Hd * C + (((2 * w + (j & 1)) * nsub + NW * r) * 2 + (j >> 1)) * 1024;
+  };
+  mlp_u32x4 wf[RING];
+#pragma unroll
+  for (int s = 0; s < RING; ++s) wf[s] = wload(foff(0, s));
+
+  // the lane's two token rows (one per token block): offsets for the residual and the store
+  int64_t ro[2]; bool row_ok[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    const int64_t row = row0 + 32 * tb + l32;
+    row_ok[tb] = row < g.M;
+    const int64_t prow = row_ok[tb] ? row : g.M - 1;
+    ro[tb] = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
+  }
+  mlp_load_x_tile<C, 512>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  if (row0 + 32 < g.M) mlp_load_x_tile<C, 512>(x_l + 32 * XP, (const bf16_t*)g.X, row0 + 32, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  else for (int s = tid; s < 32 * XP; s += 512) x_l[32 * XP + s] = mlp_u32x4{0u, 0u, 0u, 0u};
+  for (int s = tid; s < Hd / 8; s += 512) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
+  __syncthreads();
+  if (g.norm) {
+    mlp_norm_x_tile<C, 64>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
+    __syncthreads();
+  }
+
+  mlp_f32x16 out[2][2];                                 // [feature block][token block]
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) out[i >> 1][i & 1][e] = 0.f;
+  const mlp_u32x4 zero4[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+
+  for (int r = 0; r < rounds; ++r) {
+    // ---- first product: slice NW r + w of the hidden units, both token blocks
+    int xo = l32 * XP + hf;
+    asm volatile("" : "+v"(xo));                        // opaque per round: the X fragments are re-read, not hoisted
+    mlp_f32x16 h[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { h[0][e] = 0.f; h[1][e] = 0.f; }
+    mlp_u32x4 fa[2][2] = {{x_l[xo], x_l[xo + 32 * XP]}, {x_l[xo + 2], x_l[xo + 2 + 32 * XP]}};     // two steps ahead
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const mlp_bf16x8 wv = __builtin_bit_cast(mlp_bf16x8, wf[kk % RING]);
+      h[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][0]), h[0], 0, 0, 0);
+      h[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][1]), h[1], 0, 0, 0);
+      wf[kk % RING] = wload(foff(r, kk + RING));
+      if (kk + 2 < KK) { fa[kk & 1][0] = x_l[xo + 2 * (kk + 2)]; fa[kk & 1][1] = x_l[xo + 2 * (kk + 2) + 32 * XP]; }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    const int sc = NW * r + w;
+    const mlp_u32x4 bias_v = b1_l[sc * 4 + hf], bias_w = b1_l[sc * 4 + 2 + hf];
+    mlp_u32x4* hb = h_l + (r & 1) * (64 * HP);
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      mlp_u32x4 hv[2];
+      mlp_finish(h[tb], bias_v, bias_w, zero4, true, hv);
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) hb[(32 * tb + l32) * HP + w * 4 + 2 * gp + hf] = hv[gp];
+    }
+    __syncthreads();
+    // ---- second product: the wave's 64 features over the round's 256 hidden units (16 steps), both token blocks
+    int ho = l32 * HP + hf;
+    asm volatile("" : "+v"(ho));
+    mlp_u32x4 ga[2][2] = {{hb[ho], hb[ho + 32 * HP]}, {hb[ho + 2], hb[ho + 2 + 32 * HP]}};
+#pragma unroll
+    for (int i = 0; i < 2 * NW; ++i) {
+#pragma unroll
+      for (int bt = 0; bt < 2; ++bt) {
+        const int s = KK + 2 * i + bt;
+        const mlp_bf16x8 wv = __builtin_bit_cast(mlp_bf16x8, wf[s % RING]);
+        out[bt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, ga[i & 1][0]), out[bt][0], 0, 0, 0);
+        out[bt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, ga[i & 1][1]), out[bt][1], 0, 0, 0);
+        wf[s % RING] = wload(foff(r, s + RING));
+      }
+      if (i + 2 < 2 * NW) { ga[i & 1][0] = hb[ho + 2 * (i + 2)]; ga[i & 1][1] = hb[ho + 2 * (i + 2) + 32 * HP]; }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int i = 0; i < 2 * NW; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+  }
+
+  // every wave holds its 64 features of Y^T for the 64 tokens: bias, residual, two 16-byte stores per block and lane
+  bf16_t* Y = (bf16_t*)g.Y;
+  const bf16_t* R = (const bf16_t*)g.residual;
+#pragma unroll
+  for (int bt = 0; bt < 2; ++bt) {
+    const int fo = (2 * w + bt) * 32 + hf * 8;
+    const mlp_u32x4 b2v = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo), b2w = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo + 16);
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      mlp_u32x4 resid[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+      if (R) { resid[0] = *(const mlp_u32x4*)(R + ro[tb] + fo); resid[1] = *(const mlp_u32x4*)(R + ro[tb] + fo + 16); }
+      mlp_u32x4 yv[2];
+      mlp_finish(out[bt][tb], b2v, b2w, resid, false, yv);
+      if (row_ok[tb]) {
+        *(mlp_u32x4*)(Y + ro[tb] + fo) = yv[0];
+        *(mlp_u32x4*)(Y + ro[tb] + fo + 16) = yv[1];
+      }
+    }
+  }
+}
+
+static size_t mlp64_smem(int C, int Hd) { return (size_t)64 * (C / 8 + 1) * 16 + 2 * (size_t)64 * 33 * 16 + (size_t)Hd * 2; }
+static bool mlp64_shape(int C, int Hd) { return C == 512 && Hd >= 256 && Hd % 256 == 0 && Hd <= 16384; }
+
+template <int C>
+static int mlp64_launch(const MlpArgs& g, void* stream) {
+  if (g.Wproj_p || g.Y2 || g.Wq_p) return (int)hipErrorInvalidValue;      // the wide-row kernel is the MLP alone
+  const size_t smem = mlp64_smem(C, g.Hd);
+  static std::atomic<size_t> allowed{0};
+  if (smem > allowed.load()) {
+    const hipError_t e = hipFuncSetAttribute((const void*)mlp64_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return (int)e;
+    allowed.store(smem);
+  }
+  mlp64_kernel<C><<<dim3((unsigned)((g.M + 63) / 64)), dim3(512), smem, (hipStream_t)stream>>>(g);
+  return (int)hipGetLastError();
+}
+
 static size_t mlp_smem(int C, int Hd, bool proj, bool lnout) {
   const size_t tile = (size_t)32 * (C / 8 + 1) * 16, htile = (size_t)32 * (C / 8 + 1) * 16;
   return (proj ? 3 : 1) * tile + 2 * htile + (size_t)Hd * 2 + (proj ? (size_t)C * 2 : 0) + (lnout ? (size_t)2 * (C / 32) * 32 * 4 : 0);
@@ -474,10 +641,12 @@ static int mlp_launch(const MlpArgs& g, void* stream) {
 }
 
 // LDS capacity: the projection variant holds three token tiles
-bool mlp_proj_supported(int C, int Hd, int dtype) { return mlp_fused_supported(C, Hd, dtype) && mlp_smem(C, Hd, true, true) <= 160 * 1024; }
+bool mlp_proj_supported(int C, int Hd, int dtype) { return mlp_fused_supported(C, Hd, dtype) && !mlp64_shape(C, Hd) && mlp_smem(C, Hd, true, true) <= 160 * 1024; }
 
 bool mlp_fused_supported(int C, int Hd, int dtype) {
-  return dtype == SM_BF16 && (C == 128 || C == 256 || C == 384) && Hd >= 32 && Hd % 32 == 0 && Hd <= 16384;
+  if (dtype != SM_BF16) return false;
+  if (mlp64_shape(C, Hd)) return mlp64_smem(C, Hd) <= 160 * 1024;      // wide rows: the 64-token kernel, the MLP alone
+  return (C == 128 || C == 256 || C == 384) && Hd >= 32 && Hd % 32 == 0 && Hd <= 16384;
 }
 
 int launch_mlp_pack(const void* W1, const void* W2, int C, int Hd, void* packed, void* stream) {
@@ -491,6 +660,7 @@ int launch_mlp_fused(const MlpArgs& g, void* stream) {
     case 128: return mlp_launch<128>(g, stream);
     case 256: return mlp_launch<256>(g, stream);
     case 384: return mlp_launch<384>(g, stream);
+    case 512: return mlp64_shape(g.C, g.Hd) ? mlp64_launch<512>(g, stream) : (int)hipErrorInvalidValue;
   }
   return (int)hipErrorInvalidValue;
 }

@@ -335,7 +335,8 @@ def test_empty_inputs_are_no_ops():
     assert sm.linear(x1, sm.linear_pack(W1), b1, M=0, packed=True).shape == (0, 256)
 
 
-@pytest.mark.parametrize("M,C,Hd", [(32, 128, 512), (70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (45, 384, 160)])
+@pytest.mark.parametrize("M,C,Hd", [(32, 128, 512), (70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (45, 384, 160),
+                                    (64, 512, 256), (130, 512, 1024), (12544, 512, 2048), (33, 512, 512)])      # C = 512: the 64-token kernel
 @pytest.mark.parametrize("with_res,with_norm", [(True, False), (False, False), (True, True)])
 def test_mlp_fused(M, C, Hd, with_res, with_norm):
     # (LayerNorm +) FC1 + GELU + FC2 (+ residual) in one kernel against the oracle's operators; row counts that end
@@ -388,6 +389,18 @@ def test_mlp_fused_row_maps_and_unsupported_shapes():
     packed = sm.mlp_pack(dev(W1, dtype), dev(W2, dtype))
     got = sm.mlp_fused(dev(X, dtype), packed, dev(b1, dtype), dev(b2, dtype), x_map=xm)
     assert_close(got, want, dtype, "fused MLP with a mapped X", float(np.abs(want).max()) + 1.0)
+    # the wide-row kernel (C = 512, 64-token tiles): X gathered and Y scattered through a window map, tile ends inside a window
+    M, C, Hd = 3 * 49, 512, 512
+    X, R = draw((M, C), 95, dtype), draw((M, C), 96, dtype)
+    W1, b1 = draw((Hd, C), 97, dtype, C ** -0.5), draw((Hd,), 98, dtype, 0.3)
+    W2, b2 = draw((C, Hd), 99, dtype, Hd ** -0.5), draw((C,), 100, dtype, 0.3)
+    chain_in = V.window_partition_chain(3, 7, 7, C, 7, 0) + [("roll", 0, 1)]
+    xm = sm.Map.create((3, 7, 7, C), chain_in)
+    xin = V.apply_chain(to_np(X).reshape(3, 7, 7, C), chain_in).reshape(M, C)
+    want = O.linear(O.gelu(O.linear(xin, to_np(W1), to_np(b1))), to_np(W2), to_np(b2))
+    got = sm.mlp_fused(dev(X, dtype), sm.mlp_pack(dev(W1, dtype), dev(W2, dtype)), dev(b1, dtype), dev(b2, dtype), x_map=xm)
+    assert_close(got, want, dtype, "wide fused MLP with a mapped X", float(np.abs(want).max()) + 1.0)
+    assert not sm.mlp_fused_supported(512, 384, dtype)          # hidden must be whole rounds of 256
     assert not sm.mlp_fused_supported(96, 384, dtype)
     assert not sm.mlp_fused_supported(128, 100, dtype)
     assert not sm.mlp_fused_supported(128, 512, torch.float32)
