@@ -79,6 +79,7 @@ def _packed_mlp(p, Cc, mlp_ratio, dtype, fuse_mlp):
         return [None, None, None]
     code = SM_BF16 if dtype == torch.bfloat16 else SM_F32
     proj = fuse_mlp is True and bool(lib().sm_mlp_proj_supported(int(Cc), int(mlp_ratio * Cc), code))
+    # (at C = 512 the packed-weight Linear exists but LayerNorm + tiled Linear is as fast for QKV: not packed)
     return [mlp_pack(p["w1"], p["w2"]), linear_pack(p["wproj"]) if proj else None, linear_pack(p["wqkv"]) if proj else None]
 
 

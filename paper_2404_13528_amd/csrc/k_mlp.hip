@@ -142,30 +142,31 @@ __device__ __forceinline__ void mlp_norm_x_tile(mlp_u32x4* x_l, float eps, const
 // bias, optional GELU, optional residual of one 32 x 32 accumulator: register 4b + i of lane (token, hf) is row
 // 8b + 4 hf + i of the block; one v_permlane32_swap per value pair gives the lane eight consecutive rows (run
 // 2 gp + hf of the block's four), packed to bf16 in outv[gp]
+__device__ __forceinline__ mlp_u32x4 mlp_finish_half(const mlp_f32x16& h, int gp, const mlp_u32x4& bias, const mlp_u32x4& res, bool gelu_on) {
+  float v[8], bb[8], rr[8];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(h[8 * gp + q]), __float_as_uint(h[8 * gp + 4 + q]), false, false);
+    v[q] = __uint_as_float(sw[0]);
+    v[4 + q] = __uint_as_float(sw[1]);
+  }
+  mlp_unpack8(bias, bb);
+  mlp_unpack8(res, rr);
+  mlp_u32x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float a = v[2 * e] + bb[2 * e], b = v[2 * e + 1] + bb[2 * e + 1];
+    const float ga = gelu_poly(a), gb = gelu_poly(b);
+    a = gelu_on ? ga : a;
+    b = gelu_on ? gb : b;
+    o[e] = mlp_pack2(a + rr[2 * e], b + rr[2 * e + 1]);
+  }
+  return o;
+}
 __device__ __forceinline__ void mlp_finish(const mlp_f32x16& h, const mlp_u32x4& bias_v, const mlp_u32x4& bias_w, const mlp_u32x4* res,
                                            bool gelu_on, mlp_u32x4* outv) {
 #pragma unroll
-  for (int gp = 0; gp < 2; ++gp) {
-    float v[8], bb[8], rr[8];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(h[8 * gp + q]), __float_as_uint(h[8 * gp + 4 + q]), false, false);
-      v[q] = __uint_as_float(sw[0]);
-      v[4 + q] = __uint_as_float(sw[1]);
-    }
-    mlp_unpack8(gp ? bias_w : bias_v, bb);
-    mlp_unpack8(res[gp], rr);
-    mlp_u32x4 o;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      float a = v[2 * e] + bb[2 * e], b = v[2 * e + 1] + bb[2 * e + 1];
-      const float ga = gelu_poly(a), gb = gelu_poly(b);
-      a = gelu_on ? ga : a;
-      b = gelu_on ? gb : b;
-      o[e] = mlp_pack2(a + rr[2 * e], b + rr[2 * e + 1]);
-    }
-    outv[gp] = o;
-  }
+  for (int gp = 0; gp < 2; ++gp) outv[gp] = mlp_finish_half(h, gp, gp ? bias_w : bias_v, res[gp], gelu_on);
 }
 
 // PROJ: the Linear that precedes the MLP's residual stream is computed here as well (a transformer block's attention
@@ -453,15 +454,15 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 // and half a KiB from LDS.  Rounds of 256 hidden units: wave w forms slice 8 r + w of the round (32 hidden units x 64
 // tokens: bias, GELU, bf16 into the round's hidden tile in LDS, double-buffered, one barrier per round), then adds
 // the round to its 64 x 64 block of Y^T.  Same packed weight layout as the kernel above (mlp_pack_kernel).  The weight
-// stream of a wave (32 fragments of W1, then 32 of W2 in (step, feature block) order, per round) runs through a ring
-// of 16 fragment registers: each is refilled, right after the MFMAs that read it, with the fragment 16 places on.
+// stream of a wave (blocks of 32 fragments: a W1 slice, or a round's W2 fragments in (step, feature block) order) runs
+// through a ring of 16 fragment registers: each is refilled, right after the MFMAs that read it, with the fragment 16
+// places on.
 template <int C>
 __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
   constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = 8, RING = 16;
   constexpr int HP = 4 * NW + 1;                        // slots of a token's row of the round's hidden tile (+1: odd pitch)
-  constexpr int PER = KK + 4 * NW;                      // fragments of a wave's stream per round: W1 slice, then W2
   constexpr size_t TILE = (size_t)64 * XP * 16, HTILE = (size_t)64 * HP * 16;
-  static_assert(KK % RING == 0 && (4 * NW) % RING == 0, "the ring position of a fragment must be a compile-time constant");
+  static_assert(KK % RING == 0 && 4 * NW == KK, "the ring position of a fragment must be a compile-time constant");
   const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
   extern __shared__ __align__(16) unsigned char smem_raw[];
   mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                               // [64][XP] token tile, normalised in place
@@ -474,14 +475,16 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
   const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wp), 0, 4 * Hd * C, 0x00020000);
   const int lo = lane * 16;
   auto wload = [&](int soff) __attribute__((always_inline)) { return __builtin_amdgcn_raw_buffer_load_b128(rw, lo, soff, 0); };
-  // byte offset of fragment s of the wave's stream in round r (s may run into the next round; past the last round the
-  // last one again: loaded, never used)
-  auto foff = [&](int r, int s) __attribute__((always_inline)) -> int {
-    if (s >= PER) { r += 1; s -= PER; }
-    r = r < rounds ? r : rounds - 1;
-    if (s < KK) return ((NW * r + w) * KK + s) * 1024;
-    const int j = s - KK;                               // second product: step j / 2 of the round, feature block j % 2
-    return 2 * Hd * C + (((2 * w + (j & 1)) * nsub + NW * r) * 2 + (j >> 1)) * 1024;
+  // The wave's weight stream in blocks of 32 fragments: W1 slice of round 0; then, for every further round r, the W1
+  // slice of round r followed by the W2 fragments of round r - 1 (step, feature block); last the W2 fragments of the last
+  // round.  Byte offset of fragment s of block b (s may run into the next block; past the last block that one again).
+  const int last_blk = 2 * rounds - 1;
+  auto foff = [&](int b, int s) __attribute__((always_inline)) -> int {
+    if (s >= KK) { b += 1; s -= KK; }
+    b = b < last_blk ? b : last_blk;
+    const bool w2 = b == last_blk || (b != 0 && !(b & 1));
+    const int rr = b == last_blk ? rounds - 1 : (b & 1 ? (b + 1) >> 1 : (b ? (b >> 1) - 1 : 0));
+    return w2 ? 2 * Hd * C + (((2 * w + (s & 1)) * nsub + NW * rr) * 2 + (s >> 1)) * 1024 : ((NW * rr + w) * KK + s) * 1024;
   };
   mlp_u32x4 wf[RING];
 #pragma unroll
@@ -513,11 +516,10 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
     for (int e = 0; e < 16; ++e) out[i >> 1][i & 1][e] = 0.f;
   const mlp_u32x4 zero4[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
 
-  for (int r = 0; r < rounds; ++r) {
-    // ---- first product: slice NW r + w of the hidden units, both token blocks
+  // first product of round r: slice NW r + w of the hidden units, both token blocks (block `blk` of the stream)
+  auto first = [&](int blk, mlp_f32x16 (&h)[2]) __attribute__((always_inline)) {
     int xo = l32 * XP + hf;
     asm volatile("" : "+v"(xo));                        // opaque per round: the X fragments are re-read, not hoisted
-    mlp_f32x16 h[2];
 #pragma unroll
     for (int e = 0; e < 16; ++e) { h[0][e] = 0.f; h[1][e] = 0.f; }
     mlp_u32x4 fa[2][2] = {{x_l[xo], x_l[xo + 32 * XP]}, {x_l[xo + 2], x_l[xo + 2 + 32 * XP]}};     // two steps ahead
@@ -526,7 +528,7 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
       const mlp_bf16x8 wv = __builtin_bit_cast(mlp_bf16x8, wf[kk % RING]);
       h[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][0]), h[0], 0, 0, 0);
       h[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][1]), h[1], 0, 0, 0);
-      wf[kk % RING] = wload(foff(r, kk + RING));
+      wf[kk % RING] = wload(foff(blk, kk + RING));
       if (kk + 2 < KK) { fa[kk & 1][0] = x_l[xo + 2 * (kk + 2)]; fa[kk & 1][1] = x_l[xo + 2 * (kk + 2) + 32 * XP]; }
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
@@ -536,42 +538,53 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
       __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
     }
-    const int sc = NW * r + w;
-    const mlp_u32x4 bias_v = b1_l[sc * 4 + hf], bias_w = b1_l[sc * 4 + 2 + hf];
-    mlp_u32x4* hb = h_l + (r & 1) * (64 * HP);
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-      mlp_u32x4 hv[2];
-      mlp_finish(h[tb], bias_v, bias_w, zero4, true, hv);
-#pragma unroll
-      for (int gp = 0; gp < 2; ++gp) hb[(32 * tb + l32) * HP + w * 4 + 2 * gp + hf] = hv[gp];
-    }
-    __syncthreads();
-    // ---- second product: the wave's 64 features over the round's 256 hidden units (16 steps), both token blocks
+  };
+  // bias + GELU of a quarter (token block u / 2, half u % 2 of its 32 hidden units) of the slice just formed, bf16, into `hb`
+  auto finish_unit = [&](int r, int u, const mlp_f32x16 (&h)[2], mlp_u32x4* hb) __attribute__((always_inline)) {
+    const int sc = NW * r + w, tb = u >> 1, gp = u & 1;
+    hb[(32 * tb + l32) * HP + w * 4 + 2 * gp + hf] = mlp_finish_half(h[tb], gp, b1_l[sc * 4 + 2 * gp + hf], zero4[0], true);
+  };
+  // second product of a round: the wave's 64 features over the 256 hidden units of tile `hp` (16 steps), both token
+  // blocks.  between(q) runs after steps 4 q .. 4 q + 3.
+  auto second = [&](int blk, const mlp_u32x4* hp, auto between) __attribute__((always_inline)) {
     int ho = l32 * HP + hf;
     asm volatile("" : "+v"(ho));
-    mlp_u32x4 ga[2][2] = {{hb[ho], hb[ho + 32 * HP]}, {hb[ho + 2], hb[ho + 2 + 32 * HP]}};
+    mlp_u32x4 ga[2][2] = {{hp[ho], hp[ho + 32 * HP]}, {hp[ho + 2], hp[ho + 2 + 32 * HP]}};
 #pragma unroll
     for (int i = 0; i < 2 * NW; ++i) {
 #pragma unroll
       for (int bt = 0; bt < 2; ++bt) {
-        const int s = KK + 2 * i + bt;
+        const int s = 2 * i + bt;
         const mlp_bf16x8 wv = __builtin_bit_cast(mlp_bf16x8, wf[s % RING]);
         out[bt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, ga[i & 1][0]), out[bt][0], 0, 0, 0);
         out[bt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, ga[i & 1][1]), out[bt][1], 0, 0, 0);
-        wf[s % RING] = wload(foff(r, s + RING));
+        wf[s % RING] = wload(foff(blk, s + RING));
       }
-      if (i + 2 < 2 * NW) { ga[i & 1][0] = hb[ho + 2 * (i + 2)]; ga[i & 1][1] = hb[ho + 2 * (i + 2) + 32 * HP]; }
+      if (i + 2 < 2 * NW) { ga[i & 1][0] = hp[ho + 2 * (i + 2)]; ga[i & 1][1] = hp[ho + 2 * (i + 2) + 32 * HP]; }
+      if ((i & 3) == 3) {
+        __builtin_amdgcn_sched_barrier(0);
+        between(i >> 2);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+  };
+
+  // Rounds, software-pipelined: the second product of round r - 1 (matrix cores) alternates, a quarter at a time, with
+  // the bias + GELU of round r's slice (vector ALU).  A barrier per round puts all waves of the workgroup in the same
+  // phase; alternating in short stretches lets the two waves of a SIMD cover each other's vector work with MFMAs.
+  {
+    mlp_f32x16 h[2];
+    first(0, h);
 #pragma unroll
-    for (int i = 0; i < 2 * NW; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    for (int u = 0; u < 4; ++u) finish_unit(0, u, h, h_l);
+    __syncthreads();
+    for (int r = 1; r < rounds; ++r) {
+      first(2 * r - 1, h);
+      mlp_u32x4* hb = h_l + (r & 1) * (64 * HP);
+      second(2 * r, h_l + ((r - 1) & 1) * (64 * HP), [&](int q) __attribute__((always_inline)) { finish_unit(r, q, h, hb); });
+      __syncthreads();
     }
+    second(last_blk, h_l + ((rounds - 1) & 1) * (64 * HP), [&](int) __attribute__((always_inline)) {});
   }
 
   // every wave holds its 64 features of Y^T for the 64 tokens: bias, residual, two 16-byte stores per block and lane
@@ -774,6 +787,116 @@ __global__ void lin_pack_kernel(const bf16_t* W, mlp_u32x4* packed, int N, int K
   packed[o] = *(const mlp_u32x4*)(W + (int64_t)(32 * sc + l32) * K + 16 * kk + 8 * hf);
 }
 
+// The same Linear for wide rows (K = 512): 64 tokens per workgroup, eight waves, every weight fragment feeding two
+// MFMAs (the two token blocks); the N / 32 slices of W are dealt round-robin to the waves and a wave's fragments run
+// through a ring of 16 registers, as in mlp64_kernel.  LayerNorm folded as above.
+template <int C, bool RES>
+__global__ __launch_bounds__(512, 1) void lin64_kernel(Lin32Args g) {
+  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = 8, RING = 16;
+  const SM_KARG Lin32Args* gk = kernarg_ptr<Lin32Args>();
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                                  // [64][XP]
+  mlp_u32x4* b_l = (mlp_u32x4*)(smem_raw + (size_t)64 * XP * 16);         // [N / 8]
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t row0 = (int64_t)blockIdx.x * 64;
+  const int nsub = g.N >> 5;
+  const int njobs = (nsub - w + NW - 1) / NW;                             // slices of this wave: w, w + NW, ...
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wp), 0, 2 * g.N * C, 0x00020000);
+  const int lo = lane * 16;
+  auto wload = [&](int soff) __attribute__((always_inline)) { return __builtin_amdgcn_raw_buffer_load_b128(rw, lo, soff, 0); };
+  // fragment s of the wave's j-th slice (s may run into the next slice; past the last slice that one again)
+  auto foff = [&](int j, int s) __attribute__((always_inline)) -> int {
+    if (s >= KK) { j += 1; s -= KK; }
+    j = j < njobs ? j : njobs - 1;
+    return ((w + NW * (j > 0 ? j : 0)) * KK + s) * 1024;
+  };
+  mlp_u32x4 wf[RING];
+#pragma unroll
+  for (int s = 0; s < RING; ++s) wf[s] = wload(foff(0, s));
+  int64_t ro[2]; bool row_ok[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    const int64_t row = row0 + 32 * tb + l32;
+    row_ok[tb] = row < g.M;
+    const int64_t prow = row_ok[tb] ? row : g.M - 1;
+    ro[tb] = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
+  }
+  mlp_load_x_tile<C, 512>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  if (row0 + 32 < g.M) mlp_load_x_tile<C, 512>(x_l + 32 * XP, (const bf16_t*)g.X, row0 + 32, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  else for (int s = tid; s < 32 * XP; s += 512) x_l[32 * XP + s] = mlp_u32x4{0u, 0u, 0u, 0u};
+  for (int s = tid; s < g.N / 8; s += 512) b_l[s] = g.bias ? ((const mlp_u32x4*)g.bias)[s] : mlp_u32x4{0u, 0u, 0u, 0u};
+  __syncthreads();
+  if (g.norm) {
+    mlp_norm_x_tile<C, 64>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
+    __syncthreads();
+  }
+  const bf16_t* R = (const bf16_t*)g.residual;
+  bf16_t* Y = (bf16_t*)g.Y;
+  const bool gelu_on = g.act == SM_ACT_GELU;
+  for (int j = 0; j < njobs; ++j) {
+    const int sc = w + NW * j;
+    int xo = l32 * XP + hf;
+    asm volatile("" : "+v"(xo));                        // opaque per slice: the X fragments are re-read, not hoisted
+    const mlp_u32x4 bias_v = b_l[sc * 4 + hf], bias_w = b_l[sc * 4 + 2 + hf];
+    mlp_u32x4 res[2][2] = {{{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}}, {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}}};
+    if constexpr (RES) {
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        res[tb][0] = *(const mlp_u32x4*)(R + ro[tb] + sc * 32 + hf * 8);
+        res[tb][1] = *(const mlp_u32x4*)(R + ro[tb] + sc * 32 + 16 + hf * 8);
+      }
+    }
+    mlp_f32x16 h[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { h[0][e] = 0.f; h[1][e] = 0.f; }
+    mlp_u32x4 fa[2][2] = {{x_l[xo], x_l[xo + 32 * XP]}, {x_l[xo + 2], x_l[xo + 2 + 32 * XP]}};     // two steps ahead
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const mlp_bf16x8 wv = __builtin_bit_cast(mlp_bf16x8, wf[kk % RING]);
+      h[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][0]), h[0], 0, 0, 0);
+      h[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][1]), h[1], 0, 0, 0);
+      wf[kk % RING] = wload(foff(j, kk + RING));
+      if (kk + 2 < KK) { fa[kk & 1][0] = x_l[xo + 2 * (kk + 2)]; fa[kk & 1][1] = x_l[xo + 2 * (kk + 2) + 32 * XP]; }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      mlp_u32x4 outv[2];
+      mlp_finish(h[tb], bias_v, bias_w, res[tb], gelu_on, outv);
+      if (row_ok[tb]) {
+        // (assembly, as in lin32_kernel: with stores pending next to loads the compiler's wait counting falls back to
+        // waiting for everything before the next slice's first fragment)
+        bf16_t* yp = Y + ro[tb] + sc * 32 + hf * 8;
+        asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:32\n\ts_nop 2"
+                     :: "v"(yp), "v"(outv[0]), "v"(outv[1]) : "memory");
+      }
+    }
+  }
+}
+
+template <int C>
+static int lin64_launch(const Lin32Args& g, void* stream) {
+  const size_t smem = (size_t)64 * (C / 8 + 1) * 16 + (size_t)g.N * 2;
+  static std::atomic<size_t> allowed{0};
+  if (smem > allowed.load()) {
+    hipError_t e = hipFuncSetAttribute((const void*)lin64_kernel<C, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)lin64_kernel<C, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return (int)e;
+    allowed.store(smem);
+  }
+  const dim3 grid((unsigned)((g.M + 63) / 64));
+  if (g.residual) lin64_kernel<C, true><<<grid, dim3(512), smem, (hipStream_t)stream>>>(g);
+  else lin64_kernel<C, false><<<grid, dim3(512), smem, (hipStream_t)stream>>>(g);
+  return (int)hipGetLastError();
+}
+
 template <int C, bool RES, int NW>
 static int lin32_launch3(const Lin32Args& g, void* stream) {
   const size_t smem = (size_t)32 * (C / 8 + 1) * 16 + (size_t)g.N * 2;
@@ -798,7 +921,7 @@ static int lin32_launch(const Lin32Args& g, void* stream) {
 }
 
 bool lin32_supported(int N, int K, int dtype) {
-  return dtype == SM_BF16 && (K == 128 || K == 256 || K == 384) && N >= 32 && N % 32 == 0 && N <= 16384;
+  return dtype == SM_BF16 && (K == 128 || K == 256 || K == 384 || K == 512) && N >= 32 && N % 32 == 0 && N <= 16384;
 }
 
 int launch_lin_pack(const void* W, int N, int K, void* packed, void* stream) {
@@ -812,6 +935,7 @@ int launch_lin32(const Lin32Args& g, void* stream) {
     case 128: return lin32_launch<128>(g, stream);
     case 256: return lin32_launch<256>(g, stream);
     case 384: return lin32_launch<384>(g, stream);
+    case 512: return lin64_launch<512>(g, stream);      // wide rows: 64-token tiles
   }
   return (int)hipErrorInvalidValue;
 }

@@ -408,7 +408,8 @@ def test_mlp_fused_row_maps_and_unsupported_shapes():
         sm.mlp_pack(dev(draw((384, 96), 2, dtype), dtype), dev(draw((96, 384), 4, dtype), dtype))
 
 
-@pytest.mark.parametrize("M,N,K", [(32, 128, 128), (70, 96, 128), (200, 1152, 384), (6272, 384, 384), (45, 160, 256)])
+@pytest.mark.parametrize("M,N,K", [(32, 128, 128), (70, 96, 128), (200, 1152, 384), (6272, 384, 384), (45, 160, 256),
+                                   (200, 1536, 512), (12544, 1536, 512), (45, 160, 512), (97, 96, 512)])      # K = 512: 64-token tiles
 @pytest.mark.parametrize("variant", ["plain", "gelu", "res", "ln+res"])
 def test_linear_with_packed_weight(M, N, K, variant):
     # the kernel that streams a packed weight into registers against the oracle: row counts that end inside a 32-row
