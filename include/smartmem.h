@@ -244,10 +244,10 @@ typedef struct {
 int sm_linear(const sm_linear_desc*, const void* A, const void* W, const void* bias, const void* residual,
               void* C, const sm_map* a_map, const sm_map* c_map, void* stream);
 /* Weight layout for short reduction dimensions (Sec. 3.2.2's rule, the producer writes the layout its consumer reads
- * best, applied to a constant): for bf16, K in {128, 256, 384} and N a multiple of 32 (sm_linear_pack_supported),
+ * best, applied to a constant): for bf16, K in {128, 256, 384, 512} and N a multiple of 32 (sm_linear_pack_supported),
  * sm_linear_pack rewrites W [N, K] into `packed` (device, N * K elements, 16-byte aligned, caller-owned) in the order
  * of the matrix-core operand fragments.  sm_linear with w_packed = 1 and that buffer as W then runs a kernel in which
- * a workgroup keeps 32 rows of A in LDS for all N outputs and the weight streams from L2 straight into registers: no
+ * a workgroup keeps 32 rows of A (64 at K = 512) in LDS for all N outputs and the weight streams from L2 straight into registers: no
  * K-loop barriers, and a LayerNorm (norm = 1, beta required) costs one pass over the resident tile.  It pays most with
  * a folded LayerNorm and a short K against many rows (no norm kernel, no K-loop barriers).  Restrictions with w_packed: activation none or
  * GELU, no RoPE, no transposed store, row maps only (a map that splits columns returns SM_ERR_UNSUPPORTED). */
@@ -265,8 +265,9 @@ int sm_linear_pack(const void* W, int N, int K, int dtype, void* packed, void* s
  * aligned.  norm = 1: LayerNorm over C of every row of X first (gamma, beta [C], device; rounded to bf16 as sm_norm
  * would store it).  The hidden activation is rounded to bf16 before the second product, as the two-kernel path
  * stores it.  x_map / y_map (nullable): row maps as in sm_linear (the residual is read through y_map).
- * sm_mlp_fused_supported: 1 if a shape has a kernel (C in {128, 256, 384}, hidden a multiple of 32 up to 16384,
- * bf16); other shapes return SM_ERR_UNSUPPORTED from both calls and nothing is enqueued. */
+ * sm_mlp_fused_supported: 1 if a shape has a kernel (bf16; C in {128, 256, 384} with hidden a multiple of 32 up to
+ * 16384: 32-token tiles; C = 512 with hidden a multiple of 256: 64-token tiles, the MLP alone, i.e. no proj_packed);
+ * other shapes return SM_ERR_UNSUPPORTED from both calls and nothing is enqueued. */
 typedef struct {
   int64_t M; int32_t C, hidden, dtype;
   int32_t norm; float norm_eps;

@@ -717,17 +717,24 @@ class DecodeStep:
         self.rope_base, self.eps = rope_base, eps
         self.ws = None
 
-    def __call__(self, x, k_cache, v_cache, L, stream=None):
+    def _cfg(self, L, pitch):
+        return DecodeCfg(SM_BF16, self.B, self.E, self.heads, self.F, self.rot, int(L), int(pitch), self.rope_base, self.eps)
+
+    def reserve(self, L, pitch):
+        """Sizes the workspace for a step with L cached tokens (so that a later call, e.g. under graph capture, allocates nothing)."""
         import torch
-        d = self.E // self.heads
-        cfg = DecodeCfg(SM_BF16, self.B, self.E, self.heads, self.F, self.rot, int(L), int(k_cache.shape[2]),
-                        self.rope_base, self.eps)
-        n = lib().sm_decode_step_workspace_bytes(C.byref(cfg), self.mode)
+        n = lib().sm_decode_step_workspace_bytes(C.byref(self._cfg(L, pitch)), self.mode)
         if n == 0:
             raise SmError("sm_decode_step_workspace_bytes: " + lib().sm_last_error().decode())
         if self.ws is None or self.ws.numel() < n:
             self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
-        y = torch.empty_like(x)
+
+    def __call__(self, x, k_cache, v_cache, L, out=None, stream=None):
+        import torch
+        d = self.E // self.heads
+        cfg = self._cfg(L, k_cache.shape[2])
+        self.reserve(L, k_cache.shape[2])
+        y = torch.empty_like(x) if out is None else out
         ko = vo = None
         if self.mode == SM_EXPLICIT:
             ko = torch.empty(self.B, self.heads, L + 1, d, dtype=x.dtype, device=x.device)

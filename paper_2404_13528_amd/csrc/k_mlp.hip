@@ -764,7 +764,8 @@ __global__ __launch_bounds__(64 * NW, 1) void lin32_kernel(Lin32Args g) {
       if constexpr (!XREG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     mlp_u32x4 outv[2];
-    mlp_finish(h, bias_v, bias_w, res, gelu_on, outv);
+    // (a literal flag in each branch: with a run-time flag the polynomial is evaluated for every value and thrown away)
+    if (gelu_on) mlp_finish(h, bias_v, bias_w, res, true, outv); else mlp_finish(h, bias_v, bias_w, res, false, outv);
     if (row_ok) {
       // Written as assembly so that the compiler's wait-count bookkeeping sees loads only: with stores pending next to
       // loads it stops counting and waits for everything (vmcnt 0) at the top of the next slice, which exposes the
@@ -869,7 +870,7 @@ __global__ __launch_bounds__(512, 1) void lin64_kernel(Lin32Args g) {
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
       mlp_u32x4 outv[2];
-      mlp_finish(h[tb], bias_v, bias_w, res[tb], gelu_on, outv);
+      if (gelu_on) mlp_finish(h[tb], bias_v, bias_w, res[tb], true, outv); else mlp_finish(h[tb], bias_v, bias_w, res[tb], false, outv);
       if (row_ok[tb]) {
         // (assembly, as in lin32_kernel: with stores pending next to loads the compiler's wait counting falls back to
         // waiting for everything before the next slice's first fragment)

@@ -75,3 +75,37 @@ def test_chain_and_attn_block_under_capture():
     ref2 = sm.AttnBlock("llama", dq, dtype, sm.SM_ELIDED, B=Bq, S=S, E=E, heads=hh, F=F)
     _replays_match(lambda x, out: blk(x, out=out), lambda x: ref2(x),
                    lambda i: dev(Wl.llama_case(Bq, S, E, F, seed=30 + i)[0], dtype))
+
+
+def test_decode_step_first_call_under_capture():
+    # a decode step whose plan the library has not built yet, captured; every replay rewrites cache row L and must give
+    # the eager result bit for bit (the arrival counters of its split reductions are zeroed by the step's first kernel)
+    dtype = torch.bfloat16
+    B, E, h, L, F, rot = 4, 256, 2, 333, 512, 64
+    d = E // h
+    x0, p, kc, vc = Wl.neox_decode_case(B, E, h, L, F, seed=9, bf16=True, std=0.1)
+    dp = dev_params(p, dtype)
+    step = sm.DecodeStep(dp, B, E, h, F, rot, sm.SM_ELIDED)
+    ref = sm.DecodeStep(dp, B, E, h, F, rot, sm.SM_ELIDED)
+    caches = []
+    for _ in range(2):
+        kb = torch.zeros(B, h, L + 5, d, dtype=dtype, device="cuda")
+        vb = torch.zeros_like(kb)
+        kb[:, :, :L], vb[:, :, :L] = dev(kc, dtype), dev(vc, dtype)
+        caches.append((kb, vb))
+    step.reserve(L, L + 5)
+    x_static = dev(x0, dtype).clone()
+    y_static = torch.empty_like(x_static)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(x_static, caches[0][0], caches[0][1], L, out=y_static)
+    for i in range(1, 4):
+        x = dev(Wl.neox_decode_case(B, E, h, L, F, seed=40 + i, bf16=True)[0], dtype)
+        x_static.copy_(x)
+        g.replay()
+        torch.cuda.synchronize()
+        got, k_got = y_static.clone(), caches[0][0][:, :, L].clone()
+        want = ref(x, caches[1][0], caches[1][1], L)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want) and torch.equal(k_got, caches[1][0][:, :, L]), "replay %d differs from the eager call" % i
