@@ -608,12 +608,312 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
   }
 }
 
+// mlp64_kernel with the attention output projection in front and, optionally, the next block's LayerNorm-1 (LNOUT = 1)
+// or LayerNorm-1 + QKV Linear (LNOUT = 2) behind it: the C = 512 form of mlp_fused_kernel<C, true, LNOUT>, 64-token
+// tiles.  x1 = A . Wproj^T + bproj + x0 (x0 read and Y written through y_rows); x1 (bf16) goes to LDS, where it is
+// normalised for the first product, and to Y in memory, from where every lane reads back what it stored itself as the
+// residual of the final sum (three 64-token tiles do not fit the LDS).  LDS: [x1 normalised | A tile, then the two
+// hidden tiles, then the normalised Y for the QKV Linear | b1, then bq | bproj | row statistics].
+// One weight stream per wave through the ring of 16 fragment registers, in blocks of 32 fragments: two blocks of Wproj
+// ((step, feature block) order, the wave's two slices of lin_pack_kernel's layout), the blocks of mlp64_kernel, then
+// the wave's six QKV slices.
+template <int C, int LNOUT>
+__global__ __launch_bounds__(512, 1) void mlp64p_kernel(MlpArgs g) {
+  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = 8, RING = 16, HP = 4 * NW + 1, NQ = 3 * C / 32 / NW;
+  constexpr size_t TILE = (size_t)64 * XP * 16, HTILE = (size_t)64 * HP * 16;
+  static_assert(KK % RING == 0 && 4 * NW == KK && 2 * HTILE >= TILE, "block and alias assumptions");
+  const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                               // [64][XP] x1, normalised in place
+  mlp_u32x4* a_l = (mlp_u32x4*)(smem_raw + TILE);                      // [64][XP] attention output; dead after the projection
+  mlp_u32x4* h_l = a_l;                                                // [2][64][HP] hidden tiles
+  mlp_u32x4* n_l = a_l;                                                // [64][XP] normalised Y (LNOUT = 2), after the last round
+  mlp_u32x4* b1_l = (mlp_u32x4*)(smem_raw + TILE + 2 * HTILE);         // [Hd / 8], later bq [3 C / 8]
+  mlp_u32x4* bp_l = b1_l + g.Hd / 8;                                   // [C / 8]
+  float* st_l = (float*)(bp_l + XS);                                   // [2][NW][64] row statistics
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t row0 = (int64_t)blockIdx.x * 64;
+  const int Hd = g.Hd, nsub = Hd >> 5, rounds = nsub / NW;
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wp), 0, 4 * Hd * C, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wproj_p), 0, 2 * C * C, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rq = LNOUT == 2 ? __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.Wq_p), 0, 6 * C * C, 0x00020000) : rw;
+  const int lo = lane * 16;
+  // The wave's stream: 64 fragments of Wproj ((step, feature block) order), the MLP's blocks of 32 (see mlp64_kernel),
+  // then NQ blocks of the QKV weight.  Which weight a refill reads is known where it is written, so each kind has its
+  // own loader (descriptor and offset scalar) and the MFMA loops stay straight-line code.
+  const int lastm = 2 * rounds - 1;
+  auto frag_p = [&](int t) __attribute__((always_inline)) {          // t < 64: step t / 2, feature block t % 2
+    return __builtin_amdgcn_raw_buffer_load_b128(rp, lo, ((2 * w + (t & 1)) * KK + (t >> 1)) * 1024, 0);
+  };
+  auto frag_m = [&](int m, int s) __attribute__((always_inline)) {   // fragment s of MLP block m (s >= KK: of block m + 1)
+    if (s >= KK) { m += 1; s -= KK; }
+    m = m < lastm ? m : lastm;
+    const bool w2 = m == lastm || (m != 0 && !(m & 1));
+    const int rr = m == lastm ? rounds - 1 : (m & 1 ? (m + 1) >> 1 : (m ? (m >> 1) - 1 : 0));
+    return __builtin_amdgcn_raw_buffer_load_b128(rw, lo, w2 ? 2 * Hd * C + (((2 * w + (s & 1)) * nsub + NW * rr) * 2 + (s >> 1)) * 1024
+                                                            : ((NW * rr + w) * KK + s) * 1024, 0);
+  };
+  auto frag_q = [&](int j, int s) __attribute__((always_inline)) {   // fragment s of the wave's j-th QKV slice
+    if (s >= KK) { j += 1; s -= KK; }
+    j = j < NQ ? j : NQ - 1;
+    return __builtin_amdgcn_raw_buffer_load_b128(rq, lo, ((w + NW * j) * KK + s) * 1024, 0);
+  };
+  mlp_u32x4 wf[RING];
+#pragma unroll
+  for (int s = 0; s < RING; ++s) wf[s] = frag_p(s);
+
+  int64_t ro[2], ro2[2] = {0, 0}; bool row_ok[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    const int64_t row = row0 + 32 * tb + l32;
+    row_ok[tb] = row < g.M;
+    const int64_t prow = row_ok[tb] ? row : g.M - 1;
+    ro[tb] = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
+    if constexpr (LNOUT != 0) ro2[tb] = g.y2_rows.identity ? prow * g.y2_rows.ld : eval_rows_k(&gk->y2_rows, prow);
+  }
+  mlp_load_x_tile<C, 512>(a_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  if (row0 + 32 < g.M) mlp_load_x_tile<C, 512>(a_l + 32 * XP, (const bf16_t*)g.X, row0 + 32, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  else for (int s = tid; s < 32 * XP; s += 512) a_l[32 * XP + s] = mlp_u32x4{0u, 0u, 0u, 0u};
+  for (int s = tid; s < Hd / 8; s += 512) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
+  for (int s = tid; s < XS; s += 512) bp_l[s] = ((const mlp_u32x4*)g.bproj)[s];
+  __syncthreads();
+
+  mlp_f32x16 out[2][2];                                 // [feature block][token block]: the projection, then Y^T
+  const mlp_u32x4 zero4[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+  auto clear_out = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) out[i >> 1][i & 1][e] = 0.f;
+  };
+  // out[bt][tb] += W(step i, feature block bt) x tile(token block tb, step i) for `steps` steps: the wave's 64 features
+  // against a 64-token tile in LDS (row pitch `pitch` slots); refill(t) loads the fragment at position t of the call's
+  // stream (t >= 2 * steps: what follows it).  between(q) after steps 4 q .. 4 q + 3.
+  auto pair_product = [&](const mlp_u32x4* tile, int pitch, int steps, auto refill, auto between) __attribute__((always_inline)) {
+    int to = l32 * pitch + hf;
+    asm volatile("" : "+v"(to));
+    const int hi = 32 * pitch;
+    mlp_u32x4 ga[2][2] = {{tile[to], tile[to + hi]}, {tile[to + 2], tile[to + 2 + hi]}};
+#pragma unroll
+    for (int i = 0; i < KK; ++i) {
+      if (i < steps) {
+#pragma unroll
+        for (int bt = 0; bt < 2; ++bt) {
+          const int t = 2 * i + bt;
+          const mlp_bf16x8 wv = __builtin_bit_cast(mlp_bf16x8, wf[t % RING]);
+          out[bt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, ga[i & 1][0]), out[bt][0], 0, 0, 0);
+          out[bt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, ga[i & 1][1]), out[bt][1], 0, 0, 0);
+          wf[t % RING] = refill(t + RING);
+        }
+        if (i + 2 < steps) { ga[i & 1][0] = tile[to + 2 * (i + 2)]; ga[i & 1][1] = tile[to + 2 * (i + 2) + hi]; }
+        if ((i & 3) == 3) {
+          __builtin_amdgcn_sched_barrier(0);
+          between(i >> 2);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  };
+  // h[tb] = W(slice of block blk) x tile(token block tb): 32 hidden / output features of a slice for the 64 tokens
+  auto slice_product = [&](const mlp_u32x4* tile, mlp_f32x16 (&h)[2], auto refill) __attribute__((always_inline)) {
+    int xo = l32 * XP + hf;
+    asm volatile("" : "+v"(xo));
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { h[0][e] = 0.f; h[1][e] = 0.f; }
+    mlp_u32x4 fa[2][2] = {{tile[xo], tile[xo + 32 * XP]}, {tile[xo + 2], tile[xo + 2 + 32 * XP]}};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const mlp_bf16x8 wv = __builtin_bit_cast(mlp_bf16x8, wf[kk % RING]);
+      h[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][0]), h[0], 0, 0, 0);
+      h[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][1]), h[1], 0, 0, 0);
+      wf[kk % RING] = refill(kk + RING);
+      if (kk + 2 < KK) { fa[kk & 1][0] = tile[xo + 2 * (kk + 2)]; fa[kk & 1][1] = tile[xo + 2 * (kk + 2) + 32 * XP]; }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+  };
+  auto nothing = [&](int) __attribute__((always_inline)) {};
+  bf16_t* Y = (bf16_t*)g.Y;
+
+  // ---- projection: x1 = A . Wproj^T + bproj + x0 for the wave's 64 features
+  clear_out();
+  pair_product(a_l, XP, KK, [&](int t) __attribute__((always_inline)) { return t < 2 * KK ? frag_p(t) : frag_m(0, t - 2 * KK); }, nothing);
+  {
+    const bf16_t* R0 = (const bf16_t*)g.resid0;
+#pragma unroll
+    for (int bt = 0; bt < 2; ++bt) {
+      const int fb = 2 * w + bt, fo = fb * 32 + hf * 8;
+      const mlp_u32x4 bias_v = bp_l[fb * 4 + hf], bias_w = bp_l[fb * 4 + 2 + hf];
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        const mlp_u32x4 res[2] = {*(const mlp_u32x4*)(R0 + ro[tb] + fo), *(const mlp_u32x4*)(R0 + ro[tb] + fo + 16)};
+        mlp_u32x4 xv[2];
+        mlp_finish(out[bt][tb], bias_v, bias_w, res, false, xv);          // x1 rounded to bf16, as the separate Linear stores it
+#pragma unroll
+        for (int gp = 0; gp < 2; ++gp) x_l[(32 * tb + l32) * XP + fb * 4 + 2 * gp + hf] = xv[gp];
+        if (row_ok[tb]) {                                                  // the residual of the final sum, read back below
+          *(mlp_u32x4*)(Y + ro[tb] + fo) = xv[0];
+          *(mlp_u32x4*)(Y + ro[tb] + fo + 16) = xv[1];
+        }
+      }
+    }
+  }
+  __syncthreads();
+  mlp_norm_x_tile<C, 64>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
+  __syncthreads();
+
+  // ---- the MLP's rounds, as in mlp64_kernel (stream blocks 2 ..)
+  clear_out();
+  auto finish_unit = [&](int r, int u, const mlp_f32x16 (&h)[2], mlp_u32x4* hb) __attribute__((always_inline)) {
+    const int sc = NW * r + w, tb = u >> 1, gp = u & 1;
+    hb[(32 * tb + l32) * HP + w * 4 + 2 * gp + hf] = mlp_finish_half(h[tb], gp, b1_l[sc * 4 + 2 * gp + hf], zero4[0], true);
+  };
+  {
+    mlp_f32x16 h[2];
+    slice_product(x_l, h, [&](int s) __attribute__((always_inline)) { return frag_m(0, s); });
+#pragma unroll
+    for (int u = 0; u < 4; ++u) finish_unit(0, u, h, h_l);
+    __syncthreads();
+    for (int r = 1; r < rounds; ++r) {
+      slice_product(x_l, h, [&](int s) __attribute__((always_inline)) { return frag_m(2 * r - 1, s); });
+      mlp_u32x4* hb = h_l + (r & 1) * (64 * HP);
+      pair_product(h_l + ((r - 1) & 1) * (64 * HP), HP, 2 * NW, [&](int s) __attribute__((always_inline)) { return frag_m(2 * r, s); },
+                   [&](int q) __attribute__((always_inline)) { finish_unit(r, q, h, hb); });
+      __syncthreads();
+    }
+    // the last block of the MLP: what follows it in the stream is the first QKV slice (or nothing)
+    pair_product(h_l + ((rounds - 1) & 1) * (64 * HP), HP, 2 * NW,
+                 [&](int s) __attribute__((always_inline)) { return (LNOUT == 2 && s >= KK) ? frag_q(0, s - KK) : frag_m(lastm, s < KK ? s : KK - 1); }, nothing);
+  }
+
+  // ---- Y = x1 + MLP: bias, the residual this lane stored above, two 16-byte stores per block and lane
+  mlp_u32x4 yv[2][2][2];
+#pragma unroll
+  for (int bt = 0; bt < 2; ++bt) {
+    const int fo = (2 * w + bt) * 32 + hf * 8;
+    const mlp_u32x4 b2v = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo), b2w = *(const mlp_u32x4*)((const bf16_t*)g.b2 + fo + 16);
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      const mlp_u32x4 resid[2] = {*(const mlp_u32x4*)(Y + ro[tb] + fo), *(const mlp_u32x4*)(Y + ro[tb] + fo + 16)};
+      mlp_finish(out[bt][tb], b2v, b2w, resid, false, yv[bt][tb]);
+      if (row_ok[tb]) {
+        *(mlp_u32x4*)(Y + ro[tb] + fo) = yv[bt][tb][0];
+        *(mlp_u32x4*)(Y + ro[tb] + fo + 16) = yv[bt][tb][1];
+      }
+    }
+  }
+  if constexpr (LNOUT != 0) {
+    // LayerNorm of the bf16 rows of Y (two-pass fp32 statistics, as the norm kernel computes them from the stored
+    // tensor): a lane holds 32 of its token's features per token block, its partner lane 32 more, the other waves the rest
+    float mean[2], rstd[2];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        float acc = 0.f;
+#pragma unroll
+        for (int bt = 0; bt < 2; ++bt)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            float f[8];
+            mlp_unpack8(yv[bt][tb][q], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float d = pass ? f[e] - mean[tb] : f[e]; acc += pass ? d * d : d; }
+          }
+        acc += __shfl_xor(acc, 32, 64);
+        if (hf == 0) st_l[(pass * NW + w) * 64 + 32 * tb + l32] = acc;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        float tot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) tot += st_l[(pass * NW + ww) * 64 + 32 * tb + l32];
+        if (pass == 0) mean[tb] = tot / (float)C; else rstd[tb] = rsqrtf(tot / (float)C + g.ln2_eps);
+      }
+    }
+#pragma unroll
+    for (int bt = 0; bt < 2; ++bt) {
+      const int fb = 2 * w + bt, fo = fb * 32 + hf * 8;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        float gf[8], bf[8];
+        mlp_unpack8(*(const mlp_u32x4*)((const bf16_t*)g.ln2_gamma + fo + 16 * q), gf);
+        mlp_unpack8(*(const mlp_u32x4*)((const bf16_t*)g.ln2_beta + fo + 16 * q), bf);
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+          float f[8];
+          mlp_unpack8(yv[bt][tb][q], f);
+          const float sh = -mean[tb] * rstd[tb];
+          mlp_u32x4 nv;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            nv[e] = mlp_pack2(fmaf(fmaf(f[2 * e], rstd[tb], sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[2 * e + 1], rstd[tb], sh), gf[2 * e + 1], bf[2 * e + 1]));
+          if constexpr (LNOUT == 1) {
+            if (row_ok[tb]) *(mlp_u32x4*)((bf16_t*)g.Y2 + ro2[tb] + fo + 16 * q) = nv;
+          } else {
+            n_l[(32 * tb + l32) * XP + fb * 4 + 2 * q + hf] = nv;        // (the hidden tiles are dead: two barriers ago)
+          }
+        }
+      }
+    }
+    if constexpr (LNOUT == 2) {
+      // the next block's QKV Linear on the normalised tile: wave w forms outputs 32 (w + NW j) ..+31, j < NQ
+      for (int s = tid; s < 3 * XS; s += 512) b1_l[s] = ((const mlp_u32x4*)g.bq)[s];
+      __syncthreads();
+      bf16_t* Q = (bf16_t*)g.Y2;
+#pragma unroll 1
+      for (int j = 0; j < NQ; ++j) {
+        const int sc = w + NW * j;
+        mlp_f32x16 h[2];
+        slice_product(n_l, h, [&](int s) __attribute__((always_inline)) { return frag_q(j, s); });
+        const mlp_u32x4 bias_v = b1_l[sc * 4 + hf], bias_w = b1_l[sc * 4 + 2 + hf];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+          mlp_u32x4 qv[2];
+          mlp_finish(h[tb], bias_v, bias_w, zero4, false, qv);
+          if (row_ok[tb]) {
+            bf16_t* qp = Q + 3 * ro2[tb] + sc * 32 + hf * 8;      // same row map, rows three times as long
+            asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:32\n\ts_nop 2" :: "v"(qp), "v"(qv[0]), "v"(qv[1]) : "memory");
+          }
+        }
+      }
+    }
+  }
+}
+
+static size_t mlp64p_smem(int C, int Hd) { return (size_t)64 * (C / 8 + 1) * 16 + 2 * (size_t)64 * 33 * 16 + (size_t)Hd * 2 + (size_t)C * 2 + 2 * 8 * 64 * 4; }
+
+template <int C, int LNOUT>
+static int mlp64p_launch(const MlpArgs& g, void* stream) {
+  const size_t smem = mlp64p_smem(C, g.Hd);
+  static std::atomic<size_t> allowed{0};
+  if (smem > allowed.load()) {
+    const hipError_t e = hipFuncSetAttribute((const void*)mlp64p_kernel<C, LNOUT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return (int)e;
+    allowed.store(smem);
+  }
+  mlp64p_kernel<C, LNOUT><<<dim3((unsigned)((g.M + 63) / 64)), dim3(512), smem, (hipStream_t)stream>>>(g);
+  return (int)hipGetLastError();
+}
+
 static size_t mlp64_smem(int C, int Hd) { return (size_t)64 * (C / 8 + 1) * 16 + 2 * (size_t)64 * 33 * 16 + (size_t)Hd * 2; }
 static bool mlp64_shape(int C, int Hd) { return C == 512 && Hd >= 256 && Hd % 256 == 0 && Hd <= 16384; }
 
 template <int C>
 static int mlp64_launch(const MlpArgs& g, void* stream) {
-  if (g.Wproj_p || g.Y2 || g.Wq_p) return (int)hipErrorInvalidValue;      // the wide-row kernel is the MLP alone
+  if (g.Wproj_p) {      // projection in front (the folded LayerNorm is part of that form), optionally the next block's norm / QKV
+    if (!g.norm || g.Hd < 3 * C) return (int)hipErrorInvalidValue;
+    if (g.Y2 && g.Wq_p) return mlp64p_launch<C, 2>(g, stream);
+    return g.Y2 ? mlp64p_launch<C, 1>(g, stream) : mlp64p_launch<C, 0>(g, stream);
+  }
+  if (g.Y2 || g.Wq_p) return (int)hipErrorInvalidValue;
   const size_t smem = mlp64_smem(C, g.Hd);
   static std::atomic<size_t> allowed{0};
   if (smem > allowed.load()) {
@@ -654,7 +954,11 @@ static int mlp_launch(const MlpArgs& g, void* stream) {
 }
 
 // LDS capacity: the projection variant holds three token tiles
-bool mlp_proj_supported(int C, int Hd, int dtype) { return mlp_fused_supported(C, Hd, dtype) && !mlp64_shape(C, Hd) && mlp_smem(C, Hd, true, true) <= 160 * 1024; }
+bool mlp_proj_supported(int C, int Hd, int dtype) {
+  if (!mlp_fused_supported(C, Hd, dtype)) return false;
+  if (mlp64_shape(C, Hd)) return Hd >= 3 * C && mlp64p_smem(C, Hd) <= 160 * 1024;
+  return mlp_smem(C, Hd, true, true) <= 160 * 1024;
+}
 
 bool mlp_fused_supported(int C, int Hd, int dtype) {
   if (dtype != SM_BF16) return false;

@@ -455,7 +455,7 @@ def test_linear_with_packed_weight_row_maps_and_refusals():
         sm.linear(dev(A, dtype), Wp, dev(b, dtype), act="swiglu", packed=True)
 
 
-@pytest.mark.parametrize("M,C,Hd", [(70, 128, 96), (200, 256, 1024), (6272, 384, 1536)])
+@pytest.mark.parametrize("M,C,Hd", [(70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (130, 512, 1536), (12544, 512, 2048)])
 def test_mlp_fused_with_projection(M, C, Hd):
     # x1 = A . Wp^T + bp + x0, y = x1 + MLP(LayerNorm(x1)) in one kernel; x0 read and y written through a row map
     dtype = torch.bfloat16
@@ -497,6 +497,28 @@ def test_mlp_fused_with_projection_scattered_rows():
                        norm=(dev(g, dtype), dev(be, dtype), 1e-5),
                        proj=(sm.linear_pack(dev(Wp, dtype)), dev(bp, dtype), dev(x0, dtype)), y_map=ym)
     assert_close(got, want, dtype, "projection + fused MLP through the window-reverse store", float(np.abs(want).max()) + 1.0)
+
+
+def test_wide_mlp_with_projection_scattered_rows():
+    # the same through the 64-token kernel (C = 512): tiles that straddle windows, a ragged last tile
+    dtype = torch.bfloat16
+    C, Hd, M = 512, 1536, 3 * 4 * 49
+    A = draw((M, C), 140, dtype)
+    Wp, bp = draw((C, C), 141, dtype, C ** -0.5), draw((C,), 142, dtype, 0.3)
+    x0 = draw((M, C), 143, dtype)
+    W1, b1 = draw((Hd, C), 144, dtype, C ** -0.5), draw((Hd,), 145, dtype, 0.3)
+    W2, b2 = draw((C, Hd), 146, dtype, Hd ** -0.5), draw((C,), 147, dtype, 0.3)
+    g, be = draw((C,), 148, dtype, 0.2, 1.0), draw((C,), 149, dtype, 0.2)
+    rev = V.window_reverse_chain(3, 14, 14, C, 7, 3)
+    x1_win = O.linear(to_np(A), to_np(Wp), to_np(bp))
+    x1 = V.apply_chain(x1_win.reshape(12, 49, C), rev).reshape(M, C) + to_np(x0)
+    hid = O.gelu(O.linear(O.layer_norm(x1, to_np(g), to_np(be)), to_np(W1), to_np(b1)))
+    want = x1 + O.linear(hid, to_np(W2), to_np(b2))
+    ym = sm.Map.create((3, 14, 14, C), V.window_partition_chain(3, 14, 14, C, 7, 3))
+    got = sm.mlp_fused(dev(A, dtype), sm.mlp_pack(dev(W1, dtype), dev(W2, dtype)), dev(b1, dtype), dev(b2, dtype),
+                       norm=(dev(g, dtype), dev(be, dtype), 1e-5),
+                       proj=(sm.linear_pack(dev(Wp, dtype)), dev(bp, dtype), dev(x0, dtype)), y_map=ym)
+    assert_close(got, want, dtype, "wide projection + fused MLP through the window-reverse store", float(np.abs(want).max()) + 1.0)
 
 
 @pytest.mark.parametrize("dtype", DT)

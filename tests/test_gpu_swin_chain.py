@@ -91,6 +91,18 @@ def test_small_net_with_fused_kernel_widths(mode, fuse_mlp):
         assert sm.launch_counts()[0] == 2 + per_stage[0] + 2 + per_stage[1] + 3
 
 
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("fuse_mlp", [True, "mlp"])
+def test_small_net_with_wide_rows(mode, fuse_mlp):
+    # stage widths 256 and 512: the second stage runs the 64-token kernels (projection + MLP + the next block's
+    # LayerNorm-1 and QKV when fully fused and elided; the MLP alone otherwise)
+    f, fw, l, lw = small_net_case(torch.bfloat16, mode, embed=256, heads=(8, 16), fuse_mlp=fuse_mlp)
+    assert_bf16_close(f, fw, "feature map")
+    assert_bf16_close(l, lw, "logits")
+    if mode == sm.SM_ELIDED and fuse_mlp is True:
+        assert sm.launch_counts()[0] == 2 + (3 + 2) + 2 + (3 + 2) + 3
+
+
 CFG3_SAMPLE = list(range(0, 64, 4))          # 16 of the 64 images, spread over the batch (images are independent)
 
 
