@@ -105,37 +105,38 @@ __device__ __forceinline__ void mlp_load_x_tile(mlp_u32x4* x_l, const bf16_t* X,
 template <int C, int NTOK = 32>
 __device__ __forceinline__ void mlp_norm_x_tile(mlp_u32x4* x_l, float eps, const mlp_u32x4* gam, const mlp_u32x4* bet) {
   constexpr int XS = C / 8, XP = XS + 1;
-  if (threadIdx.x >= 8 * NTOK) return;          // eight threads per token; no barrier inside
-  const int r = threadIdx.x >> 3, p = threadIdx.x & 7;
-  mlp_u32x4* xr = x_l + r * XP;
-  float sum = 0.f;
-  for (int c = p; c < XS; c += 8) {
-    float f[8];
-    mlp_unpack8(xr[c], f);
+  const int p = threadIdx.x & 7;                // eight threads per token; no barrier inside
+  for (int r = threadIdx.x >> 3; r < NTOK; r += blockDim.x >> 3) {
+    mlp_u32x4* xr = x_l + r * XP;
+    float sum = 0.f;
+    for (int c = p; c < XS; c += 8) {
+      float f[8];
+      mlp_unpack8(xr[c], f);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sum += f[e];
-  }
-  sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64); sum += __shfl_xor(sum, 4, 64);
-  const float mean = sum / (float)C;
-  float var = 0.f;
-  for (int c = p; c < XS; c += 8) {
-    float f[8];
-    mlp_unpack8(xr[c], f);
+      for (int e = 0; e < 8; ++e) sum += f[e];
+    }
+    sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64); sum += __shfl_xor(sum, 4, 64);
+    const float mean = sum / (float)C;
+    float var = 0.f;
+    for (int c = p; c < XS; c += 8) {
+      float f[8];
+      mlp_unpack8(xr[c], f);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; var += d * d; }
-  }
-  var += __shfl_xor(var, 1, 64); var += __shfl_xor(var, 2, 64); var += __shfl_xor(var, 4, 64);
-  const float rstd = rsqrtf(var / (float)C + eps), sh = -mean * rstd;
-  for (int c = p; c < XS; c += 8) {
-    float f[8], gf[8], bf[8];
-    mlp_unpack8(xr[c], f);
-    mlp_unpack8(gam[c], gf);
-    mlp_unpack8(bet[c], bf);
-    mlp_u32x4 o;
+      for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; var += d * d; }
+    }
+    var += __shfl_xor(var, 1, 64); var += __shfl_xor(var, 2, 64); var += __shfl_xor(var, 4, 64);
+    const float rstd = rsqrtf(var / (float)C + eps), sh = -mean * rstd;
+    for (int c = p; c < XS; c += 8) {
+      float f[8], gf[8], bf[8];
+      mlp_unpack8(xr[c], f);
+      mlp_unpack8(gam[c], gf);
+      mlp_unpack8(bet[c], bf);
+      mlp_u32x4 o;
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      o[e] = mlp_pack2(fmaf(fmaf(f[2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
-    xr[c] = o;
+      for (int e = 0; e < 4; ++e)
+        o[e] = mlp_pack2(fmaf(fmaf(f[2 * e], rstd, sh), gf[2 * e], bf[2 * e]), fmaf(fmaf(f[2 * e + 1], rstd, sh), gf[2 * e + 1], bf[2 * e + 1]));
+      xr[c] = o;
+    }
   }
 }
 
@@ -458,11 +459,12 @@ __global__ __launch_bounds__(64 * (C / 32), 1) void mlp_fused_kernel(MlpArgs g) 
 // through a ring of 16 fragment registers: each is refilled, right after the MFMAs that read it, with the fragment 16
 // places on.
 template <int C>
-__global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
-  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = 8, RING = 16;
+__global__ __launch_bounds__(C, (C >= 384 ? 1 : 2)) void mlp64_kernel(MlpArgs g) {
+  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = C / 64, NTHR = 64 * NW, RING = KK % 16 == 0 ? 16 : 8;
+  constexpr int UG = NW / 2;                            // steps of the second product between two quarters of the bias + GELU work
   constexpr int HP = 4 * NW + 1;                        // slots of a token's row of the round's hidden tile (+1: odd pitch)
   constexpr size_t TILE = (size_t)64 * XP * 16, HTILE = (size_t)64 * HP * 16;
-  static_assert(KK % RING == 0 && 4 * NW == KK, "the ring position of a fragment must be a compile-time constant");
+  static_assert(C % 64 == 0 && KK % RING == 0 && 4 * NW == KK && NW % 2 == 0, "the ring position of a fragment must be a compile-time constant");
   const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
   extern __shared__ __align__(16) unsigned char smem_raw[];
   mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                               // [64][XP] token tile, normalised in place
@@ -499,10 +501,10 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
     const int64_t prow = row_ok[tb] ? row : g.M - 1;
     ro[tb] = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
   }
-  mlp_load_x_tile<C, 512>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
-  if (row0 + 32 < g.M) mlp_load_x_tile<C, 512>(x_l + 32 * XP, (const bf16_t*)g.X, row0 + 32, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
-  else for (int s = tid; s < 32 * XP; s += 512) x_l[32 * XP + s] = mlp_u32x4{0u, 0u, 0u, 0u};
-  for (int s = tid; s < Hd / 8; s += 512) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
+  mlp_load_x_tile<C, NTHR>(x_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  if (row0 + 32 < g.M) mlp_load_x_tile<C, NTHR>(x_l + 32 * XP, (const bf16_t*)g.X, row0 + 32, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  else for (int s = tid; s < 32 * XP; s += NTHR) x_l[32 * XP + s] = mlp_u32x4{0u, 0u, 0u, 0u};
+  for (int s = tid; s < Hd / 8; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
   __syncthreads();
   if (g.norm) {
     mlp_norm_x_tile<C, 64>(x_l, g.norm_eps, (const mlp_u32x4*)g.norm_gamma, (const mlp_u32x4*)g.norm_beta);
@@ -545,7 +547,7 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
     hb[(32 * tb + l32) * HP + w * 4 + 2 * gp + hf] = mlp_finish_half(h[tb], gp, b1_l[sc * 4 + 2 * gp + hf], zero4[0], true);
   };
   // second product of a round: the wave's 64 features over the 256 hidden units of tile `hp` (16 steps), both token
-  // blocks.  between(q) runs after steps 4 q .. 4 q + 3.
+  // blocks.  between(q), q < 4, runs after every UG steps.
   auto second = [&](int blk, const mlp_u32x4* hp, auto between) __attribute__((always_inline)) {
     int ho = l32 * HP + hf;
     asm volatile("" : "+v"(ho));
@@ -561,9 +563,9 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
         wf[s % RING] = wload(foff(blk, s + RING));
       }
       if (i + 2 < 2 * NW) { ga[i & 1][0] = hp[ho + 2 * (i + 2)]; ga[i & 1][1] = hp[ho + 2 * (i + 2) + 32 * HP]; }
-      if ((i & 3) == 3) {
+      if (i % UG == UG - 1) {
         __builtin_amdgcn_sched_barrier(0);
-        between(i >> 2);
+        between(i / UG);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -618,10 +620,11 @@ __global__ __launch_bounds__(512, 1) void mlp64_kernel(MlpArgs g) {
 // ((step, feature block) order, the wave's two slices of lin_pack_kernel's layout), the blocks of mlp64_kernel, then
 // the wave's six QKV slices.
 template <int C, int LNOUT>
-__global__ __launch_bounds__(512, 1) void mlp64p_kernel(MlpArgs g) {
-  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = 8, RING = 16, HP = 4 * NW + 1, NQ = 3 * C / 32 / NW;
+__global__ __launch_bounds__(C, (C >= 384 ? 1 : 2)) void mlp64p_kernel(MlpArgs g) {
+  constexpr int KK = C / 16, XS = C / 8, XP = XS + 1, NW = C / 64, NTHR = 64 * NW, RING = KK % 16 == 0 ? 16 : 8, HP = 4 * NW + 1, NQ = 3 * C / 32 / NW;
+  constexpr int UG = NW / 2;                            // steps of the second product between two quarters of the bias + GELU work
   constexpr size_t TILE = (size_t)64 * XP * 16, HTILE = (size_t)64 * HP * 16;
-  static_assert(KK % RING == 0 && 4 * NW == KK && 2 * HTILE >= TILE, "block and alias assumptions");
+  static_assert(C % 64 == 0 && KK % RING == 0 && 4 * NW == KK && NW % 2 == 0 && 2 * HTILE >= TILE, "block and alias assumptions");
   const SM_KARG MlpArgs* gk = kernarg_ptr<MlpArgs>();
   extern __shared__ __align__(16) unsigned char smem_raw[];
   mlp_u32x4* x_l = (mlp_u32x4*)smem_raw;                               // [64][XP] x1, normalised in place
@@ -672,11 +675,11 @@ __global__ __launch_bounds__(512, 1) void mlp64p_kernel(MlpArgs g) {
     ro[tb] = g.y_rows.identity ? prow * g.y_rows.ld : eval_rows_k(&gk->y_rows, prow);
     if constexpr (LNOUT != 0) ro2[tb] = g.y2_rows.identity ? prow * g.y2_rows.ld : eval_rows_k(&gk->y2_rows, prow);
   }
-  mlp_load_x_tile<C, 512>(a_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
-  if (row0 + 32 < g.M) mlp_load_x_tile<C, 512>(a_l + 32 * XP, (const bf16_t*)g.X, row0 + 32, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
-  else for (int s = tid; s < 32 * XP; s += 512) a_l[32 * XP + s] = mlp_u32x4{0u, 0u, 0u, 0u};
-  for (int s = tid; s < Hd / 8; s += 512) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
-  for (int s = tid; s < XS; s += 512) bp_l[s] = ((const mlp_u32x4*)g.bproj)[s];
+  mlp_load_x_tile<C, NTHR>(a_l, (const bf16_t*)g.X, row0, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  if (row0 + 32 < g.M) mlp_load_x_tile<C, NTHR>(a_l + 32 * XP, (const bf16_t*)g.X, row0 + 32, g.M, g.x_rows.identity, g.x_rows.ld, &gk->x_rows);
+  else for (int s = tid; s < 32 * XP; s += NTHR) a_l[32 * XP + s] = mlp_u32x4{0u, 0u, 0u, 0u};
+  for (int s = tid; s < Hd / 8; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.b1)[s];
+  for (int s = tid; s < XS; s += NTHR) bp_l[s] = ((const mlp_u32x4*)g.bproj)[s];
   __syncthreads();
 
   mlp_f32x16 out[2][2];                                 // [feature block][token block]: the projection, then Y^T
@@ -707,9 +710,9 @@ __global__ __launch_bounds__(512, 1) void mlp64p_kernel(MlpArgs g) {
           wf[t % RING] = refill(t + RING);
         }
         if (i + 2 < steps) { ga[i & 1][0] = tile[to + 2 * (i + 2)]; ga[i & 1][1] = tile[to + 2 * (i + 2) + hi]; }
-        if ((i & 3) == 3) {
+        if (i % UG == UG - 1 && i / UG < 4) {
           __builtin_amdgcn_sched_barrier(0);
-          between(i >> 2);
+          between(i / UG);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -865,7 +868,7 @@ __global__ __launch_bounds__(512, 1) void mlp64p_kernel(MlpArgs g) {
     }
     if constexpr (LNOUT == 2) {
       // the next block's QKV Linear on the normalised tile: wave w forms outputs 32 (w + NW j) ..+31, j < NQ
-      for (int s = tid; s < 3 * XS; s += 512) b1_l[s] = ((const mlp_u32x4*)g.bq)[s];
+      for (int s = tid; s < 3 * XS; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.bq)[s];
       __syncthreads();
       bf16_t* Q = (bf16_t*)g.Y2;
 #pragma unroll 1
@@ -888,7 +891,10 @@ __global__ __launch_bounds__(512, 1) void mlp64p_kernel(MlpArgs g) {
   }
 }
 
-static size_t mlp64p_smem(int C, int Hd) { return (size_t)64 * (C / 8 + 1) * 16 + 2 * (size_t)64 * 33 * 16 + (size_t)Hd * 2 + (size_t)C * 2 + 2 * 8 * 64 * 4; }
+static size_t mlp64p_smem(int C, int Hd) {
+  const int NW = C / 64;
+  return (size_t)64 * (C / 8 + 1) * 16 + 2 * (size_t)64 * (4 * NW + 1) * 16 + (size_t)Hd * 2 + (size_t)C * 2 + (size_t)2 * NW * 64 * 4;
+}
 
 template <int C, int LNOUT>
 static int mlp64p_launch(const MlpArgs& g, void* stream) {
@@ -899,12 +905,23 @@ static int mlp64p_launch(const MlpArgs& g, void* stream) {
     if (e != hipSuccess) return (int)e;
     allowed.store(smem);
   }
-  mlp64p_kernel<C, LNOUT><<<dim3((unsigned)((g.M + 63) / 64)), dim3(512), smem, (hipStream_t)stream>>>(g);
+  mlp64p_kernel<C, LNOUT><<<dim3((unsigned)((g.M + 63) / 64)), dim3(C), smem, (hipStream_t)stream>>>(g);
   return (int)hipGetLastError();
 }
 
-static size_t mlp64_smem(int C, int Hd) { return (size_t)64 * (C / 8 + 1) * 16 + 2 * (size_t)64 * 33 * 16 + (size_t)Hd * 2; }
-static bool mlp64_shape(int C, int Hd) { return C == 512 && Hd >= 256 && Hd % 256 == 0 && Hd <= 16384; }
+static size_t mlp64_smem(int C, int Hd) { return (size_t)64 * (C / 8 + 1) * 16 + 2 * (size_t)64 * (4 * (C / 64) + 1) * 16 + (size_t)Hd * 2; }
+// shapes the 64-token kernels take: whole rounds of C / 2 hidden units
+static bool mlp64_shape(int C, int Hd) { return (C == 256 || C == 384 || C == 512) && Hd >= C / 2 && Hd % (C / 2) == 0 && Hd <= 16384; }
+// ... and where they are used: always at C = 512 (the 32-token kernels stop at 384); at 256 and 384 on grids of at least
+// one workgroup of 64 tokens per CU (on smaller ones the 32-token tile fills more CUs); not at 128, where the 32-token
+// kernel is faster (measured at 32768 tokens, MLP alone: C = 128 21 us against 32; 256: 66 against 51; 384: 147 against 122)
+static bool mlp64_use(const MlpArgs& g) {
+  if (!mlp64_shape(g.C, g.Hd)) return false;
+  if (g.C == 512) return true;
+  if (g.C == 128 || g.M < 64 * 256) return false;
+  if (g.Wproj_p) return g.norm && g.Hd >= 3 * g.C && mlp64p_smem(g.C, g.Hd) <= 160 * 1024;
+  return !g.Y2 && !g.Wq_p && mlp64_smem(g.C, g.Hd) <= 160 * 1024;
+}
 
 template <int C>
 static int mlp64_launch(const MlpArgs& g, void* stream) {
@@ -921,7 +938,7 @@ static int mlp64_launch(const MlpArgs& g, void* stream) {
     if (e != hipSuccess) return (int)e;
     allowed.store(smem);
   }
-  mlp64_kernel<C><<<dim3((unsigned)((g.M + 63) / 64)), dim3(512), smem, (hipStream_t)stream>>>(g);
+  mlp64_kernel<C><<<dim3((unsigned)((g.M + 63) / 64)), dim3(C), smem, (hipStream_t)stream>>>(g);
   return (int)hipGetLastError();
 }
 
@@ -956,13 +973,13 @@ static int mlp_launch(const MlpArgs& g, void* stream) {
 // LDS capacity: the projection variant holds three token tiles
 bool mlp_proj_supported(int C, int Hd, int dtype) {
   if (!mlp_fused_supported(C, Hd, dtype)) return false;
-  if (mlp64_shape(C, Hd)) return Hd >= 3 * C && mlp64p_smem(C, Hd) <= 160 * 1024;
+  if (C == 512) return mlp64_shape(C, Hd) && Hd >= 3 * C && mlp64p_smem(C, Hd) <= 160 * 1024;
   return mlp_smem(C, Hd, true, true) <= 160 * 1024;
 }
 
 bool mlp_fused_supported(int C, int Hd, int dtype) {
   if (dtype != SM_BF16) return false;
-  if (mlp64_shape(C, Hd)) return mlp64_smem(C, Hd) <= 160 * 1024;      // wide rows: the 64-token kernel, the MLP alone
+  if (C == 512) return mlp64_shape(C, Hd) && mlp64_smem(C, Hd) <= 160 * 1024;      // wide rows: the 64-token kernels only
   return (C == 128 || C == 256 || C == 384) && Hd >= 32 && Hd % 32 == 0 && Hd <= 16384;
 }
 
@@ -973,11 +990,17 @@ int launch_mlp_pack(const void* W1, const void* W2, int C, int Hd, void* packed,
 }
 
 int launch_mlp_fused(const MlpArgs& g, void* stream) {
+  if (mlp64_use(g)) {
+    switch (g.C) {
+      case 256: return mlp64_launch<256>(g, stream);
+      case 384: return mlp64_launch<384>(g, stream);
+      case 512: return mlp64_launch<512>(g, stream);
+    }
+  }
   switch (g.C) {
     case 128: return mlp_launch<128>(g, stream);
     case 256: return mlp_launch<256>(g, stream);
     case 384: return mlp_launch<384>(g, stream);
-    case 512: return mlp64_shape(g.C, g.Hd) ? mlp64_launch<512>(g, stream) : (int)hipErrorInvalidValue;
   }
   return (int)hipErrorInvalidValue;
 }

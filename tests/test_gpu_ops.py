@@ -336,7 +336,8 @@ def test_empty_inputs_are_no_ops():
 
 
 @pytest.mark.parametrize("M,C,Hd", [(32, 128, 512), (70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (45, 384, 160),
-                                    (64, 512, 256), (130, 512, 1024), (12544, 512, 2048), (33, 512, 512)])      # C = 512: the 64-token kernel
+                                    (64, 512, 256), (130, 512, 1024), (12544, 512, 2048), (33, 512, 512),      # C = 512: the 64-token kernel
+                                    (16400, 256, 1024), (16384, 384, 1536)])     # large grids: 64-token tiles from C = 256 up
 @pytest.mark.parametrize("with_res,with_norm", [(True, False), (False, False), (True, True)])
 def test_mlp_fused(M, C, Hd, with_res, with_norm):
     # (LayerNorm +) FC1 + GELU + FC2 (+ residual) in one kernel against the oracle's operators; row counts that end
@@ -455,7 +456,8 @@ def test_linear_with_packed_weight_row_maps_and_refusals():
         sm.linear(dev(A, dtype), Wp, dev(b, dtype), act="swiglu", packed=True)
 
 
-@pytest.mark.parametrize("M,C,Hd", [(70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (130, 512, 1536), (12544, 512, 2048)])
+@pytest.mark.parametrize("M,C,Hd", [(70, 128, 96), (200, 256, 1024), (6272, 384, 1536), (130, 512, 1536), (12544, 512, 2048),
+                                    (16400, 256, 1024), (16387, 384, 1536)])     # large grids: 64-token tiles
 def test_mlp_fused_with_projection(M, C, Hd):
     # x1 = A . Wp^T + bp + x0, y = x1 + MLP(LayerNorm(x1)) in one kernel; x0 read and y written through a row map
     dtype = torch.bfloat16
