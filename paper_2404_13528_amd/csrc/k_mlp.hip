@@ -719,7 +719,8 @@ __global__ __launch_bounds__(C, (C >= 384 ? 1 : 2)) void mlp64p_kernel(MlpArgs g
     }
   };
   // h[tb] = W(slice of block blk) x tile(token block tb): 32 hidden / output features of a slice for the 64 tokens
-  auto slice_product = [&](const mlp_u32x4* tile, mlp_f32x16 (&h)[2], auto refill) __attribute__((always_inline)) {
+  // between(q), q < 4, after every KK / 4 steps
+  auto slice_product = [&](const mlp_u32x4* tile, mlp_f32x16 (&h)[2], auto refill, auto between) __attribute__((always_inline)) {
     int xo = l32 * XP + hf;
     asm volatile("" : "+v"(xo));
 #pragma unroll
@@ -732,13 +733,11 @@ __global__ __launch_bounds__(C, (C >= 384 ? 1 : 2)) void mlp64p_kernel(MlpArgs g
       h[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, __builtin_bit_cast(mlp_bf16x8, fa[kk & 1][1]), h[1], 0, 0, 0);
       wf[kk % RING] = refill(kk + RING);
       if (kk + 2 < KK) { fa[kk & 1][0] = tile[xo + 2 * (kk + 2)]; fa[kk & 1][1] = tile[xo + 2 * (kk + 2) + 32 * XP]; }
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      if (kk % (KK / 4) == KK / 4 - 1) {
+        __builtin_amdgcn_sched_barrier(0);
+        between(kk / (KK / 4));
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   };
   auto nothing = [&](int) __attribute__((always_inline)) {};
@@ -779,12 +778,12 @@ __global__ __launch_bounds__(C, (C >= 384 ? 1 : 2)) void mlp64p_kernel(MlpArgs g
   };
   {
     mlp_f32x16 h[2];
-    slice_product(x_l, h, [&](int s) __attribute__((always_inline)) { return frag_m(0, s); });
+    slice_product(x_l, h, [&](int s) __attribute__((always_inline)) { return frag_m(0, s); }, nothing);
 #pragma unroll
     for (int u = 0; u < 4; ++u) finish_unit(0, u, h, h_l);
     __syncthreads();
     for (int r = 1; r < rounds; ++r) {
-      slice_product(x_l, h, [&](int s) __attribute__((always_inline)) { return frag_m(2 * r - 1, s); });
+      slice_product(x_l, h, [&](int s) __attribute__((always_inline)) { return frag_m(2 * r - 1, s); }, nothing);
       mlp_u32x4* hb = h_l + (r & 1) * (64 * HP);
       pair_product(h_l + ((r - 1) & 1) * (64 * HP), HP, 2 * NW, [&](int s) __attribute__((always_inline)) { return frag_m(2 * r, s); },
                    [&](int q) __attribute__((always_inline)) { finish_unit(r, q, h, hb); });
@@ -871,20 +870,29 @@ __global__ __launch_bounds__(C, (C >= 384 ? 1 : 2)) void mlp64p_kernel(MlpArgs g
       for (int s = tid; s < 3 * XS; s += NTHR) b1_l[s] = ((const mlp_u32x4*)g.bq)[s];
       __syncthreads();
       bf16_t* Q = (bf16_t*)g.Y2;
+      // bias and store of slice j (a quarter at a time: token block u / 2, half u % 2 of its 32 outputs) are issued
+      // between the quarters of slice j + 1's product
+      auto emit = [&](int j, int u, const mlp_f32x16 (&h)[2]) __attribute__((always_inline)) {
+        const int sc = w + NW * j, tb = u >> 1, gp = u & 1;
+        const mlp_u32x4 qv = mlp_finish_half(h[tb], gp, b1_l[sc * 4 + 2 * gp + hf], zero4[0], false);
+        if (row_ok[tb]) {
+          bf16_t* qp = Q + 3 * ro2[tb] + sc * 32 + hf * 8 + 16 * gp;      // same row map, rows three times as long
+          asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" :: "v"(qp), "v"(qv) : "memory");
+        }
+      };
+      static_assert(NQ % 2 == 0, "slices are taken two at a time");
+      mlp_f32x16 ha[2], hb2[2];
+      slice_product(n_l, ha, [&](int s) __attribute__((always_inline)) { return frag_q(0, s); }, nothing);
 #pragma unroll 1
-      for (int j = 0; j < NQ; ++j) {
-        const int sc = w + NW * j;
-        mlp_f32x16 h[2];
-        slice_product(n_l, h, [&](int s) __attribute__((always_inline)) { return frag_q(j, s); });
-        const mlp_u32x4 bias_v = b1_l[sc * 4 + hf], bias_w = b1_l[sc * 4 + 2 + hf];
+      for (int j = 0; j < NQ; j += 2) {
+        slice_product(n_l, hb2, [&](int s) __attribute__((always_inline)) { return frag_q(j + 1, s); },
+                      [&](int u) __attribute__((always_inline)) { emit(j, u, ha); });
+        if (j + 2 < NQ) {
+          slice_product(n_l, ha, [&](int s) __attribute__((always_inline)) { return frag_q(j + 2, s); },
+                        [&](int u) __attribute__((always_inline)) { emit(j + 1, u, hb2); });
+        } else {
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-          mlp_u32x4 qv[2];
-          mlp_finish(h[tb], bias_v, bias_w, zero4, false, qv);
-          if (row_ok[tb]) {
-            bf16_t* qp = Q + 3 * ro2[tb] + sc * 32 + hf * 8;      // same row map, rows three times as long
-            asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:32\n\ts_nop 2" :: "v"(qp), "v"(qv[0]), "v"(qv[1]) : "memory");
-          }
+          for (int u = 0; u < 4; ++u) emit(j + 1, u, hb2);
         }
       }
     }
