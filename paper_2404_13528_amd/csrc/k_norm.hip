@@ -157,12 +157,87 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(NormArgs a) {
   }
 }
 
+// Rows of at most LPR 16-byte chunks (LPR = 16 or 32 lanes per row): 64 / LPR rows side by side in a wave, RPL such groups
+// per wave one after the other; the statistics are sums over the LPR lanes of a row (DPP row operations, and one
+// cross-row-of-16 exchange when LPR = 32).  One segment per row; the same row maps as norm_rows_kernel.
+__device__ __forceinline__ float norm_sum16(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));      // xor 1
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));      // xor 2
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));     // mirror within 8
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));     // mirror within 16
+  return v;
+}
+template <typename T, int LPR, int RPL>
+__global__ __launch_bounds__(256) void norm_short_rows_kernel(NormArgs a) {
+  constexpr int VEC = Elem<T>::VEC, RPP = 64 / LPR;      // rows per pass of the wave
+  typedef typename Vec16<T>::type V;
+  const SM_KARG NormArgs* ak = kernarg_ptr<NormArgs>();
+  const int lane = threadIdx.x & 63, sub = lane / LPR, ch = lane % LPR;
+  const int64_t row0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * (RPP * RPL);
+  if (row0 >= a.rows) return;
+  const int nchunk = a.C / VEC;
+  const bool on = ch < nchunk;
+  const T* x = (const T*)a.x;
+  int64_t in_off[RPL], out_off[RPL];
+  float v[RPL][VEC];
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    const int64_t row = min(row0 + r * RPP + sub, a.rows - 1);      // a clamped duplicate row is computed and not stored
+    in_off[r] = a.load.identity ? row * a.load.ld : eval_rows_k(&ak->load, row);
+    out_off[r] = a.store.identity ? row * a.store.ld : eval_rows_k(&ak->store, row);
+  }
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    if (on) { V raw = *(const V*)(x + in_off[r] + (int64_t)ch * VEC); unpack<T>(raw, v[r]); }
+    else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[r][e] = 0.f;
+    }
+  }
+  const T* g = (const T*)a.gamma;
+  const T* bta = (const T*)a.beta;
+  float gg[VEC], bb[VEC];
+  { V graw = *(const V*)(g + min(ch, nchunk - 1) * VEC); unpack<T>(graw, gg); }
+  if (!a.rms && bta) { V braw = *(const V*)(bta + min(ch, nchunk - 1) * VEC); unpack<T>(braw, bb); }
+  else {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) bb[e] = 0.f;
+  }
+  T* y = (T*)a.y;
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s += v[r][e];
+    s = norm_sum16(s);
+    if (LPR == 32) s += __shfl_xor(s, 16, 64);
+    const float mean = a.rms ? 0.f : s / (float)a.C;
+    float ss = 0.f;
+    if (on) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { const float d = v[r][e] - mean; ss += d * d; }
+    }
+    ss = norm_sum16(ss);
+    if (LPR == 32) ss += __shfl_xor(ss, 16, 64);
+    const float rstd = rsqrtf(ss / (float)a.C + a.eps);
+    if (on && row0 + r * RPP + sub < a.rows) {
+      float o[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o[e] = (v[r][e] - mean) * rstd * gg[e] + bb[e];
+      *(V*)(y + out_off[r] + (int64_t)ch * VEC) = pack<T>(o);
+    }
+  }
+}
+
 template <typename T>
 static int norm_dispatch(const NormArgs& a, hipStream_t s) {
   constexpr int VEC = Elem<T>::VEC;
   const int nchunk = a.C / VEC;
   dim3 block(256);
-  if (nchunk <= 64) norm_rows_kernel<T, 1, 2><<<dim3((unsigned)((a.rows + 7) / 8)), block, 0, s>>>(a);
+  // short rows (one segment): several rows side by side in a wave instead of lanes without a chunk
+  if (a.nseg == 1 && nchunk <= 16) norm_short_rows_kernel<T, 16, 2><<<dim3((unsigned)((a.rows + 31) / 32)), block, 0, s>>>(a);
+  else if (a.nseg == 1 && nchunk <= 32) norm_short_rows_kernel<T, 32, 2><<<dim3((unsigned)((a.rows + 15) / 16)), block, 0, s>>>(a);
+  else if (nchunk <= 64) norm_rows_kernel<T, 1, 2><<<dim3((unsigned)((a.rows + 7) / 8)), block, 0, s>>>(a);
   else if (nchunk <= 128) norm_rows_kernel<T, 2, 1><<<dim3((unsigned)((a.rows + 3) / 4)), block, 0, s>>>(a);
   else if (nchunk <= 256) norm_rows_kernel<T, 4, 1><<<dim3((unsigned)((a.rows + 3) / 4)), block, 0, s>>>(a);
   else norm_rows_kernel<T, 8, 1><<<dim3((unsigned)((a.rows + 3) / 4)), block, 0, s>>>(a);

@@ -19,7 +19,7 @@ def draw(shape, seed, dtype, std=1.0, mean=0.0):
 
 
 @pytest.mark.parametrize("dtype", DT)
-@pytest.mark.parametrize("rows,C", [(37, 96), (200, 384), (5, 1024), (3, 4096)])
+@pytest.mark.parametrize("rows,C", [(37, 96), (200, 384), (5, 1024), (3, 4096), (1003, 128), (45, 64), (70, 256), (9, 32)])
 def test_layernorm_and_rmsnorm(dtype, rows, C):
     if dtype == torch.float32 and C > 2048:
         pytest.skip("fp32 rows are limited to 2048 columns")
