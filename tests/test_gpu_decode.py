@@ -54,6 +54,7 @@ def run_case(B, E, h, L, F, rot, mode, seed=0, std=0.02, pitch=None):
     (8, 512, 2, 300, 1024, 64),     # d = 256
     (5, 256, 4, 0, 320, 0),         # empty cache, no rotary features
     (32, 128, 2, 77, 192, 32),      # the largest batch
+    (3, 2560, 20, 70, 2560, 32),    # rows longer than 2048: the first kernel's long-row form
 ])
 def test_decode_step_matches_the_oracle(B, E, h, L, F, rot, mode):
     run_case(B, E, h, L, F, rot, mode, seed=B + L, std=0.1)
