@@ -1,0 +1,47 @@
+"""Cross-shaped window self-attention of the CSwin Transformer (one of the transformer models whose Reshape /
+Transpose count the paper reports, Table 1, and evaluates, Table 7).  TEST INFRASTRUCTURE ONLY: plain numpy float64,
+every layout operator materialised.
+
+Readings (the paper gives no definition of the operator; this is the public CSwin one, without its locally-enhanced
+positional encoding, a depth-wise convolution added to the attention output, which is outside this operator): the input
+is what the query-key-value Linear leaves, [B, H*W, 3C] with columns [q | k | v], each of C = heads * d features; the
+first half of the channels (heads [0, heads/2)) attends inside vertical stripes of H x sw grid positions, the second
+half inside horizontal stripes of sw x W; softmax scale d^-1/2, no bias and no mask; the two halves are Concat-ed
+along the channel axis into [B, H*W, C].
+"""
+import numpy as np
+from . import views as V
+from . import ops as O
+
+
+def stripe_shape(H, W, sw, branch):
+    """(rows, columns) of one stripe: branch 0 vertical, branch 1 horizontal."""
+    return (H, sw) if branch == 0 else (sw, W)
+
+
+def branch_attention(q, k, v, B, H, W, heads_b, Hs, Ws):
+    """q, k, v [B, H*W, Cb] (one half of the channels) -> [B, H*W, Cb]: partition into Hs x Ws stripes, split the heads,
+    attend inside each stripe, merge heads and stripes again."""
+    Cb = q.shape[-1]
+    d = Cb // heads_b
+    nwin, S = B * (H // Hs) * (W // Ws), Hs * Ws
+    part = []
+    for t in (q, k, v):
+        t = V.apply_chain(t, V.stripe_partition_chain(B, H, W, Cb, Hs, Ws))
+        part.append(V.apply_chain(t, V.head_split_chain(nwin, S, heads_b, d)))
+    o, _ = O.attention(part[0], part[1], part[2], d ** -0.5)
+    o = V.apply_chain(o, V.head_merge_chain(nwin, S, heads_b, d))
+    return V.apply_chain(o, V.stripe_merge_chain(B, H, W, Cb, Hs, Ws))
+
+
+def cross_window_attention(qkv, B, H, W, C, heads, sw):
+    """qkv [B, H*W, 3C] -> [B, H*W, C]."""
+    t = V.reshape(qkv, (B, H * W, 3, C))
+    q, k, v = [V.reshape(V.slice_(t, 2, i, i + 1), (B, H * W, C)) for i in range(3)]
+    Cb = C // 2
+    halves = []
+    for branch in range(2):
+        Hs, Ws = stripe_shape(H, W, sw, branch)
+        sl = [V.slice_(x, 2, branch * Cb, (branch + 1) * Cb) for x in (q, k, v)]
+        halves.append(branch_attention(sl[0], sl[1], sl[2], B, H, W, heads // 2, Hs, Ws))
+    return V.concat(halves, 2)

@@ -131,3 +131,19 @@ def nchw_to_tokens_chain(B, C, H, W):
 
 def tokens_to_nchw_chain(B, C, H, W):
     return [("permute", (0, 2, 1)), ("reshape", (B, C, H, W))]
+
+
+def stripe_partition_chain(B, H, W, C, Hs, Ws):
+    """Tokens [B, H*W, C] -> stripes [B*(H/Hs)*(W/Ws), Hs*Ws, C] of Hs x Ws grid positions, as the public CSwin model
+    writes it: channels first, the grid split on both axes, the two stripe axes moved next to each other."""
+    return [("permute", (0, 2, 1)),
+            ("reshape", (B, C, H // Hs, Hs, W // Ws, Ws)),
+            ("permute", (0, 2, 4, 3, 5, 1)),
+            ("reshape", (B * (H // Hs) * (W // Ws), Hs * Ws, C))]
+
+
+def stripe_merge_chain(B, H, W, C, Hs, Ws):
+    """Stripes [B*(H/Hs)*(W/Ws), Hs*Ws, C] -> tokens [B, H*W, C]."""
+    return [("reshape", (B, H // Hs, W // Ws, Hs, Ws, C)),
+            ("permute", (0, 1, 3, 2, 4, 5)),
+            ("reshape", (B, H * W, C))]

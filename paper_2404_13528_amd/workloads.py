@@ -120,6 +120,13 @@ def neox_decode_case(B, E, h, L, F, seed=0, bf16=True, std=STD, in_std=1.0):
     return x, p, k_cache, v_cache
 
 
+def cswin_qkv_case(B, H, W, C, seed=0, bf16=True, in_std=1.0):
+    """Input of the cross-shaped window attention: the fused query-key-value projection of an image's tokens,
+    [B, H*W, 3C], O(1) entries like any projected activation."""
+    dr = Draw(seed, bf16)
+    return dr.normal(B, H * W, 3 * C, std=in_std)
+
+
 def fanout_case(D1, D2, D3, Kin, Cout, seed=0, bf16=True):
     """Operands of the Fig. 4 graph: activations N(0,1), weights scaled so that every output is O(1)."""
     dr = Draw(seed, bf16)

@@ -1,0 +1,77 @@
+"""Pins of oracle/cswin.py (cross-shaped window attention) against things other than itself: a token-by-token
+assembly from the definition of a stripe with the library's scaled-dot-product attention, the special case in which a
+stripe is the whole image, and locality invariants."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import cswin as CS
+from oracle import views as V
+from paper_2404_13528_amd import workloads as Wl
+from util import to_np
+
+
+def by_definition(qkv, B, H, W, C, heads, sw, swap=False):
+    """For every image, branch, stripe and head: collect the stripe's tokens from the definition (vertical stripe j =
+    the grid columns [j sw, (j + 1) sw), horizontal stripe j = the grid rows [j sw, (j + 1) sw)), attend among them
+    with the library routine, and put every token's result back at its own place."""
+    d = C // heads
+    t = torch.from_numpy(qkv)
+    out = torch.zeros(B, H * W, C, dtype=torch.float64)
+    for b in range(B):
+        for hh in range(heads):
+            vertical = (hh < heads // 2) != swap
+            n_str = (W if vertical else H) // sw
+            for j in range(n_str):
+                toks = [y * W + x for y in range(H) for x in range(W) if (x if vertical else y) // sw == j]
+                q = t[b, toks, 0 * C + hh * d:0 * C + (hh + 1) * d]
+                k = t[b, toks, 1 * C + hh * d:1 * C + (hh + 1) * d]
+                v = t[b, toks, 2 * C + hh * d:2 * C + (hh + 1) * d]
+                o = F.scaled_dot_product_attention(q[None], k[None], v[None])[0]
+                out[b, toks, hh * d:(hh + 1) * d] = o
+    return out.numpy()
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,sw", [(2, 4, 4, 16, 2, 1), (1, 6, 6, 32, 4, 2), (2, 6, 4, 24, 2, 2), (1, 4, 8, 16, 4, 4)])
+def test_matches_the_definition_token_by_token(B, H, W, C, heads, sw):
+    qkv = to_np(Wl.cswin_qkv_case(B, H, W, C, seed=11, bf16=False))
+    got = CS.cross_window_attention(qkv, B, H, W, C, heads, sw)
+    assert np.abs(got - by_definition(qkv, B, H, W, C, heads, sw)).max() < 1e-12
+    # the two halves of the heads mixed up (horizontal stripes first) is a different function
+    assert np.abs(got - by_definition(qkv, B, H, W, C, heads, sw, swap=True)).max() > 1e-3
+
+
+def test_stripe_as_wide_as_the_image_is_global_attention():
+    B, H, W, C, heads = 2, 4, 4, 32, 4
+    d = C // heads
+    qkv = to_np(Wl.cswin_qkv_case(B, H, W, C, seed=12, bf16=False))
+    got = CS.cross_window_attention(qkv, B, H, W, C, heads, 4)
+    t = torch.from_numpy(qkv).view(B, H * W, 3, heads, d).permute(2, 0, 3, 1, 4)
+    want = F.scaled_dot_product_attention(t[0], t[1], t[2]).transpose(1, 2).reshape(B, H * W, C).numpy()
+    assert np.abs(got - want).max() < 1e-12
+
+
+def test_a_token_only_reaches_its_own_stripes():
+    B, H, W, C, heads, sw = 1, 6, 6, 16, 2, 2
+    Cb = C // 2
+    qkv = to_np(Wl.cswin_qkv_case(B, H, W, C, seed=13, bf16=False))
+    base = CS.cross_window_attention(qkv, B, H, W, C, heads, sw)
+    y0, x0 = 3, 4
+    moved = qkv.copy()
+    moved[0, y0 * W + x0, C:] += 1.0                      # its key and value (not its query)
+    diff = np.abs(CS.cross_window_attention(moved, B, H, W, C, heads, sw) - base).reshape(H, W, C)
+    col = np.zeros((H, W), bool); col[:, (x0 // sw) * sw:(x0 // sw + 1) * sw] = True
+    row = np.zeros((H, W), bool); row[(y0 // sw) * sw:(y0 // sw + 1) * sw, :] = True
+    assert diff[..., :Cb][~col].max() == 0 and diff[..., :Cb][col].min() > 0         # vertical half: its column stripe
+    assert diff[..., Cb:][~row].max() == 0 and diff[..., Cb:][row].min() > 0         # horizontal half: its row stripe
+
+
+def test_partition_and_merge_are_inverse_and_keep_grid_order():
+    B, H, W, C, Hs, Ws = 2, 6, 4, 3, 6, 2
+    x = np.arange(B * H * W * C, dtype=np.float64).reshape(B, H * W, C)
+    s = V.apply_chain(x, V.stripe_partition_chain(B, H, W, C, Hs, Ws))
+    assert s.shape == (B * (W // Ws), H * Ws, C)
+    assert np.array_equal(V.apply_chain(s, V.stripe_merge_chain(B, H, W, C, Hs, Ws)), x)
+    # stripe 1 of image 0 starts at grid column 2; its tokens run row-major inside the stripe
+    assert np.array_equal(s[1, :4, 0] / C, [2, 3, W + 2, W + 3])
