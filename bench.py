@@ -76,6 +76,9 @@ def kernel_model(label):
     m = re.match(r"concat_bf16\[(\d+),(\d+),(\d+)\]", label)
     if m:
         return 2 * int(m.group(1)) * int(m.group(2)) * int(m.group(3)) * e, 0.0
+    m = re.match(r"concat_bf16\[(\d+),(\d+)\]", label)
+    if m:      # Concat along the channels: [rows, C] written, its two halves read
+        return 2 * int(m.group(1)) * int(m.group(2)) * e, 0.0
     m = re.match(r"(?:ln\+|rms\+)?p?gemm_\w+\[(\d+),(\d+),(\d+)\](.*)", label)
     if m:
         M, N, K = int(m.group(1)), int(m.group(2)), int(m.group(3))
@@ -274,6 +277,14 @@ def build_config(k, sm, torch, Wl):
         return ("extra: Pythia-1B-shaped layer at a decode step, bf16, B=8 sequences, 1 new token each, hidden 2048, 8 heads x 256, "
                 "64 rotary features, 2047 cached tokens, GELU MLP 8192, parallel residual", "tokens/s", B,
                 {n: (lambda s_=s_: s_(xd, kbuf, vbuf, L)) for n, s_ in st.items()}, None, "bf16")
+    if k == 9:     # CSwin (Tables 1, 7): cross-shaped window attention at the shape of CSwin-T's third stage
+        B, H, W, C, h, sw = 64, 14, 14, 256, 8, 7
+        qkv = Wl.cswin_qkv_case(B, H, W, C).to(bf).cuda()
+        y = torch.empty(B, H * W, C, dtype=bf, device="cuda")
+        ops = {n: sm.CswinAttention(B, H, W, C, h, sw, m) for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
+        return ("extra: CSwin-style cross-shaped window attention, bf16, B=64, 14x14 tokens, 256 channels, 8 heads x 32 "
+                "(4 in vertical, 4 in horizontal stripes of width 7), from the fused q|k|v projection to the merged output",
+                "images/s", B, {n: (lambda o=o: o(qkv, out=y)) for n, o in ops.items()}, None, "bf16")
     raise ValueError(k)
 
 
@@ -334,7 +345,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json (6: ViT block, 7: Fig. 4 graph, 8: decode step); 0 = all")
+    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json (6: ViT block, 7: Fig. 4 graph, 8: decode step, 9: CSwin attention); 0 = all")
     ap.add_argument("--variants", default="", help="comma-separated subset of the variants (elided, explicit, elided_per_op, explicit_per_op)")
     ap.add_argument("--kernels", action="store_true", help="include every variant's per-kernel table in the JSON line (long)")
     ap.add_argument("--no-autotune", action="store_true",
@@ -367,7 +378,7 @@ def main():
 
     traffic = measured_traffic()
     HEAD = 3
-    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6, 7, 8]
+    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6, 7, 8, 9]
     want = [v for v in a.variants.split(",") if v]
     configs, oracle_sample, calib = {}, None, None
     for k in which:

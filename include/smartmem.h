@@ -294,14 +294,22 @@ int sm_mlp_fused(const sm_mlp_desc*, const void* X, const void* packed, const vo
  * kind: SM_ATT_FULL, SM_ATT_CAUSAL (key j visible to query i iff j <= i), or
  * SM_ATT_WINDOW (Swin: n = window*window tokens, rel-pos bias gathered from
  * rpb_table [(2w-1)^2, heads], shifted-window mask computed from the window's
- * position on the H x W grid when shift > 0; masked logits get -100). */
-enum { SM_ATT_FULL = 0, SM_ATT_CAUSAL = 1, SM_ATT_WINDOW = 2 };
+ * position on the H x W grid when shift > 0; masked logits get -100), or
+ * SM_ATT_STRIPE (cross-shaped windows, CSwin: a batch entry is one stripe of an
+ * image's token grid, whose n tokens lie in n / run runs of `run` adjacent
+ * tokens; bf16, d <= 32, nq == nk): batch entry b is stripe b % stripes of image
+ * b / stripes and starts (b / stripes) * stride[0] + (b % stripes) * stripe[0]
+ * elements into the operand; its token s lies (s / run) * stripe[1] +
+ * (s % run) * stride[2] elements further on. */
+enum { SM_ATT_FULL = 0, SM_ATT_CAUSAL = 1, SM_ATT_WINDOW = 2, SM_ATT_STRIPE = 3 };
 typedef struct {
   int32_t kind, dtype;
   int32_t nb, heads, nq, nk, d;
   float scale;
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];   /* batch, head, token */
   int32_t window, shift, H, W;      /* SM_ATT_WINDOW only; batch index = (image, wy, wx) row-major */
+  int32_t stripes, run;             /* SM_ATT_STRIPE only: stripes per image, adjacent tokens per run */
+  int64_t q_stripe[2], k_stripe[2], v_stripe[2], o_stripe[2];   /* SM_ATT_STRIPE only: element strides (stripe, run) */
 } sm_attention_desc;
 int sm_attention(const sm_attention_desc*, const void* q, const void* k, const void* v, void* o,
                  const void* rpb_table, void* stream);
@@ -410,6 +418,30 @@ int sm_decode_pack(const void* W, int N, int K, int dtype, void* packed, void* s
 size_t sm_decode_step_workspace_bytes(const sm_decode_cfg*, int mode);
 int sm_decode_step(const sm_decode_cfg*, const sm_decode_weights*, const void* x, void* k_cache, void* v_cache,
                    void* y, void* k_out, void* v_out, void* ws, size_t ws_bytes, int mode, void* stream);
+
+/* Cross-shaped window self-attention of the CSwin Transformer (Table 1 counts its
+ * Reshape / Transpose operators, Table 7 evaluates it): the stripe partition,
+ * head split, head merge and stripe merge around the two attentions are Reshape /
+ * Transpose / Slice runs that the planner turns into the attention kernel's load
+ * and store addresses (Sec. 3.2.1).
+ * qkv [B, H*W, 3C] (device; columns [q | k | v], each heads x d with d = C / heads)
+ * as the fused Linear leaves it; out [B, H*W, C] (device).  Heads [0, heads/2)
+ * attend inside vertical stripes (H x sw grid positions), the others inside
+ * horizontal stripes (sw x W); scale d^-1/2; the locally-enhanced positional
+ * encoding (a depth-wise convolution) is not part of this operator.
+ *   SM_ELIDED: two attention kernels that read qkv in place and store into their
+ *     half of out's channels (the Concat of the halves has two inputs and is not
+ *     planned: it is applied as the store address, by hand).
+ *   SM_EXPLICIT: per half one copy kernel for the Slice + partition + head split
+ *     of q, k, v, the attention on contiguous operands, one copy for head merge +
+ *     stripe merge, then one Concat kernel: 5 copies around the same 2 kernels.
+ * Limits: bf16; heads even; d a multiple of 8, at most 32; H and W multiples of
+ * sw; a stripe of at most 65536 tokens.  ws: device workspace of at least
+ * sm_cswin_attention_workspace_bytes(cfg, mode) bytes, owned by the caller.
+ * Nothing is allocated; SM_ERR_* with a message otherwise. */
+typedef struct { int32_t dtype, B, H, W, C, heads, sw; } sm_cswin_cfg;
+size_t sm_cswin_attention_workspace_bytes(const sm_cswin_cfg*, int mode);
+int sm_cswin_attention(const sm_cswin_cfg*, const void* qkv, void* out, void* ws, size_t ws_bytes, int mode, void* stream);
 
 /* A whole producer-consumer chain (Sec. 3.2: elimination and fusion alternate
  * over rounds, so removed layout operators leave compute operators adjacent):

@@ -26,7 +26,7 @@ OP_KIND = {"CONV": 0, "MATMUL": 1, "LAYERNORM": 2, "SOFTMAX": 3, "GROUPNORM": 4,
            "GATHER": 48, "SLICE": 49, "ROLL": 50, "CONCAT": 51}
 VIEW_KIND = {"reshape": 0, "permute": 1, "roll": 2, "slice": 3}
 ACT = {"none": 0, "gelu": 1, "swiglu": 2, "geglu": 3}
-ATT = {"full": 0, "causal": 1, "window": 2}
+ATT = {"full": 0, "causal": 1, "window": 2, "stripe": 3}
 
 
 class TensorDesc(C.Structure):
@@ -55,7 +55,14 @@ class AttentionDesc(C.Structure):
                 ("nq", C.c_int32), ("nk", C.c_int32), ("d", C.c_int32), ("scale", C.c_float),
                 ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3), ("v_stride", C.c_int64 * 3),
                 ("o_stride", C.c_int64 * 3),
-                ("window", C.c_int32), ("shift", C.c_int32), ("H", C.c_int32), ("W", C.c_int32)]
+                ("window", C.c_int32), ("shift", C.c_int32), ("H", C.c_int32), ("W", C.c_int32),
+                ("stripes", C.c_int32), ("run", C.c_int32),
+                ("q_stripe", C.c_int64 * 2), ("k_stripe", C.c_int64 * 2), ("v_stripe", C.c_int64 * 2),
+                ("o_stripe", C.c_int64 * 2)]
+
+
+class CswinCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("dtype", "B", "H", "W", "C", "heads", "sw")]
 
 
 class SwinCfg(C.Structure):
@@ -110,7 +117,8 @@ def lib():
         L.sm_last_error.restype = C.c_char_p
         L.sm_map_numel.restype = C.c_int64
         for f in ("sm_fanout_graph_workspace_bytes", "sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes",
-                  "sm_swin_block_static_max_bytes", "sm_decode_step_workspace_bytes"):
+                  "sm_swin_block_static_max_bytes", "sm_decode_step_workspace_bytes",
+                  "sm_cswin_attention_workspace_bytes"):
             getattr(L, f).restype = C.c_size_t
         _lib = L
     return _lib
@@ -398,9 +406,11 @@ def mlp_fused(X, packed, b1, b2, residual=None, norm=None, proj=None, x_map=None
 
 
 def attention(q, k, v, kind="full", scale=None, out=None, rpb_table=None, window=0, shift=0, H=0, W=0,
-              shape=None, q_stride=None, k_stride=None, v_stride=None, o_stride=None, stream=None):
+              shape=None, q_stride=None, k_stride=None, v_stride=None, o_stride=None, stream=None,
+              stripes=0, run=0, q_stripe=(0, 0), k_stripe=(0, 0), v_stripe=(0, 0), o_stripe=(0, 0)):
     """q, k, v: 4-D tensors [nb, heads, n, d] (any strides with unit innermost stride), or raw
-    buffers with explicit shape = (nb, heads, nq, nk, d) and element strides (batch, head, token)."""
+    buffers with explicit shape = (nb, heads, nq, nk, d) and element strides (batch, head, token);
+    kind "stripe": also stripes per image, tokens per run and the (stripe, run) element strides."""
     import torch
     d = AttentionDesc()
     if shape is None:
@@ -417,6 +427,9 @@ def attention(q, k, v, kind="full", scale=None, out=None, rpb_table=None, window
     for i in range(3):
         d.q_stride[i], d.k_stride[i], d.v_stride[i], d.o_stride[i] = q_stride[i], k_stride[i], v_stride[i], o_stride[i]
     d.window, d.shift, d.H, d.W = window, shift, H, W
+    d.stripes, d.run = stripes, run
+    for i in range(2):
+        d.q_stripe[i], d.k_stripe[i], d.v_stripe[i], d.o_stripe[i] = q_stripe[i], k_stripe[i], v_stripe[i], o_stripe[i]
     check(lib().sm_attention(C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rpb_table), _stream(stream)),
           "sm_attention")
     return out
@@ -743,6 +756,28 @@ class DecodeStep:
                                    _ptr(vo), _ptr(self.ws), C.c_size_t(self.ws.numel()), self.mode, _stream(stream)),
               "sm_decode_step")
         return (y, ko, vo) if self.mode == SM_EXPLICIT else y
+
+
+class CswinAttention:
+    """sm_cswin_attention: qkv [B, H*W, 3C] (bf16, device) -> [B, H*W, C]; owns its workspace (explicit mode only)."""
+
+    def __init__(self, B, H, W, Cc, heads, sw, mode=SM_ELIDED):
+        import torch
+        self.cfg = CswinCfg(SM_BF16, B, H, W, Cc, heads, sw)
+        self.mode = mode
+        n = lib().sm_cswin_attention_workspace_bytes(C.byref(self.cfg), mode)
+        if n == 0:
+            raise SmError("sm_cswin_attention_workspace_bytes: " + lib().sm_last_error().decode())
+        self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def __call__(self, qkv, out=None, stream=None):
+        import torch
+        c = self.cfg
+        if out is None:
+            out = torch.empty(c.B, c.H * c.W, c.C, dtype=qkv.dtype, device=qkv.device)
+        check(lib().sm_cswin_attention(C.byref(self.cfg), _ptr(qkv), _ptr(out), _ptr(self.ws), C.c_size_t(self.ws.numel()),
+                                       self.mode, _stream(stream)), "sm_cswin_attention")
+        return out
 
 
 class AttnBlock:

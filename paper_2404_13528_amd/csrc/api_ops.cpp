@@ -83,7 +83,7 @@ int attention_checked(const sm_attention_desc& d, const void* q, const void* k, 
                       void* stream, const char* who) {
   if (!q || !k || !v || !o) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
   if (!dtype_ok(d.dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
-  if (d.kind < SM_ATT_FULL || d.kind > SM_ATT_WINDOW) return fail(SM_ERR_INVALID_ARG, "%s: unknown kind", who);
+  if (d.kind < SM_ATT_FULL || d.kind > SM_ATT_STRIPE) return fail(SM_ERR_INVALID_ARG, "%s: unknown kind", who);
   if (d.nb < 1 || d.heads < 1 || d.nq < 1 || d.nk < 1 || d.d < 1) return fail(SM_ERR_SHAPE, "%s: bad shape", who);
   const int vec = d.dtype == SM_F32 ? 4 : 8;
   if (d.d % vec || d.d > 128) return fail(SM_ERR_SHAPE, "%s: head size must be a multiple of %d and <= 128", who, vec);
@@ -100,12 +100,20 @@ int attention_checked(const sm_attention_desc& d, const void* q, const void* k, 
     if (d.nq > 64) return fail(SM_ERR_UNSUPPORTED, "%s: window attention supports windows of at most 64 tokens", who);
     if (d.nb % ((d.H / d.window) * (d.W / d.window))) return fail(SM_ERR_SHAPE, "%s: batch is not a whole number of images", who);
   }
+  if (d.kind == SM_ATT_STRIPE) {
+    if (d.dtype != SM_BF16 || d.d > 32 || !(d.scale > 0.f)) return fail(SM_ERR_UNSUPPORTED, "%s: stripe attention needs bf16, a head size <= 32 and a positive scale", who);
+    if (d.nq != d.nk || d.nq > 65536) return fail(SM_ERR_SHAPE, "%s: stripe attention needs nq == nk <= 65536", who);
+    if (d.stripes < 1 || d.run < 1 || d.nb % d.stripes || d.nq % d.run) return fail(SM_ERR_SHAPE, "%s: batch must be whole images of `stripes` stripes, a stripe whole runs", who);
+    for (int i = 0; i < 2; ++i)
+      if (d.q_stripe[i] % vec || d.k_stripe[i] % vec || d.v_stripe[i] % vec || d.o_stripe[i] % 4)
+        return fail(SM_ERR_SHAPE, "%s: stripe strides must keep 16-byte alignment", who);
+  }
   if (d.dtype == SM_F32) {
     if (d.kind != SM_ATT_WINDOW) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 supports window attention only", who);
     if (d.nq > 64 || d.d > 64) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 window attention needs window^2 <= 64 and head size <= 64", who);
   }
   char label[128];
-  snprintf(label, sizeof(label), "attention_%s_%s[%d,%d,%d,%d,%d]", d.kind == SM_ATT_WINDOW ? "window" : (d.kind == SM_ATT_CAUSAL ? "causal" : "full"),
+  snprintf(label, sizeof(label), "attention_%s_%s[%d,%d,%d,%d,%d]", d.kind == SM_ATT_WINDOW ? "window" : (d.kind == SM_ATT_CAUSAL ? "causal" : (d.kind == SM_ATT_STRIPE ? "stripe" : "full")),
            d.dtype == SM_F32 ? "f32" : "bf16", d.nb, d.heads, d.nq, d.nk, d.d);
   Timed tm(label, stream);
   int rc = launch_attention(d, q, k, v, o, table, stream);

@@ -1,0 +1,230 @@
+// sm_cswin_attention: cross-shaped window self-attention of the CSwin Transformer (Table 1 counts its Reshape /
+// Transpose operators, Table 7 evaluates it), elided and explicit.
+//
+// The operator is written down as the exporter's graph and planned (Sec. 3.2): per half of the channels, the Slices
+// that take q, k, v out of the fused projection, the stripe partition (Transpose, Reshape, Transpose, Reshape), the
+// head split, and after the attention the head merge and the stripe merge.  The plan eliminates every one of them;
+// what remains are two attention operators whose load and store maps are strided in the factored index
+// (image, stripe, head, run, token in run, feature): the executor asks the composer for exactly that factoring and
+// hands the strides to the attention kernel.  The Concat that joins the two halves has two inputs and is outside the
+// planner; it is eliminated by the same rule applied by hand (the producer stores the layout the consumer reads,
+// Sec. 3.2.2): each attention stores into its half of the output's channels.  In explicit mode every run of layout
+// operators is a copy kernel, the Concat included.
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <vector>
+#include "common.h"
+#include "copy_plan.h"
+#include "graph_build.h"
+#include "index_map.h"
+#include "kernels.h"
+#include "plan_chains.h"
+
+using namespace sm;
+
+namespace {
+
+// element strides of an attention operand in the factored index (image, stripe, head, run, token in run, feature)
+struct Strides6 { int64_t base, img, stripe, head, runs, tok; };
+struct Branch {
+  int64_t Hs, Ws, S, stripes, run, nwin;
+  Strides6 q, k, v, o;            // elided: views of qkv [B, L, 3C] and of this half's result [B, L, C/2]
+  Copy split, merge;              // explicit
+};
+struct CswinPlan {
+  Branch br[2];
+  TableRegion ex_tables;
+  int n_layout, n_eliminated, n_kept;
+};
+
+struct Key { int v[7]; bool operator<(const Key& o) const { return std::memcmp(v, o.v, sizeof(v)) < 0; } };
+std::mutex g_mu;
+std::map<Key, std::shared_ptr<CswinPlan>> g_plans;
+
+// the planned map of a [nwin, heads, S, d] operand, looked at as [B, stripes, heads, S / run, run, d]: strided or refused
+bool factored(const sm_map* m, const Branch& b, int64_t B, int64_t hb, int64_t d, Strides6* out, std::string* err, const char* what) {
+  if (!m) { *err = std::string(what) + ": no map planned"; return false; }
+  std::vector<sm_view_op> ch = m->chain;
+  ch.push_back(chains::reshape({B, b.stripes, hb, b.S / b.run, b.run, d}));
+  sm_map* m6 = nullptr;
+  if (map_create(m->src_shape, ch.data(), (int)ch.size(), &m6, err) != SM_OK) return false;
+  std::unique_ptr<sm_map> guard(m6);
+  int64_t st[SM_MAX_RANK];
+  if (!m6->affine(&out->base, st) || st[5] != 1) { *err = std::string(what) + ": not strided in (image, stripe, head, run, token, feature)"; return false; }
+  out->img = st[0]; out->stripe = st[1]; out->head = st[2]; out->runs = st[3]; out->tok = st[4];
+  return true;
+}
+
+std::shared_ptr<CswinPlan> cswin_plan(const sm_cswin_cfg& c, std::string* err) {
+  Key key{{c.B, c.H, c.W, c.C, c.heads, c.sw, c.dtype}};
+  std::lock_guard<std::mutex> lock(g_mu);
+  auto it = g_plans.find(key);
+  if (it != g_plans.end()) return it->second;
+  auto p = std::make_shared<CswinPlan>();
+  const int64_t B = c.B, H = c.H, W = c.W, C = c.C, L = H * W, hb = c.heads / 2, Cb = C / 2, d = C / c.heads;
+  for (int i = 0; i < 2; ++i) {
+    Branch& b = p->br[i];
+    b.Hs = i == 0 ? H : c.sw; b.Ws = i == 0 ? c.sw : W;
+    b.S = b.Hs * b.Ws;
+    b.stripes = (H / b.Hs) * (W / b.Ws);
+    b.nwin = B * b.stripes;
+    b.run = i == 0 ? c.sw : b.S;          // vertical stripe: sw adjacent tokens per grid row; horizontal: whole rows, all adjacent
+  }
+  GraphB g;
+  const int qkv = g.tensor({B, L, 3 * C});
+  const int t4 = g.reshape(qkv, {B, L, 3, C});
+  int whole[3];
+  for (int k = 0; k < 3; ++k) whole[k] = g.reshape(g.slice(t4, 2, k, k + 1), {B, L, C});
+  for (int i = 0; i < 2; ++i) {
+    const Branch& b = p->br[i];
+    int part[3];
+    for (int k = 0; k < 3; ++k) {
+      int t = g.slice(whole[k], 2, i * Cb, (i + 1) * Cb);
+      t = g.transpose(t, {0, 2, 1});
+      t = g.reshape(t, {B, Cb, H / b.Hs, b.Hs, W / b.Ws, b.Ws});
+      t = g.transpose(t, {0, 2, 4, 3, 5, 1});
+      t = g.reshape(t, {b.nwin, b.S, Cb});
+      t = g.reshape(t, {b.nwin, b.S, hb, d});
+      part[k] = g.transpose(t, {0, 2, 1, 3});
+    }
+    int t = g.op(SM_OP_ATTENTION, {part[0], part[1], part[2]}, {b.nwin, hb, b.S, d}, i == 0 ? "attn0" : "attn1", {3, 3, -1});
+    t = g.transpose(t, {0, 2, 1, 3});
+    t = g.reshape(t, {b.nwin, b.S, Cb});
+    t = g.reshape(t, {B, H / b.Hs, W / b.Ws, b.Hs, b.Ws, Cb});
+    t = g.transpose(t, {0, 1, 3, 2, 4, 5});
+    g.reshape(t, {B, L, Cb});
+  }
+  sm_plan* plan = nullptr;
+  if (sm_layout_plan(g.tensors.data(), (int)g.tensors.size(), g.ops.data(), (int)g.ops.size(), 1, &plan) != SM_OK) { *err = sm_last_error(); return nullptr; }
+  std::unique_ptr<sm_plan, void (*)(sm_plan*)> guard(plan, sm_plan_destroy);
+  p->n_kept = p->n_layout = p->n_eliminated = 0;
+  for (int i = 0; i < (int)g.ops.size(); ++i) {
+    int grp, st;
+    sm_plan_op(plan, i, &grp, nullptr, &st, nullptr, nullptr);
+    p->n_kept += st == SM_KEPT;
+    if (grp == SM_ILD_FIX || grp == SM_ILI_FIX) { ++p->n_layout; p->n_eliminated += (st == SM_ELIMINATED_STORE || st == SM_ELIMINATED_LOAD); }
+  }
+  if (p->n_eliminated != p->n_layout || p->n_kept != 2) { *err = "planner did not reduce the operator to its two attentions"; return nullptr; }
+  const int es = (int)dtype_size(c.dtype);
+  for (int i = 0; i < 2; ++i) {
+    Branch& b = p->br[i];
+    const int attn = g.find(i == 0 ? "attn0" : "attn1");
+    const sm_map* m = nullptr;
+    Strides6* dst[3] = {&b.q, &b.k, &b.v};
+    for (int k = 0; k < 3; ++k) {
+      sm_plan_load_map(plan, attn, k, &m, nullptr);
+      if (!factored(m, b, B, hb, d, dst[k], err, "attention load")) return nullptr;
+    }
+    sm_plan_store_map(plan, attn, &m, nullptr);
+    if (!factored(m, b, B, hb, d, &b.o, err, "attention store")) return nullptr;
+    // explicit chain: q, k, v of this half in one copy [3, nwin, heads, S, d]; head merge + stripe merge in another
+    std::vector<sm_view_op> split{chains::reshape({B, L, 3, C}), chains::slice(3, i * Cb, (i + 1) * Cb), chains::permute({2, 0, 3, 1}),
+                                  chains::reshape({3, B, Cb, H / b.Hs, b.Hs, W / b.Ws, b.Ws}), chains::permute({0, 1, 3, 5, 4, 6, 2}),
+                                  chains::reshape({3, b.nwin, b.S, hb, d}), chains::permute({0, 1, 3, 2, 4})};
+    if (!make_copy({B, L, 3 * C}, split, es, &p->ex_tables, &b.split, err)) return nullptr;
+    std::vector<sm_view_op> merge{chains::permute({0, 2, 1, 3}), chains::reshape({b.nwin, b.S, Cb}), chains::reshape({B, H / b.Hs, W / b.Ws, b.Hs, b.Ws, Cb}),
+                                  chains::permute({0, 1, 3, 2, 4, 5}), chains::reshape({B, L, Cb})};
+    if (!make_copy({b.nwin, hb, b.S, d}, merge, es, &p->ex_tables, &b.merge, err)) return nullptr;
+  }
+  if (g_plans.size() >= 64) g_plans.clear();
+  g_plans[key] = p;
+  return p;
+}
+
+int check_cfg(const sm_cswin_cfg* c, const char* who) {
+  if (!c) return fail(SM_ERR_INVALID_ARG, "%s: null configuration", who);
+  if (c->dtype != SM_BF16) return fail(SM_ERR_UNSUPPORTED, "%s: bf16 only", who);
+  if (c->B < 1 || c->H < 1 || c->W < 1 || c->C < 1 || c->heads < 2 || c->sw < 1) return fail(SM_ERR_SHAPE, "%s: bad shape", who);
+  if (c->heads % 2 || c->C % c->heads) return fail(SM_ERR_SHAPE, "%s: the channels must split into an even number of heads", who);
+  const int d = c->C / c->heads;
+  if (d % 8 || d > 32) return fail(SM_ERR_SHAPE, "%s: head size must be a multiple of 8, at most 32", who);
+  if (c->H % c->sw || c->W % c->sw) return fail(SM_ERR_SHAPE, "%s: grid %d x %d is not a multiple of the stripe width %d", who, c->H, c->W, c->sw);
+  if ((int64_t)c->sw * std::max(c->H, c->W) > 65536) return fail(SM_ERR_SHAPE, "%s: a stripe may hold at most 65536 tokens", who);
+  if ((int64_t)c->B * c->H * c->W * 3 * c->C >= (1LL << 31)) return fail(SM_ERR_SHAPE, "%s: more than 2^31 elements", who);
+  return SM_OK;
+}
+
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+// explicit mode: per half, [3, nwin, heads/2, S, d] operands, the attention result, the merged result
+size_t half_bytes(const sm_cswin_cfg& c) { return align256((size_t)c.B * c.H * c.W * (c.C / 2) * dtype_size(c.dtype)); }
+
+}  // namespace
+
+extern "C" size_t sm_cswin_attention_workspace_bytes(const sm_cswin_cfg* c, int mode) {
+  if (check_cfg(c, "sm_cswin_attention_workspace_bytes") != SM_OK) return 0;
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) { set_error("sm_cswin_attention_workspace_bytes: unknown mode %d", mode); return 0; }
+  std::string err;
+  auto plan = cswin_plan(*c, &err);
+  if (!plan) { set_error("sm_cswin_attention_workspace_bytes: %s", err.c_str()); return 0; }
+  if (mode == SM_ELIDED) return 256;       // nothing is staged (0 is this query's error value)
+  return 10 * half_bytes(*c) + plan->ex_tables.bytes;
+}
+
+extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, void* out, void* ws, size_t ws_bytes, int mode, void* stream) {
+  int rc = check_cfg(c, "sm_cswin_attention");
+  if (rc) return rc;
+  if (!qkv || !out) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: null pointer");
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: unknown mode %d", mode);
+  if (!aligned16(qkv) || !aligned16(out) || (ws && !aligned16(ws))) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: pointers must be 16-byte aligned");
+  std::string err;
+  auto plan = cswin_plan(*c, &err);
+  if (!plan) return fail(SM_ERR_UNSUPPORTED, "sm_cswin_attention: %s", err.c_str());
+  const bool el = mode == SM_ELIDED;
+  const size_t hbytes = half_bytes(*c);
+  if (!el) {
+    const size_t need = 10 * hbytes + plan->ex_tables.bytes;
+    if (!ws || ws_bytes < need) return fail(SM_ERR_WORKSPACE, "sm_cswin_attention: workspace of %zu bytes, %zu needed", ws ? ws_bytes : (size_t)0, need);
+  }
+  count_reset();
+  const int64_t B = c->B, L = (int64_t)c->H * c->W, C = c->C, Cb = C / 2, hb = c->heads / 2, d = C / c->heads;
+  const unsigned short* src = (const unsigned short*)qkv;
+  unsigned short* dst = (unsigned short*)out;
+  char* base = (char*)ws;
+  const void* tables = el ? nullptr : base + 10 * hbytes;
+  if (!el && (rc = fill_tables(plan->ex_tables, base + 10 * hbytes, stream, ~0ull))) return rc;
+  void* merged[2] = {nullptr, nullptr};
+  for (int i = 0; i < 2; ++i) {
+    const Branch& b = plan->br[i];
+    sm_attention_desc a; std::memset(&a, 0, sizeof(a));
+    a.dtype = c->dtype; a.nb = (int)b.nwin; a.heads = (int)hb; a.nq = a.nk = (int)b.S; a.d = (int)d;
+    a.scale = (float)(1.0 / std::sqrt((double)d));
+    if (el) {
+      a.kind = SM_ATT_STRIPE; a.stripes = (int)b.stripes; a.run = (int)b.run;
+      const Strides6* in[3] = {&b.q, &b.k, &b.v};
+      int64_t* st[3] = {a.q_stride, a.k_stride, a.v_stride};
+      int64_t* sp[3] = {a.q_stripe, a.k_stripe, a.v_stripe};
+      for (int k = 0; k < 3; ++k) { st[k][0] = in[k]->img; st[k][1] = in[k]->head; st[k][2] = in[k]->tok; sp[k][0] = in[k]->stripe; sp[k][1] = in[k]->runs; }
+      // the planned store map addresses this half's result [B, L, C/2]; the Concat puts that tensor into columns
+      // [i C/2, (i + 1) C/2) of rows of C elements: token strides grow by C / (C/2), the column offset is added
+      const Strides6& o = b.o;
+      if (o.img % Cb || o.stripe % Cb || o.runs % Cb || o.tok % Cb || o.base != 0 || o.head >= Cb)
+        return fail(SM_ERR_UNSUPPORTED, "sm_cswin_attention: the planned store is not by whole tokens");
+      a.o_stride[0] = o.img / Cb * C; a.o_stride[1] = o.head; a.o_stride[2] = o.tok / Cb * C;
+      a.o_stripe[0] = o.stripe / Cb * C; a.o_stripe[1] = o.runs / Cb * C;
+      if ((rc = attention_checked(a, src + b.q.base, src + b.k.base, src + b.v.base, dst + i * Cb, nullptr, stream, "sm_cswin_attention"))) return rc;
+    } else {
+      unsigned short* parts = (unsigned short*)(base + (size_t)i * 5 * hbytes);      // [3, nwin, heads/2, S, d]
+      unsigned short* res = (unsigned short*)(base + (size_t)i * 5 * hbytes + 3 * hbytes);
+      merged[i] = base + (size_t)i * 5 * hbytes + 4 * hbytes;
+      if ((rc = copy_launch(b.split, tables, qkv, parts, c->dtype, stream))) return rc;
+      a.kind = SM_ATT_FULL;
+      const int64_t per = b.nwin * hb * b.S * d;
+      int64_t* st[4] = {a.q_stride, a.k_stride, a.v_stride, a.o_stride};
+      for (int k = 0; k < 4; ++k) { st[k][0] = hb * b.S * d; st[k][1] = b.S * d; st[k][2] = d; }
+      if ((rc = attention_checked(a, parts, parts + per, parts + 2 * per, res, nullptr, stream, "sm_cswin_attention"))) return rc;
+      if ((rc = copy_launch(b.merge, tables, res, merged[i], c->dtype, stream))) return rc;
+    }
+  }
+  if (!el) {
+    char label[96];
+    snprintf(label, sizeof(label), "concat_bf16[%lld,%lld]", (long long)(B * L), (long long)C);
+    Timed tm(label, stream);
+    if (int e = launch_concat2_cols(merged[0], merged[1], out, B * L, (int)(Cb * dtype_size(c->dtype)), stream))
+      return fail(SM_ERR_DEVICE, "sm_cswin_attention: concat launch failed (hip error %d)", e);
+    count_copy();
+  }
+  return SM_OK;
+}

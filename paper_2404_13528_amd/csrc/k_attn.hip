@@ -190,9 +190,13 @@ typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
-template <int DK, bool CAUSAL>
+// MODE 0: every key visible; 1: causal; 2: stripes (a batch entry is one stripe of an image's token grid: its tokens
+// lie in runs of a.run adjacent tokens, so the stripe partition and merge of cross-shaped windows are two more
+// strides in the row addresses).
+template <int DK, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh) {
+  constexpr bool CAUSAL = MODE == 1, STRIPE = MODE == 2;
   constexpr int DB = (DK + 1) / 2;           // 32-wide output column blocks
   // Row pitches in 16-byte chunks, chosen for the 64-bank LDS.  K rows are read whole-chunk by 16 consecutive rows
   // at a time (ds_read_b128): an odd pitch spreads them over all banks.  V rows are read by the transposing load,
@@ -212,11 +216,25 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
   const int bh = blockIdx.x % nbh, rank = blockIdx.x / nbh;
   int qt = rank;
   if (CAUSAL) { const int hq = (n_qt + 1) >> 1; qt = rank < hq ? n_qt - 1 - rank : rank - hq; }
-  const int hh = bh % a.heads, b = bh / a.heads;
-  const bf16_t* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
-  const bf16_t* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
-  const bf16_t* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
-  bf16_t* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
+  const int hh = bh % a.heads;
+  int b = bh / a.heads;
+  const bf16_t *qp = q, *kp = k, *vp = v;
+  bf16_t* op = o;
+  if (STRIPE) {
+    const int img = b / a.stripes, j = b - img * a.stripes;
+    qp += (int64_t)j * a.q_stripe[0]; kp += (int64_t)j * a.k_stripe[0]; vp += (int64_t)j * a.v_stripe[0]; op += (int64_t)j * a.o_stripe[0];
+    b = img;
+  }
+  qp += (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
+  kp += (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
+  vp += (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
+  op += (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
+  // element offset of token s_ of the sequence
+  auto row_off = [&](int s_, int64_t tok_stride, int64_t run_stride) -> int64_t {
+    if (!STRIPE) return (int64_t)s_ * tok_stride;
+    const int so = s_ / a.run;
+    return (int64_t)so * run_stride + (int64_t)(s_ - so * a.run) * tok_stride;
+  };
   const int Q0 = qt * 128, q0 = Q0 + wave * 32, qi = q0 + l32;
   const int chv = a.d >> 3;                  // valid chunks per row
 
@@ -240,15 +258,15 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
 #pragma unroll
     for (int i = 0; i < NLW; ++i) {
       if (wave + 4 * i < P) {                // wave-uniform
-        const int64_t key = min(kt * 64 + ld_row[i], a.nk - 1);    // rows past the end repeat the last key (masked below)
-        __builtin_amdgcn_global_load_lds(SM_GPTR_(kp + key * a.k_stride[2] + ld_col[i]), SM_LPTR_(st + (wave + 4 * i) * 64), 16, 0, 0);
+        const int key = min(kt * 64 + ld_row[i], a.nk - 1);        // rows past the end repeat the last key (masked below)
+        __builtin_amdgcn_global_load_lds(SM_GPTR_(kp + row_off(key, a.k_stride[2], a.k_stripe[1]) + ld_col[i]), SM_LPTR_(st + (wave + 4 * i) * 64), 16, 0, 0);
       }
     }
 #pragma unroll
     for (int i = 0; i < NLV; ++i) {
       if (wave + 4 * i < PV && lv_col[i] < a.d) {
-        const int64_t key = min(kt * 64 + lv_row[i], a.nk - 1);
-        __builtin_amdgcn_global_load_lds(SM_GPTR_(vp + key * a.v_stride[2] + lv_col[i]), SM_LPTR_(st + TILE + (wave + 4 * i) * 64), 16, 0, 0);
+        const int key = min(kt * 64 + lv_row[i], a.nk - 1);
+        __builtin_amdgcn_global_load_lds(SM_GPTR_(vp + row_off(key, a.v_stride[2], a.v_stripe[1]) + lv_col[i]), SM_LPTR_(st + TILE + (wave + 4 * i) * 64), 16, 0, 0);
       }
     }
   };
@@ -260,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
   const au32x4 zero = {0u, 0u, 0u, 0u};
   au32x4 qf[DK];
   {
-    const bf16_t* qrow = qp + (int64_t)min(qi, a.nq - 1) * a.q_stride[2];
+    const bf16_t* qrow = qp + row_off(min(qi, a.nq - 1), a.q_stride[2], a.q_stripe[1]);
 #pragma unroll
     for (int ks = 0; ks < DK; ++ks) {
       const int e = 16 * ks + 8 * hf;
@@ -355,6 +373,7 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
   if (qi >= a.nq) return;
   l_run += __shfl_xor(l_run, 32, 64);
   const float inv = 1.f / l_run;
+  bf16_t* orow = op + row_off(qi, a.o_stride[2], a.o_stripe[1]);
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -362,7 +381,7 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
       const int e = 32 * db + g4 * 8 + hf * 4;
       if (e < a.d) {
         const f32x2_t x0 = {oacc[db][4 * g4] * inv, oacc[db][4 * g4 + 1] * inv}, x1 = {oacc[db][4 * g4 + 2] * inv, oacc[db][4 * g4 + 3] * inv};
-        *(uint2*)(op + (int64_t)qi * a.o_stride[2] + e) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
+        *(uint2*)(orow + e) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
                                                                     __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
       }
     }
@@ -829,6 +848,7 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     }
     return (int)hipGetLastError();
   }
+  if (d.kind == SM_ATT_STRIPE && (d.d > 32 || d.scale <= 0.f)) return (int)hipErrorInvalidValue;      // one instantiation: head size <= 32
   if (d.kind != SM_ATT_WINDOW && d.scale > 0.f) {
     const int n_qt = (d.nq + 127) / 128, nbh = d.nb * d.heads, dk = (d.d + 15) / 16;
     const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
@@ -836,12 +856,18 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     const dim3 grid((unsigned)((long)n_qt * nbh)), block(256);
 #define FLASH(DK_) do { \
       const size_t smem = 2 * 64 * ((2 * DK_ + 1) + (DK_ <= 2 ? 4 : (DK_ == 3 ? 7 : (DK_ <= 6 ? 12 : 20)))) * 16 + 64;      /* two stages of a K tile and a V tile */ \
-      static const hipError_t attr_f = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
-      static const hipError_t attr_c = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+      static const hipError_t attr_f = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+      static const hipError_t attr_c = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
       if (attr_f != hipSuccess || attr_c != hipSuccess) return (int)(attr_f != hipSuccess ? attr_f : attr_c); \
-      if (d.kind == SM_ATT_CAUSAL) attn_flash_kernel<DK_, true><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); \
-      else attn_flash_kernel<DK_, false><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); } while (0)
-    if (dk <= 2) FLASH(2);
+      if (d.kind == SM_ATT_CAUSAL) attn_flash_kernel<DK_, 1><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); \
+      else attn_flash_kernel<DK_, 0><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); } while (0)
+    if (d.kind == SM_ATT_STRIPE) {
+      const size_t smem = 2 * 64 * ((2 * 2 + 1) + 4) * 16 + 64;
+      static const hipError_t attr_s = hipFuncSetAttribute((const void*)attn_flash_kernel<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (attr_s != hipSuccess) return (int)attr_s;
+      attn_flash_kernel<2, 2><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh);
+    }
+    else if (dk <= 2) FLASH(2);
     else if (dk == 3) FLASH(3);
     else if (dk == 4) FLASH(4);
     else if (dk <= 6) FLASH(6);

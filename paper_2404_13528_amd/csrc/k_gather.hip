@@ -174,6 +174,23 @@ int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const v
   return (int)hipGetLastError();
 }
 
+// Concat along the last axis: out [rows, 2 * cv] = [a [rows, cv] | b [rows, cv]], cv in 16-byte vectors
+__global__ __launch_bounds__(256) void concat2_cols_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b, uint4* __restrict__ out,
+                                                           int cv, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t r = i / (2 * cv);
+  const int c = (int)(i - r * 2 * cv);
+  out[i] = c < cv ? a[r * cv + c] : b[r * cv + c - cv];
+}
+int launch_concat2_cols(const void* a, const void* b, void* out, int64_t rows, int cols_bytes, void* stream) {
+  const int cv = cols_bytes / 16;
+  const int64_t total = rows * 2 * cv;
+  if (total == 0) return 0;
+  concat2_cols_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>((const uint4*)a, (const uint4*)b, (uint4*)out, cv, total);
+  return (int)hipGetLastError();
+}
+
 int launch_gather(const MapProg& prog, int64_t numel, int vec_elems, const void* src, void* dst, int esize, void* stream) {
   if (numel == 0) return 0;
   int64_t nvec = numel / vec_elems;

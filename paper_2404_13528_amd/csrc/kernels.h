@@ -16,6 +16,8 @@ int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const v
 int launch_empty(void* stream);
 
 // row copies: dst row r (inner contiguous elements) = src[rows(r) ...] (+ addend row r); rows(r) keeps 16-byte alignment
+// out [rows, 2 * cols] = [a | b] along the last axis; cols_bytes (of one input row) a multiple of 16
+int launch_concat2_cols(const void* a, const void* b, void* out, int64_t rows, int cols_bytes, void* stream);
 int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const void* src, const void* addend, void* dst, int dtype, void* stream);
 
 // table[r] = offset of row r under `prog` (interpreted), r < n_rows: fills one per-row offset table

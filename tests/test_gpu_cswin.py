@@ -1,0 +1,100 @@
+"""sm_cswin_attention (cross-shaped window attention) and the stripe kind of sm_attention against oracle/cswin.py: both
+modes, the stripe widths and grids of the four stages of CSwin-T, a non-square grid, and the full batch bench-sized case."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cswin as CS
+from oracle import ops as O
+from paper_2404_13528_amd import binding as sm, workloads as Wl
+from util import assert_bf16_close, to_np
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    (2, 56, 56, 64, 2, 1),       # stage 1: stripes one token wide (runs of one token)
+    (2, 28, 28, 128, 4, 2),      # stage 2
+    (3, 14, 14, 256, 8, 7),      # stage 3: 98 tokens per stripe
+    (2, 7, 7, 512, 16, 7),       # stage 4: the stripe is the whole image
+    (2, 8, 12, 96, 4, 4),        # non-square grid, head size 24, stripes of 32 and 48 tokens
+    (1, 48, 48, 32, 2, 3),       # 144 tokens per stripe: two query tiles and three key tiles with ragged tails
+]
+
+
+def run_case(B, H, W, Cc, heads, sw, mode, seed=0):
+    qkv = Wl.cswin_qkv_case(B, H, W, Cc, seed=seed, bf16=True)
+    want = CS.cross_window_attention(to_np(qkv), B, H, W, Cc, heads, sw)
+    op = sm.CswinAttention(B, H, W, Cc, heads, sw, mode)
+    dev = qkv.to(torch.bfloat16).cuda()
+    before = dev.clone()
+    out = op(dev)
+    torch.cuda.synchronize()
+    assert sm.launch_counts() == ((2, 0) if mode == sm.SM_ELIDED else (2, 5))
+    assert torch.equal(dev, before)
+    assert_bf16_close(out.reshape(B * H * W, Cc), want.reshape(B * H * W, Cc), what="cross-window attention")
+    return out
+
+
+@pytest.mark.parametrize("mode", [sm.SM_ELIDED, sm.SM_EXPLICIT])
+@pytest.mark.parametrize("B,H,W,Cc,heads,sw", CASES)
+def test_matches_the_oracle(B, H, W, Cc, heads, sw, mode):
+    run_case(B, H, W, Cc, heads, sw, mode, seed=H + sw)
+
+
+def test_modes_agree_and_repeat():
+    B, H, W, Cc, heads, sw = 4, 14, 14, 256, 8, 7
+    a = run_case(B, H, W, Cc, heads, sw, sm.SM_ELIDED, seed=5)
+    b = run_case(B, H, W, Cc, heads, sw, sm.SM_EXPLICIT, seed=5)
+    # same kernel arithmetic on the same values, only the addresses differ
+    assert torch.equal(a, b)
+    assert torch.equal(a, run_case(B, H, W, Cc, heads, sw, sm.SM_ELIDED, seed=5))
+
+
+def test_full_batch_stage3():
+    # the size bench-style runs use: 64 images of 14 x 14 tokens, 256 channels, stripes 7 wide
+    run_case(64, 14, 14, 256, 8, 7, sm.SM_ELIDED, seed=9)
+
+
+def test_a_planted_mistake_in_the_oracle_shows():
+    B, H, W, Cc, heads, sw = 2, 14, 14, 64, 2, 7
+    qkv = Wl.cswin_qkv_case(B, H, W, Cc, seed=3, bf16=True)
+    out = sm.CswinAttention(B, H, W, Cc, heads, sw)(qkv.to(torch.bfloat16).cuda())
+    # horizontal stripes for the first half of the heads and vertical for the second (the halves exchanged)
+    x = to_np(qkv).reshape(B, H, W, 3, Cc).transpose(0, 2, 1, 3, 4).reshape(B, H * W, 3 * Cc)
+    wrong = CS.cross_window_attention(np.ascontiguousarray(x), B, W, H, Cc, heads, sw)
+    wrong = wrong.reshape(B, W, H, Cc).transpose(0, 2, 1, 3).reshape(B * H * W, Cc)
+    with pytest.raises(AssertionError):
+        assert_bf16_close(out.reshape(B * H * W, Cc), wrong, what="exchanged halves")
+
+
+def test_stripe_kind_of_the_attention_operator():
+    # one tensor [B, H, W, heads, d] read as vertical stripes of width 2 (runs of 2 tokens, a grid row apart) and
+    # written back in place order; against the oracle's attention on gathered stripes
+    B, H, W, h, d, sw = 2, 6, 8, 3, 16, 2
+    g = torch.Generator().manual_seed(1)
+    q, k, v = [torch.randn(B, H, W, h, d, generator=g).to(torch.bfloat16) for _ in range(3)]
+    ns, S = W // sw, H * sw
+    tok = h * d
+    strides = dict(q_stride=(H * W * tok, d, tok), k_stride=(H * W * tok, d, tok), v_stride=(H * W * tok, d, tok), o_stride=(H * W * tok, d, tok))
+    stripe = (sw * tok, W * tok)
+    out = torch.zeros(B, H, W, h, d, dtype=torch.bfloat16, device="cuda")
+    sm.attention(q.cuda(), k.cuda(), v.cuda(), kind="stripe", out=out, shape=(B * ns, h, S, S, d), stripes=ns, run=sw,
+                 q_stripe=stripe, k_stripe=stripe, v_stripe=stripe, o_stripe=stripe, **strides)
+    torch.cuda.synchronize()
+
+    def gather(t):          # [B, H, W, h, d] -> [B, ns, h, H * sw, d]
+        return to_np(t).reshape(B, H, ns, sw, h, d).transpose(0, 2, 4, 1, 3, 5).reshape(B, ns, h, S, d)
+    want, _ = O.attention(gather(q), gather(k), gather(v), d ** -0.5)
+    want = want.reshape(B, ns, h, H, sw, d).transpose(0, 3, 1, 4, 2, 5).reshape(B * H * W, h * d)
+    assert_bf16_close(out.reshape(B * H * W, h * d), want, what="stripe attention")
+
+
+def test_refusals_on_device():
+    q = torch.zeros(2, 2, 8, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sm.SmError):        # head size 64 has no stripe variant
+        sm.attention(q, q, q, kind="stripe", stripes=1, run=8)
+    q = torch.zeros(3, 2, 8, 32, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sm.SmError):        # three batch entries are not whole images of two stripes
+        sm.attention(q, q, q, kind="stripe", stripes=2, run=8)
+    with pytest.raises(sm.SmError):        # a stripe of 8 tokens is not whole runs of 3
+        sm.attention(q, q, q, kind="stripe", stripes=1, run=3)
