@@ -216,8 +216,10 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
   const int bh = blockIdx.x % nbh, rank = blockIdx.x / nbh;
   int qt = rank;
   if (CAUSAL) { const int hq = (n_qt + 1) >> 1; qt = rank < hq ? n_qt - 1 - rank : rank - hq; }
-  const int hh = bh % a.heads;
-  int b = bh / a.heads;
+  // stripes: heads whose rows share cache lines (head size 32 is half a line) follow each other at a distance of
+  // a.nb workgroups, which keeps them on one XCD's L2 whenever a.nb is a multiple of 8
+  const int hh = STRIPE ? bh / a.nb : bh % a.heads;
+  int b = STRIPE ? bh - hh * a.nb : bh / a.heads;
   const bf16_t *qp = q, *kp = k, *vp = v;
   bf16_t* op = o;
   if (STRIPE) {
