@@ -127,6 +127,13 @@ def cswin_qkv_case(B, H, W, C, seed=0, bf16=True, in_std=1.0):
     return dr.normal(B, H * W, 3 * C, std=in_std)
 
 
+def cswin_lepe_params(C, seed=0, bf16=True, std=0.2):
+    """Depth-wise 3 x 3 weights [C, 3, 3] and bias [C] of the locally-enhanced positional encoding (both halves of the
+    channels, first half first); std 0.2 so that the encoding is a visible share of the attention output."""
+    dr = Draw(seed + 1000, bf16, std)
+    return dr.weight(C, 3, 3), dr.weight(C)
+
+
 def fanout_case(D1, D2, D3, Kin, Cout, seed=0, bf16=True):
     """Operands of the Fig. 4 graph: activations N(0,1), weights scaled so that every output is O(1)."""
     dr = Draw(seed, bf16)

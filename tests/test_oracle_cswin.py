@@ -12,7 +12,7 @@ from paper_2404_13528_amd import workloads as Wl
 from util import to_np
 
 
-def by_definition(qkv, B, H, W, C, heads, sw, swap=False):
+def by_definition(qkv, B, H, W, C, heads, sw, swap=False, lepe=None):
     """For every image, branch, stripe and head: collect the stripe's tokens from the definition (vertical stripe j =
     the grid columns [j sw, (j + 1) sw), horizontal stripe j = the grid rows [j sw, (j + 1) sw)), attend among them
     with the library routine, and put every token's result back at its own place."""
@@ -29,6 +29,12 @@ def by_definition(qkv, B, H, W, C, heads, sw, swap=False):
                 k = t[b, toks, 1 * C + hh * d:1 * C + (hh + 1) * d]
                 v = t[b, toks, 2 * C + hh * d:2 * C + (hh + 1) * d]
                 o = F.scaled_dot_product_attention(q[None], k[None], v[None])[0]
+                if lepe is not None:
+                    # the stripe's values as an image [d, rows, columns] through the library's grouped convolution
+                    rows, cols = (H, sw) if vertical else (sw, W)
+                    wt, bs = [torch.from_numpy(t)[hh * d:(hh + 1) * d] for t in lepe]
+                    img = v.T.reshape(1, d, rows, cols)
+                    o = o + F.conv2d(img, wt[:, None], bs, padding=1, groups=d).reshape(d, rows * cols).T
                 out[b, toks, hh * d:(hh + 1) * d] = o
     return out.numpy()
 
@@ -75,3 +81,32 @@ def test_partition_and_merge_are_inverse_and_keep_grid_order():
     assert np.array_equal(V.apply_chain(s, V.stripe_merge_chain(B, H, W, C, Hs, Ws)), x)
     # stripe 1 of image 0 starts at grid column 2; its tokens run row-major inside the stripe
     assert np.array_equal(s[1, :4, 0] / C, [2, 3, W + 2, W + 3])
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,sw", [(2, 4, 4, 16, 2, 2), (1, 6, 6, 32, 4, 3), (1, 4, 8, 16, 4, 1)])
+def test_positional_encoding_matches_the_library_convolution_per_stripe(B, H, W, C, heads, sw):
+    qkv = to_np(Wl.cswin_qkv_case(B, H, W, C, seed=21, bf16=False))
+    w, b = [to_np(t) for t in Wl.cswin_lepe_params(C, seed=21, bf16=False)]
+    got = CS.cross_window_attention(qkv, B, H, W, C, heads, sw, w, b)
+    assert np.abs(got - by_definition(qkv, B, H, W, C, heads, sw, lepe=(w, b))).max() < 1e-12
+    # it is a visible share of the output, and a flipped kernel (convolution instead of cross-correlation) shows
+    plain = CS.cross_window_attention(qkv, B, H, W, C, heads, sw)
+    assert np.abs(got - plain).max() > 0.1
+    flipped = CS.cross_window_attention(qkv, B, H, W, C, heads, sw, w[:, ::-1, ::-1].copy(), b)
+    assert np.abs(flipped - got).max() > 1e-2
+
+
+def test_positional_encoding_stops_at_the_stripe_border():
+    # a single non-zero value: its encoding reaches the 3 x 3 neighbours inside its stripe only
+    B, H, W, C, heads, sw = 1, 6, 6, 4, 2, 2
+    qkv = np.zeros((B, H * W, 3 * C))
+    y0, x0 = 2, 3                                    # in vertical stripe 1 (columns 2, 3) and horizontal stripe 1 (rows 2, 3)
+    qkv[0, y0 * W + x0, 2 * C:] = 1.0
+    w, b = np.ones((C, 3, 3)), np.zeros(C)
+    with_pe = CS.cross_window_attention(qkv, B, H, W, C, heads, sw, w, b)
+    plain = CS.cross_window_attention(qkv, B, H, W, C, heads, sw)
+    pe = (with_pe - plain).reshape(H, W, C)
+    want_v = np.zeros((H, W)); want_v[1:4, 2:4] = 1.0            # rows 1..3, columns of the stripe only
+    want_h = np.zeros((H, W)); want_h[2:4, 2:5] = 1.0            # rows of the stripe only, columns 2..4
+    assert np.allclose(pe[..., 0], want_v) and np.allclose(pe[..., 1], want_v)
+    assert np.allclose(pe[..., 2], want_h) and np.allclose(pe[..., 3], want_h)
