@@ -76,6 +76,10 @@ def kernel_model(label):
     m = re.match(r"concat_bf16\[(\d+),(\d+),(\d+)\]", label)
     if m:
         return 2 * int(m.group(1)) * int(m.group(2)) * int(m.group(3)) * e, 0.0
+    m = re.match(r"dwconv3x3_bf16\[(\d+),(\d+),(\d+),(\d+)\]", label)
+    if m:      # depth-wise 3 x 3: the values read, the result written, 9 weights + bias per channel
+        n, H, W, C = [int(m.group(i)) for i in range(1, 5)]
+        return (2 * n * H * W * C + 10 * C) * e, 18.0 * n * H * W * C
     m = re.match(r"concat_bf16\[(\d+),(\d+)\]", label)
     if m:      # Concat along the channels: [rows, C] written, its two halves read
         return 2 * int(m.group(1)) * int(m.group(2)) * e, 0.0
@@ -281,10 +285,12 @@ def build_config(k, sm, torch, Wl):
         B, H, W, C, h, sw = 64, 14, 14, 256, 8, 7
         qkv = Wl.cswin_qkv_case(B, H, W, C).to(bf).cuda()
         y = torch.empty(B, H * W, C, dtype=bf, device="cuda")
+        pe = [t.to(bf).cuda() for t in Wl.cswin_lepe_params(C)]
         ops = {n: sm.CswinAttention(B, H, W, C, h, sw, m) for n, m in (("elided", sm.SM_ELIDED), ("explicit", sm.SM_EXPLICIT))}
-        return ("extra: CSwin-style cross-shaped window attention, bf16, B=64, 14x14 tokens, 256 channels, 8 heads x 32 "
-                "(4 in vertical, 4 in horizontal stripes of width 7), from the fused q|k|v projection to the merged output",
-                "images/s", B, {n: (lambda o=o: o(qkv, out=y)) for n, o in ops.items()}, None, "bf16")
+        return ("extra: CSwin-style cross-shaped window attention with its positional encoding (depth-wise 3x3 on the values), bf16, "
+                "B=64, 14x14 tokens, 256 channels, 8 heads x 32 (4 in vertical, 4 in horizontal stripes of width 7), from the fused "
+                "q|k|v projection to the merged output", "images/s", B,
+                {n: (lambda o=o: o(qkv, out=y, lepe=pe)) for n, o in ops.items()}, None, "bf16")
     raise ValueError(k)
 
 

@@ -310,6 +310,7 @@ typedef struct {
   int32_t window, shift, H, W;      /* SM_ATT_WINDOW only; batch index = (image, wy, wx) row-major */
   int32_t stripes, run;             /* SM_ATT_STRIPE only: stripes per image, adjacent tokens per run */
   int64_t q_stripe[2], k_stripe[2], v_stripe[2], o_stripe[2];   /* SM_ATT_STRIPE only: element strides (stripe, run) */
+  int32_t accumulate, reserved;     /* accumulate != 0: O += the result (O is read; bf16 full / causal / stripe kinds with scale > 0) */
 } sm_attention_desc;
 int sm_attention(const sm_attention_desc*, const void* q, const void* k, const void* v, void* o,
                  const void* rpb_table, void* stream);
@@ -427,21 +428,29 @@ int sm_decode_step(const sm_decode_cfg*, const sm_decode_weights*, const void* x
  * qkv [B, H*W, 3C] (device; columns [q | k | v], each heads x d with d = C / heads)
  * as the fused Linear leaves it; out [B, H*W, C] (device).  Heads [0, heads/2)
  * attend inside vertical stripes (H x sw grid positions), the others inside
- * horizontal stripes (sw x W); scale d^-1/2; the locally-enhanced positional
- * encoding (a depth-wise convolution) is not part of this operator.
+ * horizontal stripes (sw x W); scale d^-1/2.  lepe_w [C, 3, 3], lepe_b [C]
+ * (device, bf16; both null: none): the locally-enhanced positional encoding,
+ * a depth-wise 3 x 3 cross-correlation of each half's values inside their own
+ * stripe (zero beyond the stripe's border), added to that half's attention
+ * output; channel order as in out.
  *   SM_ELIDED: two attention kernels that read qkv in place and store into their
  *     half of out's channels (the Concat of the halves has two inputs and is not
- *     planned: it is applied as the store address, by hand).
+ *     planned: it is applied as the store address, by hand).  With the encoding:
+ *     per half one convolution kernel first, which reads the values in place and
+ *     writes out's channels, to which the attention then adds.
  *   SM_EXPLICIT: per half one copy kernel for the Slice + partition + head split
  *     of q, k, v, the attention on contiguous operands, one copy for head merge +
- *     stripe merge, then one Concat kernel: 5 copies around the same 2 kernels.
+ *     stripe merge, then one Concat kernel: 5 copies around the same 2 kernels
+ *     (with the encoding 9 around 4: the values as stripe images and the
+ *     encoding's head split are copies too).
  * Limits: bf16; heads even; d a multiple of 8, at most 32; H and W multiples of
  * sw; a stripe of at most 65536 tokens.  ws: device workspace of at least
  * sm_cswin_attention_workspace_bytes(cfg, mode) bytes, owned by the caller.
  * Nothing is allocated; SM_ERR_* with a message otherwise. */
 typedef struct { int32_t dtype, B, H, W, C, heads, sw; } sm_cswin_cfg;
 size_t sm_cswin_attention_workspace_bytes(const sm_cswin_cfg*, int mode);
-int sm_cswin_attention(const sm_cswin_cfg*, const void* qkv, void* out, void* ws, size_t ws_bytes, int mode, void* stream);
+int sm_cswin_attention(const sm_cswin_cfg*, const void* qkv, const void* lepe_w, const void* lepe_b, void* out,
+                       void* ws, size_t ws_bytes, int mode, void* stream);
 
 /* A whole producer-consumer chain (Sec. 3.2: elimination and fusion alternate
  * over rounds, so removed layout operators leave compute operators adjacent):

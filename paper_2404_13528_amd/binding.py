@@ -58,7 +58,7 @@ class AttentionDesc(C.Structure):
                 ("window", C.c_int32), ("shift", C.c_int32), ("H", C.c_int32), ("W", C.c_int32),
                 ("stripes", C.c_int32), ("run", C.c_int32),
                 ("q_stripe", C.c_int64 * 2), ("k_stripe", C.c_int64 * 2), ("v_stripe", C.c_int64 * 2),
-                ("o_stripe", C.c_int64 * 2)]
+                ("o_stripe", C.c_int64 * 2), ("accumulate", C.c_int32), ("reserved", C.c_int32)]
 
 
 class CswinCfg(C.Structure):
@@ -407,10 +407,11 @@ def mlp_fused(X, packed, b1, b2, residual=None, norm=None, proj=None, x_map=None
 
 def attention(q, k, v, kind="full", scale=None, out=None, rpb_table=None, window=0, shift=0, H=0, W=0,
               shape=None, q_stride=None, k_stride=None, v_stride=None, o_stride=None, stream=None,
-              stripes=0, run=0, q_stripe=(0, 0), k_stripe=(0, 0), v_stripe=(0, 0), o_stripe=(0, 0)):
+              stripes=0, run=0, q_stripe=(0, 0), k_stripe=(0, 0), v_stripe=(0, 0), o_stripe=(0, 0), accumulate=False):
     """q, k, v: 4-D tensors [nb, heads, n, d] (any strides with unit innermost stride), or raw
     buffers with explicit shape = (nb, heads, nq, nk, d) and element strides (batch, head, token);
-    kind "stripe": also stripes per image, tokens per run and the (stripe, run) element strides."""
+    kind "stripe": also stripes per image, tokens per run and the (stripe, run) element strides.
+    accumulate: out += the result."""
     import torch
     d = AttentionDesc()
     if shape is None:
@@ -427,7 +428,7 @@ def attention(q, k, v, kind="full", scale=None, out=None, rpb_table=None, window
     for i in range(3):
         d.q_stride[i], d.k_stride[i], d.v_stride[i], d.o_stride[i] = q_stride[i], k_stride[i], v_stride[i], o_stride[i]
     d.window, d.shift, d.H, d.W = window, shift, H, W
-    d.stripes, d.run = stripes, run
+    d.stripes, d.run, d.accumulate = stripes, run, int(bool(accumulate))
     for i in range(2):
         d.q_stripe[i], d.k_stripe[i], d.v_stripe[i], d.o_stripe[i] = q_stripe[i], k_stripe[i], v_stripe[i], o_stripe[i]
     check(lib().sm_attention(C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rpb_table), _stream(stream)),
@@ -759,7 +760,8 @@ class DecodeStep:
 
 
 class CswinAttention:
-    """sm_cswin_attention: qkv [B, H*W, 3C] (bf16, device) -> [B, H*W, C]; owns its workspace (explicit mode only)."""
+    """sm_cswin_attention: qkv [B, H*W, 3C] (bf16, device) -> [B, H*W, C]; owns its workspace (explicit mode only).
+    lepe = (weights [C, 3, 3], bias [C]) adds the locally-enhanced positional encoding."""
 
     def __init__(self, B, H, W, Cc, heads, sw, mode=SM_ELIDED):
         import torch
@@ -770,13 +772,14 @@ class CswinAttention:
             raise SmError("sm_cswin_attention_workspace_bytes: " + lib().sm_last_error().decode())
         self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
 
-    def __call__(self, qkv, out=None, stream=None):
+    def __call__(self, qkv, out=None, lepe=None, stream=None):
         import torch
         c = self.cfg
         if out is None:
             out = torch.empty(c.B, c.H * c.W, c.C, dtype=qkv.dtype, device=qkv.device)
-        check(lib().sm_cswin_attention(C.byref(self.cfg), _ptr(qkv), _ptr(out), _ptr(self.ws), C.c_size_t(self.ws.numel()),
-                                       self.mode, _stream(stream)), "sm_cswin_attention")
+        w, b = (None, None) if lepe is None else lepe
+        check(lib().sm_cswin_attention(C.byref(self.cfg), _ptr(qkv), _ptr(w), _ptr(b), _ptr(out), _ptr(self.ws),
+                                       C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_cswin_attention")
         return out
 
 

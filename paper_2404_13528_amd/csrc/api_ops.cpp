@@ -100,6 +100,8 @@ int attention_checked(const sm_attention_desc& d, const void* q, const void* k, 
     if (d.nq > 64) return fail(SM_ERR_UNSUPPORTED, "%s: window attention supports windows of at most 64 tokens", who);
     if (d.nb % ((d.H / d.window) * (d.W / d.window))) return fail(SM_ERR_SHAPE, "%s: batch is not a whole number of images", who);
   }
+  if (d.accumulate && (d.kind == SM_ATT_WINDOW || d.dtype != SM_BF16 || !(d.scale > 0.f)))
+    return fail(SM_ERR_UNSUPPORTED, "%s: accumulating into O needs a bf16 full, causal or stripe attention with a positive scale", who);
   if (d.kind == SM_ATT_STRIPE) {
     if (d.dtype != SM_BF16 || d.d > 32 || !(d.scale > 0.f)) return fail(SM_ERR_UNSUPPORTED, "%s: stripe attention needs bf16, a head size <= 32 and a positive scale", who);
     if (d.nq != d.nk || d.nq > 65536) return fail(SM_ERR_SHAPE, "%s: stripe attention needs nq == nk <= 65536", who);

@@ -10,6 +10,13 @@
 // planner; it is eliminated by the same rule applied by hand (the producer stores the layout the consumer reads,
 // Sec. 3.2.2): each attention stores into its half of the output's channels.  In explicit mode every run of layout
 // operators is a copy kernel, the Concat included.
+//
+// With the locally-enhanced positional encoding the graph has, per half, a depth-wise convolution of the values laid
+// out as stripe images and an Add of its result to the attention output.  The plan keeps the convolution, fuses the Add
+// into the attention and eliminates the Reshapes / Transposes on both sides of the convolution.  The convolution
+// kernel reads the values in place (its planned load map is checked against the kernel's token-major addressing when
+// the plan is built) and writes where the sum will finally live, in the output's layout; the attention then adds to
+// what it finds there.
 #include <cmath>
 #include <cstring>
 #include <map>
@@ -33,6 +40,7 @@ struct Branch {
   int64_t Hs, Ws, S, stripes, run, nwin;
   Strides6 q, k, v, o;            // elided: views of qkv [B, L, 3C] and of this half's result [B, L, C/2]
   Copy split, merge;              // explicit
+  Copy v_images, pe_split;        // explicit, with the positional encoding: values as [nwin, S, C/2], its result head-split
 };
 struct CswinPlan {
   Branch br[2];
@@ -40,7 +48,7 @@ struct CswinPlan {
   int n_layout, n_eliminated, n_kept;
 };
 
-struct Key { int v[7]; bool operator<(const Key& o) const { return std::memcmp(v, o.v, sizeof(v)) < 0; } };
+struct Key { int v[8]; bool operator<(const Key& o) const { return std::memcmp(v, o.v, sizeof(v)) < 0; } };
 std::mutex g_mu;
 std::map<Key, std::shared_ptr<CswinPlan>> g_plans;
 
@@ -58,8 +66,8 @@ bool factored(const sm_map* m, const Branch& b, int64_t B, int64_t hb, int64_t d
   return true;
 }
 
-std::shared_ptr<CswinPlan> cswin_plan(const sm_cswin_cfg& c, std::string* err) {
-  Key key{{c.B, c.H, c.W, c.C, c.heads, c.sw, c.dtype}};
+std::shared_ptr<CswinPlan> cswin_plan(const sm_cswin_cfg& c, bool lepe, std::string* err) {
+  Key key{{c.B, c.H, c.W, c.C, c.heads, c.sw, c.dtype, lepe ? 1 : 0}};
   std::lock_guard<std::mutex> lock(g_mu);
   auto it = g_plans.find(key);
   if (it != g_plans.end()) return it->second;
@@ -90,7 +98,19 @@ std::shared_ptr<CswinPlan> cswin_plan(const sm_cswin_cfg& c, std::string* err) {
       t = g.reshape(t, {b.nwin, b.S, hb, d});
       part[k] = g.transpose(t, {0, 2, 1, 3});
     }
+    int pe = -1;
+    if (lepe) {        // before the attention in graph order: the Add then joins the attention, its later producer
+      int u = g.slice(whole[2], 2, i * Cb, (i + 1) * Cb);
+      u = g.transpose(u, {0, 2, 1});
+      u = g.reshape(u, {B, Cb, H / b.Hs, b.Hs, W / b.Ws, b.Ws});
+      u = g.transpose(u, {0, 2, 4, 1, 3, 5});
+      u = g.reshape(u, {b.nwin, Cb, b.Hs, b.Ws});
+      u = g.op(SM_OP_CONV, {u}, {b.nwin, Cb, b.Hs, b.Ws}, i == 0 ? "lepe0" : "lepe1");
+      u = g.reshape(u, {b.nwin, hb, d, b.S});
+      pe = g.transpose(u, {0, 1, 3, 2});
+    }
     int t = g.op(SM_OP_ATTENTION, {part[0], part[1], part[2]}, {b.nwin, hb, b.S, d}, i == 0 ? "attn0" : "attn1", {3, 3, -1});
+    if (lepe) t = g.op(SM_OP_ADD, {t, pe}, {b.nwin, hb, b.S, d}, "add_pe");
     t = g.transpose(t, {0, 2, 1, 3});
     t = g.reshape(t, {b.nwin, b.S, Cb});
     t = g.reshape(t, {B, H / b.Hs, W / b.Ws, b.Hs, b.Ws, Cb});
@@ -107,7 +127,12 @@ std::shared_ptr<CswinPlan> cswin_plan(const sm_cswin_cfg& c, std::string* err) {
     p->n_kept += st == SM_KEPT;
     if (grp == SM_ILD_FIX || grp == SM_ILI_FIX) { ++p->n_layout; p->n_eliminated += (st == SM_ELIMINATED_STORE || st == SM_ELIMINATED_LOAD); }
   }
-  if (p->n_eliminated != p->n_layout || p->n_kept != 2) { *err = "planner did not reduce the operator to its two attentions"; return nullptr; }
+  if (p->n_eliminated != p->n_layout || p->n_kept != (lepe ? 4 : 2)) {
+    char msg[160];
+    snprintf(msg, sizeof(msg), "planner did not reduce the operator to its attentions and convolutions (%d kept, %d of %d layout operators eliminated)",
+             p->n_kept, p->n_eliminated, p->n_layout);
+    *err = msg; return nullptr;
+  }
   const int es = (int)dtype_size(c.dtype);
   for (int i = 0; i < 2; ++i) {
     Branch& b = p->br[i];
@@ -128,6 +153,31 @@ std::shared_ptr<CswinPlan> cswin_plan(const sm_cswin_cfg& c, std::string* err) {
     std::vector<sm_view_op> merge{chains::permute({0, 2, 1, 3}), chains::reshape({b.nwin, b.S, Cb}), chains::reshape({B, H / b.Hs, W / b.Ws, b.Hs, b.Ws, Cb}),
                                   chains::permute({0, 1, 3, 2, 4, 5}), chains::reshape({B, L, Cb})};
     if (!make_copy({b.nwin, hb, b.S, d}, merge, es, &p->ex_tables, &b.merge, err)) return nullptr;
+    if (lepe) {
+      // the convolution kernel addresses element (image, y, x, channel) of the values at
+      // image * 3CL + (y W + x) * 3C + channel, from 2C + i C/2: the planned load map must say the same
+      const int conv = g.find(i == 0 ? "lepe0" : "lepe1");
+      sm_plan_load_map(plan, conv, 0, &m, nullptr);
+      if (!m || m->shape.size() != 4) { *err = "convolution load: no map planned"; return nullptr; }
+      const int64_t wst = W / b.Ws;                   // stripes per grid row
+      uint64_t rng = 0x9e3779b97f4a7c15ull;
+      for (int trial = 0; trial < 256; ++trial) {
+        int64_t idx[4];
+        for (int a = 0; a < 4; ++a) {
+          rng = rng * 6364136223846793005ull + 1442695040888963407ull;
+          const int64_t n = m->shape[a];
+          idx[a] = trial == 0 ? 0 : (trial == 1 ? n - 1 : (int64_t)((rng >> 33) % (uint64_t)n));
+        }
+        const int64_t win = idx[0], img = win / b.stripes, sidx = win % b.stripes;
+        const int64_t y = (sidx / wst) * b.Hs + idx[2], x = (sidx % wst) * b.Ws + idx[3];
+        if (m->at(idx) != 2 * C + i * Cb + idx[1] + img * 3 * C * L + (y * W + x) * 3 * C) { *err = "convolution load: the planned map is not the token-major view the kernel reads"; return nullptr; }
+      }
+      std::vector<sm_view_op> vi{chains::reshape({B, L, 3, C}), chains::slice(2, 2, 3), chains::reshape({B, L, C}), chains::slice(2, i * Cb, (i + 1) * Cb),
+                                 chains::permute({0, 2, 1}), chains::reshape({B, Cb, H / b.Hs, b.Hs, W / b.Ws, b.Ws}), chains::permute({0, 2, 4, 3, 5, 1}),
+                                 chains::reshape({b.nwin, b.S, Cb})};
+      if (!make_copy({B, L, 3 * C}, vi, es, &p->ex_tables, &b.v_images, err)) return nullptr;
+      if (!make_copy({b.nwin, b.S, Cb}, chains::head_split(b.nwin, b.S, hb, d), es, &p->ex_tables, &b.pe_split, err)) return nullptr;
+    }
   }
   if (g_plans.size() >= 64) g_plans.clear();
   g_plans[key] = p;
@@ -148,7 +198,8 @@ int check_cfg(const sm_cswin_cfg* c, const char* who) {
 }
 
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
-// explicit mode: per half, [3, nwin, heads/2, S, d] operands, the attention result, the merged result
+// explicit mode: per half, [3, nwin, heads/2, S, d] operands, the attention result, the merged result (5 units; with
+// the positional encoding also the values as stripe images and the encoding: 7)
 size_t half_bytes(const sm_cswin_cfg& c) { return align256((size_t)c.B * c.H * c.W * (c.C / 2) * dtype_size(c.dtype)); }
 
 }  // namespace
@@ -157,25 +208,29 @@ extern "C" size_t sm_cswin_attention_workspace_bytes(const sm_cswin_cfg* c, int 
   if (check_cfg(c, "sm_cswin_attention_workspace_bytes") != SM_OK) return 0;
   if (mode != SM_ELIDED && mode != SM_EXPLICIT) { set_error("sm_cswin_attention_workspace_bytes: unknown mode %d", mode); return 0; }
   std::string err;
-  auto plan = cswin_plan(*c, &err);
-  if (!plan) { set_error("sm_cswin_attention_workspace_bytes: %s", err.c_str()); return 0; }
+  auto plan = cswin_plan(*c, true, &err);        // the larger of the two forms
+  if (!plan || !cswin_plan(*c, false, &err)) { set_error("sm_cswin_attention_workspace_bytes: %s", err.c_str()); return 0; }
   if (mode == SM_ELIDED) return 256;       // nothing is staged (0 is this query's error value)
-  return 10 * half_bytes(*c) + plan->ex_tables.bytes;
+  return 14 * half_bytes(*c) + plan->ex_tables.bytes;
 }
 
-extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, void* out, void* ws, size_t ws_bytes, int mode, void* stream) {
+extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, const void* lepe_w, const void* lepe_b, void* out,
+                                  void* ws, size_t ws_bytes, int mode, void* stream) {
   int rc = check_cfg(c, "sm_cswin_attention");
   if (rc) return rc;
   if (!qkv || !out) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: null pointer");
   if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: unknown mode %d", mode);
   if (!aligned16(qkv) || !aligned16(out) || (ws && !aligned16(ws))) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: pointers must be 16-byte aligned");
+  if ((lepe_w == nullptr) != (lepe_b == nullptr)) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: the positional encoding needs both its weights and its bias");
+  if (lepe_w && (!aligned16(lepe_w) || !aligned16(lepe_b))) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: pointers must be 16-byte aligned");
+  const bool lepe = lepe_w != nullptr;
   std::string err;
-  auto plan = cswin_plan(*c, &err);
+  auto plan = cswin_plan(*c, lepe, &err);
   if (!plan) return fail(SM_ERR_UNSUPPORTED, "sm_cswin_attention: %s", err.c_str());
   const bool el = mode == SM_ELIDED;
   const size_t hbytes = half_bytes(*c);
   if (!el) {
-    const size_t need = 10 * hbytes + plan->ex_tables.bytes;
+    const size_t need = (lepe ? 14 : 10) * hbytes + plan->ex_tables.bytes;
     if (!ws || ws_bytes < need) return fail(SM_ERR_WORKSPACE, "sm_cswin_attention: workspace of %zu bytes, %zu needed", ws ? ws_bytes : (size_t)0, need);
   }
   count_reset();
@@ -183,14 +238,28 @@ extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, void* 
   const unsigned short* src = (const unsigned short*)qkv;
   unsigned short* dst = (unsigned short*)out;
   char* base = (char*)ws;
-  const void* tables = el ? nullptr : base + 10 * hbytes;
-  if (!el && (rc = fill_tables(plan->ex_tables, base + 10 * hbytes, stream, ~0ull))) return rc;
+  const size_t units = lepe ? 7 : 5;
+  const void* tables = el ? nullptr : base + 2 * units * hbytes;
+  if (!el && (rc = fill_tables(plan->ex_tables, base + 2 * units * hbytes, stream, ~0ull))) return rc;
+  auto conv = [&](const Branch& b, int i, const void* v, void* o, int n_img, int gh, int gw, int64_t v_img, int64_t v_tok, int64_t o_img, int64_t o_tok) -> int {
+    DwconvArgs k; std::memset(&k, 0, sizeof(k));
+    k.v = v; k.out = o; k.w = (const unsigned short*)lepe_w + (size_t)i * Cb * 9; k.bias = (const unsigned short*)lepe_b + (size_t)i * Cb;
+    k.n_img = n_img; k.H = gh; k.W = gw; k.Cn = (int)Cb; k.Hs = (int)b.Hs; k.Ws = (int)b.Ws;
+    k.v_img = v_img; k.v_tok = v_tok; k.o_img = o_img; k.o_tok = o_tok;
+    char label[96];
+    snprintf(label, sizeof(label), "dwconv3x3_bf16[%d,%d,%d,%d]", n_img, gh, gw, (int)Cb);
+    Timed tm(label, stream);
+    if (int e = launch_dwconv3x3(k, stream)) return fail(SM_ERR_DEVICE, "sm_cswin_attention: convolution launch failed (hip error %d)", e);
+    count_compute();
+    return SM_OK;
+  };
   void* merged[2] = {nullptr, nullptr};
   for (int i = 0; i < 2; ++i) {
     const Branch& b = plan->br[i];
     sm_attention_desc a; std::memset(&a, 0, sizeof(a));
     a.dtype = c->dtype; a.nb = (int)b.nwin; a.heads = (int)hb; a.nq = a.nk = (int)b.S; a.d = (int)d;
     a.scale = (float)(1.0 / std::sqrt((double)d));
+    a.accumulate = lepe ? 1 : 0;
     if (el) {
       a.kind = SM_ATT_STRIPE; a.stripes = (int)b.stripes; a.run = (int)b.run;
       const Strides6* in[3] = {&b.q, &b.k, &b.v};
@@ -204,12 +273,21 @@ extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, void* 
         return fail(SM_ERR_UNSUPPORTED, "sm_cswin_attention: the planned store is not by whole tokens");
       a.o_stride[0] = o.img / Cb * C; a.o_stride[1] = o.head; a.o_stride[2] = o.tok / Cb * C;
       a.o_stripe[0] = o.stripe / Cb * C; a.o_stripe[1] = o.runs / Cb * C;
+      // the encoding first, straight into this half's channels of the output (whole images, stripe-aware taps)
+      if (lepe && (rc = conv(b, i, src + 2 * C + i * Cb, dst + i * Cb, (int)B, c->H, c->W, 3 * C * L, 3 * C, C * L, C))) return rc;
       if ((rc = attention_checked(a, src + b.q.base, src + b.k.base, src + b.v.base, dst + i * Cb, nullptr, stream, "sm_cswin_attention"))) return rc;
     } else {
-      unsigned short* parts = (unsigned short*)(base + (size_t)i * 5 * hbytes);      // [3, nwin, heads/2, S, d]
-      unsigned short* res = (unsigned short*)(base + (size_t)i * 5 * hbytes + 3 * hbytes);
-      merged[i] = base + (size_t)i * 5 * hbytes + 4 * hbytes;
+      char* mine = base + (size_t)i * units * hbytes;
+      unsigned short* parts = (unsigned short*)mine;      // [3, nwin, heads/2, S, d]
+      unsigned short* res = (unsigned short*)(mine + 3 * hbytes);
+      merged[i] = mine + 4 * hbytes;
       if ((rc = copy_launch(b.split, tables, qkv, parts, c->dtype, stream))) return rc;
+      if (lepe) {        // values as stripe images [nwin, Hs, Ws, C/2], the convolution on them, its result head-split under the attention's
+        void* vimg = mine + 5 * hbytes; void* pe = mine + 6 * hbytes;
+        if ((rc = copy_launch(b.v_images, tables, qkv, vimg, c->dtype, stream))) return rc;
+        if ((rc = conv(b, i, vimg, pe, (int)b.nwin, (int)b.Hs, (int)b.Ws, b.S * Cb, Cb, b.S * Cb, Cb))) return rc;
+        if ((rc = copy_launch(b.pe_split, tables, pe, res, c->dtype, stream))) return rc;
+      }
       a.kind = SM_ATT_FULL;
       const int64_t per = b.nwin * hb * b.S * d;
       int64_t* st[4] = {a.q_stride, a.k_stride, a.v_stride, a.o_stride};

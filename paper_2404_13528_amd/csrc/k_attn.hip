@@ -382,7 +382,12 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
     for (int g4 = 0; g4 < 4; ++g4) {
       const int e = 32 * db + g4 * 8 + hf * 4;
       if (e < a.d) {
-        const f32x2_t x0 = {oacc[db][4 * g4] * inv, oacc[db][4 * g4 + 1] * inv}, x1 = {oacc[db][4 * g4 + 2] * inv, oacc[db][4 * g4 + 3] * inv};
+        f32x2_t x0 = {oacc[db][4 * g4] * inv, oacc[db][4 * g4 + 1] * inv}, x1 = {oacc[db][4 * g4 + 2] * inv, oacc[db][4 * g4 + 3] * inv};
+        if (a.accumulate) {                   // O += result: what is there is an addend in the output's own layout
+          const uint2 old = *(const uint2*)(orow + e);
+          x0[0] += __uint_as_float(old.x << 16); x0[1] += __uint_as_float(old.x & 0xffff0000u);
+          x1[0] += __uint_as_float(old.y << 16); x1[1] += __uint_as_float(old.y & 0xffff0000u);
+        }
         *(uint2*)(orow + e) = make_uint2(__builtin_bit_cast(unsigned, __builtin_convertvector(x0, bf16x2_t)),
                                                                     __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
       }
@@ -814,6 +819,63 @@ __global__ __launch_bounds__(64) void attn_window_f32_kernel(sm_attention_desc a
     for (int j = 0; j < a.nk; ++j) acc = fmaf(ss[i * 65 + j], vs[j * 65 + e], acc);
     op[(int64_t)i * a.o_stride[2] + e] = acc * inv;
   }
+}
+
+// Depth-wise 3 x 3 cross-correlation on a token-major grid: one thread per (token, 8 channels); the 72 weights of its
+// channels are 144 contiguous bytes.  Memory-bound: every value is read once from HBM and eight more times from cache.
+__global__ __launch_bounds__(256) void dwconv3x3_kernel(DwconvArgs a, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int cv = a.Cn >> 3;
+  const int c = (int)(idx % cv) * 8;
+  const int64_t t = idx / cv;
+  const int hw = a.H * a.W;
+  const int img = (int)(t / hw), p = (int)(t - (int64_t)img * hw);
+  const int y = p / a.W, x = p - y * a.W;
+  const int y_lo = (y / a.Hs) * a.Hs, x_lo = (x / a.Ws) * a.Ws;        // the token's stripe
+  const bf16_t* vb = (const bf16_t*)a.v + (int64_t)img * a.v_img + c;
+  float wv[72];
+  {
+    const au32x4* wp = (const au32x4*)((const bf16_t*)a.w + (int64_t)c * 9);
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+      const au32x4 u = wp[i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { wv[8 * i + 2 * j] = __uint_as_float(u[j] << 16); wv[8 * i + 2 * j + 1] = __uint_as_float(u[j] & 0xffff0000u); }
+    }
+  }
+  float acc[8];
+  {
+    const au32x4 u = *(const au32x4*)((const bf16_t*)a.bias + c);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { acc[2 * j] = __uint_as_float(u[j] << 16); acc[2 * j + 1] = __uint_as_float(u[j] & 0xffff0000u); }
+  }
+#pragma unroll
+  for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+    for (int dx = 0; dx < 3; ++dx) {
+      const int yy = y + dy - 1, xx = x + dx - 1;
+      if (yy < y_lo || yy >= y_lo + a.Hs || xx < x_lo || xx >= x_lo + a.Ws) continue;      // beyond the stripe: zero
+      const au32x4 u = *(const au32x4*)(vb + (int64_t)(yy * a.W + xx) * a.v_tok);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        acc[2 * j] = fmaf(__uint_as_float(u[j] << 16), wv[(2 * j) * 9 + dy * 3 + dx], acc[2 * j]);
+        acc[2 * j + 1] = fmaf(__uint_as_float(u[j] & 0xffff0000u), wv[(2 * j + 1) * 9 + dy * 3 + dx], acc[2 * j + 1]);
+      }
+    }
+  au32x4 r;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const f32x2_t pr = {acc[2 * j], acc[2 * j + 1]};
+    r[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2_t));
+  }
+  *(au32x4*)((bf16_t*)a.out + (int64_t)img * a.o_img + (int64_t)p * a.o_tok + c) = r;
+}
+int launch_dwconv3x3(const DwconvArgs& a, void* stream) {
+  const int64_t total = (int64_t)a.n_img * a.H * a.W * (a.Cn / 8);
+  if (total == 0) return 0;
+  dwconv3x3_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(a, total);
+  return (int)hipGetLastError();
 }
 
 int launch_attention(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o,

@@ -16,6 +16,15 @@ int launch_gather_add(const MapProg& prog, int64_t numel, int vec_elems, const v
 int launch_empty(void* stream);
 
 // row copies: dst row r (inner contiguous elements) = src[rows(r) ...] (+ addend row r); rows(r) keeps 16-byte alignment
+// Depth-wise 3 x 3 cross-correlation over the token grid of n_img images of H x W tokens with Cn channels (bf16):
+// element (img, y, x, c) of v / out at img * *_img + (y * W + x) * *_tok + c; w [Cn][3][3], bias [Cn].  A tap
+// contributes only when it lies in the token's own Hs x Ws stripe (Hs = H, Ws = W: plain zero padding).
+struct DwconvArgs {
+  const void* v; void* out; const void* w; const void* bias;
+  int n_img, H, W, Cn, Hs, Ws;
+  int64_t v_img, v_tok, o_img, o_tok;
+};
+int launch_dwconv3x3(const DwconvArgs& a, void* stream);      // Cn a multiple of 8
 // out [rows, 2 * cols] = [a | b] along the last axis; cols_bytes (of one input row) a multiple of 16
 int launch_concat2_cols(const void* a, const void* b, void* out, int64_t rows, int cols_bytes, void* stream);
 int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const void* src, const void* addend, void* dst, int dtype, void* stream);

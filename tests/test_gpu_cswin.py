@@ -21,15 +21,20 @@ CASES = [
 ]
 
 
-def run_case(B, H, W, Cc, heads, sw, mode, seed=0):
+def run_case(B, H, W, Cc, heads, sw, mode, seed=0, lepe=False):
     qkv = Wl.cswin_qkv_case(B, H, W, Cc, seed=seed, bf16=True)
-    want = CS.cross_window_attention(to_np(qkv), B, H, W, Cc, heads, sw)
+    pe = Wl.cswin_lepe_params(Cc, seed=seed, bf16=True) if lepe else None
+    want = CS.cross_window_attention(to_np(qkv), B, H, W, Cc, heads, sw, *([to_np(t) for t in pe] if lepe else []))
     op = sm.CswinAttention(B, H, W, Cc, heads, sw, mode)
     dev = qkv.to(torch.bfloat16).cuda()
     before = dev.clone()
-    out = op(dev)
+    out = torch.full((B, H * W, Cc), float("nan"), dtype=torch.bfloat16, device="cuda")      # nothing of it may survive
+    out = op(dev, out=out, lepe=[t.to(torch.bfloat16).cuda() for t in pe] if lepe else None)
     torch.cuda.synchronize()
-    assert sm.launch_counts() == ((2, 0) if mode == sm.SM_ELIDED else (2, 5))
+    if lepe:
+        assert sm.launch_counts() == ((4, 0) if mode == sm.SM_ELIDED else (4, 9))
+    else:
+        assert sm.launch_counts() == ((2, 0) if mode == sm.SM_ELIDED else (2, 5))
     assert torch.equal(dev, before)
     assert_bf16_close(out.reshape(B * H * W, Cc), want.reshape(B * H * W, Cc), what="cross-window attention")
     return out
@@ -39,6 +44,38 @@ def run_case(B, H, W, Cc, heads, sw, mode, seed=0):
 @pytest.mark.parametrize("B,H,W,Cc,heads,sw", CASES)
 def test_matches_the_oracle(B, H, W, Cc, heads, sw, mode):
     run_case(B, H, W, Cc, heads, sw, mode, seed=H + sw)
+
+
+@pytest.mark.parametrize("mode", [sm.SM_ELIDED, sm.SM_EXPLICIT])
+@pytest.mark.parametrize("B,H,W,Cc,heads,sw", CASES)
+def test_with_positional_encoding_matches_the_oracle(B, H, W, Cc, heads, sw, mode):
+    run_case(B, H, W, Cc, heads, sw, mode, seed=H + sw + 1, lepe=True)
+
+
+def test_positional_encoding_is_visible_and_its_planted_mistake_shows():
+    B, H, W, Cc, heads, sw = 2, 14, 14, 64, 2, 7
+    out = run_case(B, H, W, Cc, heads, sw, sm.SM_ELIDED, seed=4, lepe=True)
+    qkv = to_np(Wl.cswin_qkv_case(B, H, W, Cc, seed=4, bf16=True))
+    w, b = [to_np(t) for t in Wl.cswin_lepe_params(Cc, seed=4, bf16=True)]
+    for wrong in (CS.cross_window_attention(qkv, B, H, W, Cc, heads, sw),                              # encoding dropped
+                  CS.cross_window_attention(qkv, B, H, W, Cc, heads, sw, w[:, ::-1, ::-1].copy(), b)):     # kernel flipped
+        with pytest.raises(AssertionError):
+            assert_bf16_close(out.reshape(B * H * W, Cc), wrong.reshape(B * H * W, Cc), what="planted mistake")
+
+
+def test_attention_accumulates_into_its_output():
+    nb, h, n, d = 3, 2, 150, 32
+    g = torch.Generator().manual_seed(2)
+    q, k, v, o0 = [torch.randn(nb, h, n, d, generator=g).to(torch.bfloat16) for _ in range(4)]
+    want, _ = O.attention(to_np(q), to_np(k), to_np(v), d ** -0.5, causal=True)
+    out = o0.cuda().clone()
+    sm.attention(q.cuda(), k.cuda(), v.cuda(), kind="causal", out=out, accumulate=True)
+    torch.cuda.synchronize()
+    assert_bf16_close(out.reshape(nb * h * n, d), (want + to_np(o0)).reshape(nb * h * n, d), what="accumulating attention")
+    with pytest.raises(sm.SmError):        # the window kernels have no accumulating form
+        t = torch.zeros(169, 2, dtype=torch.bfloat16, device="cuda")
+        w = torch.zeros(1, 2, 49, 32, dtype=torch.bfloat16, device="cuda")
+        sm.attention(w, w, w, kind="window", rpb_table=t, window=7, H=7, W=7, accumulate=True)
 
 
 def test_modes_agree_and_repeat():

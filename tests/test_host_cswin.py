@@ -18,9 +18,10 @@ def test_the_operator_plans_down_to_two_attentions(shape):
     el = lib.sm_cswin_attention_workspace_bytes(C.byref(c), sm.SM_ELIDED)
     ex = lib.sm_cswin_attention_workspace_bytes(C.byref(c), sm.SM_EXPLICIT)
     assert el > 0, lib.sm_last_error()
-    # explicit: per half of the channels, the three partitioned operands, the attention result and the merged result
+    # explicit: per half of the channels, the three partitioned operands, the attention result and the merged result,
+    # and for the positional encoding the values as stripe images and the encoding itself
     tokens = c.B * c.H * c.W
-    assert ex >= 5 * tokens * c.C * 2 and ex < 5 * tokens * c.C * 2 + (1 << 20) + 64 * tokens
+    assert ex >= 7 * tokens * c.C * 2 and ex < 7 * tokens * c.C * 2 + (1 << 20) + 64 * tokens
 
 
 def test_refusals():
@@ -30,7 +31,7 @@ def test_refusals():
         assert lib.sm_cswin_attention_workspace_bytes(C.byref(c), sm.SM_ELIDED) == 0
         assert len(lib.sm_last_error()) > 0
     assert lib.sm_cswin_attention_workspace_bytes(C.byref(cfg()), 5) == 0
-    assert lib.sm_cswin_attention(C.byref(cfg()), None, None, None, C.c_size_t(0), sm.SM_ELIDED, None) < 0
+    assert lib.sm_cswin_attention(C.byref(cfg()), None, None, None, None, None, C.c_size_t(0), sm.SM_ELIDED, None) < 0
     f32 = cfg(); f32.dtype = sm.SM_F32
     assert lib.sm_cswin_attention_workspace_bytes(C.byref(f32), sm.SM_ELIDED) == 0
 
