@@ -93,11 +93,11 @@ def kernel_model(label):
     if m:
         R, C = int(m.group(2)), int(m.group(3))
         return (2 * R * C + 2 * C) * e, 8.0 * R * C
-    m = re.match(r"attention_(\w+?)_\w+\[(\d+),(\d+),(\d+),(\d+),(\d+)\]", label)
-    if m:
+    m = re.match(r"attention_(\w+?)_\w+\[(\d+),(\d+),(\d+),(\d+),(\d+)\](\+acc)?", label)
+    if m:      # q read, o written, k and v read ("+acc": o read as well)
         nb, h, nq, nk, d = [int(m.group(i)) for i in range(2, 7)]
         fl = 4.0 * nb * h * nq * nk * d * (0.5 if m.group(1) == "causal" else 1.0)
-        return nb * h * (2 * nq + 2 * nk) * d * e, fl
+        return nb * h * ((3 if m.group(7) else 2) * nq + 2 * nk) * d * e, fl
     m = re.match(r"copy_\w+\[(\d+)\](.*)", label)
     if m:
         n = int(m.group(1))

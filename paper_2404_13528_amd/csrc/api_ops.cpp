@@ -115,8 +115,8 @@ int attention_checked(const sm_attention_desc& d, const void* q, const void* k, 
     if (d.nq > 64 || d.d > 64) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 window attention needs window^2 <= 64 and head size <= 64", who);
   }
   char label[128];
-  snprintf(label, sizeof(label), "attention_%s_%s[%d,%d,%d,%d,%d]", d.kind == SM_ATT_WINDOW ? "window" : (d.kind == SM_ATT_CAUSAL ? "causal" : (d.kind == SM_ATT_STRIPE ? "stripe" : "full")),
-           d.dtype == SM_F32 ? "f32" : "bf16", d.nb, d.heads, d.nq, d.nk, d.d);
+  snprintf(label, sizeof(label), "attention_%s_%s[%d,%d,%d,%d,%d]%s", d.kind == SM_ATT_WINDOW ? "window" : (d.kind == SM_ATT_CAUSAL ? "causal" : (d.kind == SM_ATT_STRIPE ? "stripe" : "full")),
+           d.dtype == SM_F32 ? "f32" : "bf16", d.nb, d.heads, d.nq, d.nk, d.d, d.accumulate ? "+acc" : "");
   Timed tm(label, stream);
   int rc = launch_attention(d, q, k, v, o, table, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);

@@ -823,8 +823,11 @@ __global__ __launch_bounds__(64) void attn_window_f32_kernel(sm_attention_desc a
 
 // Depth-wise 3 x 3 cross-correlation on a token-major grid: one thread per (token, 8 channels); the 72 weights of its
 // channels are 144 contiguous bytes.  Memory-bound: every value is read once from HBM and eight more times from cache.
+// Workgroups are dealt to the 8 XCDs round-robin: XCD x takes the x-th eighth of the tokens, so that the rows above
+// and below a token are fetched into the same L2 as the token's own.
 __global__ __launch_bounds__(256) void dwconv3x3_kernel(DwconvArgs a, int64_t total) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t block = (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);      // the grid is a multiple of 8
+  const int64_t idx = block * 256 + threadIdx.x;
   if (idx >= total) return;
   const int cv = a.Cn >> 3;
   const int c = (int)(idx % cv) * 8;
@@ -874,7 +877,8 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(DwconvArgs a, int64_t to
 int launch_dwconv3x3(const DwconvArgs& a, void* stream) {
   const int64_t total = (int64_t)a.n_img * a.H * a.W * (a.Cn / 8);
   if (total == 0) return 0;
-  dwconv3x3_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(a, total);
+  const int64_t blocks = ((total + 255) / 256 + 7) / 8 * 8;
+  dwconv3x3_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(a, total);
   return (int)hipGetLastError();
 }
 
