@@ -69,3 +69,20 @@ def cross_window_attention(qkv, B, H, W, C, heads, sw, lepe_w=None, lepe_b=None)
         halves.append(branch_attention(sl[0], sl[1], sl[2], B, H, W, heads // 2, Hs, Ws,
                                        None if lepe_w is None else lepe_w[cs], None if lepe_w is None else lepe_b[cs]))
     return V.concat(halves, 2)
+
+
+def cswin_block(x, p, B, H, W, C, heads, sw, want_all=False):
+    """One CSwin block, x [B, H*W, C] -> [B, H*W, C] (the public definition: LayerNorm eps 1e-5, fused q | k | v Linear
+    with bias, cross-shaped window attention with its positional encoding, output Linear, residual, LayerNorm, MLP of
+    width ratio * C with the exact GELU, residual).  p: ln1_g, ln1_b, wqkv [3C, C], bqkv, lepe_w [C, 3, 3], lepe_b,
+    wproj, bproj, ln2_g, ln2_b, w1, b1, w2, b2."""
+    n1 = O.layer_norm(x, p["ln1_g"], p["ln1_b"])
+    qkv = O.linear(n1, p["wqkv"], p["bqkv"])
+    a = cross_window_attention(qkv, B, H, W, C, heads, sw, p["lepe_w"], p["lepe_b"])
+    x1 = x + O.linear(a, p["wproj"], p["bproj"])
+    n2 = O.layer_norm(x1, p["ln2_g"], p["ln2_b"])
+    hid = O.gelu(O.linear(n2, p["w1"], p["b1"]))
+    y = x1 + O.linear(hid, p["w2"], p["b2"])
+    if want_all:
+        return {"qkv": qkv, "attn": a, "x1": x1, "y": y}
+    return y

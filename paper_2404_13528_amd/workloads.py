@@ -134,6 +134,19 @@ def cswin_lepe_params(C, seed=0, bf16=True, std=0.2):
     return dr.weight(C, 3, 3), dr.weight(C)
 
 
+def cswin_block_case(B, H, W, C, mlp_ratio=4, seed=0, bf16=True, std=STD, in_std=1.0, lepe_std=0.2):
+    """Input tokens [B, H*W, C] and the parameters of one CSwin block (the positional encoding's 3 x 3 weights drawn
+    wider than the Linears', so that the encoding is a visible share of the attention branch)."""
+    dr = Draw(seed, bf16, std)
+    x = dr.normal(B, H * W, C, std=in_std)
+    p = {"ln1_g": dr.gain(C), "ln1_b": dr.weight(C), "wqkv": dr.weight(3 * C, C), "bqkv": dr.weight(3 * C)}
+    p["lepe_w"], p["lepe_b"] = dr.normal(C, 3, 3, std=lepe_std), dr.weight(C)
+    p.update({"wproj": dr.weight(C, C), "bproj": dr.weight(C), "ln2_g": dr.gain(C), "ln2_b": dr.weight(C),
+              "w1": dr.weight(mlp_ratio * C, C), "b1": dr.weight(mlp_ratio * C),
+              "w2": dr.weight(C, mlp_ratio * C), "b2": dr.weight(C)})
+    return x, p
+
+
 def fanout_case(D1, D2, D3, Kin, Cout, seed=0, bf16=True):
     """Operands of the Fig. 4 graph: activations N(0,1), weights scaled so that every output is O(1)."""
     dr = Draw(seed, bf16)

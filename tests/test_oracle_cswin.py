@@ -110,3 +110,20 @@ def test_positional_encoding_stops_at_the_stripe_border():
     want_h = np.zeros((H, W)); want_h[2:4, 2:5] = 1.0            # rows of the stripe only, columns 2..4
     assert np.allclose(pe[..., 0], want_v) and np.allclose(pe[..., 1], want_v)
     assert np.allclose(pe[..., 2], want_h) and np.allclose(pe[..., 3], want_h)
+
+
+@pytest.mark.parametrize("std", [0.02, 0.2])
+def test_block_matches_an_assembly_from_library_routines(std):
+    """LayerNorm, Linear and GELU from torch; the attention with its encoding from the token-by-token definition above."""
+    from util import np_params
+    B, H, W, C, heads, sw = 2, 4, 6, 16, 2, 2
+    x, p = Wl.cswin_block_case(B, H, W, C, seed=31, bf16=False, std=std)
+    got = CS.cswin_block(to_np(x), np_params(p), B, H, W, C, heads, sw)
+    t = {k: v.double() for k, v in p.items()}
+    xt = x.double()
+    qkv = F.linear(F.layer_norm(xt, (C,), t["ln1_g"], t["ln1_b"], 1e-5), t["wqkv"], t["bqkv"])
+    a = torch.from_numpy(by_definition(qkv.numpy(), B, H, W, C, heads, sw, lepe=(t["lepe_w"].numpy(), t["lepe_b"].numpy())))
+    x1 = xt + F.linear(a, t["wproj"], t["bproj"])
+    y = x1 + F.linear(F.gelu(F.linear(F.layer_norm(x1, (C,), t["ln2_g"], t["ln2_b"], 1e-5), t["w1"], t["b1"])), t["w2"], t["b2"])
+    assert np.abs(got - y.numpy()).max() < 1e-10
+    assert np.abs(got - to_np(x)).max() > 1e-2              # the branches contribute
