@@ -291,6 +291,16 @@ def build_config(k, sm, torch, Wl):
                 "B=64, 14x14 tokens, 256 channels, 8 heads x 32 (4 in vertical, 4 in horizontal stripes of width 7), from the fused "
                 "q|k|v projection to the merged output", "images/s", B,
                 {n: (lambda o=o: o(qkv, out=y, lepe=pe)) for n, o in ops.items()}, None, "bf16")
+    if k == 10:    # ... and the whole CSwin block around it, at the same shape (third stage of CSwin-T)
+        B, H, W, C, h, sw = 64, 14, 14, 256, 8, 7
+        x, p = Wl.cswin_block_case(B, H, W, C)
+        dp, xd = dev(p, bf), x.to(bf).cuda()
+        y = torch.empty_like(xd)
+        blk = {"elided": sm.CswinBlock(B, H, W, C, h, sw, dp, sm.SM_ELIDED), "explicit": sm.CswinBlock(B, H, W, C, h, sw, dp, sm.SM_EXPLICIT),
+               "elided_per_op": sm.CswinBlock(B, H, W, C, h, sw, dp, sm.SM_ELIDED, fuse=False),
+               "explicit_per_op": sm.CswinBlock(B, H, W, C, h, sw, dp, sm.SM_EXPLICIT, fuse=False)}
+        return ("extra: one CSwin-T stage-3 block, bf16, B=64, 14x14 tokens, 256 channels, 8 heads x 32, stripes 7 wide, MLP 4x",
+                "images/s", B, {n: (lambda b=b: b(xd, out=y)) for n, b in blk.items()}, None, "bf16")
     raise ValueError(k)
 
 
@@ -351,7 +361,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json (6: ViT block, 7: Fig. 4 graph, 8: decode step, 9: CSwin attention); 0 = all")
+    ap.add_argument("--config", type=int, default=0, help="1..5: only this configuration of BASELINE.json (6: ViT block, 7: Fig. 4 graph, 8: decode step, 9: CSwin attention, 10: CSwin block); 0 = all")
     ap.add_argument("--variants", default="", help="comma-separated subset of the variants (elided, explicit, elided_per_op, explicit_per_op)")
     ap.add_argument("--kernels", action="store_true", help="include every variant's per-kernel table in the JSON line (long)")
     ap.add_argument("--no-autotune", action="store_true",
@@ -384,7 +394,7 @@ def main():
 
     traffic = measured_traffic()
     HEAD = 3
-    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6, 7, 8, 9]
+    which = [a.config] if a.config else [3, 1, 2, 4, 5, 6, 7, 8, 9, 10]
     want = [v for v in a.variants.split(",") if v]
     configs, oracle_sample, calib = {}, None, None
     for k in which:

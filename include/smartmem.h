@@ -452,6 +452,24 @@ size_t sm_cswin_attention_workspace_bytes(const sm_cswin_cfg*, int mode);
 int sm_cswin_attention(const sm_cswin_cfg*, const void* qkv, const void* lepe_w, const void* lepe_b, void* out,
                        void* ws, size_t ws_bytes, int mode, void* stream);
 
+/* One CSwin block (Tables 1, 7): y = x1 + MLP(LayerNorm(x1)), x1 = x + proj(cross-shaped window attention of the fused
+ * q | k | v Linear of LayerNorm(x)); x, y [B, H*W, C] (device, bf16).  Every layout operator of the block sits inside
+ * the attention operator above (mode selects its elided or explicit form); around it the block is LayerNorm + Linear
+ * (one kernel: the norm folded into the Linear's load, or the packed-weight Linear when qkv_packed is given), and the
+ * output Linear + residual + LayerNorm + MLP + residual (one kernel when mlp_packed and proj_packed are given and
+ * sm_mlp_proj_supported(C, mlp_ratio * C), else the Linears one by one).  Weights as in sm_swin_weights ([out, in],
+ * packed forms from sm_mlp_pack / sm_linear_pack, optional); lepe_w [C, 3, 3], lepe_b [C].  Limits as for
+ * sm_cswin_attention, C a multiple of 16.  Workspace from sm_cswin_block_workspace_bytes, caller-owned; nothing is
+ * allocated. */
+typedef struct { int32_t dtype, B, H, W, C, heads, sw, mlp_ratio; float eps; } sm_cswin_block_cfg;
+typedef struct {
+  const void *ln1_g, *ln1_b, *wqkv, *bqkv, *lepe_w, *lepe_b, *wproj, *bproj, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+  const void *mlp_packed, *proj_packed, *qkv_packed;
+} sm_cswin_weights;
+size_t sm_cswin_block_workspace_bytes(const sm_cswin_block_cfg*, int mode);
+int sm_cswin_block(const sm_cswin_block_cfg*, const sm_cswin_weights*, const void* x, void* y, void* ws, size_t ws_bytes,
+                   int mode, void* stream);
+
 /* A whole producer-consumer chain (Sec. 3.2: elimination and fusion alternate
  * over rounds, so removed layout operators leave compute operators adjacent):
  * A Swin chain: optional patch embedding (NCHW image, patch x patch stride

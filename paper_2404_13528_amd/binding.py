@@ -65,6 +65,18 @@ class CswinCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("dtype", "B", "H", "W", "C", "heads", "sw")]
 
 
+class CswinBlockCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("dtype", "B", "H", "W", "C", "heads", "sw", "mlp_ratio")] + [("eps", C.c_float)]
+
+
+CSWIN_WEIGHT_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "lepe_w", "lepe_b", "wproj", "bproj",
+                      "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+
+class CswinWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in CSWIN_WEIGHT_NAMES + ("mlp_packed", "proj_packed", "qkv_packed")]
+
+
 class SwinCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "H", "W", "C", "heads", "window", "shift", "mlp_ratio", "dtype")] + \
                [("eps", C.c_float)]
@@ -118,7 +130,7 @@ def lib():
         L.sm_map_numel.restype = C.c_int64
         for f in ("sm_fanout_graph_workspace_bytes", "sm_swin_block_workspace_bytes", "sm_attn_block_workspace_bytes", "sm_run_chain_workspace_bytes",
                   "sm_swin_block_static_max_bytes", "sm_decode_step_workspace_bytes",
-                  "sm_cswin_attention_workspace_bytes"):
+                  "sm_cswin_attention_workspace_bytes", "sm_cswin_block_workspace_bytes"):
             getattr(L, f).restype = C.c_size_t
         _lib = L
     return _lib
@@ -781,6 +793,31 @@ class CswinAttention:
         check(lib().sm_cswin_attention(C.byref(self.cfg), _ptr(qkv), _ptr(w), _ptr(b), _ptr(out), _ptr(self.ws),
                                        C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_cswin_attention")
         return out
+
+
+class CswinBlock:
+    """sm_cswin_block; params follow workloads.cswin_block_case (device tensors, bf16).  The MLP, projection and QKV
+    weights are packed here, once, where a fused kernel exists for the width (fuse=False: one kernel per Linear)."""
+
+    def __init__(self, B, H, W, Cc, heads, sw, params, mode=SM_ELIDED, mlp_ratio=4, eps=1e-5, fuse=True):
+        import torch
+        self.cfg = CswinBlockCfg(SM_BF16, B, H, W, Cc, heads, sw, mlp_ratio, eps)
+        self.mode = mode
+        self.params = params
+        self.packed = _packed_mlp(params, Cc, mlp_ratio, torch.bfloat16, fuse)
+        self.w = CswinWeights(*([params[n].data_ptr() for n in CSWIN_WEIGHT_NAMES] +
+                                [t.data_ptr() if t is not None else None for t in self.packed]))
+        n = lib().sm_cswin_block_workspace_bytes(C.byref(self.cfg), mode)
+        if n == 0:
+            raise SmError("sm_cswin_block_workspace_bytes: " + lib().sm_last_error().decode())
+        self.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def __call__(self, x, out=None, stream=None):
+        import torch
+        y = torch.empty_like(x) if out is None else out
+        check(lib().sm_cswin_block(C.byref(self.cfg), C.byref(self.w), _ptr(x), _ptr(y), _ptr(self.ws),
+                                   C.c_size_t(self.ws.numel()), self.mode, _stream(stream)), "sm_cswin_block")
+        return y
 
 
 class AttnBlock:

@@ -214,8 +214,17 @@ extern "C" size_t sm_cswin_attention_workspace_bytes(const sm_cswin_cfg* c, int 
   return 14 * half_bytes(*c) + plan->ex_tables.bytes;
 }
 
+namespace {
+int cswin_attention_impl(const sm_cswin_cfg* c, const void* qkv, const void* lepe_w, const void* lepe_b, void* out,
+                         void* ws, size_t ws_bytes, int mode, void* stream, bool reset_counts);
+}
 extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, const void* lepe_w, const void* lepe_b, void* out,
                                   void* ws, size_t ws_bytes, int mode, void* stream) {
+  return cswin_attention_impl(c, qkv, lepe_w, lepe_b, out, ws, ws_bytes, mode, stream, true);
+}
+namespace {
+int cswin_attention_impl(const sm_cswin_cfg* c, const void* qkv, const void* lepe_w, const void* lepe_b, void* out,
+                         void* ws, size_t ws_bytes, int mode, void* stream, bool reset_counts) {
   int rc = check_cfg(c, "sm_cswin_attention");
   if (rc) return rc;
   if (!qkv || !out) return fail(SM_ERR_INVALID_ARG, "sm_cswin_attention: null pointer");
@@ -233,7 +242,7 @@ extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, const 
     const size_t need = (lepe ? 14 : 10) * hbytes + plan->ex_tables.bytes;
     if (!ws || ws_bytes < need) return fail(SM_ERR_WORKSPACE, "sm_cswin_attention: workspace of %zu bytes, %zu needed", ws ? ws_bytes : (size_t)0, need);
   }
-  count_reset();
+  if (reset_counts) count_reset();
   const int64_t B = c->B, L = (int64_t)c->H * c->W, C = c->C, Cb = C / 2, hb = c->heads / 2, d = C / c->heads;
   const unsigned short* src = (const unsigned short*)qkv;
   unsigned short* dst = (unsigned short*)out;
@@ -305,4 +314,114 @@ extern "C" int sm_cswin_attention(const sm_cswin_cfg* c, const void* qkv, const 
     count_copy();
   }
   return SM_OK;
+}
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// sm_cswin_block
+// ---------------------------------------------------------------------------
+namespace {
+
+sm_cswin_cfg attn_cfg(const sm_cswin_block_cfg& c) { return sm_cswin_cfg{c.dtype, c.B, c.H, c.W, c.C, c.heads, c.sw}; }
+int check_block(const sm_cswin_block_cfg* c, const char* who) {
+  if (!c) return fail(SM_ERR_INVALID_ARG, "%s: null configuration", who);
+  const sm_cswin_cfg a = attn_cfg(*c);
+  if (int rc = check_cfg(&a, who)) return rc;
+  if (c->C % 16) return fail(SM_ERR_SHAPE, "%s: C must be a multiple of 16", who);
+  if (c->mlp_ratio < 1 || c->mlp_ratio > 8 || !(c->eps > 0.f)) return fail(SM_ERR_SHAPE, "%s: bad MLP ratio or epsilon", who);
+  return SM_OK;
+}
+size_t token_bytes(const sm_cswin_block_cfg& c) { return align256((size_t)c.B * c.H * c.W * c.C * dtype_size(c.dtype)); }
+// q | k | v (3 units), attention output, x1, a normalised copy, the MLP's hidden tensor
+size_t block_act_bytes(const sm_cswin_block_cfg& c) { return (6 + (size_t)c.mlp_ratio) * token_bytes(c); }
+
+int norm_rows(const void* x, const void* g, const void* b, void* y, int64_t rows, int C, float eps, int dt, void* stream) {
+  NormArgs a; std::memset(&a, 0, sizeof(a));
+  a.x = x; a.gamma = g; a.beta = b; a.y = y; a.rows = rows; a.C = C; a.eps = eps; a.rms = 0; a.dtype = dt; a.nseg = 1;
+  a.load = identity_rows(C); a.store = identity_rows(C);
+  return norm_checked(a, stream, "sm_cswin_block(norm)");
+}
+// ln_g != null: LayerNorm of A's rows folded into the load
+int linear_rows(const void* A, const void* W, const void* bias, const void* res, void* Cc, int64_t M, int N, int K, int dt, int act,
+                void* stream, const void* ln_g = nullptr, const void* ln_b = nullptr, float eps = 0.f) {
+  GemmArgs g; std::memset(&g, 0, sizeof(g));
+  g.A = A; g.W = W; g.bias = bias; g.residual = res; g.C = Cc; g.M = M; g.N = N; g.K = K; g.dtype = dt; g.act = act; g.ldw = K;
+  if (ln_g) { g.norm = 1; g.norm_gamma = ln_g; g.norm_beta = ln_b; g.norm_eps = eps; }
+  g.a_rows = identity_rows(K); g.c_rows = identity_rows(N);
+  return gemm_checked(g, stream, "sm_cswin_block(linear)");
+}
+// the norm is folded into the Linear while the Linear has few column tiles (it is repeated per column tile)
+bool fold(int n_cols) { return n_cols <= 512; }
+
+}  // namespace
+
+extern "C" size_t sm_cswin_block_workspace_bytes(const sm_cswin_block_cfg* c, int mode) {
+  if (check_block(c, "sm_cswin_block_workspace_bytes") != SM_OK) return 0;
+  const sm_cswin_cfg a = attn_cfg(*c);
+  const size_t inner = sm_cswin_attention_workspace_bytes(&a, mode);
+  if (inner == 0) return 0;
+  return block_act_bytes(*c) + inner;
+}
+
+extern "C" int sm_cswin_block(const sm_cswin_block_cfg* c, const sm_cswin_weights* wt, const void* x, void* y, void* ws, size_t ws_bytes,
+                              int mode, void* stream) {
+  int rc = check_block(c, "sm_cswin_block");
+  if (rc) return rc;
+  if (!wt || !x || !y || !ws) return fail(SM_ERR_INVALID_ARG, "sm_cswin_block: null pointer");
+  if (mode != SM_ELIDED && mode != SM_EXPLICIT) return fail(SM_ERR_INVALID_ARG, "sm_cswin_block: unknown mode %d", mode);
+  const void* need_w[] = {wt->ln1_g, wt->ln1_b, wt->wqkv, wt->bqkv, wt->lepe_w, wt->lepe_b, wt->wproj, wt->bproj, wt->ln2_g, wt->ln2_b, wt->w1, wt->b1, wt->w2, wt->b2};
+  for (const void* p : need_w) if (!p || !aligned16(p)) return fail(SM_ERR_INVALID_ARG, "sm_cswin_block: a weight is null or misaligned");
+  if (!aligned16(x) || !aligned16(y) || !aligned16(ws)) return fail(SM_ERR_INVALID_ARG, "sm_cswin_block: pointers must be 16-byte aligned");
+  const sm_cswin_cfg acfg = attn_cfg(*c);
+  const size_t inner = sm_cswin_attention_workspace_bytes(&acfg, mode);
+  if (inner == 0) return SM_ERR_UNSUPPORTED;          // message set by the query
+  const size_t act = block_act_bytes(*c);
+  if (ws_bytes < act + inner) return fail(SM_ERR_WORKSPACE, "sm_cswin_block: workspace of %zu bytes, %zu needed", ws_bytes, act + inner);
+  count_reset();
+  const int64_t T = (int64_t)c->B * c->H * c->W;
+  const int C = c->C, Hd = c->mlp_ratio * C, dt = c->dtype;
+  const size_t tc = token_bytes(*c);
+  char* base = (char*)ws;
+  void* qkv = base; void* att = base + 3 * tc; void* x1 = base + 4 * tc; void* nbuf = base + 5 * tc; void* hid = base + 6 * tc;
+  void* inner_ws = base + act;
+
+  // LayerNorm + fused q | k | v Linear
+  if (wt->qkv_packed && lin32_supported(3 * C, C, dt)) {
+    Lin32Args a; std::memset(&a, 0, sizeof(a));
+    a.X = x; a.Wp = wt->qkv_packed; a.bias = wt->bqkv; a.Y = qkv; a.M = T; a.N = 3 * C; a.K = C; a.act = SM_ACT_NONE;
+    a.norm = 1; a.norm_eps = c->eps; a.norm_gamma = wt->ln1_g; a.norm_beta = wt->ln1_b;
+    a.x_rows = identity_rows(C); a.y_rows = identity_rows(3 * C);
+    if ((rc = lin32_checked(a, stream, "sm_cswin_block(ln1+qkv)"))) return rc;
+  } else if (fold(3 * C)) {
+    if ((rc = linear_rows(x, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, stream, wt->ln1_g, wt->ln1_b, c->eps))) return rc;
+  } else {
+    if ((rc = norm_rows(x, wt->ln1_g, wt->ln1_b, nbuf, T, C, c->eps, dt, stream))) return rc;
+    if ((rc = linear_rows(nbuf, wt->wqkv, wt->bqkv, nullptr, qkv, T, 3 * C, C, dt, SM_ACT_NONE, stream))) return rc;
+  }
+  // every layout operator of the block: elided or explicit
+  if ((rc = cswin_attention_impl(&acfg, qkv, wt->lepe_w, wt->lepe_b, att, inner_ws, inner, mode, stream, false))) return rc;
+  // output Linear + residual + LayerNorm + MLP + residual
+  if (wt->proj_packed && wt->mlp_packed && mlp_proj_supported(C, Hd, dt)) {
+    MlpArgs a; std::memset(&a, 0, sizeof(a));
+    a.X = att; a.Wp = wt->mlp_packed; a.b1 = wt->b1; a.b2 = wt->b2; a.Y = y; a.M = T; a.C = C; a.Hd = Hd;
+    a.norm = 1; a.norm_eps = c->eps; a.norm_gamma = wt->ln2_g; a.norm_beta = wt->ln2_b;
+    a.Wproj_p = wt->proj_packed; a.bproj = wt->bproj; a.resid0 = x;
+    a.x_rows = identity_rows(C); a.y_rows = identity_rows(C);
+    return mlp_checked(a, stream, "sm_cswin_block(proj+mlp)");
+  }
+  if ((rc = linear_rows(att, wt->wproj, wt->bproj, x, x1, T, C, C, dt, SM_ACT_NONE, stream))) return rc;
+  if (wt->mlp_packed && mlp_fused_supported(C, Hd, dt)) {
+    MlpArgs a; std::memset(&a, 0, sizeof(a));
+    a.X = x1; a.Wp = wt->mlp_packed; a.b1 = wt->b1; a.b2 = wt->b2; a.residual = x1; a.Y = y; a.M = T; a.C = C; a.Hd = Hd;
+    a.norm = 1; a.norm_eps = c->eps; a.norm_gamma = wt->ln2_g; a.norm_beta = wt->ln2_b;
+    a.x_rows = identity_rows(C); a.y_rows = identity_rows(C);
+    return mlp_checked(a, stream, "sm_cswin_block(mlp)");
+  }
+  if (fold(Hd)) {
+    if ((rc = linear_rows(x1, wt->w1, wt->b1, nullptr, hid, T, Hd, C, dt, SM_ACT_GELU, stream, wt->ln2_g, wt->ln2_b, c->eps))) return rc;
+  } else {
+    if ((rc = norm_rows(x1, wt->ln2_g, wt->ln2_b, nbuf, T, C, c->eps, dt, stream))) return rc;
+    if ((rc = linear_rows(nbuf, wt->w1, wt->b1, nullptr, hid, T, Hd, C, dt, SM_ACT_GELU, stream))) return rc;
+  }
+  return linear_rows(hid, wt->w2, wt->b2, x1, y, T, C, Hd, dt, SM_ACT_NONE, stream);
 }

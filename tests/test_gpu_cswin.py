@@ -7,7 +7,7 @@ import torch
 from oracle import cswin as CS
 from oracle import ops as O
 from paper_2404_13528_amd import binding as sm, workloads as Wl
-from util import assert_bf16_close, to_np
+from util import assert_bf16_close, np_params, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -135,3 +135,48 @@ def test_refusals_on_device():
         sm.attention(q, q, q, kind="stripe", stripes=2, run=8)
     with pytest.raises(sm.SmError):        # a stripe of 8 tokens is not whole runs of 3
         sm.attention(q, q, q, kind="stripe", stripes=1, run=3)
+
+
+BLOCKS = [
+    (2, 56, 56, 64, 2, 1),       # stage 1 of CSwin-T: no fused kernel at 64 channels, one kernel per Linear
+    (2, 28, 28, 128, 4, 2),      # stage 2: packed-weight LayerNorm + QKV, projection + MLP as one kernel
+    (3, 14, 14, 256, 8, 7),      # stage 3
+    (2, 7, 7, 512, 16, 7),       # stage 4: the 64-token fused kernel
+    (2, 8, 12, 96, 4, 4),        # CSwin-B's first width: head size 24, no fused kernel
+]
+
+
+def run_block(B, H, W, Cc, heads, sw, mode, seed=0, std=0.02, fuse=True):
+    x, p = Wl.cswin_block_case(B, H, W, Cc, seed=seed, bf16=True, std=std)
+    want = CS.cswin_block(to_np(x), np_params(p), B, H, W, Cc, heads, sw)
+    dev = {k: v.to(torch.bfloat16).cuda() for k, v in p.items()}
+    blk = sm.CswinBlock(B, H, W, Cc, heads, sw, dev, mode, fuse=fuse)
+    xd = x.to(torch.bfloat16).cuda()
+    y = blk(xd)
+    torch.cuda.synchronize()
+    n_compute, n_copy = sm.launch_counts()
+    assert n_copy == (0 if mode == sm.SM_ELIDED else 9)
+    assert_bf16_close(y.reshape(B * H * W, Cc), want.reshape(B * H * W, Cc), x=to_np(x), what="CSwin block")
+    return y, n_compute
+
+
+@pytest.mark.parametrize("mode", [sm.SM_ELIDED, sm.SM_EXPLICIT])
+@pytest.mark.parametrize("B,H,W,Cc,heads,sw", BLOCKS)
+def test_block_matches_the_oracle(B, H, W, Cc, heads, sw, mode):
+    # weights of std 0.02 leave a branch delta y - x of about 0.05 here (the attention averages 50 to 100 values under a
+    # nearly uniform softmax), of which the bf16 rounding of y alone (magnitude 1) is already 3 %: wider weights, so
+    # that the delta check sees the arithmetic and not that rounding
+    _, n = run_block(B, H, W, Cc, heads, sw, mode, seed=H, std=0.06)
+    # LayerNorm + QKV, two convolutions, two attentions, then projection + MLP in one kernel or the Linears one by one
+    fused = Cc in (128, 256, 512)
+    assert n == (6 if fused else 8)
+
+
+# kernels without fusion: at 256 channels both LayerNorms are kernels of their own (their Linears have too many column
+# tiles to repeat the norm in each), at 128 they are folded into the Linear's load
+@pytest.mark.parametrize("B,H,W,Cc,heads,sw,n_per_op", [(2, 14, 14, 256, 8, 7, 10), (1, 28, 28, 128, 4, 2, 8)])
+def test_block_on_the_stress_distribution_and_without_fusion(B, H, W, Cc, heads, sw, n_per_op):
+    a, _ = run_block(B, H, W, Cc, heads, sw, sm.SM_ELIDED, seed=7, std=0.1)
+    b, n = run_block(B, H, W, Cc, heads, sw, sm.SM_ELIDED, seed=7, std=0.1, fuse=False)
+    assert n == n_per_op
+    assert_bf16_close(a.reshape(-1, Cc), to_np(b).reshape(-1, Cc), what="fused against kernel per operator")

@@ -60,3 +60,18 @@ def test_operand_maps_are_strided_in_the_factored_index(B, H, W, Cc, heads, sw):
             assert base == k * Cc + branch * Cb
             for axis, n in enumerate(got.shape):
                 assert n == 1 or st[axis] == expect[axis], (axis, st, expect)      # an axis of one entry has no stride
+
+
+def test_block_workspace_and_refusals():
+    lib = sm.lib()
+
+    def bcfg(B=2, H=14, W=14, Cc=256, heads=8, sw=7, ratio=4, eps=1e-5):
+        return sm.CswinBlockCfg(sm.SM_BF16, B, H, W, Cc, heads, sw, ratio, eps)
+    el = lib.sm_cswin_block_workspace_bytes(C.byref(bcfg()), sm.SM_ELIDED)
+    ex = lib.sm_cswin_block_workspace_bytes(C.byref(bcfg()), sm.SM_EXPLICIT)
+    tokens = 2 * 14 * 14 * 256 * 2
+    assert 10 * tokens <= el < 11 * tokens and ex > el + 7 * tokens          # q|k|v, attention output, x1, a norm, the hidden tensor
+    for bad in (bcfg(ratio=0), bcfg(eps=0.0), bcfg(heads=3), bcfg(sw=4), bcfg(Cc=24, heads=2)):
+        assert lib.sm_cswin_block_workspace_bytes(C.byref(bad), sm.SM_ELIDED) == 0
+    w = sm.CswinWeights()
+    assert lib.sm_cswin_block(C.byref(bcfg()), C.byref(w), None, None, None, C.c_size_t(0), sm.SM_ELIDED, None) < 0
