@@ -180,3 +180,10 @@ def test_block_on_the_stress_distribution_and_without_fusion(B, H, W, Cc, heads,
     b, n = run_block(B, H, W, Cc, heads, sw, sm.SM_ELIDED, seed=7, std=0.1, fuse=False)
     assert n == n_per_op
     assert_bf16_close(a.reshape(-1, Cc), to_np(b).reshape(-1, Cc), what="fused against kernel per operator")
+
+
+def test_block_full_batch_stage3_both_modes():
+    # the size bench.py times: 64 images of 14 x 14 tokens, 256 channels
+    a, _ = run_block(64, 14, 14, 256, 8, 7, sm.SM_ELIDED, seed=12, std=0.06)
+    b, _ = run_block(64, 14, 14, 256, 8, 7, sm.SM_EXPLICIT, seed=12, std=0.06)
+    assert torch.equal(a, b)          # the same kernels on the same values: only the addresses differ
