@@ -433,11 +433,12 @@ int sm_decode_step(const sm_decode_cfg*, const sm_decode_weights*, const void* x
  * a depth-wise 3 x 3 cross-correlation of each half's values inside their own
  * stripe (zero beyond the stripe's border), added to that half's attention
  * output; channel order as in out.
- *   SM_ELIDED: two attention kernels that read qkv in place and store into their
- *     half of out's channels (the Concat of the halves has two inputs and is not
- *     planned: it is applied as the store address, by hand).  With the encoding:
- *     per half one convolution kernel first, which reads the values in place and
- *     writes out's channels, to which the attention then adds.
+ *   SM_ELIDED: two attentions that read qkv in place and store into their half
+ *     of out's channels (the Concat of the halves has two inputs and is not
+ *     planned: it is applied as the store address, by hand); one launch holds
+ *     both when H == W (the halves then have one shape), else two.  With the
+ *     encoding: one convolution kernel first, which reads the values of both
+ *     halves in place and writes out, to which the attentions then add.
  *   SM_EXPLICIT: per half one copy kernel for the Slice + partition + head split
  *     of q, k, v, the attention on contiguous operands, one copy for head merge +
  *     stripe merge, then one Concat kernel: 5 copies around the same 2 kernels

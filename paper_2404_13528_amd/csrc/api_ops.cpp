@@ -79,8 +79,8 @@ int gemm_checked(GemmArgs& g, void* stream, const char* who) {
   return SM_OK;
 }
 
-int attention_checked(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table,
-                      void* stream, const char* who) {
+namespace {
+int attention_validate(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table, const char* who) {
   if (!q || !k || !v || !o) return fail(SM_ERR_INVALID_ARG, "%s: null pointer", who);
   if (!dtype_ok(d.dtype)) return fail(SM_ERR_INVALID_ARG, "%s: unknown dtype", who);
   if (d.kind < SM_ATT_FULL || d.kind > SM_ATT_STRIPE) return fail(SM_ERR_INVALID_ARG, "%s: unknown kind", who);
@@ -114,11 +114,37 @@ int attention_checked(const sm_attention_desc& d, const void* q, const void* k, 
     if (d.kind != SM_ATT_WINDOW) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 supports window attention only", who);
     if (d.nq > 64 || d.d > 64) return fail(SM_ERR_UNSUPPORTED, "%s: fp32 window attention needs window^2 <= 64 and head size <= 64", who);
   }
+  return SM_OK;
+}
+}  // namespace
+
+int attention_checked(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table,
+                      void* stream, const char* who) {
+  if (int rc = attention_validate(d, q, k, v, o, table, who)) return rc;
   char label[128];
   snprintf(label, sizeof(label), "attention_%s_%s[%d,%d,%d,%d,%d]%s", d.kind == SM_ATT_WINDOW ? "window" : (d.kind == SM_ATT_CAUSAL ? "causal" : (d.kind == SM_ATT_STRIPE ? "stripe" : "full")),
            d.dtype == SM_F32 ? "f32" : "bf16", d.nb, d.heads, d.nq, d.nk, d.d, d.accumulate ? "+acc" : "");
   Timed tm(label, stream);
   int rc = launch_attention(d, q, k, v, o, table, stream);
+  if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
+  count_compute();
+  return SM_OK;
+}
+
+// two stripe attentions of one shape (the halves of a cross-shaped window attention) as one launch; p0 / p1: {q, k, v, o}
+int attention_stripe_pair_checked(const sm_attention_desc& d0, void* const* p0, const sm_attention_desc& d1, void* const* p1,
+                                  void* stream, const char* who) {
+  if (int rc = attention_validate(d0, p0[0], p0[1], p0[2], p0[3], nullptr, who)) return rc;
+  if (int rc = attention_validate(d1, p1[0], p1[1], p1[2], p1[3], nullptr, who)) return rc;
+  if (d0.kind != SM_ATT_STRIPE || d1.kind != SM_ATT_STRIPE || d0.nb != d1.nb || d0.heads != d1.heads || d0.nq != d1.nq || d0.d != d1.d ||
+      d0.scale != d1.scale || d0.accumulate != d1.accumulate)
+    return fail(SM_ERR_SHAPE, "%s: the two attentions of a pair must be stripe attentions of one shape", who);
+  char label[128];
+  snprintf(label, sizeof(label), "attention_stripe_bf16[%d,%d,%d,%d,%d]%s", 2 * d0.nb, d0.heads, d0.nq, d0.nk, d0.d, d0.accumulate ? "+acc" : "");
+  Timed tm(label, stream);
+  const void* c0[4] = {p0[0], p0[1], p0[2], p0[3]};
+  const void* c1[4] = {p1[0], p1[1], p1[2], p1[3]};
+  int rc = launch_attention_stripe_pair(d0, c0, d1, c1, stream);
   if (rc) return fail(SM_ERR_DEVICE, "%s: launch failed (hip error %d)", who, rc);
   count_compute();
   return SM_OK;

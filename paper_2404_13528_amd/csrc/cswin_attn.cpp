@@ -250,19 +250,25 @@ int cswin_attention_impl(const sm_cswin_cfg* c, const void* qkv, const void* lep
   const size_t units = lepe ? 7 : 5;
   const void* tables = el ? nullptr : base + 2 * units * hbytes;
   if (!el && (rc = fill_tables(plan->ex_tables, base + 2 * units * hbytes, stream, ~0ull))) return rc;
+  // i < 0: both halves of the channels in one launch (whole images, each half with its own stripe shape)
   auto conv = [&](const Branch& b, int i, const void* v, void* o, int n_img, int gh, int gw, int64_t v_img, int64_t v_tok, int64_t o_img, int64_t o_tok) -> int {
     DwconvArgs k; std::memset(&k, 0, sizeof(k));
-    k.v = v; k.out = o; k.w = (const unsigned short*)lepe_w + (size_t)i * Cb * 9; k.bias = (const unsigned short*)lepe_b + (size_t)i * Cb;
-    k.n_img = n_img; k.H = gh; k.W = gw; k.Cn = (int)Cb; k.Hs = (int)b.Hs; k.Ws = (int)b.Ws;
+    const int first = i < 0 ? 0 : i;
+    k.v = v; k.out = o; k.w = (const unsigned short*)lepe_w + (size_t)first * Cb * 9; k.bias = (const unsigned short*)lepe_b + (size_t)first * Cb;
+    k.n_img = n_img; k.H = gh; k.W = gw; k.Cn = (int)(i < 0 ? C : Cb); k.Hs = (int)b.Hs; k.Ws = (int)b.Ws;
+    if (i < 0) { k.split_c = (int)Cb; k.Hs2 = (int)plan->br[1].Hs; k.Ws2 = (int)plan->br[1].Ws; }
     k.v_img = v_img; k.v_tok = v_tok; k.o_img = o_img; k.o_tok = o_tok;
     char label[96];
-    snprintf(label, sizeof(label), "dwconv3x3_bf16[%d,%d,%d,%d]", n_img, gh, gw, (int)Cb);
+    snprintf(label, sizeof(label), "dwconv3x3_bf16[%d,%d,%d,%d]", n_img, gh, gw, k.Cn);
     Timed tm(label, stream);
     if (int e = launch_dwconv3x3(k, stream)) return fail(SM_ERR_DEVICE, "sm_cswin_attention: convolution launch failed (hip error %d)", e);
     count_compute();
     return SM_OK;
   };
   void* merged[2] = {nullptr, nullptr};
+  sm_attention_desc el_desc[2];
+  // elided: the encoding of both halves first, in one launch, straight into the output (stripe-aware taps)
+  if (el && lepe && (rc = conv(plan->br[0], -1, src + 2 * C, dst, (int)B, c->H, c->W, 3 * C * L, 3 * C, C * L, C))) return rc;
   for (int i = 0; i < 2; ++i) {
     const Branch& b = plan->br[i];
     sm_attention_desc a; std::memset(&a, 0, sizeof(a));
@@ -282,9 +288,7 @@ int cswin_attention_impl(const sm_cswin_cfg* c, const void* qkv, const void* lep
         return fail(SM_ERR_UNSUPPORTED, "sm_cswin_attention: the planned store is not by whole tokens");
       a.o_stride[0] = o.img / Cb * C; a.o_stride[1] = o.head; a.o_stride[2] = o.tok / Cb * C;
       a.o_stripe[0] = o.stripe / Cb * C; a.o_stripe[1] = o.runs / Cb * C;
-      // the encoding first, straight into this half's channels of the output (whole images, stripe-aware taps)
-      if (lepe && (rc = conv(b, i, src + 2 * C + i * Cb, dst + i * Cb, (int)B, c->H, c->W, 3 * C * L, 3 * C, C * L, C))) return rc;
-      if ((rc = attention_checked(a, src + b.q.base, src + b.k.base, src + b.v.base, dst + i * Cb, nullptr, stream, "sm_cswin_attention"))) return rc;
+      el_desc[i] = a;
     } else {
       char* mine = base + (size_t)i * units * hbytes;
       unsigned short* parts = (unsigned short*)mine;      // [3, nwin, heads/2, S, d]
@@ -305,7 +309,16 @@ int cswin_attention_impl(const sm_cswin_cfg* c, const void* qkv, const void* lep
       if ((rc = copy_launch(b.merge, tables, res, merged[i], c->dtype, stream))) return rc;
     }
   }
-  if (!el) {
+  if (el) {
+    // the two halves as one launch when they have one shape (square grids), else one after the other
+    const Branch &b0 = plan->br[0], &b1 = plan->br[1];
+    void* p0[4] = {(void*)(src + b0.q.base), (void*)(src + b0.k.base), (void*)(src + b0.v.base), dst};
+    void* p1[4] = {(void*)(src + b1.q.base), (void*)(src + b1.k.base), (void*)(src + b1.v.base), dst + Cb};
+    if (b0.nwin == b1.nwin && b0.S == b1.S) return attention_stripe_pair_checked(el_desc[0], p0, el_desc[1], p1, stream, "sm_cswin_attention");
+    if ((rc = attention_checked(el_desc[0], p0[0], p0[1], p0[2], p0[3], nullptr, stream, "sm_cswin_attention"))) return rc;
+    return attention_checked(el_desc[1], p1[0], p1[1], p1[2], p1[3], nullptr, stream, "sm_cswin_attention");
+  }
+  {
     char label[96];
     snprintf(label, sizeof(label), "concat_bf16[%lld,%lld]", (long long)(B * L), (long long)C);
     Timed tm(label, stream);

@@ -193,9 +193,10 @@ typedef short s16x8_t __attribute__((ext_vector_type(8)));
 // MODE 0: every key visible; 1: causal; 2: stripes (a batch entry is one stripe of an image's token grid: its tokens
 // lie in runs of a.run adjacent tokens, so the stripe partition and merge of cross-shaped windows are two more
 // strides in the row addresses).
+// bid: the workgroup's index among those of this attention (one launch may hold two attentions, below).
 template <int DK, int MODE>
-__global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                            const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh) {
+__device__ __forceinline__ void attn_flash_body(const sm_attention_desc& a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh, int bid) {
   constexpr bool CAUSAL = MODE == 1, STRIPE = MODE == 2;
   constexpr int DB = (DK + 1) / 2;           // 32-wide output column blocks
   // Row pitches in 16-byte chunks, chosen for the 64-bank LDS.  K rows are read whole-chunk by 16 consecutive rows
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
   // keeps them on one XCD (one L2) whenever nbh is a multiple of 8.  Causal: the first half of the ranks takes
   // the long query tiles in descending order and the second half the short ones in ascending order, so that
   // co-resident workgroups of ranks r and r + n_qt / 2 carry about the same total work.
-  const int bh = blockIdx.x % nbh, rank = blockIdx.x / nbh;
+  const int bh = bid % nbh, rank = bid / nbh;
   int qt = rank;
   if (CAUSAL) { const int hq = (n_qt + 1) >> 1; qt = rank < hq ? n_qt - 1 - rank : rank - hq; }
   // stripes: heads whose rows share cache lines (head size 32 is half a line) follow each other at a distance of
@@ -392,6 +393,20 @@ __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a,
                                                                     __builtin_bit_cast(unsigned, __builtin_convertvector(x1, bf16x2_t)));
       }
     }
+}
+
+template <int DK, int MODE>
+__global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                            const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh) {
+  attn_flash_body<DK, MODE>(a, q, k, v, o, n_qt, nbh, (int)blockIdx.x);
+}
+// Two stripe attentions of one shape in one launch (the two halves of a cross-shaped window attention): workgroups
+// [0, g0) belong to the first.  Each half has its own strides and pointers; nothing else differs.
+struct FlashPairPtrs { const bf16_t *q, *k, *v; bf16_t* o; };
+__global__ __launch_bounds__(256, 2) void attn_stripe_pair_kernel(sm_attention_desc a0, sm_attention_desc a1, FlashPairPtrs p0, FlashPairPtrs p1,
+                                                                  int n_qt, int nbh, int g0) {
+  if ((int)blockIdx.x < g0) attn_flash_body<2, 2>(a0, p0.q, p0.k, p0.v, p0.o, n_qt, nbh, (int)blockIdx.x);
+  else attn_flash_body<2, 2>(a1, p1.q, p1.k, p1.v, p1.o, n_qt, nbh, (int)blockIdx.x - g0);
 }
 
 // Window attention, bf16, head size 32, at most 64 tokens per window: one wave per (window, head, block of 32
@@ -835,7 +850,9 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(DwconvArgs a, int64_t to
   const int hw = a.H * a.W;
   const int img = (int)(t / hw), p = (int)(t - (int64_t)img * hw);
   const int y = p / a.W, x = p - y * a.W;
-  const int y_lo = (y / a.Hs) * a.Hs, x_lo = (x / a.Ws) * a.Ws;        // the token's stripe
+  const bool second = a.split_c > 0 && c >= a.split_c;                // channels from split_c on: the other stripe shape
+  const int Hs = second ? a.Hs2 : a.Hs, Ws = second ? a.Ws2 : a.Ws;
+  const int y_lo = (y / Hs) * Hs, x_lo = (x / Ws) * Ws;               // the token's stripe
   const bf16_t* vb = (const bf16_t*)a.v + (int64_t)img * a.v_img + c;
   float wv[72];
   {
@@ -858,7 +875,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(DwconvArgs a, int64_t to
 #pragma unroll
     for (int dx = 0; dx < 3; ++dx) {
       const int yy = y + dy - 1, xx = x + dx - 1;
-      if (yy < y_lo || yy >= y_lo + a.Hs || xx < x_lo || xx >= x_lo + a.Ws) continue;      // beyond the stripe: zero
+      if (yy < y_lo || yy >= y_lo + Hs || xx < x_lo || xx >= x_lo + Ws) continue;          // beyond the stripe: zero
       const au32x4 u = *(const au32x4*)(vb + (int64_t)(yy * a.W + xx) * a.v_tok);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -879,6 +896,20 @@ int launch_dwconv3x3(const DwconvArgs& a, void* stream) {
   if (total == 0) return 0;
   const int64_t blocks = ((total + 255) / 256 + 7) / 8 * 8;
   dwconv3x3_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(a, total);
+  return (int)hipGetLastError();
+}
+
+// both descriptors: SM_ATT_STRIPE, bf16, head size <= 32, positive scale, the same nb, heads, nq (checked by the caller)
+int launch_attention_stripe_pair(const sm_attention_desc& d0, const void* const* p0, const sm_attention_desc& d1, const void* const* p1, void* stream) {
+  const int n_qt = (d0.nq + 127) / 128, nbh = d0.nb * d0.heads;
+  const long g0 = (long)n_qt * nbh;
+  if (2 * g0 >= (1L << 31)) return (int)hipErrorInvalidValue;
+  const size_t smem = 2 * 64 * ((2 * 2 + 1) + 4) * 16 + 64;
+  static const hipError_t attr = hipFuncSetAttribute((const void*)attn_stripe_pair_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) return (int)attr;
+  const FlashPairPtrs a{(const bf16_t*)p0[0], (const bf16_t*)p0[1], (const bf16_t*)p0[2], (bf16_t*)p0[3]};
+  const FlashPairPtrs b{(const bf16_t*)p1[0], (const bf16_t*)p1[1], (const bf16_t*)p1[2], (bf16_t*)p1[3]};
+  attn_stripe_pair_kernel<<<dim3((unsigned)(2 * g0)), dim3(256), smem, (hipStream_t)stream>>>(d0, d1, a, b, n_qt, nbh, (int)g0);
   return (int)hipGetLastError();
 }
 

@@ -18,13 +18,17 @@ int launch_empty(void* stream);
 // row copies: dst row r (inner contiguous elements) = src[rows(r) ...] (+ addend row r); rows(r) keeps 16-byte alignment
 // Depth-wise 3 x 3 cross-correlation over the token grid of n_img images of H x W tokens with Cn channels (bf16):
 // element (img, y, x, c) of v / out at img * *_img + (y * W + x) * *_tok + c; w [Cn][3][3], bias [Cn].  A tap
-// contributes only when it lies in the token's own Hs x Ws stripe (Hs = H, Ws = W: plain zero padding).
+// contributes only when it lies in the token's own Hs x Ws stripe (Hs = H, Ws = W: plain zero padding).  split_c > 0
+// (a multiple of 8): channels [split_c, Cn) use stripes of Hs2 x Ws2 instead.
 struct DwconvArgs {
   const void* v; void* out; const void* w; const void* bias;
   int n_img, H, W, Cn, Hs, Ws;
   int64_t v_img, v_tok, o_img, o_tok;
+  int split_c, Hs2, Ws2;
 };
 int launch_dwconv3x3(const DwconvArgs& a, void* stream);      // Cn a multiple of 8
+// two stripe attentions of one shape in one launch; p0 / p1: {q, k, v, o}
+int launch_attention_stripe_pair(const sm_attention_desc& d0, const void* const* p0, const sm_attention_desc& d1, const void* const* p1, void* stream);
 // out [rows, 2 * cols] = [a | b] along the last axis; cols_bytes (of one input row) a multiple of 16
 int launch_concat2_cols(const void* a, const void* b, void* out, int64_t rows, int cols_bytes, void* stream);
 int launch_gather_rows(const RowProg& rows, int64_t n_rows, int inner, const void* src, const void* addend, void* dst, int dtype, void* stream);
@@ -182,5 +186,7 @@ int mlp_checked(MlpArgs& a, void* stream, const char* who);
 int lin32_checked(Lin32Args& a, void* stream, const char* who);
 int attention_checked(const sm_attention_desc& d, const void* q, const void* k, const void* v, void* o, const void* table,
                       void* stream, const char* who);
+int attention_stripe_pair_checked(const sm_attention_desc& d0, void* const* p0, const sm_attention_desc& d1, void* const* p1,
+                                  void* stream, const char* who);
 int map_vector_width(const sm_map& m, int esize);
 }
