@@ -18,6 +18,8 @@ CASES = [
     (2, 7, 7, 512, 16, 7),       # stage 4: the stripe is the whole image
     (2, 8, 12, 96, 4, 4),        # non-square grid, head size 24, stripes of 32 and 48 tokens
     (1, 48, 48, 32, 2, 3),       # 144 tokens per stripe: two query tiles and three key tiles with ragged tails
+    (2, 6, 10, 32, 4, 2),        # head size 8, stripes of 12 and 20 tokens: less than one key tile
+    (1, 5, 5, 16, 2, 5),         # a single stripe of 25 tokens per half, one head per half
 ]
 
 
