@@ -791,49 +791,91 @@ __global__ __launch_bounds__(256, 4) void attn_window7_kernel(sm_attention_desc 
   }
 }
 
-// fp32 window attention: nq, nk <= 64, d <= 64.  One workgroup of 64 threads
-// per (window, head); thread i owns query i.
-__global__ __launch_bounds__(64) void attn_window_f32_kernel(sm_attention_desc a, const float* __restrict__ q, const float* __restrict__ k,
-                                                             const float* __restrict__ v, float* __restrict__ o, const float* __restrict__ table) {
-  __shared__ float ks[64 * 65], vs[64 * 65], ss[64 * 65];
+// fp32 window attention: nq, nk <= 64, d <= 4 DV.  One workgroup of 256 threads per (window, head); the four lanes of
+// a quad own query i = tid / 4 and a quarter of the head's features each: a score is four partial dot products added
+// across the quad, the product with V is taken per quarter.  K and V rows sit in LDS as 16-byte chunks (all quads read
+// the same chunks at the same time: a broadcast), the head's column of the relative-position table as well; the
+// scores of a query stay in its own LDS column between the two passes (maximum, then exponentials and the product
+// with V in one sweep over the keys).
+template <int DV>
+__global__ __launch_bounds__(256) void attn_window_f32_kernel(sm_attention_desc a, const float* __restrict__ q, const float* __restrict__ k,
+                                                              const float* __restrict__ v, float* __restrict__ o, const float* __restrict__ table) {
+  constexpr int P = DV + 1;                  // row pitch in chunks, odd: the staging stores spread over the banks
+  constexpr int CPL = DV / 4;                // chunks per lane
+  __shared__ float4 ks[64 * P], vs[64 * P];
+  __shared__ float ss[64 * 65];
+  __shared__ float bias_s[232];              // (2 w - 1)^2 <= 225 entries (w <= 8)
   const int b = blockIdx.x / a.heads, hh = blockIdx.x % a.heads;
   const float* qp = q + (int64_t)b * a.q_stride[0] + (int64_t)hh * a.q_stride[1];
   const float* kp = k + (int64_t)b * a.k_stride[0] + (int64_t)hh * a.k_stride[1];
   const float* vp = v + (int64_t)b * a.v_stride[0] + (int64_t)hh * a.v_stride[1];
   float* op = o + (int64_t)b * a.o_stride[0] + (int64_t)hh * a.o_stride[1];
-  const int tid = threadIdx.x;
-  for (int idx = tid; idx < a.nk * a.d; idx += 64) {
-    const int j = idx / a.d, e = idx - j * a.d;
-    ks[j * 65 + e] = kp[(int64_t)j * a.k_stride[2] + e];
-    vs[j * 65 + e] = vp[(int64_t)j * a.v_stride[2] + e];
+  const int tid = threadIdx.x, dv = a.d >> 2;
+  const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  for (int idx = tid; idx < a.nk * DV; idx += 256) {
+    const int j = idx / DV, c = idx - j * DV;
+    float4 kk = zero4, vv = zero4;          // chunks past the head size: zeros, so that the sums below can run to DV
+    if (c < dv) {
+      kk = *(const float4*)(kp + (int64_t)j * a.k_stride[2] + 4 * c);
+      vv = *(const float4*)(vp + (int64_t)j * a.v_stride[2] + 4 * c);
+    }
+    ks[j * P + c] = kk; vs[j * P + c] = vv;
+  }
+  if (a.kind == SM_ATT_WINDOW) {
+    const int nt = (2 * a.window - 1) * (2 * a.window - 1);
+    for (int t = tid; t < nt; t += 256) bias_s[t] = table[(int64_t)t * a.heads + hh];
   }
   __syncthreads();
   WinGeom wg;
   wg.w = a.window; wg.shift = a.shift; wg.H = a.H; wg.W = a.W; wg.nWx = a.W / a.window; wg.nW = (a.H / a.window) * wg.nWx;
   const int win = b % wg.nW;
   wg.wy = win / wg.nWx; wg.wx = win - wg.wy * wg.nWx;
-  const int i = tid;
-  if (i >= a.nq) return;
-  float qr[64];
+  const int i = tid >> 2, c0 = (tid & 3) * CPL;       // the quad's query, this lane's first chunk
+  const int iq = min(i, a.nq - 1);                    // quads past the last query repeat it and store nothing
+  float4 qr[CPL];
 #pragma unroll
-  for (int e = 0; e < 64; ++e) qr[e] = e < a.d ? qp[(int64_t)i * a.q_stride[2] + e] * a.scale : 0.f;
+  for (int c = 0; c < CPL; ++c) {
+    qr[c] = zero4;
+    if (c0 + c < dv) {
+      const float4 t = *(const float4*)(qp + (int64_t)iq * a.q_stride[2] + 4 * (c0 + c));
+      qr[c].x = t.x * a.scale; qr[c].y = t.y * a.scale; qr[c].z = t.z * a.scale; qr[c].w = t.w * a.scale;
+    }
+  }
   float mx = -INFINITY;
   for (int j = 0; j < a.nk; ++j) {
     float s = 0.f;
 #pragma unroll
-    for (int e = 0; e < 64; ++e) if (e < a.d) s = fmaf(qr[e], ks[j * 65 + e], s);
-    if (a.kind == SM_ATT_WINDOW) s += window_term<float>(wg, table, a.heads, hh, win, i, j);
-    ss[i * 65 + j] = s;
+    for (int c = 0; c < CPL; ++c) {
+      const float4 kk = ks[j * P + c0 + c];
+      s = fmaf(qr[c].x, kk.x, s); s = fmaf(qr[c].y, kk.y, s); s = fmaf(qr[c].z, kk.z, s); s = fmaf(qr[c].w, kk.w, s);
+    }
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);              // the whole dot product, the same bits in the four lanes
+    if (a.kind == SM_ATT_WINDOW) s += window_term<float>(wg, bias_s, 1, 0, win, iq, j);
+    ss[i * 65 + j] = s;                      // four lanes, one value, one address
     mx = fmaxf(mx, s);
   }
   float sum = 0.f;
-  for (int j = 0; j < a.nk; ++j) { const float p = expf(ss[i * 65 + j] - mx); ss[i * 65 + j] = p; sum += p; }
-  const float inv = 1.f / sum;
-  for (int e = 0; e < a.d; ++e) {
-    float acc = 0.f;
-    for (int j = 0; j < a.nk; ++j) acc = fmaf(ss[i * 65 + j], vs[j * 65 + e], acc);
-    op[(int64_t)i * a.o_stride[2] + e] = acc * inv;
+  float4 acc[CPL];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) acc[c] = zero4;
+  for (int j = 0; j < a.nk; ++j) {
+    const float p = expf(ss[i * 65 + j] - mx);
+    sum += p;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+      const float4 vv = vs[j * P + c0 + c];
+      acc[c].x = fmaf(p, vv.x, acc[c].x); acc[c].y = fmaf(p, vv.y, acc[c].y); acc[c].z = fmaf(p, vv.z, acc[c].z); acc[c].w = fmaf(p, vv.w, acc[c].w);
+    }
   }
+  if (i >= a.nq) return;
+  const float inv = 1.f / sum;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c)
+    if (c0 + c < dv) {
+      const float4 r = {acc[c].x * inv, acc[c].y * inv, acc[c].z * inv, acc[c].w * inv};
+      *(float4*)(op + (int64_t)i * a.o_stride[2] + 4 * (c0 + c)) = r;
+    }
 }
 
 // Depth-wise 3 x 3 cross-correlation on a token-major grid: one thread per (token, 8 channels); the 72 weights of its
@@ -917,8 +959,10 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
                      const void* rpb_table, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   if (d.dtype == SM_F32) {
-    attn_window_f32_kernel<<<dim3((unsigned)(d.nb * d.heads)), dim3(64), 0, s>>>(d, (const float*)q, (const float*)k, (const float*)v,
-                                                                               (float*)o, (const float*)rpb_table);
+    if (d.d <= 32) attn_window_f32_kernel<8><<<dim3((unsigned)(d.nb * d.heads)), dim3(256), 0, s>>>(d, (const float*)q, (const float*)k, (const float*)v,
+                                                                                                     (float*)o, (const float*)rpb_table);
+    else attn_window_f32_kernel<16><<<dim3((unsigned)(d.nb * d.heads)), dim3(256), 0, s>>>(d, (const float*)q, (const float*)k, (const float*)v,
+                                                                                          (float*)o, (const float*)rpb_table);
     return (int)hipGetLastError();
   }
   if (d.kind == SM_ATT_WINDOW && d.d == 32 && d.nq <= 64 && d.window <= 8) {
