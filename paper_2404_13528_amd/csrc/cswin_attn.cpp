@@ -16,7 +16,10 @@
 // into the attention and eliminates the Reshapes / Transposes on both sides of the convolution.  The convolution
 // kernel reads the values in place (its planned load map is checked against the kernel's token-major addressing when
 // the plan is built) and writes where the sum will finally live, in the output's layout; the attention then adds to
-// what it finds there.
+// what it finds there.  In the elided chain the two halves share one launch of each kernel (the attentions only when
+// both halves have one shape, i.e. on square grids): these kernels are short, and a launch costs as much as their work.
+//
+// sm_cswin_block (below) puts the block's other operators around it: they have no layout operator between them.
 #include <cmath>
 #include <cstring>
 #include <map>

@@ -15,10 +15,16 @@
 // wave per 32 queries, operands straight from global memory).  Window attention
 // adds the relative-position bias gathered from its table and the
 // shifted-window mask computed from the window's position: no bias or mask
-// tensor is ever materialised.
+// tensor is ever materialised.  attn_flash_kernel's stripe mode reads the stripes of
+// CSwin's cross-shaped windows in place (two more strides per operand) and can add
+// to its output; attn_stripe_pair_kernel puts the two halves of such an attention
+// into one grid.
 //
 // fp32 path (window attention only): plain FMA kernel, one workgroup per
 // (window, head), K / V / scores in LDS.
+//
+// dwconv3x3_kernel: the depth-wise 3 x 3 positional encoding of the cross-shaped
+// windows, token-major, taps masked at the border of the token's stripe.
 #include <type_traits>
 #include "device_common.h"
 #include "kernels.h"
