@@ -12,8 +12,9 @@ ms per step, throughput, algorithmic HBM bytes, the per-kernel table from HIP ev
 dominant kernel and its roofline.  `roofline` (top level) is the headline chain's dominant kernel; `cpu_baseline`
 is the CPU oracle on a bounded sample of the headline workload.
 
-  python bench.py                       all five configurations (about two minutes)
-  python bench.py --config 3            one configuration (1-based, as in the benchmark's list)
+  python bench.py                       all five configurations and the extras 6-10 (about two minutes)
+  python bench.py --config 3            one configuration (1-based, as in the benchmark's list; 6: ViT block, 7: Fig. 4
+                                        graph, 8: decode step, 9: CSwin attention, 10: CSwin block)
   python bench.py --fold-microbench     the read- versus write-side folding micro-experiment (Sec. 3.2.2)
 """
 import argparse
