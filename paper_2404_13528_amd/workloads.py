@@ -293,6 +293,79 @@ def llama_layer_graph(B, S, E, h, F):
     return g
 
 
+def cswin_attention_graph(B, H, W, C, h, sw, lepe=True):
+    """Cross-shaped window attention as an exporter writes it: q, k, v sliced out of the fused projection [B, H*W, 3C],
+    per half of the channels the stripe partition (Transpose, Reshape, Transpose, Reshape) and the head split, the
+    attention, head merge and stripe merge; with the positional encoding a depth-wise Conv of the values as stripe
+    images (emitted before the attention) and an Add of its result.  The Concat of the two halves is left out: layout
+    operators with several inputs are outside the planner."""
+    g = Graph()
+    L, Cb, hb, d = H * W, C // 2, h // 2, C // h
+    qkv = g.tensor((B, L, 3 * C), "qkv")
+    t4 = g.reshape(qkv, (B, L, 3, C))
+    whole = [g.reshape(g.slice(t4, 2, k, k + 1), (B, L, C)) for k in range(3)]
+    for i in range(2):
+        Hs, Ws = (H, sw) if i == 0 else (sw, W)
+        S, nwin = Hs * Ws, B * (H // Hs) * (W // Ws)
+        part = []
+        for k in range(3):
+            t = g.slice(whole[k], 2, i * Cb, (i + 1) * Cb)
+            t = g.transpose(t, (0, 2, 1))
+            t = g.reshape(t, (B, Cb, H // Hs, Hs, W // Ws, Ws))
+            t = g.transpose(t, (0, 2, 4, 3, 5, 1))
+            t = g.reshape(t, (nwin, S, Cb))
+            t = g.reshape(t, (nwin, S, hb, d))
+            part.append(g.transpose(t, (0, 2, 1, 3)))
+        pe = None
+        if lepe:
+            u = g.slice(whole[2], 2, i * Cb, (i + 1) * Cb)
+            u = g.transpose(u, (0, 2, 1))
+            u = g.reshape(u, (B, Cb, H // Hs, Hs, W // Ws, Ws))
+            u = g.transpose(u, (0, 2, 4, 1, 3, 5))
+            u = g.reshape(u, (nwin, Cb, Hs, Ws))
+            u = g.op("CONV", [u], (nwin, Cb, Hs, Ws), name="lepe%d" % i)
+            u = g.reshape(u, (nwin, hb, d, S))
+            pe = g.transpose(u, (0, 1, 3, 2))
+        t = g.op("ATTENTION", part, (nwin, hb, S, d), name="attn%d" % i, red=[3, 3, None])
+        if lepe:
+            t = g.op("ADD", [t, pe], (nwin, hb, S, d), name="add_pe%d" % i)
+        t = g.transpose(t, (0, 2, 1, 3))
+        t = g.reshape(t, (nwin, S, Cb))
+        t = g.reshape(t, (B, H // Hs, W // Ws, Hs, Ws, Cb))
+        t = g.transpose(t, (0, 1, 3, 2, 4, 5))
+        g.reshape(t, (B, L, Cb))
+    return g
+
+
+def neox_decode_graph(B, E, h, L, F):
+    """A GPT-NeoX-style layer at a decode step (one token per sequence): the fused projection viewed [B, 1, h, 3d],
+    Slices and Permutes to [B, h, 1, d], rotary embedding on q and k, attention against the grown caches (graph inputs:
+    the Concat that grows them has two inputs and is outside the planner), head merge, parallel residual."""
+    g = Graph()
+    d = E // h
+    x = g.tensor((B, 1, E), "x")
+    kfull = g.tensor((B, h, L + 1, d), "k_full")
+    vfull = g.tensor((B, h, L + 1, d), "v_full")
+    t = g.op("LAYERNORM", [x], (B, 1, E), name="ln1", red=[2])
+    qkv = g.reshape(g.linear(t, 3 * E, "qkv"), (B, 1, h, 3 * d))
+    part = []
+    for k in range(3):
+        u = g.transpose(g.slice(qkv, 3, k * d, (k + 1) * d), (0, 2, 1, 3))
+        if k < 2:
+            u = g.op("ROPE", [u], (B, h, 1, d), name="rope%d" % k)
+        part.append(u)
+    t = g.op("ATTENTION", [part[0], kfull, vfull], (B, h, 1, d), name="attn", red=[3, 3, None])
+    t = g.reshape(g.transpose(t, (0, 2, 1, 3)), (B, 1, E))
+    t = g.linear(t, E, "dense")
+    r1 = g.op("ADD", [x, t], (B, 1, E), name="res1")
+    t = g.op("LAYERNORM", [x], (B, 1, E), name="ln2", red=[2])
+    t = g.linear(t, F, "fc1")
+    t = g.op("UNARY", [t], (B, 1, F), name="gelu")
+    t = g.linear(t, E, "fc2")
+    g.op("ADD", [r1, t], (B, 1, E), name="res2")
+    return g
+
+
 def fig4_graph(D1=6, D2=4, D3=8):
     """The simplified graph of the paper's layout-selection example (Sec. 3.2.2):
     MatMul -> Transpose -> Reshape -> {Reduce over D3, Reduce' over D1, Conv over D3}."""

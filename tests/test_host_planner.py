@@ -46,6 +46,9 @@ GRAPHS = {
     "swin_s0": lambda: Wl.swin_block_graph(2, 14, 21, 32, 2, 7, 0),
     "llama": lambda: Wl.llama_layer_graph(1, 16, 64, 4, 96),
     "fig4": lambda: Wl.fig4_graph(),
+    "cswin_attention": lambda: Wl.cswin_attention_graph(2, 4, 6, 16, 4, 2, lepe=False),
+    "cswin_attention_lepe": lambda: Wl.cswin_attention_graph(1, 6, 6, 16, 2, 3, lepe=True),
+    "neox_decode": lambda: Wl.neox_decode_graph(2, 32, 2, 5, 48),
 }
 for _a in ("MATMUL", "UNARY", "TRANSPOSE", "SLICE"):
     for _b in ("MATMUL", "UNARY", "TRANSPOSE", "SLICE"):
@@ -197,3 +200,26 @@ def test_hand_derived_plans():
         n_maps = sum(p.load_map(c, s)[0] is not None for c in range(len(g.ops)) for s in range(len(g.ops[c]["in"])))
         assert n_maps == sum(l[0] == "load" for l in want)
         assert sum(p.store_map(i)[0] is not None for i in range(len(g.ops))) == sum(l[0] == "store" for l in want)
+
+
+def test_new_workloads_plan_down_to_their_compute_operators():
+    """Cross-shaped window attention: every Reshape / Transpose / Slice eliminated, the attentions (and, with the
+    positional encoding, the convolutions) kept, each Add fused into its attention (its later producer, Table 6).  Decode
+    step: the two LayerNorms, four Linears and the attention kept."""
+    for g, kept_names in ((Wl.cswin_attention_graph(1, 6, 6, 16, 2, 3, lepe=False), {"attn0", "attn1"}),
+                          (Wl.cswin_attention_graph(1, 6, 6, 16, 2, 3, lepe=True), {"attn0", "attn1", "lepe0", "lepe1"}),
+                          (Wl.neox_decode_graph(2, 32, 2, 5, 48), {"ln1", "qkv", "attn", "dense", "ln2", "fc1", "fc2"})):
+        p = sm.Plan(g.tensors, g.ops, k=1)
+        kept = set()
+        for i, o in enumerate(g.ops):
+            st = p.op(i)
+            if o["kind"] in ("RESHAPE", "TRANSPOSE", "SLICE"):
+                assert st["status"].startswith("eliminated"), (i, o, st)
+            elif st["status"] == "kept":
+                kept.add(o["name"])
+            else:
+                assert st["status"] == "fused", (i, o, st)
+        assert kept == kept_names
+        for i, o in enumerate(g.ops):
+            if o["name"].startswith("add_pe"):
+                assert g.ops[p.op(i)["absorbed_by"]]["name"] == "attn" + o["name"][-1]
