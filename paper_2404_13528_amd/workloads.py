@@ -366,6 +366,31 @@ def neox_decode_graph(B, E, h, L, F):
     return g
 
 
+def vit_block_graph(B, S, E, h, F):
+    """A ViT encoder block: LayerNorm, fused q | k | v Linear with bias, Slices + head split, global attention, head
+    merge, output Linear, residual, LayerNorm, GELU MLP, residual."""
+    g = Graph()
+    d = E // h
+    x = g.tensor((B, S, E), "x")
+    t = g.op("LAYERNORM", [x], (B, S, E), name="ln1", red=[2])
+    qkv = g.linear(t, 3 * E, "qkv")
+    parts = []
+    for k in range(3):
+        u = g.slice(qkv, 2, k * E, (k + 1) * E)
+        u = g.reshape(u, (B, S, h, d))
+        parts.append(g.transpose(u, (0, 2, 1, 3)))
+    t = g.op("ATTENTION", parts, (B, h, S, d), name="attn", red=[3, 3, None])
+    t = g.reshape(g.transpose(t, (0, 2, 1, 3)), (B, S, E))
+    t = g.linear(t, E, "wo")
+    h1 = g.op("ADD", [x, t], (B, S, E), name="res1")
+    t = g.op("LAYERNORM", [h1], (B, S, E), name="ln2", red=[2])
+    t = g.linear(t, F, "fc1")
+    t = g.op("UNARY", [t], (B, S, F), name="gelu")
+    t = g.linear(t, E, "fc2")
+    g.op("ADD", [h1, t], (B, S, E), name="res2")
+    return g
+
+
 def fig4_graph(D1=6, D2=4, D3=8):
     """The simplified graph of the paper's layout-selection example (Sec. 3.2.2):
     MatMul -> Transpose -> Reshape -> {Reduce over D3, Reduce' over D1, Conv over D3}."""

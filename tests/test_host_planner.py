@@ -49,6 +49,7 @@ GRAPHS = {
     "cswin_attention": lambda: Wl.cswin_attention_graph(2, 4, 6, 16, 4, 2, lepe=False),
     "cswin_attention_lepe": lambda: Wl.cswin_attention_graph(1, 6, 6, 16, 2, 3, lepe=True),
     "neox_decode": lambda: Wl.neox_decode_graph(2, 32, 2, 5, 48),
+    "vit": lambda: Wl.vit_block_graph(2, 5, 32, 4, 64),
 }
 for _a in ("MATMUL", "UNARY", "TRANSPOSE", "SLICE"):
     for _b in ("MATMUL", "UNARY", "TRANSPOSE", "SLICE"):
