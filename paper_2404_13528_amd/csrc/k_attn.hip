@@ -202,7 +202,7 @@ typedef short s16x8_t __attribute__((ext_vector_type(8)));
 // bid: the workgroup's index among those of this attention (one launch may hold two attentions, below).
 template <int DK, int MODE>
 __device__ __forceinline__ void attn_flash_body(const sm_attention_desc& a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh, int bid) {
+                                                const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh, int bid, int pair = 0) {
   constexpr bool CAUSAL = MODE == 1, STRIPE = MODE == 2;
   constexpr int DB = (DK + 1) / 2;           // 32-wide output column blocks
   // Row pitches in 16-byte chunks, chosen for the 64-bank LDS.  K rows are read whole-chunk by 16 consecutive rows
@@ -220,7 +220,10 @@ __device__ __forceinline__ void attn_flash_body(const sm_attention_desc& a, cons
   // keeps them on one XCD (one L2) whenever nbh is a multiple of 8.  Causal: the first half of the ranks takes
   // the long query tiles in descending order and the second half the short ones in ascending order, so that
   // co-resident workgroups of ranks r and r + n_qt / 2 carry about the same total work.
-  const int bh = bid % nbh, rank = bid / nbh;
+  // pair: heads narrower than a cache line share their lines with the next head; pairs of heads, not heads, then go
+  // round the XCDs (both heads of a pair and all their query tiles on one L2), which needs nbh / 2 to be a multiple of 8
+  int bh = bid % nbh, rank = bid / nbh;
+  if (pair) { const int half = nbh >> 1, t = bid / half; bh = 2 * (bid - t * half) + (t & 1); rank = t >> 1; }
   int qt = rank;
   if (CAUSAL) { const int hq = (n_qt + 1) >> 1; qt = rank < hq ? n_qt - 1 - rank : rank - hq; }
   // stripes: heads whose rows share cache lines (head size 32 is half a line) follow each other at a distance of
@@ -403,8 +406,8 @@ __device__ __forceinline__ void attn_flash_body(const sm_attention_desc& a, cons
 
 template <int DK, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_flash_kernel(sm_attention_desc a, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                            const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh) {
-  attn_flash_body<DK, MODE>(a, q, k, v, o, n_qt, nbh, (int)blockIdx.x);
+                                                            const bf16_t* __restrict__ v, bf16_t* __restrict__ o, int n_qt, int nbh, int pair) {
+  attn_flash_body<DK, MODE>(a, q, k, v, o, n_qt, nbh, (int)blockIdx.x, pair);
 }
 // Two stripe attentions of one shape in one launch (the two halves of a cross-shaped window attention): workgroups
 // [0, g0) belong to the first.  Each half has its own strides and pointers; nothing else differs.
@@ -1003,18 +1006,21 @@ int launch_attention(const sm_attention_desc& d, const void* q, const void* k, c
     const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
     bf16_t* oo = (bf16_t*)o;
     const dim3 grid((unsigned)((long)n_qt * nbh)), block(256);
+    // heads interleaved within a cache line (head stride under 128 bytes on the key side): see attn_flash_body
+    const int64_t hs = d.k_stride[1] < 0 ? -d.k_stride[1] : d.k_stride[1];
+    const int pair = (d.kind != SM_ATT_STRIPE && d.heads % 2 == 0 && hs * 2 < 128 && (nbh / 2) % 8 == 0) ? 1 : 0;
 #define FLASH(DK_) do { \
       const size_t smem = 2 * 64 * ((2 * DK_ + 1) + (DK_ <= 2 ? 4 : (DK_ == 3 ? 7 : (DK_ <= 6 ? 12 : 20)))) * 16 + 64;      /* two stages of a K tile and a V tile */ \
       static const hipError_t attr_f = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
       static const hipError_t attr_c = hipFuncSetAttribute((const void*)attn_flash_kernel<DK_, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
       if (attr_f != hipSuccess || attr_c != hipSuccess) return (int)(attr_f != hipSuccess ? attr_f : attr_c); \
-      if (d.kind == SM_ATT_CAUSAL) attn_flash_kernel<DK_, 1><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); \
-      else attn_flash_kernel<DK_, 0><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh); } while (0)
+      if (d.kind == SM_ATT_CAUSAL) attn_flash_kernel<DK_, 1><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh, pair); \
+      else attn_flash_kernel<DK_, 0><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh, pair); } while (0)
     if (d.kind == SM_ATT_STRIPE) {
       const size_t smem = 2 * 64 * ((2 * 2 + 1) + 4) * 16 + 64;
       static const hipError_t attr_s = hipFuncSetAttribute((const void*)attn_flash_kernel<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (attr_s != hipSuccess) return (int)attr_s;
-      attn_flash_kernel<2, 2><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh);
+      attn_flash_kernel<2, 2><<<grid, block, smem, s>>>(d, qq, kk, vv, oo, n_qt, nbh, 0);
     }
     else if (dk <= 2) FLASH(2);
     else if (dk == 3) FLASH(3);
